@@ -1,0 +1,413 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix.
+
+None of these tests retypes the oracle's own formula: each one checks a stage against a
+closed form, an invariant, a library routine used as an independent witness, a hand-typed
+fixture, or brute force on tiny inputs.
+"""
+
+import itertools
+import os
+
+import numpy as np
+import pytest
+import scipy.linalg
+
+import synth_inputs as synth
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+THR = (-1.0, 0.0, 1.0)
+
+
+def bf16(x):
+    return synth.f32_to_bf16_bits(np.asarray(x, dtype=np.float32))
+
+
+def widen(b):
+    return synth.bf16_bits_to_f32(b).astype(np.float64)
+
+
+# ------------------------------------------------------------------ Hadamard matrix (Eq. 2)
+
+def test_h2_and_h4_match_hand_typed_fixtures(oracle):
+    h2 = np.loadtxt(os.path.join(GOLDEN, "hadamard_h2.txt"), dtype=np.int64)
+    h4 = np.loadtxt(os.path.join(GOLDEN, "hadamard_h4_kron.txt"), dtype=np.int64)
+    assert np.array_equal(oracle.hadamard_matrix(2), h2)
+    assert np.array_equal(oracle.hadamard_matrix(4), h4)
+
+
+@pytest.mark.parametrize("d", [1, 2, 8, 64, 128, 256])
+def test_hadamard_rows_orthogonal(oracle, d):
+    H = oracle.hadamard_matrix(d).astype(np.int64)
+    assert set(np.unique(H)) <= {-1, 1}
+    assert np.array_equal(H @ H.T, d * np.eye(d, dtype=np.int64))      # H H^T = d I
+    assert np.array_equal(H, H.T)
+    assert np.all(H[0] == 1) and np.all(H[:, 0] == 1)
+
+
+def test_hadamard_matches_popcount_form_and_scipy(oracle):
+    H = oracle.hadamard_matrix(128).astype(np.int64)
+    i, j = np.meshgrid(np.arange(128), np.arange(128), indexing="ij")
+    pc = np.vectorize(lambda v: bin(v).count("1"))(i & j)
+    assert np.array_equal(H, 1 - 2 * (pc & 1))                         # (-1)^popcount(i & j)
+    assert np.array_equal(H, scipy.linalg.hadamard(128).astype(np.int64))
+    # Kronecker rule under Eq. 2: H_128 = H_2 (x) H_64
+    assert np.array_equal(H, np.kron(oracle.hadamard_matrix(2).astype(np.int64),
+                                     oracle.hadamard_matrix(64).astype(np.int64)))
+
+
+# --------------------------------------------------------------------- transform (Eq. 4)
+
+def test_transform_unit_vectors_give_matrix_rows(oracle):
+    H = scipy.linalg.hadamard(128).astype(np.float64)
+    for i in (0, 1, 2, 63, 64, 127):
+        e = np.zeros(128)
+        e[i] = 1.0
+        assert np.array_equal(oracle.hadamard_transform(e), H[i])
+
+
+def test_transform_twice_is_d_times_identity_exactly(oracle):
+    rng = np.random.default_rng(1)
+    for _ in range(20):
+        x = widen(bf16(rng.standard_normal(128) * rng.choice([1, 8, 0.01], 128)))
+        y = oracle.hadamard_transform(x)
+        z = oracle.hadamard_transform(y)
+        assert np.array_equal(z, 128.0 * x)          # exact: normalised transform is an involution
+
+
+def test_transform_parseval_and_inner_products(oracle):
+    rng = np.random.default_rng(2)
+    a = rng.integers(-50, 51, 128).astype(np.float64)
+    b = rng.integers(-50, 51, 128).astype(np.float64)
+    ya, yb = oracle.hadamard_transform(a), oracle.hadamard_transform(b)
+    assert np.dot(ya, ya) == 128.0 * np.dot(a, a)                      # Parseval, exact in integers
+    assert np.dot(ya, yb) == 128.0 * np.dot(a, b)                      # Eq. 3: (QH)(KH)^T = QK^T
+
+
+def test_transform_is_x_times_h_not_transposed_or_permuted(oracle):
+    # A non-symmetric check: x = e_1 + 2 e_2 has transform H[1] + 2 H[2] in natural order.
+    H = scipy.linalg.hadamard(128).astype(np.float64)
+    x = np.zeros(128)
+    x[1], x[2] = 1.0, 2.0
+    y = oracle.hadamard_transform(x)
+    assert np.array_equal(y, H[1] + 2 * H[2])
+    assert y[0] == 3 and y[1] == 1 and y[2] == -1 and y[3] == -3      # typed by hand
+
+
+def test_transform_other_orders(oracle):
+    for d in (2, 4, 32):
+        x = np.arange(1, d + 1, dtype=np.float64)
+        assert np.array_equal(oracle.hadamard_transform(x), x @ scipy.linalg.hadamard(d))
+
+
+# ---------------------------------------------------------------------- bucketize (Eq. 5)
+
+def test_bucketize_hand_cases(oracle):
+    root = np.sqrt(128.0)
+    y = np.array([-2 * root, -root, -0.5 * root, 0.0, -0.0, 0.5 * root, root, 2 * root,
+                  np.nextafter(root, np.inf), np.nextafter(-root, np.inf)])
+    # strict '>' : a value equal to a threshold falls into the LOWER bucket
+    assert oracle.bucketize(y, THR).tolist() == [0, 0, 1, 1, 1, 2, 2, 3, 3, 1]
+
+
+def test_bucketize_monotone_and_range(oracle):
+    y = np.sort(np.random.default_rng(3).standard_normal(4096) * 30)
+    c = oracle.bucketize(y, (-0.7, 0.1, 1.3)).astype(int)
+    assert c.min() >= 0 and c.max() <= 3 and np.all(np.diff(c) >= 0)
+    # counts agree with numpy's searchsorted on the scaled thresholds (side='left' == strict >)
+    tau = np.array([-0.7, 0.1, 1.3], dtype=np.float32).astype(np.float64) * np.sqrt(128.0)
+    assert np.array_equal(c, np.searchsorted(tau, y, side="left"))
+
+
+def test_bucketize_rejects_unsorted_thresholds(oracle):
+    with pytest.raises(oracle.OracleError):
+        oracle.bucketize(np.zeros(4), (0.0, 0.0, 1.0))
+
+
+# ------------------------------------------------------------------------------- compress
+
+def test_pack_layout_single_positions(oracle):
+    for dim in range(128):
+        for c in (1, 2, 3):
+            code = np.zeros(128, dtype=np.uint8)
+            code[dim] = c
+            row = oracle.pack_row(code)
+            words = row.view("<u8")
+            g, j = divmod(dim, 32)
+            expect = ((c & 1) << j) | ((c >> 1) << (32 + j))
+            assert int(words[g]) == expect
+            assert all(int(words[o]) == 0 for o in range(4) if o != g)
+            assert np.array_equal(oracle.unpack_row(row), code)
+
+
+def test_pack_density_and_roundtrip(oracle):
+    # eight 2-bit codes per 16 bits -> 32 bytes per 128-d vector = 1/16 of 512 bytes of K+V
+    with open(os.path.join(GOLDEN, "cost_model_cfg1.txt")) as f:
+        vals = dict(l.split() for l in f if not l.startswith("#"))
+    assert oracle.ROW_BYTES == int(vals["code_bytes_per_token_per_head"]) == 128 * 2 // 8
+    assert oracle.ROW_BYTES * 16 == 2 * 128 * 2
+    assert 32 * 32768 * oracle.ROW_BYTES + 4096 // 8 * 2 == int(vals["distance_read_bytes"])
+    rng = np.random.default_rng(4)
+    for _ in range(50):
+        code = rng.integers(0, 4, 128).astype(np.uint8)
+        assert np.array_equal(oracle.unpack_row(oracle.pack_row(code)), code)
+
+
+def test_pack_planes_equal_threshold_indicator_masks(oracle):
+    # high plane = indicator(y > B2); low plane = parity of the three nested indicators
+    rng = np.random.default_rng(5)
+    y = rng.standard_normal(128) * 25
+    code = oracle.bucketize(y, THR)
+    words = oracle.pack_row(code).view("<u8")
+    tau = np.array(THR) * np.sqrt(128.0)
+    m = [(y > t) for t in tau]
+    for g in range(4):
+        lo = sum(int(m[0][32 * g + j] ^ m[1][32 * g + j] ^ m[2][32 * g + j]) << j for j in range(32))
+        hi = sum(int(m[1][32 * g + j]) << j for j in range(32))
+        assert int(words[g]) == lo | (hi << 32)
+
+
+# ------------------------------------------------------------------------ encode end to end
+
+def test_encode_matches_float_matmul_away_from_thresholds(oracle):
+    rng = np.random.default_rng(6)
+    x = bf16(rng.standard_normal((64, 128)) * np.where(np.arange(128) % 37 == 0, 8, 1))
+    codes, rows = oracle.encode(x, THR)
+    y = widen(x) @ scipy.linalg.hadamard(128).astype(np.float64) / np.sqrt(128.0)
+    ref = (y > -1).astype(int) + (y > 0).astype(int) + (y > 1).astype(int)
+    far = np.min(np.abs(y[..., None] - np.array(THR)), axis=-1) > 1e-9
+    assert far.mean() > 0.99
+    assert np.array_equal(codes[far], ref[far])
+    assert np.array_equal(oracle.unpack_rows(rows), codes)
+
+
+def test_encode_zero_vector_and_exact_threshold(oracle):
+    codes, _ = oracle.encode(np.zeros((1, 128), dtype=np.uint16), THR)
+    assert np.all(codes == 1)                                # thresholds below 0: only -1
+    # x = c * e_0 -> every coefficient equals c.  c = sqrt(128) is not representable, so use
+    # thresholds (.., 0.5, ..) hit exactly by an x whose sum is 0.5*sqrt(128)? not representable
+    # either; instead hit threshold 0 exactly with x = e_0 - e_1: coefficients are 0 or 2.
+    x = np.zeros(128, dtype=np.float32)
+    x[0], x[1] = 1.0, -1.0
+    codes, _ = oracle.encode(bf16(x)[None], THR)
+    H = scipy.linalg.hadamard(128)
+    y = H[0] - H[1]
+    assert np.array_equal(codes[0], np.where(y == 0, 1, 2))  # 0 -> bucket 1 (not > 0); 2 -> (1 <..)
+
+
+def test_encode_precondition_flagged(oracle):
+    x = np.zeros(128, dtype=np.float32)
+    x[0], x[1] = 2.0 ** 60, 2.0 ** -60
+    u = (x.view(np.uint32) >> 16).astype(np.uint16)
+    with pytest.raises(oracle.OracleError):
+        oracle.encode(u[None], THR)
+    x[1] = np.inf
+    u = (x.view(np.uint32) >> 16).astype(np.uint16)
+    with pytest.raises(oracle.OracleError):
+        oracle.encode(u[None], THR)
+
+
+# ------------------------------------------------------------------ Manhattan distance (Eq. 6)
+
+def test_l1_all_code_pairs_from_fixture(oracle):
+    pairs = np.loadtxt(os.path.join(GOLDEN, "l1_pairs.txt"), dtype=np.int64)
+    assert pairs.shape == (16, 3)
+    for a, b, d in pairs:
+        for dim in (0, 31, 32, 127):
+            qa = np.zeros(128, dtype=np.uint8)
+            kb = np.zeros((1, 128), dtype=np.uint8)
+            qa[dim], kb[0, dim] = a, b
+            assert oracle.manhattan(qa, kb)[0] == d
+
+
+def test_l1_extremes_symmetry_triangle(oracle):
+    rng = np.random.default_rng(7)
+    c = rng.integers(0, 4, (40, 128)).astype(np.uint8)
+    assert oracle.manhattan(np.zeros(128, np.uint8), np.full((1, 128), 3, np.uint8))[0] == 384
+    for i in range(40):
+        assert oracle.manhattan(c[i], c[i:i + 1])[0] == 0
+    Dm = np.stack([oracle.manhattan(c[i], c) for i in range(40)])
+    assert np.array_equal(Dm, Dm.T)
+    assert np.all(Dm[:, :, None] <= Dm[:, None, :] + Dm[None, :, :].transpose(0, 2, 1))
+    assert np.array_equal(Dm, np.abs(c[:, None, :].astype(int) - c[None].astype(int)).sum(-1))
+
+
+def test_l1_bitplane_identity_brute_force():
+    # |a-b| = popcount(x0) + 2*popcount(x1 & ~(x0 & g)), x = a^b per plane, g = a1^a0:
+    # the identity a bit-plane kernel may use, checked here over all 16 pairs (no oracle call).
+    for a in range(4):
+        for b in range(4):
+            x0, x1 = (a ^ b) & 1, (a ^ b) >> 1
+            g = (a >> 1) ^ (a & 1)
+            assert abs(a - b) == x0 + 2 * (x1 & ~(x0 & g) & 1)
+
+
+def test_l1_with_one_bit_thresholds_is_hamming_of_signs(oracle):
+    rng = np.random.default_rng(8)
+    x = bf16(rng.standard_normal((33, 128)))
+    big = 1e30
+    codes, _ = oracle.encode(x, (-big, 0.0, big))             # codes in {1, 2}: sign pattern
+    assert set(np.unique(codes)) <= {1, 2}
+    y = widen(x) @ scipy.linalg.hadamard(128).astype(np.float64)
+    sign = (y > 0)
+    ham = (sign[0][None] ^ sign[1:]).sum(-1)
+    assert np.array_equal(oracle.manhattan(codes[0], codes[1:]), ham)
+
+
+# ----------------------------------------------------------------------------------- top-k
+
+def test_topk_exhaustive_subsets(oracle):
+    rng = np.random.default_rng(9)
+    for trial in range(60):
+        L = int(rng.integers(1, 10))
+        k = int(rng.integers(1, 8))
+        D = rng.integers(0, 4, L).astype(np.int32)            # few values -> many ties
+        got = oracle.topk(D, k)
+        n = min(k, L)
+        best = None
+        for sub in itertools.combinations(range(L), n):
+            # minimise total distance; among minimisers the set whose sorted (distance, index)
+            # sequence is lexicographically smallest = ties resolved towards lower indices
+            key = (int(D[list(sub)].sum()), sorted((int(D[t]), t) for t in sub))
+            if best is None or key < best[0]:
+                best = (key, sub)
+        assert got[:n].tolist() == list(best[1])
+        assert np.all(got[n:] == -1)
+
+
+def test_topk_special_cases(oracle):
+    assert oracle.topk(np.full(10, 7, np.int32), 4).tolist() == [0, 1, 2, 3]
+    assert oracle.topk(np.array([5, 1, 5, 1, 0], np.int32), 8).tolist() == [0, 1, 2, 3, 4, -1, -1, -1]
+    assert oracle.topk(np.array([9, 8, 7, 6], np.int32), 2).tolist() == [2, 3]
+    assert oracle.topk(np.array([3, 1, 3, 1, 3, 1], np.int32), 4).tolist() == [0, 1, 3, 5]
+    assert oracle.topk(np.zeros(0, np.int32), 3).tolist() == [-1, -1, -1]
+
+
+def test_topk_against_numpy_stable_sort(oracle):
+    rng = np.random.default_rng(10)
+    D = rng.integers(90, 200, 5000).astype(np.int32)
+    for k in (1, 64, 257, 5000, 6000):
+        order = np.argsort(D, kind="stable")[:min(k, 5000)]
+        got = oracle.topk(D, k)
+        assert np.array_equal(got[:len(order)], np.sort(order))
+        assert np.all(got[len(order):] == -1)
+
+
+# ------------------------------------------------------------------------ attention (Eq. 1)
+
+def test_sparse_equals_full_when_k_is_L(oracle):
+    rng = np.random.default_rng(11)
+    L = 77
+    q, K, V = bf16(rng.standard_normal(128)), bf16(rng.standard_normal((L, 128))), \
+        bf16(rng.standard_normal((L, 128)))
+    s = 1 / np.sqrt(128.0)
+    a = oracle.sparse_attention(q, K, V, np.arange(L, dtype=np.int32), s)
+    b = oracle.full_attention(q, K, V, s)
+    assert np.allclose(a, b, rtol=0, atol=1e-7)
+
+
+def test_attention_against_numpy_softmax(oracle):
+    rng = np.random.default_rng(12)
+    L = 50
+    q, K, V = bf16(rng.standard_normal(128)), bf16(rng.standard_normal((L, 128)) * 2), \
+        bf16(rng.standard_normal((L, 128)))
+    idx = np.array([3, 7, -1, 20, 49, -1], dtype=np.int32)
+    sel = idx[idx >= 0]
+    s = widen(K)[sel] @ widen(q) / np.sqrt(128.0)
+    p = np.exp(s - s.max())
+    ref = (p / p.sum()) @ widen(V)[sel]
+    got = oracle.sparse_attention(q, K, V, idx, 1 / np.sqrt(128.0))
+    assert np.allclose(got, ref, rtol=1e-6, atol=1e-7)
+    assert np.allclose(oracle.full_attention(q, K, V, 1 / np.sqrt(128.0)),
+                       (lambda s: (np.exp(s - s.max()) / np.exp(s - s.max()).sum()) @ widen(V))(
+                           widen(K) @ widen(q) / np.sqrt(128.0)), rtol=1e-6, atol=1e-7)
+
+
+def test_attention_closed_forms(oracle):
+    rng = np.random.default_rng(13)
+    q = bf16(rng.standard_normal(128))
+    K = bf16(rng.standard_normal((9, 128)))
+    V = bf16(rng.standard_normal((9, 128)))
+    one = oracle.sparse_attention(q, K, V, np.array([4], np.int32), 0.3)
+    assert np.array_equal(one, synth.bf16_bits_to_f32(V[4]))          # single row -> that V row
+    Ksame = np.repeat(K[:1], 9, axis=0)                                # equal scores -> mean of V
+    mean = oracle.sparse_attention(q, Ksame, V, np.arange(9, dtype=np.int32), 0.3)
+    assert np.allclose(mean, widen(V).mean(0), rtol=1e-6, atol=1e-7)
+    assert np.all(oracle.sparse_attention(q, K, V, np.array([-1, -1], np.int32), 0.3) == 0)
+    # scale matters and enters the exponent: scale 0 -> uniform weights
+    flat = oracle.sparse_attention(q, K, V, np.arange(9, dtype=np.int32), 0.0)
+    assert np.allclose(flat, widen(V).mean(0), rtol=1e-6, atol=1e-7)
+    # large scores do not overflow (max subtracted)
+    big = oracle.sparse_attention(bf16(np.full(128, 30.0)), bf16(np.full((2, 128), 30.0)), V[:2],
+                                  np.array([0, 1], np.int32), 1.0)
+    assert np.all(np.isfinite(big))
+
+
+# -------------------------------------------------------------------- whole step (Alg. 1)
+
+def _step(oracle, case, k, want_dist=True):
+    K, V = case.K.copy(), case.V.copy()
+    _, rows = oracle.encode(K, case.thresholds)
+    out, idx, dist = oracle.decode_step(case.q, K, V, rows, case.seq_start, case.seq_len, k,
+                                        case.thresholds, case.thresholds, 1 / np.sqrt(128.0),
+                                        k_new=case.k_new, v_new=case.v_new, want_dist=want_dist)
+    return out, idx, dist, K, V, rows
+
+
+def test_decode_step_composes_the_stages(oracle):
+    case = synth.make_case("t", 77, 2, 4, 2, [300, 129], [16],
+                           lambda b, L, h, rng: rng.choice(L, (2, 1), replace=False))
+    out, idx, dist, K, V, rows = _step(oracle, case, 16)
+    for b in range(2):
+        L, s = int(case.seq_len[b]), int(case.seq_start[b])
+        for h in range(4):
+            kvh = h // 2
+            qc, _ = oracle.encode(case.q[b, h], case.thresholds)
+            kc = oracle.unpack_rows(rows[kvh, s:s + L])
+            Dref = oracle.manhattan(qc, kc)
+            assert np.array_equal(dist[b, h, :L], Dref)
+            sel = oracle.topk(Dref, 16)
+            assert np.array_equal(idx[b, h], sel)
+            ref = oracle.sparse_attention(case.q[b, h], case.K[kvh, s:s + L], case.V[kvh, s:s + L],
+                                          sel, 1 / np.sqrt(128.0))
+            assert np.array_equal(out[b, h], ref)
+            assert case.needles[b][h][0] in sel.tolist()
+
+
+def test_decode_step_k_at_least_L_is_full_attention(oracle):
+    case = synth.make_case("t", 78, 1, 2, 1, [40], [64],
+                           lambda b, L, h, rng: rng.choice(L, (2, 1), replace=False))
+    out, idx, _, _, _, _ = _step(oracle, case, 64, want_dist=False)
+    for h in range(2):
+        assert idx[0, h, :40].tolist() == list(range(40)) and np.all(idx[0, h, 40:] == -1)
+        full = oracle.full_attention(case.q[0, h], case.K[0, :40], case.V[0, :40], 1 / np.sqrt(128.0))
+        assert np.allclose(out[0, h], full, rtol=0, atol=1e-7)
+
+
+def test_decode_step_append_updates_cache_before_scan(oracle):
+    case = synth.make_case("t", 79, 2, 2, 2, [65, 17], [8],
+                           lambda b, L, h, rng: rng.choice(L, (1, 1), replace=False), append=True)
+    # make the query of (b=0, h=0) equal to the appended key: the new row must be selected
+    case.q[0, 0] = case.k_new[0, 0]
+    out, idx, dist, K, V, rows = _step(oracle, case, 8)
+    for b in range(2):
+        last = int(case.seq_start[b] + case.seq_len[b] - 1)
+        for h in range(2):
+            assert np.array_equal(K[h, last], case.k_new[b, h])
+            assert np.array_equal(V[h, last], case.v_new[b, h])
+            assert np.array_equal(rows[h, last], oracle.encode(case.k_new[b, h], case.thresholds)[1])
+    assert dist[0, 0, 64] == 0 and 64 in idx[0, 0].tolist()
+
+
+def test_decode_step_empty_sequence(oracle):
+    case = synth.make_case("t", 80, 2, 1, 1, [0, 5], [4], lambda b, L, h, rng: np.zeros((1, 0)))
+    out, idx, _, _, _, _ = _step(oracle, case, 8, want_dist=False)
+    assert np.all(out[0] == 0) and np.all(idx[0] == -1)
+    assert idx[1, 0].tolist() == [0, 1, 2, 3, 4, -1, -1, -1]
+
+
+def test_tiny_config_needle_is_selected(oracle):
+    case = synth.tiny_single_head()
+    out, idx, dist, _, _, _ = _step(oracle, case, 64)
+    needle = case.needles[0][0][0]
+    assert needle in idx[0, 0].tolist()
+    assert dist[0, 0, needle] == dist[0, 0, :1024].min()
