@@ -1,0 +1,196 @@
+/*
+ * adamas.h -- C ABI of the MI355X (gfx950) implementation of the Adamas
+ * decode-time sparse-attention path (Algorithm 1 of the paper):
+ *
+ *   Hadamard transform of each query / key head vector      (Alg. 1 l.1, Eq. 4)
+ *   bucketize into 2-bit codes and pack, 32 B per vector    (Alg. 1 l.2-3, Eq. 5)
+ *   append K, V and the code row to the cache               (Alg. 1 l.4)
+ *   Manhattan distance of the query codes to every cached
+ *   key's codes                                             (Alg. 1 l.5, Eq. 6)
+ *   top-k: the k cached tokens of smallest distance         (Alg. 1 l.6)
+ *   softmax attention of the original q over the selected
+ *   rows of the original K, V                               (Alg. 1 l.7-8, Eq. 1)
+ *
+ * GENERAL CONVENTIONS
+ *
+ * Pointers.  `cfg` is HOST memory.  Every other pointer is DEVICE memory of
+ * the current HIP device, owned by the caller for the whole call and until
+ * the enqueued work has finished.  The library never allocates, frees or
+ * synchronises: all work is enqueued on `stream` (a hipStream_t passed as
+ * void*; NULL is the default stream) and the call returns at once.
+ *
+ * Cache layout ("pools").  pool_tokens rows per KV head:
+ *     K, V   : bf16   [num_kv_heads][pool_tokens][128]
+ *     codes  : uint8  [num_kv_heads][pool_tokens][32]
+ * Sequence b of a batch owns rows seq_start[b] .. seq_start[b]+seq_len[b]-1
+ * of every KV head (ragged batches are packed into one pool).  Token t of
+ * sequence b is pool row seq_start[b]+t.  All indices the library returns
+ * are token positions t inside the sequence, not pool rows.  Pools must be
+ * 16-byte aligned.
+ *
+ * Heads.  Query head h reads KV head h / (num_q_heads / num_kv_heads).  With
+ * grouped-query attention every query head encodes its own query and picks
+ * its own top-k from its group's shared code plane.
+ *
+ * Code row (32 B).  Four little-endian 64-bit words; word g covers transform
+ * coefficients 32g..32g+31 (natural/Sylvester order); bit j is the low bit
+ * of the 2-bit code of coefficient 32g+j, bit 32+j its high bit.  This keeps
+ * the paper's density of eight codes per 16 bits (1/16 of the bf16 K+V
+ * bytes); the paper does not fix a bit order.
+ *
+ * Codes.  code_j = #{ i : y_j > thr[i] } in {0,1,2,3}, strict comparison,
+ * where y = x H / sqrt(128) is the orthonormal transform evaluated EXACTLY:
+ * the kernels form the +-1 sums in fp64, which is exact when, within one
+ * vector, the binary exponents of the largest and smallest non-zero input
+ * differ by at most 38, and compare with (double)thr[i] * sqrt(128.0).
+ * Inputs outside that range, NaN or Inf give unspecified codes.
+ *
+ * Selection.  The min(k, seq_len) tokens of smallest distance, equal
+ * distances ranked by token position (lower first).  Written in ascending
+ * token position, padded with -1 up to k entries.  Every cached position,
+ * including a token appended by the same call, is a candidate.
+ *
+ * Errors.  Return 0 on success.  A negative return means nothing was
+ * enqueued and no output was touched:
+ *     ADAMAS_ERR_BAD_ARG      null pointer, non-positive size, heads not
+ *                             divisible, thresholds not strictly increasing,
+ *                             non-finite scale, misaligned pool, ...
+ *     ADAMAS_ERR_UNSUPPORTED  head_dim != 128, k > ADAMAS_MAX_K,
+ *                             group size > ADAMAS_MAX_GROUP,
+ *                             max_seq_len > ADAMAS_MAX_SEQ_LEN
+ *     ADAMAS_ERR_WORKSPACE    workspace_bytes < adamas_workspace_bytes(...)
+ *     ADAMAS_ERR_HIP          a launch failed (adamas_last_hip_error() tells)
+ * seq_len[b] and seq_start[b] live on the device and are NOT validated: the
+ * caller guarantees 0 <= seq_len[b] <= max_seq_len and
+ * 0 <= seq_start[b], seq_start[b]+seq_len[b] <= pool_tokens.
+ *
+ * Workspace.  Calls that take `workspace` need at least
+ * adamas_workspace_bytes(cfg, batch, max_seq_len, k) bytes, 256-byte aligned.
+ * Its contents need no initialisation and carry nothing between calls, but
+ * two calls that may run concurrently must not share one workspace.
+ */
+#ifndef ADAMAS_H
+#define ADAMAS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ADAMAS_HEAD_DIM 128
+#define ADAMAS_CODE_ROW_BYTES 32
+#define ADAMAS_MAX_DISTANCE 384          /* 3 * 128 */
+#define ADAMAS_MAX_K 4096                /* largest budget in the paper's tables */
+#define ADAMAS_MAX_GROUP 8               /* query heads per KV head */
+#define ADAMAS_MAX_SEQ_LEN (1 << 20)
+
+#define ADAMAS_OK 0
+#define ADAMAS_ERR_BAD_ARG (-1)
+#define ADAMAS_ERR_UNSUPPORTED (-2)
+#define ADAMAS_ERR_WORKSPACE (-3)
+#define ADAMAS_ERR_HIP (-4)
+
+typedef struct adamas_config {
+  int32_t head_dim;      /* must be 128 */
+  int32_t num_q_heads;   /* Hq */
+  int32_t num_kv_heads;  /* Hkv; Hq % Hkv == 0 */
+  int32_t reserved;      /* must be 0 */
+  int64_t pool_tokens;   /* rows per KV head in K, V and codes */
+  float thr_k[3];        /* key thresholds B1 < B2 < B3 of Eq. 5, orthonormal scale */
+  float thr_q[3];        /* query thresholds (the paper uses one triple: pass the same) */
+  float sm_scale;        /* softmax scale of Eq. 1; 0 means 1/sqrt(128) */
+} adamas_config;
+
+/* Human-readable name of a status code; never NULL. */
+const char *adamas_status_string(int status);
+
+/* hipError_t (as int) of the launch that made the last call on this thread
+ * return ADAMAS_ERR_HIP; 0 if none. */
+int adamas_last_hip_error(void);
+
+/* Bytes of workspace the calls below need for these sizes; 0 if the
+ * arguments are invalid or unsupported.  Host-only, enqueues nothing. */
+size_t adamas_workspace_bytes(const adamas_config *cfg, int32_t batch,
+                              int64_t max_seq_len, int32_t k);
+
+/*
+ * Alg. 1 l.1-3 for cached keys (prefill-time bulk encode): for every KV
+ * head, transform, bucketize (thr_k) and pack pool rows
+ * [row_begin, row_begin + n_rows) of K into the same rows of codes.
+ * K: bf16 [Hkv][pool_tokens][128] (read), codes: uint8 [Hkv][pool_tokens][32]
+ * (written).  n_rows == 0 is a no-op.
+ */
+int adamas_encode_keys(const adamas_config *cfg, const void *K, void *codes,
+                       int64_t row_begin, int64_t n_rows, void *stream);
+
+/*
+ * Alg. 1 l.1-3 for queries: q bf16 [batch][Hq][128] -> qcodes uint8
+ * [batch][Hq][32], thresholds thr_q.
+ */
+int adamas_encode_query(const adamas_config *cfg, const void *q, void *qcodes,
+                        int32_t batch, void *stream);
+
+/*
+ * Alg. 1 l.5 (Eq. 6): dist_out[b][h][t] = sum_j |qcode[b][h]_j - code[kv(h)][seq_start[b]+t]_j|
+ * for t < seq_len[b]; entries t >= seq_len[b] are left untouched.
+ * qcodes uint8 [batch][Hq][32]; seq_start int64 [batch]; seq_len int32 [batch];
+ * dist_out uint16 [batch][Hq][max_seq_len], values 0..384.
+ */
+int adamas_manhattan_distance(const adamas_config *cfg, const void *qcodes,
+                              const void *codes, const int64_t *seq_start,
+                              const int32_t *seq_len, int32_t batch,
+                              uint16_t *dist_out, int64_t max_seq_len,
+                              void *stream);
+
+/*
+ * Alg. 1 l.5-6: distances as above, then the top-k selection described
+ * under "Selection".  idx_out int32 [batch][Hq][k].  dist_out may be NULL;
+ * otherwise it receives the distances as in adamas_manhattan_distance.
+ */
+int adamas_select_topk(const adamas_config *cfg, const void *qcodes,
+                       const void *codes, const int64_t *seq_start,
+                       const int32_t *seq_len, int32_t batch, int32_t k,
+                       int32_t *idx_out, uint16_t *dist_out,
+                       int64_t max_seq_len, void *workspace,
+                       size_t workspace_bytes, void *stream);
+
+/*
+ * Alg. 1 l.7-8 (Eq. 1): out[b][h] = softmax(q[b][h] . K_s^T * sm_scale) V_s
+ * over the rows idx[b][h][0..k) of sequence b (token positions; negative
+ * entries are skipped; no valid entry -> zeros).  q bf16 [batch][Hq][128];
+ * idx int32 [batch][Hq][k]; out fp32 [batch][Hq][128].  Products and sums are
+ * fp32; the caller guarantees 0 <= idx < seq_len[b] for non-negative entries.
+ * max_seq_len is only used to size the workspace (pass the same value as to
+ * adamas_workspace_bytes).
+ */
+int adamas_sparse_attn(const adamas_config *cfg, const void *q, const void *K,
+                       const void *V, const int64_t *seq_start,
+                       const int32_t *idx, int32_t batch, int32_t k, float *out,
+                       int64_t max_seq_len, void *workspace,
+                       size_t workspace_bytes, void *stream);
+
+/*
+ * One whole decode step of one attention layer (Alg. 1 l.1-8), fused:
+ * encodes q (and k_new), appends, scans, selects and attends.
+ *
+ * k_new, v_new: bf16 [batch][Hkv][128], or both NULL for "no append".  With
+ * an append, seq_len[b] already counts the new token; its K, V and code row
+ * are written to pool row seq_start[b]+seq_len[b]-1 before the scan, so it
+ * is a candidate like any other (sequences with seq_len[b] == 0 append
+ * nothing).  K, V, codes are therefore read AND written.
+ * out fp32 [batch][Hq][128]; idx_out int32 [batch][Hq][k] or NULL.
+ */
+int adamas_decode_step(const adamas_config *cfg, const void *q,
+                       const void *k_new, const void *v_new, void *K, void *V,
+                       void *codes, const int64_t *seq_start,
+                       const int32_t *seq_len, int32_t batch, int32_t k,
+                       float *out, int32_t *idx_out, int64_t max_seq_len,
+                       void *workspace, size_t workspace_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+
+#endif /* ADAMAS_H */

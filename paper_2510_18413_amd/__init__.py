@@ -1,0 +1,18 @@
+"""MI355X-native Adamas decode path: HIP kernels behind a C ABI (libadamas.so) and a thin
+ctypes binding with the same entry-point names (see include/adamas.h)."""
+
+from .binding import (  # noqa: F401
+    AdamasError,
+    Config,
+    EXPORTED_SYMBOLS,
+    adamas_decode_step,
+    adamas_encode_keys,
+    adamas_encode_query,
+    adamas_manhattan_distance,
+    adamas_select_topk,
+    adamas_sparse_attn,
+    adamas_status_string,
+    adamas_workspace_bytes,
+    library,
+    library_path,
+)

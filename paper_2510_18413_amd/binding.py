@@ -1,0 +1,230 @@
+"""ctypes binding of libadamas.so: argument marshalling only.
+
+Every function mirrors the C entry point of the same name in include/adamas.h, takes torch
+tensors that already live on the GPU, checks dtype / device / contiguity, and passes raw
+device pointers plus the current HIP stream.  All arithmetic happens in the HIP kernels; there
+is no CPU or PyTorch fallback: if the shared library is missing and cannot be built, loading
+raises.
+"""
+
+from __future__ import annotations
+
+import ctypes
+from typing import Optional, Sequence
+
+from . import build as _build
+
+EXPORTED_SYMBOLS = (
+    "adamas_status_string",
+    "adamas_last_hip_error",
+    "adamas_workspace_bytes",
+    "adamas_encode_keys",
+    "adamas_encode_query",
+    "adamas_manhattan_distance",
+    "adamas_select_topk",
+    "adamas_sparse_attn",
+    "adamas_decode_step",
+)
+
+HEAD_DIM = 128
+CODE_ROW_BYTES = 32
+
+
+class AdamasError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s: %s (%d)" % (where, adamas_status_string(status), status))
+
+
+class Config(ctypes.Structure):
+    """Mirror of struct adamas_config."""
+    _fields_ = [
+        ("head_dim", ctypes.c_int32),
+        ("num_q_heads", ctypes.c_int32),
+        ("num_kv_heads", ctypes.c_int32),
+        ("reserved", ctypes.c_int32),
+        ("pool_tokens", ctypes.c_int64),
+        ("thr_k", ctypes.c_float * 3),
+        ("thr_q", ctypes.c_float * 3),
+        ("sm_scale", ctypes.c_float),
+    ]
+
+    @classmethod
+    def make(cls, num_q_heads: int, num_kv_heads: int, pool_tokens: int,
+             thr_k: Sequence[float] = (-1.0, 0.0, 1.0), thr_q: Optional[Sequence[float]] = None,
+             sm_scale: float = 0.0, head_dim: int = HEAD_DIM) -> "Config":
+        thr_q = thr_k if thr_q is None else thr_q
+        return cls(head_dim, num_q_heads, num_kv_heads, 0, pool_tokens,
+                   (ctypes.c_float * 3)(*thr_k), (ctypes.c_float * 3)(*thr_q), sm_scale)
+
+
+_lib = None
+
+
+def library_path():
+    return _build.LIB
+
+
+def library() -> ctypes.CDLL:
+    """Loads libadamas.so (building it first only if it does not exist)."""
+    global _lib
+    if _lib is None:
+        if not _build.LIB.exists():
+            _build.build()
+        lib = ctypes.CDLL(str(_build.LIB))
+        vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
+        cfgp = ctypes.POINTER(Config)
+        lib.adamas_status_string.restype = ctypes.c_char_p
+        lib.adamas_status_string.argtypes = [ctypes.c_int]
+        lib.adamas_last_hip_error.restype = ctypes.c_int
+        lib.adamas_last_hip_error.argtypes = []
+        lib.adamas_workspace_bytes.restype = sz
+        lib.adamas_workspace_bytes.argtypes = [cfgp, i32, i64, i32]
+        lib.adamas_encode_keys.restype = ctypes.c_int
+        lib.adamas_encode_keys.argtypes = [cfgp, vp, vp, i64, i64, vp]
+        lib.adamas_encode_query.restype = ctypes.c_int
+        lib.adamas_encode_query.argtypes = [cfgp, vp, vp, i32, vp]
+        lib.adamas_manhattan_distance.restype = ctypes.c_int
+        lib.adamas_manhattan_distance.argtypes = [cfgp, vp, vp, vp, vp, i32, vp, i64, vp]
+        lib.adamas_select_topk.restype = ctypes.c_int
+        lib.adamas_select_topk.argtypes = [cfgp, vp, vp, vp, vp, i32, i32, vp, vp, i64, vp, sz, vp]
+        lib.adamas_sparse_attn.restype = ctypes.c_int
+        lib.adamas_sparse_attn.argtypes = [cfgp, vp, vp, vp, vp, vp, i32, i32, vp, i64, vp, sz, vp]
+        lib.adamas_decode_step.restype = ctypes.c_int
+        lib.adamas_decode_step.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp,
+                                           i64, vp, sz, vp]
+        _lib = lib
+    return _lib
+
+
+def adamas_status_string(status: int) -> str:
+    return library().adamas_status_string(int(status)).decode()
+
+
+def adamas_workspace_bytes(cfg: Config, batch: int, max_seq_len: int, k: int) -> int:
+    return int(library().adamas_workspace_bytes(ctypes.byref(cfg), batch, max_seq_len, k))
+
+
+# ------------------------------------------------------------------ tensor marshalling
+
+def _ptr(t, dtype, name, shape=None, optional=False):
+    import torch
+    if t is None:
+        if optional:
+            return None
+        raise TypeError("%s must not be None" % name)
+    if not isinstance(t, torch.Tensor):
+        raise TypeError("%s must be a torch.Tensor" % name)
+    if not t.is_cuda:
+        raise ValueError("%s must live on the GPU" % name)
+    if t.dtype != dtype:
+        raise ValueError("%s must have dtype %s, got %s" % (name, dtype, t.dtype))
+    if not t.is_contiguous():
+        raise ValueError("%s must be contiguous" % name)
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError("%s must have shape %s, got %s" % (name, tuple(shape), tuple(t.shape)))
+    return t.data_ptr()
+
+
+def _stream(stream):
+    import torch
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _check(rc, where):
+    if rc != 0:
+        raise AdamasError(rc, where)
+
+
+def adamas_encode_keys(cfg: Config, K, codes, row_begin: int, n_rows: int, stream=None) -> None:
+    import torch
+    hkv, pool = cfg.num_kv_heads, cfg.pool_tokens
+    rc = library().adamas_encode_keys(
+        ctypes.byref(cfg), _ptr(K, torch.bfloat16, "K", (hkv, pool, HEAD_DIM)),
+        _ptr(codes, torch.uint8, "codes", (hkv, pool, CODE_ROW_BYTES)), row_begin, n_rows,
+        _stream(stream))
+    _check(rc, "adamas_encode_keys")
+
+
+def adamas_encode_query(cfg: Config, q, qcodes, stream=None) -> None:
+    import torch
+    batch = q.shape[0]
+    rc = library().adamas_encode_query(
+        ctypes.byref(cfg), _ptr(q, torch.bfloat16, "q", (batch, cfg.num_q_heads, HEAD_DIM)),
+        _ptr(qcodes, torch.uint8, "qcodes", (batch, cfg.num_q_heads, CODE_ROW_BYTES)), batch,
+        _stream(stream))
+    _check(rc, "adamas_encode_query")
+
+
+def adamas_manhattan_distance(cfg: Config, qcodes, codes, seq_start, seq_len, dist_out,
+                              stream=None) -> None:
+    import torch
+    batch = qcodes.shape[0]
+    max_seq_len = dist_out.shape[2]
+    rc = library().adamas_manhattan_distance(
+        ctypes.byref(cfg),
+        _ptr(qcodes, torch.uint8, "qcodes", (batch, cfg.num_q_heads, CODE_ROW_BYTES)),
+        _ptr(codes, torch.uint8, "codes", (cfg.num_kv_heads, cfg.pool_tokens, CODE_ROW_BYTES)),
+        _ptr(seq_start, torch.int64, "seq_start", (batch,)),
+        _ptr(seq_len, torch.int32, "seq_len", (batch,)), batch,
+        _ptr(dist_out, torch.uint16, "dist_out", (batch, cfg.num_q_heads, max_seq_len)),
+        max_seq_len, _stream(stream))
+    _check(rc, "adamas_manhattan_distance")
+
+
+def adamas_select_topk(cfg: Config, qcodes, codes, seq_start, seq_len, k: int, idx_out,
+                       max_seq_len: int, workspace, dist_out=None, stream=None) -> None:
+    import torch
+    batch = qcodes.shape[0]
+    rc = library().adamas_select_topk(
+        ctypes.byref(cfg),
+        _ptr(qcodes, torch.uint8, "qcodes", (batch, cfg.num_q_heads, CODE_ROW_BYTES)),
+        _ptr(codes, torch.uint8, "codes", (cfg.num_kv_heads, cfg.pool_tokens, CODE_ROW_BYTES)),
+        _ptr(seq_start, torch.int64, "seq_start", (batch,)),
+        _ptr(seq_len, torch.int32, "seq_len", (batch,)), batch, k,
+        _ptr(idx_out, torch.int32, "idx_out", (batch, cfg.num_q_heads, k)),
+        _ptr(dist_out, torch.uint16, "dist_out", (batch, cfg.num_q_heads, max_seq_len),
+             optional=True),
+        max_seq_len, _ptr(workspace, torch.uint8, "workspace"), workspace.numel(),
+        _stream(stream))
+    _check(rc, "adamas_select_topk")
+
+
+def adamas_sparse_attn(cfg: Config, q, K, V, seq_start, idx, out, max_seq_len: int, workspace,
+                       stream=None) -> None:
+    import torch
+    batch, _, k = idx.shape
+    hkv, pool = cfg.num_kv_heads, cfg.pool_tokens
+    rc = library().adamas_sparse_attn(
+        ctypes.byref(cfg), _ptr(q, torch.bfloat16, "q", (batch, cfg.num_q_heads, HEAD_DIM)),
+        _ptr(K, torch.bfloat16, "K", (hkv, pool, HEAD_DIM)),
+        _ptr(V, torch.bfloat16, "V", (hkv, pool, HEAD_DIM)),
+        _ptr(seq_start, torch.int64, "seq_start", (batch,)),
+        _ptr(idx, torch.int32, "idx", (batch, cfg.num_q_heads, k)), batch, k,
+        _ptr(out, torch.float32, "out", (batch, cfg.num_q_heads, HEAD_DIM)), max_seq_len,
+        _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream))
+    _check(rc, "adamas_sparse_attn")
+
+
+def adamas_decode_step(cfg: Config, q, K, V, codes, seq_start, seq_len, k: int, out,
+                       max_seq_len: int, workspace, k_new=None, v_new=None, idx_out=None,
+                       stream=None) -> None:
+    import torch
+    batch = q.shape[0]
+    hkv, pool = cfg.num_kv_heads, cfg.pool_tokens
+    rc = library().adamas_decode_step(
+        ctypes.byref(cfg), _ptr(q, torch.bfloat16, "q", (batch, cfg.num_q_heads, HEAD_DIM)),
+        _ptr(k_new, torch.bfloat16, "k_new", (batch, hkv, HEAD_DIM), optional=True),
+        _ptr(v_new, torch.bfloat16, "v_new", (batch, hkv, HEAD_DIM), optional=True),
+        _ptr(K, torch.bfloat16, "K", (hkv, pool, HEAD_DIM)),
+        _ptr(V, torch.bfloat16, "V", (hkv, pool, HEAD_DIM)),
+        _ptr(codes, torch.uint8, "codes", (hkv, pool, CODE_ROW_BYTES)),
+        _ptr(seq_start, torch.int64, "seq_start", (batch,)),
+        _ptr(seq_len, torch.int32, "seq_len", (batch,)), batch, k,
+        _ptr(out, torch.float32, "out", (batch, cfg.num_q_heads, HEAD_DIM)),
+        _ptr(idx_out, torch.int32, "idx_out", (batch, cfg.num_q_heads, k), optional=True),
+        max_seq_len, _ptr(workspace, torch.uint8, "workspace"), workspace.numel(),
+        _stream(stream))
+    _check(rc, "adamas_decode_step")

@@ -1,0 +1,372 @@
+// C ABI of the Adamas decode path for MI355X (gfx950): argument checks, the
+// launch plan and the kernel launches.  See include/adamas.h for the contract.
+#include "adamas.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+
+#include "encode.hpp"
+#include "scan.hpp"
+#include "select_attn.hpp"
+
+namespace {
+
+using namespace adamas;
+
+thread_local int g_last_hip_error = 0;
+
+constexpr int kTargetWorkgroups = 256;  // one per compute unit of an MI355X
+constexpr int kMaxSegments = 16;
+constexpr int kAttnPartsMax = 16;
+constexpr double kLog2e = 1.4426950408889634;
+
+// How one call is cut into workgroups and where its scratch lives in the workspace.
+struct Plan {
+  int tile_tokens;   // tokens per scan workgroup (threads = tile_tokens / 4)
+  int n_tiles;       // scan tiles per (sequence, KV head)
+  int seg_len;       // tokens per select workgroup, multiple of tile_tokens and of kSelPass
+  int n_segs;        // select workgroups per (sequence, query head)
+  int n_parts;       // attention partial slots per head
+  int64_t dist_stride;
+  size_t off_dist, off_hist, off_partial, off_counters, total;
+};
+
+size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+int check_config(const adamas_config* c) {
+  if (c == nullptr) return ADAMAS_ERR_BAD_ARG;
+  if (c->num_q_heads < 1 || c->num_kv_heads < 1 || c->pool_tokens < 1 || c->reserved != 0)
+    return ADAMAS_ERR_BAD_ARG;
+  if (c->num_q_heads % c->num_kv_heads != 0) return ADAMAS_ERR_BAD_ARG;
+  if (c->num_q_heads > 65535) return ADAMAS_ERR_BAD_ARG;
+  for (const float* t : {c->thr_k, c->thr_q}) {
+    if (!(std::isfinite(t[0]) && std::isfinite(t[1]) && std::isfinite(t[2]))) return ADAMAS_ERR_BAD_ARG;
+    if (!(t[0] < t[1] && t[1] < t[2])) return ADAMAS_ERR_BAD_ARG;
+  }
+  if (!std::isfinite(c->sm_scale) || c->sm_scale < 0.f) return ADAMAS_ERR_BAD_ARG;
+  if (c->head_dim != ADAMAS_HEAD_DIM) return ADAMAS_ERR_UNSUPPORTED;
+  if (c->num_q_heads / c->num_kv_heads > ADAMAS_MAX_GROUP) return ADAMAS_ERR_UNSUPPORTED;
+  return ADAMAS_OK;
+}
+
+int check_sizes(int32_t batch, int64_t max_seq_len, int32_t k) {
+  if (batch < 1 || batch > 65535 || max_seq_len < 1 || k < 1) return ADAMAS_ERR_BAD_ARG;
+  if (k > ADAMAS_MAX_K || max_seq_len > ADAMAS_MAX_SEQ_LEN) return ADAMAS_ERR_UNSUPPORTED;
+  return ADAMAS_OK;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+Plan make_plan(const adamas_config* c, int32_t batch, int64_t max_seq_len) {
+  Plan pl{};
+  const int64_t planes = (int64_t)batch * c->num_kv_heads;
+  pl.tile_tokens = 1024;
+  for (int tile : {4096, 2048}) {
+    if (planes * ((max_seq_len + tile - 1) / tile) >= kTargetWorkgroups) {
+      pl.tile_tokens = tile;
+      break;
+    }
+  }
+  pl.n_tiles = (int)((max_seq_len + pl.tile_tokens - 1) / pl.tile_tokens);
+  int64_t seg = kSelPass;  // 4096, a multiple of every tile size
+  while ((max_seq_len + seg - 1) / seg > kMaxSegments) seg += kSelPass;
+  pl.seg_len = (int)seg;
+  pl.n_segs = (int)((max_seq_len + seg - 1) / seg);
+  pl.n_parts = kAttnPartsMax;
+  pl.dist_stride = (max_seq_len + 127) & ~(int64_t)127;
+  const size_t heads = (size_t)batch * c->num_q_heads;
+  size_t off = 0;
+  pl.off_dist = off;
+  off = align256(off + heads * (size_t)pl.dist_stride * sizeof(uint16_t));
+  pl.off_hist = off;
+  off = align256(off + heads * (size_t)pl.n_tiles * kHistStride * sizeof(uint16_t));
+  pl.off_partial = off;
+  off = align256(off + heads * (size_t)pl.n_parts * kPartialStride * sizeof(float));
+  pl.off_counters = off;
+  off = align256(off + heads * sizeof(uint32_t));
+  pl.total = off;
+  return pl;
+}
+
+Thresholds scaled(const float thr[3]) {
+  Thresholds t;
+  const double root = std::sqrt((double)ADAMAS_HEAD_DIM);
+  for (int i = 0; i < 3; ++i) t.tau[i] = (double)thr[i] * root;
+  return t;
+}
+
+float scale_log2e(const adamas_config* c) {
+  const double s = c->sm_scale > 0.f ? (double)c->sm_scale : 1.0 / std::sqrt((double)ADAMAS_HEAD_DIM);
+  return (float)(s * kLog2e);
+}
+
+int launch_status() {
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) {
+    g_last_hip_error = (int)e;
+    return ADAMAS_ERR_HIP;
+  }
+  return ADAMAS_OK;
+}
+
+template <bool FUSED>
+void launch_scan(int G, dim3 grid, dim3 block, hipStream_t st, const ScanParams& sp) {
+  switch (G) {
+    case 1: hipLaunchKernelGGL((scan_kernel<1, FUSED>), grid, block, 0, st, sp); break;
+    case 2: hipLaunchKernelGGL((scan_kernel<2, FUSED>), grid, block, 0, st, sp); break;
+    case 3: hipLaunchKernelGGL((scan_kernel<3, FUSED>), grid, block, 0, st, sp); break;
+    case 4: hipLaunchKernelGGL((scan_kernel<4, FUSED>), grid, block, 0, st, sp); break;
+    case 5: hipLaunchKernelGGL((scan_kernel<5, FUSED>), grid, block, 0, st, sp); break;
+    case 6: hipLaunchKernelGGL((scan_kernel<6, FUSED>), grid, block, 0, st, sp); break;
+    case 7: hipLaunchKernelGGL((scan_kernel<7, FUSED>), grid, block, 0, st, sp); break;
+    default: hipLaunchKernelGGL((scan_kernel<8, FUSED>), grid, block, 0, st, sp); break;
+  }
+}
+
+uint8_t* ws_at(void* ws, size_t off) { return static_cast<uint8_t*>(ws) + off; }
+
+}  // namespace
+
+extern "C" {
+
+const char* adamas_status_string(int status) {
+  switch (status) {
+    case ADAMAS_OK: return "ok";
+    case ADAMAS_ERR_BAD_ARG: return "bad argument";
+    case ADAMAS_ERR_UNSUPPORTED: return "unsupported configuration";
+    case ADAMAS_ERR_WORKSPACE: return "workspace too small";
+    case ADAMAS_ERR_HIP: return "HIP launch failed";
+    default: return "unknown status";
+  }
+}
+
+int adamas_last_hip_error(void) { return g_last_hip_error; }
+
+size_t adamas_workspace_bytes(const adamas_config* cfg, int32_t batch, int64_t max_seq_len,
+                              int32_t k) {
+  if (check_config(cfg) != ADAMAS_OK || check_sizes(batch, max_seq_len, k) != ADAMAS_OK) return 0;
+  return make_plan(cfg, batch, max_seq_len).total;
+}
+
+int adamas_encode_keys(const adamas_config* cfg, const void* K, void* codes, int64_t row_begin,
+                       int64_t n_rows, void* stream) {
+  if (int rc = check_config(cfg)) return rc;
+  if (K == nullptr || codes == nullptr || row_begin < 0 || n_rows < 0) return ADAMAS_ERR_BAD_ARG;
+  if (row_begin + n_rows > cfg->pool_tokens) return ADAMAS_ERR_BAD_ARG;
+  if (!aligned16(K) || !aligned16(codes)) return ADAMAS_ERR_BAD_ARG;
+  if (n_rows == 0) return ADAMAS_OK;
+  const int64_t n_vec = n_rows * cfg->num_kv_heads;
+  const int64_t want = (n_vec + 3) / 4;
+  const int grid = (int)(want < 16384 ? want : 16384);
+  hipLaunchKernelGGL(encode_rows_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream,
+                     static_cast<const uint16_t*>(K), static_cast<uint8_t*>(codes),
+                     cfg->pool_tokens, row_begin, n_rows, n_vec, scaled(cfg->thr_k));
+  return launch_status();
+}
+
+int adamas_encode_query(const adamas_config* cfg, const void* q, void* qcodes, int32_t batch,
+                        void* stream) {
+  if (int rc = check_config(cfg)) return rc;
+  if (q == nullptr || qcodes == nullptr || batch < 1 || batch > 65535) return ADAMAS_ERR_BAD_ARG;
+  if (!aligned16(q) || !aligned16(qcodes)) return ADAMAS_ERR_BAD_ARG;
+  const int64_t n_vec = (int64_t)batch * cfg->num_q_heads;
+  const int64_t want = (n_vec + 3) / 4;
+  const int grid = (int)(want < 16384 ? want : 16384);
+  // queries form one "head" of n_vec consecutive rows
+  hipLaunchKernelGGL(encode_rows_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream,
+                     static_cast<const uint16_t*>(q), static_cast<uint8_t*>(qcodes), (int64_t)0,
+                     (int64_t)0, n_vec, n_vec, scaled(cfg->thr_q));
+  return launch_status();
+}
+
+int adamas_manhattan_distance(const adamas_config* cfg, const void* qcodes, const void* codes,
+                              const int64_t* seq_start, const int32_t* seq_len, int32_t batch,
+                              uint16_t* dist_out, int64_t max_seq_len, void* stream) {
+  if (int rc = check_config(cfg)) return rc;
+  if (int rc = check_sizes(batch, max_seq_len, 1)) return rc;
+  if (!qcodes || !codes || !seq_start || !seq_len || !dist_out) return ADAMAS_ERR_BAD_ARG;
+  if (!aligned16(codes) || !aligned16(qcodes)) return ADAMAS_ERR_BAD_ARG;
+  const Plan pl = make_plan(cfg, batch, max_seq_len);
+  ScanParams sp{};
+  sp.codes = static_cast<const uint8_t*>(codes);
+  sp.qcodes = static_cast<const uint8_t*>(qcodes);
+  sp.seq_start = seq_start;
+  sp.seq_len = seq_len;
+  sp.dist_user = dist_out;
+  sp.dist_user_stride = max_seq_len;
+  sp.pool_tokens = cfg->pool_tokens;
+  sp.max_seq_len = max_seq_len;
+  sp.Hq = cfg->num_q_heads;
+  sp.Hkv = cfg->num_kv_heads;
+  sp.n_tiles = pl.n_tiles;
+  launch_scan<false>(cfg->num_q_heads / cfg->num_kv_heads, dim3(pl.n_tiles, cfg->num_kv_heads, batch),
+                     dim3(pl.tile_tokens / kScanTokPerThread), (hipStream_t)stream, sp);
+  return launch_status();
+}
+
+int adamas_select_topk(const adamas_config* cfg, const void* qcodes, const void* codes,
+                       const int64_t* seq_start, const int32_t* seq_len, int32_t batch, int32_t k,
+                       int32_t* idx_out, uint16_t* dist_out, int64_t max_seq_len, void* workspace,
+                       size_t workspace_bytes, void* stream) {
+  if (int rc = check_config(cfg)) return rc;
+  if (int rc = check_sizes(batch, max_seq_len, k)) return rc;
+  if (!qcodes || !codes || !seq_start || !seq_len || !idx_out || !workspace) return ADAMAS_ERR_BAD_ARG;
+  if (!aligned16(codes) || !aligned16(qcodes)) return ADAMAS_ERR_BAD_ARG;
+  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return ADAMAS_ERR_BAD_ARG;
+  const Plan pl = make_plan(cfg, batch, max_seq_len);
+  if (workspace_bytes < pl.total) return ADAMAS_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)stream;
+
+  ScanParams sp{};
+  sp.codes = static_cast<const uint8_t*>(codes);
+  sp.qcodes = static_cast<const uint8_t*>(qcodes);
+  sp.seq_start = seq_start;
+  sp.seq_len = seq_len;
+  sp.dist = reinterpret_cast<uint16_t*>(ws_at(workspace, pl.off_dist));
+  sp.dist_stride = pl.dist_stride;
+  sp.dist_user = dist_out;
+  sp.dist_user_stride = max_seq_len;
+  sp.tilehist = reinterpret_cast<uint16_t*>(ws_at(workspace, pl.off_hist));
+  sp.pool_tokens = cfg->pool_tokens;
+  sp.max_seq_len = max_seq_len;
+  sp.Hq = cfg->num_q_heads;
+  sp.Hkv = cfg->num_kv_heads;
+  sp.n_tiles = pl.n_tiles;
+  launch_scan<false>(cfg->num_q_heads / cfg->num_kv_heads, dim3(pl.n_tiles, cfg->num_kv_heads, batch),
+                     dim3(pl.tile_tokens / kScanTokPerThread), st, sp);
+  if (int rc = launch_status()) return rc;
+
+  SelectParams sl{};
+  sl.dist = sp.dist;
+  sl.dist_stride = pl.dist_stride;
+  sl.tilehist = sp.tilehist;
+  sl.seq_start = seq_start;
+  sl.seq_len = seq_len;
+  sl.idx_out = idx_out;
+  sl.pool_tokens = cfg->pool_tokens;
+  sl.max_seq_len = max_seq_len;
+  sl.Hq = cfg->num_q_heads;
+  sl.Hkv = cfg->num_kv_heads;
+  sl.k = k;
+  sl.n_tiles = pl.n_tiles;
+  sl.tile_tokens = pl.tile_tokens;
+  sl.seg_len = pl.seg_len;
+  sl.n_parts = pl.n_parts;
+  hipLaunchKernelGGL((select_kernel<false>), dim3(pl.n_segs, cfg->num_q_heads, batch),
+                     dim3(kSelThreads), 0, st, sl);
+  return launch_status();
+}
+
+int adamas_sparse_attn(const adamas_config* cfg, const void* q, const void* K, const void* V,
+                       const int64_t* seq_start, const int32_t* idx, int32_t batch, int32_t k,
+                       float* out, int64_t max_seq_len, void* workspace, size_t workspace_bytes,
+                       void* stream) {
+  if (int rc = check_config(cfg)) return rc;
+  if (int rc = check_sizes(batch, max_seq_len, k)) return rc;
+  if (!q || !K || !V || !seq_start || !idx || !out || !workspace) return ADAMAS_ERR_BAD_ARG;
+  if (!aligned16(q) || !aligned16(K) || !aligned16(V)) return ADAMAS_ERR_BAD_ARG;
+  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return ADAMAS_ERR_BAD_ARG;
+  const Plan pl = make_plan(cfg, batch, max_seq_len);
+  if (workspace_bytes < pl.total) return ADAMAS_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)stream;
+  const int64_t heads = (int64_t)batch * cfg->num_q_heads;
+
+  AttnParams ap{};
+  ap.q = static_cast<const uint16_t*>(q);
+  ap.K = static_cast<const uint16_t*>(K);
+  ap.V = static_cast<const uint16_t*>(V);
+  ap.seq_start = seq_start;
+  ap.idx = idx;
+  ap.out = out;
+  ap.partial = reinterpret_cast<float*>(ws_at(workspace, pl.off_partial));
+  ap.counters = reinterpret_cast<uint32_t*>(ws_at(workspace, pl.off_counters));
+  ap.pool_tokens = cfg->pool_tokens;
+  ap.Hq = cfg->num_q_heads;
+  ap.Hkv = cfg->num_kv_heads;
+  ap.k = k;
+  // about 32 rows per workgroup, at most kAttnPartsMax workgroups per head
+  int parts = (k + 31) / 32;
+  if (parts > kAttnPartsMax) parts = kAttnPartsMax;
+  ap.chunk = (k + parts - 1) / parts;
+  ap.n_parts = (k + ap.chunk - 1) / ap.chunk;
+  ap.scale_log2e = scale_log2e(cfg);
+  hipLaunchKernelGGL(zero_u32_kernel, dim3((unsigned)((heads + 255) / 256)), dim3(256), 0, st,
+                     ap.counters, heads);
+  if (int rc = launch_status()) return rc;
+  hipLaunchKernelGGL(sparse_attn_kernel, dim3(ap.n_parts, cfg->num_q_heads, batch),
+                     dim3(kSelThreads), 0, st, ap);
+  return launch_status();
+}
+
+int adamas_decode_step(const adamas_config* cfg, const void* q, const void* k_new,
+                       const void* v_new, void* K, void* V, void* codes, const int64_t* seq_start,
+                       const int32_t* seq_len, int32_t batch, int32_t k, float* out,
+                       int32_t* idx_out, int64_t max_seq_len, void* workspace,
+                       size_t workspace_bytes, void* stream) {
+  if (int rc = check_config(cfg)) return rc;
+  if (int rc = check_sizes(batch, max_seq_len, k)) return rc;
+  if (!q || !K || !V || !codes || !seq_start || !seq_len || !out || !workspace) return ADAMAS_ERR_BAD_ARG;
+  if ((k_new == nullptr) != (v_new == nullptr)) return ADAMAS_ERR_BAD_ARG;
+  if (!aligned16(q) || !aligned16(K) || !aligned16(V) || !aligned16(codes)) return ADAMAS_ERR_BAD_ARG;
+  if (k_new && (!aligned16(k_new) || !aligned16(v_new))) return ADAMAS_ERR_BAD_ARG;
+  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return ADAMAS_ERR_BAD_ARG;
+  const Plan pl = make_plan(cfg, batch, max_seq_len);
+  if (workspace_bytes < pl.total) return ADAMAS_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)stream;
+
+  ScanParams sp{};
+  sp.codes = static_cast<const uint8_t*>(codes);
+  sp.codes_w = static_cast<uint8_t*>(codes);
+  sp.q = static_cast<const uint16_t*>(q);
+  sp.k_new = static_cast<const uint16_t*>(k_new);
+  sp.v_new = static_cast<const uint16_t*>(v_new);
+  sp.K = static_cast<uint16_t*>(K);
+  sp.V = static_cast<uint16_t*>(V);
+  sp.seq_start = seq_start;
+  sp.seq_len = seq_len;
+  sp.dist = reinterpret_cast<uint16_t*>(ws_at(workspace, pl.off_dist));
+  sp.dist_stride = pl.dist_stride;
+  sp.tilehist = reinterpret_cast<uint16_t*>(ws_at(workspace, pl.off_hist));
+  sp.counters = reinterpret_cast<uint32_t*>(ws_at(workspace, pl.off_counters));
+  sp.pool_tokens = cfg->pool_tokens;
+  sp.max_seq_len = max_seq_len;
+  sp.Hq = cfg->num_q_heads;
+  sp.Hkv = cfg->num_kv_heads;
+  sp.n_tiles = pl.n_tiles;
+  sp.thr_q = scaled(cfg->thr_q);
+  sp.thr_k = scaled(cfg->thr_k);
+  launch_scan<true>(cfg->num_q_heads / cfg->num_kv_heads, dim3(pl.n_tiles, cfg->num_kv_heads, batch),
+                    dim3(pl.tile_tokens / kScanTokPerThread), st, sp);
+  if (int rc = launch_status()) return rc;
+
+  SelectParams sl{};
+  sl.dist = sp.dist;
+  sl.dist_stride = pl.dist_stride;
+  sl.tilehist = sp.tilehist;
+  sl.seq_start = seq_start;
+  sl.seq_len = seq_len;
+  sl.idx_out = idx_out;
+  sl.q = sp.q;
+  sl.K = sp.K;
+  sl.V = sp.V;
+  sl.out = out;
+  sl.partial = reinterpret_cast<float*>(ws_at(workspace, pl.off_partial));
+  sl.counters = sp.counters;
+  sl.pool_tokens = cfg->pool_tokens;
+  sl.max_seq_len = max_seq_len;
+  sl.Hq = cfg->num_q_heads;
+  sl.Hkv = cfg->num_kv_heads;
+  sl.k = k;
+  sl.n_tiles = pl.n_tiles;
+  sl.tile_tokens = pl.tile_tokens;
+  sl.seg_len = pl.seg_len;
+  sl.n_parts = pl.n_parts;
+  sl.scale_log2e = scale_log2e(cfg);
+  hipLaunchKernelGGL((select_kernel<true>), dim3(pl.n_segs, cfg->num_q_heads, batch),
+                     dim3(kSelThreads), 0, st, sl);
+  return launch_status();
+}
+
+}  // extern "C"

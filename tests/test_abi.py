@@ -1,0 +1,155 @@
+"""CPU-side checks of the C ABI: the library loads, exports what the header declares, and
+rejects bad arguments before touching the GPU (none of these calls launches anything)."""
+
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2510_18413_amd as A
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = ctypes.c_void_p(0x1000)      # non-null, 256-byte aligned; never dereferenced on these paths
+ODD = ctypes.c_void_p(0x1008)
+
+
+def header_functions():
+    text = open(os.path.join(ROOT, "include", "adamas.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(adamas_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = A.library()
+    declared = header_functions()
+    assert len(declared) >= 9
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert sorted(A.EXPORTED_SYMBOLS) == declared
+
+
+def test_status_strings():
+    assert A.adamas_status_string(0) == "ok"
+    for code in (-1, -2, -3, -4, -99):
+        assert A.adamas_status_string(code)
+
+
+def cfg(**kw):
+    base = dict(num_q_heads=32, num_kv_heads=8, pool_tokens=32768)
+    base.update(kw)
+    return A.Config.make(**base)
+
+
+def test_workspace_bytes():
+    c = cfg()
+    w = A.adamas_workspace_bytes(c, 1, 32768, 128)
+    assert w > 32 * 32768 * 2 and w % 256 == 0
+    assert A.adamas_workspace_bytes(c, 2, 32768, 128) > w
+    assert A.adamas_workspace_bytes(c, 1, 65536, 128) > w
+    assert A.adamas_workspace_bytes(c, 0, 32768, 128) == 0
+    assert A.adamas_workspace_bytes(c, 1, 0, 128) == 0
+    assert A.adamas_workspace_bytes(c, 1, 32768, 0) == 0
+    assert A.adamas_workspace_bytes(c, 1, 32768, 4097) == 0
+    assert A.adamas_workspace_bytes(c, 1, (1 << 20) + 1, 128) == 0
+    assert A.adamas_workspace_bytes(cfg(head_dim=64), 1, 32768, 128) == 0
+
+
+@pytest.mark.parametrize("bad, status", [
+    (dict(head_dim=64), -2),
+    (dict(num_q_heads=32, num_kv_heads=3), -1),
+    (dict(num_q_heads=0), -1),
+    (dict(pool_tokens=0), -1),
+    (dict(thr_k=(0.0, 0.0, 1.0)), -1),
+    (dict(thr_q=(1.0, 0.0, -1.0)), -1),
+    (dict(thr_k=(float("nan"), 0.0, 1.0)), -1),
+    (dict(sm_scale=-1.0), -1),
+    (dict(sm_scale=float("inf")), -1),
+    (dict(num_q_heads=32, num_kv_heads=2), -2),        # group of 16 > ADAMAS_MAX_GROUP
+])
+def test_bad_config_rejected_everywhere(bad, status):
+    lib, c = A.library(), cfg(**bad)
+    p = ctypes.byref(c)
+    assert lib.adamas_encode_keys(p, FAKE, FAKE, 0, 16, None) == status
+    assert lib.adamas_encode_query(p, FAKE, FAKE, 1, None) == status
+    assert lib.adamas_manhattan_distance(p, FAKE, FAKE, FAKE, FAKE, 1, FAKE, 1024, None) == status
+    assert lib.adamas_select_topk(p, FAKE, FAKE, FAKE, FAKE, 1, 64, FAKE, None, 1024, FAKE,
+                                  1 << 30, None) == status
+    assert lib.adamas_sparse_attn(p, FAKE, FAKE, FAKE, FAKE, FAKE, 1, 64, FAKE, 1024, FAKE,
+                                  1 << 30, None) == status
+    assert lib.adamas_decode_step(p, FAKE, None, None, FAKE, FAKE, FAKE, FAKE, FAKE, 1, 64, FAKE,
+                                  None, 1024, FAKE, 1 << 30, None) == status
+
+
+def test_null_and_misaligned_pointers_rejected():
+    lib, c = A.library(), cfg()
+    p = ctypes.byref(c)
+    assert lib.adamas_encode_keys(None, FAKE, FAKE, 0, 16, None) == -1
+    assert lib.adamas_encode_keys(p, None, FAKE, 0, 16, None) == -1
+    assert lib.adamas_encode_keys(p, FAKE, None, 0, 16, None) == -1
+    assert lib.adamas_encode_keys(p, ODD, FAKE, 0, 16, None) == -1
+    assert lib.adamas_encode_keys(p, FAKE, FAKE, -1, 16, None) == -1
+    assert lib.adamas_encode_keys(p, FAKE, FAKE, 32760, 16, None) == -1      # past the pool
+    assert lib.adamas_encode_keys(p, FAKE, FAKE, 0, 0, None) == 0            # empty: no-op
+    assert lib.adamas_encode_query(p, FAKE, FAKE, 0, None) == -1
+    assert lib.adamas_manhattan_distance(p, FAKE, FAKE, None, FAKE, 1, FAKE, 1024, None) == -1
+    assert lib.adamas_manhattan_distance(p, FAKE, FAKE, FAKE, FAKE, 1, None, 1024, None) == -1
+    args = [p, FAKE, FAKE, FAKE, FAKE, 1, 64, FAKE, None, 1024, FAKE, 1 << 30, None]
+    for pos in (1, 2, 3, 4, 7, 10):
+        a = list(args)
+        a[pos] = None
+        assert lib.adamas_select_topk(*a) == -1
+    a = list(args)
+    a[10] = ODD
+    assert lib.adamas_select_topk(*a) == -1                                   # workspace alignment
+    dargs = [p, FAKE, None, None, FAKE, FAKE, FAKE, FAKE, FAKE, 1, 64, FAKE, None, 1024, FAKE,
+             1 << 30, None]
+    for pos in (1, 4, 5, 6, 7, 8, 11, 14):
+        a = list(dargs)
+        a[pos] = None
+        assert lib.adamas_decode_step(*a) == -1
+    a = list(dargs)
+    a[2] = FAKE                                                               # k_new without v_new
+    assert lib.adamas_decode_step(*a) == -1
+
+
+def test_size_limits_and_workspace_check():
+    lib, c = A.library(), cfg()
+    p = ctypes.byref(c)
+    need = A.adamas_workspace_bytes(c, 1, 1024, 64)
+    base = [p, FAKE, FAKE, FAKE, FAKE, 1, 64, FAKE, None, 1024, FAKE, need - 1, None]
+    assert lib.adamas_select_topk(*base) == -3
+    for k, st in ((0, -1), (-5, -1), (4097, -2)):
+        a = list(base)
+        a[6] = k
+        assert lib.adamas_select_topk(*a) == st
+    a = list(base)
+    a[9] = (1 << 20) + 1
+    assert lib.adamas_select_topk(*a) == -2
+    a = list(base)
+    a[5] = 0
+    assert lib.adamas_select_topk(*a) == -1
+    d = [p, FAKE, None, None, FAKE, FAKE, FAKE, FAKE, FAKE, 1, 64, FAKE, None, 1024, FAKE, need - 1,
+         None]
+    assert lib.adamas_decode_step(*d) == -3
+    s = [p, FAKE, FAKE, FAKE, FAKE, FAKE, 1, 64, FAKE, 1024, FAKE, need - 1, None]
+    assert lib.adamas_sparse_attn(*s) == -3
+
+
+def test_binding_rejects_cpu_tensors():
+    import torch
+    c = cfg(num_q_heads=1, num_kv_heads=1, pool_tokens=8)
+    K = torch.zeros(1, 8, 128, dtype=torch.bfloat16)
+    codes = torch.zeros(1, 8, 32, dtype=torch.uint8)
+    with pytest.raises(ValueError):
+        A.adamas_encode_keys(c, K, codes, 0, 8, stream=0)
+
+
+def test_product_code_never_touches_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2510_18413_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".hpp", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.lower(), os.path.join(dirpath, f)
+    assert "oracle" not in open(os.path.join(ROOT, "include", "adamas.h")).read().lower()

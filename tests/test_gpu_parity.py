@@ -1,0 +1,265 @@
+"""GPU parity: every C-ABI entry point against the CPU oracle on the same seeded inputs.
+
+Codes, distances and indices must match bit for bit; attention outputs within ATTN_TOL.
+Sizes here are small enough for the oracle to finish in seconds but span several scan tiles,
+select segments and ragged tails.  Full-size configurations live in test_gpu_configs.py.
+"""
+
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def H():
+    import gpu_harness
+    assert torch.cuda.is_available()
+    return gpu_harness
+
+
+def small_case(seed, B, Hq, Hkv, lens, append=False, needles=1):
+    G = Hq // Hkv
+    return synth.make_case("small", seed, B, Hq, Hkv, lens, [0],
+                           lambda b, L, h, rng: rng.choice(L, (G, min(needles, L // G)), replace=False),
+                           append=append)
+
+
+# ----------------------------------------------------------------------------- encode
+
+def test_encode_keys_and_query_bit_exact(H, oracle):
+    import paper_2510_18413_amd as A
+    case = small_case(101, 2, 8, 4, [777, 1300])
+    d = H.DeviceCase(case, 16)
+    torch.cuda.synchronize()
+    _, rows = oracle.encode(case.K, case.thresholds)
+    assert np.array_equal(d.codes.cpu().numpy(), rows)
+    qcodes = torch.zeros(case.B, case.Hq, 32, dtype=torch.uint8, device="cuda")
+    A.adamas_encode_query(d.cfg, d.q, qcodes)
+    torch.cuda.synchronize()
+    assert np.array_equal(qcodes.cpu().numpy(), oracle.encode(case.q, case.thresholds)[1])
+
+
+def test_encode_keys_row_ranges_and_thresholds(H, oracle):
+    import paper_2510_18413_amd as A
+    case = small_case(102, 1, 2, 2, [500])
+    thr = (-0.4, 0.25, 1.7)
+    cfg = A.Config.make(2, 2, case.pool_tokens, thr_k=thr)
+    K = H.dev_bf16(case.K)
+    codes = torch.full((2, case.pool_tokens, 32), 0xEE, dtype=torch.uint8, device="cuda")
+    A.adamas_encode_keys(cfg, K, codes, 37, 101)
+    torch.cuda.synchronize()
+    got = codes.cpu().numpy()
+    _, rows = oracle.encode(case.K, thr)
+    assert np.array_equal(got[:, 37:138], rows[:, 37:138])
+    assert np.all(got[:, :37] == 0xEE) and np.all(got[:, 138:] == 0xEE)   # untouched outside
+
+
+def test_encode_values_on_thresholds_and_zeros(H, oracle):
+    import paper_2510_18413_amd as A
+    # vectors whose transform hits thresholds exactly: +-e_i combinations give coefficients in
+    # {0, +-2, ...}; with thresholds at 2/sqrt(128) multiples the strict '>' decides.
+    x = np.zeros((6, 128), dtype=np.float32)
+    x[1, 0] = 1.0
+    x[2, 0], x[2, 1] = 1.0, -1.0
+    x[3, 5], x[3, 77] = 0.5, 0.5
+    x[4, :] = 0.125
+    x[5, 3] = -0.0
+    bits = synth.f32_to_bf16_bits(x)
+    root = np.float32(np.sqrt(128.0))
+    for thr in ((-1.0, 0.0, 1.0), (0.0, float(np.float32(1.0) / root), float(np.float32(2.0) / root))):
+        cfg = A.Config.make(1, 1, 6, thr_k=thr)
+        K = H.dev_bf16(bits.reshape(1, 6, 128))
+        codes = torch.zeros(1, 6, 32, dtype=torch.uint8, device="cuda")
+        A.adamas_encode_keys(cfg, K, codes, 0, 6)
+        torch.cuda.synchronize()
+        assert np.array_equal(codes.cpu().numpy()[0], oracle.encode(bits, thr)[1])
+
+
+# -------------------------------------------------------------------- distance + top-k
+
+@pytest.mark.parametrize("B,Hq,Hkv,lens,k", [
+    (1, 1, 1, [1024], 64),
+    (1, 4, 4, [5000], 128),          # two 4096-token segments with a ragged tail
+    (2, 8, 2, [4097, 333], 256),     # GQA group 4, k close to one sequence's length
+    (3, 6, 2, [1, 64, 65], 8),       # group 3, tiny sequences
+    (1, 8, 1, [9000], 100),          # group 8
+    (1, 2, 2, [70000], 1024),        # 18 segments -> longer segments, several passes
+])
+def test_distance_and_topk_bit_exact(H, oracle, B, Hq, Hkv, lens, k):
+    import paper_2510_18413_amd as A
+    case = small_case(200 + Hq + B, B, Hq, Hkv, lens)
+    d = H.DeviceCase(case, k)
+    qcodes = torch.zeros(B, Hq, 32, dtype=torch.uint8, device="cuda")
+    A.adamas_encode_query(d.cfg, d.q, qcodes)
+    dist = torch.full((B, Hq, d.max_len), 0xFFFF, dtype=torch.uint16, device="cuda")
+    A.adamas_manhattan_distance(d.cfg, qcodes, d.codes, d.seq_start, d.seq_len, dist)
+    dist2 = torch.full((B, Hq, d.max_len), 0xFFFF, dtype=torch.uint16, device="cuda")
+    A.adamas_select_topk(d.cfg, qcodes, d.codes, d.seq_start, d.seq_len, k, d.idx, d.max_len,
+                         d.workspace, dist_out=dist2)
+    torch.cuda.synchronize()
+    ref = H.oracle_step(case, k)
+    got, got2 = H.host_dist(dist), H.host_dist(dist2)
+    for b in range(B):
+        L = int(case.seq_len[b])
+        assert np.array_equal(got[b, :, :L], ref["dist"][b, :, :L])
+        assert np.array_equal(got2[b, :, :L], ref["dist"][b, :, :L])
+        assert np.all(got[b, :, L:] == 0xFFFF)                 # untouched past the sequence
+    assert np.array_equal(d.idx.cpu().numpy(), ref["idx"])
+
+
+def test_topk_ties_everywhere(H, oracle):
+    """All keys identical: every distance equal, so the rule 'lowest position first' decides
+    everything; then two distance levels with the boundary inside the second."""
+    import paper_2510_18413_amd as A
+    case = small_case(301, 1, 2, 1, [6000])
+    case.K[0, :] = case.K[0, 0]
+    case.K[0, 4500:4600] = synth.f32_to_bf16_bits(
+        synth.bf16_bits_to_f32(case.q[0, 0]))                  # 100 near-exact matches of head 0
+    for k in (1, 37, 100, 101, 4096):
+        d = H.DeviceCase(case, k)
+        qcodes = torch.zeros(1, 2, 32, dtype=torch.uint8, device="cuda")
+        A.adamas_encode_query(d.cfg, d.q, qcodes)
+        A.adamas_select_topk(d.cfg, qcodes, d.codes, d.seq_start, d.seq_len, k, d.idx, d.max_len,
+                             d.workspace)
+        torch.cuda.synchronize()
+        ref = H.oracle_step(case, k, want_dist=False)
+        assert np.array_equal(d.idx.cpu().numpy(), ref["idx"]), k
+
+
+def test_topk_k_at_least_length_and_empty(H, oracle):
+    import paper_2510_18413_amd as A
+    case = small_case(302, 3, 2, 2, [0, 5, 300], needles=0)
+    k = 300
+    d = H.DeviceCase(case, k)
+    qcodes = torch.zeros(3, 2, 32, dtype=torch.uint8, device="cuda")
+    A.adamas_encode_query(d.cfg, d.q, qcodes)
+    A.adamas_select_topk(d.cfg, qcodes, d.codes, d.seq_start, d.seq_len, k, d.idx, d.max_len,
+                         d.workspace)
+    torch.cuda.synchronize()
+    got = d.idx.cpu().numpy()
+    assert np.all(got[0] == -1)
+    assert np.all(got[1, :, :5] == np.arange(5)) and np.all(got[1, :, 5:] == -1)
+    assert np.all(got[2] == np.arange(300))
+    assert np.array_equal(got, H.oracle_step(case, k, want_dist=False)["idx"])
+
+
+# ------------------------------------------------------------------- sparse attention
+
+def test_sparse_attn_matches_oracle(H, oracle):
+    import paper_2510_18413_amd as A
+    case = small_case(401, 2, 4, 2, [900, 2000])
+    for k in (1, 17, 64, 700):
+        d = H.DeviceCase(case, k, encode=False)
+        rng = np.random.default_rng(k)
+        idx = np.full((2, 4, k), -1, dtype=np.int32)
+        for b in range(2):
+            for h in range(4):
+                n = int(rng.integers(0, k + 1)) if (b, h) != (0, 0) else k
+                if (b, h) == (1, 3):
+                    n = 0                                         # nothing selected -> zeros
+                sel = np.sort(rng.choice(int(case.seq_len[b]), n, replace=False))
+                slots = np.sort(rng.choice(k, n, replace=False))  # -1 holes anywhere
+                idx[b, h, slots] = sel
+        A.adamas_sparse_attn(d.cfg, d.q, d.K, d.V, d.seq_start, torch.from_numpy(idx).cuda(), d.out,
+                             d.max_len, d.workspace)
+        torch.cuda.synchronize()
+        got = d.out.cpu().numpy()
+        ref = np.zeros_like(got)
+        for b in range(2):
+            s, L = int(case.seq_start[b]), int(case.seq_len[b])
+            for h in range(4):
+                ref[b, h] = oracle.sparse_attention(case.q[b, h], case.K[h // 2, s:s + L],
+                                                    case.V[h // 2, s:s + L], idx[b, h], H.SM_SCALE)
+        assert np.all(got[1, 3] == 0)
+        assert H.attn_rel_err(got, ref) <= H.ATTN_TOL
+
+
+def test_sparse_attn_equals_full_attention_when_all_rows_listed(H, oracle):
+    import paper_2510_18413_amd as A
+    case = small_case(402, 1, 2, 1, [513])
+    d = H.DeviceCase(case, 513, encode=False)
+    idx = torch.arange(513, dtype=torch.int32, device="cuda").repeat(1, 2, 1)
+    A.adamas_sparse_attn(d.cfg, d.q, d.K, d.V, d.seq_start, idx, d.out, d.max_len, d.workspace)
+    torch.cuda.synchronize()
+    ref = np.stack([oracle.full_attention(case.q[0, h], case.K[0, :513], case.V[0, :513], H.SM_SCALE)
+                    for h in range(2)])[None]
+    assert H.attn_rel_err(d.out.cpu().numpy(), ref) <= H.ATTN_TOL
+
+
+def test_sparse_attn_large_scores_do_not_overflow(H, oracle):
+    import paper_2510_18413_amd as A
+    case = small_case(403, 1, 1, 1, [64])
+    case.q[:] = synth.f32_to_bf16_bits(np.full(128, 30.0, np.float32))
+    case.K[0, :32] = synth.f32_to_bf16_bits(np.full(128, 30.0, np.float32))
+    d = H.DeviceCase(case, 64, encode=False)
+    idx = torch.arange(64, dtype=torch.int32, device="cuda").view(1, 1, 64)
+    A.adamas_sparse_attn(d.cfg, d.q, d.K, d.V, d.seq_start, idx, d.out, d.max_len, d.workspace)
+    torch.cuda.synchronize()
+    ref = oracle.full_attention(case.q[0, 0], case.K[0, :64], case.V[0, :64], H.SM_SCALE)[None, None]
+    got = d.out.cpu().numpy()
+    assert np.all(np.isfinite(got)) and H.attn_rel_err(got, ref) <= H.ATTN_TOL
+
+
+# ----------------------------------------------------------------------- fused decode step
+
+@pytest.mark.parametrize("B,Hq,Hkv,lens,k,append", [
+    (1, 1, 1, [1024], 64, False),
+    (1, 4, 4, [5000], 128, False),
+    (2, 8, 2, [4097, 333], 256, True),
+    (4, 8, 2, [0, 1, 4096, 8193], 64, True),
+    (3, 6, 2, [100, 64, 65], 128, False),      # k above every length: full attention
+    (1, 8, 1, [20000], 4096, True),
+    (1, 2, 2, [70000], 1024, False),
+])
+def test_decode_step_matches_oracle(H, oracle, B, Hq, Hkv, lens, k, append):
+    case = small_case(500 + B + Hq, B, Hq, Hkv, lens, append=append)
+    d = H.DeviceCase(case, k)
+    out, idx = d.decode_step()
+    ref = H.oracle_step(case, k, want_dist=False)
+    assert np.array_equal(idx, ref["idx"])
+    assert H.attn_rel_err(out, ref["out"]) <= H.ATTN_TOL
+    for b in range(B):
+        if case.seq_len[b] == 0:
+            assert np.all(out[b] == 0) and np.all(idx[b] == -1)
+    if append:   # Alg. 1 line 4: cache rows and code rows of the new token, bit for bit
+        assert np.array_equal(H.host_u16(d.K), ref["K"])
+        assert np.array_equal(H.host_u16(d.V), ref["V"])
+        assert np.array_equal(d.codes.cpu().numpy(), ref["rows"])
+    # same call without the index output, on a fresh poisoned workspace: same attention result
+    d2 = H.DeviceCase(case, k)
+    out2, _ = d2.decode_step(with_idx=False)
+    assert np.array_equal(out, out2)
+
+
+def test_decode_step_repeatable_and_workspace_reusable(H, oracle):
+    case = small_case(601, 2, 8, 2, [3000, 9000])
+    d = H.DeviceCase(case, 128)
+    first = d.decode_step()
+    for _ in range(3):
+        again = d.decode_step()
+        assert np.array_equal(first[0], again[0]) and np.array_equal(first[1], again[1])
+
+
+def test_appended_token_is_a_candidate(H, oracle):
+    case = small_case(602, 1, 2, 2, [4097], append=True)     # new token alone in the 2nd segment
+    case.q[0, 0] = case.k_new[0, 0]
+    d = H.DeviceCase(case, 8)
+    out, idx = d.decode_step()
+    assert 4096 in idx[0, 0].tolist()
+    ref = H.oracle_step(case, 8, want_dist=False)
+    assert np.array_equal(idx, ref["idx"]) and H.attn_rel_err(out, ref["out"]) <= H.ATTN_TOL
+
+
+def test_invalid_device_lengths_are_treated_as_empty(H, oracle):
+    case = small_case(603, 2, 2, 2, [500, 600], needles=0)
+    d = H.DeviceCase(case, 16)
+    d.seq_len = torch.tensor([500, 10 ** 6], dtype=torch.int32, device="cuda")   # beyond max/pool
+    out, idx = d.decode_step()
+    assert np.all(idx[1] == -1) and np.all(out[1] == 0)
+    case.seq_len[1] = 0
+    ref = H.oracle_step(case, 16, want_dist=False)
+    assert np.array_equal(idx[0], ref["idx"][0])
