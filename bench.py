@@ -1,0 +1,328 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused Adamas decode step on one MI355X.
+
+A "step" is one call of adamas_decode_step for one attention layer: query encode, (optional)
+append, Manhattan-distance scan over the whole code plane, top-k, gather and sparse attention
+(Algorithm 1, lines 1-8).  Steps rotate over `--layers` distinct layer caches so that the
+256 MB last-level cache cannot stand in for HBM, and are replayed from a HIP graph that holds
+one sweep over all layers (launch latency of the Python caller is not what is measured).
+
+Prints ONE JSON line ("Measurement").
+"""
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E peak
+
+WORKLOADS = {
+    # name: (B, Hq, Hkv, context, default k, append, ragged)
+    "cfg1": dict(B=1, Hq=32, Hkv=32, L=32768, k=256, append=False, ragged=False,
+                 text="config 1: Llama-style MHA layer decode, batch 1, 32 query = 32 KV heads, "
+                      "head_dim 128, context 32768, all keys pre-encoded, no append"),
+    "cfg2": dict(B=1, Hq=32, Hkv=8, L=32768, k=128, append=False, ragged=False,
+                 text="config 2: GQA layer decode, batch 1, 32 query / 8 KV heads, context 32768"),
+    "cfg3": dict(B=1, Hq=32, Hkv=8, L=131072, k=1024, append=True, ragged=False,
+                 text="config 3: long-context decode, 32 query / 8 KV heads, context 131072 "
+                      "after appending one token per step"),
+    "cfg4": dict(B=16, Hq=32, Hkv=8, L=32768, k=128, append=False, ragged=True,
+                 text="config 4: batched decode, 16 sequences with lengths uniform in "
+                      "[8192, 32768], 32 query / 8 KV heads, ragged pool"),
+}
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=6400)
+    ap.add_argument("--warmup", type=int, default=640)
+    ap.add_argument("--config", default="cfg1", choices=sorted(WORKLOADS))
+    ap.add_argument("--k", type=int, default=0, help="token budget (0: the workload's default)")
+    ap.add_argument("--layers", type=int, default=32, help="distinct layer caches to rotate over")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--eager", action="store_true", help="launch from Python instead of a graph")
+    return ap.parse_args()
+
+
+def algorithmic_bytes(B, Hq, Hkv, lens, k, append):
+    """Bytes the method itself must move per step: every code row once per KV head, every
+    selected K and V row once per query head, q in, out back, plus the appended rows."""
+    codes = Hkv * sum(lens) * 32
+    gather = Hq * sum(min(k, L) for L in lens) * 512
+    small = B * Hq * (256 + 512)
+    app = B * Hkv * (2 * 512 + 32) if append else 0
+    return codes + gather + small + app, codes
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        sys.stderr.write("bench.py: this build measures one GPU only (every stage of the path "
+                         "runs on one MI355X and no collective exists); --gpus %d is not "
+                         "supported.\n" % args.gpus)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2510_18413_amd as A
+    import synth_inputs as synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    wl = WORKLOADS[args.config]
+    B, Hq, Hkv, G = wl["B"], wl["Hq"], wl["Hkv"], wl["Hq"] // wl["Hkv"]
+    k = args.k or wl["k"]
+    append = wl["append"]
+    n_layers = max(1, args.layers)
+    cfg_id = int(args.config[3:])
+
+    # ------------------------------------------------------------------ inputs
+    if wl["ragged"]:
+        lens = np.random.default_rng(synth.config_seed(cfg_id) + 500).integers(
+            8192, wl["L"] + 1, size=B).astype(np.int32)
+    else:
+        lens = np.full(B, wl["L"], dtype=np.int32)
+    starts = np.zeros(B, dtype=np.int64)
+    pos = 0
+    for b in range(B):
+        starts[b] = pos
+        pos += int(lens[b]) + synth.SEQ_GAP_ROWS
+    pool = pos - synth.SEQ_GAP_ROWS
+    max_len = int(lens.max())
+    cfg = A.Config.make(Hq, Hkv, pool, thr_k=synth.DEFAULT_THRESHOLDS)
+    seq_start = torch.from_numpy(starts).to(dev)
+    seq_len = torch.from_numpy(lens).to(dev)
+
+    def gen_layer(layer):
+        """Same recipe as synth_inputs (N(0,1) bf16, 4 outlier channels x8 per KV head, one
+        needle per query head, tiny magnitudes flushed to 0), drawn on the GPU."""
+        g = torch.Generator(device=dev)
+        g.manual_seed(synth.config_seed(cfg_id, layer))
+
+        def rows(n, scale):
+            x = torch.randn(n, 128, generator=g, device=dev) * scale
+            return torch.where(x.abs() < synth.FLUSH_BELOW, torch.zeros_like(x), x)
+
+        K = torch.empty(Hkv, pool, 128, dtype=torch.bfloat16, device=dev)
+        V = torch.empty(Hkv, pool, 128, dtype=torch.bfloat16, device=dev)
+        q = torch.empty(B, Hq, 128, dtype=torch.bfloat16, device=dev)
+        k_new = torch.empty(B, Hkv, 128, dtype=torch.bfloat16, device=dev) if append else None
+        v_new = torch.empty(B, Hkv, 128, dtype=torch.bfloat16, device=dev) if append else None
+        for h in range(Hkv):
+            sk = torch.ones(128, device=dev)
+            sk[torch.randperm(128, generator=g, device=dev)[:4]] = synth.OUTLIER_SCALE
+            sv = torch.ones(128, device=dev)
+            sv[torch.randperm(128, generator=g, device=dev)[:4]] = synth.OUTLIER_SCALE
+            K[h] = rows(pool, sk).to(torch.bfloat16)
+            V[h] = rows(pool, sv).to(torch.bfloat16)
+            for b in range(B):
+                cached = int(lens[b]) - (1 if append else 0)
+                if append:
+                    k_new[b, h] = rows(1, sk)[0].to(torch.bfloat16)
+                    v_new[b, h] = rows(1, sv)[0].to(torch.bfloat16)
+                where = torch.randperm(cached, generator=g, device=dev)[:G].tolist()
+                for gq in range(G):
+                    u = rows(1, sk)[0]
+                    q[b, h * G + gq] = (u + synth.NEEDLE_SIGMA * torch.randn(
+                        128, generator=g, device=dev)).to(torch.bfloat16)
+                    K[h, int(starts[b]) + where[gq]] = (u + synth.NEEDLE_SIGMA * torch.randn(
+                        128, generator=g, device=dev)).to(torch.bfloat16)
+        return dict(q=q, K=K, V=V, k_new=k_new, v_new=v_new)
+
+    def upload_case(case):
+        def d(a):
+            return None if a is None else torch.from_numpy(
+                np.ascontiguousarray(a).view(np.int16)).view(torch.bfloat16).to(dev)
+        return dict(q=d(case.q), K=d(case.K), V=d(case.V), k_new=d(case.k_new), v_new=d(case.v_new))
+
+    t_gen = time.time()
+    layers = []
+    case0 = None
+    for layer in range(n_layers):
+        if layer == 0 and args.config == "cfg1":
+            case0 = synth.mha_32k(layer=0)      # the numpy recipe: checked against the oracle below
+            data = upload_case(case0)
+        else:
+            data = gen_layer(layer)
+        data["codes"] = torch.empty(Hkv, pool, 32, dtype=torch.uint8, device=dev)
+        data["out"] = torch.zeros(B, Hq, 128, device=dev)
+        A.adamas_encode_keys(cfg, data["K"], data["codes"], 0, pool)
+        layers.append(data)
+    idx0 = torch.empty(B, Hq, k, dtype=torch.int32, device=dev)
+    ws = torch.empty(A.adamas_workspace_bytes(cfg, B, max_len, k), dtype=torch.uint8, device=dev)
+    torch.cuda.synchronize()
+    t_gen = time.time() - t_gen
+
+    def step(i, stages=None):
+        d = layers[i % n_layers]
+        A.adamas_decode_step_stages(cfg, d["q"], d["K"], d["V"], d["codes"], seq_start, seq_len, k,
+                                    d["out"], max_len, ws, k_new=d["k_new"], v_new=d["v_new"],
+                                    idx_out=idx0 if (i % n_layers == 0) else None, stages=stages)
+
+    # With an append every step rewrites the same last row with the same values: the cache
+    # length stays fixed, so all timed steps do identical work.
+
+    def make_graph(stages):
+        for i in range(n_layers):      # warm the code path before capture
+            step(i, stages)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for i in range(n_layers):
+                step(i, stages)
+        return g
+
+    def timed(stages, steps, warmup):
+        """Returns (ms per step from HIP events, ms per step wall, per-sweep event ms list)."""
+        if args.eager:
+            for i in range(warmup):
+                step(i, stages)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            t0 = time.perf_counter()
+            e0.record()
+            for i in range(steps):
+                step(i, stages)
+            e1.record()
+            torch.cuda.synchronize()
+            wall = (time.perf_counter() - t0) * 1e3
+            return e0.elapsed_time(e1) / steps, wall / steps, []
+        g = make_graph(stages)
+        sweeps, rem = divmod(steps, n_layers)
+        for _ in range(max(1, warmup // n_layers)):
+            g.replay()
+        torch.cuda.synchronize()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(sweeps + 2)]
+        t0 = time.perf_counter()
+        ev[0].record()
+        for s in range(sweeps):
+            g.replay()
+            ev[s + 1].record()
+        for i in range(rem):
+            step(i, stages)
+        ev[sweeps + 1].record()
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t0) * 1e3
+        per_sweep = [ev[s].elapsed_time(ev[s + 1]) for s in range(sweeps)]
+        return ev[0].elapsed_time(ev[sweeps + 1]) / steps, wall / steps, per_sweep
+
+    # ------------------------------------------------------------------ the timed region
+    ms_evt, ms_wall, per_sweep = timed(None, args.steps, args.warmup)
+    us_step = ms_wall * 1e3
+    # dominant kernel alone (distance scan with fused query encode), same rotation
+    ms_scan, _, _ = timed(A.STAGE_SCAN, max(n_layers, args.steps // 4), args.warmup // 4)
+
+    total_bytes, code_bytes = algorithmic_bytes(B, Hq, Hkv, [int(x) for x in lens], k, append)
+    gbps_step = total_bytes / (us_step * 1e-6) / 1e9
+    gbps_scan = code_bytes / (ms_scan * 1e-3) / 1e9
+
+    traffic = None
+    prof = os.path.join(ROOT, "profiles", "scan_kernel_%s_pmc.md" % args.config)
+    if os.path.exists(prof):
+        for line in open(prof):
+            if line.startswith("traffic_bytes_per_launch:"):
+                traffic = float(line.split(":")[1])
+
+    result = {
+        "metric": "decode-step us/layer at 32K ctx (encode+select+sparse attn); achieved HBM GB/s",
+        "value": round(us_step, 3),
+        "unit": "us/layer",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_wall, 6),
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u32 popcount (select) + f32 (attention) on bf16 K/V",
+        "data": "synthetic",
+        "config": {
+            "workload": wl["text"] + ", budget k=%d, %d rotating layer caches" % (k, n_layers),
+            "batch": B, "q_heads": Hq, "kv_heads": Hkv, "context": int(max_len),
+            "sum_context": int(lens.sum()), "k": k, "append": append,
+            "launch": "eager" if args.eager else "hipGraph of one %d-layer sweep" % n_layers,
+        },
+        "achieved_hbm_GBps": round(gbps_step, 1),
+        "hbm_frac_whole_step": round(gbps_step / HBM_PEAK_GBPS, 4),
+        "algorithmic_bytes_per_step": total_bytes,
+        "us_per_step_hip_events": round(ms_evt * 1e3, 3),
+        "roofline": {
+            "kernel": "scan_kernel (Manhattan-distance scan + fused query encode)",
+            "bound": "hbm",
+            "achieved": round(gbps_scan, 1),
+            "peak": HBM_PEAK_GBPS,
+            "unit": "GB/s",
+            "frac": round(gbps_scan / HBM_PEAK_GBPS, 4),
+            "traffic": traffic,
+            "algorithmic_bytes_per_launch": code_bytes,
+            "us_per_launch": round(ms_scan * 1e3, 3),
+        },
+    }
+    if per_sweep:
+        ps = sorted(x / n_layers * 1e3 for x in per_sweep)
+        result["us_per_layer_p10_p50_p90"] = [round(ps[len(ps) // 10], 3), round(ps[len(ps) // 2], 3),
+                                              round(ps[(len(ps) * 9) // 10], 3)]
+
+    # ------------------------------------------------------------------ oracle on the host
+    if not args.no_cpu_baseline:
+        import oracle
+        if case0 is None:
+            # pull layer 0 back to the host for the oracle
+            def h(t):
+                return None if t is None else t.cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
+            d0 = layers[0]
+            Kh, Vh, qh = h(d0["K"]), h(d0["V"]), h(d0["q"])
+            knh, vnh = h(d0["k_new"]), h(d0["v_new"])
+        else:
+            Kh, Vh, qh, knh, vnh = case0.K.copy(), case0.V.copy(), case0.q, None, None
+        cores = oracle.max_threads()
+        # sample: as many KV heads of layer 0 as keep the oracle near 10-30 s of CPU work
+        n_kv = min(Hkv, max(1, int(round(Hkv * min(1.0, 2.0e6 / max(1, Hkv * int(lens.sum())))))))
+        sel_kv = list(range(n_kv))
+        sel_q = [hh * G + g for hh in sel_kv for g in range(G)]
+        Ks, Vs = np.ascontiguousarray(Kh[sel_kv]), np.ascontiguousarray(Vh[sel_kv])
+        if append:      # the device cache already holds the appended row; the oracle re-appends it
+            kns, vns = np.ascontiguousarray(knh[:, sel_kv]), np.ascontiguousarray(vnh[:, sel_kv])
+        else:
+            kns = vns = None
+        _, rows = oracle.encode(Ks, synth.DEFAULT_THRESHOLDS)          # cache state, not timed
+        qs = np.ascontiguousarray(qh[:, sel_q])
+        t0 = time.perf_counter()
+        ref_out, ref_idx, _ = oracle.decode_step(qs, Ks, Vs, rows, starts, lens, k,
+                                                 synth.DEFAULT_THRESHOLDS, synth.DEFAULT_THRESHOLDS,
+                                                 1.0 / np.sqrt(128.0), k_new=kns, v_new=vns)
+        cpu_s = time.perf_counter() - t0
+        scale_up = Hkv / n_kv
+        result["cpu_baseline"] = {
+            "value": round(cpu_s * scale_up * 1e6, 1),
+            "unit": "us/layer",
+            "cores": cores,
+            "kind": "oracle",
+            "sample": "one decode step of layer 0 on %d of %d KV heads (%d query heads), full "
+                      "context, measured %.3f s, scaled by %.1f" % (n_kv, Hkv, len(sel_q), cpu_s,
+                                                                    scale_up),
+        }
+        # the same sample doubles as a full-size parity check of the timed launch configuration
+        step(0)
+        torch.cuda.synchronize()
+        got_idx = idx0.cpu().numpy()[:, sel_q]
+        got_out = layers[0]["out"].cpu().numpy()[:, sel_q]
+        floor = 1e-3 * np.abs(ref_out).max(axis=-1, keepdims=True)
+        rel = float(np.max(np.abs(got_out - ref_out) / np.maximum(np.abs(ref_out), floor)))
+        result["parity_vs_oracle"] = {"indices_bit_exact": bool(np.array_equal(got_idx, ref_idx)),
+                                      "attn_max_rel_err": rel, "heads_checked": len(sel_q)}
+    result["setup_seconds"] = round(t_gen, 1)
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -189,6 +189,28 @@ int adamas_decode_step(const adamas_config *cfg, const void *q,
                        float *out, int32_t *idx_out, int64_t max_seq_len,
                        void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * Profiling hook: adamas_decode_step cut at its one internal kernel
+ * boundary.  `stages` is a bit mask; ADAMAS_STAGE_ALL is exactly
+ * adamas_decode_step.  ADAMAS_STAGE_SCAN runs Alg. 1 l.1-5 (query encode,
+ * append, distance scan; leaves distances and histograms in the workspace,
+ * writes neither out nor idx_out).  ADAMAS_STAGE_SELECT_ATTN runs l.6-8 on
+ * what a preceding ADAMAS_STAGE_SCAN call with the same arguments left in
+ * the same workspace; without such a call its outputs are unspecified
+ * (all accesses stay in bounds).  Same arguments and errors as
+ * adamas_decode_step; stages outside 1..3 -> ADAMAS_ERR_BAD_ARG.
+ */
+#define ADAMAS_STAGE_SCAN 1u
+#define ADAMAS_STAGE_SELECT_ATTN 2u
+#define ADAMAS_STAGE_ALL 3u
+int adamas_decode_step_stages(const adamas_config *cfg, const void *q,
+                              const void *k_new, const void *v_new, void *K,
+                              void *V, void *codes, const int64_t *seq_start,
+                              const int32_t *seq_len, int32_t batch, int32_t k,
+                              float *out, int32_t *idx_out, int64_t max_seq_len,
+                              void *workspace, size_t workspace_bytes,
+                              void *stream, uint32_t stages);
+
 #ifdef __cplusplus
 }
 #endif

@@ -6,6 +6,10 @@ from .binding import (  # noqa: F401
     Config,
     EXPORTED_SYMBOLS,
     adamas_decode_step,
+    adamas_decode_step_stages,
+    STAGE_ALL,
+    STAGE_SCAN,
+    STAGE_SELECT_ATTN,
     adamas_encode_keys,
     adamas_encode_query,
     adamas_manhattan_distance,

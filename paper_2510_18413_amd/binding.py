@@ -24,6 +24,7 @@ EXPORTED_SYMBOLS = (
     "adamas_select_topk",
     "adamas_sparse_attn",
     "adamas_decode_step",
+    "adamas_decode_step_stages",
 )
 
 HEAD_DIM = 128
@@ -33,7 +34,9 @@ CODE_ROW_BYTES = 32
 class AdamasError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
-        super().__init__("%s: %s (%d)" % (where, adamas_status_string(status), status))
+        hip = library().adamas_last_hip_error() if status == -4 else 0
+        super().__init__("%s: %s (%d)%s" % (where, adamas_status_string(status), status,
+                                            " hipError %d" % hip if hip else ""))
 
 
 class Config(ctypes.Structure):
@@ -69,6 +72,9 @@ def library() -> ctypes.CDLL:
     """Loads libadamas.so (building it first only if it does not exist)."""
     global _lib
     if _lib is None:
+        # torch first: the process then has one HIP runtime (the one torch ships), and this
+        # library, which only needs the public HIP launch API, binds to it.
+        import torch  # noqa: F401
         if not _build.LIB.exists():
             _build.build()
         lib = ctypes.CDLL(str(_build.LIB))
@@ -93,6 +99,8 @@ def library() -> ctypes.CDLL:
         lib.adamas_decode_step.restype = ctypes.c_int
         lib.adamas_decode_step.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp,
                                            i64, vp, sz, vp]
+        lib.adamas_decode_step_stages.restype = ctypes.c_int
+        lib.adamas_decode_step_stages.argtypes = lib.adamas_decode_step.argtypes + [ctypes.c_uint32]
         _lib = lib
     return _lib
 
@@ -208,13 +216,27 @@ def adamas_sparse_attn(cfg: Config, q, K, V, seq_start, idx, out, max_seq_len: i
     _check(rc, "adamas_sparse_attn")
 
 
+STAGE_SCAN, STAGE_SELECT_ATTN, STAGE_ALL = 1, 2, 3
+
+
 def adamas_decode_step(cfg: Config, q, K, V, codes, seq_start, seq_len, k: int, out,
                        max_seq_len: int, workspace, k_new=None, v_new=None, idx_out=None,
                        stream=None) -> None:
+    adamas_decode_step_stages(cfg, q, K, V, codes, seq_start, seq_len, k, out, max_seq_len,
+                              workspace, k_new=k_new, v_new=v_new, idx_out=idx_out, stream=stream,
+                              stages=None)
+
+
+def adamas_decode_step_stages(cfg: Config, q, K, V, codes, seq_start, seq_len, k: int, out,
+                              max_seq_len: int, workspace, k_new=None, v_new=None, idx_out=None,
+                              stream=None, stages=STAGE_ALL) -> None:
+    """stages=None calls the plain adamas_decode_step entry point."""
     import torch
     batch = q.shape[0]
     hkv, pool = cfg.num_kv_heads, cfg.pool_tokens
-    rc = library().adamas_decode_step(
+    fn = library().adamas_decode_step if stages is None else library().adamas_decode_step_stages
+    extra = () if stages is None else (int(stages),)
+    rc = fn(
         ctypes.byref(cfg), _ptr(q, torch.bfloat16, "q", (batch, cfg.num_q_heads, HEAD_DIM)),
         _ptr(k_new, torch.bfloat16, "k_new", (batch, hkv, HEAD_DIM), optional=True),
         _ptr(v_new, torch.bfloat16, "v_new", (batch, hkv, HEAD_DIM), optional=True),
@@ -226,5 +248,5 @@ def adamas_decode_step(cfg: Config, q, K, V, codes, seq_start, seq_len, k: int, 
         _ptr(out, torch.float32, "out", (batch, cfg.num_q_heads, HEAD_DIM)),
         _ptr(idx_out, torch.int32, "idx_out", (batch, cfg.num_q_heads, k), optional=True),
         max_seq_len, _ptr(workspace, torch.uint8, "workspace"), workspace.numel(),
-        _stream(stream))
+        _stream(stream), *extra)
     _check(rc, "adamas_decode_step")

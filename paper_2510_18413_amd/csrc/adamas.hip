@@ -102,6 +102,10 @@ float scale_log2e(const adamas_config* c) {
   return (float)(s * kLog2e);
 }
 
+// Drops an error an earlier, unrelated HIP call may have left on this thread,
+// so that launch_status() reports only this library's launches.
+void clear_stale_error() { (void)hipGetLastError(); }
+
 int launch_status() {
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) {
@@ -157,6 +161,7 @@ int adamas_encode_keys(const adamas_config* cfg, const void* K, void* codes, int
   if (row_begin + n_rows > cfg->pool_tokens) return ADAMAS_ERR_BAD_ARG;
   if (!aligned16(K) || !aligned16(codes)) return ADAMAS_ERR_BAD_ARG;
   if (n_rows == 0) return ADAMAS_OK;
+  clear_stale_error();
   const int64_t n_vec = n_rows * cfg->num_kv_heads;
   const int64_t want = (n_vec + 3) / 4;
   const int grid = (int)(want < 16384 ? want : 16384);
@@ -171,6 +176,7 @@ int adamas_encode_query(const adamas_config* cfg, const void* q, void* qcodes, i
   if (int rc = check_config(cfg)) return rc;
   if (q == nullptr || qcodes == nullptr || batch < 1 || batch > 65535) return ADAMAS_ERR_BAD_ARG;
   if (!aligned16(q) || !aligned16(qcodes)) return ADAMAS_ERR_BAD_ARG;
+  clear_stale_error();
   const int64_t n_vec = (int64_t)batch * cfg->num_q_heads;
   const int64_t want = (n_vec + 3) / 4;
   const int grid = (int)(want < 16384 ? want : 16384);
@@ -188,6 +194,7 @@ int adamas_manhattan_distance(const adamas_config* cfg, const void* qcodes, cons
   if (int rc = check_sizes(batch, max_seq_len, 1)) return rc;
   if (!qcodes || !codes || !seq_start || !seq_len || !dist_out) return ADAMAS_ERR_BAD_ARG;
   if (!aligned16(codes) || !aligned16(qcodes)) return ADAMAS_ERR_BAD_ARG;
+  clear_stale_error();
   const Plan pl = make_plan(cfg, batch, max_seq_len);
   ScanParams sp{};
   sp.codes = static_cast<const uint8_t*>(codes);
@@ -218,6 +225,7 @@ int adamas_select_topk(const adamas_config* cfg, const void* qcodes, const void*
   const Plan pl = make_plan(cfg, batch, max_seq_len);
   if (workspace_bytes < pl.total) return ADAMAS_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;
+  clear_stale_error();
 
   ScanParams sp{};
   sp.codes = static_cast<const uint8_t*>(codes);
@@ -271,6 +279,7 @@ int adamas_sparse_attn(const adamas_config* cfg, const void* q, const void* K, c
   const Plan pl = make_plan(cfg, batch, max_seq_len);
   if (workspace_bytes < pl.total) return ADAMAS_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;
+  clear_stale_error();
   const int64_t heads = (int64_t)batch * cfg->num_q_heads;
 
   AttnParams ap{};
@@ -305,7 +314,19 @@ int adamas_decode_step(const adamas_config* cfg, const void* q, const void* k_ne
                        const int32_t* seq_len, int32_t batch, int32_t k, float* out,
                        int32_t* idx_out, int64_t max_seq_len, void* workspace,
                        size_t workspace_bytes, void* stream) {
+  return adamas_decode_step_stages(cfg, q, k_new, v_new, K, V, codes, seq_start, seq_len, batch, k,
+                                   out, idx_out, max_seq_len, workspace, workspace_bytes, stream,
+                                   ADAMAS_STAGE_ALL);
+}
+
+int adamas_decode_step_stages(const adamas_config* cfg, const void* q, const void* k_new,
+                              const void* v_new, void* K, void* V, void* codes,
+                              const int64_t* seq_start, const int32_t* seq_len, int32_t batch,
+                              int32_t k, float* out, int32_t* idx_out, int64_t max_seq_len,
+                              void* workspace, size_t workspace_bytes, void* stream,
+                              uint32_t stages) {
   if (int rc = check_config(cfg)) return rc;
+  if (stages < 1u || stages > ADAMAS_STAGE_ALL) return ADAMAS_ERR_BAD_ARG;
   if (int rc = check_sizes(batch, max_seq_len, k)) return rc;
   if (!q || !K || !V || !codes || !seq_start || !seq_len || !out || !workspace) return ADAMAS_ERR_BAD_ARG;
   if ((k_new == nullptr) != (v_new == nullptr)) return ADAMAS_ERR_BAD_ARG;
@@ -315,6 +336,7 @@ int adamas_decode_step(const adamas_config* cfg, const void* q, const void* k_ne
   const Plan pl = make_plan(cfg, batch, max_seq_len);
   if (workspace_bytes < pl.total) return ADAMAS_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;
+  clear_stale_error();
 
   ScanParams sp{};
   sp.codes = static_cast<const uint8_t*>(codes);
@@ -337,9 +359,13 @@ int adamas_decode_step(const adamas_config* cfg, const void* q, const void* k_ne
   sp.n_tiles = pl.n_tiles;
   sp.thr_q = scaled(cfg->thr_q);
   sp.thr_k = scaled(cfg->thr_k);
-  launch_scan<true>(cfg->num_q_heads / cfg->num_kv_heads, dim3(pl.n_tiles, cfg->num_kv_heads, batch),
-                    dim3(pl.tile_tokens / kScanTokPerThread), st, sp);
-  if (int rc = launch_status()) return rc;
+  if (stages & ADAMAS_STAGE_SCAN) {
+    launch_scan<true>(cfg->num_q_heads / cfg->num_kv_heads,
+                      dim3(pl.n_tiles, cfg->num_kv_heads, batch),
+                      dim3(pl.tile_tokens / kScanTokPerThread), st, sp);
+    if (int rc = launch_status()) return rc;
+  }
+  if (!(stages & ADAMAS_STAGE_SELECT_ATTN)) return ADAMAS_OK;
 
   SelectParams sl{};
   sl.dist = sp.dist;
