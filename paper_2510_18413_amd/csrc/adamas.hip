@@ -30,7 +30,7 @@ struct Plan {
   int n_segs;        // select workgroups per (sequence, query head)
   int n_parts;       // attention partial slots per head
   int64_t dist_stride;
-  size_t off_dist, off_hist, off_partial, off_counters, total;
+  size_t off_dist, off_hist, off_partial, total;
 };
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -84,8 +84,6 @@ Plan make_plan(const adamas_config* c, int32_t batch, int64_t max_seq_len) {
   off = align256(off + heads * (size_t)pl.n_tiles * kHistStride * sizeof(uint16_t));
   pl.off_partial = off;
   off = align256(off + heads * (size_t)pl.n_parts * kPartialStride * sizeof(float));
-  pl.off_counters = off;
-  off = align256(off + heads * sizeof(uint32_t));
   pl.total = off;
   return pl;
 }
@@ -280,8 +278,6 @@ int adamas_sparse_attn(const adamas_config* cfg, const void* q, const void* K, c
   if (workspace_bytes < pl.total) return ADAMAS_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;
   clear_stale_error();
-  const int64_t heads = (int64_t)batch * cfg->num_q_heads;
-
   AttnParams ap{};
   ap.q = static_cast<const uint16_t*>(q);
   ap.K = static_cast<const uint16_t*>(K);
@@ -290,7 +286,6 @@ int adamas_sparse_attn(const adamas_config* cfg, const void* q, const void* K, c
   ap.idx = idx;
   ap.out = out;
   ap.partial = reinterpret_cast<float*>(ws_at(workspace, pl.off_partial));
-  ap.counters = reinterpret_cast<uint32_t*>(ws_at(workspace, pl.off_counters));
   ap.pool_tokens = cfg->pool_tokens;
   ap.Hq = cfg->num_q_heads;
   ap.Hkv = cfg->num_kv_heads;
@@ -301,11 +296,17 @@ int adamas_sparse_attn(const adamas_config* cfg, const void* q, const void* K, c
   ap.chunk = (k + parts - 1) / parts;
   ap.n_parts = (k + ap.chunk - 1) / ap.chunk;
   ap.scale_log2e = scale_log2e(cfg);
-  hipLaunchKernelGGL(zero_u32_kernel, dim3((unsigned)((heads + 255) / 256)), dim3(256), 0, st,
-                     ap.counters, heads);
-  if (int rc = launch_status()) return rc;
   hipLaunchKernelGGL(sparse_attn_kernel, dim3(ap.n_parts, cfg->num_q_heads, batch),
                      dim3(kSelThreads), 0, st, ap);
+  if (int rc = launch_status()) return rc;
+  MergeParams mp{};
+  mp.partial = ap.partial;
+  mp.out = out;
+  mp.seq_start = seq_start;
+  mp.Hq = cfg->num_q_heads;
+  mp.n_parts = ap.n_parts;
+  mp.seg_len = 0;
+  hipLaunchKernelGGL(merge_kernel, dim3(cfg->num_q_heads, batch), dim3(kHeadDim), 0, st, mp);
   return launch_status();
 }
 
@@ -351,7 +352,6 @@ int adamas_decode_step_stages(const adamas_config* cfg, const void* q, const voi
   sp.dist = reinterpret_cast<uint16_t*>(ws_at(workspace, pl.off_dist));
   sp.dist_stride = pl.dist_stride;
   sp.tilehist = reinterpret_cast<uint16_t*>(ws_at(workspace, pl.off_hist));
-  sp.counters = reinterpret_cast<uint32_t*>(ws_at(workspace, pl.off_counters));
   sp.pool_tokens = cfg->pool_tokens;
   sp.max_seq_len = max_seq_len;
   sp.Hq = cfg->num_q_heads;
@@ -379,7 +379,6 @@ int adamas_decode_step_stages(const adamas_config* cfg, const void* q, const voi
   sl.V = sp.V;
   sl.out = out;
   sl.partial = reinterpret_cast<float*>(ws_at(workspace, pl.off_partial));
-  sl.counters = sp.counters;
   sl.pool_tokens = cfg->pool_tokens;
   sl.max_seq_len = max_seq_len;
   sl.Hq = cfg->num_q_heads;
@@ -392,6 +391,18 @@ int adamas_decode_step_stages(const adamas_config* cfg, const void* q, const voi
   sl.scale_log2e = scale_log2e(cfg);
   hipLaunchKernelGGL((select_kernel<true>), dim3(pl.n_segs, cfg->num_q_heads, batch),
                      dim3(kSelThreads), 0, st, sl);
+  if (int rc = launch_status()) return rc;
+  MergeParams mp{};
+  mp.partial = sl.partial;
+  mp.out = out;
+  mp.seq_start = seq_start;
+  mp.seq_len = seq_len;
+  mp.pool_tokens = cfg->pool_tokens;
+  mp.max_seq_len = max_seq_len;
+  mp.Hq = cfg->num_q_heads;
+  mp.n_parts = pl.n_parts;
+  mp.seg_len = pl.seg_len;
+  hipLaunchKernelGGL(merge_kernel, dim3(cfg->num_q_heads, batch), dim3(kHeadDim), 0, st, mp);
   return launch_status();
 }
 

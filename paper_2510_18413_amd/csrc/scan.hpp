@@ -42,7 +42,6 @@ struct ScanParams {
   uint16_t* dist_user;       // optional second copy, [B*Hq][dist_user_stride]
   int64_t dist_user_stride;
   uint16_t* tilehist;        // [B*Hq][n_tiles][kHistStride]; may be null
-  uint32_t* counters;        // [B*Hq], zeroed here for the following kernel; may be null
   int64_t pool_tokens, max_seq_len;
   int32_t Hq, Hkv, n_tiles;
   Thresholds thr_q, thr_k;
@@ -62,7 +61,6 @@ __global__ __launch_bounds__(1024) void scan_kernel(const ScanParams p) {
   const int t0 = tile_id * tile_tokens;
   const int head0 = b * p.Hq + kvh * G;
 
-  if (tile_id == 0 && p.counters != nullptr && tid < G) p.counters[head0 + tid] = 0u;
   if (t0 >= L) return;  // whole workgroup
 
   // Issue this thread's row loads first: they do not depend on the query.

@@ -13,8 +13,10 @@
 // One workgroup (256 threads) owns one segment of one (sequence, query head).
 // With attention enabled it then gathers the K, V rows it selected, runs a
 // one-pass online softmax over them (16 lanes per row, 8 dims per lane, fp32),
-// stores an (m, l, o[128]) partial, and the last workgroup of the head to
-// arrive merges the partials in segment order into the output.
+// stores an (m, l, o[128]) partial; a small follow-up kernel merges the
+// partials of a head in segment order into the output.  (A merge inside the
+// same kernel would need device-scope fences, which on this part cost far more
+// than a kernel boundary: each one walks the XCD's whole L2.)
 #pragma once
 
 #include "device_utils.hpp"
@@ -40,7 +42,6 @@ struct SelectParams {
   const uint16_t* V;
   float* out;                 // [B*Hq][128]
   float* partial;             // [B*Hq][n_parts][kPartialStride]
-  uint32_t* counters;         // [B*Hq], zero on entry
   int64_t pool_tokens, max_seq_len;
   int32_t Hq, Hkv, k;
   int32_t n_tiles, tile_tokens, seg_len, n_parts;
@@ -51,17 +52,17 @@ struct AttnShared {
   float m[kAttnGroups];
   float l[kAttnGroups];
   float acc[kAttnGroups][kHeadDim];
-  uint32_t last;
 };
 
 // Attention partial of this workgroup over the n rows listed in s_sel (token
-// positions of sequence rows starting at pool row `row0` of K and V), then
-// publication and, in the last workgroup of the head, the merge.
+// positions; Kp, Vp point at the sequence's first row of the right KV head):
+// writes (m, l, o[128]) -- running maximum in the exp2 domain, sum of weights,
+// unnormalised weighted sum of V -- to partial_head[part].
 // All 256 threads must call it.
-__device__ __forceinline__ void attention_partial_and_merge(
+__device__ __forceinline__ void attention_partial(
     const int32_t* s_sel, int n, const uint16_t* __restrict__ q, const uint16_t* __restrict__ Kp,
     const uint16_t* __restrict__ Vp, float scale_log2e, float* __restrict__ partial_head,
-    int part, int n_expected, uint32_t* counter, float* __restrict__ out_head, AttnShared& sh) {
+    int part, AttnShared& sh) {
   const int tid = threadIdx.x, grp = tid >> 4, gl = tid & 15;
 
   float qf[8];
@@ -150,27 +151,6 @@ __device__ __forceinline__ void attention_partial_and_merge(
       mine[1] = lsum;
     }
     mine[4 + tid] = o;
-  }
-  __threadfence();  // make the partial visible device-wide before announcing it
-  __syncthreads();
-  if (tid == 0) {
-    const uint32_t old = atomicAdd(counter, 1u);
-    sh.last = (old == (uint32_t)(n_expected - 1)) ? 1u : 0u;
-  }
-  __syncthreads();
-  if (sh.last == 0u) return;
-  __threadfence();  // acquire side: the other workgroups' partials
-  if (tid < kHeadDim) {
-    float M = kNegBig;
-    for (int s = 0; s < n_expected; ++s) M = fmaxf(M, partial_head[(int64_t)s * kPartialStride]);
-    float lsum = 0.f, o = 0.f;
-    for (int s = 0; s < n_expected; ++s) {
-      const float* ps = partial_head + (int64_t)s * kPartialStride;
-      const float w = exp2f(ps[0] - M);
-      lsum = fmaf(ps[1], w, lsum);
-      o = fmaf(ps[4 + tid], w, o);
-    }
-    out_head[tid] = lsum > 0.f ? o / lsum : 0.f;
   }
 }
 
@@ -332,9 +312,8 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const SelectParams 
     __syncthreads();  // s_sel complete
     const int kvh = hq / (p.Hq / p.Hkv);
     const int64_t row0 = ((int64_t)kvh * p.pool_tokens + p.seq_start[b]) * kHeadDim;
-    attention_partial_and_merge(s_sel, n_sel, p.q + head * kHeadDim, p.K + row0, p.V + row0,
-                                p.scale_log2e, p.partial + head * p.n_parts * kPartialStride, seg,
-                                n_active, p.counters + head, p.out + head * kHeadDim, s_attn);
+    attention_partial(s_sel, n_sel, p.q + head * kHeadDim, p.K + row0, p.V + row0, p.scale_log2e,
+                      p.partial + head * p.n_parts * kPartialStride, seg, s_attn);
   }
 }
 
@@ -348,7 +327,6 @@ struct AttnParams {
   const int32_t* idx;  // [B*Hq][k]
   float* out;
   float* partial;      // [B*Hq][n_parts][kPartialStride]
-  uint32_t* counters;  // zero on entry
   int64_t pool_tokens;
   int32_t Hq, Hkv, k, n_parts, chunk;  // chunk = idx entries per workgroup
   float scale_log2e;
@@ -379,14 +357,42 @@ __global__ __launch_bounds__(kSelThreads) void sparse_attn_kernel(const AttnPara
   __syncthreads();
   const int kvh = hq / (p.Hq / p.Hkv);
   const int64_t row0 = ((int64_t)kvh * p.pool_tokens + start) * kHeadDim;
-  attention_partial_and_merge(s_sel, (int)n, p.q + head * kHeadDim, p.K + row0, p.V + row0,
-                              p.scale_log2e, p.partial + head * p.n_parts * kPartialStride, part,
-                              p.n_parts, p.counters + head, p.out + head * kHeadDim, s_attn);
+  attention_partial(s_sel, (int)n, p.q + head * kHeadDim, p.K + row0, p.V + row0, p.scale_log2e,
+                    p.partial + head * p.n_parts * kPartialStride, part, s_attn);
 }
 
-__global__ void zero_u32_kernel(uint32_t* ptr, int64_t n) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) ptr[i] = 0u;
+// Merges the attention partials of one head, in part order, into out.
+// seg_len > 0: the number of partials is the number of segments that hold
+// tokens of the head's sequence (as select_kernel wrote them); seg_len == 0:
+// n_parts partials (as sparse_attn_kernel wrote them).
+struct MergeParams {
+  const float* partial;      // [B*Hq][n_parts][kPartialStride]
+  float* out;                // [B*Hq][128]
+  const int64_t* seq_start;
+  const int32_t* seq_len;
+  int64_t pool_tokens, max_seq_len;
+  int32_t Hq, n_parts, seg_len;
+};
+
+__global__ __launch_bounds__(kHeadDim) void merge_kernel(const MergeParams p) {
+  const int hq = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+  const int64_t head = (int64_t)b * p.Hq + hq;
+  int n = p.n_parts;
+  if (p.seg_len > 0) {
+    const int L = safe_seq_len(p.seq_len, p.seq_start, b, p.max_seq_len, p.pool_tokens);
+    n = max(1, (L + p.seg_len - 1) / p.seg_len);
+  }
+  const float* ph = p.partial + head * p.n_parts * kPartialStride;
+  float M = kNegBig;
+  for (int s = 0; s < n; ++s) M = fmaxf(M, ph[(int64_t)s * kPartialStride]);
+  float lsum = 0.f, o = 0.f;
+  for (int s = 0; s < n; ++s) {
+    const float* ps = ph + (int64_t)s * kPartialStride;
+    const float w = exp2f(ps[0] - M);
+    lsum = fmaf(ps[1], w, lsum);
+    o = fmaf(ps[4 + tid], w, o);
+  }
+  p.out[head * kHeadDim + tid] = lsum > 0.f ? o / lsum : 0.f;
 }
 
 }  // namespace adamas
