@@ -6,6 +6,7 @@
 
 #include <cmath>
 #include <cstdint>
+#include <cstdlib>
 
 #include "encode.hpp"
 #include "scan.hpp"
@@ -18,8 +19,8 @@ using namespace adamas;
 thread_local int g_last_hip_error = 0;
 
 constexpr int kTargetWorkgroups = 256;  // one per compute unit of an MI355X
-constexpr int kMaxSegments = 16;
-constexpr int kAttnPartsMax = 16;
+constexpr int kSelThreads = 256;
+constexpr int kSegGranule = 4096;
 constexpr double kLog2e = 1.4426950408889634;
 
 // How one call is cut into workgroups and where its scratch lives in the workspace.
@@ -28,7 +29,6 @@ struct Plan {
   int n_tiles;       // scan tiles per (sequence, KV head)
   int seg_len;       // tokens per select workgroup, multiple of tile_tokens and of kSelPass
   int n_segs;        // select workgroups per (sequence, query head)
-  int n_parts;       // attention partial slots per head
   int64_t dist_stride;
   size_t off_dist, off_hist, off_partial, total;
 };
@@ -59,7 +59,7 @@ int check_sizes(int32_t batch, int64_t max_seq_len, int32_t k) {
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-Plan make_plan(const adamas_config* c, int32_t batch, int64_t max_seq_len) {
+Plan make_plan(const adamas_config* c, int32_t batch, int64_t max_seq_len, int32_t k) {
   Plan pl{};
   const int64_t planes = (int64_t)batch * c->num_kv_heads;
   pl.tile_tokens = 1024;
@@ -69,12 +69,22 @@ Plan make_plan(const adamas_config* c, int32_t batch, int64_t max_seq_len) {
       break;
     }
   }
+#ifdef EXP_TILE_ENV
+  if (const char* e = getenv("ADAMAS_TILE")) pl.tile_tokens = atoi(e);
+#endif
   pl.n_tiles = (int)((max_seq_len + pl.tile_tokens - 1) / pl.tile_tokens);
-  int64_t seg = kSelPass;  // 4096, a multiple of every tile size
-  while ((max_seq_len + seg - 1) / seg > kMaxSegments) seg += kSelPass;
+  // Select + attention: a head is cut into at most kMaxParts segments, one
+  // workgroup each (a single compute unit is far too slow to compact a whole
+  // 32K-token head or to gather all of its rows); a merge kernel combines the
+  // segments' attention partials.  A head that fits one segment needs no merge.
+  int64_t want = kMaxParts;
+#ifdef EXP_TILE_ENV
+  if (const char* e = getenv("ADAMAS_SEGS")) want = atoi(e);
+#endif
+  int64_t seg = (max_seq_len + want - 1) / want;
+  seg = (seg + kSegGranule - 1) / kSegGranule * kSegGranule;  // multiple of every tile size
   pl.seg_len = (int)seg;
   pl.n_segs = (int)((max_seq_len + seg - 1) / seg);
-  pl.n_parts = kAttnPartsMax;
   pl.dist_stride = (max_seq_len + 127) & ~(int64_t)127;
   const size_t heads = (size_t)batch * c->num_q_heads;
   size_t off = 0;
@@ -83,7 +93,7 @@ Plan make_plan(const adamas_config* c, int32_t batch, int64_t max_seq_len) {
   pl.off_hist = off;
   off = align256(off + heads * (size_t)pl.n_tiles * kHistStride * sizeof(uint16_t));
   pl.off_partial = off;
-  off = align256(off + heads * (size_t)pl.n_parts * kPartialStride * sizeof(float));
+  off = align256(off + heads * (size_t)kMaxParts * kPartialStride * sizeof(float));
   pl.total = off;
   return pl;
 }
@@ -149,7 +159,7 @@ int adamas_last_hip_error(void) { return g_last_hip_error; }
 size_t adamas_workspace_bytes(const adamas_config* cfg, int32_t batch, int64_t max_seq_len,
                               int32_t k) {
   if (check_config(cfg) != ADAMAS_OK || check_sizes(batch, max_seq_len, k) != ADAMAS_OK) return 0;
-  return make_plan(cfg, batch, max_seq_len).total;
+  return make_plan(cfg, batch, max_seq_len, k).total;
 }
 
 int adamas_encode_keys(const adamas_config* cfg, const void* K, void* codes, int64_t row_begin,
@@ -193,7 +203,7 @@ int adamas_manhattan_distance(const adamas_config* cfg, const void* qcodes, cons
   if (!qcodes || !codes || !seq_start || !seq_len || !dist_out) return ADAMAS_ERR_BAD_ARG;
   if (!aligned16(codes) || !aligned16(qcodes)) return ADAMAS_ERR_BAD_ARG;
   clear_stale_error();
-  const Plan pl = make_plan(cfg, batch, max_seq_len);
+  const Plan pl = make_plan(cfg, batch, max_seq_len, 1);
   ScanParams sp{};
   sp.codes = static_cast<const uint8_t*>(codes);
   sp.qcodes = static_cast<const uint8_t*>(qcodes);
@@ -220,7 +230,7 @@ int adamas_select_topk(const adamas_config* cfg, const void* qcodes, const void*
   if (!qcodes || !codes || !seq_start || !seq_len || !idx_out || !workspace) return ADAMAS_ERR_BAD_ARG;
   if (!aligned16(codes) || !aligned16(qcodes)) return ADAMAS_ERR_BAD_ARG;
   if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return ADAMAS_ERR_BAD_ARG;
-  const Plan pl = make_plan(cfg, batch, max_seq_len);
+  const Plan pl = make_plan(cfg, batch, max_seq_len, k);
   if (workspace_bytes < pl.total) return ADAMAS_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;
   clear_stale_error();
@@ -259,8 +269,7 @@ int adamas_select_topk(const adamas_config* cfg, const void* qcodes, const void*
   sl.n_tiles = pl.n_tiles;
   sl.tile_tokens = pl.tile_tokens;
   sl.seg_len = pl.seg_len;
-  sl.n_parts = pl.n_parts;
-  hipLaunchKernelGGL((select_kernel<false>), dim3(pl.n_segs, cfg->num_q_heads, batch),
+  hipLaunchKernelGGL((select_kernel<kSelThreads, false>), dim3(pl.n_segs, cfg->num_q_heads, batch),
                      dim3(kSelThreads), 0, st, sl);
   return launch_status();
 }
@@ -274,7 +283,7 @@ int adamas_sparse_attn(const adamas_config* cfg, const void* q, const void* K, c
   if (!q || !K || !V || !seq_start || !idx || !out || !workspace) return ADAMAS_ERR_BAD_ARG;
   if (!aligned16(q) || !aligned16(K) || !aligned16(V)) return ADAMAS_ERR_BAD_ARG;
   if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return ADAMAS_ERR_BAD_ARG;
-  const Plan pl = make_plan(cfg, batch, max_seq_len);
+  const Plan pl = make_plan(cfg, batch, max_seq_len, k);
   if (workspace_bytes < pl.total) return ADAMAS_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;
   clear_stale_error();
@@ -292,13 +301,14 @@ int adamas_sparse_attn(const adamas_config* cfg, const void* q, const void* K, c
   ap.k = k;
   // about 32 rows per workgroup, at most kAttnPartsMax workgroups per head
   int parts = (k + 31) / 32;
-  if (parts > kAttnPartsMax) parts = kAttnPartsMax;
+  if (parts > kMaxParts) parts = kMaxParts;
   ap.chunk = (k + parts - 1) / parts;
   ap.n_parts = (k + ap.chunk - 1) / ap.chunk;
   ap.scale_log2e = scale_log2e(cfg);
   hipLaunchKernelGGL(sparse_attn_kernel, dim3(ap.n_parts, cfg->num_q_heads, batch),
-                     dim3(kSelThreads), 0, st, ap);
+                     dim3(kAttnThreads), 0, st, ap);
   if (int rc = launch_status()) return rc;
+  if (ap.n_parts == 1) return ADAMAS_OK;
   MergeParams mp{};
   mp.partial = ap.partial;
   mp.out = out;
@@ -334,7 +344,7 @@ int adamas_decode_step_stages(const adamas_config* cfg, const void* q, const voi
   if (!aligned16(q) || !aligned16(K) || !aligned16(V) || !aligned16(codes)) return ADAMAS_ERR_BAD_ARG;
   if (k_new && (!aligned16(k_new) || !aligned16(v_new))) return ADAMAS_ERR_BAD_ARG;
   if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return ADAMAS_ERR_BAD_ARG;
-  const Plan pl = make_plan(cfg, batch, max_seq_len);
+  const Plan pl = make_plan(cfg, batch, max_seq_len, k);
   if (workspace_bytes < pl.total) return ADAMAS_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;
   clear_stale_error();
@@ -387,11 +397,11 @@ int adamas_decode_step_stages(const adamas_config* cfg, const void* q, const voi
   sl.n_tiles = pl.n_tiles;
   sl.tile_tokens = pl.tile_tokens;
   sl.seg_len = pl.seg_len;
-  sl.n_parts = pl.n_parts;
   sl.scale_log2e = scale_log2e(cfg);
-  hipLaunchKernelGGL((select_kernel<true>), dim3(pl.n_segs, cfg->num_q_heads, batch),
+  hipLaunchKernelGGL((select_kernel<kSelThreads, true>), dim3(pl.n_segs, cfg->num_q_heads, batch),
                      dim3(kSelThreads), 0, st, sl);
   if (int rc = launch_status()) return rc;
+  if (pl.n_segs == 1) return ADAMAS_OK;  // the select workgroup wrote `out` itself
   MergeParams mp{};
   mp.partial = sl.partial;
   mp.out = out;
@@ -400,7 +410,7 @@ int adamas_decode_step_stages(const adamas_config* cfg, const void* q, const voi
   mp.pool_tokens = cfg->pool_tokens;
   mp.max_seq_len = max_seq_len;
   mp.Hq = cfg->num_q_heads;
-  mp.n_parts = pl.n_parts;
+  mp.n_parts = pl.n_segs;
   mp.seg_len = pl.seg_len;
   hipLaunchKernelGGL(merge_kernel, dim3(cfg->num_q_heads, batch), dim3(kHeadDim), 0, st, mp);
   return launch_status();

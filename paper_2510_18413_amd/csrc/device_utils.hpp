@@ -31,35 +31,58 @@ __device__ __forceinline__ float bf16_hi(uint32_t packed) {
   return __uint_as_float(packed & 0xffff0000u);
 }
 
-__device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v, int lane) {
-#pragma unroll
-  for (int off = 1; off < kWave; off <<= 1) {
-    uint32_t o = __shfl_up(v, off, kWave);
-    if (lane >= off) v += o;
-  }
+// Per-half-word subtraction of two packed uint16 pairs (no borrow across halves).
+typedef unsigned short ushort2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pk_sub_u16(uint32_t a, uint32_t b) {
+  const ushort2_t d = __builtin_bit_cast(ushort2_t, a) - __builtin_bit_cast(ushort2_t, b);
+  return __builtin_bit_cast(uint32_t, d);
+}
+
+// ---- data-parallel-primitive (DPP) cross-lane moves: one VALU instruction each,
+// no LDS round trip.  A "row" is 16 consecutive lanes.
+constexpr int kDppQuadXor1 = 0xB1;       // quad_perm [1,0,3,2]
+constexpr int kDppQuadXor2 = 0x4E;       // quad_perm [2,3,0,1]
+constexpr int kDppRowShr = 0x110;        // + n: lane i reads lane i-n of its row
+constexpr int kDppRowMirror = 0x140;     // lane i reads lane 15-i of its row
+constexpr int kDppRowHalfMirror = 0x141; // lane i reads lane 7-i of its half row
+constexpr int kDppRowBcast15 = 0x142;    // lane 15 of each row -> the next row
+constexpr int kDppRowBcast31 = 0x143;    // lane 31 -> rows 2 and 3
+
+template <int CTRL, int ROW_MASK = 0xf>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t v) {
+  // lanes with no source (shifted in, masked rows) receive 0
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, 0xf, false);
+}
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
+}
+
+// Sum over each row of 16 lanes; every lane of the row receives the total.
+// After the two quad steps all lanes of a quad agree, so mirroring inside the
+// half row pairs quad 0 with quad 1, and mirroring the row pairs the halves.
+__device__ __forceinline__ float row16_sum_f32(float v) {
+  v += dpp_f32<kDppQuadXor1>(v);
+  v += dpp_f32<kDppQuadXor2>(v);
+  v += dpp_f32<kDppRowHalfMirror>(v);
+  v += dpp_f32<kDppRowMirror>(v);
+  return v;
+}
+
+// Inclusive prefix sum over the 64 lanes of a wave (Hillis-Steele inside each
+// row, then the row totals are carried across rows with the two broadcasts).
+__device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v) {
+  v += dpp_u32<kDppRowShr + 1>(v);
+  v += dpp_u32<kDppRowShr + 2>(v);
+  v += dpp_u32<kDppRowShr + 4>(v);
+  v += dpp_u32<kDppRowShr + 8>(v);
+  v += dpp_u32<kDppRowBcast15, 0xa>(v);  // rows 1 and 3 += total of the row before
+  v += dpp_u32<kDppRowBcast31, 0xc>(v);  // rows 2 and 3 += total of lanes 0..31
   return v;
 }
 
 __device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, kWave);
-  return v;
-}
-
-// Exclusive prefix sum over a 256-thread workgroup.  s_wave must hold 4 words.
-// Returns the exclusive prefix of v; total receives the workgroup sum.
-// Contains two barriers; every thread of the workgroup must call it.
-__device__ __forceinline__ uint32_t block256_excl_scan(uint32_t v, uint32_t* s_wave,
-                                                       uint32_t& total) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  uint32_t incl = wave_incl_scan_u32(v, lane);
-  if (lane == 63) s_wave[wave] = incl;
-  __syncthreads();
-  uint32_t w0 = s_wave[0], w1 = s_wave[1], w2 = s_wave[2], w3 = s_wave[3];
-  uint32_t before = (wave > 0 ? w0 : 0u) + (wave > 1 ? w1 : 0u) + (wave > 2 ? w2 : 0u);
-  total = w0 + w1 + w2 + w3;
-  __syncthreads();
-  return before + incl - v;
+  return (uint32_t)__builtin_amdgcn_readlane((int)wave_incl_scan_u32(v), 63);
 }
 
 }  // namespace adamas

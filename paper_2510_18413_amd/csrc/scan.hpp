@@ -88,7 +88,11 @@ __global__ __launch_bounds__(1024) void scan_kernel(const ScanParams p) {
     for (int v = wave; v < n_enc; v += nwaves) {
       uint64_t w[4];
       if (v < G) {
+#ifdef EXP_NOENC
+        w[0] = w[1] = w[2] = w[3] = 0x123456789abcdefull;
+#else
         encode_vector_wave(p.q + (int64_t)(head0 + v) * kHeadDim, p.thr_q, w);
+#endif
         if (lane < 4) {
           const uint64_t x = lane == 0 ? w[0] : lane == 1 ? w[1] : lane == 2 ? w[2] : w[3];
           const uint32_t lo = (uint32_t)x, hi = (uint32_t)(x >> 32);
@@ -163,9 +167,15 @@ __global__ __launch_bounds__(1024) void scan_kernel(const ScanParams p) {
       const uint32_t d = c1 + 2u * c2;
       if (t < L) {
         const int64_t head = head0 + g;
+#ifndef EXP_NODIST
         if (p.dist != nullptr) p.dist[head * p.dist_stride + t] = (uint16_t)d;
+#endif
         if (p.dist_user != nullptr) p.dist_user[head * p.dist_user_stride + t] = (uint16_t)d;
+#ifndef EXP_NOHIST
         atomicAdd(hist_lane + g * (kHistReplicas * kNumBins) + d, 1u);
+#else
+        if (d == 0x7fffffffu) hist_lane[0] = 1;
+#endif
       }
     }
   }

@@ -23,11 +23,9 @@
 
 namespace adamas {
 
-constexpr int kSelThreads = 256;
 constexpr int kSelTokPerThread = 16;
-constexpr int kSelPass = kSelThreads * kSelTokPerThread;  // tokens per pass
+constexpr int kMaxParts = 16;  // attention partial slots per head in the workspace
 constexpr int kMaxK = 4096;
-constexpr int kAttnGroups = kSelThreads / 16;
 constexpr float kNegBig = -1.0e30f;
 
 struct SelectParams {
@@ -41,28 +39,62 @@ struct SelectParams {
   const uint16_t* K;          // pools
   const uint16_t* V;
   float* out;                 // [B*Hq][128]
-  float* partial;             // [B*Hq][n_parts][kPartialStride]
+  float* partial;             // [B*Hq][kMaxParts][kPartialStride]
   int64_t pool_tokens, max_seq_len;
   int32_t Hq, Hkv, k;
-  int32_t n_tiles, tile_tokens, seg_len, n_parts;
+  int32_t n_tiles, tile_tokens, seg_len;
   float scale_log2e;          // sm_scale * log2(e)
 };
 
+// Exclusive prefix sum over a workgroup of THREADS threads (a multiple of 64).
+// s_wave must hold THREADS/64 words.  Two barriers inside; all threads call it.
+template <int THREADS>
+__device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* s_wave, uint32_t& total) {
+  constexpr int NW = THREADS / kWave;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const uint32_t incl = wave_incl_scan_u32(v);
+  if (lane == 63) s_wave[wave] = incl;
+  __syncthreads();
+  uint32_t before = 0, all = 0;
+#pragma unroll
+  for (int w = 0; w < NW; ++w) {
+    const uint32_t x = s_wave[w];
+    before += w < wave ? x : 0u;
+    all += x;
+  }
+  total = all;
+  __syncthreads();
+  return before + incl - v;
+}
+
+template <int THREADS>
 struct AttnShared {
-  float m[kAttnGroups];
-  float l[kAttnGroups];
-  float acc[kAttnGroups][kHeadDim];
+  static constexpr int kGroups = THREADS / 16;
+  float m[kGroups];
+  float l[kGroups];
+  float acc[kGroups][kHeadDim];
 };
 
-// Attention partial of this workgroup over the n rows listed in s_sel (token
-// positions; Kp, Vp point at the sequence's first row of the right KV head):
-// writes (m, l, o[128]) -- running maximum in the exp2 domain, sum of weights,
-// unnormalised weighted sum of V -- to partial_head[part].
-// All 256 threads must call it.
-__device__ __forceinline__ void attention_partial(
-    const int32_t* s_sel, int n, const uint16_t* __restrict__ q, const uint16_t* __restrict__ Kp,
-    const uint16_t* __restrict__ Vp, float scale_log2e, float* __restrict__ partial_head,
-    int part, AttnShared& sh) {
+// Softmax attention (Eq. 1) of one query over the n rows listed in s_sel (token
+// positions; Kp, Vp point at the sequence's first row of the right KV head),
+// by the whole workgroup: 16 lanes per row, 8 dims per lane, one-pass online
+// softmax per 16-lane group in fp32 (exp2 domain), groups combined in fixed
+// order through LDS.  Threads 0..127 receive, for output dim tid: M (running
+// maximum), lsum (sum of weights) and o (unnormalised weighted sum of V).
+// All threads must call it.
+template <int THREADS>
+__device__ __forceinline__ void attention_rows(const int32_t* s_sel, int n,
+                                               const uint16_t* __restrict__ q,
+                                               const uint16_t* __restrict__ Kp,
+                                               const uint16_t* __restrict__ Vp, float scale_log2e,
+                                               AttnShared<THREADS>& sh, float& M, float& lsum,
+                                               float& o) {
+  // No implicit FMA contraction here: a scaled score must be rounded once, and
+  // that one value must feed both the running maximum and the exponent, or rows
+  // with equal scores would not get equal weights.  The dot products use
+  // explicit fmaf and stay fused.
+#pragma clang fp contract(off)
+  constexpr int kGroups = THREADS / 16;
   const int tid = threadIdx.x, grp = tid >> 4, gl = tid & 15;
 
   float qf[8];
@@ -76,12 +108,12 @@ __device__ __forceinline__ void attention_partial(
   for (int j = 0; j < 8; ++j) acc[j] = 0.f;
 
   constexpr int U = 4;  // rows in flight per 16-lane group
-  for (int i0 = grp; i0 < n; i0 += kAttnGroups * U) {
+  for (int i0 = grp; i0 < n; i0 += kGroups * U) {
     uint4 kv[U], vv[U];
     bool ok[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int i = i0 + u * kAttnGroups;
+      const int i = i0 + u * kGroups;
       ok[u] = i < n;
       if (ok[u]) {
         const int64_t off = (int64_t)s_sel[i] * kHeadDim + gl * 8;
@@ -92,6 +124,8 @@ __device__ __forceinline__ void attention_partial(
         vv[u] = make_uint4(0, 0, 0, 0);
       }
     }
+    float sc[U];
+    float mn = m;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       float s = qf[0] * bf16_lo(kv[u].x);
@@ -102,26 +136,29 @@ __device__ __forceinline__ void attention_partial(
       s = fmaf(qf[5], bf16_hi(kv[u].z), s);
       s = fmaf(qf[6], bf16_lo(kv[u].w), s);
       s = fmaf(qf[7], bf16_hi(kv[u].w), s);
-      // the 16 lanes of a group sit in one wave: butterfly over lane bits 0..3
-      s += __shfl_xor(s, 1, kWave);
-      s += __shfl_xor(s, 2, kWave);
-      s += __shfl_xor(s, 4, kWave);
-      s += __shfl_xor(s, 8, kWave);
-      if (ok[u]) {
-        s *= scale_log2e;
-        const float mn = fmaxf(m, s);
-        const float corr = exp2f(m - mn), pw = exp2f(s - mn);
-        m = mn;
-        l = l * corr + pw;
-        acc[0] = fmaf(pw, bf16_lo(vv[u].x), acc[0] * corr);
-        acc[1] = fmaf(pw, bf16_hi(vv[u].x), acc[1] * corr);
-        acc[2] = fmaf(pw, bf16_lo(vv[u].y), acc[2] * corr);
-        acc[3] = fmaf(pw, bf16_hi(vv[u].y), acc[3] * corr);
-        acc[4] = fmaf(pw, bf16_lo(vv[u].z), acc[4] * corr);
-        acc[5] = fmaf(pw, bf16_hi(vv[u].z), acc[5] * corr);
-        acc[6] = fmaf(pw, bf16_lo(vv[u].w), acc[6] * corr);
-        acc[7] = fmaf(pw, bf16_hi(vv[u].w), acc[7] * corr);
-      }
+      // the group's 16 lanes are one DPP row
+      s = row16_sum_f32(s) * scale_log2e;
+      sc[u] = ok[u] ? s : kNegBig;
+      mn = fmaxf(mn, sc[u]);
+    }
+    // one rescale of the running state for the whole batch of rows
+    const float corr = exp2f(m - mn);
+    m = mn;
+    l *= corr;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] *= corr;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const float pw = ok[u] ? exp2f(sc[u] - mn) : 0.f;
+      l += pw;
+      acc[0] = fmaf(pw, bf16_lo(vv[u].x), acc[0]);
+      acc[1] = fmaf(pw, bf16_hi(vv[u].x), acc[1]);
+      acc[2] = fmaf(pw, bf16_lo(vv[u].y), acc[2]);
+      acc[3] = fmaf(pw, bf16_hi(vv[u].y), acc[3]);
+      acc[4] = fmaf(pw, bf16_lo(vv[u].z), acc[4]);
+      acc[5] = fmaf(pw, bf16_hi(vv[u].z), acc[5]);
+      acc[6] = fmaf(pw, bf16_lo(vv[u].w), acc[6]);
+      acc[7] = fmaf(pw, bf16_hi(vv[u].w), acc[7]);
     }
   }
 
@@ -133,86 +170,125 @@ __device__ __forceinline__ void attention_partial(
   for (int j = 0; j < 8; ++j) sh.acc[grp][gl * 8 + j] = acc[j];
   __syncthreads();
 
-  // Merge the 16 groups (fixed order), publish the workgroup's partial.
+  M = kNegBig;
+  lsum = 0.f;
+  o = 0.f;
   if (tid < kHeadDim) {
-    float M = kNegBig;
-#pragma unroll
-    for (int g = 0; g < kAttnGroups; ++g) M = fmaxf(M, sh.m[g]);
-    float lsum = 0.f, o = 0.f;
-#pragma unroll
-    for (int g = 0; g < kAttnGroups; ++g) {
+    for (int g = 0; g < kGroups; ++g) M = fmaxf(M, sh.m[g]);
+    for (int g = 0; g < kGroups; ++g) {
       const float w = exp2f(sh.m[g] - M);
       lsum = fmaf(sh.l[g], w, lsum);
       o = fmaf(sh.acc[g][tid], w, o);
     }
-    float* mine = partial_head + (int64_t)part * kPartialStride;
-    if (tid == 0) {
-      mine[0] = M;
-      mine[1] = lsum;
-    }
-    mine[4 + tid] = o;
   }
 }
 
-template <bool ATTN>
-__global__ __launch_bounds__(kSelThreads) void select_kernel(const SelectParams p) {
+// Grid (n_segs, Hq, B).  With a single segment per head and ATTN the
+// workgroup finishes the head and writes `out`; otherwise it leaves an
+// (M, lsum, o[128]) partial for merge_kernel.
+template <int THREADS, bool ATTN>
+__global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
+  constexpr int NB = (kHistStride + THREADS - 1) / THREADS;  // histogram bins per thread
+  constexpr int PASS = THREADS * kSelTokPerThread;           // tokens per pass
   __shared__ uint32_t s_tot[448];
-  __shared__ uint32_t s_scan[4];
+  __shared__ uint32_t s_scan[THREADS / kWave];
   __shared__ int32_t s_T, s_cntlt;
   __shared__ uint32_t s_ltb, s_eqb;
   __shared__ int32_t s_sel[ATTN ? kMaxK : 1];
-  __shared__ AttnShared s_attn;
+  __shared__ AttnShared<ATTN ? THREADS : 16> s_attn;
 
   const int seg = blockIdx.x, hq = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63;
   const int64_t head = (int64_t)b * p.Hq + hq;
+  const int seg_t0 = seg * p.seg_len;
+#ifdef EXP_TIMING
+  long long tk[8]; int tki = 0;
+#define TICK() do { tk[tki++] = wall_clock64(); } while (0)
+#else
+#define TICK() do {} while (0)
+#endif
+  TICK();
+
+  // Nothing below depends on the sequence length until the loads are issued:
+  // the workspace rows exist up to dist_stride / n_tiles whatever L is, and
+  // what lies beyond L is masked once L has arrived.
+  const uint16_t* drow = p.dist + head * p.dist_stride;
+  // distances of this thread for the current pass and the next one (rolling prefetch)
+  uint4 cur_a, cur_b, nxt_a, nxt_b;
+  {
+    const int o0 = tid * kSelTokPerThread, o1 = PASS + tid * kSelTokPerThread;
+    if (o0 < p.seg_len && seg_t0 + o0 < p.dist_stride) {
+      const uint4* src = reinterpret_cast<const uint4*>(drow + seg_t0 + o0);
+      cur_a = src[0];
+      cur_b = src[1];
+    } else {
+      cur_a = cur_b = make_uint4(0, 0, 0, 0);
+    }
+    if (o1 < p.seg_len && seg_t0 + o1 < p.dist_stride) {
+      const uint4* src = reinterpret_cast<const uint4*>(drow + seg_t0 + o1);
+      nxt_a = src[0];
+      nxt_b = src[1];
+    } else {
+      nxt_a = nxt_b = make_uint4(0, 0, 0, 0);
+    }
+  }
+  const uint16_t* hrow = p.tilehist + head * p.n_tiles * kHistStride;
+  const int first_tile = seg_t0 / p.tile_tokens;
+  uint32_t hv[NB][8];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+    // clamped, never out of bounds: no branches, so all loads are in flight together
+    const int bin = min(tid + nb * THREADS, kHistStride - 1);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) hv[nb][u] = hrow[(int64_t)min(u, p.n_tiles - 1) * kHistStride + bin];
+  }
+
   const int L = safe_seq_len(p.seq_len, p.seq_start, b, p.max_seq_len, p.pool_tokens);
   const int kk = min(p.k, L);
   const int n_active = max(1, (L + p.seg_len - 1) / p.seg_len);  // segments that hold tokens
   if (seg >= n_active) return;
-  const int seg_t0 = seg * p.seg_len, seg_t1 = min(L, seg_t0 + p.seg_len);
-
-  // Prefetch the first pass of this segment's distances.
-  const uint16_t* drow = p.dist + head * p.dist_stride;
-  uint4 da, db;
-  {
-    const int t = seg_t0 + tid * kSelTokPerThread;
-    if (t < seg_t1) {
-      const uint4* src = reinterpret_cast<const uint4*>(drow + t);
-      da = src[0];
-      db = src[1];
-    } else {
-      da = db = make_uint4(0, 0, 0, 0);
-    }
-  }
-
-  // Head histogram (all tiles) and the part of it that lies before this segment.
+  if (L >= 0) TICK();
+  const int seg_t1 = min(L, seg_t0 + p.seg_len);
   const int tiles_active = (L + p.tile_tokens - 1) / p.tile_tokens;
-  const int first_tile = seg_t0 / p.tile_tokens;
-  const uint16_t* hrow = p.tilehist + head * p.n_tiles * kHistStride;
-  uint32_t tot0 = 0, tot1 = 0, pre0 = 0, pre1 = 0;
-  const int bin0 = tid, bin1 = tid + kSelThreads;
-  for (int tb = 0; tb < tiles_active; tb += 8) {
-    uint32_t v0[8], v1[8];
+
+  // Head histogram (all tiles with tokens) and the part of it before this segment.
+  uint32_t tot[NB], pre[NB];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {  // all loads of the batch in flight together
-      const int ti = tb + u;
-      const bool in = ti < tiles_active;
-      v0[u] = in ? hrow[(int64_t)ti * kHistStride + bin0] : 0u;
-      v1[u] = (in && bin1 < kNumBins) ? hrow[(int64_t)ti * kHistStride + bin1] : 0u;
-    }
+  for (int nb = 0; nb < NB; ++nb) {
+    tot[nb] = 0;
+    pre[nb] = 0;
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
-      tot0 += v0[u];
-      tot1 += v1[u];
-      if (tb + u < first_tile) {
-        pre0 += v0[u];
-        pre1 += v1[u];
+      const uint32_t v = u < tiles_active ? hv[nb][u] : 0u;
+      tot[nb] += v;
+      pre[nb] += u < first_tile ? v : 0u;
+    }
+  }
+  for (int tb = 8; tb < tiles_active; tb += 8) {
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      const int bin = min(tid + nb * THREADS, kHistStride - 1);
+#pragma unroll
+      for (int u = 0; u < 8; ++u)  // all loads of the batch in flight together
+        hv[nb][u] = hrow[(int64_t)min(tb + u, p.n_tiles - 1) * kHistStride + bin];
+    }
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const uint32_t v = tb + u < tiles_active ? hv[nb][u] : 0u;
+        tot[nb] += v;
+        pre[nb] += tb + u < first_tile ? v : 0u;
       }
     }
   }
-  s_tot[bin0] = tot0;
-  if (bin1 < 448) s_tot[bin1] = tot1;
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+    const int bin = tid + nb * THREADS;
+    if (bin < 448) s_tot[bin] = bin < kNumBins ? tot[nb] : 0u;
+  }
+  if (THREADS < 448)
+    for (int bin = NB * THREADS + tid; bin < 448; bin += THREADS) s_tot[bin] = 0u;
   if (tid == 0) {
     s_ltb = 0u;
     s_eqb = 0u;
@@ -220,6 +296,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const SelectParams 
     s_cntlt = 0;
   }
   __syncthreads();
+  TICK();
 
   // Threshold distance T and #{D < T}, by one wave: 7 bins per lane.
   if (tid < kWave) {
@@ -229,7 +306,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const SelectParams 
       c[j] = s_tot[lane * 7 + j];
       sum += c[j];
     }
-    const uint32_t incl = wave_incl_scan_u32(sum, lane);
+    const uint32_t incl = wave_incl_scan_u32(sum);
     uint32_t run = incl - sum;
     if (kk > 0 && run < (uint32_t)kk && incl >= (uint32_t)kk) {
 #pragma unroll
@@ -245,51 +322,68 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const SelectParams 
   __syncthreads();
   const int T = s_T;
   const int r = kk - s_cntlt;  // ties at distance T to take, lowest positions first
+  TICK();
 
-  {
-    uint32_t ltb = (bin0 < T ? pre0 : 0u) + (bin1 < T ? pre1 : 0u);
-    uint32_t eqb = (bin0 == T ? pre0 : 0u) + (bin1 == T ? pre1 : 0u);
+  if (gridDim.x > 1) {  // tokens of earlier segments: #{D < T} and #{D == T}
+    uint32_t ltb = 0, eqb = 0;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      const int bin = tid + nb * THREADS;
+      ltb += bin < T ? pre[nb] : 0u;
+      eqb += bin == T ? pre[nb] : 0u;
+    }
     ltb = wave_sum_u32(ltb);
     eqb = wave_sum_u32(eqb);
     if (lane == 0) {
       atomicAdd(&s_ltb, ltb);
       atomicAdd(&s_eqb, eqb);
     }
+    __syncthreads();
   }
-  __syncthreads();
   uint32_t run_lt = s_ltb, run_eq = s_eqb;
   const uint32_t seg_pos0 = run_lt + min(run_eq, (uint32_t)r);
   int32_t* idx_row = p.idx_out != nullptr ? p.idx_out + head * p.k : nullptr;
 
-  for (int pass_t0 = seg_t0; pass_t0 < seg_t1; pass_t0 += kSelPass) {
+  for (int pass_t0 = seg_t0; pass_t0 < seg_t1; pass_t0 += PASS) {
     const int t = pass_t0 + tid * kSelTokPerThread;
-    if (pass_t0 != seg_t0) {
-      if (t < seg_t1) {
-        const uint4* src = reinterpret_cast<const uint4*>(drow + t);
-        da = src[0];
-        db = src[1];
-      } else {
-        da = db = make_uint4(0, 0, 0, 0);
-      }
+    const uint4 da = cur_a, db = cur_b;
+    cur_a = nxt_a;
+    cur_b = nxt_b;
+    if (t + 2 * PASS < seg_t1) {  // fetch the pass after next while this one is processed
+      const uint4* src = reinterpret_cast<const uint4*>(drow + t + 2 * PASS);
+      nxt_a = src[0];
+      nxt_b = src[1];
     }
+    // Two distances per 32-bit word.  Per half-word, without unpacking:
+    //   d < T  <=> bit 15 of (d - T) mod 2^16   (both below 2^15)
+    //   d == T <=> (z - 1) & ~z has bit 15 set, z = d ^ T
+    // Bit j of m_lt / m_eq stands for token t + j.
     const uint32_t words[8] = {da.x, da.y, da.z, da.w, db.x, db.y, db.z, db.w};
-    uint32_t c_lt = 0, c_eq = 0;
+    const uint32_t TT = (uint32_t)T * 0x00010001u;
+    uint32_t m_lt = 0, m_eq = 0;
 #pragma unroll
-    for (int j = 0; j < kSelTokPerThread; ++j) {
-      const int d = (int)((words[j >> 1] >> ((j & 1) * 16)) & 0xffffu);
-      const bool valid = t + j < seg_t1;
-      c_lt += (valid && d < T) ? 1u : 0u;
-      c_eq += (valid && d == T) ? 1u : 0u;
+    for (int w = 0; w < 8; ++w) {
+      const uint32_t y = pk_sub_u16(words[w], TT) & 0x80008000u;
+      const uint32_t z = words[w] ^ TT;
+      const uint32_t e = pk_sub_u16(z, 0x00010001u) & ~z & 0x80008000u;
+      m_lt |= (((y >> 15) & 1u) | (y >> 30)) << (2 * w);
+      m_eq |= (((e >> 15) & 1u) | (e >> 30)) << (2 * w);
     }
+    const int n_valid = min(max(seg_t1 - t, 0), kSelTokPerThread);
+    const uint32_t vmask = (1u << n_valid) - 1u;
+    m_lt &= vmask;
+    m_eq &= vmask;
     uint32_t total;
-    const uint32_t ex = block256_excl_scan(c_lt | (c_eq << 16), s_scan, total);
+    const uint32_t ex =
+        block_excl_scan<THREADS>((uint32_t)__popc(m_lt) | ((uint32_t)__popc(m_eq) << 16), s_scan, total);
     uint32_t lt = run_lt + (ex & 0xffffu), eq = run_eq + (ex >> 16);
-#pragma unroll
-    for (int j = 0; j < kSelTokPerThread; ++j) {
-      const int d = (int)((words[j >> 1] >> ((j & 1) * 16)) & 0xffffu);
-      const bool valid = t + j < seg_t1;
-      const bool is_lt = valid && d < T, is_eq = valid && d == T;
-      if (is_lt || (is_eq && eq < (uint32_t)r)) {
+    // Visit only the candidate tokens (set bits), in position order.
+    uint32_t cand = m_lt | m_eq;
+    while (cand != 0u) {
+      const int j = __builtin_ctz(cand);
+      cand &= cand - 1u;
+      const bool is_eq = (m_eq >> j) & 1u;
+      if (!is_eq || eq < (uint32_t)r) {
         const uint32_t pos = lt + min(eq, (uint32_t)r);
         // pos < kk always holds for consistent histograms; the checks keep a
         // corrupted workspace from turning into an out-of-bounds store.
@@ -298,26 +392,50 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const SelectParams 
           if (ATTN && pos - seg_pos0 < (uint32_t)kMaxK) s_sel[pos - seg_pos0] = t + j;
         }
       }
-      lt += is_lt ? 1u : 0u;
+      lt += is_eq ? 0u : 1u;
       eq += is_eq ? 1u : 0u;
     }
     run_lt += total & 0xffffu;
     run_eq += total >> 16;
   }
   if (seg == 0 && idx_row != nullptr)
-    for (int i = kk + tid; i < p.k; i += kSelThreads) idx_row[i] = -1;
+    for (int i = kk + tid; i < p.k; i += THREADS) idx_row[i] = -1;
+  TICK();
 
-  if (ATTN) {
+  if constexpr (ATTN) {
     const int n_sel = min((int)(run_lt + min(run_eq, (uint32_t)r) - seg_pos0), kk);
     __syncthreads();  // s_sel complete
     const int kvh = hq / (p.Hq / p.Hkv);
     const int64_t row0 = ((int64_t)kvh * p.pool_tokens + p.seq_start[b]) * kHeadDim;
-    attention_partial(s_sel, n_sel, p.q + head * kHeadDim, p.K + row0, p.V + row0, p.scale_log2e,
-                      p.partial + head * p.n_parts * kPartialStride, seg, s_attn);
+    float M, lsum, o;
+    attention_rows<THREADS>(s_sel, n_sel, p.q + head * kHeadDim, p.K + row0, p.V + row0,
+                            p.scale_log2e, s_attn, M, lsum, o);
+    TICK();
+#ifdef EXP_TIMING
+    if (tid == 0 && hq == 5 && b == 0) {
+      long long* dbg = reinterpret_cast<long long*>(p.partial + ((int64_t)gridDim.y * gridDim.z * kMaxParts * kPartialStride + 63) / 64 * 64) + seg * 8;
+      for (int i = 0; i < tki; ++i) dbg[i] = tk[i] - tk[0];
+      dbg[7] = tki;
+    }
+#endif
+    if (tid < kHeadDim) {
+      if (gridDim.x == 1) {
+        p.out[head * kHeadDim + tid] = lsum > 0.f ? o / lsum : 0.f;
+      } else {
+        float* mine = p.partial + (head * kMaxParts + seg) * kPartialStride;
+        if (tid == 0) {
+          mine[0] = M;
+          mine[1] = lsum;
+        }
+        mine[4 + tid] = o;
+      }
+    }
   }
 }
 
 // ---------------------------------------------------------------- stand-alone attention
+
+constexpr int kAttnThreads = 256;
 
 struct AttnParams {
   const uint16_t* q;
@@ -326,16 +444,18 @@ struct AttnParams {
   const int64_t* seq_start;
   const int32_t* idx;  // [B*Hq][k]
   float* out;
-  float* partial;      // [B*Hq][n_parts][kPartialStride]
+  float* partial;      // [B*Hq][kMaxParts][kPartialStride]
   int64_t pool_tokens;
   int32_t Hq, Hkv, k, n_parts, chunk;  // chunk = idx entries per workgroup
   float scale_log2e;
 };
 
-__global__ __launch_bounds__(kSelThreads) void sparse_attn_kernel(const AttnParams p) {
+// Grid (n_parts, Hq, B): workgroup `part` attends over idx entries
+// [part*chunk, (part+1)*chunk) of its head.  n_parts == 1 writes out directly.
+__global__ __launch_bounds__(kAttnThreads) void sparse_attn_kernel(const AttnParams p) {
   __shared__ int32_t s_sel[kMaxK];
-  __shared__ uint32_t s_scan[4];
-  __shared__ AttnShared s_attn;
+  __shared__ uint32_t s_scan[kAttnThreads / kWave];
+  __shared__ AttnShared<kAttnThreads> s_attn;
   const int part = blockIdx.x, hq = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x;
   const int64_t head = (int64_t)b * p.Hq + hq;
@@ -345,20 +465,33 @@ __global__ __launch_bounds__(kSelThreads) void sparse_attn_kernel(const AttnPara
   // Order-preserving compaction of the usable entries of this chunk: negative
   // entries are padding; an entry that would leave the pool is dropped too.
   uint32_t n = 0;
-  for (int base = i0; base < i1; base += kSelThreads) {
+  for (int base = i0; base < i1; base += kAttnThreads) {
     const int i = base + tid;
     const int32_t tok = i < i1 ? idx_row[i] : -1;
     const bool use = tok >= 0 && start >= 0 && start + tok < p.pool_tokens;
     uint32_t total;
-    const uint32_t ex = block256_excl_scan(use ? 1u : 0u, s_scan, total);
+    const uint32_t ex = block_excl_scan<kAttnThreads>(use ? 1u : 0u, s_scan, total);
     if (use) s_sel[n + ex] = tok;
     n += total;
   }
   __syncthreads();
   const int kvh = hq / (p.Hq / p.Hkv);
   const int64_t row0 = ((int64_t)kvh * p.pool_tokens + start) * kHeadDim;
-  attention_partial(s_sel, (int)n, p.q + head * kHeadDim, p.K + row0, p.V + row0, p.scale_log2e,
-                    p.partial + head * p.n_parts * kPartialStride, part, s_attn);
+  float M, lsum, o;
+  attention_rows<kAttnThreads>(s_sel, (int)n, p.q + head * kHeadDim, p.K + row0, p.V + row0,
+                               p.scale_log2e, s_attn, M, lsum, o);
+  if (tid < kHeadDim) {
+    if (gridDim.x == 1) {
+      p.out[head * kHeadDim + tid] = lsum > 0.f ? o / lsum : 0.f;
+    } else {
+      float* mine = p.partial + (head * kMaxParts + part) * kPartialStride;
+      if (tid == 0) {
+        mine[0] = M;
+        mine[1] = lsum;
+      }
+      mine[4 + tid] = o;
+    }
+  }
 }
 
 // Merges the attention partials of one head, in part order, into out.
@@ -366,7 +499,7 @@ __global__ __launch_bounds__(kSelThreads) void sparse_attn_kernel(const AttnPara
 // tokens of the head's sequence (as select_kernel wrote them); seg_len == 0:
 // n_parts partials (as sparse_attn_kernel wrote them).
 struct MergeParams {
-  const float* partial;      // [B*Hq][n_parts][kPartialStride]
+  const float* partial;      // [B*Hq][kMaxParts][kPartialStride]
   float* out;                // [B*Hq][128]
   const int64_t* seq_start;
   const int32_t* seq_len;
@@ -377,20 +510,34 @@ struct MergeParams {
 __global__ __launch_bounds__(kHeadDim) void merge_kernel(const MergeParams p) {
   const int hq = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
   const int64_t head = (int64_t)b * p.Hq + hq;
+  const float* ph = p.partial + head * kMaxParts * kPartialStride;
+  // All kMaxParts slots exist in the workspace whatever n_parts is: load them
+  // unconditionally (no branches, so every load is in flight at once) and mask
+  // the unused ones afterwards.
+  float pm[kMaxParts], pl[kMaxParts], po[kMaxParts];
+#pragma unroll
+  for (int s = 0; s < kMaxParts; ++s) {
+    const float* ps = ph + (int64_t)s * kPartialStride;
+    pm[s] = ps[0];
+    pl[s] = ps[1];
+    po[s] = ps[4 + tid];
+  }
   int n = p.n_parts;
   if (p.seg_len > 0) {
     const int L = safe_seq_len(p.seq_len, p.seq_start, b, p.max_seq_len, p.pool_tokens);
     n = max(1, (L + p.seg_len - 1) / p.seg_len);
   }
-  const float* ph = p.partial + head * p.n_parts * kPartialStride;
   float M = kNegBig;
-  for (int s = 0; s < n; ++s) M = fmaxf(M, ph[(int64_t)s * kPartialStride]);
+  n = min(n, min(p.n_parts, kMaxParts));
+#pragma unroll
+  for (int s = 0; s < kMaxParts; ++s) M = fmaxf(M, s < n ? pm[s] : kNegBig);
   float lsum = 0.f, o = 0.f;
-  for (int s = 0; s < n; ++s) {
-    const float* ps = ph + (int64_t)s * kPartialStride;
-    const float w = exp2f(ps[0] - M);
-    lsum = fmaf(ps[1], w, lsum);
-    o = fmaf(ps[4 + tid], w, o);
+#pragma unroll
+  for (int s = 0; s < kMaxParts; ++s) {
+    const bool use = s < n;  // slots past n hold whatever the workspace held
+    const float w = use ? exp2f(pm[s] - M) : 0.f;
+    lsum = fmaf(use ? pl[s] : 0.f, w, lsum);
+    o = fmaf(use ? po[s] : 0.f, w, o);
   }
   p.out[head * kHeadDim + tid] = lsum > 0.f ? o / lsum : 0.f;
 }
