@@ -369,6 +369,9 @@ int adamas_decode_step_stages(const adamas_config* cfg, const void* q, const voi
   sp.n_tiles = pl.n_tiles;
   sp.thr_q = scaled(cfg->thr_q);
   sp.thr_k = scaled(cfg->thr_k);
+#ifdef EXP_TIMING
+  sp.dbg = reinterpret_cast<long long*>(ws_at(workspace, pl.total));
+#endif
   if (stages & ADAMAS_STAGE_SCAN) {
     launch_scan<true>(cfg->num_q_heads / cfg->num_kv_heads,
                       dim3(pl.n_tiles, cfg->num_kv_heads, batch),

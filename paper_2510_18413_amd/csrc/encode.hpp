@@ -19,11 +19,14 @@ struct Thresholds {
 // so the stage order does not influence the result.
 // Result: the four 64-bit words of the packed row, identical in every lane.
 // src must be wave-uniform.  All 64 lanes must be active.
-__device__ __forceinline__ void encode_vector_wave(const uint16_t* __restrict__ src,
+//
+// encode_values_wave takes the two elements already loaded (raw bf16 bits), so
+// that a caller can issue that load ahead of other memory traffic.
+__device__ __forceinline__ void encode_values_wave(uint32_t bits_lo, uint32_t bits_hi,
                                                    const Thresholds& thr, uint64_t w[4]) {
   const int lane = threadIdx.x & 63;
-  double a = (double)bf16_bits_to_float(src[lane]);
-  double b = (double)bf16_bits_to_float(src[lane + 64]);
+  double a = (double)bf16_bits_to_float(bits_lo);
+  double b = (double)bf16_bits_to_float(bits_hi);
   {
     double s = a + b, d = a - b;
     a = s;
@@ -48,6 +51,12 @@ __device__ __forceinline__ void encode_vector_wave(const uint16_t* __restrict__ 
   w[1] = (alo >> 32) | (ahi & 0xffffffff00000000ull);
   w[2] = (blo & 0xffffffffull) | (bhi << 32);
   w[3] = (blo >> 32) | (bhi & 0xffffffff00000000ull);
+}
+
+__device__ __forceinline__ void encode_vector_wave(const uint16_t* __restrict__ src,
+                                                   const Thresholds& thr, uint64_t w[4]) {
+  const int lane = threadIdx.x & 63;
+  encode_values_wave(src[lane], src[lane + 64], thr, w);
 }
 
 __device__ __forceinline__ void store_row_wave(uint8_t* __restrict__ dst, const uint64_t w[4]) {

@@ -45,6 +45,7 @@ struct ScanParams {
   int64_t pool_tokens, max_seq_len;
   int32_t Hq, Hkv, n_tiles;
   Thresholds thr_q, thr_k;
+  long long* dbg;            // timing experiments only
 };
 
 template <int G, bool FUSED>
@@ -52,6 +53,7 @@ __global__ __launch_bounds__(1024) void scan_kernel(const ScanParams p) {
   __shared__ uint32_t s_hist[G][kHistReplicas][kNumBins];
   __shared__ uint32_t s_q[G][12];   // per query head: lo[4], hi[4], lo^hi[4]
   __shared__ uint32_t s_new[8];     // code row of the appended key
+  __shared__ uint32_t s_ready;      // query / new-key code rows published so far
 
   const int tile_id = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nwaves = blockDim.x >> 6;
@@ -60,75 +62,123 @@ __global__ __launch_bounds__(1024) void scan_kernel(const ScanParams p) {
   const int64_t start = p.seq_start[b];
   const int t0 = tile_id * tile_tokens;
   const int head0 = b * p.Hq + kvh * G;
+#ifdef EXP_TIMING
+  long long tk[8]; int tki = 0;
+#define STICK() do { tk[tki++] = wall_clock64(); } while (0)
+#else
+#define STICK() do {} while (0)
+#endif
+  STICK();
 
   if (t0 >= L) return;  // whole workgroup
 
-  // Issue this thread's row loads first: they do not depend on the query.
+  // The only workgroup barrier before the scan sits here, where every wave has
+  // just started.  Later on the waves must not wait for each other: a compute
+  // unit serves memory requests in order, so late waves get their rows late,
+  // and a barrier after the loads would hold the early waves back with them.
+  for (int i = tid; i < G * kHistReplicas * kNumBins; i += blockDim.x)
+    (&s_hist[0][0][0])[i] = 0u;
+  if (tid == 0) s_ready = 0u;
+  __syncthreads();
+
+  // Order of the memory operations matters: loads return in issue order, so a
+  // wave that waits for its query vector also waits for everything it issued
+  // before.  The (tiny) vector loads of the encoding waves therefore go first,
+  // then the code rows, which are consumed one token at a time as they arrive.
+  const bool appending = FUSED && p.k_new != nullptr && (L - 1) / tile_tokens == tile_id;
+  const int n_enc = FUSED ? G + (appending ? 1 : 0) : 0;
+  constexpr int kEncRounds = (G + 1 + 3) / 4;  // G queries + 1 new key over at least 4 waves
+  uint32_t enc_lo[kEncRounds], enc_hi[kEncRounds];
+#pragma unroll
+  for (int r = 0; r < kEncRounds; ++r) {
+    // Only the encoding waves load: inside a compute unit requests are served
+    // in order across waves, so a needless load here would hold a late wave
+    // (and with it the workgroup barrier) behind every earlier wave's rows.
+    const int v = wave + r * nwaves;
+    enc_lo[r] = enc_hi[r] = 0;
+    if (FUSED && v < n_enc) {
+      const uint16_t* src = v < G ? p.q + (int64_t)(head0 + v) * kHeadDim
+                                  : p.k_new + ((int64_t)b * p.Hkv + kvh) * kHeadDim;
+      enc_lo[r] = src[lane];
+      enc_hi[r] = src[lane + 64];
+    }
+  }
+  uint32_t qraw_lo = 0, qraw_hi = 0;
+  if (!FUSED && wave == 0) {
+    const int i = min(tid, G * 4 - 1);
+    const uint32_t* qc =
+        reinterpret_cast<const uint32_t*>(p.qcodes + (int64_t)(head0 + (i >> 2)) * kRowBytes);
+    qraw_lo = qc[2 * (i & 3)];
+    qraw_hi = qc[2 * (i & 3) + 1];
+  }
+
   const uint8_t* plane = p.codes + ((int64_t)kvh * p.pool_tokens + start) * kRowBytes;
   uint4 ra[kScanTokPerThread], rb[kScanTokPerThread];
 #pragma unroll
   for (int i = 0; i < kScanTokPerThread; ++i) {
-    const int t = t0 + (wave * kScanTokPerThread + i) * kWave + lane;
-    if (t < L) {
-      const uint4* row = reinterpret_cast<const uint4*>(plane + (int64_t)t * kRowBytes);
-      ra[i] = row[0];
-      rb[i] = row[1];
-    } else {
-      ra[i] = make_uint4(0, 0, 0, 0);
-      rb[i] = make_uint4(0, 0, 0, 0);
-    }
+    // Unconditional: a lane past the end re-reads the last row (masked at use).
+    // A branch here would make the compiler wait for all loads at once.
+    const int t = min(t0 + (wave * kScanTokPerThread + i) * kWave + lane, L - 1);
+    const uint4* row = reinterpret_cast<const uint4*>(plane + (int64_t)t * kRowBytes);
+    ra[i] = row[0];
+    rb[i] = row[1];
   }
 
-  for (int i = tid; i < G * kHistReplicas * kNumBins; i += blockDim.x)
-    (&s_hist[0][0][0])[i] = 0u;
-
-  const bool appending = FUSED && p.k_new != nullptr && (L - 1) / tile_tokens == tile_id;
+  // Nothing above may be consumed before the row loads have been issued.
   if (FUSED) {
-    const int n_enc = G + (appending ? 1 : 0);
-    for (int v = wave; v < n_enc; v += nwaves) {
-      uint64_t w[4];
-      if (v < G) {
-#ifdef EXP_NOENC
-        w[0] = w[1] = w[2] = w[3] = 0x123456789abcdefull;
-#else
-        encode_vector_wave(p.q + (int64_t)(head0 + v) * kHeadDim, p.thr_q, w);
-#endif
+#pragma unroll
+    for (int r = 0; r < kEncRounds; ++r) asm volatile("" : "+v"(enc_lo[r]), "+v"(enc_hi[r]));
+  } else {
+    asm volatile("" : "+v"(qraw_lo), "+v"(qraw_hi));
+  }
+  STICK();  // q arrived
+
+  if (FUSED) {
+#pragma unroll
+    for (int r = 0; r < kEncRounds; ++r) {
+      const int v = wave + r * nwaves;
+      if (v < n_enc) {
+        uint64_t w[4];
+        encode_values_wave(enc_lo[r], enc_hi[r], v < G ? p.thr_q : p.thr_k, w);
         if (lane < 4) {
           const uint64_t x = lane == 0 ? w[0] : lane == 1 ? w[1] : lane == 2 ? w[2] : w[3];
           const uint32_t lo = (uint32_t)x, hi = (uint32_t)(x >> 32);
-          s_q[v][lane] = lo;
-          s_q[v][4 + lane] = hi;
-          s_q[v][8 + lane] = lo ^ hi;
+          if (v < G) {
+            s_q[v][lane] = lo;
+            s_q[v][4 + lane] = hi;
+            s_q[v][8 + lane] = lo ^ hi;
+          } else {  // code row of the appended key
+            s_new[2 * lane] = lo;
+            s_new[2 * lane + 1] = hi;
+          }
         }
-      } else {
-        // Alg. 1 line 4: the new token's K, V and code row enter the cache
-        // before the scan; this workgroup owns the tile that holds it.
-        const int64_t src = ((int64_t)b * p.Hkv + kvh) * kHeadDim;
-        const int64_t row = (int64_t)kvh * p.pool_tokens + start + (L - 1);
-        encode_vector_wave(p.k_new + src, p.thr_k, w);
-        store_row_wave(p.codes_w + row * kRowBytes, w);
-        if (lane < 4) {
-          const uint64_t x = lane == 0 ? w[0] : lane == 1 ? w[1] : lane == 2 ? w[2] : w[3];
-          s_new[2 * lane] = (uint32_t)x;
-          s_new[2 * lane + 1] = (uint32_t)(x >> 32);
-        }
-        reinterpret_cast<uint32_t*>(p.K + row * kHeadDim)[lane] =
-            reinterpret_cast<const uint32_t*>(p.k_new + src)[lane];
-        reinterpret_cast<uint32_t*>(p.V + row * kHeadDim)[lane] =
-            reinterpret_cast<const uint32_t*>(p.v_new + src)[lane];
+        if (lane == 0)
+          __hip_atomic_fetch_add(&s_ready, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
       }
     }
-  } else {
+  } else if (wave == 0) {
     if (tid < G * 4) {
       const int g = tid >> 2, wd = tid & 3;
-      const uint32_t* qc = reinterpret_cast<const uint32_t*>(p.qcodes + (int64_t)(head0 + g) * kRowBytes);
-      const uint32_t lo = qc[2 * wd], hi = qc[2 * wd + 1];
-      s_q[g][wd] = lo;
-      s_q[g][4 + wd] = hi;
-      s_q[g][8 + wd] = lo ^ hi;
+      s_q[g][wd] = qraw_lo;
+      s_q[g][4 + wd] = qraw_hi;
+      s_q[g][8 + wd] = qraw_lo ^ qraw_hi;
+    }
+    if (lane == 0)
+      __hip_atomic_fetch_add(&s_ready, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+  }
+  STICK();  // encode done (wave 0)
+  // Wait for the publishing waves only.  They never wait for anybody, so this
+  // ends; the spin bound is a last resort that turns a logic error into wrong
+  // distances instead of a hung GPU.
+  {
+    const uint32_t n_ready = FUSED ? (uint32_t)n_enc : 1u;
+    for (int spin = 0; spin < (1 << 22); ++spin) {
+      if (__hip_atomic_load(&s_ready, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) >= n_ready)
+        break;
+      __builtin_amdgcn_s_sleep(2);
     }
   }
-  __syncthreads();
+  STICK();
 
   // The query planes are wave-uniform: keep them in scalar registers.
   uint32_t qlo[G][4], qhi[G][4], qg[G][4];
@@ -145,6 +195,8 @@ __global__ __launch_bounds__(1024) void scan_kernel(const ScanParams p) {
 
 #pragma unroll
   for (int i = 0; i < kScanTokPerThread; ++i) {
+    // keep the tokens in load order, so that each waits only for its own rows
+    __builtin_amdgcn_sched_barrier(0);
     const int t = t0 + (wave * kScanTokPerThread + i) * kWave + lane;
     uint32_t klo[4] = {ra[i].x, ra[i].z, rb[i].x, rb[i].z};
     uint32_t khi[4] = {ra[i].y, ra[i].w, rb[i].y, rb[i].w};
@@ -180,6 +232,19 @@ __global__ __launch_bounds__(1024) void scan_kernel(const ScanParams p) {
     }
   }
 
+  // Alg. 1 line 4: the new token's K, V and code row enter the cache.  The
+  // scan above already used the new code row (from LDS); the stores come last
+  // so that no other memory operation sits between the row loads and their use.
+  if (appending && wave == 0) {
+    const int64_t src = ((int64_t)b * p.Hkv + kvh) * kHeadDim;
+    const int64_t row = (int64_t)kvh * p.pool_tokens + start + (L - 1);
+    if (lane < 8) reinterpret_cast<uint32_t*>(p.codes_w + row * kRowBytes)[lane] = s_new[lane];
+    reinterpret_cast<uint32_t*>(p.K + row * kHeadDim)[lane] =
+        reinterpret_cast<const uint32_t*>(p.k_new + src)[lane];
+    reinterpret_cast<uint32_t*>(p.V + row * kHeadDim)[lane] =
+        reinterpret_cast<const uint32_t*>(p.v_new + src)[lane];
+  }
+  STICK();
   if (p.tilehist != nullptr) {
     __syncthreads();
     for (int i = tid; i < G * kNumBins; i += blockDim.x) {
@@ -190,6 +255,20 @@ __global__ __launch_bounds__(1024) void scan_kernel(const ScanParams p) {
       p.tilehist[((int64_t)(head0 + g) * p.n_tiles + tile_id) * kHistStride + bin] = (uint16_t)s;
     }
   }
+#ifdef EXP_TIMING
+  STICK();
+  if (lane == 0 && p.dbg != nullptr) {
+    long long* wd = p.dbg + 256 + 8192 * 8 + (((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 16 + wave) * 2;
+    wd[0] = tk[0]; wd[1] = tk[2];
+  }
+  if (tid == 0 && p.dbg != nullptr) {
+    long long* dbg = p.dbg + 256 + ((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 8;
+    for (int i = 0; i < tki; ++i) dbg[i] = tk[i];
+    unsigned xcc; asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+    unsigned hwid; asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hwid));
+    dbg[6] = xcc; dbg[7] = hwid;
+  }
+#endif
 }
 
 }  // namespace adamas
