@@ -48,6 +48,9 @@ def parse_args():
     ap.add_argument("--layers", type=int, default=32, help="distinct layer caches to rotate over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--eager", action="store_true", help="launch from Python instead of a graph")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run 8 plain 256 MiB copy-like kernels (reference for rocprofv3 --pmc "
+                         "FETCH_SIZE / WRITE_SIZE readings)")
     return ap.parse_args()
 
 
@@ -214,6 +217,16 @@ def main():
         wall = (time.perf_counter() - t0) * 1e3
         per_sweep = [ev[s].elapsed_time(ev[s + 1]) for s in range(sweeps)]
         return ev[0].elapsed_time(ev[sweeps + 1]) / steps, wall / steps, per_sweep
+
+    if args.calibrate_copy:
+        # bitwise_not: one read and one write of 256 MiB, under a kernel name that is easy to
+        # find in the counter output
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(7)
+        dst = torch.empty_like(src)
+        for _ in range(8):
+            torch.bitwise_not(src, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ------------------------------------------------------------------ the timed region
     ms_evt, ms_wall, per_sweep = timed(None, args.steps, args.warmup)
