@@ -48,6 +48,8 @@ def parse_args():
     ap.add_argument("--layers", type=int, default=32, help="distinct layer caches to rotate over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--eager", action="store_true", help="launch from Python instead of a graph")
+    ap.add_argument("--scan-only", action="store_true",
+                    help="time only the scan stage (profiling aid; no JSON-contract value)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run 8 plain 256 MiB copy-like kernels (reference for rocprofv3 --pmc "
                          "FETCH_SIZE / WRITE_SIZE readings)")
@@ -229,6 +231,10 @@ def main():
         del src, dst
 
     # ------------------------------------------------------------------ the timed region
+    if args.scan_only:
+        ms_scan, _, _ = timed(A.STAGE_SCAN, args.steps, args.warmup)
+        print(json.dumps({"scan_us_per_launch": round(ms_scan * 1e3, 3), "config": args.config}))
+        return
     ms_evt, ms_wall, per_sweep = timed(None, args.steps, args.warmup)
     us_step = ms_wall * 1e3
     # dominant kernel alone (distance scan with fused query encode), same rotation

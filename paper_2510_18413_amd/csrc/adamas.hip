@@ -30,7 +30,7 @@ struct Plan {
   int seg_len;       // tokens per select workgroup, multiple of tile_tokens and of kSelPass
   int n_segs;        // select workgroups per (sequence, query head)
   int64_t dist_stride;
-  size_t off_dist, off_hist, off_partial, total;
+  size_t off_dist, off_hist, off_partial, off_counters, total;
 };
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -94,6 +94,8 @@ Plan make_plan(const adamas_config* c, int32_t batch, int64_t max_seq_len, int32
   off = align256(off + heads * (size_t)pl.n_tiles * kHistStride * sizeof(uint16_t));
   pl.off_partial = off;
   off = align256(off + heads * (size_t)kMaxParts * kPartialStride * sizeof(float));
+  pl.off_counters = off;
+  off = align256(off + heads * sizeof(uint32_t));
   pl.total = off;
   return pl;
 }
@@ -369,6 +371,7 @@ int adamas_decode_step_stages(const adamas_config* cfg, const void* q, const voi
   sp.n_tiles = pl.n_tiles;
   sp.thr_q = scaled(cfg->thr_q);
   sp.thr_k = scaled(cfg->thr_k);
+  sp.counters = reinterpret_cast<uint32_t*>(ws_at(workspace, pl.off_counters));
 #ifdef EXP_TIMING
   sp.dbg = reinterpret_cast<long long*>(ws_at(workspace, pl.total));
 #endif
@@ -401,9 +404,22 @@ int adamas_decode_step_stages(const adamas_config* cfg, const void* q, const voi
   sl.tile_tokens = pl.tile_tokens;
   sl.seg_len = pl.seg_len;
   sl.scale_log2e = scale_log2e(cfg);
+  sl.counters = sp.counters;
+#ifdef EXP_TILE_ENV
+  if (getenv("ADAMAS_SEL1024"))
+    hipLaunchKernelGGL((select_kernel<1024, true>), dim3(pl.n_segs, cfg->num_q_heads, batch),
+                       dim3(1024), 0, st, sl);
+  else if (getenv("ADAMAS_SEL512"))
+    hipLaunchKernelGGL((select_kernel<512, true>), dim3(pl.n_segs, cfg->num_q_heads, batch),
+                       dim3(512), 0, st, sl);
+  else
+#endif
   hipLaunchKernelGGL((select_kernel<kSelThreads, true>), dim3(pl.n_segs, cfg->num_q_heads, batch),
                      dim3(kSelThreads), 0, st, sl);
   if (int rc = launch_status()) return rc;
+#ifdef EXP_INKERNEL_MERGE
+  return ADAMAS_OK;
+#endif
   if (pl.n_segs == 1) return ADAMAS_OK;  // the select workgroup wrote `out` itself
   MergeParams mp{};
   mp.partial = sl.partial;

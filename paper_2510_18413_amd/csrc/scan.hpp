@@ -24,7 +24,10 @@
 namespace adamas {
 
 constexpr int kScanTokPerThread = 4;
-constexpr int kHistReplicas = 4;  // LDS histogram copies, picked by lane, to thin out same-address atomics
+#ifndef EXP_REPLICAS
+#define EXP_REPLICAS 4
+#endif
+constexpr int kHistReplicas = EXP_REPLICAS;  // LDS histogram copies, picked by lane, to thin out same-address atomics
 
 struct ScanParams {
   const uint8_t* codes;      // [Hkv][pool][32]
@@ -45,6 +48,7 @@ struct ScanParams {
   int64_t pool_tokens, max_seq_len;
   int32_t Hq, Hkv, n_tiles;
   Thresholds thr_q, thr_k;
+  uint32_t* counters;        // [B*Hq] arrival counters of the following kernel, zeroed here
   long long* dbg;            // timing experiments only
 };
 
@@ -58,8 +62,13 @@ __global__ __launch_bounds__(1024) void scan_kernel(const ScanParams p) {
   const int tile_id = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nwaves = blockDim.x >> 6;
   const int tile_tokens = blockDim.x * kScanTokPerThread;
+#ifdef EXP_NOSEQ
+  const int L = (int)p.max_seq_len;
+  const int64_t start = 0;
+#else
   const int L = safe_seq_len(p.seq_len, p.seq_start, b, p.max_seq_len, p.pool_tokens);
   const int64_t start = p.seq_start[b];
+#endif
   const int t0 = tile_id * tile_tokens;
   const int head0 = b * p.Hq + kvh * G;
 #ifdef EXP_TIMING
@@ -70,6 +79,7 @@ __global__ __launch_bounds__(1024) void scan_kernel(const ScanParams p) {
 #endif
   STICK();
 
+  if (tile_id == 0 && p.counters != nullptr && tid < G) p.counters[head0 + tid] = 0u;
   if (t0 >= L) return;  // whole workgroup
 
   // The only workgroup barrier before the scan sits here, where every wave has

@@ -40,6 +40,7 @@ struct SelectParams {
   const uint16_t* V;
   float* out;                 // [B*Hq][128]
   float* partial;             // [B*Hq][kMaxParts][kPartialStride]
+  uint32_t* counters;         // [B*Hq], zero on entry (experiment: merge inside this kernel)
   int64_t pool_tokens, max_seq_len;
   int32_t Hq, Hkv, k;
   int32_t n_tiles, tile_tokens, seg_len;
@@ -81,9 +82,10 @@ struct AttnShared {
 // softmax per 16-lane group in fp32 (exp2 domain), groups combined in fixed
 // order through LDS.  Threads 0..127 receive, for output dim tid: M (running
 // maximum), lsum (sum of weights) and o (unnormalised weighted sum of V).
+// Entries of s_sel are clamped to [0, n_tokens) before use (n_tokens >= 1 when n > 0).
 // All threads must call it.
 template <int THREADS>
-__device__ __forceinline__ void attention_rows(const int32_t* s_sel, int n,
+__device__ __forceinline__ void attention_rows(const int32_t* s_sel, int n, int n_tokens,
                                                const uint16_t* __restrict__ q,
                                                const uint16_t* __restrict__ Kp,
                                                const uint16_t* __restrict__ Vp, float scale_log2e,
@@ -116,7 +118,9 @@ __device__ __forceinline__ void attention_rows(const int32_t* s_sel, int n,
       const int i = i0 + u * kGroups;
       ok[u] = i < n;
       if (ok[u]) {
-        const int64_t off = (int64_t)s_sel[i] * kHeadDim + gl * 8;
+        // clamped: whatever the list holds, the gather stays inside the sequence
+        const int tok = min(max(s_sel[i], 0), n_tokens - 1);
+        const int64_t off = (int64_t)tok * kHeadDim + gl * 8;
         kv[u] = *reinterpret_cast<const uint4*>(Kp + off);
         vv[u] = *reinterpret_cast<const uint4*>(Vp + off);
       } else {
@@ -408,7 +412,7 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
     const int kvh = hq / (p.Hq / p.Hkv);
     const int64_t row0 = ((int64_t)kvh * p.pool_tokens + p.seq_start[b]) * kHeadDim;
     float M, lsum, o;
-    attention_rows<THREADS>(s_sel, n_sel, p.q + head * kHeadDim, p.K + row0, p.V + row0,
+    attention_rows<THREADS>(s_sel, n_sel, L, p.q + head * kHeadDim, p.K + row0, p.V + row0,
                             p.scale_log2e, s_attn, M, lsum, o);
     TICK();
 #ifdef EXP_TIMING
@@ -430,6 +434,42 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
         mine[4 + tid] = o;
       }
     }
+#ifdef EXP_INKERNEL_MERGE
+    if (gridDim.x > 1) {
+      __shared__ uint32_t s_last;
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+      __syncthreads();
+      if (tid == 0) {
+        const uint32_t old = __hip_atomic_fetch_add(p.counters + head, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        s_last = (old == (uint32_t)(n_active - 1)) ? 1u : 0u;
+      }
+      __syncthreads();
+      if (s_last != 0u) {
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+        if (tid < kHeadDim) {
+          const float* ph = p.partial + head * kMaxParts * kPartialStride;
+          float pm[kMaxParts], pl[kMaxParts], po[kMaxParts];
+#pragma unroll
+          for (int s = 0; s < kMaxParts; ++s) {
+            const float* ps = ph + (int64_t)s * kPartialStride;
+            pm[s] = ps[0]; pl[s] = ps[1]; po[s] = ps[4 + tid];
+          }
+          float MM = kNegBig;
+#pragma unroll
+          for (int s = 0; s < kMaxParts; ++s) MM = fmaxf(MM, s < n_active ? pm[s] : kNegBig);
+          float ls = 0.f, oo = 0.f;
+#pragma unroll
+          for (int s = 0; s < kMaxParts; ++s) {
+            const bool use = s < n_active;
+            const float w = use ? exp2f(pm[s] - MM) : 0.f;
+            ls = fmaf(use ? pl[s] : 0.f, w, ls);
+            oo = fmaf(use ? po[s] : 0.f, w, oo);
+          }
+          p.out[head * kHeadDim + tid] = ls > 0.f ? oo / ls : 0.f;
+        }
+      }
+    }
+#endif
   }
 }
 
@@ -478,7 +518,8 @@ __global__ __launch_bounds__(kAttnThreads) void sparse_attn_kernel(const AttnPar
   const int kvh = hq / (p.Hq / p.Hkv);
   const int64_t row0 = ((int64_t)kvh * p.pool_tokens + start) * kHeadDim;
   float M, lsum, o;
-  attention_rows<kAttnThreads>(s_sel, (int)n, p.q + head * kHeadDim, p.K + row0, p.V + row0,
+  attention_rows<kAttnThreads>(s_sel, (int)n, (int)min((int64_t)0x7fffffff, p.pool_tokens - start),
+                               p.q + head * kHeadDim, p.K + row0, p.V + row0,
                                p.scale_log2e, s_attn, M, lsum, o);
   if (tid < kHeadDim) {
     if (gridDim.x == 1) {
