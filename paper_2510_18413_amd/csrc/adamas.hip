@@ -6,7 +6,6 @@
 
 #include <cmath>
 #include <cstdint>
-#include <cstdlib>
 
 #include "encode.hpp"
 #include "scan.hpp"
@@ -30,7 +29,7 @@ struct Plan {
   int seg_len;       // tokens per select workgroup, multiple of tile_tokens and of kSelPass
   int n_segs;        // select workgroups per (sequence, query head)
   int64_t dist_stride;
-  size_t off_dist, off_hist, off_partial, off_counters, total;
+  size_t off_dist, off_hist, off_partial, total;
 };
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -69,18 +68,16 @@ Plan make_plan(const adamas_config* c, int32_t batch, int64_t max_seq_len, int32
       break;
     }
   }
-#ifdef EXP_TILE_ENV
-  if (const char* e = getenv("ADAMAS_TILE")) pl.tile_tokens = atoi(e);
-#endif
   pl.n_tiles = (int)((max_seq_len + pl.tile_tokens - 1) / pl.tile_tokens);
-  // Select + attention: a head is cut into at most kMaxParts segments, one
-  // workgroup each (a single compute unit is far too slow to compact a whole
-  // 32K-token head or to gather all of its rows); a merge kernel combines the
-  // segments' attention partials.  A head that fits one segment needs no merge.
-  int64_t want = kMaxParts;
-#ifdef EXP_TILE_ENV
-  if (const char* e = getenv("ADAMAS_SEGS")) want = atoi(e);
-#endif
+  // Select + attention: a head is cut into segments, one workgroup each (a
+  // single compute unit is too slow to compact a whole 32K-token head or to
+  // gather all of its rows), and a merge kernel combines the segments'
+  // attention partials.  With many heads in flight there is parallelism enough
+  // already: fewer segments mean fewer re-reads of the head's histograms, and a
+  // head that fits one segment needs no merge at all.
+  const int64_t n_heads = (int64_t)batch * c->num_q_heads;
+  int64_t want = (2 * kTargetWorkgroups + n_heads - 1) / n_heads;
+  if (want > kMaxParts) want = kMaxParts;
   int64_t seg = (max_seq_len + want - 1) / want;
   seg = (seg + kSegGranule - 1) / kSegGranule * kSegGranule;  // multiple of every tile size
   pl.seg_len = (int)seg;
@@ -94,8 +91,6 @@ Plan make_plan(const adamas_config* c, int32_t batch, int64_t max_seq_len, int32
   off = align256(off + heads * (size_t)pl.n_tiles * kHistStride * sizeof(uint16_t));
   pl.off_partial = off;
   off = align256(off + heads * (size_t)kMaxParts * kPartialStride * sizeof(float));
-  pl.off_counters = off;
-  off = align256(off + heads * sizeof(uint32_t));
   pl.total = off;
   return pl;
 }
@@ -371,10 +366,6 @@ int adamas_decode_step_stages(const adamas_config* cfg, const void* q, const voi
   sp.n_tiles = pl.n_tiles;
   sp.thr_q = scaled(cfg->thr_q);
   sp.thr_k = scaled(cfg->thr_k);
-  sp.counters = reinterpret_cast<uint32_t*>(ws_at(workspace, pl.off_counters));
-#ifdef EXP_TIMING
-  sp.dbg = reinterpret_cast<long long*>(ws_at(workspace, pl.total));
-#endif
   if (stages & ADAMAS_STAGE_SCAN) {
     launch_scan<true>(cfg->num_q_heads / cfg->num_kv_heads,
                       dim3(pl.n_tiles, cfg->num_kv_heads, batch),
@@ -404,22 +395,9 @@ int adamas_decode_step_stages(const adamas_config* cfg, const void* q, const voi
   sl.tile_tokens = pl.tile_tokens;
   sl.seg_len = pl.seg_len;
   sl.scale_log2e = scale_log2e(cfg);
-  sl.counters = sp.counters;
-#ifdef EXP_TILE_ENV
-  if (getenv("ADAMAS_SEL1024"))
-    hipLaunchKernelGGL((select_kernel<1024, true>), dim3(pl.n_segs, cfg->num_q_heads, batch),
-                       dim3(1024), 0, st, sl);
-  else if (getenv("ADAMAS_SEL512"))
-    hipLaunchKernelGGL((select_kernel<512, true>), dim3(pl.n_segs, cfg->num_q_heads, batch),
-                       dim3(512), 0, st, sl);
-  else
-#endif
   hipLaunchKernelGGL((select_kernel<kSelThreads, true>), dim3(pl.n_segs, cfg->num_q_heads, batch),
                      dim3(kSelThreads), 0, st, sl);
   if (int rc = launch_status()) return rc;
-#ifdef EXP_INKERNEL_MERGE
-  return ADAMAS_OK;
-#endif
   if (pl.n_segs == 1) return ADAMAS_OK;  // the select workgroup wrote `out` itself
   MergeParams mp{};
   mp.partial = sl.partial;

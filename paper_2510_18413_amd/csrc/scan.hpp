@@ -24,10 +24,7 @@
 namespace adamas {
 
 constexpr int kScanTokPerThread = 4;
-#ifndef EXP_REPLICAS
-#define EXP_REPLICAS 4
-#endif
-constexpr int kHistReplicas = EXP_REPLICAS;  // LDS histogram copies, picked by lane, to thin out same-address atomics
+constexpr int kHistReplicas = 4;  // LDS histogram copies, picked by lane, to thin out same-address atomics
 
 struct ScanParams {
   const uint8_t* codes;      // [Hkv][pool][32]
@@ -48,8 +45,6 @@ struct ScanParams {
   int64_t pool_tokens, max_seq_len;
   int32_t Hq, Hkv, n_tiles;
   Thresholds thr_q, thr_k;
-  uint32_t* counters;        // [B*Hq] arrival counters of the following kernel, zeroed here
-  long long* dbg;            // timing experiments only
 };
 
 template <int G, bool FUSED>
@@ -62,34 +57,22 @@ __global__ __launch_bounds__(1024) void scan_kernel(const ScanParams p) {
   const int tile_id = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nwaves = blockDim.x >> 6;
   const int tile_tokens = blockDim.x * kScanTokPerThread;
-#ifdef EXP_NOSEQ
-  const int L = (int)p.max_seq_len;
-  const int64_t start = 0;
-#else
   const int L = safe_seq_len(p.seq_len, p.seq_start, b, p.max_seq_len, p.pool_tokens);
   const int64_t start = p.seq_start[b];
-#endif
   const int t0 = tile_id * tile_tokens;
   const int head0 = b * p.Hq + kvh * G;
-#ifdef EXP_TIMING
-  long long tk[8]; int tki = 0;
-#define STICK() do { tk[tki++] = wall_clock64(); } while (0)
-#else
-#define STICK() do {} while (0)
-#endif
-  STICK();
-
-  if (tile_id == 0 && p.counters != nullptr && tid < G) p.counters[head0 + tid] = 0u;
-  if (t0 >= L) return;  // whole workgroup
 
   // The only workgroup barrier before the scan sits here, where every wave has
-  // just started.  Later on the waves must not wait for each other: a compute
-  // unit serves memory requests in order, so late waves get their rows late,
-  // and a barrier after the loads would hold the early waves back with them.
+  // just started (and while the sequence length is still on its way).  Later
+  // on the waves must not wait for each other: a compute unit serves memory
+  // requests in order, so late waves get their rows late, and a barrier after
+  // the loads would hold the early waves back with them.
   for (int i = tid; i < G * kHistReplicas * kNumBins; i += blockDim.x)
     (&s_hist[0][0][0])[i] = 0u;
   if (tid == 0) s_ready = 0u;
   __syncthreads();
+
+  if (t0 >= L) return;  // whole workgroup
 
   // Order of the memory operations matters: loads return in issue order, so a
   // wave that waits for its query vector also waits for everything it issued
@@ -141,7 +124,6 @@ __global__ __launch_bounds__(1024) void scan_kernel(const ScanParams p) {
   } else {
     asm volatile("" : "+v"(qraw_lo), "+v"(qraw_hi));
   }
-  STICK();  // q arrived
 
   if (FUSED) {
 #pragma unroll
@@ -176,7 +158,6 @@ __global__ __launch_bounds__(1024) void scan_kernel(const ScanParams p) {
     if (lane == 0)
       __hip_atomic_fetch_add(&s_ready, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
   }
-  STICK();  // encode done (wave 0)
   // Wait for the publishing waves only.  They never wait for anybody, so this
   // ends; the spin bound is a last resort that turns a logic error into wrong
   // distances instead of a hung GPU.
@@ -188,7 +169,6 @@ __global__ __launch_bounds__(1024) void scan_kernel(const ScanParams p) {
       __builtin_amdgcn_s_sleep(2);
     }
   }
-  STICK();
 
   // The query planes are wave-uniform: keep them in scalar registers.
   uint32_t qlo[G][4], qhi[G][4], qg[G][4];
@@ -229,15 +209,9 @@ __global__ __launch_bounds__(1024) void scan_kernel(const ScanParams p) {
       const uint32_t d = c1 + 2u * c2;
       if (t < L) {
         const int64_t head = head0 + g;
-#ifndef EXP_NODIST
         if (p.dist != nullptr) p.dist[head * p.dist_stride + t] = (uint16_t)d;
-#endif
         if (p.dist_user != nullptr) p.dist_user[head * p.dist_user_stride + t] = (uint16_t)d;
-#ifndef EXP_NOHIST
         atomicAdd(hist_lane + g * (kHistReplicas * kNumBins) + d, 1u);
-#else
-        if (d == 0x7fffffffu) hist_lane[0] = 1;
-#endif
       }
     }
   }
@@ -254,7 +228,6 @@ __global__ __launch_bounds__(1024) void scan_kernel(const ScanParams p) {
     reinterpret_cast<uint32_t*>(p.V + row * kHeadDim)[lane] =
         reinterpret_cast<const uint32_t*>(p.v_new + src)[lane];
   }
-  STICK();
   if (p.tilehist != nullptr) {
     __syncthreads();
     for (int i = tid; i < G * kNumBins; i += blockDim.x) {
@@ -265,20 +238,6 @@ __global__ __launch_bounds__(1024) void scan_kernel(const ScanParams p) {
       p.tilehist[((int64_t)(head0 + g) * p.n_tiles + tile_id) * kHistStride + bin] = (uint16_t)s;
     }
   }
-#ifdef EXP_TIMING
-  STICK();
-  if (lane == 0 && p.dbg != nullptr) {
-    long long* wd = p.dbg + 256 + 8192 * 8 + (((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 16 + wave) * 2;
-    wd[0] = tk[0]; wd[1] = tk[2];
-  }
-  if (tid == 0 && p.dbg != nullptr) {
-    long long* dbg = p.dbg + 256 + ((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 8;
-    for (int i = 0; i < tki; ++i) dbg[i] = tk[i];
-    unsigned xcc; asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
-    unsigned hwid; asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hwid));
-    dbg[6] = xcc; dbg[7] = hwid;
-  }
-#endif
 }
 
 }  // namespace adamas

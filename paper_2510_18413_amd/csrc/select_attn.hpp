@@ -40,7 +40,6 @@ struct SelectParams {
   const uint16_t* V;
   float* out;                 // [B*Hq][128]
   float* partial;             // [B*Hq][kMaxParts][kPartialStride]
-  uint32_t* counters;         // [B*Hq], zero on entry (experiment: merge inside this kernel)
   int64_t pool_tokens, max_seq_len;
   int32_t Hq, Hkv, k;
   int32_t n_tiles, tile_tokens, seg_len;
@@ -205,13 +204,6 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int64_t head = (int64_t)b * p.Hq + hq;
   const int seg_t0 = seg * p.seg_len;
-#ifdef EXP_TIMING
-  long long tk[8]; int tki = 0;
-#define TICK() do { tk[tki++] = wall_clock64(); } while (0)
-#else
-#define TICK() do {} while (0)
-#endif
-  TICK();
 
   // Nothing below depends on the sequence length until the loads are issued:
   // the workspace rows exist up to dist_stride / n_tiles whatever L is, and
@@ -251,7 +243,6 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
   const int kk = min(p.k, L);
   const int n_active = max(1, (L + p.seg_len - 1) / p.seg_len);  // segments that hold tokens
   if (seg >= n_active) return;
-  if (L >= 0) TICK();
   const int seg_t1 = min(L, seg_t0 + p.seg_len);
   const int tiles_active = (L + p.tile_tokens - 1) / p.tile_tokens;
 
@@ -300,7 +291,6 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
     s_cntlt = 0;
   }
   __syncthreads();
-  TICK();
 
   // Threshold distance T and #{D < T}, by one wave: 7 bins per lane.
   if (tid < kWave) {
@@ -326,7 +316,6 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
   __syncthreads();
   const int T = s_T;
   const int r = kk - s_cntlt;  // ties at distance T to take, lowest positions first
-  TICK();
 
   if (gridDim.x > 1) {  // tokens of earlier segments: #{D < T} and #{D == T}
     uint32_t ltb = 0, eqb = 0;
@@ -404,7 +393,6 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
   }
   if (seg == 0 && idx_row != nullptr)
     for (int i = kk + tid; i < p.k; i += THREADS) idx_row[i] = -1;
-  TICK();
 
   if constexpr (ATTN) {
     const int n_sel = min((int)(run_lt + min(run_eq, (uint32_t)r) - seg_pos0), kk);
@@ -414,15 +402,7 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
     float M, lsum, o;
     attention_rows<THREADS>(s_sel, n_sel, L, p.q + head * kHeadDim, p.K + row0, p.V + row0,
                             p.scale_log2e, s_attn, M, lsum, o);
-    TICK();
-#ifdef EXP_TIMING
-    if (tid == 0 && hq == 5 && b == 0) {
-      long long* dbg = reinterpret_cast<long long*>(p.partial + ((int64_t)gridDim.y * gridDim.z * kMaxParts * kPartialStride + 63) / 64 * 64) + seg * 8;
-      for (int i = 0; i < tki; ++i) dbg[i] = tk[i] - tk[0];
-      dbg[7] = tki;
-    }
-#endif
-    if (tid < kHeadDim) {
+      if (tid < kHeadDim) {
       if (gridDim.x == 1) {
         p.out[head * kHeadDim + tid] = lsum > 0.f ? o / lsum : 0.f;
       } else {
@@ -434,42 +414,6 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
         mine[4 + tid] = o;
       }
     }
-#ifdef EXP_INKERNEL_MERGE
-    if (gridDim.x > 1) {
-      __shared__ uint32_t s_last;
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-      __syncthreads();
-      if (tid == 0) {
-        const uint32_t old = __hip_atomic_fetch_add(p.counters + head, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        s_last = (old == (uint32_t)(n_active - 1)) ? 1u : 0u;
-      }
-      __syncthreads();
-      if (s_last != 0u) {
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-        if (tid < kHeadDim) {
-          const float* ph = p.partial + head * kMaxParts * kPartialStride;
-          float pm[kMaxParts], pl[kMaxParts], po[kMaxParts];
-#pragma unroll
-          for (int s = 0; s < kMaxParts; ++s) {
-            const float* ps = ph + (int64_t)s * kPartialStride;
-            pm[s] = ps[0]; pl[s] = ps[1]; po[s] = ps[4 + tid];
-          }
-          float MM = kNegBig;
-#pragma unroll
-          for (int s = 0; s < kMaxParts; ++s) MM = fmaxf(MM, s < n_active ? pm[s] : kNegBig);
-          float ls = 0.f, oo = 0.f;
-#pragma unroll
-          for (int s = 0; s < kMaxParts; ++s) {
-            const bool use = s < n_active;
-            const float w = use ? exp2f(pm[s] - MM) : 0.f;
-            ls = fmaf(use ? pl[s] : 0.f, w, ls);
-            oo = fmaf(use ? po[s] : 0.f, w, oo);
-          }
-          p.out[head * kHeadDim + tid] = ls > 0.f ? oo / ls : 0.f;
-        }
-      }
-    }
-#endif
   }
 }
 
