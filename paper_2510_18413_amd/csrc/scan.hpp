@@ -5,7 +5,8 @@
 // One workgroup owns one tile of blockDim.x * 4 consecutive tokens of one
 // (sequence, KV head) and evaluates all G query heads of that KV head's
 // group on it, so every code row is fetched once.  It writes
-//   - one uint16 distance per (query head, token), and
+//   - one uint16 distance per (query head, token) (staged through LDS so that
+//     stores are 8 bytes per lane), and
 //   - one 385-bin histogram of those distances per (query head, tile),
 // both with plain stores: nothing needs zero-initialised memory and the
 // result does not depend on the order workgroups run in.
@@ -24,6 +25,7 @@
 namespace adamas {
 
 constexpr int kScanTokPerThread = 4;
+constexpr int kMaxScanWaves = 16;
 constexpr int kHistReplicas = 4;  // LDS histogram copies, picked by lane, to thin out same-address atomics
 
 struct ScanParams {
@@ -53,6 +55,8 @@ __global__ __launch_bounds__(1024) void scan_kernel(const ScanParams p) {
   __shared__ uint32_t s_q[G][12];   // per query head: lo[4], hi[4], lo^hi[4]
   __shared__ uint32_t s_new[8];     // code row of the appended key
   __shared__ uint32_t s_ready;      // query / new-key code rows published so far
+  // per wave: its 256 distances per query head, in token order, for wide stores
+  __shared__ uint16_t s_dt[kMaxScanWaves][G][kScanTokPerThread * kWave];
 
   const int tile_id = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nwaves = blockDim.x >> 6;
@@ -207,11 +211,31 @@ __global__ __launch_bounds__(1024) void scan_kernel(const ScanParams p) {
         c2 += __popc(xh & ~(xl & qg[g][wd]));
       }
       const uint32_t d = c1 + 2u * c2;
+      s_dt[wave][g][i * kWave + lane] = (uint16_t)d;
       if (t < L) {
         const int64_t head = head0 + g;
-        if (p.dist != nullptr) p.dist[head * p.dist_stride + t] = (uint16_t)d;
         if (p.dist_user != nullptr) p.dist_user[head * p.dist_user_stride + t] = (uint16_t)d;
         atomicAdd(hist_lane + g * (kHistReplicas * kNumBins) + d, 1u);
+      }
+    }
+  }
+
+  // Distances leave through LDS: a lane computed tokens 64 apart, but stores
+  // four consecutive tokens (8 bytes), so a wave writes 512 contiguous bytes
+  // per query head with one instruction instead of four 2-byte-per-lane ones.
+  // The region is private to the wave, so no barrier is needed.
+  if (p.dist != nullptr) {
+    const int tt = t0 + wave * (kScanTokPerThread * kWave) + kScanTokPerThread * lane;
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      const uint2 v = *reinterpret_cast<const uint2*>(&s_dt[wave][g][kScanTokPerThread * lane]);
+      uint16_t* dst = p.dist + (int64_t)(head0 + g) * p.dist_stride + tt;
+      if (tt + 3 < L) {
+        *reinterpret_cast<uint2*>(dst) = v;
+      } else {
+        if (tt < L) dst[0] = (uint16_t)(v.x & 0xffffu);
+        if (tt + 1 < L) dst[1] = (uint16_t)(v.x >> 16);
+        if (tt + 2 < L) dst[2] = (uint16_t)(v.y & 0xffffu);
       }
     }
   }
