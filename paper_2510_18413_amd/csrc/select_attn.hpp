@@ -24,6 +24,8 @@
 namespace adamas {
 
 constexpr int kSelTokPerThread = 16;
+constexpr int kHistPairs = kHistStride / 2;  // 196 pairs of uint16 histogram bins
+constexpr int kHistBatch = 16;               // tiles whose histograms are loaded together
 constexpr int kMaxParts = 16;  // attention partial slots per head in the workspace
 constexpr int kMaxK = 4096;
 constexpr float kNegBig = -1.0e30f;
@@ -191,7 +193,7 @@ __device__ __forceinline__ void attention_rows(const int32_t* s_sel, int n, int 
 // (M, lsum, o[128]) partial for merge_kernel.
 template <int THREADS, bool ATTN>
 __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
-  constexpr int NB = (kHistStride + THREADS - 1) / THREADS;  // histogram bins per thread
+  static_assert(THREADS >= kHistPairs, "one thread per pair of histogram bins");
   constexpr int PASS = THREADS * kSelTokPerThread;           // tokens per pass
   __shared__ uint32_t s_tot[448];
   __shared__ uint32_t s_scan[THREADS / kWave];
@@ -228,16 +230,14 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
       nxt_a = nxt_b = make_uint4(0, 0, 0, 0);
     }
   }
+  // Tile histograms: thread t < 196 owns bins 2t and 2t+1 (one 32-bit load per tile).
   const uint16_t* hrow = p.tilehist + head * p.n_tiles * kHistStride;
   const int first_tile = seg_t0 / p.tile_tokens;
-  uint32_t hv[NB][8];
+  const int pair = min(tid, kHistPairs - 1);  // clamped: spare threads repeat the last pair
+  uint32_t hv[kHistBatch];
 #pragma unroll
-  for (int nb = 0; nb < NB; ++nb) {
-    // clamped, never out of bounds: no branches, so all loads are in flight together
-    const int bin = min(tid + nb * THREADS, kHistStride - 1);
-#pragma unroll
-    for (int u = 0; u < 8; ++u) hv[nb][u] = hrow[(int64_t)min(u, p.n_tiles - 1) * kHistStride + bin];
-  }
+  for (int u = 0; u < kHistBatch; ++u)  // clamped, branch-free: all loads in flight together
+    hv[u] = reinterpret_cast<const uint32_t*>(hrow + (int64_t)min(u, p.n_tiles - 1) * kHistStride)[pair];
 
   const int L = safe_seq_len(p.seq_len, p.seq_start, b, p.max_seq_len, p.pool_tokens);
   const int kk = min(p.k, L);
@@ -247,43 +247,30 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
   const int tiles_active = (L + p.tile_tokens - 1) / p.tile_tokens;
 
   // Head histogram (all tiles with tokens) and the part of it before this segment.
-  uint32_t tot[NB], pre[NB];
+  uint32_t tot0 = 0, tot1 = 0, pre0 = 0, pre1 = 0;
+  for (int tb = 0; tb < tiles_active; tb += kHistBatch) {
+    if (tb > 0) {
 #pragma unroll
-  for (int nb = 0; nb < NB; ++nb) {
-    tot[nb] = 0;
-    pre[nb] = 0;
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      const uint32_t v = u < tiles_active ? hv[nb][u] : 0u;
-      tot[nb] += v;
-      pre[nb] += u < first_tile ? v : 0u;
-    }
-  }
-  for (int tb = 8; tb < tiles_active; tb += 8) {
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-      const int bin = min(tid + nb * THREADS, kHistStride - 1);
-#pragma unroll
-      for (int u = 0; u < 8; ++u)  // all loads of the batch in flight together
-        hv[nb][u] = hrow[(int64_t)min(tb + u, p.n_tiles - 1) * kHistStride + bin];
+      for (int u = 0; u < kHistBatch; ++u)
+        hv[u] = reinterpret_cast<const uint32_t*>(
+            hrow + (int64_t)min(tb + u, p.n_tiles - 1) * kHistStride)[pair];
     }
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-#pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const uint32_t v = tb + u < tiles_active ? hv[nb][u] : 0u;
-        tot[nb] += v;
-        pre[nb] += tb + u < first_tile ? v : 0u;
+    for (int u = 0; u < kHistBatch; ++u) {
+      const uint32_t v = tb + u < tiles_active ? hv[u] : 0u;
+      tot0 += v & 0xffffu;
+      tot1 += v >> 16;
+      if (tb + u < first_tile) {
+        pre0 += v & 0xffffu;
+        pre1 += v >> 16;
       }
     }
   }
-#pragma unroll
-  for (int nb = 0; nb < NB; ++nb) {
-    const int bin = tid + nb * THREADS;
-    if (bin < 448) s_tot[bin] = bin < kNumBins ? tot[nb] : 0u;
+  const int bin0 = 2 * tid, bin1 = 2 * tid + 1;  // meaningful for tid < kHistPairs
+  for (int i = tid; i < 448 / 2; i += THREADS) {
+    s_tot[2 * i] = (i == tid && tid < kHistPairs && bin0 < kNumBins) ? tot0 : 0u;
+    s_tot[2 * i + 1] = (i == tid && tid < kHistPairs && bin1 < kNumBins) ? tot1 : 0u;
   }
-  if (THREADS < 448)
-    for (int bin = NB * THREADS + tid; bin < 448; bin += THREADS) s_tot[bin] = 0u;
   if (tid == 0) {
     s_ltb = 0u;
     s_eqb = 0u;
@@ -319,11 +306,9 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
 
   if (gridDim.x > 1) {  // tokens of earlier segments: #{D < T} and #{D == T}
     uint32_t ltb = 0, eqb = 0;
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-      const int bin = tid + nb * THREADS;
-      ltb += bin < T ? pre[nb] : 0u;
-      eqb += bin == T ? pre[nb] : 0u;
+    if (tid < kHistPairs) {
+      ltb = (bin0 < T ? pre0 : 0u) + (bin1 < T ? pre1 : 0u);
+      eqb = (bin0 == T ? pre0 : 0u) + (bin1 == T ? pre1 : 0u);
     }
     ltb = wave_sum_u32(ltb);
     eqb = wave_sum_u32(eqb);
