@@ -68,6 +68,10 @@ Plan make_plan(const adamas_config* c, int32_t batch, int64_t max_seq_len, int32
       break;
     }
   }
+  // Half-size workgroups balance better over the compute units (measured 0.4 us
+  // on a 32 MiB plane) as long as a head keeps at most one batch of tile
+  // histograms for the select kernel to read.
+  if (pl.tile_tokens == 4096 && (max_seq_len + 2047) / 2048 <= kHistBatch) pl.tile_tokens = 2048;
   pl.n_tiles = (int)((max_seq_len + pl.tile_tokens - 1) / pl.tile_tokens);
   // Select + attention: a head is cut into segments, one workgroup each (a
   // single compute unit is too slow to compact a whole 32K-token head or to
