@@ -172,7 +172,7 @@ int adamas_encode_keys(const adamas_config* cfg, const void* K, void* codes, int
   if (n_rows == 0) return ADAMAS_OK;
   clear_stale_error();
   const int64_t n_vec = n_rows * cfg->num_kv_heads;
-  const int64_t want = (n_vec + 3) / 4;
+  const int64_t want = (n_vec + 63) / 64;  // 64 vectors per 256-thread workgroup
   const int grid = (int)(want < 16384 ? want : 16384);
   hipLaunchKernelGGL(encode_rows_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream,
                      static_cast<const uint16_t*>(K), static_cast<uint8_t*>(codes),
@@ -187,7 +187,7 @@ int adamas_encode_query(const adamas_config* cfg, const void* q, void* qcodes, i
   if (!aligned16(q) || !aligned16(qcodes)) return ADAMAS_ERR_BAD_ARG;
   clear_stale_error();
   const int64_t n_vec = (int64_t)batch * cfg->num_q_heads;
-  const int64_t want = (n_vec + 3) / 4;
+  const int64_t want = (n_vec + 63) / 64;
   const int grid = (int)(want < 16384 ? want : 16384);
   // queries form one "head" of n_vec consecutive rows
   hipLaunchKernelGGL(encode_rows_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream,

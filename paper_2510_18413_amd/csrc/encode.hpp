@@ -67,23 +67,102 @@ __device__ __forceinline__ void store_row_wave(uint8_t* __restrict__ dst, const 
   }
 }
 
-// Bulk encode: vector v of n_vec = n_heads * n_rows lives at
+// ---- bulk encode: four lanes per vector -----------------------------------
+//
+// Lane j of a quad holds elements 32j .. 32j+31 of one vector as doubles, so
+// five of the seven butterfly stages are register-to-register and only index
+// bits 5 and 6 cross lanes (DPP quad permutes).  After the transform lane j
+// holds coefficients 32j .. 32j+31, which is exactly word j of the packed row:
+// every lane assembles and stores its own 8 bytes.  A wave encodes 16 vectors
+// and moves 4 KiB in, 512 B out, both contiguous.  All sums are fp64 and exact
+// under the documented exponent spread, hence identical to the wave-per-vector
+// routine above whatever the order.
+
+__device__ __forceinline__ double dpp_quad_xor_f64(double v, bool xor2) {
+  const uint64_t bits = __builtin_bit_cast(uint64_t, v);
+  const int lo = (int)(uint32_t)bits, hi = (int)(uint32_t)(bits >> 32);
+  int plo, phi;
+  if (xor2) {
+    plo = __builtin_amdgcn_update_dpp(0, lo, kDppQuadXor2, 0xf, 0xf, false);
+    phi = __builtin_amdgcn_update_dpp(0, hi, kDppQuadXor2, 0xf, 0xf, false);
+  } else {
+    plo = __builtin_amdgcn_update_dpp(0, lo, kDppQuadXor1, 0xf, 0xf, false);
+    phi = __builtin_amdgcn_update_dpp(0, hi, kDppQuadXor1, 0xf, 0xf, false);
+  }
+  return __builtin_bit_cast(double, ((uint64_t)(uint32_t)phi << 32) | (uint32_t)plo);
+}
+
+// Appends the sign bit of (tau - y) -- set exactly when y > tau -- to a mask
+// that is shifted left once per call: elements must be fed from 31 down to 0.
+__device__ __forceinline__ uint32_t push_greater(uint32_t mask, double y, double tau) {
+  const double d = tau - y;  // +0 when equal: not greater
+  const uint32_t hi = (uint32_t)(__builtin_bit_cast(uint64_t, d) >> 32);
+  return __builtin_amdgcn_alignbit(mask, hi, 31);  // (mask << 1) | (hi >> 31)
+}
+
+// Vector v of n_vec = n_heads * n_rows lives at
 // src + (head * head_stride_rows + row_begin + r) * 128, head = v / n_rows,
 // r = v % n_rows; its code row goes to the same row of dst (32 B rows).
-// One wave per vector, grid-stride.
 __global__ __launch_bounds__(256) void encode_rows_kernel(const uint16_t* __restrict__ src,
                                                           uint8_t* __restrict__ dst,
                                                           int64_t head_stride_rows,
                                                           int64_t row_begin, int64_t n_rows,
                                                           int64_t n_vec, Thresholds thr) {
-  const int64_t wave_global = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-  const int64_t n_waves = (int64_t)gridDim.x * 4;
-  for (int64_t v = wave_global; v < n_vec; v += n_waves) {
+  const int j = threadIdx.x & 3;  // which 32-element quarter of the vector
+  const int64_t quad = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 2;
+  const int64_t n_quads = ((int64_t)gridDim.x * blockDim.x) >> 2;
+  for (int64_t v = quad; v < n_vec; v += n_quads) {
     const int64_t head = v / n_rows, r = v - head * n_rows;
     const int64_t row = head * head_stride_rows + row_begin + r;
-    uint64_t w[4];
-    encode_vector_wave(src + row * kHeadDim, thr, w);
-    store_row_wave(dst + row * kRowBytes, w);
+    const uint4* in = reinterpret_cast<const uint4*>(src + row * kHeadDim + j * 32);
+    uint4 raw[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) raw[i] = in[i];
+    double x[32];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const uint32_t w[4] = {raw[i].x, raw[i].y, raw[i].z, raw[i].w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        x[i * 8 + 2 * e] = (double)bf16_lo(w[e]);
+        x[i * 8 + 2 * e + 1] = (double)bf16_hi(w[e]);
+      }
+    }
+    // index bits 0..4: inside the lane
+#pragma unroll
+    for (int h = 1; h < 32; h <<= 1) {
+#pragma unroll
+      for (int i = 0; i < 32; ++i) {
+        if ((i & h) == 0) {
+          const double a = x[i], b = x[i + h];
+          x[i] = a + b;
+          x[i + h] = a - b;
+        }
+      }
+    }
+    // index bits 5 and 6: across the quad
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+      const bool upper = ((j >> s) & 1) != 0;
+#pragma unroll
+      for (int i = 0; i < 32; ++i) {
+        const double partner = dpp_quad_xor_f64(x[i], s == 1);
+        x[i] = upper ? partner - x[i] : x[i] + partner;
+      }
+    }
+    // Eq. 5 on the lane's 32 coefficients: nested indicator masks m1 >= m2 >= m3,
+    // code = m1 + m2 + m3, low bit = parity, high bit = m2.
+    uint32_t m1 = 0, m2 = 0, m3 = 0;
+#pragma unroll
+    for (int i = 31; i >= 0; --i) {
+      m1 = push_greater(m1, x[i], thr.tau[0]);
+      m2 = push_greater(m2, x[i], thr.tau[1]);
+      m3 = push_greater(m3, x[i], thr.tau[2]);
+    }
+    uint2 word;
+    word.x = m1 ^ m2 ^ m3;
+    word.y = m2;
+    *reinterpret_cast<uint2*>(dst + row * kRowBytes + j * 8) = word;
   }
 }
 
