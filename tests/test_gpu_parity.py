@@ -263,3 +263,42 @@ def test_invalid_device_lengths_are_treated_as_empty(H, oracle):
     case.seq_len[1] = 0
     ref = H.oracle_step(case, 16, want_dist=False)
     assert np.array_equal(idx[0], ref["idx"][0])
+
+
+def test_decode_step_random_shapes(H, oracle):
+    """Seeded sweep over batch, group size, lengths, budgets, thresholds, scale and append:
+    every case against the oracle."""
+    import paper_2510_18413_amd as A
+    rng = np.random.default_rng(20251018)
+    for case_no in range(24):
+        Hkv = int(rng.choice([1, 2, 3]))
+        G = int(rng.choice([1, 2, 3, 4, 5, 6, 7, 8]))
+        B = int(rng.integers(1, 4))
+        lens = [int(x) for x in rng.choice([0, 1, 2, 63, 64, 65, 255, 1000, 4095, 4096, 4097, 9001,
+                                            12345], size=B)]
+        k = int(rng.choice([1, 2, 31, 64, 100, 256, 1000, 4096]))
+        append = bool(rng.integers(0, 2))
+        case = small_case(7000 + case_no, B, Hkv * G, Hkv, lens, append=append)
+        if case_no % 3 == 0:       # coarse keys: few distinct code rows, ties everywhere
+            for h in range(Hkv):
+                rows = case.K[h, :8].copy()
+                pick = rng.integers(0, 8, size=case.K.shape[1])
+                case.K[h] = rows[pick]
+        thr = [(-1.0, 0.0, 1.0), (-0.3, 0.4, 2.5), (-2.0, -1.0, -0.5)][case_no % 3]
+        case.thresholds = thr
+        scale = [0.0, 0.05, 0.2][case_no % 3]
+        d = H.DeviceCase(case, k)
+        d.cfg = A.Config.make(case.Hq, case.Hkv, case.pool_tokens, thr_k=thr, sm_scale=scale)
+        A.adamas_encode_keys(d.cfg, d.K, d.codes, 0, case.pool_tokens)
+        out, idx = d.decode_step()
+        K, V = case.K.copy(), case.V.copy()
+        _, rows = oracle.encode(K, thr)
+        ref_out, ref_idx, _ = oracle.decode_step(case.q, K, V, rows, case.seq_start, case.seq_len, k,
+                                                 thr, thr, scale if scale > 0 else H.SM_SCALE,
+                                                 k_new=case.k_new, v_new=case.v_new)
+        tag = "case %d: B=%d Hkv=%d G=%d lens=%s k=%d append=%s" % (case_no, B, Hkv, G, lens, k, append)
+        assert np.array_equal(idx, ref_idx), tag
+        assert H.attn_rel_err(out, ref_out) <= H.ATTN_TOL, tag
+        if append:
+            assert np.array_equal(d.codes.cpu().numpy(), rows), tag
+            assert np.array_equal(H.host_u16(d.K), K), tag
