@@ -174,15 +174,24 @@ __global__ __launch_bounds__(1024) void scan_kernel(const ScanParams p) {
     }
   }
 
-  // The query planes are wave-uniform: keep them in scalar registers.
+  // The query planes are wave-uniform.  Small groups keep them in vector
+  // registers (a VALU instruction takes one scalar operand only, so scalar
+  // planes cost an extra move per word); large groups keep them scalar to stay
+  // within the register budget of a 1024-thread workgroup.
   uint32_t qlo[G][4], qhi[G][4], qg[G][4];
 #pragma unroll
   for (int g = 0; g < G; ++g) {
 #pragma unroll
     for (int wd = 0; wd < 4; ++wd) {
-      qlo[g][wd] = __builtin_amdgcn_readfirstlane(s_q[g][wd]);
-      qhi[g][wd] = __builtin_amdgcn_readfirstlane(s_q[g][4 + wd]);
-      qg[g][wd] = __builtin_amdgcn_readfirstlane(s_q[g][8 + wd]);
+      if constexpr (G <= 4) {
+        qlo[g][wd] = s_q[g][wd];
+        qhi[g][wd] = s_q[g][4 + wd];
+        qg[g][wd] = s_q[g][8 + wd];
+      } else {
+        qlo[g][wd] = __builtin_amdgcn_readfirstlane(s_q[g][wd]);
+        qhi[g][wd] = __builtin_amdgcn_readfirstlane(s_q[g][4 + wd]);
+        qg[g][wd] = __builtin_amdgcn_readfirstlane(s_q[g][8 + wd]);
+      }
     }
   }
   uint32_t* hist_lane = &s_hist[0][lane & (kHistReplicas - 1)][0];
