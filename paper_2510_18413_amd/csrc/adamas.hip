@@ -370,6 +370,9 @@ int adamas_decode_step_stages(const adamas_config* cfg, const void* q, const voi
   sp.n_tiles = pl.n_tiles;
   sp.thr_q = scaled(cfg->thr_q);
   sp.thr_k = scaled(cfg->thr_k);
+  // segment counters live in the unused words of each head's first partial slot
+  sp.arrivals = reinterpret_cast<uint32_t*>(ws_at(workspace, pl.off_partial)) + 2;
+  sp.arrivals_stride = (int64_t)kMaxParts * kPartialStride;
   if (stages & ADAMAS_STAGE_SCAN) {
     launch_scan<true>(cfg->num_q_heads / cfg->num_kv_heads,
                       dim3(pl.n_tiles, cfg->num_kv_heads, batch),
@@ -390,6 +393,8 @@ int adamas_decode_step_stages(const adamas_config* cfg, const void* q, const voi
   sl.V = sp.V;
   sl.out = out;
   sl.partial = reinterpret_cast<float*>(ws_at(workspace, pl.off_partial));
+  sl.arrivals = (stages & ADAMAS_STAGE_SCAN) ? sp.arrivals : nullptr;
+  sl.arrivals_stride = sp.arrivals_stride;
   sl.pool_tokens = cfg->pool_tokens;
   sl.max_seq_len = max_seq_len;
   sl.Hq = cfg->num_q_heads;
@@ -402,7 +407,7 @@ int adamas_decode_step_stages(const adamas_config* cfg, const void* q, const voi
   hipLaunchKernelGGL((select_kernel<kSelThreads, true>), dim3(pl.n_segs, cfg->num_q_heads, batch),
                      dim3(kSelThreads), 0, st, sl);
   if (int rc = launch_status()) return rc;
-  if (pl.n_segs == 1) return ADAMAS_OK;  // the select workgroup wrote `out` itself
+  if (pl.n_segs == 1 || sl.arrivals != nullptr) return ADAMAS_OK;  // the select kernel wrote `out` itself
   MergeParams mp{};
   mp.partial = sl.partial;
   mp.out = out;

@@ -44,6 +44,8 @@ struct ScanParams {
   uint16_t* dist_user;       // optional second copy, [B*Hq][dist_user_stride]
   int64_t dist_user_stride;
   uint16_t* tilehist;        // [B*Hq][n_tiles][kHistStride]; may be null
+  uint32_t* arrivals;        // per-head counter at [head * arrivals_stride], zeroed here; may be null
+  int64_t arrivals_stride;
   int64_t pool_tokens, max_seq_len;
   int32_t Hq, Hkv, n_tiles;
   Thresholds thr_q, thr_k;
@@ -261,6 +263,9 @@ __global__ __launch_bounds__(1024) void scan_kernel(const ScanParams p) {
     reinterpret_cast<uint32_t*>(p.V + row * kHeadDim)[lane] =
         reinterpret_cast<const uint32_t*>(p.v_new + src)[lane];
   }
+  // The select kernel counts its finished segments per head from zero.
+  if (p.arrivals != nullptr && tile_id == 0 && tid < G)
+    p.arrivals[(int64_t)(head0 + tid) * p.arrivals_stride] = 0u;
   if (p.tilehist != nullptr) {
     __syncthreads();
     for (int i = tid; i < G * kNumBins; i += blockDim.x) {

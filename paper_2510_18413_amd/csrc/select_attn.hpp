@@ -12,11 +12,15 @@
 //
 // One workgroup (256 threads) owns one segment of one (sequence, query head).
 // With attention enabled it then gathers the K, V rows it selected, runs a
-// one-pass online softmax over them (16 lanes per row, 8 dims per lane, fp32),
-// stores an (m, l, o[128]) partial; a small follow-up kernel merges the
-// partials of a head in segment order into the output.  (A merge inside the
-// same kernel would need device-scope fences, which on this part cost far more
-// than a kernel boundary: each one walks the XCD's whole L2.)
+// one-pass online softmax over them (16 lanes per row, 8 dims per lane, fp32)
+// and leaves an (m, l, o[128]) partial.  Inside the fused step the partials of
+// a head are combined, in segment order, by whichever of its workgroups
+// finishes last (a per-head arrival counter that the scan kernel zeroed).
+// Partials and counter are exchanged through device-scope atomic stores, loads
+// and one fetch-add, which are coherent across the chip by themselves, so no
+// device-scope fence is needed (on this part such a fence walks the XCD's whole
+// L2 and costs more than a kernel boundary).  Without a zeroed counter (staged
+// calls, stand-alone attention) a small follow-up kernel does the same merge.
 #pragma once
 
 #include "device_utils.hpp"
@@ -42,6 +46,8 @@ struct SelectParams {
   const uint16_t* V;
   float* out;                 // [B*Hq][128]
   float* partial;             // [B*Hq][kMaxParts][kPartialStride]
+  uint32_t* arrivals;         // per-head counter of finished segments, zero on entry; null: no in-kernel merge
+  int64_t arrivals_stride;
   int64_t pool_tokens, max_seq_len;
   int32_t Hq, Hkv, k;
   int32_t n_tiles, tile_tokens, seg_len;
@@ -188,9 +194,10 @@ __device__ __forceinline__ void attention_rows(const int32_t* s_sel, int n, int 
   }
 }
 
-// Grid (n_segs, Hq, B).  With a single segment per head and ATTN the
-// workgroup finishes the head and writes `out`; otherwise it leaves an
-// (M, lsum, o[128]) partial for merge_kernel.
+// Grid (n_segs, Hq, B).  With ATTN a head that has a single segment with
+// tokens is finished by that workgroup; otherwise each workgroup leaves an
+// (M, lsum, o[128]) partial, merged by the last one to arrive (p.arrivals set)
+// or by merge_kernel (p.arrivals null).
 template <int THREADS, bool ATTN>
 __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
   static_assert(THREADS >= kHistPairs, "one thread per pair of histogram bins");
@@ -387,18 +394,66 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
     float M, lsum, o;
     attention_rows<THREADS>(s_sel, n_sel, L, p.q + head * kHeadDim, p.K + row0, p.V + row0,
                             p.scale_log2e, s_attn, M, lsum, o);
+    if (gridDim.x == 1 || (p.arrivals != nullptr && n_active == 1)) {
+      if (tid < kHeadDim) p.out[head * kHeadDim + tid] = lsum > 0.f ? o / lsum : 0.f;
+      return;
+    }
+    float* mine = p.partial + (head * kMaxParts + seg) * kPartialStride;
+    if (p.arrivals == nullptr) {
       if (tid < kHeadDim) {
-      if (gridDim.x == 1) {
-        p.out[head * kHeadDim + tid] = lsum > 0.f ? o / lsum : 0.f;
-      } else {
-        float* mine = p.partial + (head * kMaxParts + seg) * kPartialStride;
         if (tid == 0) {
           mine[0] = M;
           mine[1] = lsum;
         }
         mine[4 + tid] = o;
       }
+      return;
     }
+    // Merge by the last segment to finish.  Everything exchanged between
+    // workgroups goes through device-scope atomic accesses, which are coherent
+    // by themselves: no cache write-back or invalidate is needed, only that a
+    // workgroup's stores have been acknowledged before it counts itself, and
+    // that the merging workgroup loads after its fetch-add has returned.  The
+    // arithmetic and its order are merge_kernel's: both give the same bits.
+    if (tid < kHeadDim) {
+      if (tid == 0) {
+        __hip_atomic_store(mine + 0, M, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(mine + 1, lsum, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+      __hip_atomic_store(mine + 4 + tid, o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_waitcnt(0);  // this wave's stores are acknowledged
+    __syncthreads();
+    if (tid == 0) {
+      const uint32_t before = __hip_atomic_fetch_add(p.arrivals + head * p.arrivals_stride, 1u,
+                                                     __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      s_T = before + 1u == (uint32_t)n_active ? 1 : 0;
+    }
+    __syncthreads();
+    if (s_T == 0 || tid >= kHeadDim) return;
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    const float* ph = p.partial + head * kMaxParts * kPartialStride;
+    float pm[kMaxParts], pl[kMaxParts], po[kMaxParts];
+#pragma unroll
+    for (int s = 0; s < kMaxParts; ++s) {
+      const float* ps = ph + (int64_t)min(s, n_active - 1) * kPartialStride;
+      pm[s] = __hip_atomic_load(ps + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      pl[s] = __hip_atomic_load(ps + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      po[s] = __hip_atomic_load(ps + 4 + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    float Mh = kNegBig;
+#pragma unroll
+    for (int s = 0; s < kMaxParts; ++s) Mh = fmaxf(Mh, s < n_active ? pm[s] : kNegBig);
+    float lh = 0.f, oh = 0.f;
+#pragma unroll
+    for (int s = 0; s < kMaxParts; ++s) {
+      const bool use = s < n_active;
+      const float w = use ? exp2f(pm[s] - Mh) : 0.f;
+      lh = fmaf(use ? pl[s] : 0.f, w, lh);
+      oh = fmaf(use ? po[s] : 0.f, w, oh);
+    }
+    p.out[head * kHeadDim + tid] = lh > 0.f ? oh / lh : 0.f;
   }
 }
 

@@ -244,6 +244,38 @@ def test_decode_step_repeatable_and_workspace_reusable(H, oracle):
         assert np.array_equal(first[0], again[0]) and np.array_equal(first[1], again[1])
 
 
+def test_decode_step_back_to_back_on_one_workspace(H, oracle):
+    """Different inputs alternate on ONE workspace with no host synchronisation between the
+    calls.  The one-call step combines the segments' attention partials inside the select
+    kernel (last segment to finish, device-scope atomics only); the staged call uses the
+    separate merge kernel.  Both must give the same bits every time, and the oracle's answer."""
+    import paper_2510_18413_amd as A
+    cases = [small_case(610 + i, 2, 16, 4, [30000, 9000 + 4000 * i]) for i in range(2)]
+    devs = [H.DeviceCase(c, 256) for c in cases]
+    shared = devs[0].workspace
+    assert devs[1].workspace.numel() == shared.numel()
+    want = []
+    for d in devs:        # scan, then select + merge kernel, as two calls
+        for stages in (A.STAGE_SCAN, A.STAGE_SELECT_ATTN):
+            A.adamas_decode_step_stages(d.cfg, d.q, d.K, d.V, d.codes, d.seq_start, d.seq_len, d.k,
+                                        d.out, d.max_len, shared, idx_out=d.idx, stages=stages)
+        torch.cuda.synchronize()
+        want.append(d.out.clone())
+        ref = H.oracle_step(d.case, d.k, want_dist=False)
+        assert np.array_equal(d.idx.cpu().numpy(), ref["idx"])
+        assert H.attn_rel_err(d.out.cpu().numpy(), ref["out"]) <= H.ATTN_TOL
+    got = []
+    for it in range(48):
+        d = devs[it % 2]
+        d.out.fill_(float("nan"))
+        A.adamas_decode_step(d.cfg, d.q, d.K, d.V, d.codes, d.seq_start, d.seq_len, d.k, d.out,
+                             d.max_len, shared)
+        got.append(d.out.clone())
+    torch.cuda.synchronize()
+    for it, g in enumerate(got):
+        assert torch.equal(g, want[it % 2]), f"call {it}"
+
+
 def test_appended_token_is_a_candidate(H, oracle):
     case = small_case(602, 1, 2, 2, [4097], append=True)     # new token alone in the 2nd segment
     case.q[0, 0] = case.k_new[0, 0]
