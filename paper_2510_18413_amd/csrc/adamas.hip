@@ -61,22 +61,29 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 Plan make_plan(const adamas_config* c, int32_t batch, int64_t max_seq_len, int32_t k) {
   Plan pl{};
   const int64_t planes = (int64_t)batch * c->num_kv_heads;
-  pl.tile_tokens = 1024;
-  for (int tile : {4096, 2048}) {
-    if (planes * ((max_seq_len + tile - 1) / tile) >= kTargetWorkgroups) {
-      pl.tile_tokens = tile;
-      break;
-    }
+  // Scan tile (measured on MI355X): large tiles amortise the per-workgroup
+  // prologue and leave the select kernel fewer tile histograms to read, small
+  // ones fit more workgroups on a compute unit.
+  auto n_wg = [&](int tile) { return planes * ((max_seq_len + tile - 1) / tile); };
+  if (n_wg(4096) >= 4 * kTargetWorkgroups) {
+    // many rounds of workgroups per compute unit: residency matters most
+    pl.tile_tokens = 1024;
+  } else if (n_wg(4096) >= kTargetWorkgroups) {
+    // Half-size workgroups balance better over the compute units (0.4 us on a
+    // 32 MiB plane) as long as a head keeps at most one batch of tile
+    // histograms for the select kernel to read.
+    pl.tile_tokens = (max_seq_len + 2047) / 2048 <= kHistBatch ? 2048 : 4096;
+  } else if (n_wg(2048) >= kTargetWorkgroups / 2) {
+    pl.tile_tokens = 2048;
+  } else {
+    pl.tile_tokens = 1024;
   }
-  // Half-size workgroups balance better over the compute units (measured 0.4 us
-  // on a 32 MiB plane) as long as a head keeps at most one batch of tile
-  // histograms for the select kernel to read.
-  if (pl.tile_tokens == 4096 && (max_seq_len + 2047) / 2048 <= kHistBatch) pl.tile_tokens = 2048;
   pl.n_tiles = (int)((max_seq_len + pl.tile_tokens - 1) / pl.tile_tokens);
   // Select + attention: a head is cut into segments, one workgroup each (a
   // single compute unit is too slow to compact a whole 32K-token head or to
-  // gather all of its rows), and a merge kernel combines the segments'
-  // attention partials.  With many heads in flight there is parallelism enough
+  // gather all of its rows), and the segments' attention partials are merged
+  // afterwards (by the last segment to finish, or by the merge kernel in staged
+  // calls).  With many heads in flight there is parallelism enough
   // already: fewer segments mean fewer re-reads of the head's histograms, and a
   // head that fits one segment needs no merge at all.
   const int64_t n_heads = (int64_t)batch * c->num_q_heads;
@@ -124,17 +131,28 @@ int launch_status() {
   return ADAMAS_OK;
 }
 
+template <int G, bool FUSED>
+void launch_scan_g(const Plan& pl, dim3 grid, hipStream_t st, const ScanParams& sp) {
+  switch (pl.tile_tokens) {
+    case 1024: hipLaunchKernelGGL((scan_kernel<G, FUSED, 4>), grid, dim3(256), 0, st, sp); break;
+    case 2048: hipLaunchKernelGGL((scan_kernel<G, FUSED, 8>), grid, dim3(512), 0, st, sp); break;
+    default: hipLaunchKernelGGL((scan_kernel<G, FUSED, 16>), grid, dim3(1024), 0, st, sp); break;
+  }
+}
+
+// pl.tile_tokens is 1024, 2048 or 4096 (make_plan).
 template <bool FUSED>
-void launch_scan(int G, dim3 grid, dim3 block, hipStream_t st, const ScanParams& sp) {
+void launch_scan(int G, const Plan& pl, int Hkv, int batch, hipStream_t st, const ScanParams& sp) {
+  const dim3 grid(pl.n_tiles, Hkv, batch);
   switch (G) {
-    case 1: hipLaunchKernelGGL((scan_kernel<1, FUSED>), grid, block, 0, st, sp); break;
-    case 2: hipLaunchKernelGGL((scan_kernel<2, FUSED>), grid, block, 0, st, sp); break;
-    case 3: hipLaunchKernelGGL((scan_kernel<3, FUSED>), grid, block, 0, st, sp); break;
-    case 4: hipLaunchKernelGGL((scan_kernel<4, FUSED>), grid, block, 0, st, sp); break;
-    case 5: hipLaunchKernelGGL((scan_kernel<5, FUSED>), grid, block, 0, st, sp); break;
-    case 6: hipLaunchKernelGGL((scan_kernel<6, FUSED>), grid, block, 0, st, sp); break;
-    case 7: hipLaunchKernelGGL((scan_kernel<7, FUSED>), grid, block, 0, st, sp); break;
-    default: hipLaunchKernelGGL((scan_kernel<8, FUSED>), grid, block, 0, st, sp); break;
+    case 1: launch_scan_g<1, FUSED>(pl, grid, st, sp); break;
+    case 2: launch_scan_g<2, FUSED>(pl, grid, st, sp); break;
+    case 3: launch_scan_g<3, FUSED>(pl, grid, st, sp); break;
+    case 4: launch_scan_g<4, FUSED>(pl, grid, st, sp); break;
+    case 5: launch_scan_g<5, FUSED>(pl, grid, st, sp); break;
+    case 6: launch_scan_g<6, FUSED>(pl, grid, st, sp); break;
+    case 7: launch_scan_g<7, FUSED>(pl, grid, st, sp); break;
+    default: launch_scan_g<8, FUSED>(pl, grid, st, sp); break;
   }
 }
 
@@ -217,8 +235,8 @@ int adamas_manhattan_distance(const adamas_config* cfg, const void* qcodes, cons
   sp.Hq = cfg->num_q_heads;
   sp.Hkv = cfg->num_kv_heads;
   sp.n_tiles = pl.n_tiles;
-  launch_scan<false>(cfg->num_q_heads / cfg->num_kv_heads, dim3(pl.n_tiles, cfg->num_kv_heads, batch),
-                     dim3(pl.tile_tokens / kScanTokPerThread), (hipStream_t)stream, sp);
+  launch_scan<false>(cfg->num_q_heads / cfg->num_kv_heads, pl, cfg->num_kv_heads, batch,
+                     (hipStream_t)stream, sp);
   return launch_status();
 }
 
@@ -251,8 +269,7 @@ int adamas_select_topk(const adamas_config* cfg, const void* qcodes, const void*
   sp.Hq = cfg->num_q_heads;
   sp.Hkv = cfg->num_kv_heads;
   sp.n_tiles = pl.n_tiles;
-  launch_scan<false>(cfg->num_q_heads / cfg->num_kv_heads, dim3(pl.n_tiles, cfg->num_kv_heads, batch),
-                     dim3(pl.tile_tokens / kScanTokPerThread), st, sp);
+  launch_scan<false>(cfg->num_q_heads / cfg->num_kv_heads, pl, cfg->num_kv_heads, batch, st, sp);
   if (int rc = launch_status()) return rc;
 
   SelectParams sl{};
@@ -374,9 +391,7 @@ int adamas_decode_step_stages(const adamas_config* cfg, const void* q, const voi
   sp.arrivals = reinterpret_cast<uint32_t*>(ws_at(workspace, pl.off_partial)) + 2;
   sp.arrivals_stride = (int64_t)kMaxParts * kPartialStride;
   if (stages & ADAMAS_STAGE_SCAN) {
-    launch_scan<true>(cfg->num_q_heads / cfg->num_kv_heads,
-                      dim3(pl.n_tiles, cfg->num_kv_heads, batch),
-                      dim3(pl.tile_tokens / kScanTokPerThread), st, sp);
+    launch_scan<true>(cfg->num_q_heads / cfg->num_kv_heads, pl, cfg->num_kv_heads, batch, st, sp);
     if (int rc = launch_status()) return rc;
   }
   if (!(stages & ADAMAS_STAGE_SELECT_ATTN)) return ADAMAS_OK;

@@ -25,8 +25,7 @@
 namespace adamas {
 
 constexpr int kScanTokPerThread = 4;
-constexpr int kMaxScanWaves = 16;
-constexpr int kHistReplicas = 4;  // LDS histogram copies, picked by lane, to thin out same-address atomics
+constexpr int kHistReplicas = 2;  // LDS histogram copies, picked by lane, to thin out same-address atomics
 
 struct ScanParams {
   const uint8_t* codes;      // [Hkv][pool][32]
@@ -51,29 +50,52 @@ struct ScanParams {
   Thresholds thr_q, thr_k;
 };
 
-template <int G, bool FUSED>
-__global__ __launch_bounds__(1024) void scan_kernel(const ScanParams p) {
+// WAVES = wavefronts per workgroup (4, 8 or 16): the tile is WAVES * 256 tokens.
+template <int G, bool FUSED, int WAVES>
+__global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p) {
   __shared__ uint32_t s_hist[G][kHistReplicas][kNumBins];
   __shared__ uint32_t s_q[G][12];   // per query head: lo[4], hi[4], lo^hi[4]
   __shared__ uint32_t s_new[8];     // code row of the appended key
   __shared__ uint32_t s_ready;      // query / new-key code rows published so far
   // per wave: its 256 distances per query head, in token order, for wide stores
-  __shared__ uint16_t s_dt[kMaxScanWaves][G][kScanTokPerThread * kWave];
+  __shared__ uint16_t s_dt[WAVES][G][kScanTokPerThread * kWave];
 
   const int tile_id = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nwaves = blockDim.x >> 6;
-  const int tile_tokens = blockDim.x * kScanTokPerThread;
-  const int L = safe_seq_len(p.seq_len, p.seq_start, b, p.max_seq_len, p.pool_tokens);
-  const int64_t start = p.seq_start[b];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  constexpr int nthreads = WAVES * kWave;
+  constexpr int tile_tokens = nthreads * kScanTokPerThread;
   const int t0 = tile_id * tile_tokens;
   const int head0 = b * p.Hq + kvh * G;
 
+  // First of all the encoding waves request their vectors (G queries and, if
+  // the call appends, the new key): their addresses need nothing from memory,
+  // so these loads travel together with the scalar loads of the sequence
+  // length and start below.  Only the encoding waves load: inside a compute
+  // unit requests are served in order across waves, so a needless load here
+  // would sit in front of other waves' rows.
+  constexpr int kEncRounds = (G + 1 + WAVES - 1) / WAVES;  // G queries + 1 new key over the waves
+  uint32_t enc_lo[kEncRounds], enc_hi[kEncRounds];
+#pragma unroll
+  for (int r = 0; r < kEncRounds; ++r) {
+    const int v = wave + r * WAVES;
+    enc_lo[r] = enc_hi[r] = 0;
+    if (FUSED && (v < G || (v == G && p.k_new != nullptr))) {
+      const uint16_t* src = v < G ? p.q + (int64_t)(head0 + v) * kHeadDim
+                                  : p.k_new + ((int64_t)b * p.Hkv + kvh) * kHeadDim;
+      enc_lo[r] = src[lane];
+      enc_hi[r] = src[lane + 64];
+    }
+  }
+
+  const int L = safe_seq_len(p.seq_len, p.seq_start, b, p.max_seq_len, p.pool_tokens);
+  const int64_t start = p.seq_start[b];
+
   // The only workgroup barrier before the scan sits here, where every wave has
-  // just started (and while the sequence length is still on its way).  Later
-  // on the waves must not wait for each other: a compute unit serves memory
+  // just started (and while the loads above are still on their way).  Later on
+  // the waves must not wait for each other: a compute unit serves memory
   // requests in order, so late waves get their rows late, and a barrier after
-  // the loads would hold the early waves back with them.
-  for (int i = tid; i < G * kHistReplicas * kNumBins; i += blockDim.x)
+  // the row loads would hold the early waves back with them.
+  for (int i = tid; i < G * kHistReplicas * kNumBins; i += nthreads)
     (&s_hist[0][0][0])[i] = 0u;
   if (tid == 0) s_ready = 0u;
   __syncthreads();
@@ -81,27 +103,11 @@ __global__ __launch_bounds__(1024) void scan_kernel(const ScanParams p) {
   if (t0 >= L) return;  // whole workgroup
 
   // Order of the memory operations matters: loads return in issue order, so a
-  // wave that waits for its query vector also waits for everything it issued
-  // before.  The (tiny) vector loads of the encoding waves therefore go first,
-  // then the code rows, which are consumed one token at a time as they arrive.
+  // wave that waits for one load also waits for everything it issued before.
+  // The code rows are requested next and consumed one token at a time as they
+  // arrive; the encode runs while they travel.
   const bool appending = FUSED && p.k_new != nullptr && (L - 1) / tile_tokens == tile_id;
   const int n_enc = FUSED ? G + (appending ? 1 : 0) : 0;
-  constexpr int kEncRounds = (G + 1 + 3) / 4;  // G queries + 1 new key over at least 4 waves
-  uint32_t enc_lo[kEncRounds], enc_hi[kEncRounds];
-#pragma unroll
-  for (int r = 0; r < kEncRounds; ++r) {
-    // Only the encoding waves load: inside a compute unit requests are served
-    // in order across waves, so a needless load here would hold a late wave
-    // (and with it the workgroup barrier) behind every earlier wave's rows.
-    const int v = wave + r * nwaves;
-    enc_lo[r] = enc_hi[r] = 0;
-    if (FUSED && v < n_enc) {
-      const uint16_t* src = v < G ? p.q + (int64_t)(head0 + v) * kHeadDim
-                                  : p.k_new + ((int64_t)b * p.Hkv + kvh) * kHeadDim;
-      enc_lo[r] = src[lane];
-      enc_hi[r] = src[lane + 64];
-    }
-  }
   uint32_t qraw_lo = 0, qraw_hi = 0;
   if (!FUSED && wave == 0) {
     const int i = min(tid, G * 4 - 1);
@@ -134,7 +140,7 @@ __global__ __launch_bounds__(1024) void scan_kernel(const ScanParams p) {
   if (FUSED) {
 #pragma unroll
     for (int r = 0; r < kEncRounds; ++r) {
-      const int v = wave + r * nwaves;
+      const int v = wave + r * WAVES;
       if (v < n_enc) {
         uint64_t w[4];
         encode_values_wave(enc_lo[r], enc_hi[r], v < G ? p.thr_q : p.thr_k, w);
@@ -268,12 +274,18 @@ __global__ __launch_bounds__(1024) void scan_kernel(const ScanParams p) {
     p.arrivals[(int64_t)(head0 + tid) * p.arrivals_stride] = 0u;
   if (p.tilehist != nullptr) {
     __syncthreads();
-    for (int i = tid; i < G * kNumBins; i += blockDim.x) {
-      const int g = i / kNumBins, bin = i - g * kNumBins;
-      uint32_t s = 0;
+    // two 16-bit bins per 32-bit store; bins kNumBins.. of a stored row stay unwritten
+    constexpr int kPairs = (kNumBins + 1) / 2;
+    for (int i = tid; i < G * kPairs; i += nthreads) {
+      const int g = i / kPairs, pr = i - g * kPairs;
+      uint32_t lo = 0, hi = 0;
 #pragma unroll
-      for (int r = 0; r < kHistReplicas; ++r) s += s_hist[g][r][bin];
-      p.tilehist[((int64_t)(head0 + g) * p.n_tiles + tile_id) * kHistStride + bin] = (uint16_t)s;
+      for (int r = 0; r < kHistReplicas; ++r) {
+        lo += s_hist[g][r][2 * pr];
+        if (2 * pr + 1 < kNumBins) hi += s_hist[g][r][2 * pr + 1];
+      }
+      uint16_t* row = p.tilehist + ((int64_t)(head0 + g) * p.n_tiles + tile_id) * kHistStride;
+      reinterpret_cast<uint32_t*>(row)[pr] = lo | (hi << 16);
     }
   }
 }
