@@ -211,6 +211,18 @@ int adamas_decode_step_stages(const adamas_config *cfg, const void *q,
                               void *workspace, size_t workspace_bytes,
                               void *stream, uint32_t stages);
 
+/*
+ * Measurement aid, not a step of the method: reads `bytes` bytes of device
+ * memory at `src` once, 32 bytes per lane in the scan's access pattern, does
+ * no arithmetic on them and writes nothing (`sink`, device, at least 4 bytes,
+ * is only touched if the data's checksum hits one particular value).  Timing
+ * it over the code planes gives the streaming-read rate this GPU reaches on
+ * the buffers the Eq. 6 scan must read: the achievable ceiling that the scan's
+ * time is compared with.  src 16-byte aligned, bytes a multiple of 32;
+ * bytes == 0 is a no-op.  ADAMAS_ERR_BAD_ARG otherwise.
+ */
+int adamas_stream_read(const void *src, size_t bytes, void *sink, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

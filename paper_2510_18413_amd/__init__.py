@@ -16,6 +16,7 @@ from .binding import (  # noqa: F401
     adamas_select_topk,
     adamas_sparse_attn,
     adamas_status_string,
+    adamas_stream_read,
     adamas_workspace_bytes,
     library,
     library_path,

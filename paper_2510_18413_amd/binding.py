@@ -25,6 +25,7 @@ EXPORTED_SYMBOLS = (
     "adamas_sparse_attn",
     "adamas_decode_step",
     "adamas_decode_step_stages",
+    "adamas_stream_read",
 )
 
 HEAD_DIM = 128
@@ -99,6 +100,8 @@ def library() -> ctypes.CDLL:
         lib.adamas_decode_step.restype = ctypes.c_int
         lib.adamas_decode_step.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp,
                                            i64, vp, sz, vp]
+        lib.adamas_stream_read.restype = ctypes.c_int
+        lib.adamas_stream_read.argtypes = [vp, sz, vp, vp]
         lib.adamas_decode_step_stages.restype = ctypes.c_int
         lib.adamas_decode_step_stages.argtypes = lib.adamas_decode_step.argtypes + [ctypes.c_uint32]
         _lib = lib
@@ -164,6 +167,14 @@ def adamas_encode_query(cfg: Config, q, qcodes, stream=None) -> None:
         _ptr(qcodes, torch.uint8, "qcodes", (batch, cfg.num_q_heads, CODE_ROW_BYTES)), batch,
         _stream(stream))
     _check(rc, "adamas_encode_query")
+
+
+def adamas_stream_read(src, sink, stream=None) -> None:
+    """Reads every byte of the uint8 tensor `src` once (measurement aid); `sink` int32, >= 1 element."""
+    import torch
+    rc = library().adamas_stream_read(_ptr(src, torch.uint8, "src"), src.numel(),
+                                      _ptr(sink, torch.int32, "sink"), _stream(stream))
+    _check(rc, "adamas_stream_read")
 
 
 def adamas_manhattan_distance(cfg: Config, qcodes, codes, seq_start, seq_len, dist_out,

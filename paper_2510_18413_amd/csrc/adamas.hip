@@ -437,4 +437,19 @@ int adamas_decode_step_stages(const adamas_config* cfg, const void* q, const voi
   return launch_status();
 }
 
+int adamas_stream_read(const void* src, size_t bytes, void* sink, void* stream) {
+  if (src == nullptr || sink == nullptr || !aligned16(src) || (bytes & 31u) != 0)
+    return ADAMAS_ERR_BAD_ARG;
+  if ((reinterpret_cast<uintptr_t>(sink) & 3u) != 0) return ADAMAS_ERR_BAD_ARG;
+  if (bytes == 0) return ADAMAS_OK;
+  const int64_t n_rows = (int64_t)(bytes / kRowBytes);
+  const int64_t rows_per_wg = 256 * 2;
+  const int64_t grid = (n_rows + rows_per_wg - 1) / rows_per_wg;
+  if (grid > 0x7fffffff) return ADAMAS_ERR_UNSUPPORTED;
+  clear_stale_error();
+  hipLaunchKernelGGL(stream_read_kernel, dim3((unsigned)grid), dim3(256), 0, (hipStream_t)stream,
+                     static_cast<const uint4*>(src), static_cast<uint32_t*>(sink), n_rows);
+  return launch_status();
+}
+
 }  // extern "C"

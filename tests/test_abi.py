@@ -102,6 +102,11 @@ def test_null_and_misaligned_pointers_rejected():
     a = list(args)
     a[10] = ODD
     assert lib.adamas_select_topk(*a) == -1                                   # workspace alignment
+    assert lib.adamas_stream_read(None, 64, FAKE, None) == -1
+    assert lib.adamas_stream_read(FAKE, 64, None, None) == -1
+    assert lib.adamas_stream_read(ODD, 64, FAKE, None) == -1
+    assert lib.adamas_stream_read(FAKE, 48, FAKE, None) == -1                 # not whole rows
+    assert lib.adamas_stream_read(FAKE, 0, FAKE, None) == 0                   # empty: no-op
     dargs = [p, FAKE, None, None, FAKE, FAKE, FAKE, FAKE, FAKE, 1, 64, FAKE, None, 1024, FAKE,
              1 << 30, None]
     for pos in (1, 4, 5, 6, 7, 8, 11, 14):

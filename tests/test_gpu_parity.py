@@ -204,6 +204,19 @@ def test_sparse_attn_large_scores_do_not_overflow(H, oracle):
     assert np.all(np.isfinite(got)) and H.attn_rel_err(got, ref) <= H.ATTN_TOL
 
 
+def test_stream_read_probe_touches_nothing(H, oracle):
+    """The bandwidth probe only reads: source and sink stay as they were, for full and ragged
+    launch sizes."""
+    import paper_2510_18413_amd as A
+    for n in (32, 32 * 513, 1 << 20):
+        src = torch.randint(0, 256, (n,), dtype=torch.uint8, device="cuda")
+        keep = src.clone()
+        sink = torch.full((4,), 7, dtype=torch.int32, device="cuda")
+        A.adamas_stream_read(src, sink)
+        torch.cuda.synchronize()
+        assert torch.equal(src, keep) and sink.tolist() == [7, 7, 7, 7]
+
+
 # ----------------------------------------------------------------------- fused decode step
 
 @pytest.mark.parametrize("B,Hq,Hkv,lens,k,append", [
