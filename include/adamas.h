@@ -60,9 +60,11 @@
  *                             max_seq_len > ADAMAS_MAX_SEQ_LEN
  *     ADAMAS_ERR_WORKSPACE    workspace_bytes < adamas_workspace_bytes(...)
  *     ADAMAS_ERR_HIP          a launch failed (adamas_last_hip_error() tells)
- * seq_len[b] and seq_start[b] live on the device and are NOT validated: the
- * caller guarantees 0 <= seq_len[b] <= max_seq_len and
- * 0 <= seq_start[b], seq_start[b]+seq_len[b] <= pool_tokens.
+ * seq_len[b] and seq_start[b] live on the device, so the host cannot reject
+ * them: the caller guarantees 0 <= seq_len[b] <= max_seq_len and
+ * 0 <= seq_start[b], seq_start[b]+seq_len[b] <= pool_tokens.  The kernels
+ * check the same conditions and treat a sequence that violates them as empty
+ * (out zeros, idx all -1, nothing appended): no access leaves the pools.
  *
  * Workspace.  Calls that take `workspace` need at least
  * adamas_workspace_bytes(cfg, batch, max_seq_len, k) bytes, 256-byte aligned.
