@@ -276,6 +276,34 @@ def main():
     stream_us = s0.elapsed_time(s1) * 1e3 / (n_rep * n_layers)
     stream_gbps = Hkv * pool * 32 / stream_us / 1e3
 
+    # comparison point: dense decode attention (Eq. 1 over every cached row) on the same layers
+    full_ws = torch.empty(A.adamas_full_attn_workspace_bytes(cfg, B, max_len), dtype=torch.uint8,
+                          device=dev)
+    full_out = torch.zeros(B, Hq, 128, device=dev)
+
+    def full_graph():
+        for d in layers:
+            A.adamas_full_attn(cfg, d["q"], d["K"], d["V"], seq_start, seq_len, full_out, max_len,
+                               full_ws)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for d in layers:
+                A.adamas_full_attn(cfg, d["q"], d["K"], d["V"], seq_start, seq_len, full_out,
+                                   max_len, full_ws)
+        return g
+    fg = full_graph()
+    fg.replay()
+    torch.cuda.synchronize()
+    n_rep = max(1, min(20, args.steps // (16 * n_layers)))
+    s0.record()
+    for _ in range(n_rep):
+        fg.replay()
+    s1.record()
+    torch.cuda.synchronize()
+    full_us = s0.elapsed_time(s1) * 1e3 / (n_rep * n_layers)
+    full_bytes = Hkv * int(lens.sum()) * 512
+
     total_bytes, code_bytes = algorithmic_bytes(B, Hq, Hkv, [int(x) for x in lens], k, append)
     gbps_step = total_bytes / (us_step * 1e-6) / 1e9
     gbps_scan = code_bytes / (ms_scan * 1e-3) / 1e9
@@ -329,6 +357,10 @@ def main():
     result["bulk_encode"] = {"us": round(encode_us, 1), "rows": Hkv * pool,
                              "GBps": round(encode_bytes / encode_us / 1e3, 1),
                              "hbm_frac": round(encode_bytes / encode_us / 1e3 / HBM_PEAK_GBPS, 4)}
+    result["full_attention"] = {"us_per_layer": round(full_us, 2),
+                                "GBps": round(full_bytes / full_us / 1e3, 1),
+                                "hbm_frac": round(full_bytes / full_us / 1e3 / HBM_PEAK_GBPS, 4),
+                                "speedup_of_sparse_step": round(full_us / us_step, 2)}
     if per_sweep:
         ps = sorted(x / n_layers * 1e3 for x in per_sweep)
         result["us_per_layer_p10_p50_p90"] = [round(ps[len(ps) // 10], 3), round(ps[len(ps) // 2], 3),

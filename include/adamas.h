@@ -214,6 +214,24 @@ int adamas_decode_step_stages(const adamas_config *cfg, const void *q,
                               void *stream, uint32_t stages);
 
 /*
+ * Comparison point, not a step of the method: Eq. 1 over ALL cached rows of
+ * every sequence (dense decode attention), the baseline of the paper's
+ * "self-attention speedup" (Sec. 4.3), so that both sides of that ratio can be
+ * measured on one GPU.  q bf16 [batch][Hq][128]; K, V pools as above;
+ * out fp32 [batch][Hq][128] (zeros for an empty sequence).  Workspace:
+ * adamas_full_attn_workspace_bytes(cfg, batch, max_seq_len) bytes, 256-byte
+ * aligned, no initialisation needed.  Same argument checks and error codes as
+ * adamas_sparse_attn.
+ */
+size_t adamas_full_attn_workspace_bytes(const adamas_config *cfg, int32_t batch,
+                                        int64_t max_seq_len);
+int adamas_full_attn(const adamas_config *cfg, const void *q, const void *K,
+                     const void *V, const int64_t *seq_start,
+                     const int32_t *seq_len, int32_t batch, float *out,
+                     int64_t max_seq_len, void *workspace,
+                     size_t workspace_bytes, void *stream);
+
+/*
  * Measurement aid, not a step of the method: reads `bytes` bytes of device
  * memory at `src` once, 32 bytes per lane in the scan's access pattern, does
  * no arithmetic on them and writes nothing (`sink`, device, at least 4 bytes,

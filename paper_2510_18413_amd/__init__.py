@@ -11,6 +11,8 @@ from .binding import (  # noqa: F401
     STAGE_SCAN,
     STAGE_SELECT_ATTN,
     adamas_encode_keys,
+    adamas_full_attn,
+    adamas_full_attn_workspace_bytes,
     adamas_encode_query,
     adamas_manhattan_distance,
     adamas_select_topk,

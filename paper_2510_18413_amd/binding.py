@@ -26,6 +26,8 @@ EXPORTED_SYMBOLS = (
     "adamas_decode_step",
     "adamas_decode_step_stages",
     "adamas_stream_read",
+    "adamas_full_attn_workspace_bytes",
+    "adamas_full_attn",
 )
 
 HEAD_DIM = 128
@@ -100,6 +102,10 @@ def library() -> ctypes.CDLL:
         lib.adamas_decode_step.restype = ctypes.c_int
         lib.adamas_decode_step.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp,
                                            i64, vp, sz, vp]
+        lib.adamas_full_attn_workspace_bytes.restype = sz
+        lib.adamas_full_attn_workspace_bytes.argtypes = [cfgp, i32, i64]
+        lib.adamas_full_attn.restype = ctypes.c_int
+        lib.adamas_full_attn.argtypes = [cfgp, vp, vp, vp, vp, vp, i32, vp, i64, vp, sz, vp]
         lib.adamas_stream_read.restype = ctypes.c_int
         lib.adamas_stream_read.argtypes = [vp, sz, vp, vp]
         lib.adamas_decode_step_stages.restype = ctypes.c_int
@@ -167,6 +173,26 @@ def adamas_encode_query(cfg: Config, q, qcodes, stream=None) -> None:
         _ptr(qcodes, torch.uint8, "qcodes", (batch, cfg.num_q_heads, CODE_ROW_BYTES)), batch,
         _stream(stream))
     _check(rc, "adamas_encode_query")
+
+
+def adamas_full_attn_workspace_bytes(cfg: Config, batch: int, max_seq_len: int) -> int:
+    return int(library().adamas_full_attn_workspace_bytes(ctypes.byref(cfg), batch, max_seq_len))
+
+
+def adamas_full_attn(cfg: Config, q, K, V, seq_start, seq_len, out, max_seq_len: int, workspace,
+                     stream=None) -> None:
+    import torch
+    batch = q.shape[0]
+    hkv, pool = cfg.num_kv_heads, cfg.pool_tokens
+    rc = library().adamas_full_attn(
+        ctypes.byref(cfg), _ptr(q, torch.bfloat16, "q", (batch, cfg.num_q_heads, HEAD_DIM)),
+        _ptr(K, torch.bfloat16, "K", (hkv, pool, HEAD_DIM)),
+        _ptr(V, torch.bfloat16, "V", (hkv, pool, HEAD_DIM)),
+        _ptr(seq_start, torch.int64, "seq_start", (batch,)),
+        _ptr(seq_len, torch.int32, "seq_len", (batch,)), batch,
+        _ptr(out, torch.float32, "out", (batch, cfg.num_q_heads, HEAD_DIM)),
+        max_seq_len, _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream))
+    _check(rc, "adamas_full_attn")
 
 
 def adamas_stream_read(src, sink, stream=None) -> None:

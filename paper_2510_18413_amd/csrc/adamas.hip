@@ -10,6 +10,7 @@
 #include "encode.hpp"
 #include "scan.hpp"
 #include "select_attn.hpp"
+#include "full_attn.hpp"
 
 namespace {
 
@@ -154,6 +155,30 @@ void launch_scan(int G, const Plan& pl, int Hkv, int batch, hipStream_t st, cons
     case 7: launch_scan_g<7, FUSED>(pl, grid, st, sp); break;
     default: launch_scan_g<8, FUSED>(pl, grid, st, sp); break;
   }
+}
+
+struct FullPlan {
+  int n_splits, chunk;
+  size_t total;
+};
+
+// About four workgroups per compute unit; a split covers a multiple of 256 tokens.
+FullPlan make_full_plan(const adamas_config* c, int32_t batch, int64_t max_seq_len) {
+  FullPlan fp{};
+  const int64_t planes = (int64_t)batch * c->num_kv_heads;
+  int64_t want = (4 * kTargetWorkgroups + planes - 1) / planes;
+  if (want > kFullMaxSplits) want = kFullMaxSplits;
+  int64_t chunk = (max_seq_len + want - 1) / want;
+  chunk = (chunk + 255) / 256 * 256;
+  fp.chunk = (int)chunk;
+  fp.n_splits = (int)((max_seq_len + chunk - 1) / chunk);
+  fp.total = align256((size_t)batch * c->num_q_heads * fp.n_splits * kPartialStride * sizeof(float));
+  return fp;
+}
+
+template <int G>
+void launch_full(dim3 grid, hipStream_t st, const FullAttnParams& fp) {
+  hipLaunchKernelGGL((full_attn_kernel<G>), grid, dim3(kFullThreads), 0, st, fp);
 }
 
 uint8_t* ws_at(void* ws, size_t off) { return static_cast<uint8_t*>(ws) + off; }
@@ -434,6 +459,55 @@ int adamas_decode_step_stages(const adamas_config* cfg, const void* q, const voi
   mp.n_parts = pl.n_segs;
   mp.seg_len = pl.seg_len;
   hipLaunchKernelGGL(merge_kernel, dim3(cfg->num_q_heads, batch), dim3(kHeadDim), 0, st, mp);
+  return launch_status();
+}
+
+size_t adamas_full_attn_workspace_bytes(const adamas_config* cfg, int32_t batch,
+                                        int64_t max_seq_len) {
+  if (check_config(cfg) != ADAMAS_OK || check_sizes(batch, max_seq_len, 1) != ADAMAS_OK) return 0;
+  return make_full_plan(cfg, batch, max_seq_len).total;
+}
+
+int adamas_full_attn(const adamas_config* cfg, const void* q, const void* K, const void* V,
+                     const int64_t* seq_start, const int32_t* seq_len, int32_t batch, float* out,
+                     int64_t max_seq_len, void* workspace, size_t workspace_bytes, void* stream) {
+  if (int rc = check_config(cfg)) return rc;
+  if (int rc = check_sizes(batch, max_seq_len, 1)) return rc;
+  if (!q || !K || !V || !seq_start || !seq_len || !out || !workspace) return ADAMAS_ERR_BAD_ARG;
+  if (!aligned16(q) || !aligned16(K) || !aligned16(V)) return ADAMAS_ERR_BAD_ARG;
+  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return ADAMAS_ERR_BAD_ARG;
+  const FullPlan pl = make_full_plan(cfg, batch, max_seq_len);
+  if (workspace_bytes < pl.total) return ADAMAS_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)stream;
+  clear_stale_error();
+  FullAttnParams fp{};
+  fp.q = static_cast<const uint16_t*>(q);
+  fp.K = static_cast<const uint16_t*>(K);
+  fp.V = static_cast<const uint16_t*>(V);
+  fp.seq_start = seq_start;
+  fp.seq_len = seq_len;
+  fp.partial = static_cast<float*>(workspace);
+  fp.pool_tokens = cfg->pool_tokens;
+  fp.max_seq_len = max_seq_len;
+  fp.Hq = cfg->num_q_heads;
+  fp.Hkv = cfg->num_kv_heads;
+  fp.n_splits = pl.n_splits;
+  fp.chunk = pl.chunk;
+  fp.scale_log2e = scale_log2e(cfg);
+  const dim3 grid(pl.n_splits, cfg->num_kv_heads, batch);
+  switch (cfg->num_q_heads / cfg->num_kv_heads) {
+    case 1: launch_full<1>(grid, st, fp); break;
+    case 2: launch_full<2>(grid, st, fp); break;
+    case 3: launch_full<3>(grid, st, fp); break;
+    case 4: launch_full<4>(grid, st, fp); break;
+    case 5: launch_full<5>(grid, st, fp); break;
+    case 6: launch_full<6>(grid, st, fp); break;
+    case 7: launch_full<7>(grid, st, fp); break;
+    default: launch_full<8>(grid, st, fp); break;
+  }
+  if (int rc = launch_status()) return rc;
+  hipLaunchKernelGGL(merge_parts_kernel, dim3(cfg->num_q_heads, batch), dim3(kHeadDim), 0, st,
+                     fp.partial, out, cfg->num_q_heads, pl.n_splits);
   return launch_status();
 }
 

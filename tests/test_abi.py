@@ -102,6 +102,16 @@ def test_null_and_misaligned_pointers_rejected():
     a = list(args)
     a[10] = ODD
     assert lib.adamas_select_topk(*a) == -1                                   # workspace alignment
+    fargs = [p, FAKE, FAKE, FAKE, FAKE, FAKE, 1, FAKE, 1024, FAKE, 1 << 30, None]
+    for pos in (1, 2, 3, 4, 5, 7, 9):
+        a = list(fargs)
+        a[pos] = None
+        assert lib.adamas_full_attn(*a) == -1
+    a = list(fargs)
+    a[10] = 16
+    assert lib.adamas_full_attn(*a) == -3                                     # workspace too small
+    assert A.adamas_full_attn_workspace_bytes(c, 1, 32768) > 0
+    assert A.adamas_full_attn_workspace_bytes(c, 0, 32768) == 0
     assert lib.adamas_stream_read(None, 64, FAKE, None) == -1
     assert lib.adamas_stream_read(FAKE, 64, None, None) == -1
     assert lib.adamas_stream_read(ODD, 64, FAKE, None) == -1

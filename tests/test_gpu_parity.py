@@ -204,6 +204,37 @@ def test_sparse_attn_large_scores_do_not_overflow(H, oracle):
     assert np.all(np.isfinite(got)) and H.attn_rel_err(got, ref) <= H.ATTN_TOL
 
 
+@pytest.mark.parametrize("B,Hq,Hkv,lens", [
+    (1, 1, 1, [1024]),
+    (1, 4, 4, [5000]),
+    (3, 8, 2, [4097, 0, 333]),
+    (2, 8, 1, [300, 9000]),
+    (1, 6, 2, [20001]),
+])
+def test_full_attention_matches_oracle(H, oracle, B, Hq, Hkv, lens):
+    """The dense comparison kernel (Eq. 1 over every cached row) against the oracle's full
+    attention, per (sequence, query head); an empty sequence gives zeros."""
+    import paper_2510_18413_amd as A
+    case = small_case(700 + Hq, B, Hq, Hkv, lens)
+    d = H.DeviceCase(case, 16, encode=False)
+    ws = torch.full((A.adamas_full_attn_workspace_bytes(d.cfg, B, d.max_len),), 0xA5,
+                    dtype=torch.uint8, device="cuda")
+    A.adamas_full_attn(d.cfg, d.q, d.K, d.V, d.seq_start, d.seq_len, d.out, d.max_len, ws)
+    torch.cuda.synchronize()
+    got = d.out.cpu().numpy()
+    G = Hq // Hkv
+    ref = np.zeros_like(got, dtype=np.float64)
+    for b in range(B):
+        s, L = int(case.seq_start[b]), int(case.seq_len[b])
+        for h in range(Hq):
+            if L > 0:
+                ref[b, h] = oracle.full_attention(case.q[b, h], case.K[h // G, s:s + L],
+                                                  case.V[h // G, s:s + L], H.SM_SCALE)
+            else:
+                assert np.all(got[b, h] == 0)
+    assert np.all(np.isfinite(got)) and H.attn_rel_err(got, ref) <= H.ATTN_TOL
+
+
 def test_stream_read_probe_touches_nothing(H, oracle):
     """The bandwidth probe only reads: source and sink stay as they were, for full and ragged
     launch sizes."""
