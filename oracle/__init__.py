@@ -49,7 +49,8 @@ def lib() -> ctypes.CDLL:
         for name in ("oracle_hadamard_matrix", "oracle_hadamard_transform", "oracle_bucketize",
                      "oracle_pack_row", "oracle_unpack_row", "oracle_encode", "oracle_manhattan",
                      "oracle_topk", "oracle_sparse_attention", "oracle_full_attention",
-                     "oracle_decode_step", "oracle_max_threads"):
+                     "oracle_decode_step", "oracle_max_threads", "oracle_encode_variant",
+                     "oracle_squared_distance", "oracle_decode_step_variant"):
             getattr(_lib, name).restype = ctypes.c_int
         _lib.oracle_set_threads.restype = None
         _lib.oracle_sparse_attention.argtypes = [ctypes.c_void_p] * 4 + [
@@ -60,6 +61,10 @@ def lib() -> ctypes.CDLL:
             ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_double] + [ctypes.c_void_p] * 8 + [ctypes.c_int32, ctypes.c_int32] + [
             ctypes.c_void_p] * 3 + [ctypes.c_int64]
+        _lib.oracle_decode_step_variant.argtypes = _lib.oracle_decode_step.argtypes + [
+            ctypes.c_int, ctypes.c_int]
+        _lib.oracle_encode_variant.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p,
+                                               ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
     return _lib
 
 
@@ -143,16 +148,30 @@ def unpack_rows(rows: np.ndarray) -> np.ndarray:
     return out.reshape(rows.shape[:-1] + (D,))
 
 
-def encode(x_bf16: np.ndarray, thr):
-    """x_bf16: uint16 [..., 128].  Returns (codes uint8 [..., 128], rows uint8 [..., 32])."""
+def encode(x_bf16: np.ndarray, thr, hadamard: bool = True):
+    """x_bf16: uint16 [..., 128].  Returns (codes uint8 [..., 128], rows uint8 [..., 32]).
+    hadamard=False is the ablation that bucketizes the raw vector (Section 4.4)."""
     x = np.ascontiguousarray(x_bf16, dtype=np.uint16)
     assert x.shape[-1] == D
     n = x.size // D
     codes = np.empty(x.shape, dtype=np.uint8)
     rows = np.empty(x.shape[:-1] + (ROW_BYTES,), dtype=np.uint8)
-    _check(lib().oracle_encode(_p(x), ctypes.c_int64(n), _p(_thr(thr)), _p(codes), _p(rows)),
-           "encode")
+    _check(lib().oracle_encode_variant(_p(x), ctypes.c_int64(n), _p(_thr(thr)),
+                                       1 if hadamard else 0, _p(codes), _p(rows)), "encode")
     return codes, rows
+
+
+def squared_distance(qcode: np.ndarray, kcodes: np.ndarray) -> np.ndarray:
+    """qcode uint8 [128], kcodes uint8 [L,128] (unpacked) -> int32 [L]: sum of squared code
+    differences (the L2 ablation of Section 4.4, without the monotone square root)."""
+    qcode = np.ascontiguousarray(qcode, dtype=np.uint8)
+    kcodes = np.ascontiguousarray(kcodes, dtype=np.uint8)
+    assert qcode.shape == (D,) and kcodes.ndim == 2 and kcodes.shape[1] == D
+    L = kcodes.shape[0]
+    out = np.empty(L, dtype=np.int32)
+    _check(lib().oracle_squared_distance(_p(qcode), _p(kcodes), ctypes.c_int64(L), _p(out)),
+           "squared_distance")
+    return out
 
 
 def manhattan(qcode: np.ndarray, kcodes: np.ndarray) -> np.ndarray:
@@ -200,13 +219,14 @@ def full_attention(q, K, V, scale: float) -> np.ndarray:
 
 
 def decode_step(q, K, V, code_rows, seq_start, seq_len, k, thr_q, thr_k, scale,
-                k_new=None, v_new=None, want_dist=False):
+                k_new=None, v_new=None, want_dist=False, hadamard=True, squared=False):
     """One decode step of one layer (Algorithm 1) over a ragged batch.
 
     q uint16 [B,Hq,128]; K, V uint16 [Hkv,pool,128] and code_rows uint8 [Hkv,pool,32] are
     UPDATED IN PLACE when k_new/v_new (uint16 [B,Hkv,128]) are given.  seq_len counts the
     appended token.  Returns (out float32 [B,Hq,128], idx int32 [B,Hq,k], dist int32
-    [B,Hq,max_len] or None).
+    [B,Hq,max_len] or None).  hadamard=False / squared=True select the ablation variants of
+    Section 4.4 (code_rows must have been encoded with the same `hadamard`).
     """
     q = np.ascontiguousarray(q, dtype=np.uint16)
     B, Hq, _ = q.shape
@@ -226,9 +246,9 @@ def decode_step(q, K, V, code_rows, seq_start, seq_len, k, thr_q, thr_k, scale,
     out = np.zeros((B, Hq, D), dtype=np.float32)
     idx = np.empty((B, Hq, k), dtype=np.int32)
     dist = np.full((B, Hq, max(max_len, 1)), -1, dtype=np.int32) if want_dist else None
-    rc = lib().oracle_decode_step(
+    rc = lib().oracle_decode_step_variant(
         Hq, Hkv, pool, _p(_thr(thr_q)), _p(_thr(thr_k)), float(scale), _p(q), _p(k_new),
         _p(v_new), _p(K), _p(V), _p(code_rows), _p(seq_start), _p(seq_len), B, k, _p(out),
-        _p(idx), _p(dist), max(max_len, 1))
+        _p(idx), _p(dist), max(max_len, 1), 1 if hadamard else 0, 1 if squared else 0)
     _check(rc, "decode_step")
     return out, idx, dist

@@ -179,15 +179,32 @@ int oracle_unpack_row(const uint8_t row[ORACLE_ROW_BYTES], uint8_t code[ORACLE_D
  * Returns ORACLE_PRECONDITION if a vector holds NaN/Inf or its exponent
  * spread is too large for the double sums to be exact (see file header).
  */
+int oracle_encode_variant(const uint16_t *x, int64_t n, const float thr[3], int use_hadamard,
+                          uint8_t *codes, uint8_t *rows);
+
 int oracle_encode(const uint16_t *x, int64_t n, const float thr[3],
                   uint8_t *codes, uint8_t *rows) {
+  return oracle_encode_variant(x, n, thr, 1, codes, rows);
+}
+
+/*
+ * use_hadamard != 0: the method (Eq. 4 then Eq. 5).  use_hadamard == 0: the
+ * ablation "without the Hadamard transform" (Section 4.4): Eq. 5 is applied
+ * to the raw vector, code_j = #{ i : x_j > thr[i] }, thresholds as given.
+ */
+int oracle_encode_variant(const uint16_t *x, int64_t n, const float thr[3], int use_hadamard,
+                          uint8_t *codes, uint8_t *rows) {
   if (!x || n < 0 || !thr) return ORACLE_BAD_ARG;
   if (!(thr[0] < thr[1] && thr[1] < thr[2])) return ORACLE_BAD_ARG;
   int8_t *H = (int8_t *)malloc((size_t)ORACLE_D * ORACLE_D);
   if (!H) return ORACLE_NOMEM;
   oracle_hadamard_matrix(ORACLE_D, H);
   double tau[3];
-  scaled_thresholds(ORACLE_D, thr, tau);
+  if (use_hadamard) {
+    scaled_thresholds(ORACLE_D, thr, tau);
+  } else {
+    for (int i = 0; i < 3; ++i) tau[i] = (double)thr[i];
+  }
   int status = ORACLE_OK;
 #pragma omp parallel for schedule(static)
   for (int64_t v = 0; v < n; ++v) {
@@ -210,9 +227,13 @@ int oracle_encode(const uint16_t *x, int64_t n, const float thr[3],
       continue;
     }
     for (int j = 0; j < ORACLE_D; ++j) {
-      double s = 0.0;
-      for (int i = 0; i < ORACLE_D; ++i) s += xv[i] * (double)H[i * ORACLE_D + j];
-      y[j] = s;
+      if (use_hadamard) {
+        double s = 0.0;
+        for (int i = 0; i < ORACLE_D; ++i) s += xv[i] * (double)H[i * ORACLE_D + j];
+        y[j] = s;
+      } else {
+        y[j] = xv[j];
+      }
     }
     for (int j = 0; j < ORACLE_D; ++j) {
       int c = 0;
@@ -238,6 +259,26 @@ int oracle_manhattan(const uint8_t *qcode, const uint8_t *kcodes, int64_t L,
     for (int j = 0; j < ORACLE_D; ++j) {
       int diff = (int)qcode[j] - (int)kcodes[t * ORACLE_D + j];
       s += diff < 0 ? -diff : diff;
+    }
+    D[t] = s;
+  }
+  return ORACLE_OK;
+}
+
+/*
+ * Ablation "with L2 distance" (Section 4.4): the estimator of Eq. 6 with the
+ * absolute difference replaced by its square, D[t] = sum_j (qcode_j - kcodes[t][j])^2.
+ * (The square root is monotone and would not change any ranking; it is left out,
+ * which keeps the distances integers.)
+ */
+int oracle_squared_distance(const uint8_t *qcode, const uint8_t *kcodes, int64_t L,
+                            int32_t *D) {
+  if (!qcode || (!kcodes && L > 0) || L < 0 || (!D && L > 0)) return ORACLE_BAD_ARG;
+  for (int64_t t = 0; t < L; ++t) {
+    int32_t s = 0;
+    for (int j = 0; j < ORACLE_D; ++j) {
+      int diff = (int)qcode[j] - (int)kcodes[t * ORACLE_D + j];
+      s += diff * diff;
     }
     D[t] = s;
   }
@@ -381,6 +422,15 @@ int oracle_full_attention(const uint16_t *q, const uint16_t *K, const uint16_t *
  * seq_len[b] untouched.  Parallel over (b, query head) when built with
  * OpenMP.
  */
+int oracle_decode_step_variant(int32_t Hq, int32_t Hkv, int64_t pool_tokens,
+                               const float thr_q[3], const float thr_k[3], double scale,
+                               const uint16_t *q, const uint16_t *k_new,
+                               const uint16_t *v_new, uint16_t *K, uint16_t *V,
+                               uint8_t *code_rows, const int64_t *seq_start,
+                               const int32_t *seq_len, int32_t B, int32_t k, float *out,
+                               int32_t *idx, int32_t *dist, int64_t max_seq_len,
+                               int use_hadamard, int squared_distance);
+
 int oracle_decode_step(int32_t Hq, int32_t Hkv, int64_t pool_tokens,
                        const float thr_q[3], const float thr_k[3], double scale,
                        const uint16_t *q, const uint16_t *k_new,
@@ -388,6 +438,25 @@ int oracle_decode_step(int32_t Hq, int32_t Hkv, int64_t pool_tokens,
                        uint8_t *code_rows, const int64_t *seq_start,
                        const int32_t *seq_len, int32_t B, int32_t k, float *out,
                        int32_t *idx, int32_t *dist, int64_t max_seq_len) {
+  return oracle_decode_step_variant(Hq, Hkv, pool_tokens, thr_q, thr_k, scale, q, k_new, v_new, K,
+                                    V, code_rows, seq_start, seq_len, B, k, out, idx, dist,
+                                    max_seq_len, 1, 0);
+}
+
+/*
+ * The same step for the ablation variants of Section 4.4: use_hadamard == 0
+ * encodes query and appended key without the transform; squared_distance != 0
+ * ranks by the squared-difference estimator instead of Eq. 6.  (1, 0) is the
+ * method itself.  code_rows must have been encoded with the same use_hadamard.
+ */
+int oracle_decode_step_variant(int32_t Hq, int32_t Hkv, int64_t pool_tokens,
+                               const float thr_q[3], const float thr_k[3], double scale,
+                               const uint16_t *q, const uint16_t *k_new,
+                               const uint16_t *v_new, uint16_t *K, uint16_t *V,
+                               uint8_t *code_rows, const int64_t *seq_start,
+                               const int32_t *seq_len, int32_t B, int32_t k, float *out,
+                               int32_t *idx, int32_t *dist, int64_t max_seq_len,
+                               int use_hadamard, int squared_distance) {
   if (Hq < 1 || Hkv < 1 || Hq % Hkv != 0 || B < 1 || k < 1) return ORACLE_BAD_ARG;
   if (!q || !K || !V || !code_rows || !seq_start || !seq_len || !out || !idx)
     return ORACLE_BAD_ARG;
@@ -407,7 +476,8 @@ int oracle_decode_step(int32_t Hq, int32_t Hkv, int64_t pool_tokens,
         int64_t off = (int64_t)h * pool_tokens + row;
         memcpy(K + off * ORACLE_D, kn, ORACLE_D * sizeof(uint16_t));
         memcpy(V + off * ORACLE_D, vn, ORACLE_D * sizeof(uint16_t));
-        int rc = oracle_encode(kn, 1, thr_k, NULL, code_rows + off * ORACLE_ROW_BYTES);
+        int rc = oracle_encode_variant(kn, 1, thr_k, use_hadamard, NULL,
+                                       code_rows + off * ORACLE_ROW_BYTES);
         if (rc != ORACLE_OK) return rc;
       }
     }
@@ -423,14 +493,15 @@ int oracle_decode_step(int32_t Hq, int32_t Hkv, int64_t pool_tokens,
       float *o = out + ((int64_t)b * Hq + h) * ORACLE_D;
       int32_t *sel = idx + ((int64_t)b * Hq + h) * k;
       uint8_t qcode[ORACLE_D];
-      int rc = oracle_encode(qv, 1, thr_q, qcode, NULL);
+      int rc = oracle_encode_variant(qv, 1, thr_q, use_hadamard, qcode, NULL);
       uint8_t *kc = (uint8_t *)malloc((size_t)(L > 0 ? L : 1) * ORACLE_D);
       int32_t *D = (int32_t *)malloc((size_t)(L > 0 ? L : 1) * sizeof(int32_t));
       if (!kc || !D) rc = ORACLE_NOMEM;
       if (rc == ORACLE_OK) {
         for (int64_t t = 0; t < L; ++t)
           oracle_unpack_row(code_rows + (base + t) * ORACLE_ROW_BYTES, kc + t * ORACLE_D);
-        oracle_manhattan(qcode, kc, L, D);
+        if (squared_distance) oracle_squared_distance(qcode, kc, L, D);
+        else oracle_manhattan(qcode, kc, L, D);
         if (dist)
           memcpy(dist + ((int64_t)b * Hq + h) * max_seq_len, D, (size_t)L * sizeof(int32_t));
         rc = oracle_topk(D, L, k, sel);

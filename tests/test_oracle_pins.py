@@ -253,6 +253,98 @@ def test_l1_with_one_bit_thresholds_is_hamming_of_signs(oracle):
     assert np.array_equal(oracle.manhattan(codes[0], codes[1:]), ham)
 
 
+# ------------------------------------------------- ablation variants (Section 4.4)
+
+def test_l2_all_code_pairs_from_fixture(oracle):
+    pairs = np.loadtxt(os.path.join(GOLDEN, "l2_pairs.txt"), dtype=np.int64)
+    assert pairs.shape == (16, 3)
+    for a, b, d in pairs:
+        for dim in (0, 31, 32, 127):
+            qa = np.zeros(128, dtype=np.uint8)
+            kb = np.zeros((1, 128), dtype=np.uint8)
+            qa[dim], kb[0, dim] = a, b
+            assert oracle.squared_distance(qa, kb)[0] == d
+
+
+def test_l2_extremes_symmetry_and_relation_to_l1(oracle):
+    rng = np.random.default_rng(17)
+    c = rng.integers(0, 4, (30, 128)).astype(np.uint8)
+    assert oracle.squared_distance(np.zeros(128, np.uint8), np.full((1, 128), 3, np.uint8))[0] == 1152
+    D2 = np.stack([oracle.squared_distance(c[i], c) for i in range(30)])
+    D1 = np.stack([oracle.manhattan(c[i], c) for i in range(30)])
+    assert np.array_equal(D2, D2.T) and np.all(np.diag(D2) == 0)
+    assert np.all(D2 >= D1) and np.all(D2 <= 3 * D1)          # |d| <= d^2 <= 3|d| for |d| in 0..3
+    # numpy's squared Euclidean norm as the independent witness
+    ref = np.linalg.norm(c[:, None, :].astype(float) - c[None].astype(float), axis=-1) ** 2
+    assert np.array_equal(D2, np.rint(ref).astype(np.int64))
+    # codes that differ by at most one level: both estimators agree
+    near = np.clip(c[0].astype(int) + rng.integers(-1, 2, (20, 128)), 0, 3).astype(np.uint8)
+    assert np.array_equal(oracle.squared_distance(c[0], near), oracle.manhattan(c[0], near))
+
+
+def test_l2_bitplane_identity_brute_force():
+    # (a-b)^2 = popcount(x0) + 4*popcount(u) + 4*popcount(u & x0), u = x1 & ~(x0 & g):
+    # the identity a bit-plane kernel may use, checked over all 16 pairs (no oracle call).
+    for a in range(4):
+        for b in range(4):
+            x0, x1 = (a ^ b) & 1, (a ^ b) >> 1
+            g = (a >> 1) ^ (a & 1)
+            u = x1 & ~(x0 & g) & 1
+            assert (a - b) ** 2 == x0 + 4 * u + 4 * (u & x0)
+
+
+def test_encode_without_hadamard_buckets_the_raw_vector(oracle):
+    x = np.zeros(128, dtype=np.float32)
+    x[:8] = [-2.0, -1.0, -0.5, 0.0, 0.5, 1.0, 1.5, 3.0]
+    codes, rows = oracle.encode(bf16(x), THR, hadamard=False)
+    # strict '>' against (-1, 0, 1): -1 -> 0, 0 -> 1, 1 -> 2
+    assert codes[:8].tolist() == [0, 0, 1, 1, 2, 2, 3, 3]
+    assert np.all(codes[8:] == 1)
+    assert np.array_equal(oracle.unpack_row(rows), codes)
+    rng = np.random.default_rng(18)
+    xs = bf16(rng.standard_normal((50, 128)) * 2)
+    codes, _ = oracle.encode(xs, THR, hadamard=False)
+    assert np.array_equal(codes, (widen(xs)[..., None] > np.array(THR)).sum(-1))
+
+
+def test_encode_variants_agree_through_the_transform(oracle):
+    # H(Hx) = 128 x: the method applied to x' = Hx with thresholds t * sqrt(128) decides
+    # 128 x_j > t * 128, i.e. exactly what the ablation decides on x with thresholds t.
+    rng = np.random.default_rng(19)
+    H = scipy.linalg.hadamard(128).astype(np.float64)
+    x = rng.integers(-3, 4, (40, 128)).astype(np.float64)
+    xt = x @ H                                              # small integers: exact in bf16? check
+    assert np.array_equal(widen(bf16(xt)), xt)
+    t = np.array([-1.5, 0.5, 1.5])
+    plain, _ = oracle.encode(bf16(x), tuple(t), hadamard=False)
+    through, _ = oracle.encode(bf16(xt), tuple(t * np.sqrt(128.0)), hadamard=True)
+    assert np.array_equal(plain, through)
+
+
+def test_decode_step_variants_compose_their_stages(oracle):
+    case = synth.make_case("t", 78, 2, 4, 2, [200, 77], [16],
+                           lambda b, L, h, rng: rng.choice(L, (2, 1), replace=False))
+    for hadamard, squared in ((False, False), (True, True), (False, True)):
+        K, V = case.K.copy(), case.V.copy()
+        _, rows = oracle.encode(K, case.thresholds, hadamard=hadamard)
+        out, idx, dist = oracle.decode_step(case.q, K, V, rows, case.seq_start, case.seq_len, 16,
+                                            case.thresholds, case.thresholds, 1 / np.sqrt(128.0),
+                                            want_dist=True, hadamard=hadamard, squared=squared)
+        for b in range(2):
+            L, s = int(case.seq_len[b]), int(case.seq_start[b])
+            for h in range(4):
+                kvh = h // 2
+                qc, _ = oracle.encode(case.q[b, h], case.thresholds, hadamard=hadamard)
+                kc = oracle.unpack_rows(rows[kvh, s:s + L])
+                Dref = oracle.squared_distance(qc, kc) if squared else oracle.manhattan(qc, kc)
+                assert np.array_equal(dist[b, h, :L], Dref)
+                sel = oracle.topk(Dref, 16)
+                assert np.array_equal(idx[b, h], sel)
+                ref = oracle.sparse_attention(case.q[b, h], case.K[kvh, s:s + L],
+                                              case.V[kvh, s:s + L], sel, 1 / np.sqrt(128.0))
+                assert np.array_equal(out[b, h], ref)
+
+
 # ----------------------------------------------------------------------------------- top-k
 
 def test_topk_exhaustive_subsets(oracle):
