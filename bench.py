@@ -46,6 +46,9 @@ def parse_args():
     ap.add_argument("--config", default="cfg1", choices=sorted(WORKLOADS))
     ap.add_argument("--k", type=int, default=0, help="token budget (0: the workload's default)")
     ap.add_argument("--layers", type=int, default=32, help="distinct layer caches to rotate over")
+    ap.add_argument("--variant", default="adamas",
+                    choices=["adamas", "no_hadamard", "l2", "no_hadamard_l2"],
+                    help="ablation switches of Section 4.4 (default: the method itself)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--eager", action="store_true", help="launch from Python instead of a graph")
     ap.add_argument("--scan-only", action="store_true",
@@ -103,7 +106,11 @@ def main():
         pos += int(lens[b]) + synth.SEQ_GAP_ROWS
     pool = pos - synth.SEQ_GAP_ROWS
     max_len = int(lens.max())
-    cfg = A.Config.make(Hq, Hkv, pool, thr_k=synth.DEFAULT_THRESHOLDS)
+    no_hadamard = args.variant in ("no_hadamard", "no_hadamard_l2")
+    squared = args.variant in ("l2", "no_hadamard_l2")
+    cfg = A.Config.make(Hq, Hkv, pool, thr_k=synth.DEFAULT_THRESHOLDS,
+                        variant=(A.VARIANT_NO_HADAMARD if no_hadamard else 0)
+                        | (A.VARIANT_L2 if squared else 0))
     seq_start = torch.from_numpy(starts).to(dev)
     seq_len = torch.from_numpy(lens).to(dev)
 
@@ -331,7 +338,7 @@ def main():
         "config": {
             "workload": wl["text"] + ", budget k=%d, %d rotating layer caches" % (k, n_layers),
             "batch": B, "q_heads": Hq, "kv_heads": Hkv, "context": int(max_len),
-            "sum_context": int(lens.sum()), "k": k, "append": append,
+            "sum_context": int(lens.sum()), "k": k, "append": append, "variant": args.variant,
             "launch": "eager" if args.eager else "hipGraph of one %d-layer sweep" % n_layers,
         },
         "achieved_hbm_GBps": round(gbps_step, 1),
@@ -388,12 +395,14 @@ def main():
             kns, vns = np.ascontiguousarray(knh[:, sel_kv]), np.ascontiguousarray(vnh[:, sel_kv])
         else:
             kns = vns = None
-        _, rows = oracle.encode(Ks, synth.DEFAULT_THRESHOLDS)          # cache state, not timed
+        _, rows = oracle.encode(Ks, synth.DEFAULT_THRESHOLDS,          # cache state, not timed
+                                hadamard=not no_hadamard)
         qs = np.ascontiguousarray(qh[:, sel_q])
         t0 = time.perf_counter()
         ref_out, ref_idx, _ = oracle.decode_step(qs, Ks, Vs, rows, starts, lens, k,
                                                  synth.DEFAULT_THRESHOLDS, synth.DEFAULT_THRESHOLDS,
-                                                 1.0 / np.sqrt(128.0), k_new=kns, v_new=vns)
+                                                 1.0 / np.sqrt(128.0), k_new=kns, v_new=vns,
+                                                 hadamard=not no_hadamard, squared=squared)
         cpu_s = time.perf_counter() - t0
         scale_up = Hkv / n_kv
         result["cpu_baseline"] = {

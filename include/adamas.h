@@ -83,7 +83,8 @@ extern "C" {
 
 #define ADAMAS_HEAD_DIM 128
 #define ADAMAS_CODE_ROW_BYTES 32
-#define ADAMAS_MAX_DISTANCE 384          /* 3 * 128 */
+#define ADAMAS_MAX_DISTANCE 384          /* 3 * 128 (Eq. 6) */
+#define ADAMAS_MAX_DISTANCE_L2 1152      /* 9 * 128 (ADAMAS_VARIANT_L2) */
 #define ADAMAS_MAX_K 4096                /* largest budget in the paper's tables */
 #define ADAMAS_MAX_GROUP 8               /* query heads per KV head */
 #define ADAMAS_MAX_SEQ_LEN (1 << 20)
@@ -94,11 +95,25 @@ extern "C" {
 #define ADAMAS_ERR_WORKSPACE (-3)
 #define ADAMAS_ERR_HIP (-4)
 
+/*
+ * Ablation variants of Section 4.4, as switches on the same kernels.  They
+ * apply to every entry point that takes the config; a cache must be encoded
+ * and queried with the same ADAMAS_VARIANT_NO_HADAMARD setting.
+ *   NO_HADAMARD  Eq. 5 is applied to the raw vector: no transform, thresholds
+ *                compared with the elements as given.
+ *   L2           tokens are ranked by sum_j (qcode_j - kcode_j)^2 instead of
+ *                Eq. 6 (no square root: it would not change the ranking);
+ *                distances then range over 0..ADAMAS_MAX_DISTANCE_L2.
+ * Other bits -> ADAMAS_ERR_UNSUPPORTED.  (1-bit / 3-bit codes are not built.)
+ */
+#define ADAMAS_VARIANT_NO_HADAMARD 1u
+#define ADAMAS_VARIANT_L2 2u
+
 typedef struct adamas_config {
   int32_t head_dim;      /* must be 128 */
   int32_t num_q_heads;   /* Hq */
   int32_t num_kv_heads;  /* Hkv; Hq % Hkv == 0 */
-  int32_t reserved;      /* must be 0 */
+  uint32_t variant;      /* 0 = the method; else ADAMAS_VARIANT_* flags (Sec. 4.4 ablations) */
   int64_t pool_tokens;   /* rows per KV head in K, V and codes */
   float thr_k[3];        /* key thresholds B1 < B2 < B3 of Eq. 5, orthonormal scale */
   float thr_q[3];        /* query thresholds (the paper uses one triple: pass the same) */

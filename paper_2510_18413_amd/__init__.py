@@ -10,6 +10,8 @@ from .binding import (  # noqa: F401
     STAGE_ALL,
     STAGE_SCAN,
     STAGE_SELECT_ATTN,
+    VARIANT_L2,
+    VARIANT_NO_HADAMARD,
     adamas_encode_keys,
     adamas_full_attn,
     adamas_full_attn_workspace_bytes,

@@ -32,6 +32,8 @@ EXPORTED_SYMBOLS = (
 
 HEAD_DIM = 128
 CODE_ROW_BYTES = 32
+VARIANT_NO_HADAMARD = 1
+VARIANT_L2 = 2
 
 
 class AdamasError(RuntimeError):
@@ -48,7 +50,7 @@ class Config(ctypes.Structure):
         ("head_dim", ctypes.c_int32),
         ("num_q_heads", ctypes.c_int32),
         ("num_kv_heads", ctypes.c_int32),
-        ("reserved", ctypes.c_int32),
+        ("variant", ctypes.c_uint32),
         ("pool_tokens", ctypes.c_int64),
         ("thr_k", ctypes.c_float * 3),
         ("thr_q", ctypes.c_float * 3),
@@ -58,9 +60,9 @@ class Config(ctypes.Structure):
     @classmethod
     def make(cls, num_q_heads: int, num_kv_heads: int, pool_tokens: int,
              thr_k: Sequence[float] = (-1.0, 0.0, 1.0), thr_q: Optional[Sequence[float]] = None,
-             sm_scale: float = 0.0, head_dim: int = HEAD_DIM) -> "Config":
+             sm_scale: float = 0.0, head_dim: int = HEAD_DIM, variant: int = 0) -> "Config":
         thr_q = thr_k if thr_q is None else thr_q
-        return cls(head_dim, num_q_heads, num_kv_heads, 0, pool_tokens,
+        return cls(head_dim, num_q_heads, num_kv_heads, variant, pool_tokens,
                    (ctypes.c_float * 3)(*thr_k), (ctypes.c_float * 3)(*thr_q), sm_scale)
 
 

@@ -29,6 +29,7 @@ struct Plan {
   int n_tiles;       // scan tiles per (sequence, KV head)
   int seg_len;       // tokens per select workgroup, multiple of tile_tokens and of kSelPass
   int n_segs;        // select workgroups per (sequence, query head)
+  int metric;        // kMetricL1 (Eq. 6) or kMetricL2 (squared-difference variant)
   int64_t dist_stride;
   size_t off_dist, off_hist, off_partial, total;
 };
@@ -37,7 +38,7 @@ size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 int check_config(const adamas_config* c) {
   if (c == nullptr) return ADAMAS_ERR_BAD_ARG;
-  if (c->num_q_heads < 1 || c->num_kv_heads < 1 || c->pool_tokens < 1 || c->reserved != 0)
+  if (c->num_q_heads < 1 || c->num_kv_heads < 1 || c->pool_tokens < 1)
     return ADAMAS_ERR_BAD_ARG;
   if (c->num_q_heads % c->num_kv_heads != 0) return ADAMAS_ERR_BAD_ARG;
   if (c->num_q_heads > 65535) return ADAMAS_ERR_BAD_ARG;
@@ -47,6 +48,7 @@ int check_config(const adamas_config* c) {
   }
   if (!std::isfinite(c->sm_scale) || c->sm_scale < 0.f) return ADAMAS_ERR_BAD_ARG;
   if (c->head_dim != ADAMAS_HEAD_DIM) return ADAMAS_ERR_UNSUPPORTED;
+  if (c->variant & ~(ADAMAS_VARIANT_NO_HADAMARD | ADAMAS_VARIANT_L2)) return ADAMAS_ERR_UNSUPPORTED;
   if (c->num_q_heads / c->num_kv_heads > ADAMAS_MAX_GROUP) return ADAMAS_ERR_UNSUPPORTED;
   return ADAMAS_OK;
 }
@@ -61,6 +63,7 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 
 Plan make_plan(const adamas_config* c, int32_t batch, int64_t max_seq_len, int32_t k) {
   Plan pl{};
+  pl.metric = (c->variant & ADAMAS_VARIANT_L2) ? kMetricL2 : kMetricL1;
   const int64_t planes = (int64_t)batch * c->num_kv_heads;
   // Scan tile (measured on MI355X): large tiles amortise the per-workgroup
   // prologue and leave the select kernel fewer tile histograms to read, small
@@ -100,16 +103,20 @@ Plan make_plan(const adamas_config* c, int32_t batch, int64_t max_seq_len, int32
   pl.off_dist = off;
   off = align256(off + heads * (size_t)pl.dist_stride * sizeof(uint16_t));
   pl.off_hist = off;
-  off = align256(off + heads * (size_t)pl.n_tiles * kHistStride * sizeof(uint16_t));
+  const size_t hist_stride = (c->variant & ADAMAS_VARIANT_L2) ? Dist<kMetricL2>::kStride
+                                                              : Dist<kMetricL1>::kStride;
+  off = align256(off + heads * (size_t)pl.n_tiles * hist_stride * sizeof(uint16_t));
   pl.off_partial = off;
   off = align256(off + heads * (size_t)kMaxParts * kPartialStride * sizeof(float));
   pl.total = off;
   return pl;
 }
 
-Thresholds scaled(const float thr[3]) {
+// Thresholds as the kernels compare them (see struct Thresholds).
+Thresholds scaled(const adamas_config* c, const float thr[3]) {
   Thresholds t;
-  const double root = std::sqrt((double)ADAMAS_HEAD_DIM);
+  t.transform = (c->variant & ADAMAS_VARIANT_NO_HADAMARD) ? 0 : 1;
+  const double root = t.transform ? std::sqrt((double)ADAMAS_HEAD_DIM) : 1.0;
   for (int i = 0; i < 3; ++i) t.tau[i] = (double)thr[i] * root;
   return t;
 }
@@ -132,13 +139,19 @@ int launch_status() {
   return ADAMAS_OK;
 }
 
+template <int G, bool FUSED, int METRIC>
+void launch_scan_gm(const Plan& pl, dim3 grid, hipStream_t st, const ScanParams& sp) {
+  switch (pl.tile_tokens) {
+    case 1024: hipLaunchKernelGGL((scan_kernel<G, FUSED, 4, METRIC>), grid, dim3(256), 0, st, sp); break;
+    case 2048: hipLaunchKernelGGL((scan_kernel<G, FUSED, 8, METRIC>), grid, dim3(512), 0, st, sp); break;
+    default: hipLaunchKernelGGL((scan_kernel<G, FUSED, 16, METRIC>), grid, dim3(1024), 0, st, sp); break;
+  }
+}
+
 template <int G, bool FUSED>
 void launch_scan_g(const Plan& pl, dim3 grid, hipStream_t st, const ScanParams& sp) {
-  switch (pl.tile_tokens) {
-    case 1024: hipLaunchKernelGGL((scan_kernel<G, FUSED, 4>), grid, dim3(256), 0, st, sp); break;
-    case 2048: hipLaunchKernelGGL((scan_kernel<G, FUSED, 8>), grid, dim3(512), 0, st, sp); break;
-    default: hipLaunchKernelGGL((scan_kernel<G, FUSED, 16>), grid, dim3(1024), 0, st, sp); break;
-  }
+  if (pl.metric == kMetricL2) launch_scan_gm<G, FUSED, kMetricL2>(pl, grid, st, sp);
+  else launch_scan_gm<G, FUSED, kMetricL1>(pl, grid, st, sp);
 }
 
 // pl.tile_tokens is 1024, 2048 or 4096 (make_plan).
@@ -219,7 +232,7 @@ int adamas_encode_keys(const adamas_config* cfg, const void* K, void* codes, int
   const int grid = (int)(want < 16384 ? want : 16384);
   hipLaunchKernelGGL(encode_rows_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream,
                      static_cast<const uint16_t*>(K), static_cast<uint8_t*>(codes),
-                     cfg->pool_tokens, row_begin, n_rows, n_vec, scaled(cfg->thr_k));
+                     cfg->pool_tokens, row_begin, n_rows, n_vec, scaled(cfg, cfg->thr_k));
   return launch_status();
 }
 
@@ -235,7 +248,7 @@ int adamas_encode_query(const adamas_config* cfg, const void* q, void* qcodes, i
   // queries form one "head" of n_vec consecutive rows
   hipLaunchKernelGGL(encode_rows_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream,
                      static_cast<const uint16_t*>(q), static_cast<uint8_t*>(qcodes), (int64_t)0,
-                     (int64_t)0, n_vec, n_vec, scaled(cfg->thr_q));
+                     (int64_t)0, n_vec, n_vec, scaled(cfg, cfg->thr_q));
   return launch_status();
 }
 
@@ -312,8 +325,12 @@ int adamas_select_topk(const adamas_config* cfg, const void* qcodes, const void*
   sl.n_tiles = pl.n_tiles;
   sl.tile_tokens = pl.tile_tokens;
   sl.seg_len = pl.seg_len;
-  hipLaunchKernelGGL((select_kernel<kSelThreads, false>), dim3(pl.n_segs, cfg->num_q_heads, batch),
-                     dim3(kSelThreads), 0, st, sl);
+  if (pl.metric == kMetricL2)
+    hipLaunchKernelGGL((select_kernel<kSelThreads, false, kMetricL2>),
+                       dim3(pl.n_segs, cfg->num_q_heads, batch), dim3(kSelThreads), 0, st, sl);
+  else
+    hipLaunchKernelGGL((select_kernel<kSelThreads, false, kMetricL1>),
+                       dim3(pl.n_segs, cfg->num_q_heads, batch), dim3(kSelThreads), 0, st, sl);
   return launch_status();
 }
 
@@ -410,8 +427,8 @@ int adamas_decode_step_stages(const adamas_config* cfg, const void* q, const voi
   sp.Hq = cfg->num_q_heads;
   sp.Hkv = cfg->num_kv_heads;
   sp.n_tiles = pl.n_tiles;
-  sp.thr_q = scaled(cfg->thr_q);
-  sp.thr_k = scaled(cfg->thr_k);
+  sp.thr_q = scaled(cfg, cfg->thr_q);
+  sp.thr_k = scaled(cfg, cfg->thr_k);
   // segment counters live in the unused words of each head's first partial slot
   sp.arrivals = reinterpret_cast<uint32_t*>(ws_at(workspace, pl.off_partial)) + 2;
   sp.arrivals_stride = (int64_t)kMaxParts * kPartialStride;
@@ -444,8 +461,12 @@ int adamas_decode_step_stages(const adamas_config* cfg, const void* q, const voi
   sl.tile_tokens = pl.tile_tokens;
   sl.seg_len = pl.seg_len;
   sl.scale_log2e = scale_log2e(cfg);
-  hipLaunchKernelGGL((select_kernel<kSelThreads, true>), dim3(pl.n_segs, cfg->num_q_heads, batch),
-                     dim3(kSelThreads), 0, st, sl);
+  if (pl.metric == kMetricL2)
+    hipLaunchKernelGGL((select_kernel<kSelThreads, true, kMetricL2>),
+                       dim3(pl.n_segs, cfg->num_q_heads, batch), dim3(kSelThreads), 0, st, sl);
+  else
+    hipLaunchKernelGGL((select_kernel<kSelThreads, true, kMetricL1>),
+                       dim3(pl.n_segs, cfg->num_q_heads, batch), dim3(kSelThreads), 0, st, sl);
   if (int rc = launch_status()) return rc;
   if (pl.n_segs == 1 || sl.arrivals != nullptr) return ADAMAS_OK;  // the select kernel wrote `out` itself
   MergeParams mp{};

@@ -8,8 +8,15 @@ namespace adamas {
 
 constexpr int kHeadDim = 128;
 constexpr int kRowBytes = 32;        // packed code row
-constexpr int kNumBins = 385;        // distances 0..384 (Eq. 6 on 128 two-bit codes)
-constexpr int kHistStride = 392;     // uint16 per stored tile histogram (784 B, 16-byte multiple)
+// Distance estimator between two code vectors: Eq. 6 (sum of |a - b|, 0..384)
+// or the squared-difference ablation of Section 4.4 (sum of (a - b)^2, 0..1152).
+constexpr int kMetricL1 = 0, kMetricL2 = 1;
+template <int METRIC>
+struct Dist {
+  static constexpr int kBins = METRIC == kMetricL1 ? 385 : 1153;  // distinct distance values
+  // uint16 per stored tile histogram, a 16-byte multiple: 392 (784 B) / 1160 (2320 B)
+  static constexpr int kStride = (kBins + 7) / 8 * 8;
+};
 constexpr int kPartialStride = 132;  // floats per attention partial: m, l, pad, pad, o[128]
 constexpr int kWave = 64;
 

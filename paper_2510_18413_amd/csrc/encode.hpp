@@ -7,10 +7,13 @@
 
 namespace adamas {
 
-// Thresholds already multiplied by sqrt(128): the kernels compare the
-// unnormalised +-1 sums against them.
+// Thresholds as the kernels compare against them: multiplied by sqrt(128)
+// when the vector is transformed (the kernels form the unnormalised +-1 sums),
+// as given for the ablation without the transform (Section 4.4), which applies
+// Eq. 5 to the raw vector (transform == 0).
 struct Thresholds {
   double tau[3];
+  int transform;
 };
 
 // One wave64 encodes one vector.  Lane l holds x[l] and x[l+64]; the
@@ -27,18 +30,20 @@ __device__ __forceinline__ void encode_values_wave(uint32_t bits_lo, uint32_t bi
   const int lane = threadIdx.x & 63;
   double a = (double)bf16_bits_to_float(bits_lo);
   double b = (double)bf16_bits_to_float(bits_hi);
-  {
-    double s = a + b, d = a - b;
-    a = s;
-    b = d;
-  }
+  if (thr.transform) {
+    {
+      double s = a + b, d = a - b;
+      a = s;
+      b = d;
+    }
 #pragma unroll
-  for (int h = 1; h < 64; h <<= 1) {
-    double pa = __shfl_xor(a, h, kWave);
-    double pb = __shfl_xor(b, h, kWave);
-    const bool upper = (lane & h) != 0;
-    a = upper ? pa - a : a + pa;
-    b = upper ? pb - b : b + pb;
+    for (int h = 1; h < 64; h <<= 1) {
+      double pa = __shfl_xor(a, h, kWave);
+      double pb = __shfl_xor(b, h, kWave);
+      const bool upper = (lane & h) != 0;
+      a = upper ? pa - a : a + pa;
+      b = upper ? pb - b : b + pb;
+    }
   }
   // Nested indicator masks m1 >= m2 >= m3 of Eq. 5; code = m1 + m2 + m3, so
   // the high bit is m2 and the low bit is the parity m1 ^ m2 ^ m3.
@@ -128,26 +133,28 @@ __global__ __launch_bounds__(256) void encode_rows_kernel(const uint16_t* __rest
         x[i * 8 + 2 * e + 1] = (double)bf16_hi(w[e]);
       }
     }
-    // index bits 0..4: inside the lane
+    if (thr.transform) {
+      // index bits 0..4: inside the lane
 #pragma unroll
-    for (int h = 1; h < 32; h <<= 1) {
+      for (int h = 1; h < 32; h <<= 1) {
 #pragma unroll
-      for (int i = 0; i < 32; ++i) {
-        if ((i & h) == 0) {
-          const double a = x[i], b = x[i + h];
-          x[i] = a + b;
-          x[i + h] = a - b;
+        for (int i = 0; i < 32; ++i) {
+          if ((i & h) == 0) {
+            const double a = x[i], b = x[i + h];
+            x[i] = a + b;
+            x[i + h] = a - b;
+          }
         }
       }
-    }
-    // index bits 5 and 6: across the quad
+      // index bits 5 and 6: across the quad
 #pragma unroll
-    for (int s = 0; s < 2; ++s) {
-      const bool upper = ((j >> s) & 1) != 0;
+      for (int s = 0; s < 2; ++s) {
+        const bool upper = ((j >> s) & 1) != 0;
 #pragma unroll
-      for (int i = 0; i < 32; ++i) {
-        const double partner = dpp_quad_xor_f64(x[i], s == 1);
-        x[i] = upper ? partner - x[i] : x[i] + partner;
+        for (int i = 0; i < 32; ++i) {
+          const double partner = dpp_quad_xor_f64(x[i], s == 1);
+          x[i] = upper ? partner - x[i] : x[i] + partner;
+        }
       }
     }
     // Eq. 5 on the lane's 32 coefficients: nested indicator masks m1 >= m2 >= m3,

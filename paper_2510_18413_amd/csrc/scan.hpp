@@ -7,7 +7,7 @@
 // group on it, so every code row is fetched once.  It writes
 //   - one uint16 distance per (query head, token) (staged through LDS so that
 //     stores are 8 bytes per lane), and
-//   - one 385-bin histogram of those distances per (query head, tile),
+//   - one histogram of those distances (385 bins for Eq. 6) per (query head, tile),
 // both with plain stores: nothing needs zero-initialised memory and the
 // result does not depend on the order workgroups run in.
 //
@@ -17,6 +17,8 @@
 // (x_hi = 0: the codes differ by x_lo; x_hi = 1, x_lo = 0: by 2; both set:
 // by 3 when the query code is 0 or 3 (g = 0), by 1 when it is 1 or 2), so a
 // 32-coefficient word costs two xor, one and, one and-not and two popcounts.
+// The squared-difference variant (Section 4.4) needs one more and + popcount:
+//   (a - b)^2 = x_lo + 4 * u + 4 * (u & x_lo),  u = x_hi & ~(x_lo & g).
 #pragma once
 
 #include "device_utils.hpp"
@@ -42,7 +44,7 @@ struct ScanParams {
   int64_t dist_stride;
   uint16_t* dist_user;       // optional second copy, [B*Hq][dist_user_stride]
   int64_t dist_user_stride;
-  uint16_t* tilehist;        // [B*Hq][n_tiles][kHistStride]; may be null
+  uint16_t* tilehist;        // [B*Hq][n_tiles][Dist<METRIC>::kStride]; may be null
   uint32_t* arrivals;        // per-head counter at [head * arrivals_stride], zeroed here; may be null
   int64_t arrivals_stride;
   int64_t pool_tokens, max_seq_len;
@@ -51,8 +53,9 @@ struct ScanParams {
 };
 
 // WAVES = wavefronts per workgroup (4, 8 or 16): the tile is WAVES * 256 tokens.
-template <int G, bool FUSED, int WAVES>
+template <int G, bool FUSED, int WAVES, int METRIC>
 __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p) {
+  constexpr int kNumBins = Dist<METRIC>::kBins, kHistStride = Dist<METRIC>::kStride;
   __shared__ uint32_t s_hist[G][kHistReplicas][kNumBins];
   __shared__ uint32_t s_q[G][12];   // per query head: lo[4], hi[4], lo^hi[4]
   __shared__ uint32_t s_new[8];     // code row of the appended key
@@ -220,14 +223,16 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
     }
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-      uint32_t c1 = 0, c2 = 0;
+      uint32_t c1 = 0, c2 = 0, c3 = 0;
 #pragma unroll
       for (int wd = 0; wd < 4; ++wd) {
         const uint32_t xl = klo[wd] ^ qlo[g][wd], xh = khi[wd] ^ qhi[g][wd];
+        const uint32_t u = xh & ~(xl & qg[g][wd]);
         c1 += __popc(xl);
-        c2 += __popc(xh & ~(xl & qg[g][wd]));
+        c2 += __popc(u);
+        if constexpr (METRIC == kMetricL2) c3 += __popc(u & xl);
       }
-      const uint32_t d = c1 + 2u * c2;
+      const uint32_t d = METRIC == kMetricL1 ? c1 + 2u * c2 : c1 + 4u * (c2 + c3);
       s_dt[wave][g][i * kWave + lane] = (uint16_t)d;
       if (t < L) {
         const int64_t head = head0 + g;

@@ -1,7 +1,8 @@
 // Top-k selection from the scan's distances and tile histograms (Algorithm 1
 // line 6) and softmax attention over the selected rows (lines 7-8, Eq. 1).
 //
-// Selection without sorting.  Distances take 385 values, so the k-th smallest
+// Selection without sorting.  Distances take few values (385 for Eq. 6, 1153
+// for the squared-difference variant), so the k-th smallest
 // is found from the head's histogram: T = smallest distance whose cumulative
 // count reaches kk = min(k, L).  Every token with distance < T is selected,
 // plus the first r = kk - #{D < T} tokens (in token order) with distance == T:
@@ -28,7 +29,6 @@
 namespace adamas {
 
 constexpr int kSelTokPerThread = 16;
-constexpr int kHistPairs = kHistStride / 2;  // 196 pairs of uint16 histogram bins
 constexpr int kHistBatch = 16;               // tiles whose histograms are loaded together
 constexpr int kMaxParts = 16;  // attention partial slots per head in the workspace
 constexpr int kMaxK = 4096;
@@ -37,7 +37,7 @@ constexpr float kNegBig = -1.0e30f;
 struct SelectParams {
   const uint16_t* dist;       // [B*Hq][dist_stride]
   int64_t dist_stride;
-  const uint16_t* tilehist;   // [B*Hq][n_tiles][kHistStride]
+  const uint16_t* tilehist;   // [B*Hq][n_tiles][Dist<METRIC>::kStride]
   const int64_t* seq_start;   // [B]
   const int32_t* seq_len;     // [B]
   int32_t* idx_out;           // [B*Hq][k] or null
@@ -198,11 +198,15 @@ __device__ __forceinline__ void attention_rows(const int32_t* s_sel, int n, int 
 // tokens is finished by that workgroup; otherwise each workgroup leaves an
 // (M, lsum, o[128]) partial, merged by the last one to arrive (p.arrivals set)
 // or by merge_kernel (p.arrivals null).
-template <int THREADS, bool ATTN>
+template <int THREADS, bool ATTN, int METRIC>
 __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
-  static_assert(THREADS >= kHistPairs, "one thread per pair of histogram bins");
+  constexpr int kNumBins = Dist<METRIC>::kBins, kHistStride = Dist<METRIC>::kStride;
+  constexpr int kHistPairs = kHistStride / 2;                      // pairs of uint16 bins per stored row
+  constexpr int PP = (kHistPairs + THREADS - 1) / THREADS;         // pairs owned by one thread
+  constexpr int BPL = (kNumBins + kWave - 1) / kWave;              // bins per lane in the threshold search
+  constexpr int kTot = BPL * kWave;
   constexpr int PASS = THREADS * kSelTokPerThread;           // tokens per pass
-  __shared__ uint32_t s_tot[448];
+  __shared__ uint32_t s_tot[kTot];
   __shared__ uint32_t s_scan[THREADS / kWave];
   __shared__ int32_t s_T, s_cntlt;
   __shared__ uint32_t s_ltb, s_eqb;
@@ -237,14 +241,21 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
       nxt_a = nxt_b = make_uint4(0, 0, 0, 0);
     }
   }
-  // Tile histograms: thread t < 196 owns bins 2t and 2t+1 (one 32-bit load per tile).
+  // Tile histograms: a thread owns PP pairs of bins, pair tid + j * THREADS (one
+  // 32-bit load per pair and tile); pairs past the row repeat its last pair.
   const uint16_t* hrow = p.tilehist + head * p.n_tiles * kHistStride;
   const int first_tile = seg_t0 / p.tile_tokens;
-  const int pair = min(tid, kHistPairs - 1);  // clamped: spare threads repeat the last pair
-  uint32_t hv[kHistBatch];
+  int pair[PP];
 #pragma unroll
-  for (int u = 0; u < kHistBatch; ++u)  // clamped, branch-free: all loads in flight together
-    hv[u] = reinterpret_cast<const uint32_t*>(hrow + (int64_t)min(u, p.n_tiles - 1) * kHistStride)[pair];
+  for (int j = 0; j < PP; ++j) pair[j] = min(tid + j * THREADS, kHistPairs - 1);
+  uint32_t hv[PP][kHistBatch];
+#pragma unroll
+  for (int u = 0; u < kHistBatch; ++u) {  // clamped, branch-free: all loads in flight together
+    const uint32_t* trow =
+        reinterpret_cast<const uint32_t*>(hrow + (int64_t)min(u, p.n_tiles - 1) * kHistStride);
+#pragma unroll
+    for (int j = 0; j < PP; ++j) hv[j][u] = trow[pair[j]];
+  }
 
   const int L = safe_seq_len(p.seq_len, p.seq_start, b, p.max_seq_len, p.pool_tokens);
   const int kk = min(p.k, L);
@@ -254,30 +265,44 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
   const int tiles_active = (L + p.tile_tokens - 1) / p.tile_tokens;
 
   // Head histogram (all tiles with tokens) and the part of it before this segment.
-  uint32_t tot0 = 0, tot1 = 0, pre0 = 0, pre1 = 0;
+  uint32_t tot0[PP], tot1[PP], pre0[PP], pre1[PP];
+#pragma unroll
+  for (int j = 0; j < PP; ++j) tot0[j] = tot1[j] = pre0[j] = pre1[j] = 0;
   for (int tb = 0; tb < tiles_active; tb += kHistBatch) {
     if (tb > 0) {
 #pragma unroll
-      for (int u = 0; u < kHistBatch; ++u)
-        hv[u] = reinterpret_cast<const uint32_t*>(
-            hrow + (int64_t)min(tb + u, p.n_tiles - 1) * kHistStride)[pair];
+      for (int u = 0; u < kHistBatch; ++u) {
+        const uint32_t* trow = reinterpret_cast<const uint32_t*>(
+            hrow + (int64_t)min(tb + u, p.n_tiles - 1) * kHistStride);
+#pragma unroll
+        for (int j = 0; j < PP; ++j) hv[j][u] = trow[pair[j]];
+      }
     }
 #pragma unroll
     for (int u = 0; u < kHistBatch; ++u) {
-      const uint32_t v = tb + u < tiles_active ? hv[u] : 0u;
-      tot0 += v & 0xffffu;
-      tot1 += v >> 16;
-      if (tb + u < first_tile) {
-        pre0 += v & 0xffffu;
-        pre1 += v >> 16;
+#pragma unroll
+      for (int j = 0; j < PP; ++j) {
+        const uint32_t v = tb + u < tiles_active ? hv[j][u] : 0u;
+        tot0[j] += v & 0xffffu;
+        tot1[j] += v >> 16;
+        if (tb + u < first_tile) {
+          pre0[j] += v & 0xffffu;
+          pre1[j] += v >> 16;
+        }
       }
     }
   }
-  const int bin0 = 2 * tid, bin1 = 2 * tid + 1;  // meaningful for tid < kHistPairs
-  for (int i = tid; i < 448 / 2; i += THREADS) {
-    s_tot[2 * i] = (i == tid && tid < kHistPairs && bin0 < kNumBins) ? tot0 : 0u;
-    s_tot[2 * i + 1] = (i == tid && tid < kHistPairs && bin1 < kNumBins) ? tot1 : 0u;
+  // Head histogram into LDS: a thread writes the bins of its pairs (bins past
+  // kNumBins hold nothing and count as zero), the tail up to kTot is cleared.
+#pragma unroll
+  for (int j = 0; j < PP; ++j) {
+    const int pr = tid + j * THREADS;
+    if (pr < kHistPairs) {
+      s_tot[2 * pr] = 2 * pr < kNumBins ? tot0[j] : 0u;
+      s_tot[2 * pr + 1] = 2 * pr + 1 < kNumBins ? tot1[j] : 0u;
+    }
   }
+  for (int i = kHistStride + tid; i < kTot; i += THREADS) s_tot[i] = 0u;
   if (tid == 0) {
     s_ltb = 0u;
     s_eqb = 0u;
@@ -286,21 +311,21 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
   }
   __syncthreads();
 
-  // Threshold distance T and #{D < T}, by one wave: 7 bins per lane.
+  // Threshold distance T and #{D < T}, by one wave: BPL bins per lane.
   if (tid < kWave) {
-    uint32_t c[7], sum = 0;
+    uint32_t c[BPL], sum = 0;
 #pragma unroll
-    for (int j = 0; j < 7; ++j) {
-      c[j] = s_tot[lane * 7 + j];
+    for (int j = 0; j < BPL; ++j) {
+      c[j] = s_tot[lane * BPL + j];
       sum += c[j];
     }
     const uint32_t incl = wave_incl_scan_u32(sum);
     uint32_t run = incl - sum;
     if (kk > 0 && run < (uint32_t)kk && incl >= (uint32_t)kk) {
 #pragma unroll
-      for (int j = 0; j < 7; ++j) {
+      for (int j = 0; j < BPL; ++j) {
         if (run < (uint32_t)kk && run + c[j] >= (uint32_t)kk) {
-          s_T = lane * 7 + j;
+          s_T = lane * BPL + j;
           s_cntlt = (int32_t)run;
         }
         run += c[j];
@@ -313,9 +338,13 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
 
   if (gridDim.x > 1) {  // tokens of earlier segments: #{D < T} and #{D == T}
     uint32_t ltb = 0, eqb = 0;
-    if (tid < kHistPairs) {
-      ltb = (bin0 < T ? pre0 : 0u) + (bin1 < T ? pre1 : 0u);
-      eqb = (bin0 == T ? pre0 : 0u) + (bin1 == T ? pre1 : 0u);
+#pragma unroll
+    for (int j = 0; j < PP; ++j) {
+      const int pr = tid + j * THREADS, bin0 = 2 * pr, bin1 = 2 * pr + 1;
+      if (pr < kHistPairs) {
+        ltb += (bin0 < T ? pre0[j] : 0u) + (bin1 < T ? pre1[j] : 0u);
+        eqb += (bin0 == T ? pre0[j] : 0u) + (bin1 == T ? pre1[j] : 0u);
+      }
     }
     ltb = wave_sum_u32(ltb);
     eqb = wave_sum_u32(eqb);

@@ -26,9 +26,10 @@ def host_dist(t: torch.Tensor) -> np.ndarray:
 class DeviceCase:
     """Device copies of a DecodeCase plus config, workspace and output buffers."""
 
-    def __init__(self, case, k, encode=True):
+    def __init__(self, case, k, encode=True, variant=0):
         self.case, self.k = case, k
-        self.cfg = A.Config.make(case.Hq, case.Hkv, case.pool_tokens, thr_k=case.thresholds)
+        self.cfg = A.Config.make(case.Hq, case.Hkv, case.pool_tokens, thr_k=case.thresholds,
+                                 variant=variant)
         self.q = dev_bf16(case.q)
         self.K = dev_bf16(case.K)
         self.V = dev_bf16(case.V)
@@ -56,13 +57,17 @@ class DeviceCase:
         return self.out.cpu().numpy(), self.idx.cpu().numpy()
 
 
-def oracle_step(case, k, want_dist=True):
-    """The oracle's answer for the whole step.  Returns dict(out, idx, dist, K, V, rows)."""
+def oracle_step(case, k, want_dist=True, variant=0):
+    """The oracle's answer for the whole step.  Returns dict(out, idx, dist, K, V, rows).
+    variant: the library's ADAMAS_VARIANT_* flags, mapped onto the oracle's two switches."""
+    hadamard = not (variant & A.VARIANT_NO_HADAMARD)
+    squared = bool(variant & A.VARIANT_L2)
     K, V = case.K.copy(), case.V.copy()
-    _, rows = oracle.encode(K, case.thresholds)
+    _, rows = oracle.encode(K, case.thresholds, hadamard=hadamard)
     out, idx, dist = oracle.decode_step(case.q, K, V, rows, case.seq_start, case.seq_len, k,
                                         case.thresholds, case.thresholds, SM_SCALE,
-                                        k_new=case.k_new, v_new=case.v_new, want_dist=want_dist)
+                                        k_new=case.k_new, v_new=case.v_new, want_dist=want_dist,
+                                        hadamard=hadamard, squared=squared)
     return dict(out=out, idx=idx, dist=dist, K=K, V=V, rows=rows)
 
 

@@ -66,6 +66,7 @@ def test_workspace_bytes():
     (dict(sm_scale=-1.0), -1),
     (dict(sm_scale=float("inf")), -1),
     (dict(num_q_heads=32, num_kv_heads=2), -2),        # group of 16 > ADAMAS_MAX_GROUP
+    (dict(variant=4), -2),                             # unknown variant bit
 ])
 def test_bad_config_rejected_everywhere(bad, status):
     lib, c = A.library(), cfg(**bad)

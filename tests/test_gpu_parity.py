@@ -341,6 +341,85 @@ def test_invalid_device_lengths_are_treated_as_empty(H, oracle):
     assert np.array_equal(idx[0], ref["idx"][0])
 
 
+# ------------------------------------------------------- ablation variants (Section 4.4)
+
+@pytest.mark.parametrize("variant", [1, 2, 3])      # NO_HADAMARD, L2, both
+@pytest.mark.parametrize("B,Hq,Hkv,lens,k,append", [
+    (1, 1, 1, [1024], 64, False),
+    (2, 8, 2, [4097, 333], 128, True),
+    (3, 4, 4, [0, 5000, 9000], 256, False),
+    (1, 8, 1, [20000], 1024, True),
+])
+def test_variant_decode_step_matches_oracle(H, oracle, variant, B, Hq, Hkv, lens, k, append):
+    """Every stage of the step under the ablation switches: code bytes, distances (through
+    adamas_select_topk's optional output), indices bit for bit; attention within tolerance."""
+    import paper_2510_18413_amd as A
+    case = small_case(800 + variant + Hq, B, Hq, Hkv, lens, append=append)
+    d = H.DeviceCase(case, k, variant=variant)
+    hadamard = not (variant & A.VARIANT_NO_HADAMARD)
+    _, rows0 = oracle.encode(case.K, case.thresholds, hadamard=hadamard)
+    assert np.array_equal(d.codes.cpu().numpy(), rows0)                   # bulk key encode
+    qcodes = torch.zeros(B, Hq, 32, dtype=torch.uint8, device="cuda")
+    A.adamas_encode_query(d.cfg, d.q, qcodes)
+    torch.cuda.synchronize()
+    _, qrows = oracle.encode(case.q, case.thresholds, hadamard=hadamard)
+    assert np.array_equal(qcodes.cpu().numpy(), qrows)
+    out, idx = d.decode_step()
+    ref = H.oracle_step(case, k, want_dist=True, variant=variant)
+    assert np.array_equal(idx, ref["idx"])
+    assert H.attn_rel_err(out, ref["out"]) <= H.ATTN_TOL
+    if append:
+        assert np.array_equal(d.codes.cpu().numpy(), ref["rows"])
+        assert np.array_equal(H.host_u16(d.K), ref["K"])
+    # stand-alone select on the updated cache: distances and indices once more
+    dist = torch.full((B, Hq, d.max_len), 0xFFFF, dtype=torch.uint16, device="cuda")
+    idx2 = torch.full((B, Hq, k), -7, dtype=torch.int32, device="cuda")
+    A.adamas_select_topk(d.cfg, qcodes, d.codes, d.seq_start, d.seq_len, k, idx2, d.max_len,
+                         d.workspace, dist_out=dist)
+    torch.cuda.synchronize()
+    got = H.host_dist(dist)
+    for b in range(B):
+        L = int(case.seq_len[b])
+        assert np.array_equal(got[b, :, :L], ref["dist"][b, :, :L])
+    assert np.array_equal(idx2.cpu().numpy(), ref["idx"])
+
+
+def test_variant_l2_extreme_distances(H, oracle):
+    """All-0 against all-3 codes: 1152, the largest squared distance, and ties everywhere."""
+    import paper_2510_18413_amd as A
+    case = small_case(850, 1, 1, 1, [3000], needles=0)
+    case.K[:] = synth.f32_to_bf16_bits(np.full(case.K.shape, 0.0, np.float32))
+    case.K[0, :, 0] = int(synth.f32_to_bf16_bits(np.float32([64.0]))[0])    # every coefficient = +64
+    case.q[:] = 0
+    case.q[0, 0, 0] = int(synth.f32_to_bf16_bits(np.float32([-64.0]))[0])   # every coefficient = -64
+    d = H.DeviceCase(case, 32, variant=A.VARIANT_L2)
+    out, idx = d.decode_step()
+    ref = H.oracle_step(case, 32, want_dist=True, variant=A.VARIANT_L2)
+    assert int(ref["dist"].max()) == 1152
+    assert np.array_equal(idx, ref["idx"]) and idx[0, 0].tolist() == list(range(32))
+    assert H.attn_rel_err(out, ref["out"]) <= H.ATTN_TOL
+
+
+def test_variant_without_hadamard_loses_the_true_top_k(H, oracle):
+    """Direction of the paper's ablation (Section 4.4, Table 7) on the synthetic outlier data:
+    without the transform the selected set overlaps the exact attention top-k far less."""
+    import paper_2510_18413_amd as A
+    case = small_case(860, 1, 4, 4, [8192], needles=8)
+    k = 256
+    overlap = {}
+    for variant in (0, A.VARIANT_NO_HADAMARD):
+        d = H.DeviceCase(case, k, variant=variant)
+        _, idx = d.decode_step()
+        q = synth.bf16_bits_to_f32(case.q[0]).astype(np.float64)
+        K = synth.bf16_bits_to_f32(case.K[:, :8192]).astype(np.float64)
+        ov = []
+        for h in range(4):
+            true_top = np.argsort(-(K[h] @ q[h]), kind="stable")[:k]
+            ov.append(len(set(true_top.tolist()) & set(idx[0, h].tolist())) / k)
+        overlap[variant] = float(np.mean(ov))
+    assert overlap[0] > 0.3 and overlap[0] > 2.0 * overlap[A.VARIANT_NO_HADAMARD], overlap
+
+
 def test_decode_step_random_shapes(H, oracle):
     """Seeded sweep over batch, group size, lengths, budgets, thresholds, scale and append:
     every case against the oracle."""

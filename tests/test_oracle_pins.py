@@ -345,6 +345,27 @@ def test_decode_step_variants_compose_their_stages(oracle):
                 assert np.array_equal(out[b, h], ref)
 
 
+def test_without_hadamard_the_selection_misses_the_true_top_k(oracle):
+    """Direction of the paper's ablation (Section 4.4) on the synthetic outlier data: the set
+    selected without the transform overlaps the exact attention top-k far less."""
+    case = synth.make_case("t", 861, 1, 4, 4, [4096], [0],
+                           lambda b, L, h, rng: rng.choice(L, (1, 8), replace=False))
+    k, overlap = 128, {}
+    q = widen(case.q[0])
+    K = widen(case.K[:, :4096])
+    for hadamard in (True, False):
+        _, rows = oracle.encode(case.K, case.thresholds, hadamard=hadamard)
+        _, idx, _ = oracle.decode_step(case.q, case.K.copy(), case.V.copy(), rows, case.seq_start,
+                                       case.seq_len, k, case.thresholds, case.thresholds,
+                                       1 / np.sqrt(128.0), hadamard=hadamard)
+        ov = []
+        for h in range(4):
+            true_top = np.argsort(-(K[h] @ q[h]), kind="stable")[:k]
+            ov.append(len(set(true_top.tolist()) & set(idx[0, h].tolist())) / k)
+        overlap[hadamard] = float(np.mean(ov))
+    assert overlap[True] > 0.25 and overlap[True] > 2.0 * overlap[False], overlap
+
+
 # ----------------------------------------------------------------------------------- top-k
 
 def test_topk_exhaustive_subsets(oracle):
