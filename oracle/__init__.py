@@ -50,7 +50,8 @@ def lib() -> ctypes.CDLL:
                      "oracle_pack_row", "oracle_unpack_row", "oracle_encode", "oracle_manhattan",
                      "oracle_topk", "oracle_sparse_attention", "oracle_full_attention",
                      "oracle_decode_step", "oracle_max_threads", "oracle_encode_variant",
-                     "oracle_squared_distance", "oracle_decode_step_variant"):
+                     "oracle_squared_distance", "oracle_decode_step_variant",
+                     "oracle_decode_step_paged"):
             getattr(_lib, name).restype = ctypes.c_int
         _lib.oracle_set_threads.restype = None
         _lib.oracle_sparse_attention.argtypes = [ctypes.c_void_p] * 4 + [
@@ -62,6 +63,11 @@ def lib() -> ctypes.CDLL:
             ctypes.c_double] + [ctypes.c_void_p] * 8 + [ctypes.c_int32, ctypes.c_int32] + [
             ctypes.c_void_p] * 3 + [ctypes.c_int64]
         _lib.oracle_decode_step_variant.argtypes = _lib.oracle_decode_step.argtypes + [
+            ctypes.c_int, ctypes.c_int]
+        _lib.oracle_decode_step_paged.argtypes = [
+            ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_double] + [ctypes.c_void_p] * 7 + [ctypes.c_int32, ctypes.c_int32,
+            ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_int, ctypes.c_int]
         _lib.oracle_encode_variant.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p,
                                                ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
@@ -252,3 +258,30 @@ def decode_step(q, K, V, code_rows, seq_start, seq_len, k, thr_q, thr_k, scale,
         _p(idx), _p(dist), max(max_len, 1), 1 if hadamard else 0, 1 if squared else 0)
     _check(rc, "decode_step")
     return out, idx, dist
+
+
+def decode_step_paged(q, K, V, code_rows, page_table, page_tokens, seq_len, k, thr_q, thr_k, scale,
+                      k_new=None, v_new=None, hadamard=True, squared=False):
+    """The step on a paged cache: token t of sequence b lives in pool row
+    page_table[b, t // page_tokens] * page_tokens + t % page_tokens.  K, V, code_rows are
+    UPDATED IN PLACE on append.  Returns (out float32 [B,Hq,128], idx int32 [B,Hq,k])."""
+    q = np.ascontiguousarray(q, dtype=np.uint16)
+    B, Hq, _ = q.shape
+    Hkv, pool, _ = K.shape
+    for a, dt in ((K, np.uint16), (V, np.uint16), (code_rows, np.uint8)):
+        assert a.dtype == dt and a.flags.c_contiguous
+    page_table = np.ascontiguousarray(page_table, dtype=np.int32)
+    seq_len = np.ascontiguousarray(seq_len, dtype=np.int32)
+    assert page_table.ndim == 2 and page_table.shape[0] == B and seq_len.shape == (B,)
+    if k_new is not None:
+        k_new = np.ascontiguousarray(k_new, dtype=np.uint16)
+        v_new = np.ascontiguousarray(v_new, dtype=np.uint16)
+    out = np.zeros((B, Hq, D), dtype=np.float32)
+    idx = np.empty((B, Hq, k), dtype=np.int32)
+    rc = lib().oracle_decode_step_paged(
+        Hq, Hkv, pool, _p(_thr(thr_q)), _p(_thr(thr_k)), float(scale), _p(q), _p(k_new),
+        _p(v_new), _p(K), _p(V), _p(code_rows), _p(page_table), page_table.shape[1],
+        int(page_tokens), _p(seq_len), B, k, _p(out), _p(idx), 1 if hadamard else 0,
+        1 if squared else 0)
+    _check(rc, "decode_step_paged")
+    return out, idx

@@ -520,6 +520,84 @@ int oracle_decode_step_variant(int32_t Hq, int32_t Hkv, int64_t pool_tokens,
   return status;
 }
 
+/* ------------------------------------------------------- paged cache layout */
+
+/*
+ * The same step on a paged cache, the layout of the serving engines the paper
+ * compares with (Section 4.1).  The pools are cut into pages of page_tokens
+ * rows; token t of sequence b lives in pool row
+ *   page_table[b * max_pages + t / page_tokens] * page_tokens + t % page_tokens
+ * of every KV head.  Nothing new is computed: every sequence's rows are copied
+ * into a contiguous scratch cache through the page table, the contiguous step
+ * above runs on that copy, and the appended row (K, V, code row) is copied back
+ * to its page.  idx holds token positions, as in the contiguous step.
+ */
+int oracle_decode_step_paged(int32_t Hq, int32_t Hkv, int64_t pool_tokens,
+                             const float thr_q[3], const float thr_k[3], double scale,
+                             const uint16_t *q, const uint16_t *k_new,
+                             const uint16_t *v_new, uint16_t *K, uint16_t *V,
+                             uint8_t *code_rows, const int32_t *page_table,
+                             int32_t max_pages, int32_t page_tokens,
+                             const int32_t *seq_len, int32_t B, int32_t k, float *out,
+                             int32_t *idx, int use_hadamard, int squared_distance) {
+  if (Hq < 1 || Hkv < 1 || B < 1 || k < 1 || !page_table || max_pages < 1 || page_tokens < 1)
+    return ORACLE_BAD_ARG;
+  if (!q || !K || !V || !code_rows || !seq_len || !out || !idx) return ORACLE_BAD_ARG;
+  int64_t total = 0, max_len = 1;
+  for (int32_t b = 0; b < B; ++b) {
+    if (seq_len[b] < 0 || (int64_t)seq_len[b] > (int64_t)max_pages * page_tokens)
+      return ORACLE_BAD_ARG;
+    total += seq_len[b];
+    if (seq_len[b] > max_len) max_len = seq_len[b];
+  }
+  int64_t pool2 = total > 0 ? total : 1;
+  uint16_t *K2 = (uint16_t *)malloc((size_t)Hkv * pool2 * ORACLE_D * sizeof(uint16_t));
+  uint16_t *V2 = (uint16_t *)malloc((size_t)Hkv * pool2 * ORACLE_D * sizeof(uint16_t));
+  uint8_t *R2 = (uint8_t *)malloc((size_t)Hkv * pool2 * ORACLE_ROW_BYTES);
+  int64_t *start2 = (int64_t *)malloc((size_t)B * sizeof(int64_t));
+  if (!K2 || !V2 || !R2 || !start2) {
+    free(K2); free(V2); free(R2); free(start2);
+    return ORACLE_NOMEM;
+  }
+  int rc = ORACLE_OK;
+  int64_t at = 0;
+  for (int32_t b = 0; b < B && rc == ORACLE_OK; ++b) {
+    start2[b] = at;
+    for (int64_t t = 0; t < seq_len[b]; ++t) {
+      int64_t page = page_table[(int64_t)b * max_pages + t / page_tokens];
+      int64_t row = page * page_tokens + t % page_tokens;
+      if (page < 0 || row >= pool_tokens) { rc = ORACLE_BAD_ARG; break; }
+      for (int32_t h = 0; h < Hkv; ++h) {
+        int64_t src = (int64_t)h * pool_tokens + row, dst = (int64_t)h * pool2 + at + t;
+        memcpy(K2 + dst * ORACLE_D, K + src * ORACLE_D, ORACLE_D * sizeof(uint16_t));
+        memcpy(V2 + dst * ORACLE_D, V + src * ORACLE_D, ORACLE_D * sizeof(uint16_t));
+        memcpy(R2 + dst * ORACLE_ROW_BYTES, code_rows + src * ORACLE_ROW_BYTES, ORACLE_ROW_BYTES);
+      }
+    }
+    at += seq_len[b];
+  }
+  if (rc == ORACLE_OK)
+    rc = oracle_decode_step_variant(Hq, Hkv, pool2, thr_q, thr_k, scale, q, k_new, v_new, K2, V2,
+                                    R2, start2, seq_len, B, k, out, idx, NULL, max_len,
+                                    use_hadamard, squared_distance);
+  if (rc == ORACLE_OK && k_new) {
+    for (int32_t b = 0; b < B; ++b) {
+      if (seq_len[b] < 1) continue;
+      int64_t t = seq_len[b] - 1;
+      int64_t row = (int64_t)page_table[(int64_t)b * max_pages + t / page_tokens] * page_tokens +
+                    t % page_tokens;
+      for (int32_t h = 0; h < Hkv; ++h) {
+        int64_t dst = (int64_t)h * pool_tokens + row, src = (int64_t)h * pool2 + start2[b] + t;
+        memcpy(K + dst * ORACLE_D, K2 + src * ORACLE_D, ORACLE_D * sizeof(uint16_t));
+        memcpy(V + dst * ORACLE_D, V2 + src * ORACLE_D, ORACLE_D * sizeof(uint16_t));
+        memcpy(code_rows + dst * ORACLE_ROW_BYTES, R2 + src * ORACLE_ROW_BYTES, ORACLE_ROW_BYTES);
+      }
+    }
+  }
+  free(K2); free(V2); free(R2); free(start2);
+  return rc;
+}
+
 /* ---------------------------------------------------------- thread control */
 
 #ifdef _OPENMP

@@ -194,3 +194,43 @@ def batched_ragged(layer: int = 0, B: int = 16, lo: int = 8192, hi: int = 32768,
     lens = np.random.default_rng(config_seed(4, layer) + 500).integers(lo, hi + 1, size=B)
     return make_case("cfg4_batched", config_seed(4, layer), B, Hq, Hkv, lens, [k],
                      lambda b, Lc, h, rng: _distinct(rng, Lc, G, 1))
+
+
+@dataclass
+class PagedCase:
+    """A DecodeCase whose cache rows were scattered over fixed-size pages.  Token t of sequence b
+    lives in pool row page_table[b, t // page_tokens] * page_tokens + t % page_tokens of every
+    KV head; rows of pages that no sequence owns hold other (random) data."""
+    case: DecodeCase              # the contiguous original (its pools are not used on the device)
+    page_tokens: int
+    pool_tokens: int              # n_pages * page_tokens
+    K: np.ndarray                 # uint16 [Hkv, pool_tokens, 128], BEFORE the step's append
+    V: np.ndarray
+    page_table: np.ndarray        # int32 [B, max_pages]; -1 where a sequence has no page
+
+
+def paginate(case: DecodeCase, page_tokens: int, seed: int, spare_pages: int = 3) -> PagedCase:
+    """Scatters the sequences of `case` over randomly chosen pages (a pure re-layout: no value
+    changes).  Each sequence gets the pages its length AFTER the append needs."""
+    rng = np.random.default_rng(seed)
+    need = [(int(L) + page_tokens - 1) // page_tokens for L in case.seq_len]
+    n_pages = sum(need) + spare_pages
+    max_pages = max(1, max(need))
+    order = rng.permutation(n_pages)
+    pool = n_pages * page_tokens
+    K = f32_to_bf16_bits(rng.standard_normal((case.Hkv, pool, D), dtype=np.float32))
+    V = f32_to_bf16_bits(rng.standard_normal((case.Hkv, pool, D), dtype=np.float32))
+    table = np.full((case.B, max_pages), -1, dtype=np.int32)
+    at = 0
+    for b in range(case.B):
+        s, L = int(case.seq_start[b]), int(case.seq_len[b])
+        for pg in range(need[b]):
+            phys = int(order[at])
+            at += 1
+            table[b, pg] = phys
+            n = min(page_tokens, L - pg * page_tokens)
+            src = slice(s + pg * page_tokens, s + pg * page_tokens + n)
+            dst = slice(phys * page_tokens, phys * page_tokens + n)
+            K[:, dst] = case.K[:, src]
+            V[:, dst] = case.V[:, src]
+    return PagedCase(case, page_tokens, pool, K, V, table)

@@ -366,6 +366,54 @@ def test_without_hadamard_the_selection_misses_the_true_top_k(oracle):
     assert overlap[True] > 0.25 and overlap[True] > 2.0 * overlap[False], overlap
 
 
+# ------------------------------------------------------------------ paged cache layout
+
+def _paged_step(oracle, pc, k):
+    K, V = pc.K.copy(), pc.V.copy()
+    _, rows = oracle.encode(K, pc.case.thresholds)
+    out, idx = oracle.decode_step_paged(pc.case.q, K, V, rows, pc.page_table, pc.page_tokens,
+                                        pc.case.seq_len, k, pc.case.thresholds, pc.case.thresholds,
+                                        1 / np.sqrt(128.0), k_new=pc.case.k_new, v_new=pc.case.v_new)
+    return out, idx, K, V, rows
+
+
+@pytest.mark.parametrize("page_tokens,append", [(64, False), (64, True), (256, True)])
+def test_paged_step_is_the_contiguous_step_on_scattered_rows(oracle, page_tokens, append):
+    # 129 = 2 * 64 + 1: with an append the new token is the first row of a fresh page
+    case = synth.make_case("t", 90, 3, 4, 2, [300, 129, 64], [16],
+                           lambda b, L, h, rng: rng.choice(L, (2, 1), replace=False), append=append)
+    want_out, want_idx, _, Kc, Vc, rows_c = _step(oracle, case, 16)
+    pc = synth.paginate(case, page_tokens, seed=5)
+    out, idx, K, V, rows = _paged_step(oracle, pc, 16)
+    assert np.array_equal(idx, want_idx) and np.array_equal(out, want_out)
+    # cache contents after the step: every sequence's rows, read through the page table, equal
+    # the contiguous cache's; rows of pages nobody owns are untouched
+    touched = np.zeros(pc.pool_tokens, dtype=bool)
+    for b in range(3):
+        s, L = int(case.seq_start[b]), int(case.seq_len[b])
+        phys = pc.page_table[b, np.arange(L) // page_tokens].astype(np.int64) * page_tokens \
+            + np.arange(L) % page_tokens
+        touched[phys] = True
+        assert np.array_equal(K[:, phys], Kc[:, s:s + L]) and np.array_equal(V[:, phys], Vc[:, s:s + L])
+        assert np.array_equal(rows[:, phys], rows_c[:, s:s + L])
+    assert np.array_equal(K[:, ~touched], pc.K[:, ~touched])
+
+
+def test_paged_step_with_identity_table_on_a_contiguous_pool(oracle):
+    case = synth.make_case("t", 91, 1, 2, 2, [500], [16],
+                           lambda b, L, h, rng: rng.choice(L, (1, 1), replace=False))
+    assert int(case.seq_start[0]) == 0
+    want_out, want_idx, *_ = _step(oracle, case, 16)
+    n_pages = (case.pool_tokens + 63) // 64
+    pad = ((0, 0), (0, n_pages * 64 - case.pool_tokens), (0, 0))
+    K, V = np.pad(case.K, pad), np.pad(case.V, pad)
+    _, rows = oracle.encode(K, case.thresholds)
+    table = np.arange(n_pages, dtype=np.int32)[None]
+    out, idx = oracle.decode_step_paged(case.q, K, V, rows, table, 64, case.seq_len, 16,
+                                        case.thresholds, case.thresholds, 1 / np.sqrt(128.0))
+    assert np.array_equal(idx, want_idx) and np.array_equal(out, want_out)
+
+
 # ----------------------------------------------------------------------------------- top-k
 
 def test_topk_exhaustive_subsets(oracle):
