@@ -229,6 +229,29 @@ int adamas_decode_step_stages(const adamas_config *cfg, const void *q,
                               void *stream, uint32_t stages);
 
 /*
+ * adamas_decode_step on a PAGED cache, the layout of the serving engines the
+ * paper compares with (Section 4.1): the pools are cut into pages of
+ * page_tokens rows (a power of two, 64..4096; pool_tokens a multiple of it)
+ * and token t of sequence b lives in pool row
+ *     page_table[b * max_pages + t / page_tokens] * page_tokens + t % page_tokens
+ * of every KV head.  page_table: device int32 [batch][max_pages]; entries for
+ * pages a sequence does not use are never read beyond being clamped into the
+ * pool; an entry outside the pool is clamped into it (wrong rows, no fault).
+ * With an append the table must already name the page of the new token
+ * (position seq_len[b]-1).  idx_out holds token positions, as in
+ * adamas_decode_step.  max_seq_len <= max_pages * page_tokens.  Everything
+ * else (arguments, workspace size, errors, variants) as adamas_decode_step.
+ */
+int adamas_decode_step_paged(const adamas_config *cfg, const void *q,
+                             const void *k_new, const void *v_new, void *K,
+                             void *V, void *codes, const int32_t *page_table,
+                             int32_t max_pages, int32_t page_tokens,
+                             const int32_t *seq_len, int32_t batch, int32_t k,
+                             float *out, int32_t *idx_out, int64_t max_seq_len,
+                             void *workspace, size_t workspace_bytes,
+                             void *stream);
+
+/*
  * Comparison point, not a step of the method: Eq. 1 over ALL cached rows of
  * every sequence (dense decode attention), the baseline of the paper's
  * "self-attention speedup" (Sec. 4.3), so that both sides of that ratio can be

@@ -6,6 +6,7 @@ from .binding import (  # noqa: F401
     Config,
     EXPORTED_SYMBOLS,
     adamas_decode_step,
+    adamas_decode_step_paged,
     adamas_decode_step_stages,
     STAGE_ALL,
     STAGE_SCAN,

@@ -26,6 +26,7 @@ EXPORTED_SYMBOLS = (
     "adamas_decode_step",
     "adamas_decode_step_stages",
     "adamas_stream_read",
+    "adamas_decode_step_paged",
     "adamas_full_attn_workspace_bytes",
     "adamas_full_attn",
 )
@@ -104,6 +105,9 @@ def library() -> ctypes.CDLL:
         lib.adamas_decode_step.restype = ctypes.c_int
         lib.adamas_decode_step.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp,
                                            i64, vp, sz, vp]
+        lib.adamas_decode_step_paged.restype = ctypes.c_int
+        lib.adamas_decode_step_paged.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp,
+                                                 i32, i32, vp, vp, i64, vp, sz, vp]
         lib.adamas_full_attn_workspace_bytes.restype = sz
         lib.adamas_full_attn_workspace_bytes.argtypes = [cfgp, i32, i64]
         lib.adamas_full_attn.restype = ctypes.c_int
@@ -175,6 +179,29 @@ def adamas_encode_query(cfg: Config, q, qcodes, stream=None) -> None:
         _ptr(qcodes, torch.uint8, "qcodes", (batch, cfg.num_q_heads, CODE_ROW_BYTES)), batch,
         _stream(stream))
     _check(rc, "adamas_encode_query")
+
+
+def adamas_decode_step_paged(cfg: Config, q, K, V, codes, page_table, page_tokens: int, seq_len,
+                             k: int, out, max_seq_len: int, workspace, k_new=None, v_new=None,
+                             idx_out=None, stream=None) -> None:
+    import torch
+    batch = q.shape[0]
+    hkv, pool = cfg.num_kv_heads, cfg.pool_tokens
+    if page_table.dim() != 2 or page_table.shape[0] != batch:
+        raise ValueError("page_table must have shape (batch, max_pages)")
+    rc = library().adamas_decode_step_paged(
+        ctypes.byref(cfg), _ptr(q, torch.bfloat16, "q", (batch, cfg.num_q_heads, HEAD_DIM)),
+        _ptr(k_new, torch.bfloat16, "k_new", (batch, hkv, HEAD_DIM), optional=True),
+        _ptr(v_new, torch.bfloat16, "v_new", (batch, hkv, HEAD_DIM), optional=True),
+        _ptr(K, torch.bfloat16, "K", (hkv, pool, HEAD_DIM)),
+        _ptr(V, torch.bfloat16, "V", (hkv, pool, HEAD_DIM)),
+        _ptr(codes, torch.uint8, "codes", (hkv, pool, CODE_ROW_BYTES)),
+        _ptr(page_table, torch.int32, "page_table"), page_table.shape[1], int(page_tokens),
+        _ptr(seq_len, torch.int32, "seq_len", (batch,)), batch, k,
+        _ptr(out, torch.float32, "out", (batch, cfg.num_q_heads, HEAD_DIM)),
+        _ptr(idx_out, torch.int32, "idx_out", (batch, cfg.num_q_heads, k), optional=True),
+        max_seq_len, _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream))
+    _check(rc, "adamas_decode_step_paged")
 
 
 def adamas_full_attn_workspace_bytes(cfg: Config, batch: int, max_seq_len: int) -> int:

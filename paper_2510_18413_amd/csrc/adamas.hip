@@ -139,13 +139,24 @@ int launch_status() {
   return ADAMAS_OK;
 }
 
+template <int G, bool FUSED, int METRIC, bool PAGED>
+void launch_scan_gmp(const Plan& pl, dim3 grid, hipStream_t st, const ScanParams& sp) {
+  switch (pl.tile_tokens) {
+    case 1024: hipLaunchKernelGGL((scan_kernel<G, FUSED, 4, METRIC, PAGED>), grid, dim3(256), 0, st, sp); break;
+    case 2048: hipLaunchKernelGGL((scan_kernel<G, FUSED, 8, METRIC, PAGED>), grid, dim3(512), 0, st, sp); break;
+    default: hipLaunchKernelGGL((scan_kernel<G, FUSED, 16, METRIC, PAGED>), grid, dim3(1024), 0, st, sp); break;
+  }
+}
+
 template <int G, bool FUSED, int METRIC>
 void launch_scan_gm(const Plan& pl, dim3 grid, hipStream_t st, const ScanParams& sp) {
-  switch (pl.tile_tokens) {
-    case 1024: hipLaunchKernelGGL((scan_kernel<G, FUSED, 4, METRIC>), grid, dim3(256), 0, st, sp); break;
-    case 2048: hipLaunchKernelGGL((scan_kernel<G, FUSED, 8, METRIC>), grid, dim3(512), 0, st, sp); break;
-    default: hipLaunchKernelGGL((scan_kernel<G, FUSED, 16, METRIC>), grid, dim3(1024), 0, st, sp); break;
+  if constexpr (FUSED) {
+    if (sp.page_table != nullptr) {
+      launch_scan_gmp<G, FUSED, METRIC, true>(pl, grid, st, sp);
+      return;
+    }
   }
+  launch_scan_gmp<G, FUSED, METRIC, false>(pl, grid, st, sp);
 }
 
 template <int G, bool FUSED>
@@ -326,10 +337,10 @@ int adamas_select_topk(const adamas_config* cfg, const void* qcodes, const void*
   sl.tile_tokens = pl.tile_tokens;
   sl.seg_len = pl.seg_len;
   if (pl.metric == kMetricL2)
-    hipLaunchKernelGGL((select_kernel<kSelThreads, false, kMetricL2>),
+    hipLaunchKernelGGL((select_kernel<kSelThreads, false, kMetricL2, false>),
                        dim3(pl.n_segs, cfg->num_q_heads, batch), dim3(kSelThreads), 0, st, sl);
   else
-    hipLaunchKernelGGL((select_kernel<kSelThreads, false, kMetricL1>),
+    hipLaunchKernelGGL((select_kernel<kSelThreads, false, kMetricL1, false>),
                        dim3(pl.n_segs, cfg->num_q_heads, batch), dim3(kSelThreads), 0, st, sl);
   return launch_status();
 }
@@ -380,6 +391,15 @@ int adamas_sparse_attn(const adamas_config* cfg, const void* q, const void* K, c
   return launch_status();
 }
 
+namespace {
+int decode_step_impl(const adamas_config* cfg, const void* q, const void* k_new, const void* v_new,
+                     void* K, void* V, void* codes, const int64_t* seq_start,
+                     const int32_t* page_table, int32_t max_pages, int32_t page_shift,
+                     const int32_t* seq_len, int32_t batch, int32_t k, float* out, int32_t* idx_out,
+                     int64_t max_seq_len, void* workspace, size_t workspace_bytes, void* stream,
+                     uint32_t stages);
+}  // namespace
+
 int adamas_decode_step(const adamas_config* cfg, const void* q, const void* k_new,
                        const void* v_new, void* K, void* V, void* codes, const int64_t* seq_start,
                        const int32_t* seq_len, int32_t batch, int32_t k, float* out,
@@ -396,10 +416,45 @@ int adamas_decode_step_stages(const adamas_config* cfg, const void* q, const voi
                               int32_t k, float* out, int32_t* idx_out, int64_t max_seq_len,
                               void* workspace, size_t workspace_bytes, void* stream,
                               uint32_t stages) {
+  if (seq_start == nullptr) return ADAMAS_ERR_BAD_ARG;
+  return decode_step_impl(cfg, q, k_new, v_new, K, V, codes, seq_start, nullptr, 0, 0, seq_len,
+                          batch, k, out, idx_out, max_seq_len, workspace, workspace_bytes, stream,
+                          stages);
+}
+
+int adamas_decode_step_paged(const adamas_config* cfg, const void* q, const void* k_new,
+                             const void* v_new, void* K, void* V, void* codes,
+                             const int32_t* page_table, int32_t max_pages, int32_t page_tokens,
+                             const int32_t* seq_len, int32_t batch, int32_t k, float* out,
+                             int32_t* idx_out, int64_t max_seq_len, void* workspace,
+                             size_t workspace_bytes, void* stream) {
+  if (int rc = check_config(cfg)) return rc;
+  if (page_table == nullptr || max_pages < 1) return ADAMAS_ERR_BAD_ARG;
+  if (page_tokens < 64 || page_tokens > 4096 || (page_tokens & (page_tokens - 1)) != 0)
+    return ADAMAS_ERR_UNSUPPORTED;
+  if (cfg->pool_tokens % page_tokens != 0 || cfg->pool_tokens > 0x7fffffff) return ADAMAS_ERR_BAD_ARG;
+  if (max_seq_len > (int64_t)max_pages * page_tokens) return ADAMAS_ERR_BAD_ARG;
+  int shift = 0;
+  while ((1 << shift) < page_tokens) ++shift;
+  return decode_step_impl(cfg, q, k_new, v_new, K, V, codes, nullptr, page_table, max_pages, shift,
+                          seq_len, batch, k, out, idx_out, max_seq_len, workspace, workspace_bytes,
+                          stream, ADAMAS_STAGE_ALL);
+}
+
+}  // extern "C"
+
+namespace {
+int decode_step_impl(const adamas_config* cfg, const void* q, const void* k_new, const void* v_new,
+                     void* K, void* V, void* codes, const int64_t* seq_start,
+                     const int32_t* page_table, int32_t max_pages, int32_t page_shift,
+                     const int32_t* seq_len, int32_t batch, int32_t k, float* out, int32_t* idx_out,
+                     int64_t max_seq_len, void* workspace, size_t workspace_bytes, void* stream,
+                     uint32_t stages) {
   if (int rc = check_config(cfg)) return rc;
   if (stages < 1u || stages > ADAMAS_STAGE_ALL) return ADAMAS_ERR_BAD_ARG;
   if (int rc = check_sizes(batch, max_seq_len, k)) return rc;
-  if (!q || !K || !V || !codes || !seq_start || !seq_len || !out || !workspace) return ADAMAS_ERR_BAD_ARG;
+  if (!q || !K || !V || !codes || !seq_len || !out || !workspace) return ADAMAS_ERR_BAD_ARG;
+  if (seq_start == nullptr && page_table == nullptr) return ADAMAS_ERR_BAD_ARG;
   if ((k_new == nullptr) != (v_new == nullptr)) return ADAMAS_ERR_BAD_ARG;
   if (!aligned16(q) || !aligned16(K) || !aligned16(V) || !aligned16(codes)) return ADAMAS_ERR_BAD_ARG;
   if (k_new && (!aligned16(k_new) || !aligned16(v_new))) return ADAMAS_ERR_BAD_ARG;
@@ -429,6 +484,9 @@ int adamas_decode_step_stages(const adamas_config* cfg, const void* q, const voi
   sp.n_tiles = pl.n_tiles;
   sp.thr_q = scaled(cfg, cfg->thr_q);
   sp.thr_k = scaled(cfg, cfg->thr_k);
+  sp.page_table = page_table;
+  sp.max_pages = max_pages;
+  sp.page_shift = page_shift;
   // segment counters live in the unused words of each head's first partial slot
   sp.arrivals = reinterpret_cast<uint32_t*>(ws_at(workspace, pl.off_partial)) + 2;
   sp.arrivals_stride = (int64_t)kMaxParts * kPartialStride;
@@ -461,12 +519,21 @@ int adamas_decode_step_stages(const adamas_config* cfg, const void* q, const voi
   sl.tile_tokens = pl.tile_tokens;
   sl.seg_len = pl.seg_len;
   sl.scale_log2e = scale_log2e(cfg);
-  if (pl.metric == kMetricL2)
-    hipLaunchKernelGGL((select_kernel<kSelThreads, true, kMetricL2>),
-                       dim3(pl.n_segs, cfg->num_q_heads, batch), dim3(kSelThreads), 0, st, sl);
-  else
-    hipLaunchKernelGGL((select_kernel<kSelThreads, true, kMetricL1>),
-                       dim3(pl.n_segs, cfg->num_q_heads, batch), dim3(kSelThreads), 0, st, sl);
+  sl.page_table = page_table;
+  sl.max_pages = max_pages;
+  sl.page_shift = page_shift;
+  {
+    const dim3 sgrid(pl.n_segs, cfg->num_q_heads, batch), sblock(kSelThreads);
+    const bool l2 = pl.metric == kMetricL2, paged = page_table != nullptr;
+    if (l2 && paged)
+      hipLaunchKernelGGL((select_kernel<kSelThreads, true, kMetricL2, true>), sgrid, sblock, 0, st, sl);
+    else if (l2)
+      hipLaunchKernelGGL((select_kernel<kSelThreads, true, kMetricL2, false>), sgrid, sblock, 0, st, sl);
+    else if (paged)
+      hipLaunchKernelGGL((select_kernel<kSelThreads, true, kMetricL1, true>), sgrid, sblock, 0, st, sl);
+    else
+      hipLaunchKernelGGL((select_kernel<kSelThreads, true, kMetricL1, false>), sgrid, sblock, 0, st, sl);
+  }
   if (int rc = launch_status()) return rc;
   if (pl.n_segs == 1 || sl.arrivals != nullptr) return ADAMAS_OK;  // the select kernel wrote `out` itself
   MergeParams mp{};
@@ -482,6 +549,9 @@ int adamas_decode_step_stages(const adamas_config* cfg, const void* q, const voi
   hipLaunchKernelGGL(merge_kernel, dim3(cfg->num_q_heads, batch), dim3(kHeadDim), 0, st, mp);
   return launch_status();
 }
+}  // namespace
+
+extern "C" {
 
 size_t adamas_full_attn_workspace_bytes(const adamas_config* cfg, int32_t batch,
                                         int64_t max_seq_len) {

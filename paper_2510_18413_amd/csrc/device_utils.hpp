@@ -30,6 +30,13 @@ __device__ __forceinline__ int safe_seq_len(const int32_t* seq_len, const int64_
   return ok ? (int)L : 0;
 }
 
+// The same for a paged cache: the sequence must fit the pages its table row can name.
+__device__ __forceinline__ int safe_paged_len(const int32_t* seq_len, int b, int64_t max_seq_len,
+                                              int64_t table_tokens) {
+  const int64_t L = seq_len[b];
+  return (L >= 0 && L <= max_seq_len && L <= table_tokens) ? (int)L : 0;
+}
+
 __device__ __forceinline__ float bf16_bits_to_float(uint32_t bits16) {
   return __uint_as_float(bits16 << 16);
 }

@@ -49,12 +49,17 @@ struct ScanParams {
   int64_t arrivals_stride;
   int64_t pool_tokens, max_seq_len;
   int32_t Hq, Hkv, n_tiles;
+  // Paged cache (PAGED kernels only): token t of sequence b lives in pool row
+  // page_table[b * max_pages + (t >> page_shift)] << page_shift | (t & page mask).
+  const int32_t* page_table;
+  int32_t max_pages, page_shift;
   Thresholds thr_q, thr_k;
 };
 
 // WAVES = wavefronts per workgroup (4, 8 or 16): the tile is WAVES * 256 tokens.
-template <int G, bool FUSED, int WAVES, int METRIC>
+template <int G, bool FUSED, int WAVES, int METRIC, bool PAGED>
 __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p) {
+  static_assert(FUSED || !PAGED, "the paged layout is served by the fused step only");
   constexpr int kNumBins = Dist<METRIC>::kBins, kHistStride = Dist<METRIC>::kStride;
   __shared__ uint32_t s_hist[G][kHistReplicas][kNumBins];
   __shared__ uint32_t s_q[G][12];   // per query head: lo[4], hi[4], lo^hi[4]
@@ -90,8 +95,21 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
     }
   }
 
-  const int L = safe_seq_len(p.seq_len, p.seq_start, b, p.max_seq_len, p.pool_tokens);
-  const int64_t start = p.seq_start[b];
+  // Paged cache: the page of each of the wave's four 64-token steps (a step
+  // never straddles a page: pages are multiples of 64 tokens).  Scalar loads,
+  // on their way together with the length.
+  int32_t pte[kScanTokPerThread];
+  if constexpr (PAGED) {
+    const int uw = __builtin_amdgcn_readfirstlane(wave);
+#pragma unroll
+    for (int i = 0; i < kScanTokPerThread; ++i) {
+      const int pg = min((t0 + (uw * kScanTokPerThread + i) * kWave) >> p.page_shift, p.max_pages - 1);
+      pte[i] = p.page_table[(int64_t)b * p.max_pages + pg];
+    }
+  }
+  const int L = PAGED ? safe_paged_len(p.seq_len, b, p.max_seq_len, (int64_t)p.max_pages << p.page_shift)
+                      : safe_seq_len(p.seq_len, p.seq_start, b, p.max_seq_len, p.pool_tokens);
+  const int64_t start = PAGED ? 0 : p.seq_start[b];
 
   // The only workgroup barrier before the scan sits here, where every wave has
   // just started (and while the loads above are still on their way).  Later on
@@ -126,8 +144,16 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
   for (int i = 0; i < kScanTokPerThread; ++i) {
     // Unconditional: a lane past the end re-reads the last row (masked at use).
     // A branch here would make the compiler wait for all loads at once.
-    const int t = min(t0 + (wave * kScanTokPerThread + i) * kWave + lane, L - 1);
-    const uint4* row = reinterpret_cast<const uint4*>(plane + (int64_t)t * kRowBytes);
+    int64_t r;
+    if constexpr (PAGED) {
+      // a page number outside the pool is clamped into it; lanes past the end read row 0
+      const int t = t0 + (wave * kScanTokPerThread + i) * kWave + lane;
+      const int64_t pg = min(max((int64_t)pte[i], (int64_t)0), (p.pool_tokens >> p.page_shift) - 1);
+      r = t < L ? (pg << p.page_shift) + (t & ((1 << p.page_shift) - 1)) : 0;
+    } else {
+      r = min(t0 + (wave * kScanTokPerThread + i) * kWave + lane, L - 1);
+    }
+    const uint4* row = reinterpret_cast<const uint4*>(plane + r * kRowBytes);
     ra[i] = row[0];
     rb[i] = row[1];
   }
@@ -267,7 +293,12 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
   // so that no other memory operation sits between the row loads and their use.
   if (appending && wave == 0) {
     const int64_t src = ((int64_t)b * p.Hkv + kvh) * kHeadDim;
-    const int64_t row = (int64_t)kvh * p.pool_tokens + start + (L - 1);
+    int64_t row = (int64_t)kvh * p.pool_tokens + start + (L - 1);
+    if constexpr (PAGED) {
+      const int64_t pg = min(max((int64_t)p.page_table[(int64_t)b * p.max_pages + ((L - 1) >> p.page_shift)],
+                                 (int64_t)0), (p.pool_tokens >> p.page_shift) - 1);
+      row = (int64_t)kvh * p.pool_tokens + (pg << p.page_shift) + ((L - 1) & ((1 << p.page_shift) - 1));
+    }
     if (lane < 8) reinterpret_cast<uint32_t*>(p.codes_w + row * kRowBytes)[lane] = s_new[lane];
     reinterpret_cast<uint32_t*>(p.K + row * kHeadDim)[lane] =
         reinterpret_cast<const uint32_t*>(p.k_new + src)[lane];

@@ -52,6 +52,9 @@ struct SelectParams {
   int32_t Hq, Hkv, k;
   int32_t n_tiles, tile_tokens, seg_len;
   float scale_log2e;          // sm_scale * log2(e)
+  // Paged cache (PAGED kernels only), as in ScanParams.
+  const int32_t* page_table;
+  int32_t max_pages, page_shift;
 };
 
 // Exclusive prefix sum over a workgroup of THREADS threads (a multiple of 64).
@@ -198,8 +201,9 @@ __device__ __forceinline__ void attention_rows(const int32_t* s_sel, int n, int 
 // tokens is finished by that workgroup; otherwise each workgroup leaves an
 // (M, lsum, o[128]) partial, merged by the last one to arrive (p.arrivals set)
 // or by merge_kernel (p.arrivals null).
-template <int THREADS, bool ATTN, int METRIC>
+template <int THREADS, bool ATTN, int METRIC, bool PAGED>
 __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
+  static_assert(ATTN || !PAGED, "only the gather needs the page table");
   constexpr int kNumBins = Dist<METRIC>::kBins, kHistStride = Dist<METRIC>::kStride;
   constexpr int kHistPairs = kHistStride / 2;                      // pairs of uint16 bins per stored row
   constexpr int PP = (kHistPairs + THREADS - 1) / THREADS;         // pairs owned by one thread
@@ -241,6 +245,15 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
       nxt_a = nxt_b = make_uint4(0, 0, 0, 0);
     }
   }
+  // Paged cache: a thread's 16 consecutive tokens share one page; its number is
+  // fetched like the distances, a pass ahead, and used when rows are emitted.
+  int32_t cur_pg = 0, nxt_pg = 0;
+  if constexpr (PAGED) {
+    const int32_t* prow = p.page_table + (int64_t)b * p.max_pages;
+    const int t_a = seg_t0 + tid * kSelTokPerThread;
+    cur_pg = prow[min(t_a >> p.page_shift, p.max_pages - 1)];
+    nxt_pg = prow[min((t_a + PASS) >> p.page_shift, p.max_pages - 1)];
+  }
   // Tile histograms: a thread owns PP pairs of bins, pair tid + j * THREADS (one
   // 32-bit load per pair and tile); pairs past the row repeat its last pair.
   const uint16_t* hrow = p.tilehist + head * p.n_tiles * kHistStride;
@@ -257,7 +270,8 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
     for (int j = 0; j < PP; ++j) hv[j][u] = trow[pair[j]];
   }
 
-  const int L = safe_seq_len(p.seq_len, p.seq_start, b, p.max_seq_len, p.pool_tokens);
+  const int L = PAGED ? safe_paged_len(p.seq_len, b, p.max_seq_len, (int64_t)p.max_pages << p.page_shift)
+                      : safe_seq_len(p.seq_len, p.seq_start, b, p.max_seq_len, p.pool_tokens);
   const int kk = min(p.k, L);
   const int n_active = max(1, (L + p.seg_len - 1) / p.seg_len);  // segments that hold tokens
   if (seg >= n_active) return;
@@ -368,6 +382,15 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
       nxt_a = src[0];
       nxt_b = src[1];
     }
+    int64_t page_row0 = 0;  // pool row of token t's page, minus the page offset of t itself
+    if constexpr (PAGED) {
+      const int64_t pg = min(max((int64_t)cur_pg, (int64_t)0), (p.pool_tokens >> p.page_shift) - 1);
+      page_row0 = (pg << p.page_shift) + (t & ((1 << p.page_shift) - 1));
+      cur_pg = nxt_pg;
+      if (t + 2 * PASS < seg_t1)
+        nxt_pg = p.page_table[(int64_t)b * p.max_pages +
+                              min((t + 2 * PASS) >> p.page_shift, p.max_pages - 1)];
+    }
     // Two distances per 32-bit word.  Per half-word, without unpacking:
     //   d < T  <=> bit 15 of (d - T) mod 2^16   (both below 2^15)
     //   d == T <=> (z - 1) & ~z has bit 15 set, z = d ^ T
@@ -403,7 +426,9 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
         // corrupted workspace from turning into an out-of-bounds store.
         if (pos < (uint32_t)kk) {
           if (idx_row != nullptr) idx_row[pos] = t + j;
-          if (ATTN && pos - seg_pos0 < (uint32_t)kMaxK) s_sel[pos - seg_pos0] = t + j;
+          // the gather list holds token positions, or pool rows for a paged cache
+          if (ATTN && pos - seg_pos0 < (uint32_t)kMaxK)
+            s_sel[pos - seg_pos0] = PAGED ? (int32_t)(page_row0 + j) : t + j;
         }
       }
       lt += is_eq ? 0u : 1u;
@@ -419,10 +444,10 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
     const int n_sel = min((int)(run_lt + min(run_eq, (uint32_t)r) - seg_pos0), kk);
     __syncthreads();  // s_sel complete
     const int kvh = hq / (p.Hq / p.Hkv);
-    const int64_t row0 = ((int64_t)kvh * p.pool_tokens + p.seq_start[b]) * kHeadDim;
+    const int64_t row0 = ((int64_t)kvh * p.pool_tokens + (PAGED ? 0 : p.seq_start[b])) * kHeadDim;
     float M, lsum, o;
-    attention_rows<THREADS>(s_sel, n_sel, L, p.q + head * kHeadDim, p.K + row0, p.V + row0,
-                            p.scale_log2e, s_attn, M, lsum, o);
+    attention_rows<THREADS>(s_sel, n_sel, PAGED ? (int)p.pool_tokens : L, p.q + head * kHeadDim,
+                            p.K + row0, p.V + row0, p.scale_log2e, s_attn, M, lsum, o);
     if (gridDim.x == 1 || (p.arrivals != nullptr && n_active == 1)) {
       if (tid < kHeadDim) p.out[head * kHeadDim + tid] = lsum > 0.f ? o / lsum : 0.f;
       return;

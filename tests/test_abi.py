@@ -103,6 +103,19 @@ def test_null_and_misaligned_pointers_rejected():
     a = list(args)
     a[10] = ODD
     assert lib.adamas_select_topk(*a) == -1                                   # workspace alignment
+    pargs = [p, FAKE, None, None, FAKE, FAKE, FAKE, FAKE, 16, 256, FAKE, 1, 64, FAKE, None, 1024,
+             FAKE, 1 << 30, None]
+    for pos in (1, 4, 5, 6, 7, 10, 13, 16):
+        a = list(pargs)
+        a[pos] = None
+        assert lib.adamas_decode_step_paged(*a) == -1
+    for bad_page in (48, 32, 8192):
+        a = list(pargs)
+        a[9] = bad_page
+        assert lib.adamas_decode_step_paged(*a) == -2                         # page size
+    a = list(pargs)
+    a[8] = 2
+    assert lib.adamas_decode_step_paged(*a) == -1                             # table too short for max_seq_len
     fargs = [p, FAKE, FAKE, FAKE, FAKE, FAKE, 1, FAKE, 1024, FAKE, 1 << 30, None]
     for pos in (1, 2, 3, 4, 5, 7, 9):
         a = list(fargs)

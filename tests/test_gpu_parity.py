@@ -420,6 +420,73 @@ def test_variant_without_hadamard_loses_the_true_top_k(H, oracle):
     assert overlap[0] > 0.3 and overlap[0] > 2.0 * overlap[A.VARIANT_NO_HADAMARD], overlap
 
 
+# --------------------------------------------------------------------- paged cache layout
+
+@pytest.mark.parametrize("variant", [0, 3])
+@pytest.mark.parametrize("B,Hq,Hkv,lens,k,page,append", [
+    (1, 1, 1, [1024], 64, 64, False),
+    (2, 8, 2, [4097, 333], 128, 256, True),       # 4097 = 16 * 256 + 1: the new token opens a page
+    (3, 4, 4, [0, 5000, 9000], 256, 64, True),
+    (1, 8, 1, [20000], 1024, 1024, True),
+    (2, 6, 2, [70000, 129], 512, 128, False),
+])
+def test_paged_decode_step_matches_oracle(H, oracle, variant, B, Hq, Hkv, lens, k, page, append):
+    """The step on a cache scattered over randomly placed pages: indices (token positions) bit
+    for bit, attention within tolerance, and the appended row in the right physical page while
+    every other pool row stays as it was."""
+    import paper_2510_18413_amd as A
+    case = small_case(900 + Hq + variant, B, Hq, Hkv, lens, append=append)
+    pc = synth.paginate(case, page, seed=11)
+    hadamard = not (variant & A.VARIANT_NO_HADAMARD)
+    cfg = A.Config.make(Hq, Hkv, pc.pool_tokens, thr_k=case.thresholds, variant=variant)
+    Kd, Vd, qd = H.dev_bf16(pc.K), H.dev_bf16(pc.V), H.dev_bf16(case.q)
+    knd = None if case.k_new is None else H.dev_bf16(case.k_new)
+    vnd = None if case.v_new is None else H.dev_bf16(case.v_new)
+    codes = torch.zeros(Hkv, pc.pool_tokens, 32, dtype=torch.uint8, device="cuda")
+    A.adamas_encode_keys(cfg, Kd, codes, 0, pc.pool_tokens)
+    table = torch.from_numpy(pc.page_table).cuda()
+    seq_len = torch.from_numpy(case.seq_len).cuda()
+    max_len = max(case.max_seq_len, 1)
+    ws = torch.full((A.adamas_workspace_bytes(cfg, B, max_len, k),), 0xA5, dtype=torch.uint8,
+                    device="cuda")
+    out = torch.full((B, Hq, 128), float("nan"), device="cuda")
+    idx = torch.full((B, Hq, k), -7, dtype=torch.int32, device="cuda")
+    A.adamas_decode_step_paged(cfg, qd, Kd, Vd, codes, table, page, seq_len, k, out, max_len, ws,
+                               k_new=knd, v_new=vnd, idx_out=idx)
+    torch.cuda.synchronize()
+    Kr, Vr = pc.K.copy(), pc.V.copy()
+    _, rows = oracle.encode(Kr, case.thresholds, hadamard=hadamard)
+    ref_out, ref_idx = oracle.decode_step_paged(
+        case.q, Kr, Vr, rows, pc.page_table, page, case.seq_len, k, case.thresholds,
+        case.thresholds, H.SM_SCALE, k_new=case.k_new, v_new=case.v_new, hadamard=hadamard,
+        squared=bool(variant & A.VARIANT_L2))
+    assert np.array_equal(idx.cpu().numpy(), ref_idx)
+    assert H.attn_rel_err(out.cpu().numpy(), ref_out) <= H.ATTN_TOL
+    assert np.array_equal(H.host_u16(Kd), Kr) and np.array_equal(H.host_u16(Vd), Vr)
+    assert np.array_equal(codes.cpu().numpy(), rows)
+
+
+def test_paged_step_clamps_page_numbers_outside_the_pool(H, oracle):
+    """A page table with entries beyond the pool must not fault: rows come from clamped pages."""
+    import paper_2510_18413_amd as A
+    case = small_case(950, 1, 2, 2, [1000], needles=0)
+    pc = synth.paginate(case, 64, seed=12)
+    cfg = A.Config.make(2, 2, pc.pool_tokens, thr_k=case.thresholds)
+    Kd, Vd, qd = H.dev_bf16(pc.K), H.dev_bf16(pc.V), H.dev_bf16(case.q)
+    codes = torch.zeros(2, pc.pool_tokens, 32, dtype=torch.uint8, device="cuda")
+    A.adamas_encode_keys(cfg, Kd, codes, 0, pc.pool_tokens)
+    bad = pc.page_table.copy()
+    bad[0, 3], bad[0, 7] = 10 ** 6, -5
+    ws = torch.empty(A.adamas_workspace_bytes(cfg, 1, 1000, 32), dtype=torch.uint8, device="cuda")
+    out = torch.zeros(1, 2, 128, device="cuda")
+    idx = torch.zeros(1, 2, 32, dtype=torch.int32, device="cuda")
+    A.adamas_decode_step_paged(cfg, qd, Kd, Vd, codes, torch.from_numpy(bad).cuda(), 64,
+                               torch.from_numpy(case.seq_len).cuda(), 32, out, 1000, ws, idx_out=idx)
+    torch.cuda.synchronize()
+    got = idx.cpu().numpy()
+    assert np.all((got >= 0) & (got < 1000)) and np.all(np.isfinite(out.cpu().numpy()))
+
+
 def test_decode_step_random_shapes(H, oracle):
     """Seeded sweep over batch, group size, lengths, budgets, thresholds, scale and append:
     every case against the oracle."""
