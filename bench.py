@@ -49,6 +49,9 @@ def parse_args():
     ap.add_argument("--variant", default="adamas",
                     choices=["adamas", "no_hadamard", "l2", "no_hadamard_l2"],
                     help="ablation switches of Section 4.4 (default: the method itself)")
+    ap.add_argument("--paged", type=int, default=0, metavar="PAGE_TOKENS",
+                    help="lay the cache out on randomly placed pages of this many tokens and time "
+                         "adamas_decode_step_paged (0: contiguous sequences)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--eager", action="store_true", help="launch from Python instead of a graph")
     ap.add_argument("--scan-only", action="store_true",
@@ -106,6 +109,25 @@ def main():
         pos += int(lens[b]) + synth.SEQ_GAP_ROWS
     pool = pos - synth.SEQ_GAP_ROWS
     max_len = int(lens.max())
+    page = args.paged
+    if page:
+        # every sequence gets its own pages, placed by a seeded permutation; src_row maps a pool
+        # row of the paged layout to the row of the contiguous layout it is filled from
+        need = [(int(L) + page - 1) // page for L in lens]
+        n_pages = sum(need)
+        order = np.random.default_rng(synth.config_seed(cfg_id) + 900).permutation(n_pages)
+        table_np = np.full((B, max(need)), -1, dtype=np.int32)
+        src_row = np.zeros(n_pages * page, dtype=np.int64)
+        at = 0
+        for b in range(B):
+            for pg in range(need[b]):
+                phys = int(order[at]); at += 1
+                table_np[b, pg] = phys
+                tok = np.minimum(pg * page + np.arange(page), int(lens[b]) - 1)
+                src_row[phys * page:(phys + 1) * page] = starts[b] + tok
+        contiguous_pool, pool = pool, n_pages * page
+        page_table = torch.from_numpy(table_np).to(dev)
+        src_row_dev = torch.from_numpy(src_row).to(dev)
     no_hadamard = args.variant in ("no_hadamard", "no_hadamard_l2")
     squared = args.variant in ("l2", "no_hadamard_l2")
     cfg = A.Config.make(Hq, Hkv, pool, thr_k=synth.DEFAULT_THRESHOLDS,
@@ -113,6 +135,8 @@ def main():
                         | (A.VARIANT_L2 if squared else 0))
     seq_start = torch.from_numpy(starts).to(dev)
     seq_len = torch.from_numpy(lens).to(dev)
+
+    globals_pool = pool
 
     def gen_layer(layer):
         """Same recipe as synth_inputs (N(0,1) bf16, 4 outlier channels x8 per KV head, one
@@ -124,6 +148,7 @@ def main():
             x = torch.randn(n, 128, generator=g, device=dev) * scale
             return torch.where(x.abs() < synth.FLUSH_BELOW, torch.zeros_like(x), x)
 
+        pool = contiguous_pool if page else globals_pool
         K = torch.empty(Hkv, pool, 128, dtype=torch.bfloat16, device=dev)
         V = torch.empty(Hkv, pool, 128, dtype=torch.bfloat16, device=dev)
         q = torch.empty(B, Hq, 128, dtype=torch.bfloat16, device=dev)
@@ -165,6 +190,9 @@ def main():
             data = upload_case(case0)
         else:
             data = gen_layer(layer)
+        if page:    # pure re-layout of the rows just generated
+            data["K"] = data["K"].index_select(1, src_row_dev).contiguous()
+            data["V"] = data["V"].index_select(1, src_row_dev).contiguous()
         data["codes"] = torch.empty(Hkv, pool, 32, dtype=torch.uint8, device=dev)
         data["out"] = torch.zeros(B, Hq, 128, device=dev)
         A.adamas_encode_keys(cfg, data["K"], data["codes"], 0, pool)
@@ -186,6 +214,13 @@ def main():
 
     def step(i, stages=None):
         d = layers[i % n_layers]
+        if page:
+            A.adamas_decode_step_paged(cfg, d["q"], d["K"], d["V"], d["codes"], page_table, page,
+                                       seq_len, k, d["out"], max_len, ws, k_new=d["k_new"],
+                                       v_new=d["v_new"],
+                                       idx_out=idx0 if (i % n_layers == 0) else None,
+                                       stages=A.STAGE_ALL if stages is None else stages)
+            return
         A.adamas_decode_step_stages(cfg, d["q"], d["K"], d["V"], d["codes"], seq_start, seq_len, k,
                                     d["out"], max_len, ws, k_new=d["k_new"], v_new=d["v_new"],
                                     idx_out=idx0 if (i % n_layers == 0) else None, stages=stages)
@@ -284,32 +319,35 @@ def main():
     stream_gbps = Hkv * pool * 32 / stream_us / 1e3
 
     # comparison point: dense decode attention (Eq. 1 over every cached row) on the same layers
-    full_ws = torch.empty(A.adamas_full_attn_workspace_bytes(cfg, B, max_len), dtype=torch.uint8,
-                          device=dev)
-    full_out = torch.zeros(B, Hq, 128, device=dev)
+    # (contiguous layout only: the dense kernel does not read page tables)
+    full_us = None
+    if not page:
+        full_ws = torch.empty(A.adamas_full_attn_workspace_bytes(cfg, B, max_len), dtype=torch.uint8,
+                              device=dev)
+        full_out = torch.zeros(B, Hq, 128, device=dev)
 
-    def full_graph():
-        for d in layers:
-            A.adamas_full_attn(cfg, d["q"], d["K"], d["V"], seq_start, seq_len, full_out, max_len,
-                               full_ws)
-        torch.cuda.synchronize()
-        g = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(g):
+        def full_graph():
             for d in layers:
-                A.adamas_full_attn(cfg, d["q"], d["K"], d["V"], seq_start, seq_len, full_out,
-                                   max_len, full_ws)
-        return g
-    fg = full_graph()
-    fg.replay()
-    torch.cuda.synchronize()
-    n_rep = max(1, min(20, args.steps // (16 * n_layers)))
-    s0.record()
-    for _ in range(n_rep):
+                A.adamas_full_attn(cfg, d["q"], d["K"], d["V"], seq_start, seq_len, full_out, max_len,
+                                   full_ws)
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                for d in layers:
+                    A.adamas_full_attn(cfg, d["q"], d["K"], d["V"], seq_start, seq_len, full_out,
+                                       max_len, full_ws)
+            return g
+        fg = full_graph()
         fg.replay()
-    s1.record()
-    torch.cuda.synchronize()
-    full_us = s0.elapsed_time(s1) * 1e3 / (n_rep * n_layers)
-    full_bytes = Hkv * int(lens.sum()) * 512
+        torch.cuda.synchronize()
+        n_rep = max(1, min(20, args.steps // (16 * n_layers)))
+        s0.record()
+        for _ in range(n_rep):
+            fg.replay()
+        s1.record()
+        torch.cuda.synchronize()
+        full_us = s0.elapsed_time(s1) * 1e3 / (n_rep * n_layers)
+        full_bytes = Hkv * int(lens.sum()) * 512
 
     total_bytes, code_bytes = algorithmic_bytes(B, Hq, Hkv, [int(x) for x in lens], k, append)
     gbps_step = total_bytes / (us_step * 1e-6) / 1e9
@@ -339,6 +377,7 @@ def main():
             "workload": wl["text"] + ", budget k=%d, %d rotating layer caches" % (k, n_layers),
             "batch": B, "q_heads": Hq, "kv_heads": Hkv, "context": int(max_len),
             "sum_context": int(lens.sum()), "k": k, "append": append, "variant": args.variant,
+            "layout": "paged, %d-token pages, random placement" % page if page else "contiguous",
             "launch": "eager" if args.eager else "hipGraph of one %d-layer sweep" % n_layers,
         },
         "achieved_hbm_GBps": round(gbps_step, 1),
@@ -364,10 +403,11 @@ def main():
     result["bulk_encode"] = {"us": round(encode_us, 1), "rows": Hkv * pool,
                              "GBps": round(encode_bytes / encode_us / 1e3, 1),
                              "hbm_frac": round(encode_bytes / encode_us / 1e3 / HBM_PEAK_GBPS, 4)}
-    result["full_attention"] = {"us_per_layer": round(full_us, 2),
-                                "GBps": round(full_bytes / full_us / 1e3, 1),
-                                "hbm_frac": round(full_bytes / full_us / 1e3 / HBM_PEAK_GBPS, 4),
-                                "speedup_of_sparse_step": round(full_us / us_step, 2)}
+    if full_us is not None:
+        result["full_attention"] = {"us_per_layer": round(full_us, 2),
+                                    "GBps": round(full_bytes / full_us / 1e3, 1),
+                                    "hbm_frac": round(full_bytes / full_us / 1e3 / HBM_PEAK_GBPS, 4),
+                                    "speedup_of_sparse_step": round(full_us / us_step, 2)}
     if per_sweep:
         ps = sorted(x / n_layers * 1e3 for x in per_sweep)
         result["us_per_layer_p10_p50_p90"] = [round(ps[len(ps) // 10], 3), round(ps[len(ps) // 2], 3),
@@ -376,7 +416,7 @@ def main():
     # ------------------------------------------------------------------ oracle on the host
     if not args.no_cpu_baseline:
         import oracle
-        if case0 is None:
+        if case0 is None or page:
             # pull layer 0 back to the host for the oracle
             def h(t):
                 return None if t is None else t.cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
@@ -403,10 +443,16 @@ def main():
         times, t_all = [], time.perf_counter()
         while len(times) < 3 or (time.perf_counter() - t_all < 4.0 and len(times) < 50):
             t0 = time.perf_counter()
-            ref_out, ref_idx, _ = oracle.decode_step(
-                qs, Ks, Vs, rows, starts, lens, k, synth.DEFAULT_THRESHOLDS,
-                synth.DEFAULT_THRESHOLDS, 1.0 / np.sqrt(128.0), k_new=kns, v_new=vns,
-                hadamard=not no_hadamard, squared=squared)
+            if page:
+                ref_out, ref_idx = oracle.decode_step_paged(
+                    qs, Ks, Vs, rows, table_np, page, lens, k, synth.DEFAULT_THRESHOLDS,
+                    synth.DEFAULT_THRESHOLDS, 1.0 / np.sqrt(128.0), k_new=kns, v_new=vns,
+                    hadamard=not no_hadamard, squared=squared)
+            else:
+                ref_out, ref_idx, _ = oracle.decode_step(
+                    qs, Ks, Vs, rows, starts, lens, k, synth.DEFAULT_THRESHOLDS,
+                    synth.DEFAULT_THRESHOLDS, 1.0 / np.sqrt(128.0), k_new=kns, v_new=vns,
+                    hadamard=not no_hadamard, squared=squared)
             times.append(time.perf_counter() - t0)
         cpu_s = sorted(times)[len(times) // 2]
         scale_up = Hkv / n_kv

@@ -239,8 +239,10 @@ int adamas_decode_step_stages(const adamas_config *cfg, const void *q,
  * pool; an entry outside the pool is clamped into it (wrong rows, no fault).
  * With an append the table must already name the page of the new token
  * (position seq_len[b]-1).  idx_out holds token positions, as in
- * adamas_decode_step.  max_seq_len <= max_pages * page_tokens.  Everything
- * else (arguments, workspace size, errors, variants) as adamas_decode_step.
+ * adamas_decode_step.  max_seq_len <= max_pages * page_tokens.  stages:
+ * ADAMAS_STAGE_ALL, or ADAMAS_STAGE_SCAN to time the scan alone (other values
+ * -> ADAMAS_ERR_BAD_ARG).  Everything else (arguments, workspace size, errors,
+ * variants) as adamas_decode_step.
  */
 int adamas_decode_step_paged(const adamas_config *cfg, const void *q,
                              const void *k_new, const void *v_new, void *K,
@@ -249,7 +251,7 @@ int adamas_decode_step_paged(const adamas_config *cfg, const void *q,
                              const int32_t *seq_len, int32_t batch, int32_t k,
                              float *out, int32_t *idx_out, int64_t max_seq_len,
                              void *workspace, size_t workspace_bytes,
-                             void *stream);
+                             void *stream, uint32_t stages);
 
 /*
  * Comparison point, not a step of the method: Eq. 1 over ALL cached rows of

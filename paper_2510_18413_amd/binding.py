@@ -35,6 +35,7 @@ HEAD_DIM = 128
 CODE_ROW_BYTES = 32
 VARIANT_NO_HADAMARD = 1
 VARIANT_L2 = 2
+STAGE_SCAN, STAGE_SELECT_ATTN, STAGE_ALL = 1, 2, 3
 
 
 class AdamasError(RuntimeError):
@@ -107,7 +108,8 @@ def library() -> ctypes.CDLL:
                                            i64, vp, sz, vp]
         lib.adamas_decode_step_paged.restype = ctypes.c_int
         lib.adamas_decode_step_paged.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp,
-                                                 i32, i32, vp, vp, i64, vp, sz, vp]
+                                                 i32, i32, vp, vp, i64, vp, sz, vp,
+                                                 ctypes.c_uint32]
         lib.adamas_full_attn_workspace_bytes.restype = sz
         lib.adamas_full_attn_workspace_bytes.argtypes = [cfgp, i32, i64]
         lib.adamas_full_attn.restype = ctypes.c_int
@@ -183,7 +185,7 @@ def adamas_encode_query(cfg: Config, q, qcodes, stream=None) -> None:
 
 def adamas_decode_step_paged(cfg: Config, q, K, V, codes, page_table, page_tokens: int, seq_len,
                              k: int, out, max_seq_len: int, workspace, k_new=None, v_new=None,
-                             idx_out=None, stream=None) -> None:
+                             idx_out=None, stream=None, stages=STAGE_ALL) -> None:
     import torch
     batch = q.shape[0]
     hkv, pool = cfg.num_kv_heads, cfg.pool_tokens
@@ -200,7 +202,8 @@ def adamas_decode_step_paged(cfg: Config, q, K, V, codes, page_table, page_token
         _ptr(seq_len, torch.int32, "seq_len", (batch,)), batch, k,
         _ptr(out, torch.float32, "out", (batch, cfg.num_q_heads, HEAD_DIM)),
         _ptr(idx_out, torch.int32, "idx_out", (batch, cfg.num_q_heads, k), optional=True),
-        max_seq_len, _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream))
+        max_seq_len, _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream),
+        int(stages))
     _check(rc, "adamas_decode_step_paged")
 
 
@@ -282,7 +285,6 @@ def adamas_sparse_attn(cfg: Config, q, K, V, seq_start, idx, out, max_seq_len: i
     _check(rc, "adamas_sparse_attn")
 
 
-STAGE_SCAN, STAGE_SELECT_ATTN, STAGE_ALL = 1, 2, 3
 
 
 def adamas_decode_step(cfg: Config, q, K, V, codes, seq_start, seq_len, k: int, out,

@@ -427,9 +427,10 @@ int adamas_decode_step_paged(const adamas_config* cfg, const void* q, const void
                              const int32_t* page_table, int32_t max_pages, int32_t page_tokens,
                              const int32_t* seq_len, int32_t batch, int32_t k, float* out,
                              int32_t* idx_out, int64_t max_seq_len, void* workspace,
-                             size_t workspace_bytes, void* stream) {
+                             size_t workspace_bytes, void* stream, uint32_t stages) {
   if (int rc = check_config(cfg)) return rc;
   if (page_table == nullptr || max_pages < 1) return ADAMAS_ERR_BAD_ARG;
+  if (stages != ADAMAS_STAGE_ALL && stages != ADAMAS_STAGE_SCAN) return ADAMAS_ERR_BAD_ARG;
   if (page_tokens < 64 || page_tokens > 4096 || (page_tokens & (page_tokens - 1)) != 0)
     return ADAMAS_ERR_UNSUPPORTED;
   if (cfg->pool_tokens % page_tokens != 0 || cfg->pool_tokens > 0x7fffffff) return ADAMAS_ERR_BAD_ARG;
@@ -438,7 +439,7 @@ int adamas_decode_step_paged(const adamas_config* cfg, const void* q, const void
   while ((1 << shift) < page_tokens) ++shift;
   return decode_step_impl(cfg, q, k_new, v_new, K, V, codes, nullptr, page_table, max_pages, shift,
                           seq_len, batch, k, out, idx_out, max_seq_len, workspace, workspace_bytes,
-                          stream, ADAMAS_STAGE_ALL);
+                          stream, stages);
 }
 
 }  // extern "C"

@@ -104,7 +104,8 @@ def test_null_and_misaligned_pointers_rejected():
     a[10] = ODD
     assert lib.adamas_select_topk(*a) == -1                                   # workspace alignment
     pargs = [p, FAKE, None, None, FAKE, FAKE, FAKE, FAKE, 16, 256, FAKE, 1, 64, FAKE, None, 1024,
-             FAKE, 1 << 30, None]
+             FAKE, 1 << 30, None, 3]
+    assert lib.adamas_decode_step_paged(*(pargs[:-1] + [2])) == -1           # select stage alone
     for pos in (1, 4, 5, 6, 7, 10, 13, 16):
         a = list(pargs)
         a[pos] = None
