@@ -51,7 +51,8 @@ def lib() -> ctypes.CDLL:
                      "oracle_topk", "oracle_sparse_attention", "oracle_full_attention",
                      "oracle_decode_step", "oracle_max_threads", "oracle_encode_variant",
                      "oracle_squared_distance", "oracle_decode_step_variant",
-                     "oracle_decode_step_paged"):
+                     "oracle_decode_step_paged", "oracle_bucketize_n", "oracle_pack_row_bits",
+                     "oracle_unpack_row_bits", "oracle_encode_bits", "oracle_decode_step_bits"):
             getattr(_lib, name).restype = ctypes.c_int
         _lib.oracle_set_threads.restype = None
         _lib.oracle_sparse_attention.argtypes = [ctypes.c_void_p] * 4 + [
@@ -69,6 +70,14 @@ def lib() -> ctypes.CDLL:
             ctypes.c_double] + [ctypes.c_void_p] * 7 + [ctypes.c_int32, ctypes.c_int32,
             ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_int, ctypes.c_int]
+        _lib.oracle_encode_bits.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p,
+                                            ctypes.c_int, ctypes.c_int, ctypes.c_void_p,
+                                            ctypes.c_void_p]
+        _lib.oracle_decode_step_bits.argtypes = [
+            ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_int, ctypes.c_double] + [ctypes.c_void_p] * 8 + [
+            ctypes.c_int32, ctypes.c_int32] + [ctypes.c_void_p] * 3 + [
+            ctypes.c_int64, ctypes.c_int, ctypes.c_int]
         _lib.oracle_encode_variant.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p,
                                                ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
     return _lib
@@ -89,9 +98,9 @@ def _p(a):
     return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
 
 
-def _thr(thr) -> np.ndarray:
+def _thr(thr, bits: int = 2) -> np.ndarray:
     t = np.ascontiguousarray(np.asarray(thr, dtype=np.float32))
-    assert t.shape == (3,)
+    assert t.shape == ((1 << bits) - 1,)
     return t
 
 
@@ -285,3 +294,80 @@ def decode_step_paged(q, K, V, code_rows, page_table, page_tokens, seq_len, k, t
         1 if squared else 0)
     _check(rc, "decode_step_paged")
     return out, idx
+
+
+# ------------------------------------------------ bucketization ablation: 1-, 2-, 3-bit codes
+
+def bucketize_n(y: np.ndarray, thr, d: int = D) -> np.ndarray:
+    """Eq. 5 with len(thr) thresholds (1, 3 or 7)."""
+    y = np.ascontiguousarray(y, dtype=np.float64)
+    t = np.ascontiguousarray(np.asarray(thr, dtype=np.float32))
+    code = np.empty(y.shape[0], dtype=np.uint8)
+    _check(lib().oracle_bucketize_n(ctypes.c_int64(y.shape[0]), _p(y), ctypes.c_int(d), _p(t),
+                                    ctypes.c_int(t.shape[0]), _p(code)), "bucketize_n")
+    return code
+
+
+def pack_row_bits(code: np.ndarray, bits: int) -> np.ndarray:
+    code = np.ascontiguousarray(code, dtype=np.uint8)
+    assert code.shape == (D,)
+    row = np.empty(16 * bits, dtype=np.uint8)
+    _check(lib().oracle_pack_row_bits(_p(code), ctypes.c_int(bits), _p(row)), "pack_row_bits")
+    return row
+
+
+def unpack_row_bits(row: np.ndarray, bits: int) -> np.ndarray:
+    row = np.ascontiguousarray(row, dtype=np.uint8)
+    assert row.shape == (16 * bits,)
+    code = np.empty(D, dtype=np.uint8)
+    _check(lib().oracle_unpack_row_bits(_p(row), ctypes.c_int(bits), _p(code)), "unpack_row_bits")
+    return code
+
+
+def unpack_rows_bits(rows: np.ndarray, bits: int) -> np.ndarray:
+    rows = np.ascontiguousarray(rows, dtype=np.uint8)
+    flat = rows.reshape(-1, 16 * bits)
+    out = np.empty((flat.shape[0], D), dtype=np.uint8)
+    for i in range(flat.shape[0]):
+        out[i] = unpack_row_bits(flat[i], bits)
+    return out.reshape(rows.shape[:-1] + (D,))
+
+
+def encode_bits(x_bf16: np.ndarray, thr, bits: int, hadamard: bool = True):
+    """x_bf16 uint16 [..., 128] -> (codes uint8 [..., 128] in 0..2^bits-1, rows uint8
+    [..., 16*bits]); thr holds 2^bits - 1 thresholds."""
+    x = np.ascontiguousarray(x_bf16, dtype=np.uint16)
+    assert x.shape[-1] == D
+    n = x.size // D
+    codes = np.empty(x.shape, dtype=np.uint8)
+    rows = np.empty(x.shape[:-1] + (16 * bits,), dtype=np.uint8)
+    _check(lib().oracle_encode_bits(_p(x), ctypes.c_int64(n), _p(_thr(thr, bits)), bits,
+                                    1 if hadamard else 0, _p(codes), _p(rows)), "encode_bits")
+    return codes, rows
+
+
+def decode_step_bits(q, K, V, code_rows, seq_start, seq_len, k, thr_q, thr_k, bits, scale,
+                     k_new=None, v_new=None, want_dist=False, hadamard=True):
+    """decode_step with `bits`-bit codes: code_rows uint8 [Hkv,pool,16*bits]."""
+    q = np.ascontiguousarray(q, dtype=np.uint16)
+    B, Hq, _ = q.shape
+    Hkv, pool, _ = K.shape
+    for a, dt in ((K, np.uint16), (V, np.uint16), (code_rows, np.uint8)):
+        assert a.dtype == dt and a.flags.c_contiguous
+    assert V.shape == K.shape and code_rows.shape == (Hkv, pool, 16 * bits)
+    seq_start = np.ascontiguousarray(seq_start, dtype=np.int64)
+    seq_len = np.ascontiguousarray(seq_len, dtype=np.int32)
+    assert np.all(seq_start >= 0) and np.all(seq_start + seq_len <= pool)
+    if k_new is not None:
+        k_new = np.ascontiguousarray(k_new, dtype=np.uint16)
+        v_new = np.ascontiguousarray(v_new, dtype=np.uint16)
+    max_len = int(seq_len.max()) if B else 0
+    out = np.zeros((B, Hq, D), dtype=np.float32)
+    idx = np.empty((B, Hq, k), dtype=np.int32)
+    dist = np.full((B, Hq, max(max_len, 1)), -1, dtype=np.int32) if want_dist else None
+    rc = lib().oracle_decode_step_bits(
+        Hq, Hkv, pool, _p(_thr(thr_q, bits)), _p(_thr(thr_k, bits)), bits, float(scale), _p(q),
+        _p(k_new), _p(v_new), _p(K), _p(V), _p(code_rows), _p(seq_start), _p(seq_len), B, k,
+        _p(out), _p(idx), _p(dist), max(max_len, 1), 1 if hadamard else 0, 0)
+    _check(rc, "decode_step_bits")
+    return out, idx, dist

@@ -118,23 +118,38 @@ int oracle_hadamard_transform(int d, const double *x, double *y) {
  * tau_i = (double)thr[i] * sqrt((double)d).
  * code = #{ i : y > tau_i }  (strict: y == tau_i falls in the lower bucket).
  */
-static void scaled_thresholds(int d, const float thr[3], double tau[3]) {
+#define ORACLE_MAX_THR 7 /* 3-bit codes */
+
+static void scaled_thresholds(int d, const float *thr, int nthr, double *tau) {
   double root = sqrt((double)d);
-  for (int i = 0; i < 3; ++i) tau[i] = (double)thr[i] * root;
+  for (int i = 0; i < nthr; ++i) tau[i] = (double)thr[i] * root;
 }
 
-int oracle_bucketize(int64_t n, const double *y, int d, const float thr[3], uint8_t *code) {
-  if (n < 0 || d < 1 || !y || !thr || !code) return ORACLE_BAD_ARG;
-  if (!(thr[0] < thr[1] && thr[1] < thr[2])) return ORACLE_BAD_ARG;
-  double tau[3];
-  scaled_thresholds(d, thr, tau);
+static int increasing(const float *thr, int nthr) {
+  for (int i = 0; i + 1 < nthr; ++i)
+    if (!(thr[i] < thr[i + 1])) return 0;
+  return thr[0] == thr[0]; /* not NaN */
+}
+
+/* Eq. 5 with nthr thresholds (1, 3 or 7 for the 1-, 2-, 3-bit codes of Section 4.4). */
+int oracle_bucketize_n(int64_t n, const double *y, int d, const float *thr, int nthr,
+                       uint8_t *code) {
+  if (n < 0 || d < 1 || !y || !thr || !code || nthr < 1 || nthr > ORACLE_MAX_THR)
+    return ORACLE_BAD_ARG;
+  if (!increasing(thr, nthr)) return ORACLE_BAD_ARG;
+  double tau[ORACLE_MAX_THR];
+  scaled_thresholds(d, thr, nthr, tau);
   for (int64_t j = 0; j < n; ++j) {
     int c = 0;
-    for (int i = 0; i < 3; ++i)
+    for (int i = 0; i < nthr; ++i)
       if (y[j] > tau[i]) ++c;
     code[j] = (uint8_t)c;
   }
   return ORACLE_OK;
+}
+
+int oracle_bucketize(int64_t n, const double *y, int d, const float thr[3], uint8_t *code) {
+  return oracle_bucketize_n(n, y, d, thr, 3, code);
 }
 
 /* ------------------------------------------------------------------ compress */
@@ -171,6 +186,34 @@ int oracle_unpack_row(const uint8_t row[ORACLE_ROW_BYTES], uint8_t code[ORACLE_D
   return ORACLE_OK;
 }
 
+/*
+ * The same layout for the 1-bit and 3-bit codes of the bucketization ablation
+ * (Section 4.4): a row is 16 * bits bytes = four words of `bits` little-endian
+ * 32-bit planes; plane p of word g holds, at bit j, bit p of the code of
+ * dimension 32g + j.  bits = 2 gives exactly the 32-byte row above.
+ */
+int oracle_pack_row_bits(const uint8_t code[ORACLE_D], int bits, uint8_t *row) {
+  if (!code || !row || bits < 1 || bits > 3) return ORACLE_BAD_ARG;
+  memset(row, 0, (size_t)16 * bits);
+  for (int dim = 0; dim < ORACLE_D; ++dim) {
+    if (code[dim] >> bits) return ORACLE_BAD_ARG;
+    int g = dim / 32, j = dim % 32;
+    for (int p = 0; p < bits; ++p)
+      if ((code[dim] >> p) & 1) row[(g * bits + p) * 4 + j / 8] |= (uint8_t)(1u << (j % 8));
+  }
+  return ORACLE_OK;
+}
+
+int oracle_unpack_row_bits(const uint8_t *row, int bits, uint8_t code[ORACLE_D]) {
+  if (!code || !row || bits < 1 || bits > 3) return ORACLE_BAD_ARG;
+  for (int dim = 0; dim < ORACLE_D; ++dim) {
+    int g = dim / 32, j = dim % 32, c = 0;
+    for (int p = 0; p < bits; ++p) c |= ((row[(g * bits + p) * 4 + j / 8] >> (j % 8)) & 1) << p;
+    code[dim] = (uint8_t)c;
+  }
+  return ORACLE_OK;
+}
+
 /* ------------------------------------- encode = transform + bucketize + pack */
 
 /*
@@ -181,6 +224,8 @@ int oracle_unpack_row(const uint8_t row[ORACLE_ROW_BYTES], uint8_t code[ORACLE_D
  */
 int oracle_encode_variant(const uint16_t *x, int64_t n, const float thr[3], int use_hadamard,
                           uint8_t *codes, uint8_t *rows);
+int oracle_encode_bits(const uint16_t *x, int64_t n, const float *thr, int bits, int use_hadamard,
+                       uint8_t *codes, uint8_t *rows);
 
 int oracle_encode(const uint16_t *x, int64_t n, const float thr[3],
                   uint8_t *codes, uint8_t *rows) {
@@ -194,16 +239,26 @@ int oracle_encode(const uint16_t *x, int64_t n, const float thr[3],
  */
 int oracle_encode_variant(const uint16_t *x, int64_t n, const float thr[3], int use_hadamard,
                           uint8_t *codes, uint8_t *rows) {
-  if (!x || n < 0 || !thr) return ORACLE_BAD_ARG;
-  if (!(thr[0] < thr[1] && thr[1] < thr[2])) return ORACLE_BAD_ARG;
+  return oracle_encode_bits(x, n, thr, 2, use_hadamard, codes, rows);
+}
+
+/*
+ * bits = 1, 2, 3: the bucketization granularities of Section 4.4, with
+ * 2^bits - 1 thresholds and rows of 16 * bits bytes (oracle_pack_row_bits).
+ */
+int oracle_encode_bits(const uint16_t *x, int64_t n, const float *thr, int bits, int use_hadamard,
+                       uint8_t *codes, uint8_t *rows) {
+  if (!x || n < 0 || !thr || bits < 1 || bits > 3) return ORACLE_BAD_ARG;
+  const int nthr = (1 << bits) - 1;
+  if (!increasing(thr, nthr)) return ORACLE_BAD_ARG;
   int8_t *H = (int8_t *)malloc((size_t)ORACLE_D * ORACLE_D);
   if (!H) return ORACLE_NOMEM;
   oracle_hadamard_matrix(ORACLE_D, H);
-  double tau[3];
+  double tau[ORACLE_MAX_THR];
   if (use_hadamard) {
-    scaled_thresholds(ORACLE_D, thr, tau);
+    scaled_thresholds(ORACLE_D, thr, nthr, tau);
   } else {
-    for (int i = 0; i < 3; ++i) tau[i] = (double)thr[i];
+    for (int i = 0; i < nthr; ++i) tau[i] = (double)thr[i];
   }
   int status = ORACLE_OK;
 #pragma omp parallel for schedule(static)
@@ -237,12 +292,12 @@ int oracle_encode_variant(const uint16_t *x, int64_t n, const float thr[3], int 
     }
     for (int j = 0; j < ORACLE_D; ++j) {
       int c = 0;
-      for (int i = 0; i < 3; ++i)
+      for (int i = 0; i < nthr; ++i)
         if (y[j] > tau[i]) ++c;
       code[j] = (uint8_t)c;
     }
     if (codes) memcpy(codes + v * ORACLE_D, code, ORACLE_D);
-    if (rows) oracle_pack_row(code, rows + v * ORACLE_ROW_BYTES);
+    if (rows) oracle_pack_row_bits(code, bits, rows + v * (int64_t)16 * bits);
   }
   free(H);
   return status;
@@ -430,6 +485,14 @@ int oracle_decode_step_variant(int32_t Hq, int32_t Hkv, int64_t pool_tokens,
                                const int32_t *seq_len, int32_t B, int32_t k, float *out,
                                int32_t *idx, int32_t *dist, int64_t max_seq_len,
                                int use_hadamard, int squared_distance);
+int oracle_decode_step_bits(int32_t Hq, int32_t Hkv, int64_t pool_tokens,
+                            const float *thr_q, const float *thr_k, int bits, double scale,
+                            const uint16_t *q, const uint16_t *k_new,
+                            const uint16_t *v_new, uint16_t *K, uint16_t *V,
+                            uint8_t *code_rows, const int64_t *seq_start,
+                            const int32_t *seq_len, int32_t B, int32_t k, float *out,
+                            int32_t *idx, int32_t *dist, int64_t max_seq_len,
+                            int use_hadamard, int squared_distance);
 
 int oracle_decode_step(int32_t Hq, int32_t Hkv, int64_t pool_tokens,
                        const float thr_q[3], const float thr_k[3], double scale,
@@ -457,6 +520,26 @@ int oracle_decode_step_variant(int32_t Hq, int32_t Hkv, int64_t pool_tokens,
                                const int32_t *seq_len, int32_t B, int32_t k, float *out,
                                int32_t *idx, int32_t *dist, int64_t max_seq_len,
                                int use_hadamard, int squared_distance) {
+  return oracle_decode_step_bits(Hq, Hkv, pool_tokens, thr_q, thr_k, 2, scale, q, k_new, v_new, K,
+                                 V, code_rows, seq_start, seq_len, B, k, out, idx, dist,
+                                 max_seq_len, use_hadamard, squared_distance);
+}
+
+/*
+ * The step with `bits`-bit codes (Section 4.4, bucketization ablation):
+ * thr_q, thr_k hold 2^bits - 1 thresholds, code_rows has 16 * bits bytes per
+ * row.  bits = 2 is the method.
+ */
+int oracle_decode_step_bits(int32_t Hq, int32_t Hkv, int64_t pool_tokens,
+                            const float *thr_q, const float *thr_k, int bits, double scale,
+                            const uint16_t *q, const uint16_t *k_new,
+                            const uint16_t *v_new, uint16_t *K, uint16_t *V,
+                            uint8_t *code_rows, const int64_t *seq_start,
+                            const int32_t *seq_len, int32_t B, int32_t k, float *out,
+                            int32_t *idx, int32_t *dist, int64_t max_seq_len,
+                            int use_hadamard, int squared_distance) {
+  if (bits < 1 || bits > 3) return ORACLE_BAD_ARG;
+  const int64_t row_bytes = (int64_t)16 * bits;
   if (Hq < 1 || Hkv < 1 || Hq % Hkv != 0 || B < 1 || k < 1) return ORACLE_BAD_ARG;
   if (!q || !K || !V || !code_rows || !seq_start || !seq_len || !out || !idx)
     return ORACLE_BAD_ARG;
@@ -476,8 +559,8 @@ int oracle_decode_step_variant(int32_t Hq, int32_t Hkv, int64_t pool_tokens,
         int64_t off = (int64_t)h * pool_tokens + row;
         memcpy(K + off * ORACLE_D, kn, ORACLE_D * sizeof(uint16_t));
         memcpy(V + off * ORACLE_D, vn, ORACLE_D * sizeof(uint16_t));
-        int rc = oracle_encode_variant(kn, 1, thr_k, use_hadamard, NULL,
-                                       code_rows + off * ORACLE_ROW_BYTES);
+        int rc = oracle_encode_bits(kn, 1, thr_k, bits, use_hadamard, NULL,
+                                    code_rows + off * row_bytes);
         if (rc != ORACLE_OK) return rc;
       }
     }
@@ -493,13 +576,13 @@ int oracle_decode_step_variant(int32_t Hq, int32_t Hkv, int64_t pool_tokens,
       float *o = out + ((int64_t)b * Hq + h) * ORACLE_D;
       int32_t *sel = idx + ((int64_t)b * Hq + h) * k;
       uint8_t qcode[ORACLE_D];
-      int rc = oracle_encode_variant(qv, 1, thr_q, use_hadamard, qcode, NULL);
+      int rc = oracle_encode_bits(qv, 1, thr_q, bits, use_hadamard, qcode, NULL);
       uint8_t *kc = (uint8_t *)malloc((size_t)(L > 0 ? L : 1) * ORACLE_D);
       int32_t *D = (int32_t *)malloc((size_t)(L > 0 ? L : 1) * sizeof(int32_t));
       if (!kc || !D) rc = ORACLE_NOMEM;
       if (rc == ORACLE_OK) {
         for (int64_t t = 0; t < L; ++t)
-          oracle_unpack_row(code_rows + (base + t) * ORACLE_ROW_BYTES, kc + t * ORACLE_D);
+          oracle_unpack_row_bits(code_rows + (base + t) * row_bytes, bits, kc + t * ORACLE_D);
         if (squared_distance) oracle_squared_distance(qcode, kc, L, D);
         else oracle_manhattan(qcode, kc, L, D);
         if (dist)

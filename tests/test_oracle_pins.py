@@ -366,6 +366,109 @@ def test_without_hadamard_the_selection_misses_the_true_top_k(oracle):
     assert overlap[True] > 0.25 and overlap[True] > 2.0 * overlap[False], overlap
 
 
+# ------------------------------------- bucketization ablation: 1-bit and 3-bit codes
+
+THR1 = (0.0,)
+THR7 = (-1.5, -1.0, -0.5, 0.0, 0.5, 1.0, 1.5)
+
+
+def test_bits_two_is_the_method(oracle):
+    rng = np.random.default_rng(30)
+    x = bf16(rng.standard_normal((20, 128)) * 2)
+    c2, r2 = oracle.encode(x, THR)
+    cb, rb = oracle.encode_bits(x, THR, 2)
+    assert np.array_equal(c2, cb) and np.array_equal(r2, rb)
+    assert np.array_equal(oracle.pack_row_bits(c2[0], 2), oracle.pack_row(c2[0]))
+
+
+@pytest.mark.parametrize("bits,thr", [(1, THR1), (3, THR7)])
+def test_bits_bucketize_and_encode_against_numpy(oracle, bits, thr):
+    # hand cases with strict '>': a value equal to a threshold falls in the lower bucket
+    y = np.array([-9.0, 0.0, 1e-9, 9.0]) * np.sqrt(128.0)
+    got = oracle.bucketize_n(y, thr)
+    assert got.tolist() == ([0, 0, 1, 1] if bits == 1 else [0, 3, 4, 7])
+    on = np.array(thr, dtype=np.float32).astype(np.float64) * np.sqrt(128.0)
+    assert oracle.bucketize_n(on, thr).tolist() == list(range(len(thr)))
+    # whole encode against a float matmul, away from the thresholds
+    rng = np.random.default_rng(31)
+    x = bf16(rng.standard_normal((60, 128)) * 1.5)
+    codes, rows = oracle.encode_bits(x, thr, bits)
+    yy = widen(x) @ scipy.linalg.hadamard(128).astype(np.float64) / np.sqrt(128.0)
+    ref = (yy[..., None] > np.array(thr)).sum(-1)
+    far = np.abs(yy[..., None] - np.array(thr)).min(-1) > 1e-6
+    assert np.array_equal(codes[far], ref[far]) and far.mean() > 0.999
+    assert codes.max() == (1 << bits) - 1 and rows.shape == (60, 16 * bits)
+    assert np.array_equal(oracle.unpack_rows_bits(rows, bits), codes)
+
+
+@pytest.mark.parametrize("bits", [1, 3])
+def test_bits_pack_layout_single_positions(oracle, bits):
+    # plane p of word g (32-bit little-endian, at byte (g*bits + p)*4) has bit j set iff bit p
+    # of the code of dimension 32g + j is set
+    for dim in (0, 7, 8, 31, 32, 95, 127):
+        for c in range(1, 1 << bits):
+            code = np.zeros(128, dtype=np.uint8)
+            code[dim] = c
+            row = oracle.pack_row_bits(code, bits)
+            words = row.view("<u4").reshape(4, bits)
+            g, j = divmod(dim, 32)
+            for p in range(bits):
+                want = np.zeros((4, bits), dtype=np.uint32)
+                assert int(words[g, p]) == (((c >> p) & 1) << j)
+            mask = np.ones((4, bits), dtype=bool)
+            mask[g] = False
+            assert np.all(words[mask] == 0)
+            assert np.array_equal(oracle.unpack_row_bits(row, bits), code)
+
+
+def test_three_bit_l1_bitplane_identity_brute_force():
+    # |a - b| on three bit planes: subtract with borrow, negate when the borrow out is set:
+    # the identity a bit-plane kernel may use, checked over all 64 pairs (no oracle call).
+    for a in range(8):
+        for b in range(8):
+            a0, a1, a2 = a & 1, (a >> 1) & 1, a >> 2
+            b0, b1, b2 = b & 1, (b >> 1) & 1, b >> 2
+            d0 = a0 ^ b0
+            br1 = (1 - a0) & b0
+            x1 = a1 ^ b1
+            d1 = x1 ^ br1
+            br2 = ((1 - a1) & b1) | ((1 - x1) & br1)
+            x2 = a2 ^ b2
+            d2 = x2 ^ br2
+            s = ((1 - a2) & b2) | ((1 - x2) & br2)
+            c1 = (1 - d0) & s
+            r1 = d1 ^ s ^ c1
+            c2 = (d1 ^ s) & c1
+            r2 = d2 ^ s ^ c2
+            assert abs(a - b) == d0 + 2 * r1 + 4 * r2
+
+
+@pytest.mark.parametrize("bits,thr", [(1, THR1), (3, THR7)])
+def test_bits_decode_step_composes_its_stages(oracle, bits, thr):
+    case = synth.make_case("t", 79, 2, 4, 2, [260, 77], [16],
+                           lambda b, L, h, rng: rng.choice(L, (2, 1), replace=False), append=True)
+    K, V = case.K.copy(), case.V.copy()
+    _, rows = oracle.encode_bits(K, thr, bits)
+    out, idx, dist = oracle.decode_step_bits(case.q, K, V, rows, case.seq_start, case.seq_len, 16,
+                                             thr, thr, bits, 1 / np.sqrt(128.0), k_new=case.k_new,
+                                             v_new=case.v_new, want_dist=True)
+    for b in range(2):
+        L, s = int(case.seq_len[b]), int(case.seq_start[b])
+        assert np.array_equal(K[:, s + L - 1], case.k_new[b])            # appended before the scan
+        for h in range(4):
+            kvh = h // 2
+            qc, _ = oracle.encode_bits(case.q[b, h], thr, bits)
+            kc, krows = oracle.encode_bits(K[kvh, s:s + L], thr, bits)
+            assert np.array_equal(krows, rows[kvh, s:s + L])
+            Dref = np.abs(qc.astype(int)[None] - kc.astype(int)).sum(-1)
+            assert np.array_equal(dist[b, h, :L], Dref) and Dref.max() <= ((1 << bits) - 1) * 128
+            sel = oracle.topk(Dref.astype(np.int32), 16)
+            assert np.array_equal(idx[b, h], sel)
+            ref = oracle.sparse_attention(case.q[b, h], K[kvh, s:s + L], V[kvh, s:s + L], sel,
+                                          1 / np.sqrt(128.0))
+            assert np.array_equal(out[b, h], ref)
+
+
 # ------------------------------------------------------------------ paged cache layout
 
 def _paged_step(oracle, pc, k):
