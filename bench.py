@@ -49,6 +49,8 @@ def parse_args():
     ap.add_argument("--variant", default="adamas",
                     choices=["adamas", "no_hadamard", "l2", "no_hadamard_l2"],
                     help="ablation switches of Section 4.4 (default: the method itself)")
+    ap.add_argument("--code-bits", type=int, default=2, choices=[1, 2, 3],
+                    help="bucketization granularity (Section 4.4 ablation; 2 is the method)")
     ap.add_argument("--paged", type=int, default=0, metavar="PAGE_TOKENS",
                     help="lay the cache out on randomly placed pages of this many tokens and time "
                          "adamas_decode_step_paged (0: contiguous sequences)")
@@ -62,13 +64,13 @@ def parse_args():
     return ap.parse_args()
 
 
-def algorithmic_bytes(B, Hq, Hkv, lens, k, append):
+def algorithmic_bytes(B, Hq, Hkv, lens, k, append, row_bytes=32):
     """Bytes the method itself must move per step: every code row once per KV head, every
     selected K and V row once per query head, q in, out back, plus the appended rows."""
-    codes = Hkv * sum(lens) * 32
+    codes = Hkv * sum(lens) * row_bytes
     gather = Hq * sum(min(k, L) for L in lens) * 512
     small = B * Hq * (256 + 512)
-    app = B * Hkv * (2 * 512 + 32) if append else 0
+    app = B * Hkv * (2 * 512 + row_bytes) if append else 0
     return codes + gather + small + app, codes
 
 
@@ -130,9 +132,14 @@ def main():
         src_row_dev = torch.from_numpy(src_row).to(dev)
     no_hadamard = args.variant in ("no_hadamard", "no_hadamard_l2")
     squared = args.variant in ("l2", "no_hadamard_l2")
-    cfg = A.Config.make(Hq, Hkv, pool, thr_k=synth.DEFAULT_THRESHOLDS,
+    bits = args.code_bits
+    thr = {1: (0.0,), 2: synth.DEFAULT_THRESHOLDS, 3: (-1.5, -1.0, -0.5, 0.0, 0.5, 1.0, 1.5)}[bits]
+    if bits != 2 and (page or squared):
+        raise SystemExit("--code-bits 1/3 is benchmarked on the contiguous layout with Eq. 6 only")
+    cfg = A.Config.make(Hq, Hkv, pool, thr_k=thr,
                         variant=(A.VARIANT_NO_HADAMARD if no_hadamard else 0)
-                        | (A.VARIANT_L2 if squared else 0))
+                        | (A.VARIANT_L2 if squared else 0), code_bits=0 if bits == 2 else bits)
+    row_bytes = cfg.code_row_bytes
     seq_start = torch.from_numpy(starts).to(dev)
     seq_len = torch.from_numpy(lens).to(dev)
 
@@ -193,7 +200,7 @@ def main():
         if page:    # pure re-layout of the rows just generated
             data["K"] = data["K"].index_select(1, src_row_dev).contiguous()
             data["V"] = data["V"].index_select(1, src_row_dev).contiguous()
-        data["codes"] = torch.empty(Hkv, pool, 32, dtype=torch.uint8, device=dev)
+        data["codes"] = torch.empty(Hkv, pool, row_bytes, dtype=torch.uint8, device=dev)
         data["out"] = torch.zeros(B, Hq, 128, device=dev)
         A.adamas_encode_keys(cfg, data["K"], data["codes"], 0, pool)
         layers.append(data)
@@ -206,7 +213,7 @@ def main():
     e1.record()
     torch.cuda.synchronize()
     encode_us = e0.elapsed_time(e1) * 1e3 / 5
-    encode_bytes = Hkv * pool * (256 + 32)
+    encode_bytes = Hkv * pool * (256 + row_bytes)
     idx0 = torch.empty(B, Hq, k, dtype=torch.int32, device=dev)
     ws = torch.empty(A.adamas_workspace_bytes(cfg, B, max_len, k), dtype=torch.uint8, device=dev)
     torch.cuda.synchronize()
@@ -316,7 +323,7 @@ def main():
     s1.record()
     torch.cuda.synchronize()
     stream_us = s0.elapsed_time(s1) * 1e3 / (n_rep * n_layers)
-    stream_gbps = Hkv * pool * 32 / stream_us / 1e3
+    stream_gbps = Hkv * pool * row_bytes / stream_us / 1e3
 
     # comparison point: dense decode attention (Eq. 1 over every cached row) on the same layers
     # (contiguous layout only: the dense kernel does not read page tables)
@@ -349,7 +356,8 @@ def main():
         full_us = s0.elapsed_time(s1) * 1e3 / (n_rep * n_layers)
         full_bytes = Hkv * int(lens.sum()) * 512
 
-    total_bytes, code_bytes = algorithmic_bytes(B, Hq, Hkv, [int(x) for x in lens], k, append)
+    total_bytes, code_bytes = algorithmic_bytes(B, Hq, Hkv, [int(x) for x in lens], k, append,
+                                               row_bytes)
     gbps_step = total_bytes / (us_step * 1e-6) / 1e9
     gbps_scan = code_bytes / (ms_scan * 1e-3) / 1e9
 
@@ -377,6 +385,7 @@ def main():
             "workload": wl["text"] + ", budget k=%d, %d rotating layer caches" % (k, n_layers),
             "batch": B, "q_heads": Hq, "kv_heads": Hkv, "context": int(max_len),
             "sum_context": int(lens.sum()), "k": k, "append": append, "variant": args.variant,
+            "code_bits": bits,
             "layout": "paged, %d-token pages, random placement" % page if page else "contiguous",
             "launch": "eager" if args.eager else "hipGraph of one %d-layer sweep" % n_layers,
         },
@@ -396,7 +405,7 @@ def main():
             "us_per_launch": round(ms_scan * 1e3, 3),
             "stream_read_same_planes": {"us_per_launch": round(stream_us, 3),
                                         "GBps": round(stream_gbps, 1),
-                                        "bytes_per_launch": Hkv * pool * 32},
+                                        "bytes_per_launch": Hkv * pool * row_bytes},
             "frac_of_stream_read": round(gbps_scan / stream_gbps, 4),
         },
     }
@@ -435,8 +444,7 @@ def main():
             kns, vns = np.ascontiguousarray(knh[:, sel_kv]), np.ascontiguousarray(vnh[:, sel_kv])
         else:
             kns = vns = None
-        _, rows = oracle.encode(Ks, synth.DEFAULT_THRESHOLDS,          # cache state, not timed
-                                hadamard=not no_hadamard)
+        _, rows = oracle.encode_bits(Ks, thr, bits, hadamard=not no_hadamard)   # cache state, not timed
         qs = np.ascontiguousarray(qh[:, sel_q])
         # repeated for a few seconds of wall time (the step is idempotent: an append rewrites
         # the same row with the same values); the median is reported
@@ -448,6 +456,10 @@ def main():
                     qs, Ks, Vs, rows, table_np, page, lens, k, synth.DEFAULT_THRESHOLDS,
                     synth.DEFAULT_THRESHOLDS, 1.0 / np.sqrt(128.0), k_new=kns, v_new=vns,
                     hadamard=not no_hadamard, squared=squared)
+            elif bits != 2:
+                ref_out, ref_idx, _ = oracle.decode_step_bits(
+                    qs, Ks, Vs, rows, starts, lens, k, thr, thr, bits, 1.0 / np.sqrt(128.0),
+                    k_new=kns, v_new=vns, hadamard=not no_hadamard)
             else:
                 ref_out, ref_idx, _ = oracle.decode_step(
                     qs, Ks, Vs, rows, starts, lens, k, synth.DEFAULT_THRESHOLDS,

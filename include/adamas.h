@@ -104,7 +104,13 @@ extern "C" {
  *   L2           tokens are ranked by sum_j (qcode_j - kcode_j)^2 instead of
  *                Eq. 6 (no square root: it would not change the ranking);
  *                distances then range over 0..ADAMAS_MAX_DISTANCE_L2.
- * Other bits -> ADAMAS_ERR_UNSUPPORTED.  (1-bit / 3-bit codes are not built.)
+ * Other bits -> ADAMAS_ERR_UNSUPPORTED.
+ * The bucketization ablation (1-bit and 3-bit codes) is adamas_config.code_bits:
+ * 2^code_bits - 1 thresholds, code rows of 16 * code_bits bytes (four words of
+ * code_bits 32-bit planes: plane p of word g holds, at bit j, bit p of the code
+ * of coefficient 32g + j; for 2 bits that is the 32-byte row described above),
+ * distances 0..(2^code_bits - 1) * 128.  Every `codes` / `qcodes` buffer then
+ * has rows of that size.  L2 needs 2-bit codes (else ADAMAS_ERR_UNSUPPORTED).
  */
 #define ADAMAS_VARIANT_NO_HADAMARD 1u
 #define ADAMAS_VARIANT_L2 2u
@@ -115,9 +121,11 @@ typedef struct adamas_config {
   int32_t num_kv_heads;  /* Hkv; Hq % Hkv == 0 */
   uint32_t variant;      /* 0 = the method; else ADAMAS_VARIANT_* flags (Sec. 4.4 ablations) */
   int64_t pool_tokens;   /* rows per KV head in K, V and codes */
-  float thr_k[3];        /* key thresholds B1 < B2 < B3 of Eq. 5, orthonormal scale */
-  float thr_q[3];        /* query thresholds (the paper uses one triple: pass the same) */
+  float thr_k[7];        /* key thresholds B1 < B2 < ... of Eq. 5, orthonormal scale; the first
+                            2^code_bits - 1 are used (three for the method) */
+  float thr_q[7];        /* query thresholds (the paper uses one set: pass the same) */
   float sm_scale;        /* softmax scale of Eq. 1; 0 means 1/sqrt(128) */
+  int32_t code_bits;     /* 0 or 2: 2-bit codes (the method); 1, 3: bucketization ablation */
 } adamas_config;
 
 /* Human-readable name of a status code; never NULL. */

@@ -54,18 +54,29 @@ class Config(ctypes.Structure):
         ("num_kv_heads", ctypes.c_int32),
         ("variant", ctypes.c_uint32),
         ("pool_tokens", ctypes.c_int64),
-        ("thr_k", ctypes.c_float * 3),
-        ("thr_q", ctypes.c_float * 3),
+        ("thr_k", ctypes.c_float * 7),
+        ("thr_q", ctypes.c_float * 7),
         ("sm_scale", ctypes.c_float),
+        ("code_bits", ctypes.c_int32),
     ]
+
+    @property
+    def code_row_bytes(self) -> int:
+        return 16 * (self.code_bits or 2)
 
     @classmethod
     def make(cls, num_q_heads: int, num_kv_heads: int, pool_tokens: int,
              thr_k: Sequence[float] = (-1.0, 0.0, 1.0), thr_q: Optional[Sequence[float]] = None,
-             sm_scale: float = 0.0, head_dim: int = HEAD_DIM, variant: int = 0) -> "Config":
+             sm_scale: float = 0.0, head_dim: int = HEAD_DIM, variant: int = 0,
+             code_bits: int = 0) -> "Config":
+        """thr_k / thr_q hold 2^code_bits - 1 thresholds (three for the default 2-bit codes)."""
         thr_q = thr_k if thr_q is None else thr_q
-        return cls(head_dim, num_q_heads, num_kv_heads, variant, pool_tokens,
-                   (ctypes.c_float * 3)(*thr_k), (ctypes.c_float * 3)(*thr_q), sm_scale)
+        n_thr = (1 << (code_bits or 2)) - 1
+        if len(thr_k) != n_thr or len(thr_q) != n_thr:
+            raise ValueError("%d thresholds needed for %d-bit codes" % (n_thr, code_bits or 2))
+        pad = lambda t: (ctypes.c_float * 7)(*(list(t) + [0.0] * (7 - len(t))))
+        return cls(head_dim, num_q_heads, num_kv_heads, variant, pool_tokens, pad(thr_k), pad(thr_q),
+                   sm_scale, code_bits)
 
 
 _lib = None
@@ -168,7 +179,7 @@ def adamas_encode_keys(cfg: Config, K, codes, row_begin: int, n_rows: int, strea
     hkv, pool = cfg.num_kv_heads, cfg.pool_tokens
     rc = library().adamas_encode_keys(
         ctypes.byref(cfg), _ptr(K, torch.bfloat16, "K", (hkv, pool, HEAD_DIM)),
-        _ptr(codes, torch.uint8, "codes", (hkv, pool, CODE_ROW_BYTES)), row_begin, n_rows,
+        _ptr(codes, torch.uint8, "codes", (hkv, pool, cfg.code_row_bytes)), row_begin, n_rows,
         _stream(stream))
     _check(rc, "adamas_encode_keys")
 
@@ -178,7 +189,7 @@ def adamas_encode_query(cfg: Config, q, qcodes, stream=None) -> None:
     batch = q.shape[0]
     rc = library().adamas_encode_query(
         ctypes.byref(cfg), _ptr(q, torch.bfloat16, "q", (batch, cfg.num_q_heads, HEAD_DIM)),
-        _ptr(qcodes, torch.uint8, "qcodes", (batch, cfg.num_q_heads, CODE_ROW_BYTES)), batch,
+        _ptr(qcodes, torch.uint8, "qcodes", (batch, cfg.num_q_heads, cfg.code_row_bytes)), batch,
         _stream(stream))
     _check(rc, "adamas_encode_query")
 
@@ -197,7 +208,7 @@ def adamas_decode_step_paged(cfg: Config, q, K, V, codes, page_table, page_token
         _ptr(v_new, torch.bfloat16, "v_new", (batch, hkv, HEAD_DIM), optional=True),
         _ptr(K, torch.bfloat16, "K", (hkv, pool, HEAD_DIM)),
         _ptr(V, torch.bfloat16, "V", (hkv, pool, HEAD_DIM)),
-        _ptr(codes, torch.uint8, "codes", (hkv, pool, CODE_ROW_BYTES)),
+        _ptr(codes, torch.uint8, "codes", (hkv, pool, cfg.code_row_bytes)),
         _ptr(page_table, torch.int32, "page_table"), page_table.shape[1], int(page_tokens),
         _ptr(seq_len, torch.int32, "seq_len", (batch,)), batch, k,
         _ptr(out, torch.float32, "out", (batch, cfg.num_q_heads, HEAD_DIM)),
@@ -242,8 +253,8 @@ def adamas_manhattan_distance(cfg: Config, qcodes, codes, seq_start, seq_len, di
     max_seq_len = dist_out.shape[2]
     rc = library().adamas_manhattan_distance(
         ctypes.byref(cfg),
-        _ptr(qcodes, torch.uint8, "qcodes", (batch, cfg.num_q_heads, CODE_ROW_BYTES)),
-        _ptr(codes, torch.uint8, "codes", (cfg.num_kv_heads, cfg.pool_tokens, CODE_ROW_BYTES)),
+        _ptr(qcodes, torch.uint8, "qcodes", (batch, cfg.num_q_heads, cfg.code_row_bytes)),
+        _ptr(codes, torch.uint8, "codes", (cfg.num_kv_heads, cfg.pool_tokens, cfg.code_row_bytes)),
         _ptr(seq_start, torch.int64, "seq_start", (batch,)),
         _ptr(seq_len, torch.int32, "seq_len", (batch,)), batch,
         _ptr(dist_out, torch.uint16, "dist_out", (batch, cfg.num_q_heads, max_seq_len)),
@@ -257,8 +268,8 @@ def adamas_select_topk(cfg: Config, qcodes, codes, seq_start, seq_len, k: int, i
     batch = qcodes.shape[0]
     rc = library().adamas_select_topk(
         ctypes.byref(cfg),
-        _ptr(qcodes, torch.uint8, "qcodes", (batch, cfg.num_q_heads, CODE_ROW_BYTES)),
-        _ptr(codes, torch.uint8, "codes", (cfg.num_kv_heads, cfg.pool_tokens, CODE_ROW_BYTES)),
+        _ptr(qcodes, torch.uint8, "qcodes", (batch, cfg.num_q_heads, cfg.code_row_bytes)),
+        _ptr(codes, torch.uint8, "codes", (cfg.num_kv_heads, cfg.pool_tokens, cfg.code_row_bytes)),
         _ptr(seq_start, torch.int64, "seq_start", (batch,)),
         _ptr(seq_len, torch.int32, "seq_len", (batch,)), batch, k,
         _ptr(idx_out, torch.int32, "idx_out", (batch, cfg.num_q_heads, k)),
@@ -310,7 +321,7 @@ def adamas_decode_step_stages(cfg: Config, q, K, V, codes, seq_start, seq_len, k
         _ptr(v_new, torch.bfloat16, "v_new", (batch, hkv, HEAD_DIM), optional=True),
         _ptr(K, torch.bfloat16, "K", (hkv, pool, HEAD_DIM)),
         _ptr(V, torch.bfloat16, "V", (hkv, pool, HEAD_DIM)),
-        _ptr(codes, torch.uint8, "codes", (hkv, pool, CODE_ROW_BYTES)),
+        _ptr(codes, torch.uint8, "codes", (hkv, pool, cfg.code_row_bytes)),
         _ptr(seq_start, torch.int64, "seq_start", (batch,)),
         _ptr(seq_len, torch.int32, "seq_len", (batch,)), batch, k,
         _ptr(out, torch.float32, "out", (batch, cfg.num_q_heads, HEAD_DIM)),

@@ -36,19 +36,42 @@ struct Plan {
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
+int code_bits(const adamas_config* c) { return c->code_bits == 0 ? 2 : c->code_bits; }
+
+// Code format + distance estimator id (see struct Dist).
+int metric_of(const adamas_config* c) {
+  if (code_bits(c) == 1) return kMetricB1;
+  if (code_bits(c) == 3) return kMetricB3;
+  return (c->variant & ADAMAS_VARIANT_L2) ? kMetricL2 : kMetricL1;
+}
+
+size_t hist_stride_of(int metric) {
+  switch (metric) {
+    case kMetricL2: return Dist<kMetricL2>::kStride;
+    case kMetricB1: return Dist<kMetricB1>::kStride;
+    case kMetricB3: return Dist<kMetricB3>::kStride;
+    default: return Dist<kMetricL1>::kStride;
+  }
+}
+
 int check_config(const adamas_config* c) {
   if (c == nullptr) return ADAMAS_ERR_BAD_ARG;
   if (c->num_q_heads < 1 || c->num_kv_heads < 1 || c->pool_tokens < 1)
     return ADAMAS_ERR_BAD_ARG;
   if (c->num_q_heads % c->num_kv_heads != 0) return ADAMAS_ERR_BAD_ARG;
   if (c->num_q_heads > 65535) return ADAMAS_ERR_BAD_ARG;
+  if (c->code_bits < 0 || c->code_bits > 3) return ADAMAS_ERR_BAD_ARG;
+  const int n_thr = (1 << code_bits(c)) - 1;
   for (const float* t : {c->thr_k, c->thr_q}) {
-    if (!(std::isfinite(t[0]) && std::isfinite(t[1]) && std::isfinite(t[2]))) return ADAMAS_ERR_BAD_ARG;
-    if (!(t[0] < t[1] && t[1] < t[2])) return ADAMAS_ERR_BAD_ARG;
+    for (int i = 0; i < n_thr; ++i) {
+      if (!std::isfinite(t[i])) return ADAMAS_ERR_BAD_ARG;
+      if (i > 0 && !(t[i - 1] < t[i])) return ADAMAS_ERR_BAD_ARG;
+    }
   }
   if (!std::isfinite(c->sm_scale) || c->sm_scale < 0.f) return ADAMAS_ERR_BAD_ARG;
   if (c->head_dim != ADAMAS_HEAD_DIM) return ADAMAS_ERR_UNSUPPORTED;
   if (c->variant & ~(ADAMAS_VARIANT_NO_HADAMARD | ADAMAS_VARIANT_L2)) return ADAMAS_ERR_UNSUPPORTED;
+  if ((c->variant & ADAMAS_VARIANT_L2) && code_bits(c) != 2) return ADAMAS_ERR_UNSUPPORTED;
   if (c->num_q_heads / c->num_kv_heads > ADAMAS_MAX_GROUP) return ADAMAS_ERR_UNSUPPORTED;
   return ADAMAS_OK;
 }
@@ -63,7 +86,7 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 
 Plan make_plan(const adamas_config* c, int32_t batch, int64_t max_seq_len, int32_t k) {
   Plan pl{};
-  pl.metric = (c->variant & ADAMAS_VARIANT_L2) ? kMetricL2 : kMetricL1;
+  pl.metric = metric_of(c);
   const int64_t planes = (int64_t)batch * c->num_kv_heads;
   // Scan tile (measured on MI355X): large tiles amortise the per-workgroup
   // prologue and leave the select kernel fewer tile histograms to read, small
@@ -103,9 +126,7 @@ Plan make_plan(const adamas_config* c, int32_t batch, int64_t max_seq_len, int32
   pl.off_dist = off;
   off = align256(off + heads * (size_t)pl.dist_stride * sizeof(uint16_t));
   pl.off_hist = off;
-  const size_t hist_stride = (c->variant & ADAMAS_VARIANT_L2) ? Dist<kMetricL2>::kStride
-                                                              : Dist<kMetricL1>::kStride;
-  off = align256(off + heads * (size_t)pl.n_tiles * hist_stride * sizeof(uint16_t));
+  off = align256(off + heads * (size_t)pl.n_tiles * hist_stride_of(pl.metric) * sizeof(uint16_t));
   pl.off_partial = off;
   off = align256(off + heads * (size_t)kMaxParts * kPartialStride * sizeof(float));
   pl.total = off;
@@ -113,12 +134,54 @@ Plan make_plan(const adamas_config* c, int32_t batch, int64_t max_seq_len, int32
 }
 
 // Thresholds as the kernels compare them (see struct Thresholds).
-Thresholds scaled(const adamas_config* c, const float thr[3]) {
-  Thresholds t;
+Thresholds scaled(const adamas_config* c, const float* thr) {
+  Thresholds t{};
   t.transform = (c->variant & ADAMAS_VARIANT_NO_HADAMARD) ? 0 : 1;
   const double root = t.transform ? std::sqrt((double)ADAMAS_HEAD_DIM) : 1.0;
-  for (int i = 0; i < 3; ++i) t.tau[i] = (double)thr[i] * root;
+  const int n_thr = (1 << code_bits(c)) - 1;
+  for (int i = 0; i < n_thr; ++i) t.tau[i] = (double)thr[i] * root;
   return t;
+}
+
+template <bool ATTN, int METRIC>
+void launch_select_m(bool paged, dim3 grid, hipStream_t st, const SelectParams& sl) {
+  if constexpr (ATTN) {
+    if (paged) {
+      hipLaunchKernelGGL((select_kernel<kSelThreads, ATTN, METRIC, true>), grid, dim3(kSelThreads), 0, st, sl);
+      return;
+    }
+  }
+  hipLaunchKernelGGL((select_kernel<kSelThreads, ATTN, METRIC, false>), grid, dim3(kSelThreads), 0, st, sl);
+}
+
+template <bool ATTN>
+void launch_select(int metric, bool paged, dim3 grid, hipStream_t st, const SelectParams& sl) {
+  switch (metric) {
+    case kMetricL2: launch_select_m<ATTN, kMetricL2>(paged, grid, st, sl); break;
+    case kMetricB1: launch_select_m<ATTN, kMetricB1>(paged, grid, st, sl); break;
+    case kMetricB3: launch_select_m<ATTN, kMetricB3>(paged, grid, st, sl); break;
+    default: launch_select_m<ATTN, kMetricL1>(paged, grid, st, sl); break;
+  }
+}
+
+// Bulk encode of n_vec vectors with the config's code width.
+void launch_encode_rows(const adamas_config* c, int grid, hipStream_t st, const uint16_t* src,
+                        uint8_t* dst, int64_t head_stride_rows, int64_t row_begin, int64_t n_rows,
+                        int64_t n_vec, const Thresholds& thr) {
+  switch (code_bits(c)) {
+    case 1:
+      hipLaunchKernelGGL(encode_rows_kernel<1>, dim3(grid), dim3(256), 0, st, src, dst,
+                         head_stride_rows, row_begin, n_rows, n_vec, thr);
+      break;
+    case 3:
+      hipLaunchKernelGGL(encode_rows_kernel<3>, dim3(grid), dim3(256), 0, st, src, dst,
+                         head_stride_rows, row_begin, n_rows, n_vec, thr);
+      break;
+    default:
+      hipLaunchKernelGGL(encode_rows_kernel<2>, dim3(grid), dim3(256), 0, st, src, dst,
+                         head_stride_rows, row_begin, n_rows, n_vec, thr);
+      break;
+  }
 }
 
 float scale_log2e(const adamas_config* c) {
@@ -161,8 +224,12 @@ void launch_scan_gm(const Plan& pl, dim3 grid, hipStream_t st, const ScanParams&
 
 template <int G, bool FUSED>
 void launch_scan_g(const Plan& pl, dim3 grid, hipStream_t st, const ScanParams& sp) {
-  if (pl.metric == kMetricL2) launch_scan_gm<G, FUSED, kMetricL2>(pl, grid, st, sp);
-  else launch_scan_gm<G, FUSED, kMetricL1>(pl, grid, st, sp);
+  switch (pl.metric) {
+    case kMetricL2: launch_scan_gm<G, FUSED, kMetricL2>(pl, grid, st, sp); break;
+    case kMetricB1: launch_scan_gm<G, FUSED, kMetricB1>(pl, grid, st, sp); break;
+    case kMetricB3: launch_scan_gm<G, FUSED, kMetricB3>(pl, grid, st, sp); break;
+    default: launch_scan_gm<G, FUSED, kMetricL1>(pl, grid, st, sp); break;
+  }
 }
 
 // pl.tile_tokens is 1024, 2048 or 4096 (make_plan).
@@ -241,9 +308,9 @@ int adamas_encode_keys(const adamas_config* cfg, const void* K, void* codes, int
   const int64_t n_vec = n_rows * cfg->num_kv_heads;
   const int64_t want = (n_vec + 63) / 64;  // 64 vectors per 256-thread workgroup
   const int grid = (int)(want < 16384 ? want : 16384);
-  hipLaunchKernelGGL(encode_rows_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream,
-                     static_cast<const uint16_t*>(K), static_cast<uint8_t*>(codes),
-                     cfg->pool_tokens, row_begin, n_rows, n_vec, scaled(cfg, cfg->thr_k));
+  launch_encode_rows(cfg, grid, (hipStream_t)stream, static_cast<const uint16_t*>(K),
+                     static_cast<uint8_t*>(codes), cfg->pool_tokens, row_begin, n_rows, n_vec,
+                     scaled(cfg, cfg->thr_k));
   return launch_status();
 }
 
@@ -257,9 +324,8 @@ int adamas_encode_query(const adamas_config* cfg, const void* q, void* qcodes, i
   const int64_t want = (n_vec + 63) / 64;
   const int grid = (int)(want < 16384 ? want : 16384);
   // queries form one "head" of n_vec consecutive rows
-  hipLaunchKernelGGL(encode_rows_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream,
-                     static_cast<const uint16_t*>(q), static_cast<uint8_t*>(qcodes), (int64_t)0,
-                     (int64_t)0, n_vec, n_vec, scaled(cfg, cfg->thr_q));
+  launch_encode_rows(cfg, grid, (hipStream_t)stream, static_cast<const uint16_t*>(q),
+                     static_cast<uint8_t*>(qcodes), 0, 0, n_vec, n_vec, scaled(cfg, cfg->thr_q));
   return launch_status();
 }
 
@@ -336,12 +402,7 @@ int adamas_select_topk(const adamas_config* cfg, const void* qcodes, const void*
   sl.n_tiles = pl.n_tiles;
   sl.tile_tokens = pl.tile_tokens;
   sl.seg_len = pl.seg_len;
-  if (pl.metric == kMetricL2)
-    hipLaunchKernelGGL((select_kernel<kSelThreads, false, kMetricL2, false>),
-                       dim3(pl.n_segs, cfg->num_q_heads, batch), dim3(kSelThreads), 0, st, sl);
-  else
-    hipLaunchKernelGGL((select_kernel<kSelThreads, false, kMetricL1, false>),
-                       dim3(pl.n_segs, cfg->num_q_heads, batch), dim3(kSelThreads), 0, st, sl);
+  launch_select<false>(pl.metric, false, dim3(pl.n_segs, cfg->num_q_heads, batch), st, sl);
   return launch_status();
 }
 
@@ -523,18 +584,7 @@ int decode_step_impl(const adamas_config* cfg, const void* q, const void* k_new,
   sl.page_table = page_table;
   sl.max_pages = max_pages;
   sl.page_shift = page_shift;
-  {
-    const dim3 sgrid(pl.n_segs, cfg->num_q_heads, batch), sblock(kSelThreads);
-    const bool l2 = pl.metric == kMetricL2, paged = page_table != nullptr;
-    if (l2 && paged)
-      hipLaunchKernelGGL((select_kernel<kSelThreads, true, kMetricL2, true>), sgrid, sblock, 0, st, sl);
-    else if (l2)
-      hipLaunchKernelGGL((select_kernel<kSelThreads, true, kMetricL2, false>), sgrid, sblock, 0, st, sl);
-    else if (paged)
-      hipLaunchKernelGGL((select_kernel<kSelThreads, true, kMetricL1, true>), sgrid, sblock, 0, st, sl);
-    else
-      hipLaunchKernelGGL((select_kernel<kSelThreads, true, kMetricL1, false>), sgrid, sblock, 0, st, sl);
-  }
+  launch_select<true>(pl.metric, page_table != nullptr, dim3(pl.n_segs, cfg->num_q_heads, batch), st, sl);
   if (int rc = launch_status()) return rc;
   if (pl.n_segs == 1 || sl.arrivals != nullptr) return ADAMAS_OK;  // the select kernel wrote `out` itself
   MergeParams mp{};

@@ -7,14 +7,22 @@
 namespace adamas {
 
 constexpr int kHeadDim = 128;
-constexpr int kRowBytes = 32;        // packed code row
-// Distance estimator between two code vectors: Eq. 6 (sum of |a - b|, 0..384)
-// or the squared-difference ablation of Section 4.4 (sum of (a - b)^2, 0..1152).
-constexpr int kMetricL1 = 0, kMetricL2 = 1;
+constexpr int kRowBytes = 32;        // packed code row of the method (2-bit codes)
+// Code format and distance estimator, one id for both:
+//   kMetricL1   2-bit codes, Eq. 6 (sum of |a - b|, 0..384): the method
+//   kMetricL2   2-bit codes, squared differences (Section 4.4 ablation, 0..1152)
+//   kMetricB1   1-bit codes, Eq. 6 = Hamming distance (Section 4.4, 0..128)
+//   kMetricB3   3-bit codes, Eq. 6 (Section 4.4, 0..896)
+// A code row is four words of kBits 32-bit planes (16 * kBits bytes): plane p of
+// word g holds, at bit j, bit p of the code of coefficient 32g + j.
+constexpr int kMetricL1 = 0, kMetricL2 = 1, kMetricB1 = 2, kMetricB3 = 3;
 template <int METRIC>
 struct Dist {
-  static constexpr int kBins = METRIC == kMetricL1 ? 385 : 1153;  // distinct distance values
-  // uint16 per stored tile histogram, a 16-byte multiple: 392 (784 B) / 1160 (2320 B)
+  static constexpr int kBits = METRIC == kMetricB1 ? 1 : METRIC == kMetricB3 ? 3 : 2;
+  static constexpr int kRowBytes = 16 * kBits;
+  static constexpr int kBins =  // distinct distance values
+      METRIC == kMetricL1 ? 385 : METRIC == kMetricL2 ? 1153 : METRIC == kMetricB1 ? 129 : 897;
+  // uint16 per stored tile histogram, a 16-byte multiple: 392, 1160, 136, 904
   static constexpr int kStride = (kBins + 7) / 8 * 8;
 };
 constexpr int kPartialStride = 132;  // floats per attention partial: m, l, pad, pad, o[128]

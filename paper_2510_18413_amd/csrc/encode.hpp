@@ -12,21 +12,38 @@ namespace adamas {
 // as given for the ablation without the transform (Section 4.4), which applies
 // Eq. 5 to the raw vector (transform == 0).
 struct Thresholds {
-  double tau[3];
+  double tau[7];  // 2^BITS - 1 used
   int transform;
 };
+
+// Bit planes of the bucket index c = #{i : y > tau_i} from the nested indicator
+// masks m_1 >= m_2 >= ... of Eq. 5 (bit j of m_i: coefficient j exceeds tau_i):
+// the lowest plane is the parity of all masks, the highest is the middle mask.
+template <int BITS, typename M>
+__device__ __forceinline__ void planes_from_masks(const M* m, M* plane) {
+  if constexpr (BITS == 1) {
+    plane[0] = m[0];
+  } else if constexpr (BITS == 2) {
+    plane[0] = m[0] ^ m[1] ^ m[2];
+    plane[1] = m[1];
+  } else {
+    plane[0] = m[0] ^ m[1] ^ m[2] ^ m[3] ^ m[4] ^ m[5] ^ m[6];
+    plane[1] = m[1] ^ m[3] ^ m[5];
+    plane[2] = m[3];
+  }
+}
 
 // One wave64 encodes one vector.  Lane l holds x[l] and x[l+64]; the
 // butterfly over index bit 6 is lane-local, bits 0..5 go across lanes.  All
 // sums are fp64 and exact for inputs within the documented exponent spread,
 // so the stage order does not influence the result.
-// Result: the four 64-bit words of the packed row, identical in every lane.
-// src must be wave-uniform.  All 64 lanes must be active.
-//
-// encode_values_wave takes the two elements already loaded (raw bf16 bits), so
-// that a caller can issue that load ahead of other memory traffic.
+// Result: w[p][g], plane p of word g of the packed row, identical in every lane.
+// All 64 lanes must be active.  The two elements come already loaded (raw bf16
+// bits), so that a caller can issue that load ahead of other memory traffic.
+template <int BITS>
 __device__ __forceinline__ void encode_values_wave(uint32_t bits_lo, uint32_t bits_hi,
-                                                   const Thresholds& thr, uint64_t w[4]) {
+                                                   const Thresholds& thr, uint32_t w[BITS][4]) {
+  constexpr int T = (1 << BITS) - 1;
   const int lane = threadIdx.x & 63;
   double a = (double)bf16_bits_to_float(bits_lo);
   double b = (double)bf16_bits_to_float(bits_hi);
@@ -45,30 +62,20 @@ __device__ __forceinline__ void encode_values_wave(uint32_t bits_lo, uint32_t bi
       b = upper ? pb - b : b + pb;
     }
   }
-  // Nested indicator masks m1 >= m2 >= m3 of Eq. 5; code = m1 + m2 + m3, so
-  // the high bit is m2 and the low bit is the parity m1 ^ m2 ^ m3.
-  const uint64_t a1 = __ballot(a > thr.tau[0]), a2 = __ballot(a > thr.tau[1]),
-                 a3 = __ballot(a > thr.tau[2]);
-  const uint64_t b1 = __ballot(b > thr.tau[0]), b2 = __ballot(b > thr.tau[1]),
-                 b3 = __ballot(b > thr.tau[2]);
-  const uint64_t alo = a1 ^ a2 ^ a3, ahi = a2, blo = b1 ^ b2 ^ b3, bhi = b2;
-  w[0] = (alo & 0xffffffffull) | (ahi << 32);
-  w[1] = (alo >> 32) | (ahi & 0xffffffff00000000ull);
-  w[2] = (blo & 0xffffffffull) | (bhi << 32);
-  w[3] = (blo >> 32) | (bhi & 0xffffffff00000000ull);
-}
-
-__device__ __forceinline__ void encode_vector_wave(const uint16_t* __restrict__ src,
-                                                   const Thresholds& thr, uint64_t w[4]) {
-  const int lane = threadIdx.x & 63;
-  encode_values_wave(src[lane], src[lane + 64], thr, w);
-}
-
-__device__ __forceinline__ void store_row_wave(uint8_t* __restrict__ dst, const uint64_t w[4]) {
-  const int lane = threadIdx.x & 63;
-  if (lane < 4) {
-    uint64_t v = lane == 0 ? w[0] : lane == 1 ? w[1] : lane == 2 ? w[2] : w[3];
-    reinterpret_cast<uint64_t*>(dst)[lane] = v;
+  uint64_t ma[T], mb[T], pa[BITS], pb[BITS];
+#pragma unroll
+  for (int i = 0; i < T; ++i) {
+    ma[i] = __ballot(a > thr.tau[i]);
+    mb[i] = __ballot(b > thr.tau[i]);
+  }
+  planes_from_masks<BITS>(ma, pa);
+  planes_from_masks<BITS>(mb, pb);
+#pragma unroll
+  for (int p = 0; p < BITS; ++p) {
+    w[p][0] = (uint32_t)pa[p];
+    w[p][1] = (uint32_t)(pa[p] >> 32);
+    w[p][2] = (uint32_t)pb[p];
+    w[p][3] = (uint32_t)(pb[p] >> 32);
   }
 }
 
@@ -107,7 +114,8 @@ __device__ __forceinline__ uint32_t push_greater(uint32_t mask, double y, double
 
 // Vector v of n_vec = n_heads * n_rows lives at
 // src + (head * head_stride_rows + row_begin + r) * 128, head = v / n_rows,
-// r = v % n_rows; its code row goes to the same row of dst (32 B rows).
+// r = v % n_rows; its code row goes to the same row of dst (16 * BITS byte rows).
+template <int BITS>
 __global__ __launch_bounds__(256) void encode_rows_kernel(const uint16_t* __restrict__ src,
                                                           uint8_t* __restrict__ dst,
                                                           int64_t head_stride_rows,
@@ -157,19 +165,25 @@ __global__ __launch_bounds__(256) void encode_rows_kernel(const uint16_t* __rest
         }
       }
     }
-    // Eq. 5 on the lane's 32 coefficients: nested indicator masks m1 >= m2 >= m3,
-    // code = m1 + m2 + m3, low bit = parity, high bit = m2.
-    uint32_t m1 = 0, m2 = 0, m3 = 0;
+    // Eq. 5 on the lane's 32 coefficients: nested indicator masks, then the
+    // planes of the bucket index; lane j stores word j of the row.
+    constexpr int T = (1 << BITS) - 1;
+    uint32_t m[T], plane[BITS];
 #pragma unroll
-    for (int i = 31; i >= 0; --i) {
-      m1 = push_greater(m1, x[i], thr.tau[0]);
-      m2 = push_greater(m2, x[i], thr.tau[1]);
-      m3 = push_greater(m3, x[i], thr.tau[2]);
+    for (int i = 0; i < T; ++i) m[i] = 0;
+#pragma unroll
+    for (int e = 31; e >= 0; --e) {
+#pragma unroll
+      for (int i = 0; i < T; ++i) m[i] = push_greater(m[i], x[e], thr.tau[i]);
     }
-    uint2 word;
-    word.x = m1 ^ m2 ^ m3;
-    word.y = m2;
-    *reinterpret_cast<uint2*>(dst + row * kRowBytes + j * 8) = word;
+    planes_from_masks<BITS>(m, plane);
+    uint32_t* out = reinterpret_cast<uint32_t*>(dst + row * (16 * BITS) + j * (4 * BITS));
+    if constexpr (BITS == 2) {
+      *reinterpret_cast<uint2*>(out) = make_uint2(plane[0], plane[1]);
+    } else {
+#pragma unroll
+      for (int p = 0; p < BITS; ++p) out[p] = plane[p];
+    }
   }
 }
 

@@ -61,9 +61,12 @@ template <int G, bool FUSED, int WAVES, int METRIC, bool PAGED>
 __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p) {
   static_assert(FUSED || !PAGED, "the paged layout is served by the fused step only");
   constexpr int kNumBins = Dist<METRIC>::kBins, kHistStride = Dist<METRIC>::kStride;
+  constexpr int BITS = Dist<METRIC>::kBits, kRowBytes = Dist<METRIC>::kRowBytes;
+  constexpr int kRowWords = 4 * BITS;  // 32-bit words per code row
   __shared__ uint32_t s_hist[G][kHistReplicas][kNumBins];
-  __shared__ uint32_t s_q[G][12];   // per query head: lo[4], hi[4], lo^hi[4]
-  __shared__ uint32_t s_new[8];     // code row of the appended key
+  // per query head: plane p of word wd at [4p + wd]; 2-bit codes also keep lo^hi at [8 + wd]
+  __shared__ uint32_t s_q[G][12];
+  __shared__ uint32_t s_new[kRowWords];  // code row of the appended key, as stored
   __shared__ uint32_t s_ready;      // query / new-key code rows published so far
   // per wave: its 256 distances per query head, in token order, for wide stores
   __shared__ uint16_t s_dt[WAVES][G][kScanTokPerThread * kWave];
@@ -129,17 +132,19 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
   // arrive; the encode runs while they travel.
   const bool appending = FUSED && p.k_new != nullptr && (L - 1) / tile_tokens == tile_id;
   const int n_enc = FUSED ? G + (appending ? 1 : 0) : 0;
-  uint32_t qraw_lo = 0, qraw_hi = 0;
+  uint32_t qraw[BITS];  // not fused: thread (head, word) of wave 0 fetches its planes
+#pragma unroll
+  for (int pl = 0; pl < BITS; ++pl) qraw[pl] = 0;
   if (!FUSED && wave == 0) {
     const int i = min(tid, G * 4 - 1);
     const uint32_t* qc =
         reinterpret_cast<const uint32_t*>(p.qcodes + (int64_t)(head0 + (i >> 2)) * kRowBytes);
-    qraw_lo = qc[2 * (i & 3)];
-    qraw_hi = qc[2 * (i & 3) + 1];
+#pragma unroll
+    for (int pl = 0; pl < BITS; ++pl) qraw[pl] = qc[BITS * (i & 3) + pl];
   }
 
   const uint8_t* plane = p.codes + ((int64_t)kvh * p.pool_tokens + start) * kRowBytes;
-  uint4 ra[kScanTokPerThread], rb[kScanTokPerThread];
+  uint4 rr[kScanTokPerThread][BITS];  // 16 * BITS bytes per row
 #pragma unroll
   for (int i = 0; i < kScanTokPerThread; ++i) {
     // Unconditional: a lane past the end re-reads the last row (masked at use).
@@ -154,8 +159,8 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
       r = min(t0 + (wave * kScanTokPerThread + i) * kWave + lane, L - 1);
     }
     const uint4* row = reinterpret_cast<const uint4*>(plane + r * kRowBytes);
-    ra[i] = row[0];
-    rb[i] = row[1];
+#pragma unroll
+    for (int c = 0; c < BITS; ++c) rr[i][c] = row[c];
   }
 
   // Nothing above may be consumed before the row loads have been issued.
@@ -163,7 +168,8 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
 #pragma unroll
     for (int r = 0; r < kEncRounds; ++r) asm volatile("" : "+v"(enc_lo[r]), "+v"(enc_hi[r]));
   } else {
-    asm volatile("" : "+v"(qraw_lo), "+v"(qraw_hi));
+#pragma unroll
+    for (int pl = 0; pl < BITS; ++pl) asm volatile("" : "+v"(qraw[pl]));
   }
 
   if (FUSED) {
@@ -171,18 +177,20 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
     for (int r = 0; r < kEncRounds; ++r) {
       const int v = wave + r * WAVES;
       if (v < n_enc) {
-        uint64_t w[4];
-        encode_values_wave(enc_lo[r], enc_hi[r], v < G ? p.thr_q : p.thr_k, w);
-        if (lane < 4) {
-          const uint64_t x = lane == 0 ? w[0] : lane == 1 ? w[1] : lane == 2 ? w[2] : w[3];
-          const uint32_t lo = (uint32_t)x, hi = (uint32_t)(x >> 32);
-          if (v < G) {
-            s_q[v][lane] = lo;
-            s_q[v][4 + lane] = hi;
+        uint32_t w[BITS][4];
+        encode_values_wave<BITS>(enc_lo[r], enc_hi[r], v < G ? p.thr_q : p.thr_k, w);
+        if (lane < 4) {  // lane wd publishes word wd
+#pragma unroll
+          for (int pl = 0; pl < BITS; ++pl) {
+            const uint32_t x = lane == 0 ? w[pl][0] : lane == 1 ? w[pl][1] : lane == 2 ? w[pl][2] : w[pl][3];
+            if (v < G) s_q[v][4 * pl + lane] = x;
+            else s_new[BITS * lane + pl] = x;  // code row of the appended key
+          }
+          if (BITS == 2 && v < G) {
+            const uint32_t lo = lane == 0 ? w[0][0] : lane == 1 ? w[0][1] : lane == 2 ? w[0][2] : w[0][3];
+            const uint32_t hi = lane == 0 ? w[BITS - 1][0] : lane == 1 ? w[BITS - 1][1]
+                              : lane == 2 ? w[BITS - 1][2] : w[BITS - 1][3];
             s_q[v][8 + lane] = lo ^ hi;
-          } else {  // code row of the appended key
-            s_new[2 * lane] = lo;
-            s_new[2 * lane + 1] = hi;
           }
         }
         if (lane == 0)
@@ -192,9 +200,9 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
   } else if (wave == 0) {
     if (tid < G * 4) {
       const int g = tid >> 2, wd = tid & 3;
-      s_q[g][wd] = qraw_lo;
-      s_q[g][4 + wd] = qraw_hi;
-      s_q[g][8 + wd] = qraw_lo ^ qraw_hi;
+#pragma unroll
+      for (int pl = 0; pl < BITS; ++pl) s_q[g][4 * pl + wd] = qraw[pl];
+      if (BITS == 2) s_q[g][8 + wd] = qraw[0] ^ qraw[BITS - 1];
     }
     if (lane == 0)
       __hip_atomic_fetch_add(&s_ready, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
@@ -215,19 +223,17 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
   // registers (a VALU instruction takes one scalar operand only, so scalar
   // planes cost an extra move per word); large groups keep them scalar to stay
   // within the register budget of a 1024-thread workgroup.
-  uint32_t qlo[G][4], qhi[G][4], qg[G][4];
+  // qp[g][j][wd]: plane j of word wd; for 2-bit codes j = 2 is lo ^ hi.
+  constexpr int QP = BITS == 2 ? 3 : BITS;
+  uint32_t qp[G][QP][4];
 #pragma unroll
   for (int g = 0; g < G; ++g) {
 #pragma unroll
-    for (int wd = 0; wd < 4; ++wd) {
-      if constexpr (G <= 4) {
-        qlo[g][wd] = s_q[g][wd];
-        qhi[g][wd] = s_q[g][4 + wd];
-        qg[g][wd] = s_q[g][8 + wd];
-      } else {
-        qlo[g][wd] = __builtin_amdgcn_readfirstlane(s_q[g][wd]);
-        qhi[g][wd] = __builtin_amdgcn_readfirstlane(s_q[g][4 + wd]);
-        qg[g][wd] = __builtin_amdgcn_readfirstlane(s_q[g][8 + wd]);
+    for (int j = 0; j < QP; ++j) {
+#pragma unroll
+      for (int wd = 0; wd < 4; ++wd) {
+        if constexpr (G <= 2 || (G <= 4 && BITS < 3)) qp[g][j][wd] = s_q[g][4 * j + wd];
+        else qp[g][j][wd] = __builtin_amdgcn_readfirstlane(s_q[g][4 * j + wd]);
       }
     }
   }
@@ -238,27 +244,57 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
     // keep the tokens in load order, so that each waits only for its own rows
     __builtin_amdgcn_sched_barrier(0);
     const int t = t0 + (wave * kScanTokPerThread + i) * kWave + lane;
-    uint32_t klo[4] = {ra[i].x, ra[i].z, rb[i].x, rb[i].z};
-    uint32_t khi[4] = {ra[i].y, ra[i].w, rb[i].y, rb[i].w};
+    // kw[BITS * wd + pl]: plane pl of word wd of the key row
+    uint32_t kw[kRowWords];
+#pragma unroll
+    for (int c = 0; c < BITS; ++c) {
+      kw[4 * c] = rr[i][c].x;
+      kw[4 * c + 1] = rr[i][c].y;
+      kw[4 * c + 2] = rr[i][c].z;
+      kw[4 * c + 3] = rr[i][c].w;
+    }
     if (appending && t == L - 1) {
 #pragma unroll
-      for (int wd = 0; wd < 4; ++wd) {
-        klo[wd] = s_new[2 * wd];
-        khi[wd] = s_new[2 * wd + 1];
-      }
+      for (int wq = 0; wq < kRowWords; ++wq) kw[wq] = s_new[wq];
     }
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-      uint32_t c1 = 0, c2 = 0, c3 = 0;
+      uint32_t d;
+      if constexpr (BITS == 2) {
+        uint32_t c1 = 0, c2 = 0, c3 = 0;
 #pragma unroll
-      for (int wd = 0; wd < 4; ++wd) {
-        const uint32_t xl = klo[wd] ^ qlo[g][wd], xh = khi[wd] ^ qhi[g][wd];
-        const uint32_t u = xh & ~(xl & qg[g][wd]);
-        c1 += __popc(xl);
-        c2 += __popc(u);
-        if constexpr (METRIC == kMetricL2) c3 += __popc(u & xl);
+        for (int wd = 0; wd < 4; ++wd) {
+          const uint32_t xl = kw[2 * wd] ^ qp[g][0][wd], xh = kw[2 * wd + 1] ^ qp[g][1][wd];
+          const uint32_t u = xh & ~(xl & qp[g][2][wd]);
+          c1 += __popc(xl);
+          c2 += __popc(u);
+          if constexpr (METRIC == kMetricL2) c3 += __popc(u & xl);
+        }
+        d = METRIC == kMetricL1 ? c1 + 2u * c2 : c1 + 4u * (c2 + c3);
+      } else if constexpr (BITS == 1) {
+        d = 0;
+#pragma unroll
+        for (int wd = 0; wd < 4; ++wd) d += __popc(kw[wd] ^ qp[g][0][wd]);
+      } else {
+        // |a - b| of 3-bit codes on bit planes (a query, b key): subtract with
+        // borrow, then negate where the borrow out (a < b) is set.
+        uint32_t c0 = 0, c1 = 0, c2 = 0;
+#pragma unroll
+        for (int wd = 0; wd < 4; ++wd) {
+          const uint32_t a0 = qp[g][0][wd], a1 = qp[g][1][wd], a2 = qp[g][2][wd];
+          const uint32_t b0 = kw[3 * wd], b1 = kw[3 * wd + 1], b2 = kw[3 * wd + 2];
+          const uint32_t d0 = a0 ^ b0, br1 = ~a0 & b0;
+          const uint32_t x1 = a1 ^ b1, d1 = x1 ^ br1, br2 = (~a1 & b1) | (~x1 & br1);
+          const uint32_t x2 = a2 ^ b2, d2 = x2 ^ br2, sg = (~a2 & b2) | (~x2 & br2);
+          const uint32_t e1 = d1 ^ sg, cy1 = ~d0 & sg;
+          const uint32_t r1 = e1 ^ cy1, cy2 = e1 & cy1;
+          const uint32_t r2 = d2 ^ sg ^ cy2;
+          c0 += __popc(d0);
+          c1 += __popc(r1);
+          c2 += __popc(r2);
+        }
+        d = c0 + 2u * c1 + 4u * c2;
       }
-      const uint32_t d = METRIC == kMetricL1 ? c1 + 2u * c2 : c1 + 4u * (c2 + c3);
       s_dt[wave][g][i * kWave + lane] = (uint16_t)d;
       if (t < L) {
         const int64_t head = head0 + g;
@@ -299,7 +335,7 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
                                  (int64_t)0), (p.pool_tokens >> p.page_shift) - 1);
       row = (int64_t)kvh * p.pool_tokens + (pg << p.page_shift) + ((L - 1) & ((1 << p.page_shift) - 1));
     }
-    if (lane < 8) reinterpret_cast<uint32_t*>(p.codes_w + row * kRowBytes)[lane] = s_new[lane];
+    if (lane < kRowWords) reinterpret_cast<uint32_t*>(p.codes_w + row * kRowBytes)[lane] = s_new[lane];
     reinterpret_cast<uint32_t*>(p.K + row * kHeadDim)[lane] =
         reinterpret_cast<const uint32_t*>(p.k_new + src)[lane];
     reinterpret_cast<uint32_t*>(p.V + row * kHeadDim)[lane] =

@@ -26,10 +26,11 @@ def host_dist(t: torch.Tensor) -> np.ndarray:
 class DeviceCase:
     """Device copies of a DecodeCase plus config, workspace and output buffers."""
 
-    def __init__(self, case, k, encode=True, variant=0):
+    def __init__(self, case, k, encode=True, variant=0, code_bits=0, thresholds=None):
         self.case, self.k = case, k
-        self.cfg = A.Config.make(case.Hq, case.Hkv, case.pool_tokens, thr_k=case.thresholds,
-                                 variant=variant)
+        self.thresholds = case.thresholds if thresholds is None else thresholds
+        self.cfg = A.Config.make(case.Hq, case.Hkv, case.pool_tokens, thr_k=self.thresholds,
+                                 variant=variant, code_bits=code_bits)
         self.q = dev_bf16(case.q)
         self.K = dev_bf16(case.K)
         self.V = dev_bf16(case.V)
@@ -38,7 +39,8 @@ class DeviceCase:
         self.seq_start = torch.from_numpy(case.seq_start).cuda()
         self.seq_len = torch.from_numpy(case.seq_len).cuda()
         self.max_len = max(case.max_seq_len, 1)
-        self.codes = torch.zeros(case.Hkv, case.pool_tokens, 32, dtype=torch.uint8, device="cuda")
+        self.codes = torch.zeros(case.Hkv, case.pool_tokens, self.cfg.code_row_bytes,
+                                 dtype=torch.uint8, device="cuda")
         nbytes = A.adamas_workspace_bytes(self.cfg, case.B, self.max_len, k)
         assert nbytes > 0
         # poison the workspace: the library must not rely on its contents

@@ -67,6 +67,8 @@ def test_workspace_bytes():
     (dict(sm_scale=float("inf")), -1),
     (dict(num_q_heads=32, num_kv_heads=2), -2),        # group of 16 > ADAMAS_MAX_GROUP
     (dict(variant=4), -2),                             # unknown variant bit
+    (dict(code_bits=3, thr_k=(0.0,) * 7), -1),          # seven thresholds must increase
+    (dict(code_bits=1, thr_k=(0.0,), variant=2), -2),   # L2 needs 2-bit codes
 ])
 def test_bad_config_rejected_everywhere(bad, status):
     lib, c = A.library(), cfg(**bad)

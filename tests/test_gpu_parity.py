@@ -420,6 +420,106 @@ def test_variant_without_hadamard_loses_the_true_top_k(H, oracle):
     assert overlap[0] > 0.3 and overlap[0] > 2.0 * overlap[A.VARIANT_NO_HADAMARD], overlap
 
 
+# ----------------------------------- bucketization ablation: 1-bit and 3-bit codes
+
+BITS_THR = {1: (0.0,), 3: (-1.5, -1.0, -0.5, 0.0, 0.5, 1.0, 1.5)}
+
+
+@pytest.mark.parametrize("bits", [1, 3])
+@pytest.mark.parametrize("B,Hq,Hkv,lens,k,append,variant", [
+    (1, 1, 1, [1024], 64, False, 0),
+    (2, 8, 2, [4097, 333], 128, True, 0),
+    (3, 4, 4, [0, 5000, 9000], 256, False, 1),
+    (1, 8, 1, [20000], 1024, True, 0),
+    (1, 6, 2, [2500], 32, True, 1),
+])
+def test_code_bits_decode_step_matches_oracle(H, oracle, bits, B, Hq, Hkv, lens, k, append, variant):
+    """1-bit and 3-bit codes through every stage: code bytes of keys and queries, distances,
+    indices bit for bit; attention within tolerance; appended rows in the cache."""
+    import paper_2510_18413_amd as A
+    thr = BITS_THR[bits]
+    hadamard = not (variant & A.VARIANT_NO_HADAMARD)
+    case = small_case(1000 + 10 * bits + Hq, B, Hq, Hkv, lens, append=append)
+    d = H.DeviceCase(case, k, variant=variant, code_bits=bits, thresholds=thr)
+    assert d.codes.shape[-1] == 16 * bits
+    _, rows0 = oracle.encode_bits(case.K, thr, bits, hadamard=hadamard)
+    assert np.array_equal(d.codes.cpu().numpy(), rows0)
+    qcodes = torch.zeros(B, Hq, 16 * bits, dtype=torch.uint8, device="cuda")
+    A.adamas_encode_query(d.cfg, d.q, qcodes)
+    torch.cuda.synchronize()
+    _, qrows = oracle.encode_bits(case.q, thr, bits, hadamard=hadamard)
+    assert np.array_equal(qcodes.cpu().numpy(), qrows)
+    out, idx = d.decode_step()
+    K, V = case.K.copy(), case.V.copy()
+    rows = rows0.copy()
+    ref_out, ref_idx, ref_dist = oracle.decode_step_bits(
+        case.q, K, V, rows, case.seq_start, case.seq_len, k, thr, thr, bits, H.SM_SCALE,
+        k_new=case.k_new, v_new=case.v_new, want_dist=True, hadamard=hadamard)
+    assert np.array_equal(idx, ref_idx)
+    assert H.attn_rel_err(out, ref_out) <= H.ATTN_TOL
+    if append:
+        assert np.array_equal(d.codes.cpu().numpy(), rows)
+        assert np.array_equal(H.host_u16(d.K), K) and np.array_equal(H.host_u16(d.V), V)
+    dist = torch.full((B, Hq, d.max_len), 0xFFFF, dtype=torch.uint16, device="cuda")
+    idx2 = torch.full((B, Hq, k), -7, dtype=torch.int32, device="cuda")
+    A.adamas_select_topk(d.cfg, qcodes, d.codes, d.seq_start, d.seq_len, k, idx2, d.max_len,
+                         d.workspace, dist_out=dist)
+    torch.cuda.synchronize()
+    got = H.host_dist(dist)
+    for b in range(B):
+        L = int(case.seq_len[b])
+        assert np.array_equal(got[b, :, :L], ref_dist[b, :, :L])
+    assert np.array_equal(idx2.cpu().numpy(), ref_idx)
+
+
+@pytest.mark.parametrize("bits", [1, 3])
+def test_code_bits_extreme_distances(H, oracle, bits):
+    """Lowest against highest code everywhere: the largest distance, (2^bits - 1) * 128."""
+    import paper_2510_18413_amd as A
+    case = small_case(1050, 1, 1, 1, [2000], needles=0)
+    case.K[:] = 0
+    case.K[0, :, 0] = int(synth.f32_to_bf16_bits(np.float32([64.0]))[0])
+    case.q[:] = 0
+    case.q[0, 0, 0] = int(synth.f32_to_bf16_bits(np.float32([-64.0]))[0])
+    d = H.DeviceCase(case, 16, code_bits=bits, thresholds=BITS_THR[bits])
+    qcodes = torch.zeros(1, 1, 16 * bits, dtype=torch.uint8, device="cuda")
+    A.adamas_encode_query(d.cfg, d.q, qcodes)
+    dist = torch.zeros(1, 1, 2000, dtype=torch.uint16, device="cuda")
+    A.adamas_manhattan_distance(d.cfg, qcodes, d.codes, d.seq_start, d.seq_len, dist)
+    torch.cuda.synchronize()
+    assert np.all(H.host_dist(dist) == ((1 << bits) - 1) * 128)
+    out, idx = d.decode_step()
+    assert idx[0, 0].tolist() == list(range(16))
+
+
+def test_code_bits_with_paged_cache(H, oracle):
+    """3-bit codes on a paged cache: the two switches compose."""
+    import paper_2510_18413_amd as A
+    thr = BITS_THR[3]
+    case = small_case(1060, 2, 4, 2, [3000, 700], append=True)
+    pc = synth.paginate(case, 128, seed=13)
+    cfg = A.Config.make(4, 2, pc.pool_tokens, thr_k=thr, code_bits=3)
+    Kd, Vd, qd = H.dev_bf16(pc.K), H.dev_bf16(pc.V), H.dev_bf16(case.q)
+    codes = torch.zeros(2, pc.pool_tokens, 48, dtype=torch.uint8, device="cuda")
+    A.adamas_encode_keys(cfg, Kd, codes, 0, pc.pool_tokens)
+    ws = torch.empty(A.adamas_workspace_bytes(cfg, 2, 3000, 64), dtype=torch.uint8, device="cuda")
+    out = torch.zeros(2, 4, 128, device="cuda")
+    idx = torch.zeros(2, 4, 64, dtype=torch.int32, device="cuda")
+    A.adamas_decode_step_paged(cfg, qd, Kd, Vd, codes, torch.from_numpy(pc.page_table).cuda(), 128,
+                               torch.from_numpy(case.seq_len).cuda(), 64, out, 3000, ws,
+                               k_new=H.dev_bf16(case.k_new), v_new=H.dev_bf16(case.v_new),
+                               idx_out=idx)
+    torch.cuda.synchronize()
+    # reference: the contiguous 3-bit step of the oracle on the unscattered case
+    K, V = case.K.copy(), case.V.copy()
+    _, rows = oracle.encode_bits(K, thr, 3)
+    ref_out, ref_idx, _ = oracle.decode_step_bits(case.q, K, V, rows, case.seq_start, case.seq_len,
+                                                  64, thr, thr, 3, H.SM_SCALE, k_new=case.k_new,
+                                                  v_new=case.v_new)
+    assert np.array_equal(idx.cpu().numpy(), ref_idx)
+    assert H.attn_rel_err(out.cpu().numpy(), ref_out) <= H.ATTN_TOL
+
+
 # --------------------------------------------------------------------- paged cache layout
 
 @pytest.mark.parametrize("variant", [0, 3])
