@@ -320,6 +320,53 @@ def test_decode_step_back_to_back_on_one_workspace(H, oracle):
         assert torch.equal(g, want[it % 2]), f"call {it}"
 
 
+def test_decode_step_in_a_replayed_graph(H, oracle):
+    """The fused step captured in a HIP graph (two layers with different inputs on one
+    workspace) and replayed several times, with eager calls and synchronisations between the
+    replays: every replay must give the eager result, which must be the oracle's."""
+    import paper_2510_18413_amd as A
+    cases = [small_case(620 + i, 2, 8, 2, [20000, 5000 + 3000 * i], append=(i == 1)) for i in range(2)]
+    devs = [H.DeviceCase(c, 128) for c in cases]
+    shared = devs[0].workspace
+    eager = []
+    for d in devs:
+        A.adamas_decode_step(d.cfg, d.q, d.K, d.V, d.codes, d.seq_start, d.seq_len, d.k, d.out,
+                             d.max_len, shared, k_new=d.k_new, v_new=d.v_new, idx_out=d.idx)
+        torch.cuda.synchronize()
+        ref = H.oracle_step(d.case, d.k, want_dist=False)
+        assert np.array_equal(d.idx.cpu().numpy(), ref["idx"])
+        assert H.attn_rel_err(d.out.cpu().numpy(), ref["out"]) <= H.ATTN_TOL
+        eager.append((d.out.clone(), d.idx.clone()))
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        for d in devs:      # warm-up on the capture stream
+            A.adamas_decode_step(d.cfg, d.q, d.K, d.V, d.codes, d.seq_start, d.seq_len, d.k,
+                                 d.out, d.max_len, shared, k_new=d.k_new, v_new=d.v_new,
+                                 idx_out=d.idx)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(g, stream=side):
+            for d in devs:
+                A.adamas_decode_step(d.cfg, d.q, d.K, d.V, d.codes, d.seq_start, d.seq_len, d.k,
+                                     d.out, d.max_len, shared, k_new=d.k_new, v_new=d.v_new,
+                                     idx_out=d.idx)
+    torch.cuda.synchronize()
+    for rep in range(5):
+        for d in devs:
+            d.out.fill_(float("nan"))
+            d.idx.fill_(-9)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for d, (o, i) in zip(devs, eager):
+            assert torch.equal(d.out, o) and torch.equal(d.idx, i), f"replay {rep}"
+        # eager work of the program itself between replays, on the same workspace
+        d = devs[rep % 2]
+        A.adamas_decode_step(d.cfg, d.q, d.K, d.V, d.codes, d.seq_start, d.seq_len, d.k, d.out,
+                             d.max_len, shared, k_new=d.k_new, v_new=d.v_new)
+        torch.cuda.synchronize()
+
+
 def test_appended_token_is_a_candidate(H, oracle):
     case = small_case(602, 1, 2, 2, [4097], append=True)     # new token alone in the 2nd segment
     case.q[0, 0] = case.k_new[0, 0]
