@@ -64,6 +64,16 @@ def parse_args():
     return ap.parse_args()
 
 
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def algorithmic_bytes(B, Hq, Hkv, lens, k, append, row_bytes=32):
     """Bytes the method itself must move per step: every code row once per KV head, every
     selected K and V row once per query head, q in, out back, plus the appended rows."""
@@ -356,6 +366,45 @@ def main():
         full_us = s0.elapsed_time(s1) * 1e3 / (n_rep * n_layers)
         full_bytes = Hkv * int(lens.sum()) * 512
 
+    def graph_us(fn, reps=8):
+        """us per call of fn(layer_dict) over the rotating layers, graph replay, HIP events."""
+        for d in layers:
+            fn(d)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for d in layers:
+                fn(d)
+        g.replay()
+        torch.cuda.synchronize()
+        a, b_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            g.replay()
+        b_.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b_) * 1e3 / (reps * len(layers))
+
+    # the stand-alone entry points, stage by stage (contiguous layout), next to the fused step
+    stage_us = None
+    if not page:
+        qcodes = torch.empty(B, Hq, row_bytes, dtype=torch.uint8, device=dev)
+        idx_s = torch.empty(B, Hq, k, dtype=torch.int32, device=dev)
+        out_s = torch.empty(B, Hq, 128, device=dev)
+        stage_us = {
+            "encode_query": graph_us(lambda d: A.adamas_encode_query(cfg, d["q"], qcodes)),
+            "select_topk": graph_us(lambda d: A.adamas_select_topk(
+                cfg, qcodes, d["codes"], seq_start, seq_len, k, idx_s, max_len, ws)),
+            "sparse_attn": graph_us(lambda d: A.adamas_sparse_attn(
+                cfg, d["q"], d["K"], d["V"], seq_start, idx_s, out_s, max_len, ws)),
+        }
+        stage_us = {n: round(v, 2) for n, v in stage_us.items()}
+        stage_us["sum"] = round(sum(stage_us.values()), 2)
+
+    # one layer over and over: its 32 MiB of codes and the workspace stay in the 256 MB
+    # Infinity Cache, so this is NOT the HBM figure
+    resident_us = graph_us(lambda d: step(0))      # n_layers launches per replay, all on layer 0
+
     total_bytes, code_bytes = algorithmic_bytes(B, Hq, Hkv, [int(x) for x in lens], k, append,
                                                row_bytes)
     gbps_step = total_bytes / (us_step * 1e-6) / 1e9
@@ -412,6 +461,9 @@ def main():
     result["bulk_encode"] = {"us": round(encode_us, 1), "rows": Hkv * pool,
                              "GBps": round(encode_bytes / encode_us / 1e3, 1),
                              "hbm_frac": round(encode_bytes / encode_us / 1e3 / HBM_PEAK_GBPS, 4)}
+    if stage_us is not None:
+        result["stages_us_standalone_entry_points"] = stage_us
+    result["cache_resident_us_per_layer"] = round(resident_us, 3)
     if full_us is not None:
         result["full_attention"] = {"us_per_layer": round(full_us, 2),
                                     "GBps": round(full_bytes / full_us / 1e3, 1),
@@ -467,12 +519,24 @@ def main():
                     hadamard=not no_hadamard, squared=squared)
             times.append(time.perf_counter() - t0)
         cpu_s = sorted(times)[len(times) // 2]
+        oracle.set_threads(1)
+        t0 = time.perf_counter()
+        if bits == 2 and not page:
+            oracle.decode_step(qs, Ks, Vs, rows, starts, lens, k, synth.DEFAULT_THRESHOLDS,
+                               synth.DEFAULT_THRESHOLDS, 1.0 / np.sqrt(128.0), k_new=kns, v_new=vns,
+                               hadamard=not no_hadamard, squared=squared)
+            cpu_1t = time.perf_counter() - t0
+        else:
+            cpu_1t = None
+        oracle.set_threads(cores)
         scale_up = Hkv / n_kv
         result["cpu_baseline"] = {
             "value": round(cpu_s * scale_up * 1e6, 1),
             "unit": "us/layer",
             "cores": cores,
             "kind": "oracle",
+            "single_thread_us_per_layer": None if cpu_1t is None else round(cpu_1t * scale_up * 1e6, 1),
+            "cpu_model": cpu_model(),
             "sample": "one decode step of layer 0 on %d of %d KV heads (%d query heads), full "
                       "context, median of %d runs %.3f s, scaled by %.1f" % (
                           n_kv, Hkv, len(sel_q), len(times), cpu_s, scale_up),
