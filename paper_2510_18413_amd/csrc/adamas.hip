@@ -29,7 +29,8 @@ struct Plan {
   int n_tiles;       // scan tiles per (sequence, KV head)
   int seg_len;       // tokens per select workgroup, multiple of tile_tokens and of kSelPass
   int n_segs;        // select workgroups per (sequence, query head)
-  int metric;        // kMetricL1 (Eq. 6) or kMetricL2 (squared-difference variant)
+  int metric;        // code format + distance estimator (struct Dist)
+  int g_split;       // scan workgroups per (tile, KV head), each with a share of the query group
   int64_t dist_stride;
   size_t off_dist, off_hist, off_partial, total;
 };
@@ -106,6 +107,12 @@ Plan make_plan(const adamas_config* c, int32_t batch, int64_t max_seq_len, int32
     pl.tile_tokens = 1024;
   }
   pl.n_tiles = (int)((max_seq_len + pl.tile_tokens - 1) / pl.tile_tokens);
+  // Few planes and a query group: the scan is then bound by the distance
+  // arithmetic of the workgroups that exist, not by memory, so the group is cut
+  // in two (each half re-reads the rows) until there is a workgroup per compute unit.
+  pl.g_split = 1;
+  const int group = c->num_q_heads / c->num_kv_heads;
+  if (group % 2 == 0 && n_wg(pl.tile_tokens) * 2 <= kTargetWorkgroups) pl.g_split = 2;
   // Select + attention: a head is cut into segments, one workgroup each (a
   // single compute unit is too slow to compact a whole 32K-token head or to
   // gather all of its rows), and the segments' attention partials are merged
@@ -234,8 +241,10 @@ void launch_scan_g(const Plan& pl, dim3 grid, hipStream_t st, const ScanParams& 
 
 // pl.tile_tokens is 1024, 2048 or 4096 (make_plan).
 template <bool FUSED>
-void launch_scan(int G, const Plan& pl, int Hkv, int batch, hipStream_t st, const ScanParams& sp) {
-  const dim3 grid(pl.n_tiles, Hkv, batch);
+void launch_scan(int group, const Plan& pl, int Hkv, int batch, hipStream_t st, ScanParams sp) {
+  sp.g_split = group % pl.g_split == 0 ? pl.g_split : 1;
+  const int G = group / sp.g_split;
+  const dim3 grid(pl.n_tiles, Hkv * sp.g_split, batch);
   switch (G) {
     case 1: launch_scan_g<1, FUSED>(pl, grid, st, sp); break;
     case 2: launch_scan_g<2, FUSED>(pl, grid, st, sp); break;

@@ -49,6 +49,7 @@ struct ScanParams {
   int64_t arrivals_stride;
   int64_t pool_tokens, max_seq_len;
   int32_t Hq, Hkv, n_tiles;
+  int32_t g_split;           // workgroups per (tile, KV head): each takes G of the group's G * g_split query heads
   // Paged cache (PAGED kernels only): token t of sequence b lives in pool row
   // page_table[b * max_pages + (t >> page_shift)] << page_shift | (t & page mask).
   const int32_t* page_table;
@@ -71,12 +72,15 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
   // per wave: its 256 distances per query head, in token order, for wide stores
   __shared__ uint16_t s_dt[WAVES][G][kScanTokPerThread * kWave];
 
-  const int tile_id = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+  // blockIdx.y = KV head * g_split + part: the G query heads of this workgroup are
+  // part `gsub` of the KV head's group of G * g_split (the parts re-read the rows).
+  const int tile_id = blockIdx.x, kvh = blockIdx.y / p.g_split, gsub = blockIdx.y % p.g_split;
+  const int b = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   constexpr int nthreads = WAVES * kWave;
   constexpr int tile_tokens = nthreads * kScanTokPerThread;
   const int t0 = tile_id * tile_tokens;
-  const int head0 = b * p.Hq + kvh * G;
+  const int head0 = b * p.Hq + (kvh * p.g_split + gsub) * G;
 
   // First of all the encoding waves request their vectors (G queries and, if
   // the call appends, the new key): their addresses need nothing from memory,
@@ -327,7 +331,7 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
   // Alg. 1 line 4: the new token's K, V and code row enter the cache.  The
   // scan above already used the new code row (from LDS); the stores come last
   // so that no other memory operation sits between the row loads and their use.
-  if (appending && wave == 0) {
+  if (appending && wave == 0 && gsub == 0) {
     const int64_t src = ((int64_t)b * p.Hkv + kvh) * kHeadDim;
     int64_t row = (int64_t)kvh * p.pool_tokens + start + (L - 1);
     if constexpr (PAGED) {
