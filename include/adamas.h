@@ -36,7 +36,9 @@
  * coefficients 32g..32g+31 (natural/Sylvester order); bit j is the low bit
  * of the 2-bit code of coefficient 32g+j, bit 32+j its high bit.  This keeps
  * the paper's density of eight codes per 16 bits (1/16 of the bf16 K+V
- * bytes); the paper does not fix a bit order.
+ * bytes); the paper does not fix a bit order.  (Everything here describes
+ * the method itself; the ablation switches further down change the code
+ * width -- rows of 16 or 48 bytes -- or the distance estimator.)
  *
  * Codes.  code_j = #{ i : y_j > thr[i] } in {0,1,2,3}, strict comparison,
  * where y = x H / sqrt(128) is the orthonormal transform evaluated EXACTLY:
@@ -161,7 +163,8 @@ int adamas_encode_query(const adamas_config *cfg, const void *q, void *qcodes,
  * Alg. 1 l.5 (Eq. 6): dist_out[b][h][t] = sum_j |qcode[b][h]_j - code[kv(h)][seq_start[b]+t]_j|
  * for t < seq_len[b]; entries t >= seq_len[b] are left untouched.
  * qcodes uint8 [batch][Hq][32]; seq_start int64 [batch]; seq_len int32 [batch];
- * dist_out uint16 [batch][Hq][max_seq_len], values 0..384.
+ * dist_out uint16 [batch][Hq][max_seq_len], values 0..384 (other ranges with
+ * the ablation switches: see ADAMAS_VARIANT_L2 and code_bits).
  */
 int adamas_manhattan_distance(const adamas_config *cfg, const void *qcodes,
                               const void *codes, const int64_t *seq_start,

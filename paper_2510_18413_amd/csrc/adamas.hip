@@ -25,9 +25,9 @@ constexpr double kLog2e = 1.4426950408889634;
 
 // How one call is cut into workgroups and where its scratch lives in the workspace.
 struct Plan {
-  int tile_tokens;   // tokens per scan workgroup (threads = tile_tokens / 4)
+  int tile_tokens;   // tokens per scan workgroup (threads = tile_tokens / 4): 1024, 2048 or 4096
   int n_tiles;       // scan tiles per (sequence, KV head)
-  int seg_len;       // tokens per select workgroup, multiple of tile_tokens and of kSelPass
+  int seg_len;       // tokens per select workgroup, a multiple of kSegGranule (hence of the tile)
   int n_segs;        // select workgroups per (sequence, query head)
   int metric;        // code format + distance estimator (struct Dist)
   int g_split;       // scan workgroups per (tile, KV head), each with a share of the query group
