@@ -73,3 +73,12 @@ def test_config4_batched_ragged(H, oracle):
     case = synth.batched_ragged()
     assert case.seq_len.min() >= 8192 and case.seq_len.max() <= 32768
     check_case(H, oracle, case, case.budgets)
+
+
+def test_maximum_sequence_length_and_budget(H, oracle):
+    """The documented limits at once: one sequence of ADAMAS_MAX_SEQ_LEN = 2^20 tokens (with an
+    append as its last token), the largest budget k = 4096, a group of two query heads."""
+    L = 1 << 20
+    case = synth.make_case("max", 4242, 1, 2, 1, [L], [4096],
+                           lambda b, Lc, h, rng: rng.choice(Lc, (2, 3), replace=False), append=True)
+    check_case(H, oracle, case, [4096], check_cache=True)
