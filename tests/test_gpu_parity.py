@@ -367,6 +367,23 @@ def test_decode_step_in_a_replayed_graph(H, oracle):
         torch.cuda.synchronize()
 
 
+def test_plain_c_client_of_the_abi(H, oracle):
+    """tests/c_abi_client.c: hipMalloc'ed buffers and adamas.h only, no Python in the process.
+    It runs the fused step (ragged batch, GQA, append) and checks it against the oracle itself."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    exe = os.path.join(root, "tests", "c_abi_client")
+    if not os.path.exists(exe):
+        sys.path.insert(0, root)
+        import __graft_entry__
+        __graft_entry__.build_c_client()
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=100)
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert "C ABI client: OK" in r.stdout
+
+
 def test_appended_token_is_a_candidate(H, oracle):
     case = small_case(602, 1, 2, 2, [4097], append=True)     # new token alone in the 2nd segment
     case.q[0, 0] = case.k_new[0, 0]
