@@ -104,6 +104,28 @@ def _thr(thr, bits: int = 2) -> np.ndarray:
     return t
 
 
+class head_dim:
+    """`with oracle.head_dim(64): ...` runs the calls inside with d = 64 (or 256); 128 is the
+    default and is restored on exit.  Process-wide state of the oracle library."""
+
+    def __init__(self, d: int):
+        self.d = int(d)
+
+    def __enter__(self):
+        global D, ROW_BYTES
+        self.prev = D
+        if lib().oracle_set_head_dim(ctypes.c_int(self.d)) != 0:
+            raise OracleError("head dimension must be 64, 128 or 256")
+        D, ROW_BYTES = self.d, self.d // 4
+        return self
+
+    def __exit__(self, *exc):
+        global D, ROW_BYTES
+        lib().oracle_set_head_dim(ctypes.c_int(self.prev))
+        D, ROW_BYTES = self.prev, self.prev // 4
+        return False
+
+
 def max_threads() -> int:
     return int(lib().oracle_max_threads())
 
@@ -311,14 +333,14 @@ def bucketize_n(y: np.ndarray, thr, d: int = D) -> np.ndarray:
 def pack_row_bits(code: np.ndarray, bits: int) -> np.ndarray:
     code = np.ascontiguousarray(code, dtype=np.uint8)
     assert code.shape == (D,)
-    row = np.empty(16 * bits, dtype=np.uint8)
+    row = np.empty((D // 8) * bits, dtype=np.uint8)
     _check(lib().oracle_pack_row_bits(_p(code), ctypes.c_int(bits), _p(row)), "pack_row_bits")
     return row
 
 
 def unpack_row_bits(row: np.ndarray, bits: int) -> np.ndarray:
     row = np.ascontiguousarray(row, dtype=np.uint8)
-    assert row.shape == (16 * bits,)
+    assert row.shape == ((D // 8) * bits,)
     code = np.empty(D, dtype=np.uint8)
     _check(lib().oracle_unpack_row_bits(_p(row), ctypes.c_int(bits), _p(code)), "unpack_row_bits")
     return code
@@ -326,7 +348,7 @@ def unpack_row_bits(row: np.ndarray, bits: int) -> np.ndarray:
 
 def unpack_rows_bits(rows: np.ndarray, bits: int) -> np.ndarray:
     rows = np.ascontiguousarray(rows, dtype=np.uint8)
-    flat = rows.reshape(-1, 16 * bits)
+    flat = rows.reshape(-1, (D // 8) * bits)
     out = np.empty((flat.shape[0], D), dtype=np.uint8)
     for i in range(flat.shape[0]):
         out[i] = unpack_row_bits(flat[i], bits)
@@ -340,7 +362,7 @@ def encode_bits(x_bf16: np.ndarray, thr, bits: int, hadamard: bool = True):
     assert x.shape[-1] == D
     n = x.size // D
     codes = np.empty(x.shape, dtype=np.uint8)
-    rows = np.empty(x.shape[:-1] + (16 * bits,), dtype=np.uint8)
+    rows = np.empty(x.shape[:-1] + ((D // 8) * bits,), dtype=np.uint8)
     _check(lib().oracle_encode_bits(_p(x), ctypes.c_int64(n), _p(_thr(thr, bits)), bits,
                                     1 if hadamard else 0, _p(codes), _p(rows)), "encode_bits")
     return codes, rows
@@ -354,7 +376,7 @@ def decode_step_bits(q, K, V, code_rows, seq_start, seq_len, k, thr_q, thr_k, bi
     Hkv, pool, _ = K.shape
     for a, dt in ((K, np.uint16), (V, np.uint16), (code_rows, np.uint8)):
         assert a.dtype == dt and a.flags.c_contiguous
-    assert V.shape == K.shape and code_rows.shape == (Hkv, pool, 16 * bits)
+    assert V.shape == K.shape and code_rows.shape == (Hkv, pool, (D // 8) * bits)
     seq_start = np.ascontiguousarray(seq_start, dtype=np.int64)
     seq_len = np.ascontiguousarray(seq_len, dtype=np.int32)
     assert np.all(seq_start >= 0) and np.all(seq_start + seq_len <= pool)

@@ -44,8 +44,26 @@
 #include <stdlib.h>
 #include <string.h>
 
-#define ORACLE_D 128
-#define ORACLE_ROW_BYTES 32
+/*
+ * Head dimension.  The paper's models have d = 128 and that is the default;
+ * Section 2 builds the transform for any power of two (H_{2n} from H_n), and
+ * oracle_set_head_dim() switches every function below to d = 64 or 256 (test
+ * code sets it before a group of calls and restores 128 afterwards; it is
+ * process-wide state, only read inside the calls).  A 2-bit code row then has
+ * d / 4 bytes: d / 32 words of two 32-bit planes.
+ */
+#define ORACLE_MAX_D 256
+static int oracle_head_dim = 128;
+#define ORACLE_D (oracle_head_dim)
+#define ORACLE_ROW_BYTES (oracle_head_dim / 4)
+
+int oracle_set_head_dim(int d) {
+  if (d != 64 && d != 128 && d != 256) return -1;
+  oracle_head_dim = d;
+  return 0;
+}
+
+int oracle_get_head_dim(void) { return oracle_head_dim; }
 
 enum {
   ORACLE_OK = 0,
@@ -160,7 +178,7 @@ int oracle_bucketize(int64_t n, const double *y, int d, const float thr[3], uint
  * Word g holds dimensions 32g .. 32g+31: bit j is the low bit of the code of
  * dimension 32g+j, bit 32+j its high bit.
  */
-int oracle_pack_row(const uint8_t code[ORACLE_D], uint8_t row[ORACLE_ROW_BYTES]) {
+int oracle_pack_row(const uint8_t *code, uint8_t *row) {
   if (!code || !row) return ORACLE_BAD_ARG;
   memset(row, 0, ORACLE_ROW_BYTES);
   for (int dim = 0; dim < ORACLE_D; ++dim) {
@@ -174,7 +192,7 @@ int oracle_pack_row(const uint8_t code[ORACLE_D], uint8_t row[ORACLE_ROW_BYTES])
   return ORACLE_OK;
 }
 
-int oracle_unpack_row(const uint8_t row[ORACLE_ROW_BYTES], uint8_t code[ORACLE_D]) {
+int oracle_unpack_row(const uint8_t *row, uint8_t *code) {
   if (!code || !row) return ORACLE_BAD_ARG;
   for (int dim = 0; dim < ORACLE_D; ++dim) {
     int g = dim / 32, j = dim % 32;
@@ -192,9 +210,9 @@ int oracle_unpack_row(const uint8_t row[ORACLE_ROW_BYTES], uint8_t code[ORACLE_D
  * 32-bit planes; plane p of word g holds, at bit j, bit p of the code of
  * dimension 32g + j.  bits = 2 gives exactly the 32-byte row above.
  */
-int oracle_pack_row_bits(const uint8_t code[ORACLE_D], int bits, uint8_t *row) {
+int oracle_pack_row_bits(const uint8_t code[ORACLE_MAX_D], int bits, uint8_t *row) {
   if (!code || !row || bits < 1 || bits > 3) return ORACLE_BAD_ARG;
-  memset(row, 0, (size_t)16 * bits);
+  memset(row, 0, (size_t)(ORACLE_D / 8) * bits);
   for (int dim = 0; dim < ORACLE_D; ++dim) {
     if (code[dim] >> bits) return ORACLE_BAD_ARG;
     int g = dim / 32, j = dim % 32;
@@ -204,7 +222,7 @@ int oracle_pack_row_bits(const uint8_t code[ORACLE_D], int bits, uint8_t *row) {
   return ORACLE_OK;
 }
 
-int oracle_unpack_row_bits(const uint8_t *row, int bits, uint8_t code[ORACLE_D]) {
+int oracle_unpack_row_bits(const uint8_t *row, int bits, uint8_t code[ORACLE_MAX_D]) {
   if (!code || !row || bits < 1 || bits > 3) return ORACLE_BAD_ARG;
   for (int dim = 0; dim < ORACLE_D; ++dim) {
     int g = dim / 32, j = dim % 32, c = 0;
@@ -263,8 +281,8 @@ int oracle_encode_bits(const uint16_t *x, int64_t n, const float *thr, int bits,
   int status = ORACLE_OK;
 #pragma omp parallel for schedule(static)
   for (int64_t v = 0; v < n; ++v) {
-    double xv[ORACLE_D], y[ORACLE_D];
-    uint8_t code[ORACLE_D];
+    double xv[ORACLE_MAX_D], y[ORACLE_MAX_D];
+    uint8_t code[ORACLE_MAX_D];
     int emax = -100000, emin = 100000, bad = 0;
     for (int i = 0; i < ORACLE_D; ++i) {
       xv[i] = bf16_to_double(x[v * ORACLE_D + i]);
@@ -297,7 +315,7 @@ int oracle_encode_bits(const uint16_t *x, int64_t n, const float *thr, int bits,
       code[j] = (uint8_t)c;
     }
     if (codes) memcpy(codes + v * ORACLE_D, code, ORACLE_D);
-    if (rows) oracle_pack_row_bits(code, bits, rows + v * (int64_t)16 * bits);
+    if (rows) oracle_pack_row_bits(code, bits, rows + v * (int64_t)(ORACLE_D / 8) * bits);
   }
   free(H);
   return status;
@@ -408,7 +426,7 @@ int oracle_sparse_attention(const uint16_t *q, const uint16_t *K,
     if (s[i] > m) m = s[i];
     any = 1;
   }
-  double acc[ORACLE_D];
+  double acc[ORACLE_MAX_D];
   for (int j = 0; j < ORACLE_D; ++j) acc[j] = 0.0;
   double denom = 0.0;
   for (int32_t i = 0; i < k && any; ++i) {
@@ -539,7 +557,7 @@ int oracle_decode_step_bits(int32_t Hq, int32_t Hkv, int64_t pool_tokens,
                             int32_t *idx, int32_t *dist, int64_t max_seq_len,
                             int use_hadamard, int squared_distance) {
   if (bits < 1 || bits > 3) return ORACLE_BAD_ARG;
-  const int64_t row_bytes = (int64_t)16 * bits;
+  const int64_t row_bytes = (int64_t)(ORACLE_D / 8) * bits;
   if (Hq < 1 || Hkv < 1 || Hq % Hkv != 0 || B < 1 || k < 1) return ORACLE_BAD_ARG;
   if (!q || !K || !V || !code_rows || !seq_start || !seq_len || !out || !idx)
     return ORACLE_BAD_ARG;
@@ -575,7 +593,7 @@ int oracle_decode_step_bits(int32_t Hq, int32_t Hkv, int64_t pool_tokens,
       const uint16_t *qv = q + ((int64_t)b * Hq + h) * ORACLE_D;
       float *o = out + ((int64_t)b * Hq + h) * ORACLE_D;
       int32_t *sel = idx + ((int64_t)b * Hq + h) * k;
-      uint8_t qcode[ORACLE_D];
+      uint8_t qcode[ORACLE_MAX_D];
       int rc = oracle_encode_bits(qv, 1, thr_q, bits, use_hadamard, qcode, NULL);
       uint8_t *kc = (uint8_t *)malloc((size_t)(L > 0 ? L : 1) * ORACLE_D);
       int32_t *D = (int32_t *)malloc((size_t)(L > 0 ? L : 1) * sizeof(int32_t));

@@ -75,19 +75,21 @@ class DecodeCase:
 
 def _rows(rng: np.random.Generator, n: int, scale: np.ndarray) -> np.ndarray:
     """n rows of N(0,1) float32 with the per-channel outlier scale applied."""
-    return rng.standard_normal((n, D), dtype=np.float32) * scale
+    return rng.standard_normal((n, scale.shape[0]), dtype=np.float32) * scale
 
 
 def make_case(name: str, seed: int, B: int, Hq: int, Hkv: int, seq_len: Sequence[int],
               budgets: Sequence[int], needle_positions, append: bool = False,
-              gap: int = SEQ_GAP_ROWS) -> DecodeCase:
+              gap: int = SEQ_GAP_ROWS, head_dim: int = D) -> DecodeCase:
     """Builds a ragged KV cache with planted needles.
 
     needle_positions(b, L, kv_head, rng) -> int array [G, n_needles] of distinct token
     positions in [0, L_cached) for the G query heads of that KV head's group.
     With append=True the cache holds seq_len[b]-1 rows and k_new/v_new carry one more.
+    head_dim: 128 (the paper's models) unless a test of other head dimensions says otherwise.
     """
     assert Hq % Hkv == 0
+    D = head_dim      # shadows the module constant inside this function
     G = Hq // Hkv
     rng = np.random.default_rng(seed)
     seq_len = np.asarray(seq_len, dtype=np.int32)

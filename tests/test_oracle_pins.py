@@ -469,6 +469,65 @@ def test_bits_decode_step_composes_its_stages(oracle, bits, thr):
             assert np.array_equal(out[b, h], ref)
 
 
+# --------------------------------------------------------- other head dimensions
+
+@pytest.mark.parametrize("d", [64, 256])
+def test_head_dim_encode_rows_and_distance(oracle, d):
+    rng = np.random.default_rng(40 + d)
+    x = bf16(rng.standard_normal((50, d)) * 1.5)
+    with oracle.head_dim(d):
+        codes, rows = oracle.encode(x, THR)
+        assert rows.shape == (50, d // 4)
+        assert np.array_equal(oracle.unpack_rows(rows), codes)
+        Dm = oracle.manhattan(codes[0], codes[1:])
+        full = oracle.manhattan(np.zeros(d, np.uint8), np.full((1, d), 3, np.uint8))[0]
+        # layout: word g = two 32-bit planes for dims 32g..32g+31
+        one = np.zeros(d, dtype=np.uint8)
+        one[d - 1] = 2
+        words = oracle.pack_row(one).view("<u4").reshape(d // 32, 2)
+    assert full == 3 * d
+    yy = widen(x) @ scipy.linalg.hadamard(d).astype(np.float64) / np.sqrt(float(d))
+    ref = (yy[..., None] > np.array(THR)).sum(-1)
+    far = np.abs(yy[..., None] - np.array(THR)).min(-1) > 1e-6
+    assert np.array_equal(codes[far], ref[far]) and far.mean() > 0.999
+    assert np.array_equal(Dm, np.abs(codes[0].astype(int)[None] - codes[1:].astype(int)).sum(-1))
+    assert int(words[d // 32 - 1, 1]) == 1 << 31 and int(words.sum()) == 1 << 31
+    # and the default is back
+    assert oracle.encode(bf16(rng.standard_normal((1, 128))), THR)[1].shape == (1, 32)
+
+
+@pytest.mark.parametrize("d", [64, 256])
+def test_head_dim_decode_step_composes_its_stages(oracle, d):
+    case = synth.make_case("t", 80 + d, 2, 4, 2, [300, 129], [16],
+                           lambda b, L, h, rng: rng.choice(L, (2, 1), replace=False), append=True,
+                           head_dim=d)
+    scale = 1 / np.sqrt(float(d))
+    with oracle.head_dim(d):
+        K, V = case.K.copy(), case.V.copy()
+        _, rows = oracle.encode(K, case.thresholds)
+        out, idx, dist = oracle.decode_step(case.q, K, V, rows, case.seq_start, case.seq_len, 16,
+                                            case.thresholds, case.thresholds, scale,
+                                            k_new=case.k_new, v_new=case.v_new, want_dist=True)
+        for b in range(2):
+            L, s = int(case.seq_len[b]), int(case.seq_start[b])
+            assert np.array_equal(K[:, s + L - 1], case.k_new[b])
+            for h in range(4):
+                kvh = h // 2
+                qc, _ = oracle.encode(case.q[b, h], case.thresholds)
+                kc, _ = oracle.encode(K[kvh, s:s + L], case.thresholds)
+                Dref = np.abs(qc.astype(int)[None] - kc.astype(int)).sum(-1)
+                assert np.array_equal(dist[b, h, :L], Dref)
+                sel = oracle.topk(Dref.astype(np.int32), 16)
+                assert np.array_equal(idx[b, h], sel)
+                assert case.needles[b][h][0] in sel.tolist()
+                # Eq. 1 by numpy on the selected rows
+                qf, Kf, Vf = widen(case.q[b, h]), widen(K[kvh, s:s + L][sel]), widen(V[kvh, s:s + L][sel])
+                sc = Kf @ qf * scale
+                w = np.exp(sc - sc.max())
+                ref = (w / w.sum()) @ Vf
+                assert np.allclose(out[b, h], ref, rtol=1e-5, atol=1e-6)
+
+
 # ------------------------------------------------------------------ paged cache layout
 
 def _paged_step(oracle, pc, k):
