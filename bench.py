@@ -3,7 +3,7 @@
 
 A "step" is one call of adamas_decode_step for one attention layer: query encode, (optional)
 append, Manhattan-distance scan over the whole code plane, top-k, gather and sparse attention
-(Algorithm 1, lines 1-8).  Steps rotate over `--layers` distinct layer caches so that the
+(all of Algorithm 1).  Steps rotate over `--layers` distinct layer caches so that the
 256 MB last-level cache cannot stand in for HBM, and are replayed from a HIP graph that holds
 one sweep over all layers (launch latency of the Python caller is not what is measured).
 
@@ -51,6 +51,9 @@ def parse_args():
                     help="ablation switches of Section 4.4 (default: the method itself)")
     ap.add_argument("--code-bits", type=int, default=2, choices=[1, 2, 3],
                     help="bucketization granularity (Section 4.4 ablation; 2 is the method)")
+    ap.add_argument("--head-dim", type=int, default=128, choices=[64, 128, 256],
+                    help="head dimension (128: the paper's models; 64 / 256 run the same workload "
+                         "shape with rows of that size, contiguous layout, the method only)")
     ap.add_argument("--paged", type=int, default=0, metavar="PAGE_TOKENS",
                     help="lay the cache out on randomly placed pages of this many tokens and time "
                          "adamas_decode_step_paged (0: contiguous sequences)")
@@ -74,13 +77,14 @@ def cpu_model():
     return "unknown"
 
 
-def algorithmic_bytes(B, Hq, Hkv, lens, k, append, row_bytes=32):
+def algorithmic_bytes(B, Hq, Hkv, lens, k, append, row_bytes=32, head_dim=128):
     """Bytes the method itself must move per step: every code row once per KV head, every
     selected K and V row once per query head, q in, out back, plus the appended rows."""
+    kv_row = 4 * head_dim            # one K row and one V row, bf16
     codes = Hkv * sum(lens) * row_bytes
-    gather = Hq * sum(min(k, L) for L in lens) * 512
-    small = B * Hq * (256 + 512)
-    app = B * Hkv * (2 * 512 + row_bytes) if append else 0
+    gather = Hq * sum(min(k, L) for L in lens) * kv_row
+    small = B * Hq * (2 * head_dim + 4 * head_dim)      # q in (bf16), out back (fp32)
+    app = B * Hkv * (2 * kv_row + row_bytes) if append else 0
     return codes + gather + small + app, codes
 
 
@@ -146,9 +150,14 @@ def main():
     thr = {1: (0.0,), 2: synth.DEFAULT_THRESHOLDS, 3: (-1.5, -1.0, -0.5, 0.0, 0.5, 1.0, 1.5)}[bits]
     if bits != 2 and (page or squared):
         raise SystemExit("--code-bits 1/3 is benchmarked on the contiguous layout with Eq. 6 only")
+    HD = args.head_dim
+    if HD != 128 and (page or squared or bits != 2 or (HD == 256 and G > 4)):
+        raise SystemExit("--head-dim 64/256: the method itself on the contiguous layout only "
+                         "(and a query group of at most 4 at 256)")
     cfg = A.Config.make(Hq, Hkv, pool, thr_k=thr,
                         variant=(A.VARIANT_NO_HADAMARD if no_hadamard else 0)
-                        | (A.VARIANT_L2 if squared else 0), code_bits=0 if bits == 2 else bits)
+                        | (A.VARIANT_L2 if squared else 0), code_bits=0 if bits == 2 else bits,
+                        head_dim=HD)
     row_bytes = cfg.code_row_bytes
     seq_start = torch.from_numpy(starts).to(dev)
     seq_len = torch.from_numpy(lens).to(dev)
@@ -162,20 +171,20 @@ def main():
         g.manual_seed(synth.config_seed(cfg_id, layer))
 
         def rows(n, scale):
-            x = torch.randn(n, 128, generator=g, device=dev) * scale
+            x = torch.randn(n, HD, generator=g, device=dev) * scale
             return torch.where(x.abs() < synth.FLUSH_BELOW, torch.zeros_like(x), x)
 
         pool = contiguous_pool if page else globals_pool
-        K = torch.empty(Hkv, pool, 128, dtype=torch.bfloat16, device=dev)
-        V = torch.empty(Hkv, pool, 128, dtype=torch.bfloat16, device=dev)
-        q = torch.empty(B, Hq, 128, dtype=torch.bfloat16, device=dev)
-        k_new = torch.empty(B, Hkv, 128, dtype=torch.bfloat16, device=dev) if append else None
-        v_new = torch.empty(B, Hkv, 128, dtype=torch.bfloat16, device=dev) if append else None
+        K = torch.empty(Hkv, pool, HD, dtype=torch.bfloat16, device=dev)
+        V = torch.empty(Hkv, pool, HD, dtype=torch.bfloat16, device=dev)
+        q = torch.empty(B, Hq, HD, dtype=torch.bfloat16, device=dev)
+        k_new = torch.empty(B, Hkv, HD, dtype=torch.bfloat16, device=dev) if append else None
+        v_new = torch.empty(B, Hkv, HD, dtype=torch.bfloat16, device=dev) if append else None
         for h in range(Hkv):
-            sk = torch.ones(128, device=dev)
-            sk[torch.randperm(128, generator=g, device=dev)[:4]] = synth.OUTLIER_SCALE
-            sv = torch.ones(128, device=dev)
-            sv[torch.randperm(128, generator=g, device=dev)[:4]] = synth.OUTLIER_SCALE
+            sk = torch.ones(HD, device=dev)
+            sk[torch.randperm(HD, generator=g, device=dev)[:4]] = synth.OUTLIER_SCALE
+            sv = torch.ones(HD, device=dev)
+            sv[torch.randperm(HD, generator=g, device=dev)[:4]] = synth.OUTLIER_SCALE
             K[h] = rows(pool, sk).to(torch.bfloat16)
             V[h] = rows(pool, sv).to(torch.bfloat16)
             for b in range(B):
@@ -187,9 +196,9 @@ def main():
                 for gq in range(G):
                     u = rows(1, sk)[0]
                     q[b, h * G + gq] = (u + synth.NEEDLE_SIGMA * torch.randn(
-                        128, generator=g, device=dev)).to(torch.bfloat16)
+                        HD, generator=g, device=dev)).to(torch.bfloat16)
                     K[h, int(starts[b]) + where[gq]] = (u + synth.NEEDLE_SIGMA * torch.randn(
-                        128, generator=g, device=dev)).to(torch.bfloat16)
+                        HD, generator=g, device=dev)).to(torch.bfloat16)
         return dict(q=q, K=K, V=V, k_new=k_new, v_new=v_new)
 
     def upload_case(case):
@@ -202,7 +211,7 @@ def main():
     layers = []
     case0 = None
     for layer in range(n_layers):
-        if layer == 0 and args.config == "cfg1":
+        if layer == 0 and args.config == "cfg1" and HD == 128:
             case0 = synth.mha_32k(layer=0)      # the numpy recipe: checked against the oracle below
             data = upload_case(case0)
         else:
@@ -211,7 +220,7 @@ def main():
             data["K"] = data["K"].index_select(1, src_row_dev).contiguous()
             data["V"] = data["V"].index_select(1, src_row_dev).contiguous()
         data["codes"] = torch.empty(Hkv, pool, row_bytes, dtype=torch.uint8, device=dev)
-        data["out"] = torch.zeros(B, Hq, 128, device=dev)
+        data["out"] = torch.zeros(B, Hq, HD, device=dev)
         A.adamas_encode_keys(cfg, data["K"], data["codes"], 0, pool)
         layers.append(data)
     # bulk key encode (prefill-side, not part of the timed step): average of 5 runs on layer 0
@@ -223,7 +232,7 @@ def main():
     e1.record()
     torch.cuda.synchronize()
     encode_us = e0.elapsed_time(e1) * 1e3 / 5
-    encode_bytes = Hkv * pool * (256 + row_bytes)
+    encode_bytes = Hkv * pool * (2 * HD + row_bytes)
     idx0 = torch.empty(B, Hq, k, dtype=torch.int32, device=dev)
     ws = torch.empty(A.adamas_workspace_bytes(cfg, B, max_len, k), dtype=torch.uint8, device=dev)
     torch.cuda.synchronize()
@@ -341,7 +350,7 @@ def main():
     if not page:
         full_ws = torch.empty(A.adamas_full_attn_workspace_bytes(cfg, B, max_len), dtype=torch.uint8,
                               device=dev)
-        full_out = torch.zeros(B, Hq, 128, device=dev)
+        full_out = torch.zeros(B, Hq, HD, device=dev)
 
         def full_graph():
             for d in layers:
@@ -364,7 +373,7 @@ def main():
         s1.record()
         torch.cuda.synchronize()
         full_us = s0.elapsed_time(s1) * 1e3 / (n_rep * n_layers)
-        full_bytes = Hkv * int(lens.sum()) * 512
+        full_bytes = Hkv * int(lens.sum()) * 4 * HD
 
     def graph_us(fn, reps=8):
         """us per call of fn(layer_dict) over the rotating layers, graph replay, HIP events."""
@@ -390,7 +399,7 @@ def main():
     if not page:
         qcodes = torch.empty(B, Hq, row_bytes, dtype=torch.uint8, device=dev)
         idx_s = torch.empty(B, Hq, k, dtype=torch.int32, device=dev)
-        out_s = torch.empty(B, Hq, 128, device=dev)
+        out_s = torch.empty(B, Hq, HD, device=dev)
         stage_us = {
             "encode_query": graph_us(lambda d: A.adamas_encode_query(cfg, d["q"], qcodes)),
             "select_topk": graph_us(lambda d: A.adamas_select_topk(
@@ -406,13 +415,14 @@ def main():
     resident_us = graph_us(lambda d: step(0))      # n_layers launches per replay, all on layer 0
 
     total_bytes, code_bytes = algorithmic_bytes(B, Hq, Hkv, [int(x) for x in lens], k, append,
-                                               row_bytes)
+                                               row_bytes, HD)
     gbps_step = total_bytes / (us_step * 1e-6) / 1e9
     gbps_scan = code_bytes / (ms_scan * 1e-3) / 1e9
 
     traffic = None
     prof = os.path.join(ROOT, "profiles", "scan_kernel_%s_pmc.md" % args.config)
-    if os.path.exists(prof):
+    default_path = HD == 128 and bits == 2 and not page and args.variant == "adamas" and not args.k
+    if default_path and os.path.exists(prof):    # the counters were read on the default path
         for line in open(prof):
             if line.startswith("traffic_bytes_per_launch:"):
                 traffic = float(line.split(":")[1])
@@ -431,10 +441,10 @@ def main():
         "dtype": "u32 popcount (select) + f32 (attention) on bf16 K/V",
         "data": "synthetic",
         "config": {
-            "workload": wl["text"] + ", budget k=%d, %d rotating layer caches" % (k, n_layers),
+            "workload": wl["text"].replace("head_dim 128", "head_dim %d" % HD) + ", budget k=%d, %d rotating layer caches" % (k, n_layers),
             "batch": B, "q_heads": Hq, "kv_heads": Hkv, "context": int(max_len),
             "sum_context": int(lens.sum()), "k": k, "append": append, "variant": args.variant,
-            "code_bits": bits,
+            "code_bits": bits, "head_dim": HD,
             "layout": "paged, %d-token pages, random placement" % page if page else "contiguous",
             "launch": "eager" if args.eager else "hipGraph of one %d-layer sweep" % n_layers,
         },
@@ -477,6 +487,8 @@ def main():
     # ------------------------------------------------------------------ oracle on the host
     if not args.no_cpu_baseline:
         import oracle
+        hd_scope = oracle.head_dim(HD)      # the oracle computes at this head dimension below
+        hd_scope.__enter__()
         if case0 is None or page:
             # pull layer 0 back to the host for the oracle
             def h(t):
@@ -506,16 +518,16 @@ def main():
             if page:
                 ref_out, ref_idx = oracle.decode_step_paged(
                     qs, Ks, Vs, rows, table_np, page, lens, k, synth.DEFAULT_THRESHOLDS,
-                    synth.DEFAULT_THRESHOLDS, 1.0 / np.sqrt(128.0), k_new=kns, v_new=vns,
+                    synth.DEFAULT_THRESHOLDS, 1.0 / np.sqrt(float(HD)), k_new=kns, v_new=vns,
                     hadamard=not no_hadamard, squared=squared)
             elif bits != 2:
                 ref_out, ref_idx, _ = oracle.decode_step_bits(
-                    qs, Ks, Vs, rows, starts, lens, k, thr, thr, bits, 1.0 / np.sqrt(128.0),
+                    qs, Ks, Vs, rows, starts, lens, k, thr, thr, bits, 1.0 / np.sqrt(float(HD)),
                     k_new=kns, v_new=vns, hadamard=not no_hadamard)
             else:
                 ref_out, ref_idx, _ = oracle.decode_step(
                     qs, Ks, Vs, rows, starts, lens, k, synth.DEFAULT_THRESHOLDS,
-                    synth.DEFAULT_THRESHOLDS, 1.0 / np.sqrt(128.0), k_new=kns, v_new=vns,
+                    synth.DEFAULT_THRESHOLDS, 1.0 / np.sqrt(float(HD)), k_new=kns, v_new=vns,
                     hadamard=not no_hadamard, squared=squared)
             times.append(time.perf_counter() - t0)
         cpu_s = sorted(times)[len(times) // 2]
@@ -523,7 +535,7 @@ def main():
         t0 = time.perf_counter()
         if bits == 2 and not page:
             oracle.decode_step(qs, Ks, Vs, rows, starts, lens, k, synth.DEFAULT_THRESHOLDS,
-                               synth.DEFAULT_THRESHOLDS, 1.0 / np.sqrt(128.0), k_new=kns, v_new=vns,
+                               synth.DEFAULT_THRESHOLDS, 1.0 / np.sqrt(float(HD)), k_new=kns, v_new=vns,
                                hadamard=not no_hadamard, squared=squared)
             cpu_1t = time.perf_counter() - t0
         else:
@@ -550,6 +562,7 @@ def main():
         rel = float(np.max(np.abs(got_out - ref_out) / np.maximum(np.abs(ref_out), floor)))
         result["parity_vs_oracle"] = {"indices_bit_exact": bool(np.array_equal(got_idx, ref_idx)),
                                       "attn_max_rel_err": rel, "heads_checked": len(sel_q)}
+        hd_scope.__exit__(None, None, None)
     result["setup_seconds"] = round(t_gen, 1)
     print(json.dumps(result), flush=True)
 

@@ -2,14 +2,14 @@
  * adamas.h -- C ABI of the MI355X (gfx950) implementation of the Adamas
  * decode-time sparse-attention path (Algorithm 1 of the paper):
  *
- *   Hadamard transform of each query / key head vector      (Alg. 1 l.1, Eq. 4)
- *   bucketize into 2-bit codes and pack, 32 B per vector    (Alg. 1 l.2-3, Eq. 5)
- *   append K, V and the code row to the cache               (Alg. 1 l.4)
+ *   Hadamard transform of each query / key head vector      (Alg. 1, Eq. 4)
+ *   bucketize into 2-bit codes and pack, 32 B per vector    (Alg. 1, Eq. 5)
+ *   append K, V and the code row to the cache               (Alg. 1)
  *   Manhattan distance of the query codes to every cached
- *   key's codes                                             (Alg. 1 l.5, Eq. 6)
- *   top-k: the k cached tokens of smallest distance         (Alg. 1 l.6)
+ *   key's codes                                             (Alg. 1, Eq. 6)
+ *   top-k: the k cached tokens of smallest distance         (Alg. 1)
  *   softmax attention of the original q over the selected
- *   rows of the original K, V                               (Alg. 1 l.7-8, Eq. 1)
+ *   rows of the original K, V                               (Alg. 1, Eq. 1)
  *
  * GENERAL CONVENTIONS
  *
@@ -57,7 +57,8 @@
  *     ADAMAS_ERR_BAD_ARG      null pointer, non-positive size, heads not
  *                             divisible, thresholds not strictly increasing,
  *                             non-finite scale, misaligned pool, ...
- *     ADAMAS_ERR_UNSUPPORTED  head_dim != 128, k > ADAMAS_MAX_K,
+ *     ADAMAS_ERR_UNSUPPORTED  head_dim not 64 / 128 / 256 (or an option
+ *                             not built for it, see below), k > ADAMAS_MAX_K,
  *                             group size > ADAMAS_MAX_GROUP,
  *                             max_seq_len > ADAMAS_MAX_SEQ_LEN
  *     ADAMAS_ERR_WORKSPACE    workspace_bytes < adamas_workspace_bytes(...)
@@ -117,8 +118,19 @@ extern "C" {
 #define ADAMAS_VARIANT_NO_HADAMARD 1u
 #define ADAMAS_VARIANT_L2 2u
 
+/*
+ * Head dimension d.  The text above and below is written for d = 128, the
+ * head dimension of the paper's models.  head_dim 64 and 256 run the method
+ * itself (Hadamard transform of order d, 2-bit codes, Eq. 6, contiguous
+ * cache) through every entry point except adamas_decode_step_paged: read
+ * d for 128 and d/4 for the 32-byte code row (d/32 words of 64 bits, same bit
+ * placement), distances 0..3d, sm_scale 0 meaning 1/sqrt(d), thresholds
+ * compared with x H / sqrt(d).  With them, ADAMAS_VARIANT_L2, code_bits 1
+ * or 3, the paged entry point, and at d = 256 a group above 4 return
+ * ADAMAS_ERR_UNSUPPORTED.
+ */
 typedef struct adamas_config {
-  int32_t head_dim;      /* must be 128 */
+  int32_t head_dim;      /* 128; or 64, 256 (see above) */
   int32_t num_q_heads;   /* Hq */
   int32_t num_kv_heads;  /* Hkv; Hq % Hkv == 0 */
   uint32_t variant;      /* 0 = the method; else ADAMAS_VARIANT_* flags (Sec. 4.4 ablations) */
@@ -126,7 +138,7 @@ typedef struct adamas_config {
   float thr_k[7];        /* key thresholds B1 < B2 < ... of Eq. 5, orthonormal scale; the first
                             2^code_bits - 1 are used (three for the method) */
   float thr_q[7];        /* query thresholds (the paper uses one set: pass the same) */
-  float sm_scale;        /* softmax scale of Eq. 1; 0 means 1/sqrt(128) */
+  float sm_scale;        /* softmax scale of Eq. 1; 0 means 1/sqrt(head_dim) */
   int32_t code_bits;     /* 0 or 2: 2-bit codes (the method); 1, 3: bucketization ablation */
 } adamas_config;
 
@@ -143,8 +155,9 @@ size_t adamas_workspace_bytes(const adamas_config *cfg, int32_t batch,
                               int64_t max_seq_len, int32_t k);
 
 /*
- * Alg. 1 l.1-3 for cached keys (prefill-time bulk encode): for every KV
- * head, transform, bucketize (thr_k) and pack pool rows
+ * Alg. 1, transform / bucketize / pack steps (Eq. 4, Eq. 5), for cached
+ * keys (prefill-time bulk encode): for every KV head, transform, bucketize
+ * (thr_k) and pack pool rows
  * [row_begin, row_begin + n_rows) of K into the same rows of codes.
  * K: bf16 [Hkv][pool_tokens][128] (read), codes: uint8 [Hkv][pool_tokens][32]
  * (written).  n_rows == 0 is a no-op.
@@ -153,14 +166,15 @@ int adamas_encode_keys(const adamas_config *cfg, const void *K, void *codes,
                        int64_t row_begin, int64_t n_rows, void *stream);
 
 /*
- * Alg. 1 l.1-3 for queries: q bf16 [batch][Hq][128] -> qcodes uint8
- * [batch][Hq][32], thresholds thr_q.
+ * The same steps of Alg. 1 for queries: q bf16 [batch][Hq][128] -> qcodes
+ * uint8 [batch][Hq][32], thresholds thr_q.
  */
 int adamas_encode_query(const adamas_config *cfg, const void *q, void *qcodes,
                         int32_t batch, void *stream);
 
 /*
- * Alg. 1 l.5 (Eq. 6): dist_out[b][h][t] = sum_j |qcode[b][h]_j - code[kv(h)][seq_start[b]+t]_j|
+ * Alg. 1, distance step (Eq. 6):
+ *   dist_out[b][h][t] = sum_j |qcode[b][h]_j - code[kv(h)][seq_start[b]+t]_j|
  * for t < seq_len[b]; entries t >= seq_len[b] are left untouched.
  * qcodes uint8 [batch][Hq][32]; seq_start int64 [batch]; seq_len int32 [batch];
  * dist_out uint16 [batch][Hq][max_seq_len], values 0..384 (other ranges with
@@ -173,7 +187,7 @@ int adamas_manhattan_distance(const adamas_config *cfg, const void *qcodes,
                               void *stream);
 
 /*
- * Alg. 1 l.5-6: distances as above, then the top-k selection described
+ * Alg. 1, distance and top-k steps: distances as above, then the top-k selection described
  * under "Selection".  idx_out int32 [batch][Hq][k].  dist_out may be NULL;
  * otherwise it receives the distances as in adamas_manhattan_distance.
  */
@@ -185,7 +199,7 @@ int adamas_select_topk(const adamas_config *cfg, const void *qcodes,
                        size_t workspace_bytes, void *stream);
 
 /*
- * Alg. 1 l.7-8 (Eq. 1): out[b][h] = softmax(q[b][h] . K_s^T * sm_scale) V_s
+ * Alg. 1, gather and attention steps (Eq. 1): out[b][h] = softmax(q[b][h] . K_s^T * sm_scale) V_s
  * over the rows idx[b][h][0..k) of sequence b (token positions; negative
  * entries are skipped; no valid entry -> zeros).  q bf16 [batch][Hq][128];
  * idx int32 [batch][Hq][k]; out fp32 [batch][Hq][128].  Products and sums are
@@ -200,7 +214,7 @@ int adamas_sparse_attn(const adamas_config *cfg, const void *q, const void *K,
                        size_t workspace_bytes, void *stream);
 
 /*
- * One whole decode step of one attention layer (Alg. 1 l.1-8), fused:
+ * One whole decode step of one attention layer (all of Alg. 1), fused:
  * encodes q (and k_new), appends, scans, selects and attends.
  *
  * k_new, v_new: bf16 [batch][Hkv][128], or both NULL for "no append".  With
@@ -220,9 +234,10 @@ int adamas_decode_step(const adamas_config *cfg, const void *q,
 /*
  * Profiling hook: adamas_decode_step cut at its one internal kernel
  * boundary.  `stages` is a bit mask; ADAMAS_STAGE_ALL is exactly
- * adamas_decode_step.  ADAMAS_STAGE_SCAN runs Alg. 1 l.1-5 (query encode,
- * append, distance scan; leaves distances and histograms in the workspace,
- * writes neither out nor idx_out).  ADAMAS_STAGE_SELECT_ATTN runs l.6-8 on
+ * adamas_decode_step.  ADAMAS_STAGE_SCAN runs Alg. 1 up to the distance
+ * step (query encode, append, distance scan; leaves distances and
+ * histograms in the workspace, writes neither out nor idx_out).
+ * ADAMAS_STAGE_SELECT_ATTN runs the top-k, gather and attention steps on
  * what a preceding ADAMAS_STAGE_SCAN call with the same arguments left in
  * the same workspace; without such a call its outputs are unspecified
  * (all accesses stay in bounds).  Same arguments and errors as

@@ -21,9 +21,9 @@
  *     reading: the paper does not give one.
  *   - Manhattan distance on the unpacked codes (Eq. 6).
  *   - Top-k: k smallest distances by a full sort, ties to the lower index
- *     (Algorithm 1 line 6; the tie rule is this build's, the paper has none).
+ *     (Algorithm 1, top-k step; the tie rule is this build's, the paper has none).
  *   - Sparse attention: Eq. 1 on the original q, K, V restricted to the
- *     selected rows (Algorithm 1 lines 7-8), in double.
+ *     selected rows (Algorithm 1, gather and attention steps), in double.
  *
  * Pins (see tests/test_oracle_*.py): H H^T = d I, H[i][j] = (-1)^popcount(i&j),
  * transform twice = d * identity exactly, Parseval, (QH)(KH)^T = d QK^T,
@@ -565,7 +565,7 @@ int oracle_decode_step_bits(int32_t Hq, int32_t Hkv, int64_t pool_tokens,
   const int group = Hq / Hkv;
   int status = ORACLE_OK;
 
-  /* lines 1-4 for the appended key: encode it and update the cache */
+  /* Algorithm 1, encode and cache-update steps for the appended key */
   if (k_new) {
     for (int32_t b = 0; b < B; ++b) {
       if (seq_len[b] < 1) continue;

@@ -62,7 +62,7 @@ class Config(ctypes.Structure):
 
     @property
     def code_row_bytes(self) -> int:
-        return 16 * (self.code_bits or 2)
+        return self.head_dim // 8 * (self.code_bits or 2)
 
     @classmethod
     def make(cls, num_q_heads: int, num_kv_heads: int, pool_tokens: int,
@@ -178,7 +178,7 @@ def adamas_encode_keys(cfg: Config, K, codes, row_begin: int, n_rows: int, strea
     import torch
     hkv, pool = cfg.num_kv_heads, cfg.pool_tokens
     rc = library().adamas_encode_keys(
-        ctypes.byref(cfg), _ptr(K, torch.bfloat16, "K", (hkv, pool, HEAD_DIM)),
+        ctypes.byref(cfg), _ptr(K, torch.bfloat16, "K", (hkv, pool, cfg.head_dim)),
         _ptr(codes, torch.uint8, "codes", (hkv, pool, cfg.code_row_bytes)), row_begin, n_rows,
         _stream(stream))
     _check(rc, "adamas_encode_keys")
@@ -188,7 +188,7 @@ def adamas_encode_query(cfg: Config, q, qcodes, stream=None) -> None:
     import torch
     batch = q.shape[0]
     rc = library().adamas_encode_query(
-        ctypes.byref(cfg), _ptr(q, torch.bfloat16, "q", (batch, cfg.num_q_heads, HEAD_DIM)),
+        ctypes.byref(cfg), _ptr(q, torch.bfloat16, "q", (batch, cfg.num_q_heads, cfg.head_dim)),
         _ptr(qcodes, torch.uint8, "qcodes", (batch, cfg.num_q_heads, cfg.code_row_bytes)), batch,
         _stream(stream))
     _check(rc, "adamas_encode_query")
@@ -203,15 +203,15 @@ def adamas_decode_step_paged(cfg: Config, q, K, V, codes, page_table, page_token
     if page_table.dim() != 2 or page_table.shape[0] != batch:
         raise ValueError("page_table must have shape (batch, max_pages)")
     rc = library().adamas_decode_step_paged(
-        ctypes.byref(cfg), _ptr(q, torch.bfloat16, "q", (batch, cfg.num_q_heads, HEAD_DIM)),
-        _ptr(k_new, torch.bfloat16, "k_new", (batch, hkv, HEAD_DIM), optional=True),
-        _ptr(v_new, torch.bfloat16, "v_new", (batch, hkv, HEAD_DIM), optional=True),
-        _ptr(K, torch.bfloat16, "K", (hkv, pool, HEAD_DIM)),
-        _ptr(V, torch.bfloat16, "V", (hkv, pool, HEAD_DIM)),
+        ctypes.byref(cfg), _ptr(q, torch.bfloat16, "q", (batch, cfg.num_q_heads, cfg.head_dim)),
+        _ptr(k_new, torch.bfloat16, "k_new", (batch, hkv, cfg.head_dim), optional=True),
+        _ptr(v_new, torch.bfloat16, "v_new", (batch, hkv, cfg.head_dim), optional=True),
+        _ptr(K, torch.bfloat16, "K", (hkv, pool, cfg.head_dim)),
+        _ptr(V, torch.bfloat16, "V", (hkv, pool, cfg.head_dim)),
         _ptr(codes, torch.uint8, "codes", (hkv, pool, cfg.code_row_bytes)),
         _ptr(page_table, torch.int32, "page_table"), page_table.shape[1], int(page_tokens),
         _ptr(seq_len, torch.int32, "seq_len", (batch,)), batch, k,
-        _ptr(out, torch.float32, "out", (batch, cfg.num_q_heads, HEAD_DIM)),
+        _ptr(out, torch.float32, "out", (batch, cfg.num_q_heads, cfg.head_dim)),
         _ptr(idx_out, torch.int32, "idx_out", (batch, cfg.num_q_heads, k), optional=True),
         max_seq_len, _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream),
         int(stages))
@@ -228,12 +228,12 @@ def adamas_full_attn(cfg: Config, q, K, V, seq_start, seq_len, out, max_seq_len:
     batch = q.shape[0]
     hkv, pool = cfg.num_kv_heads, cfg.pool_tokens
     rc = library().adamas_full_attn(
-        ctypes.byref(cfg), _ptr(q, torch.bfloat16, "q", (batch, cfg.num_q_heads, HEAD_DIM)),
-        _ptr(K, torch.bfloat16, "K", (hkv, pool, HEAD_DIM)),
-        _ptr(V, torch.bfloat16, "V", (hkv, pool, HEAD_DIM)),
+        ctypes.byref(cfg), _ptr(q, torch.bfloat16, "q", (batch, cfg.num_q_heads, cfg.head_dim)),
+        _ptr(K, torch.bfloat16, "K", (hkv, pool, cfg.head_dim)),
+        _ptr(V, torch.bfloat16, "V", (hkv, pool, cfg.head_dim)),
         _ptr(seq_start, torch.int64, "seq_start", (batch,)),
         _ptr(seq_len, torch.int32, "seq_len", (batch,)), batch,
-        _ptr(out, torch.float32, "out", (batch, cfg.num_q_heads, HEAD_DIM)),
+        _ptr(out, torch.float32, "out", (batch, cfg.num_q_heads, cfg.head_dim)),
         max_seq_len, _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream))
     _check(rc, "adamas_full_attn")
 
@@ -286,12 +286,12 @@ def adamas_sparse_attn(cfg: Config, q, K, V, seq_start, idx, out, max_seq_len: i
     batch, _, k = idx.shape
     hkv, pool = cfg.num_kv_heads, cfg.pool_tokens
     rc = library().adamas_sparse_attn(
-        ctypes.byref(cfg), _ptr(q, torch.bfloat16, "q", (batch, cfg.num_q_heads, HEAD_DIM)),
-        _ptr(K, torch.bfloat16, "K", (hkv, pool, HEAD_DIM)),
-        _ptr(V, torch.bfloat16, "V", (hkv, pool, HEAD_DIM)),
+        ctypes.byref(cfg), _ptr(q, torch.bfloat16, "q", (batch, cfg.num_q_heads, cfg.head_dim)),
+        _ptr(K, torch.bfloat16, "K", (hkv, pool, cfg.head_dim)),
+        _ptr(V, torch.bfloat16, "V", (hkv, pool, cfg.head_dim)),
         _ptr(seq_start, torch.int64, "seq_start", (batch,)),
         _ptr(idx, torch.int32, "idx", (batch, cfg.num_q_heads, k)), batch, k,
-        _ptr(out, torch.float32, "out", (batch, cfg.num_q_heads, HEAD_DIM)), max_seq_len,
+        _ptr(out, torch.float32, "out", (batch, cfg.num_q_heads, cfg.head_dim)), max_seq_len,
         _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream))
     _check(rc, "adamas_sparse_attn")
 
@@ -316,15 +316,15 @@ def adamas_decode_step_stages(cfg: Config, q, K, V, codes, seq_start, seq_len, k
     fn = library().adamas_decode_step if stages is None else library().adamas_decode_step_stages
     extra = () if stages is None else (int(stages),)
     rc = fn(
-        ctypes.byref(cfg), _ptr(q, torch.bfloat16, "q", (batch, cfg.num_q_heads, HEAD_DIM)),
-        _ptr(k_new, torch.bfloat16, "k_new", (batch, hkv, HEAD_DIM), optional=True),
-        _ptr(v_new, torch.bfloat16, "v_new", (batch, hkv, HEAD_DIM), optional=True),
-        _ptr(K, torch.bfloat16, "K", (hkv, pool, HEAD_DIM)),
-        _ptr(V, torch.bfloat16, "V", (hkv, pool, HEAD_DIM)),
+        ctypes.byref(cfg), _ptr(q, torch.bfloat16, "q", (batch, cfg.num_q_heads, cfg.head_dim)),
+        _ptr(k_new, torch.bfloat16, "k_new", (batch, hkv, cfg.head_dim), optional=True),
+        _ptr(v_new, torch.bfloat16, "v_new", (batch, hkv, cfg.head_dim), optional=True),
+        _ptr(K, torch.bfloat16, "K", (hkv, pool, cfg.head_dim)),
+        _ptr(V, torch.bfloat16, "V", (hkv, pool, cfg.head_dim)),
         _ptr(codes, torch.uint8, "codes", (hkv, pool, cfg.code_row_bytes)),
         _ptr(seq_start, torch.int64, "seq_start", (batch,)),
         _ptr(seq_len, torch.int32, "seq_len", (batch,)), batch, k,
-        _ptr(out, torch.float32, "out", (batch, cfg.num_q_heads, HEAD_DIM)),
+        _ptr(out, torch.float32, "out", (batch, cfg.num_q_heads, cfg.head_dim)),
         _ptr(idx_out, torch.int32, "idx_out", (batch, cfg.num_q_heads, k), optional=True),
         max_seq_len, _ptr(workspace, torch.uint8, "workspace"), workspace.numel(),
         _stream(stream), *extra)

@@ -30,6 +30,7 @@ struct Plan {
   int seg_len;       // tokens per select workgroup, a multiple of kSegGranule (hence of the tile)
   int n_segs;        // select workgroups per (sequence, query head)
   int metric;        // code format + distance estimator (struct Dist)
+  int head_dim;      // 64, 128 or 256
   int g_split;       // scan workgroups per (tile, KV head), each with a share of the query group
   int64_t dist_stride;
   size_t off_dist, off_hist, off_partial, total;
@@ -46,7 +47,9 @@ int metric_of(const adamas_config* c) {
   return (c->variant & ADAMAS_VARIANT_L2) ? kMetricL2 : kMetricL1;
 }
 
-size_t hist_stride_of(int metric) {
+size_t hist_stride_of(int metric, int head_dim) {
+  if (head_dim == 64) return Dist<kMetricL1, 64>::kStride;
+  if (head_dim == 256) return Dist<kMetricL1, 256>::kStride;
   switch (metric) {
     case kMetricL2: return Dist<kMetricL2>::kStride;
     case kMetricB1: return Dist<kMetricB1>::kStride;
@@ -70,7 +73,11 @@ int check_config(const adamas_config* c) {
     }
   }
   if (!std::isfinite(c->sm_scale) || c->sm_scale < 0.f) return ADAMAS_ERR_BAD_ARG;
-  if (c->head_dim != ADAMAS_HEAD_DIM) return ADAMAS_ERR_UNSUPPORTED;
+  if (c->head_dim != 64 && c->head_dim != 128 && c->head_dim != 256) return ADAMAS_ERR_UNSUPPORTED;
+  if (c->head_dim != 128) {  // other head dimensions: the method itself only
+    if ((c->variant & ADAMAS_VARIANT_L2) || code_bits(c) != 2) return ADAMAS_ERR_UNSUPPORTED;
+    if (c->head_dim == 256 && c->num_q_heads / c->num_kv_heads > 4) return ADAMAS_ERR_UNSUPPORTED;
+  }
   if (c->variant & ~(ADAMAS_VARIANT_NO_HADAMARD | ADAMAS_VARIANT_L2)) return ADAMAS_ERR_UNSUPPORTED;
   if ((c->variant & ADAMAS_VARIANT_L2) && code_bits(c) != 2) return ADAMAS_ERR_UNSUPPORTED;
   if (c->num_q_heads / c->num_kv_heads > ADAMAS_MAX_GROUP) return ADAMAS_ERR_UNSUPPORTED;
@@ -88,6 +95,7 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 Plan make_plan(const adamas_config* c, int32_t batch, int64_t max_seq_len, int32_t k) {
   Plan pl{};
   pl.metric = metric_of(c);
+  pl.head_dim = c->head_dim;
   const int64_t planes = (int64_t)batch * c->num_kv_heads;
   // Scan tile (measured on MI355X): large tiles amortise the per-workgroup
   // prologue and leave the select kernel fewer tile histograms to read, small
@@ -133,9 +141,9 @@ Plan make_plan(const adamas_config* c, int32_t batch, int64_t max_seq_len, int32
   pl.off_dist = off;
   off = align256(off + heads * (size_t)pl.dist_stride * sizeof(uint16_t));
   pl.off_hist = off;
-  off = align256(off + heads * (size_t)pl.n_tiles * hist_stride_of(pl.metric) * sizeof(uint16_t));
+  off = align256(off + heads * (size_t)pl.n_tiles * hist_stride_of(pl.metric, c->head_dim) * sizeof(uint16_t));
   pl.off_partial = off;
-  off = align256(off + heads * (size_t)kMaxParts * kPartialStride * sizeof(float));
+  off = align256(off + heads * (size_t)kMaxParts * partial_stride(c->head_dim) * sizeof(float));
   pl.total = off;
   return pl;
 }
@@ -144,55 +152,66 @@ Plan make_plan(const adamas_config* c, int32_t batch, int64_t max_seq_len, int32
 Thresholds scaled(const adamas_config* c, const float* thr) {
   Thresholds t{};
   t.transform = (c->variant & ADAMAS_VARIANT_NO_HADAMARD) ? 0 : 1;
-  const double root = t.transform ? std::sqrt((double)ADAMAS_HEAD_DIM) : 1.0;
+  const double root = t.transform ? std::sqrt((double)c->head_dim) : 1.0;
   const int n_thr = (1 << code_bits(c)) - 1;
   for (int i = 0; i < n_thr; ++i) t.tau[i] = (double)thr[i] * root;
   return t;
 }
 
-template <bool ATTN, int METRIC>
+template <bool ATTN, int METRIC, int D>
 void launch_select_m(bool paged, dim3 grid, hipStream_t st, const SelectParams& sl) {
-  if constexpr (ATTN) {
+  if constexpr (ATTN && D == 128) {
     if (paged) {
-      hipLaunchKernelGGL((select_kernel<kSelThreads, ATTN, METRIC, true>), grid, dim3(kSelThreads), 0, st, sl);
+      hipLaunchKernelGGL((select_kernel<kSelThreads, ATTN, METRIC, true, D>), grid, dim3(kSelThreads), 0, st, sl);
       return;
     }
   }
-  hipLaunchKernelGGL((select_kernel<kSelThreads, ATTN, METRIC, false>), grid, dim3(kSelThreads), 0, st, sl);
+  hipLaunchKernelGGL((select_kernel<kSelThreads, ATTN, METRIC, false, D>), grid, dim3(kSelThreads), 0, st, sl);
 }
 
+// Head dimensions 64 and 256 are built for the method itself (2-bit codes, Eq. 6,
+// contiguous cache); check_config / the paged entry point reject the rest.
 template <bool ATTN>
-void launch_select(int metric, bool paged, dim3 grid, hipStream_t st, const SelectParams& sl) {
+void launch_select(int metric, int head_dim, bool paged, dim3 grid, hipStream_t st,
+                   const SelectParams& sl) {
+  if (head_dim == 64) return launch_select_m<ATTN, kMetricL1, 64>(false, grid, st, sl);
+  if (head_dim == 256) return launch_select_m<ATTN, kMetricL1, 256>(false, grid, st, sl);
   switch (metric) {
-    case kMetricL2: launch_select_m<ATTN, kMetricL2>(paged, grid, st, sl); break;
-    case kMetricB1: launch_select_m<ATTN, kMetricB1>(paged, grid, st, sl); break;
-    case kMetricB3: launch_select_m<ATTN, kMetricB3>(paged, grid, st, sl); break;
-    default: launch_select_m<ATTN, kMetricL1>(paged, grid, st, sl); break;
+    case kMetricL2: launch_select_m<ATTN, kMetricL2, 128>(paged, grid, st, sl); break;
+    case kMetricB1: launch_select_m<ATTN, kMetricB1, 128>(paged, grid, st, sl); break;
+    case kMetricB3: launch_select_m<ATTN, kMetricB3, 128>(paged, grid, st, sl); break;
+    default: launch_select_m<ATTN, kMetricL1, 128>(paged, grid, st, sl); break;
   }
 }
 
 // Bulk encode of n_vec vectors with the config's code width.
-void launch_encode_rows(const adamas_config* c, int grid, hipStream_t st, const uint16_t* src,
-                        uint8_t* dst, int64_t head_stride_rows, int64_t row_begin, int64_t n_rows,
-                        int64_t n_vec, const Thresholds& thr) {
+template <int BITS, int D>
+void launch_encode_rows_bd(int64_t n_vec, hipStream_t st, const uint16_t* src, uint8_t* dst,
+                           int64_t head_stride_rows, int64_t row_begin, int64_t n_rows,
+                           const Thresholds& thr) {
+  const int64_t per_wg = 256 / (D / 32);  // vectors per 256-thread workgroup
+  const int64_t want = (n_vec + per_wg - 1) / per_wg;
+  const int grid = (int)(want < 16384 ? want : 16384);
+  hipLaunchKernelGGL((encode_rows_kernel<BITS, D>), dim3(grid), dim3(256), 0, st, src, dst,
+                     head_stride_rows, row_begin, n_rows, n_vec, thr);
+}
+
+void launch_encode_rows(const adamas_config* c, hipStream_t st, const uint16_t* src, uint8_t* dst,
+                        int64_t head_stride_rows, int64_t row_begin, int64_t n_rows, int64_t n_vec,
+                        const Thresholds& thr) {
+  if (c->head_dim == 64)
+    return launch_encode_rows_bd<2, 64>(n_vec, st, src, dst, head_stride_rows, row_begin, n_rows, thr);
+  if (c->head_dim == 256)
+    return launch_encode_rows_bd<2, 256>(n_vec, st, src, dst, head_stride_rows, row_begin, n_rows, thr);
   switch (code_bits(c)) {
-    case 1:
-      hipLaunchKernelGGL(encode_rows_kernel<1>, dim3(grid), dim3(256), 0, st, src, dst,
-                         head_stride_rows, row_begin, n_rows, n_vec, thr);
-      break;
-    case 3:
-      hipLaunchKernelGGL(encode_rows_kernel<3>, dim3(grid), dim3(256), 0, st, src, dst,
-                         head_stride_rows, row_begin, n_rows, n_vec, thr);
-      break;
-    default:
-      hipLaunchKernelGGL(encode_rows_kernel<2>, dim3(grid), dim3(256), 0, st, src, dst,
-                         head_stride_rows, row_begin, n_rows, n_vec, thr);
-      break;
+    case 1: launch_encode_rows_bd<1, 128>(n_vec, st, src, dst, head_stride_rows, row_begin, n_rows, thr); break;
+    case 3: launch_encode_rows_bd<3, 128>(n_vec, st, src, dst, head_stride_rows, row_begin, n_rows, thr); break;
+    default: launch_encode_rows_bd<2, 128>(n_vec, st, src, dst, head_stride_rows, row_begin, n_rows, thr); break;
   }
 }
 
 float scale_log2e(const adamas_config* c) {
-  const double s = c->sm_scale > 0.f ? (double)c->sm_scale : 1.0 / std::sqrt((double)ADAMAS_HEAD_DIM);
+  const double s = c->sm_scale > 0.f ? (double)c->sm_scale : 1.0 / std::sqrt((double)c->head_dim);
   return (float)(s * kLog2e);
 }
 
@@ -209,12 +228,12 @@ int launch_status() {
   return ADAMAS_OK;
 }
 
-template <int G, bool FUSED, int METRIC, bool PAGED>
+template <int G, bool FUSED, int METRIC, bool PAGED, int D>
 void launch_scan_gmp(const Plan& pl, dim3 grid, hipStream_t st, const ScanParams& sp) {
   switch (pl.tile_tokens) {
-    case 1024: hipLaunchKernelGGL((scan_kernel<G, FUSED, 4, METRIC, PAGED>), grid, dim3(256), 0, st, sp); break;
-    case 2048: hipLaunchKernelGGL((scan_kernel<G, FUSED, 8, METRIC, PAGED>), grid, dim3(512), 0, st, sp); break;
-    default: hipLaunchKernelGGL((scan_kernel<G, FUSED, 16, METRIC, PAGED>), grid, dim3(1024), 0, st, sp); break;
+    case 1024: hipLaunchKernelGGL((scan_kernel<G, FUSED, 4, METRIC, PAGED, D>), grid, dim3(256), 0, st, sp); break;
+    case 2048: hipLaunchKernelGGL((scan_kernel<G, FUSED, 8, METRIC, PAGED, D>), grid, dim3(512), 0, st, sp); break;
+    default: hipLaunchKernelGGL((scan_kernel<G, FUSED, 16, METRIC, PAGED, D>), grid, dim3(1024), 0, st, sp); break;
   }
 }
 
@@ -222,15 +241,19 @@ template <int G, bool FUSED, int METRIC>
 void launch_scan_gm(const Plan& pl, dim3 grid, hipStream_t st, const ScanParams& sp) {
   if constexpr (FUSED) {
     if (sp.page_table != nullptr) {
-      launch_scan_gmp<G, FUSED, METRIC, true>(pl, grid, st, sp);
+      launch_scan_gmp<G, FUSED, METRIC, true, 128>(pl, grid, st, sp);
       return;
     }
   }
-  launch_scan_gmp<G, FUSED, METRIC, false>(pl, grid, st, sp);
+  launch_scan_gmp<G, FUSED, METRIC, false, 128>(pl, grid, st, sp);
 }
 
 template <int G, bool FUSED>
 void launch_scan_g(const Plan& pl, dim3 grid, hipStream_t st, const ScanParams& sp) {
+  if (pl.head_dim == 64) return launch_scan_gmp<G, FUSED, kMetricL1, false, 64>(pl, grid, st, sp);
+  if constexpr (G <= 4) {  // check_config: groups above four are not built at 256
+    if (pl.head_dim == 256) return launch_scan_gmp<G, FUSED, kMetricL1, false, 256>(pl, grid, st, sp);
+  }
   switch (pl.metric) {
     case kMetricL2: launch_scan_gm<G, FUSED, kMetricL2>(pl, grid, st, sp); break;
     case kMetricB1: launch_scan_gm<G, FUSED, kMetricB1>(pl, grid, st, sp); break;
@@ -272,13 +295,22 @@ FullPlan make_full_plan(const adamas_config* c, int32_t batch, int64_t max_seq_l
   chunk = (chunk + 255) / 256 * 256;
   fp.chunk = (int)chunk;
   fp.n_splits = (int)((max_seq_len + chunk - 1) / chunk);
-  fp.total = align256((size_t)batch * c->num_q_heads * fp.n_splits * kPartialStride * sizeof(float));
+  fp.total = align256((size_t)batch * c->num_q_heads * fp.n_splits * partial_stride(c->head_dim) * sizeof(float));
   return fp;
 }
 
 template <int G>
-void launch_full(dim3 grid, hipStream_t st, const FullAttnParams& fp) {
-  hipLaunchKernelGGL((full_attn_kernel<G>), grid, dim3(kFullThreads), 0, st, fp);
+void launch_full(int head_dim, dim3 grid, hipStream_t st, const FullAttnParams& fp) {
+  if (head_dim == 64) hipLaunchKernelGGL((full_attn_kernel<G, 64>), grid, dim3(kFullThreads), 0, st, fp);
+  else if (head_dim == 256) hipLaunchKernelGGL((full_attn_kernel<G, 256>), grid, dim3(kFullThreads), 0, st, fp);
+  else hipLaunchKernelGGL((full_attn_kernel<G, 128>), grid, dim3(kFullThreads), 0, st, fp);
+}
+
+template <typename P>
+void launch_merge(int head_dim, dim3 grid, hipStream_t st, const P& mp) {
+  if (head_dim == 64) hipLaunchKernelGGL(merge_kernel<64>, grid, dim3(64), 0, st, mp);
+  else if (head_dim == 256) hipLaunchKernelGGL(merge_kernel<256>, grid, dim3(256), 0, st, mp);
+  else hipLaunchKernelGGL(merge_kernel<128>, grid, dim3(128), 0, st, mp);
 }
 
 uint8_t* ws_at(void* ws, size_t off) { return static_cast<uint8_t*>(ws) + off; }
@@ -315,9 +347,7 @@ int adamas_encode_keys(const adamas_config* cfg, const void* K, void* codes, int
   if (n_rows == 0) return ADAMAS_OK;
   clear_stale_error();
   const int64_t n_vec = n_rows * cfg->num_kv_heads;
-  const int64_t want = (n_vec + 63) / 64;  // 64 vectors per 256-thread workgroup
-  const int grid = (int)(want < 16384 ? want : 16384);
-  launch_encode_rows(cfg, grid, (hipStream_t)stream, static_cast<const uint16_t*>(K),
+  launch_encode_rows(cfg, (hipStream_t)stream, static_cast<const uint16_t*>(K),
                      static_cast<uint8_t*>(codes), cfg->pool_tokens, row_begin, n_rows, n_vec,
                      scaled(cfg, cfg->thr_k));
   return launch_status();
@@ -330,10 +360,8 @@ int adamas_encode_query(const adamas_config* cfg, const void* q, void* qcodes, i
   if (!aligned16(q) || !aligned16(qcodes)) return ADAMAS_ERR_BAD_ARG;
   clear_stale_error();
   const int64_t n_vec = (int64_t)batch * cfg->num_q_heads;
-  const int64_t want = (n_vec + 63) / 64;
-  const int grid = (int)(want < 16384 ? want : 16384);
   // queries form one "head" of n_vec consecutive rows
-  launch_encode_rows(cfg, grid, (hipStream_t)stream, static_cast<const uint16_t*>(q),
+  launch_encode_rows(cfg, (hipStream_t)stream, static_cast<const uint16_t*>(q),
                      static_cast<uint8_t*>(qcodes), 0, 0, n_vec, n_vec, scaled(cfg, cfg->thr_q));
   return launch_status();
 }
@@ -411,7 +439,7 @@ int adamas_select_topk(const adamas_config* cfg, const void* qcodes, const void*
   sl.n_tiles = pl.n_tiles;
   sl.tile_tokens = pl.tile_tokens;
   sl.seg_len = pl.seg_len;
-  launch_select<false>(pl.metric, false, dim3(pl.n_segs, cfg->num_q_heads, batch), st, sl);
+  launch_select<false>(pl.metric, cfg->head_dim, false, dim3(pl.n_segs, cfg->num_q_heads, batch), st, sl);
   return launch_status();
 }
 
@@ -446,8 +474,12 @@ int adamas_sparse_attn(const adamas_config* cfg, const void* q, const void* K, c
   ap.chunk = (k + parts - 1) / parts;
   ap.n_parts = (k + ap.chunk - 1) / ap.chunk;
   ap.scale_log2e = scale_log2e(cfg);
-  hipLaunchKernelGGL(sparse_attn_kernel, dim3(ap.n_parts, cfg->num_q_heads, batch),
-                     dim3(kAttnThreads), 0, st, ap);
+  {
+    const dim3 grid(ap.n_parts, cfg->num_q_heads, batch);
+    if (cfg->head_dim == 64) hipLaunchKernelGGL(sparse_attn_kernel<64>, grid, dim3(kAttnThreads), 0, st, ap);
+    else if (cfg->head_dim == 256) hipLaunchKernelGGL(sparse_attn_kernel<256>, grid, dim3(kAttnThreads), 0, st, ap);
+    else hipLaunchKernelGGL(sparse_attn_kernel<128>, grid, dim3(kAttnThreads), 0, st, ap);
+  }
   if (int rc = launch_status()) return rc;
   if (ap.n_parts == 1) return ADAMAS_OK;
   MergeParams mp{};
@@ -457,7 +489,7 @@ int adamas_sparse_attn(const adamas_config* cfg, const void* q, const void* K, c
   mp.Hq = cfg->num_q_heads;
   mp.n_parts = ap.n_parts;
   mp.seg_len = 0;
-  hipLaunchKernelGGL(merge_kernel, dim3(cfg->num_q_heads, batch), dim3(kHeadDim), 0, st, mp);
+  launch_merge(cfg->head_dim, dim3(cfg->num_q_heads, batch), st, mp);
   return launch_status();
 }
 
@@ -500,6 +532,7 @@ int adamas_decode_step_paged(const adamas_config* cfg, const void* q, const void
                              size_t workspace_bytes, void* stream, uint32_t stages) {
   if (int rc = check_config(cfg)) return rc;
   if (page_table == nullptr || max_pages < 1) return ADAMAS_ERR_BAD_ARG;
+  if (cfg->head_dim != 128) return ADAMAS_ERR_UNSUPPORTED;  // paged kernels are built for d = 128
   if (stages != ADAMAS_STAGE_ALL && stages != ADAMAS_STAGE_SCAN) return ADAMAS_ERR_BAD_ARG;
   if (page_tokens < 64 || page_tokens > 4096 || (page_tokens & (page_tokens - 1)) != 0)
     return ADAMAS_ERR_UNSUPPORTED;
@@ -560,7 +593,7 @@ int decode_step_impl(const adamas_config* cfg, const void* q, const void* k_new,
   sp.page_shift = page_shift;
   // segment counters live in the unused words of each head's first partial slot
   sp.arrivals = reinterpret_cast<uint32_t*>(ws_at(workspace, pl.off_partial)) + 2;
-  sp.arrivals_stride = (int64_t)kMaxParts * kPartialStride;
+  sp.arrivals_stride = (int64_t)kMaxParts * partial_stride(cfg->head_dim);
   if (stages & ADAMAS_STAGE_SCAN) {
     launch_scan<true>(cfg->num_q_heads / cfg->num_kv_heads, pl, cfg->num_kv_heads, batch, st, sp);
     if (int rc = launch_status()) return rc;
@@ -593,7 +626,7 @@ int decode_step_impl(const adamas_config* cfg, const void* q, const void* k_new,
   sl.page_table = page_table;
   sl.max_pages = max_pages;
   sl.page_shift = page_shift;
-  launch_select<true>(pl.metric, page_table != nullptr, dim3(pl.n_segs, cfg->num_q_heads, batch), st, sl);
+  launch_select<true>(pl.metric, cfg->head_dim, page_table != nullptr, dim3(pl.n_segs, cfg->num_q_heads, batch), st, sl);
   if (int rc = launch_status()) return rc;
   if (pl.n_segs == 1 || sl.arrivals != nullptr) return ADAMAS_OK;  // the select kernel wrote `out` itself
   MergeParams mp{};
@@ -606,7 +639,7 @@ int decode_step_impl(const adamas_config* cfg, const void* q, const void* k_new,
   mp.Hq = cfg->num_q_heads;
   mp.n_parts = pl.n_segs;
   mp.seg_len = pl.seg_len;
-  hipLaunchKernelGGL(merge_kernel, dim3(cfg->num_q_heads, batch), dim3(kHeadDim), 0, st, mp);
+  launch_merge(cfg->head_dim, dim3(cfg->num_q_heads, batch), st, mp);
   return launch_status();
 }
 }  // namespace
@@ -647,18 +680,25 @@ int adamas_full_attn(const adamas_config* cfg, const void* q, const void* K, con
   fp.scale_log2e = scale_log2e(cfg);
   const dim3 grid(pl.n_splits, cfg->num_kv_heads, batch);
   switch (cfg->num_q_heads / cfg->num_kv_heads) {
-    case 1: launch_full<1>(grid, st, fp); break;
-    case 2: launch_full<2>(grid, st, fp); break;
-    case 3: launch_full<3>(grid, st, fp); break;
-    case 4: launch_full<4>(grid, st, fp); break;
-    case 5: launch_full<5>(grid, st, fp); break;
-    case 6: launch_full<6>(grid, st, fp); break;
-    case 7: launch_full<7>(grid, st, fp); break;
-    default: launch_full<8>(grid, st, fp); break;
+    case 1: launch_full<1>(cfg->head_dim, grid, st, fp); break;
+    case 2: launch_full<2>(cfg->head_dim, grid, st, fp); break;
+    case 3: launch_full<3>(cfg->head_dim, grid, st, fp); break;
+    case 4: launch_full<4>(cfg->head_dim, grid, st, fp); break;
+    case 5: launch_full<5>(cfg->head_dim, grid, st, fp); break;
+    case 6: launch_full<6>(cfg->head_dim, grid, st, fp); break;
+    case 7: launch_full<7>(cfg->head_dim, grid, st, fp); break;
+    default: launch_full<8>(cfg->head_dim, grid, st, fp); break;
   }
   if (int rc = launch_status()) return rc;
-  hipLaunchKernelGGL(merge_parts_kernel, dim3(cfg->num_q_heads, batch), dim3(kHeadDim), 0, st,
-                     fp.partial, out, cfg->num_q_heads, pl.n_splits);
+  {
+    const dim3 mgrid(cfg->num_q_heads, batch);
+    if (cfg->head_dim == 64)
+      hipLaunchKernelGGL(merge_parts_kernel<64>, mgrid, dim3(64), 0, st, fp.partial, out, cfg->num_q_heads, pl.n_splits);
+    else if (cfg->head_dim == 256)
+      hipLaunchKernelGGL(merge_parts_kernel<256>, mgrid, dim3(256), 0, st, fp.partial, out, cfg->num_q_heads, pl.n_splits);
+    else
+      hipLaunchKernelGGL(merge_parts_kernel<128>, mgrid, dim3(128), 0, st, fp.partial, out, cfg->num_q_heads, pl.n_splits);
+  }
   return launch_status();
 }
 

@@ -15,17 +15,23 @@ constexpr int kRowBytes = 32;        // packed code row of the method (2-bit cod
 //   kMetricB3   3-bit codes, Eq. 6 (Section 4.4, 0..896)
 // A code row is four words of kBits 32-bit planes (16 * kBits bytes): plane p of
 // word g holds, at bit j, bit p of the code of coefficient 32g + j.
+// D is the head dimension (128 in the paper's models; 64 and 256 are built for
+// the method itself): D / 32 words per row, distances up to 3 * D.
 constexpr int kMetricL1 = 0, kMetricL2 = 1, kMetricB1 = 2, kMetricB3 = 3;
-template <int METRIC>
+template <int METRIC, int D = 128>
 struct Dist {
   static constexpr int kBits = METRIC == kMetricB1 ? 1 : METRIC == kMetricB3 ? 3 : 2;
-  static constexpr int kRowBytes = 16 * kBits;
-  static constexpr int kBins =  // distinct distance values
-      METRIC == kMetricL1 ? 385 : METRIC == kMetricL2 ? 1153 : METRIC == kMetricB1 ? 129 : 897;
-  // uint16 per stored tile histogram, a 16-byte multiple: 392, 1160, 136, 904
+  static constexpr int kWords = D / 32;                 // words per row, kBits planes each
+  static constexpr int kRowBytes = kWords * 4 * kBits;  // 32 for the method at D = 128
+  static constexpr int kMaxDist =  // largest distance between two code vectors
+      (METRIC == kMetricL1 ? 3 : METRIC == kMetricL2 ? 9 : METRIC == kMetricB1 ? 1 : 7) * D;
+  static constexpr int kBins = kMaxDist + 1;  // distinct distance values: 385 for the method
+  // uint16 per stored tile histogram, a 16-byte multiple (392 for the method)
   static constexpr int kStride = (kBins + 7) / 8 * 8;
+  static_assert(kRowBytes % 16 == 0, "rows are fetched in 16-byte pieces");
 };
-constexpr int kPartialStride = 132;  // floats per attention partial: m, l, pad, pad, o[128]
+// floats per attention partial of a head of dimension d: m, l, pad, pad, o[d]
+constexpr int partial_stride(int d) { return d + 4; }
 constexpr int kWave = 64;
 
 // Length of sequence b as the kernels use it: a sequence whose (device-side,
@@ -80,14 +86,17 @@ __device__ __forceinline__ float dpp_f32(float v) {
   return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
 }
 
-// Sum over each row of 16 lanes; every lane of the row receives the total.
-// After the two quad steps all lanes of a quad agree, so mirroring inside the
-// half row pairs quad 0 with quad 1, and mirroring the row pairs the halves.
-__device__ __forceinline__ float row16_sum_f32(float v) {
+// Sum over each aligned group of LANES lanes (8, 16 or 32); every lane of the
+// group receives the total.  After the two quad steps all lanes of a quad
+// agree, so mirroring inside the half row pairs quad 0 with quad 1, mirroring
+// the row pairs the halves, and a 32-lane group adds its other DPP row.
+template <int LANES>
+__device__ __forceinline__ float lanes_sum_f32(float v) {
   v += dpp_f32<kDppQuadXor1>(v);
   v += dpp_f32<kDppQuadXor2>(v);
   v += dpp_f32<kDppRowHalfMirror>(v);
-  v += dpp_f32<kDppRowMirror>(v);
+  if constexpr (LANES >= 16) v += dpp_f32<kDppRowMirror>(v);
+  if constexpr (LANES >= 32) v += __shfl_xor(v, 16, kWave);
   return v;
 }
 

@@ -1,6 +1,6 @@
 // Hadamard transform (Eq. 4) + bucketize (Eq. 5) + 2-bit pack of one 128-d
 // bf16 vector by one wavefront, and the bulk key / query encode kernels
-// (Algorithm 1 lines 1-3).
+// (Algorithm 1, transform / bucketize / compress steps).
 #pragma once
 
 #include "device_utils.hpp"
@@ -33,62 +33,68 @@ __device__ __forceinline__ void planes_from_masks(const M* m, M* plane) {
   }
 }
 
-// One wave64 encodes one vector.  Lane l holds x[l] and x[l+64]; the
-// butterfly over index bit 6 is lane-local, bits 0..5 go across lanes.  All
-// sums are fp64 and exact for inputs within the documented exponent spread,
-// so the stage order does not influence the result.
+// One wave64 encodes one vector of D elements.  Lane l holds x[l + 64e] for
+// e < D / 64; the butterflies over index bits 6 and up are lane-local, bits
+// 0..5 go across lanes.  All sums are fp64 and exact for inputs within the
+// documented exponent spread, so the stage order does not influence the result.
 // Result: w[p][g], plane p of word g of the packed row, identical in every lane.
-// All 64 lanes must be active.  The two elements come already loaded (raw bf16
+// All 64 lanes must be active.  The elements come already loaded (raw bf16
 // bits), so that a caller can issue that load ahead of other memory traffic.
-template <int BITS>
-__device__ __forceinline__ void encode_values_wave(uint32_t bits_lo, uint32_t bits_hi,
-                                                   const Thresholds& thr, uint32_t w[BITS][4]) {
-  constexpr int T = (1 << BITS) - 1;
+template <int BITS, int D>
+__device__ __forceinline__ void encode_values_wave(const uint32_t (&raw)[D / 64],
+                                                   const Thresholds& thr,
+                                                   uint32_t w[BITS][D / 32]) {
+  constexpr int T = (1 << BITS) - 1, E = D / 64;
   const int lane = threadIdx.x & 63;
-  double a = (double)bf16_bits_to_float(bits_lo);
-  double b = (double)bf16_bits_to_float(bits_hi);
+  double v[E];
+#pragma unroll
+  for (int e = 0; e < E; ++e) v[e] = (double)bf16_bits_to_float(raw[e]);
   if (thr.transform) {
-    {
-      double s = a + b, d = a - b;
-      a = s;
-      b = d;
+#pragma unroll
+    for (int h = 1; h < E; h <<= 1) {  // index bits 6.. : inside the lane
+#pragma unroll
+      for (int e = 0; e < E; ++e) {
+        if ((e & h) == 0) {
+          const double a = v[e], b = v[e + h];
+          v[e] = a + b;
+          v[e + h] = a - b;
+        }
+      }
     }
 #pragma unroll
-    for (int h = 1; h < 64; h <<= 1) {
-      double pa = __shfl_xor(a, h, kWave);
-      double pb = __shfl_xor(b, h, kWave);
+    for (int h = 1; h < 64; h <<= 1) {  // index bits 0..5: across the wave
       const bool upper = (lane & h) != 0;
-      a = upper ? pa - a : a + pa;
-      b = upper ? pb - b : b + pb;
+#pragma unroll
+      for (int e = 0; e < E; ++e) {
+        const double partner = __shfl_xor(v[e], h, kWave);
+        v[e] = upper ? partner - v[e] : v[e] + partner;
+      }
     }
   }
-  uint64_t ma[T], mb[T], pa[BITS], pb[BITS];
 #pragma unroll
-  for (int i = 0; i < T; ++i) {
-    ma[i] = __ballot(a > thr.tau[i]);
-    mb[i] = __ballot(b > thr.tau[i]);
-  }
-  planes_from_masks<BITS>(ma, pa);
-  planes_from_masks<BITS>(mb, pb);
+  for (int e = 0; e < E; ++e) {
+    uint64_t m[T], plane[BITS];
 #pragma unroll
-  for (int p = 0; p < BITS; ++p) {
-    w[p][0] = (uint32_t)pa[p];
-    w[p][1] = (uint32_t)(pa[p] >> 32);
-    w[p][2] = (uint32_t)pb[p];
-    w[p][3] = (uint32_t)(pb[p] >> 32);
+    for (int i = 0; i < T; ++i) m[i] = __ballot(v[e] > thr.tau[i]);
+    planes_from_masks<BITS>(m, plane);
+#pragma unroll
+    for (int p = 0; p < BITS; ++p) {
+      w[p][2 * e] = (uint32_t)plane[p];
+      w[p][2 * e + 1] = (uint32_t)(plane[p] >> 32);
+    }
   }
 }
 
-// ---- bulk encode: four lanes per vector -----------------------------------
+// ---- bulk encode: D / 32 lanes per vector ---------------------------------
 //
-// Lane j of a quad holds elements 32j .. 32j+31 of one vector as doubles, so
-// five of the seven butterfly stages are register-to-register and only index
-// bits 5 and 6 cross lanes (DPP quad permutes).  After the transform lane j
-// holds coefficients 32j .. 32j+31, which is exactly word j of the packed row:
-// every lane assembles and stores its own 8 bytes.  A wave encodes 16 vectors
-// and moves 4 KiB in, 512 B out, both contiguous.  All sums are fp64 and exact
-// under the documented exponent spread, hence identical to the wave-per-vector
-// routine above whatever the order.
+// Lane j of a group holds elements 32j .. 32j+31 of one vector as doubles, so
+// five butterfly stages are register-to-register and only the index bits from 5
+// up cross lanes (two stages at D = 128, by DPP quad permutes).  After the
+// transform lane j holds coefficients 32j .. 32j+31, which is exactly word j of
+// the packed row: every lane assembles and stores its own word.  At D = 128 a
+// wave encodes 16 vectors and moves 4 KiB in, 512 B out, both contiguous.  All
+// sums are fp64 and exact under the documented exponent spread, hence identical
+// to the wave-per-vector routine above whatever the order.
 
 __device__ __forceinline__ double dpp_quad_xor_f64(double v, bool xor2) {
   const uint64_t bits = __builtin_bit_cast(uint64_t, v);
@@ -113,21 +119,22 @@ __device__ __forceinline__ uint32_t push_greater(uint32_t mask, double y, double
 }
 
 // Vector v of n_vec = n_heads * n_rows lives at
-// src + (head * head_stride_rows + row_begin + r) * 128, head = v / n_rows,
-// r = v % n_rows; its code row goes to the same row of dst (16 * BITS byte rows).
-template <int BITS>
+// src + (head * head_stride_rows + row_begin + r) * D, head = v / n_rows,
+// r = v % n_rows; its code row goes to the same row of dst (D / 8 * BITS byte rows).
+template <int BITS, int D>
 __global__ __launch_bounds__(256) void encode_rows_kernel(const uint16_t* __restrict__ src,
                                                           uint8_t* __restrict__ dst,
                                                           int64_t head_stride_rows,
                                                           int64_t row_begin, int64_t n_rows,
                                                           int64_t n_vec, Thresholds thr) {
-  const int j = threadIdx.x & 3;  // which 32-element quarter of the vector
-  const int64_t quad = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 2;
-  const int64_t n_quads = ((int64_t)gridDim.x * blockDim.x) >> 2;
+  constexpr int LPV = D / 32;        // lanes per vector: 2, 4 or 8
+  const int j = threadIdx.x & (LPV - 1);  // which 32-element part of the vector
+  const int64_t quad = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / LPV;
+  const int64_t n_quads = ((int64_t)gridDim.x * blockDim.x) / LPV;
   for (int64_t v = quad; v < n_vec; v += n_quads) {
     const int64_t head = v / n_rows, r = v - head * n_rows;
     const int64_t row = head * head_stride_rows + row_begin + r;
-    const uint4* in = reinterpret_cast<const uint4*>(src + row * kHeadDim + j * 32);
+    const uint4* in = reinterpret_cast<const uint4*>(src + row * D + j * 32);
     uint4 raw[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) raw[i] = in[i];
@@ -154,13 +161,13 @@ __global__ __launch_bounds__(256) void encode_rows_kernel(const uint16_t* __rest
           }
         }
       }
-      // index bits 5 and 6: across the quad
+      // index bits 5 and up: across the lanes of the group
 #pragma unroll
-      for (int s = 0; s < 2; ++s) {
+      for (int s = 0; (1 << s) < LPV; ++s) {
         const bool upper = ((j >> s) & 1) != 0;
 #pragma unroll
         for (int i = 0; i < 32; ++i) {
-          const double partner = dpp_quad_xor_f64(x[i], s == 1);
+          const double partner = s < 2 ? dpp_quad_xor_f64(x[i], s == 1) : __shfl_xor(x[i], 4, kWave);
           x[i] = upper ? partner - x[i] : x[i] + partner;
         }
       }
@@ -177,7 +184,7 @@ __global__ __launch_bounds__(256) void encode_rows_kernel(const uint16_t* __rest
       for (int i = 0; i < T; ++i) m[i] = push_greater(m[i], x[e], thr.tau[i]);
     }
     planes_from_masks<BITS>(m, plane);
-    uint32_t* out = reinterpret_cast<uint32_t*>(dst + row * (16 * BITS) + j * (4 * BITS));
+    uint32_t* out = reinterpret_cast<uint32_t*>(dst + row * (LPV * 4 * BITS) + j * (4 * BITS));
     if constexpr (BITS == 2) {
       *reinterpret_cast<uint2*>(out) = make_uint2(plane[0], plane[1]);
     } else {

@@ -24,7 +24,7 @@ struct FullAttnParams {
   const uint16_t* V;
   const int64_t* seq_start;  // [B]
   const int32_t* seq_len;    // [B]
-  float* partial;            // [B*Hq][n_splits][kPartialStride]
+  float* partial;            // [B*Hq][n_splits][kPartial]
   int64_t pool_tokens, max_seq_len;
   int32_t Hq, Hkv, n_splits, chunk;  // chunk = tokens per split
   float scale_log2e;
@@ -33,25 +33,27 @@ struct FullAttnParams {
 // Grid (n_splits, Hkv, B).  16 lanes per row (8 dims each), 16 rows per pass
 // per workgroup, U passes in flight.  A split without tokens leaves an empty
 // partial (l = 0), so the merge needs no knowledge of the lengths.
-template <int G>
+template <int G, int D>
 __global__ __launch_bounds__(kFullThreads) void full_attn_kernel(const FullAttnParams p) {
 #pragma clang fp contract(off)  // a scaled score is rounded once and feeds both max and exponent
-  constexpr int kGroups = kFullThreads / 16;
-  __shared__ AttnShared<kFullThreads> sh;
+  constexpr int LPR = D / 8;  // lanes per row
+  constexpr int kGroups = kFullThreads / LPR;
+  constexpr int kPartial = partial_stride(D);
+  __shared__ AttnShared<kFullThreads, D> sh;
   const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
-  const int tid = threadIdx.x, grp = tid >> 4, gl = tid & 15;
+  const int tid = threadIdx.x, grp = tid / LPR, gl = tid % LPR;
   const int head0 = b * p.Hq + kvh * G;
 
   float qf[G][8];
 #pragma unroll
   for (int g = 0; g < G; ++g) {
-    const uint4 qv = *reinterpret_cast<const uint4*>(p.q + (int64_t)(head0 + g) * kHeadDim + gl * 8);
+    const uint4 qv = *reinterpret_cast<const uint4*>(p.q + (int64_t)(head0 + g) * D + gl * 8);
     qf[g][0] = bf16_lo(qv.x); qf[g][1] = bf16_hi(qv.x); qf[g][2] = bf16_lo(qv.y); qf[g][3] = bf16_hi(qv.y);
     qf[g][4] = bf16_lo(qv.z); qf[g][5] = bf16_hi(qv.z); qf[g][6] = bf16_lo(qv.w); qf[g][7] = bf16_hi(qv.w);
   }
   const int L = safe_seq_len(p.seq_len, p.seq_start, b, p.max_seq_len, p.pool_tokens);
   const int t_begin = split * p.chunk, t_end = min(L, t_begin + p.chunk);
-  const int64_t row0 = ((int64_t)kvh * p.pool_tokens + (L > 0 ? p.seq_start[b] : 0)) * kHeadDim;
+  const int64_t row0 = ((int64_t)kvh * p.pool_tokens + (L > 0 ? p.seq_start[b] : 0)) * D;
   const uint16_t* Kp = p.K + row0;
   const uint16_t* Vp = p.V + row0;
 
@@ -73,7 +75,7 @@ __global__ __launch_bounds__(kFullThreads) void full_attn_kernel(const FullAttnP
       const int t = t0 + u * kGroups;
       ok[u] = t < t_end;
       // unconditional, clamped: all loads of the pass are in flight together
-      const int64_t off = (int64_t)min(t, t_end - 1) * kHeadDim + gl * 8;
+      const int64_t off = (int64_t)min(t, t_end - 1) * D + gl * 8;
       kv[u] = *reinterpret_cast<const uint4*>(Kp + off);
       vv[u] = *reinterpret_cast<const uint4*>(Vp + off);
     }
@@ -94,7 +96,7 @@ __global__ __launch_bounds__(kFullThreads) void full_attn_kernel(const FullAttnP
         float s = qf[g][0] * kf[u][0];
 #pragma unroll
         for (int j = 1; j < 8; ++j) s = fmaf(qf[g][j], kf[u][j], s);
-        s = row16_sum_f32(s) * p.scale_log2e;
+        s = lanes_sum_f32<LPR>(s) * p.scale_log2e;
         sc[u] = ok[u] ? s : kNegBig;
         mn = fmaxf(mn, sc[u]);
       }
@@ -123,7 +125,7 @@ __global__ __launch_bounds__(kFullThreads) void full_attn_kernel(const FullAttnP
 #pragma unroll
     for (int j = 0; j < 8; ++j) sh.acc[grp][gl * 8 + j] = acc[g][j];
     __syncthreads();
-    if (tid < kHeadDim) {
+    if (tid < D) {
       float M = kNegBig, lsum = 0.f, o = 0.f;
       for (int r = 0; r < kGroups; ++r) M = fmaxf(M, sh.m[r]);
       for (int r = 0; r < kGroups; ++r) {
@@ -131,7 +133,7 @@ __global__ __launch_bounds__(kFullThreads) void full_attn_kernel(const FullAttnP
         lsum = fmaf(sh.l[r], w, lsum);
         o = fmaf(sh.acc[r][tid], w, o);
       }
-      float* mine = p.partial + ((int64_t)(head0 + g) * p.n_splits + split) * kPartialStride;
+      float* mine = p.partial + ((int64_t)(head0 + g) * p.n_splits + split) * kPartial;
       if (tid == 0) {
         mine[0] = M;
         mine[1] = lsum;
@@ -143,17 +145,19 @@ __global__ __launch_bounds__(kFullThreads) void full_attn_kernel(const FullAttnP
 }
 
 // Merges the n_parts partials of one head, in part order, into out.  Grid (Hq, B).
-__global__ __launch_bounds__(kHeadDim) void merge_parts_kernel(const float* __restrict__ partial,
-                                                               float* __restrict__ out, int Hq,
-                                                               int n_parts) {
+template <int D>
+__global__ __launch_bounds__(D) void merge_parts_kernel(const float* __restrict__ partial,
+                                                        float* __restrict__ out, int Hq,
+                                                        int n_parts) {
+  constexpr int kPartial = partial_stride(D);
   const int64_t head = (int64_t)blockIdx.y * Hq + blockIdx.x;
   const int tid = threadIdx.x;
-  const float* ph = partial + head * n_parts * kPartialStride;
+  const float* ph = partial + head * n_parts * kPartial;
   float M = kNegBig;
   for (int s0 = 0; s0 < n_parts; s0 += 8) {
     float pm[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) pm[u] = ph[(int64_t)min(s0 + u, n_parts - 1) * kPartialStride];
+    for (int u = 0; u < 8; ++u) pm[u] = ph[(int64_t)min(s0 + u, n_parts - 1) * kPartial];
 #pragma unroll
     for (int u = 0; u < 8; ++u) M = fmaxf(M, pm[u]);
   }
@@ -162,7 +166,7 @@ __global__ __launch_bounds__(kHeadDim) void merge_parts_kernel(const float* __re
     float pm[8], pl[8], po[8];
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
-      const float* ps = ph + (int64_t)min(s0 + u, n_parts - 1) * kPartialStride;
+      const float* ps = ph + (int64_t)min(s0 + u, n_parts - 1) * kPartial;
       pm[u] = ps[0];
       pl[u] = ps[1];
       po[u] = ps[4 + tid];
@@ -175,7 +179,7 @@ __global__ __launch_bounds__(kHeadDim) void merge_parts_kernel(const float* __re
       o = fmaf(use ? po[u] : 0.f, w, o);
     }
   }
-  out[head * kHeadDim + tid] = lsum > 0.f ? o / lsum : 0.f;
+  out[head * D + tid] = lsum > 0.f ? o / lsum : 0.f;
 }
 
 }  // namespace adamas

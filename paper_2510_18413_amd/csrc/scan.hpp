@@ -1,6 +1,6 @@
-// Manhattan-distance scan over the packed code plane (Algorithm 1 line 5,
-// Eq. 6), with the query encode (lines 1-3) and the cache append (line 4)
-// fused into its prologue for the decode step.
+// Manhattan-distance scan over the packed code plane (Algorithm 1, distance
+// step, Eq. 6), with the query encode and the cache append of the same
+// algorithm fused into its prologue for the decode step.
 //
 // One workgroup owns one tile of blockDim.x * 4 consecutive tokens of one
 // (sequence, KV head) and evaluates all G query heads of that KV head's
@@ -58,15 +58,18 @@ struct ScanParams {
 };
 
 // WAVES = wavefronts per workgroup (4, 8 or 16): the tile is WAVES * 256 tokens.
-template <int G, bool FUSED, int WAVES, int METRIC, bool PAGED>
+// D = head dimension: W = D / 32 words per code row.
+template <int G, bool FUSED, int WAVES, int METRIC, bool PAGED, int D>
 __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p) {
   static_assert(FUSED || !PAGED, "the paged layout is served by the fused step only");
-  constexpr int kNumBins = Dist<METRIC>::kBins, kHistStride = Dist<METRIC>::kStride;
-  constexpr int BITS = Dist<METRIC>::kBits, kRowBytes = Dist<METRIC>::kRowBytes;
-  constexpr int kRowWords = 4 * BITS;  // 32-bit words per code row
+  using Fmt = Dist<METRIC, D>;
+  constexpr int kNumBins = Fmt::kBins, kHistStride = Fmt::kStride;
+  constexpr int BITS = Fmt::kBits, kRowBytes = Fmt::kRowBytes, W = Fmt::kWords;
+  constexpr int kRowWords = W * BITS;  // 32-bit words per code row
+  constexpr int E = D / 64;            // elements per lane when a wave encodes one vector
   __shared__ uint32_t s_hist[G][kHistReplicas][kNumBins];
-  // per query head: plane p of word wd at [4p + wd]; 2-bit codes also keep lo^hi at [8 + wd]
-  __shared__ uint32_t s_q[G][12];
+  // per query head: plane p of word wd at [W * p + wd]; 2-bit codes also keep lo^hi at [2W + wd]
+  __shared__ uint32_t s_q[G][3 * W];
   __shared__ uint32_t s_new[kRowWords];  // code row of the appended key, as stored
   __shared__ uint32_t s_ready;      // query / new-key code rows published so far
   // per wave: its 256 distances per query head, in token order, for wide stores
@@ -89,16 +92,17 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
   // unit requests are served in order across waves, so a needless load here
   // would sit in front of other waves' rows.
   constexpr int kEncRounds = (G + 1 + WAVES - 1) / WAVES;  // G queries + 1 new key over the waves
-  uint32_t enc_lo[kEncRounds], enc_hi[kEncRounds];
+  uint32_t enc[kEncRounds][E];
 #pragma unroll
   for (int r = 0; r < kEncRounds; ++r) {
     const int v = wave + r * WAVES;
-    enc_lo[r] = enc_hi[r] = 0;
+#pragma unroll
+    for (int e = 0; e < E; ++e) enc[r][e] = 0;
     if (FUSED && (v < G || (v == G && p.k_new != nullptr))) {
-      const uint16_t* src = v < G ? p.q + (int64_t)(head0 + v) * kHeadDim
-                                  : p.k_new + ((int64_t)b * p.Hkv + kvh) * kHeadDim;
-      enc_lo[r] = src[lane];
-      enc_hi[r] = src[lane + 64];
+      const uint16_t* src = v < G ? p.q + (int64_t)(head0 + v) * D
+                                  : p.k_new + ((int64_t)b * p.Hkv + kvh) * D;
+#pragma unroll
+      for (int e = 0; e < E; ++e) enc[r][e] = src[lane + 64 * e];
     }
   }
 
@@ -140,15 +144,16 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
 #pragma unroll
   for (int pl = 0; pl < BITS; ++pl) qraw[pl] = 0;
   if (!FUSED && wave == 0) {
-    const int i = min(tid, G * 4 - 1);
+    const int i = min(tid, G * W - 1);
     const uint32_t* qc =
-        reinterpret_cast<const uint32_t*>(p.qcodes + (int64_t)(head0 + (i >> 2)) * kRowBytes);
+        reinterpret_cast<const uint32_t*>(p.qcodes + (int64_t)(head0 + i / W) * kRowBytes);
 #pragma unroll
-    for (int pl = 0; pl < BITS; ++pl) qraw[pl] = qc[BITS * (i & 3) + pl];
+    for (int pl = 0; pl < BITS; ++pl) qraw[pl] = qc[BITS * (i % W) + pl];
   }
 
   const uint8_t* plane = p.codes + ((int64_t)kvh * p.pool_tokens + start) * kRowBytes;
-  uint4 rr[kScanTokPerThread][BITS];  // 16 * BITS bytes per row
+  constexpr int C = kRowBytes / 16;  // 16-byte pieces of a row
+  uint4 rr[kScanTokPerThread][C];
 #pragma unroll
   for (int i = 0; i < kScanTokPerThread; ++i) {
     // Unconditional: a lane past the end re-reads the last row (masked at use).
@@ -164,13 +169,16 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
     }
     const uint4* row = reinterpret_cast<const uint4*>(plane + r * kRowBytes);
 #pragma unroll
-    for (int c = 0; c < BITS; ++c) rr[i][c] = row[c];
+    for (int c = 0; c < C; ++c) rr[i][c] = row[c];
   }
 
   // Nothing above may be consumed before the row loads have been issued.
   if (FUSED) {
 #pragma unroll
-    for (int r = 0; r < kEncRounds; ++r) asm volatile("" : "+v"(enc_lo[r]), "+v"(enc_hi[r]));
+    for (int r = 0; r < kEncRounds; ++r) {
+#pragma unroll
+      for (int e = 0; e < E; ++e) asm volatile("" : "+v"(enc[r][e]));
+    }
   } else {
 #pragma unroll
     for (int pl = 0; pl < BITS; ++pl) asm volatile("" : "+v"(qraw[pl]));
@@ -181,20 +189,18 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
     for (int r = 0; r < kEncRounds; ++r) {
       const int v = wave + r * WAVES;
       if (v < n_enc) {
-        uint32_t w[BITS][4];
-        encode_values_wave<BITS>(enc_lo[r], enc_hi[r], v < G ? p.thr_q : p.thr_k, w);
-        if (lane < 4) {  // lane wd publishes word wd
+        uint32_t w[BITS][W];
+        encode_values_wave<BITS, D>(enc[r], v < G ? p.thr_q : p.thr_k, w);
+        // lane wd publishes word wd (every lane holds the whole row)
 #pragma unroll
-          for (int pl = 0; pl < BITS; ++pl) {
-            const uint32_t x = lane == 0 ? w[pl][0] : lane == 1 ? w[pl][1] : lane == 2 ? w[pl][2] : w[pl][3];
-            if (v < G) s_q[v][4 * pl + lane] = x;
-            else s_new[BITS * lane + pl] = x;  // code row of the appended key
-          }
-          if (BITS == 2 && v < G) {
-            const uint32_t lo = lane == 0 ? w[0][0] : lane == 1 ? w[0][1] : lane == 2 ? w[0][2] : w[0][3];
-            const uint32_t hi = lane == 0 ? w[BITS - 1][0] : lane == 1 ? w[BITS - 1][1]
-                              : lane == 2 ? w[BITS - 1][2] : w[BITS - 1][3];
-            s_q[v][8 + lane] = lo ^ hi;
+        for (int wd = 0; wd < W; ++wd) {
+          if (lane == wd) {
+#pragma unroll
+            for (int pl = 0; pl < BITS; ++pl) {
+              if (v < G) s_q[v][W * pl + wd] = w[pl][wd];
+              else s_new[BITS * wd + pl] = w[pl][wd];  // code row of the appended key
+            }
+            if (BITS == 2 && v < G) s_q[v][2 * W + wd] = w[0][wd] ^ w[BITS - 1][wd];
           }
         }
         if (lane == 0)
@@ -202,11 +208,11 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
       }
     }
   } else if (wave == 0) {
-    if (tid < G * 4) {
-      const int g = tid >> 2, wd = tid & 3;
+    if (tid < G * W) {
+      const int g = tid / W, wd = tid % W;
 #pragma unroll
-      for (int pl = 0; pl < BITS; ++pl) s_q[g][4 * pl + wd] = qraw[pl];
-      if (BITS == 2) s_q[g][8 + wd] = qraw[0] ^ qraw[BITS - 1];
+      for (int pl = 0; pl < BITS; ++pl) s_q[g][W * pl + wd] = qraw[pl];
+      if (BITS == 2) s_q[g][2 * W + wd] = qraw[0] ^ qraw[BITS - 1];
     }
     if (lane == 0)
       __hip_atomic_fetch_add(&s_ready, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
@@ -229,15 +235,15 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
   // within the register budget of a 1024-thread workgroup.
   // qp[g][j][wd]: plane j of word wd; for 2-bit codes j = 2 is lo ^ hi.
   constexpr int QP = BITS == 2 ? 3 : BITS;
-  uint32_t qp[G][QP][4];
+  uint32_t qp[G][QP][W];
 #pragma unroll
   for (int g = 0; g < G; ++g) {
 #pragma unroll
     for (int j = 0; j < QP; ++j) {
 #pragma unroll
-      for (int wd = 0; wd < 4; ++wd) {
-        if constexpr (G <= 2 || (G <= 4 && BITS < 3)) qp[g][j][wd] = s_q[g][4 * j + wd];
-        else qp[g][j][wd] = __builtin_amdgcn_readfirstlane(s_q[g][4 * j + wd]);
+      for (int wd = 0; wd < W; ++wd) {
+        if constexpr (G * QP * W <= 24 || (G * QP * W <= 48 && BITS < 3)) qp[g][j][wd] = s_q[g][W * j + wd];
+        else qp[g][j][wd] = __builtin_amdgcn_readfirstlane(s_q[g][W * j + wd]);
       }
     }
   }
@@ -251,7 +257,7 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
     // kw[BITS * wd + pl]: plane pl of word wd of the key row
     uint32_t kw[kRowWords];
 #pragma unroll
-    for (int c = 0; c < BITS; ++c) {
+    for (int c = 0; c < C; ++c) {
       kw[4 * c] = rr[i][c].x;
       kw[4 * c + 1] = rr[i][c].y;
       kw[4 * c + 2] = rr[i][c].z;
@@ -267,7 +273,7 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
       if constexpr (BITS == 2) {
         uint32_t c1 = 0, c2 = 0, c3 = 0;
 #pragma unroll
-        for (int wd = 0; wd < 4; ++wd) {
+        for (int wd = 0; wd < W; ++wd) {
           const uint32_t xl = kw[2 * wd] ^ qp[g][0][wd], xh = kw[2 * wd + 1] ^ qp[g][1][wd];
           const uint32_t u = xh & ~(xl & qp[g][2][wd]);
           c1 += __popc(xl);
@@ -278,13 +284,13 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
       } else if constexpr (BITS == 1) {
         d = 0;
 #pragma unroll
-        for (int wd = 0; wd < 4; ++wd) d += __popc(kw[wd] ^ qp[g][0][wd]);
+        for (int wd = 0; wd < W; ++wd) d += __popc(kw[wd] ^ qp[g][0][wd]);
       } else {
         // |a - b| of 3-bit codes on bit planes (a query, b key): subtract with
         // borrow, then negate where the borrow out (a < b) is set.
         uint32_t c0 = 0, c1 = 0, c2 = 0;
 #pragma unroll
-        for (int wd = 0; wd < 4; ++wd) {
+        for (int wd = 0; wd < W; ++wd) {
           const uint32_t a0 = qp[g][0][wd], a1 = qp[g][1][wd], a2 = qp[g][2][wd];
           const uint32_t b0 = kw[3 * wd], b1 = kw[3 * wd + 1], b2 = kw[3 * wd + 2];
           const uint32_t d0 = a0 ^ b0, br1 = ~a0 & b0;
@@ -328,11 +334,11 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
     }
   }
 
-  // Alg. 1 line 4: the new token's K, V and code row enter the cache.  The
+  // Algorithm 1, cache update: the new token's K, V and code row enter the cache.  The
   // scan above already used the new code row (from LDS); the stores come last
   // so that no other memory operation sits between the row loads and their use.
   if (appending && wave == 0 && gsub == 0) {
-    const int64_t src = ((int64_t)b * p.Hkv + kvh) * kHeadDim;
+    const int64_t src = ((int64_t)b * p.Hkv + kvh) * D;
     int64_t row = (int64_t)kvh * p.pool_tokens + start + (L - 1);
     if constexpr (PAGED) {
       const int64_t pg = min(max((int64_t)p.page_table[(int64_t)b * p.max_pages + ((L - 1) >> p.page_shift)],
@@ -340,10 +346,11 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
       row = (int64_t)kvh * p.pool_tokens + (pg << p.page_shift) + ((L - 1) & ((1 << p.page_shift) - 1));
     }
     if (lane < kRowWords) reinterpret_cast<uint32_t*>(p.codes_w + row * kRowBytes)[lane] = s_new[lane];
-    reinterpret_cast<uint32_t*>(p.K + row * kHeadDim)[lane] =
-        reinterpret_cast<const uint32_t*>(p.k_new + src)[lane];
-    reinterpret_cast<uint32_t*>(p.V + row * kHeadDim)[lane] =
-        reinterpret_cast<const uint32_t*>(p.v_new + src)[lane];
+#pragma unroll
+    for (int c = lane; c < D / 2; c += kWave) {  // D bf16 values = D / 2 dwords per row
+      reinterpret_cast<uint32_t*>(p.K + row * D)[c] = reinterpret_cast<const uint32_t*>(p.k_new + src)[c];
+      reinterpret_cast<uint32_t*>(p.V + row * D)[c] = reinterpret_cast<const uint32_t*>(p.v_new + src)[c];
+    }
   }
   // The select kernel counts its finished segments per head from zero.
   if (p.arrivals != nullptr && tile_id == 0 && tid < G)

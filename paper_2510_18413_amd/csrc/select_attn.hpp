@@ -1,5 +1,6 @@
-// Top-k selection from the scan's distances and tile histograms (Algorithm 1
-// line 6) and softmax attention over the selected rows (lines 7-8, Eq. 1).
+// Top-k selection from the scan's distances and tile histograms (Algorithm 1,
+// top-k step) and softmax attention over the selected rows (its gather and
+// attention steps, Eq. 1).
 //
 // Selection without sorting.  Distances take few values (385 for Eq. 6, 1153
 // for the squared-difference variant), so the k-th smallest
@@ -45,7 +46,7 @@ struct SelectParams {
   const uint16_t* K;          // pools
   const uint16_t* V;
   float* out;                 // [B*Hq][128]
-  float* partial;             // [B*Hq][kMaxParts][kPartialStride]
+  float* partial;             // [B*Hq][kMaxParts][partial_stride(D)]
   uint32_t* arrivals;         // per-head counter of finished segments, zero on entry; null: no in-kernel merge
   int64_t arrivals_stride;
   int64_t pool_tokens, max_seq_len;
@@ -78,12 +79,12 @@ __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* s_wave
   return before + incl - v;
 }
 
-template <int THREADS>
+template <int THREADS, int D = kHeadDim>
 struct AttnShared {
-  static constexpr int kGroups = THREADS / 16;
+  static constexpr int kGroups = THREADS / (D / 8);
   float m[kGroups];
   float l[kGroups];
-  float acc[kGroups][kHeadDim];
+  float acc[kGroups][D];
 };
 
 // Softmax attention (Eq. 1) of one query over the n rows listed in s_sel (token
@@ -94,20 +95,21 @@ struct AttnShared {
 // maximum), lsum (sum of weights) and o (unnormalised weighted sum of V).
 // Entries of s_sel are clamped to [0, n_tokens) before use (n_tokens >= 1 when n > 0).
 // All threads must call it.
-template <int THREADS>
+template <int THREADS, int D>
 __device__ __forceinline__ void attention_rows(const int32_t* s_sel, int n, int n_tokens,
                                                const uint16_t* __restrict__ q,
                                                const uint16_t* __restrict__ Kp,
                                                const uint16_t* __restrict__ Vp, float scale_log2e,
-                                               AttnShared<THREADS>& sh, float& M, float& lsum,
+                                               AttnShared<THREADS, D>& sh, float& M, float& lsum,
                                                float& o) {
   // No implicit FMA contraction here: a scaled score must be rounded once, and
   // that one value must feed both the running maximum and the exponent, or rows
   // with equal scores would not get equal weights.  The dot products use
   // explicit fmaf and stay fused.
 #pragma clang fp contract(off)
-  constexpr int kGroups = THREADS / 16;
-  const int tid = threadIdx.x, grp = tid >> 4, gl = tid & 15;
+  constexpr int LPR = D / 8;  // lanes per row: 8 dims each
+  constexpr int kGroups = THREADS / LPR;
+  const int tid = threadIdx.x, grp = tid / LPR, gl = tid % LPR;
 
   float qf[8];
   {
@@ -130,7 +132,7 @@ __device__ __forceinline__ void attention_rows(const int32_t* s_sel, int n, int 
       if (ok[u]) {
         // clamped: whatever the list holds, the gather stays inside the sequence
         const int tok = min(max(s_sel[i], 0), n_tokens - 1);
-        const int64_t off = (int64_t)tok * kHeadDim + gl * 8;
+        const int64_t off = (int64_t)tok * D + gl * 8;
         kv[u] = *reinterpret_cast<const uint4*>(Kp + off);
         vv[u] = *reinterpret_cast<const uint4*>(Vp + off);
       } else {
@@ -150,8 +152,8 @@ __device__ __forceinline__ void attention_rows(const int32_t* s_sel, int n, int 
       s = fmaf(qf[5], bf16_hi(kv[u].z), s);
       s = fmaf(qf[6], bf16_lo(kv[u].w), s);
       s = fmaf(qf[7], bf16_hi(kv[u].w), s);
-      // the group's 16 lanes are one DPP row
-      s = row16_sum_f32(s) * scale_log2e;
+      // the row's D / 8 lanes are an aligned group of 8, 16 or 32 lanes
+      s = lanes_sum_f32<LPR>(s) * scale_log2e;
       sc[u] = ok[u] ? s : kNegBig;
       mn = fmaxf(mn, sc[u]);
     }
@@ -187,7 +189,7 @@ __device__ __forceinline__ void attention_rows(const int32_t* s_sel, int n, int 
   M = kNegBig;
   lsum = 0.f;
   o = 0.f;
-  if (tid < kHeadDim) {
+  if (tid < D) {
     for (int g = 0; g < kGroups; ++g) M = fmaxf(M, sh.m[g]);
     for (int g = 0; g < kGroups; ++g) {
       const float w = exp2f(sh.m[g] - M);
@@ -201,10 +203,12 @@ __device__ __forceinline__ void attention_rows(const int32_t* s_sel, int n, int 
 // tokens is finished by that workgroup; otherwise each workgroup leaves an
 // (M, lsum, o[128]) partial, merged by the last one to arrive (p.arrivals set)
 // or by merge_kernel (p.arrivals null).
-template <int THREADS, bool ATTN, int METRIC, bool PAGED>
+template <int THREADS, bool ATTN, int METRIC, bool PAGED, int D>
 __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
   static_assert(ATTN || !PAGED, "only the gather needs the page table");
-  constexpr int kNumBins = Dist<METRIC>::kBins, kHistStride = Dist<METRIC>::kStride;
+  static_assert(THREADS >= D, "one thread per output dimension in the merge");
+  constexpr int kNumBins = Dist<METRIC, D>::kBins, kHistStride = Dist<METRIC, D>::kStride;
+  constexpr int kPartial = partial_stride(D);
   constexpr int kHistPairs = kHistStride / 2;                      // pairs of uint16 bins per stored row
   constexpr int PP = (kHistPairs + THREADS - 1) / THREADS;         // pairs owned by one thread
   constexpr int BPL = (kNumBins + kWave - 1) / kWave;              // bins per lane in the threshold search
@@ -215,7 +219,7 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
   __shared__ int32_t s_T, s_cntlt;
   __shared__ uint32_t s_ltb, s_eqb;
   __shared__ int32_t s_sel[ATTN ? kMaxK : 1];
-  __shared__ AttnShared<ATTN ? THREADS : 16> s_attn;
+  __shared__ AttnShared<ATTN ? THREADS : D / 8, D> s_attn;
 
   const int seg = blockIdx.x, hq = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63;
@@ -444,17 +448,17 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
     const int n_sel = min((int)(run_lt + min(run_eq, (uint32_t)r) - seg_pos0), kk);
     __syncthreads();  // s_sel complete
     const int kvh = hq / (p.Hq / p.Hkv);
-    const int64_t row0 = ((int64_t)kvh * p.pool_tokens + (PAGED ? 0 : p.seq_start[b])) * kHeadDim;
+    const int64_t row0 = ((int64_t)kvh * p.pool_tokens + (PAGED ? 0 : p.seq_start[b])) * D;
     float M, lsum, o;
-    attention_rows<THREADS>(s_sel, n_sel, PAGED ? (int)p.pool_tokens : L, p.q + head * kHeadDim,
+    attention_rows<THREADS, D>(s_sel, n_sel, PAGED ? (int)p.pool_tokens : L, p.q + head * D,
                             p.K + row0, p.V + row0, p.scale_log2e, s_attn, M, lsum, o);
     if (gridDim.x == 1 || (p.arrivals != nullptr && n_active == 1)) {
-      if (tid < kHeadDim) p.out[head * kHeadDim + tid] = lsum > 0.f ? o / lsum : 0.f;
+      if (tid < D) p.out[head * D + tid] = lsum > 0.f ? o / lsum : 0.f;
       return;
     }
-    float* mine = p.partial + (head * kMaxParts + seg) * kPartialStride;
+    float* mine = p.partial + (head * kMaxParts + seg) * kPartial;
     if (p.arrivals == nullptr) {
-      if (tid < kHeadDim) {
+      if (tid < D) {
         if (tid == 0) {
           mine[0] = M;
           mine[1] = lsum;
@@ -469,7 +473,7 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
     // workgroup's stores have been acknowledged before it counts itself, and
     // that the merging workgroup loads after its fetch-add has returned.  The
     // arithmetic and its order are merge_kernel's: both give the same bits.
-    if (tid < kHeadDim) {
+    if (tid < D) {
       if (tid == 0) {
         __hip_atomic_store(mine + 0, M, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __hip_atomic_store(mine + 1, lsum, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -485,13 +489,13 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
       s_T = before + 1u == (uint32_t)n_active ? 1 : 0;
     }
     __syncthreads();
-    if (s_T == 0 || tid >= kHeadDim) return;
+    if (s_T == 0 || tid >= D) return;
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-    const float* ph = p.partial + head * kMaxParts * kPartialStride;
+    const float* ph = p.partial + head * kMaxParts * kPartial;
     float pm[kMaxParts], pl[kMaxParts], po[kMaxParts];
 #pragma unroll
     for (int s = 0; s < kMaxParts; ++s) {
-      const float* ps = ph + (int64_t)min(s, n_active - 1) * kPartialStride;
+      const float* ps = ph + (int64_t)min(s, n_active - 1) * kPartial;
       pm[s] = __hip_atomic_load(ps + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       pl[s] = __hip_atomic_load(ps + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       po[s] = __hip_atomic_load(ps + 4 + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -507,7 +511,7 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
       lh = fmaf(use ? pl[s] : 0.f, w, lh);
       oh = fmaf(use ? po[s] : 0.f, w, oh);
     }
-    p.out[head * kHeadDim + tid] = lh > 0.f ? oh / lh : 0.f;
+    p.out[head * D + tid] = lh > 0.f ? oh / lh : 0.f;
   }
 }
 
@@ -522,7 +526,7 @@ struct AttnParams {
   const int64_t* seq_start;
   const int32_t* idx;  // [B*Hq][k]
   float* out;
-  float* partial;      // [B*Hq][kMaxParts][kPartialStride]
+  float* partial;      // [B*Hq][kMaxParts][partial_stride(D)]
   int64_t pool_tokens;
   int32_t Hq, Hkv, k, n_parts, chunk;  // chunk = idx entries per workgroup
   float scale_log2e;
@@ -530,10 +534,12 @@ struct AttnParams {
 
 // Grid (n_parts, Hq, B): workgroup `part` attends over idx entries
 // [part*chunk, (part+1)*chunk) of its head.  n_parts == 1 writes out directly.
+template <int D>
 __global__ __launch_bounds__(kAttnThreads) void sparse_attn_kernel(const AttnParams p) {
+  constexpr int kPartial = partial_stride(D);
   __shared__ int32_t s_sel[kMaxK];
   __shared__ uint32_t s_scan[kAttnThreads / kWave];
-  __shared__ AttnShared<kAttnThreads> s_attn;
+  __shared__ AttnShared<kAttnThreads, D> s_attn;
   const int part = blockIdx.x, hq = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x;
   const int64_t head = (int64_t)b * p.Hq + hq;
@@ -554,16 +560,16 @@ __global__ __launch_bounds__(kAttnThreads) void sparse_attn_kernel(const AttnPar
   }
   __syncthreads();
   const int kvh = hq / (p.Hq / p.Hkv);
-  const int64_t row0 = ((int64_t)kvh * p.pool_tokens + start) * kHeadDim;
+  const int64_t row0 = ((int64_t)kvh * p.pool_tokens + start) * D;
   float M, lsum, o;
-  attention_rows<kAttnThreads>(s_sel, (int)n, (int)min((int64_t)0x7fffffff, p.pool_tokens - start),
-                               p.q + head * kHeadDim, p.K + row0, p.V + row0,
+  attention_rows<kAttnThreads, D>(s_sel, (int)n, (int)min((int64_t)0x7fffffff, p.pool_tokens - start),
+                               p.q + head * D, p.K + row0, p.V + row0,
                                p.scale_log2e, s_attn, M, lsum, o);
-  if (tid < kHeadDim) {
+  if (tid < D) {
     if (gridDim.x == 1) {
-      p.out[head * kHeadDim + tid] = lsum > 0.f ? o / lsum : 0.f;
+      p.out[head * D + tid] = lsum > 0.f ? o / lsum : 0.f;
     } else {
-      float* mine = p.partial + (head * kMaxParts + part) * kPartialStride;
+      float* mine = p.partial + (head * kMaxParts + part) * kPartial;
       if (tid == 0) {
         mine[0] = M;
         mine[1] = lsum;
@@ -578,7 +584,7 @@ __global__ __launch_bounds__(kAttnThreads) void sparse_attn_kernel(const AttnPar
 // tokens of the head's sequence (as select_kernel wrote them); seg_len == 0:
 // n_parts partials (as sparse_attn_kernel wrote them).
 struct MergeParams {
-  const float* partial;      // [B*Hq][kMaxParts][kPartialStride]
+  const float* partial;      // [B*Hq][kMaxParts][partial_stride(D)]
   float* out;                // [B*Hq][128]
   const int64_t* seq_start;
   const int32_t* seq_len;
@@ -586,17 +592,19 @@ struct MergeParams {
   int32_t Hq, n_parts, seg_len;
 };
 
-__global__ __launch_bounds__(kHeadDim) void merge_kernel(const MergeParams p) {
+template <int D>
+__global__ __launch_bounds__(D) void merge_kernel(const MergeParams p) {
+  constexpr int kPartial = partial_stride(D);
   const int hq = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
   const int64_t head = (int64_t)b * p.Hq + hq;
-  const float* ph = p.partial + head * kMaxParts * kPartialStride;
+  const float* ph = p.partial + head * kMaxParts * kPartial;
   // All kMaxParts slots exist in the workspace whatever n_parts is: load them
   // unconditionally (no branches, so every load is in flight at once) and mask
   // the unused ones afterwards.
   float pm[kMaxParts], pl[kMaxParts], po[kMaxParts];
 #pragma unroll
   for (int s = 0; s < kMaxParts; ++s) {
-    const float* ps = ph + (int64_t)s * kPartialStride;
+    const float* ps = ph + (int64_t)s * kPartial;
     pm[s] = ps[0];
     pl[s] = ps[1];
     po[s] = ps[4 + tid];
@@ -618,7 +626,7 @@ __global__ __launch_bounds__(kHeadDim) void merge_kernel(const MergeParams p) {
     lsum = fmaf(use ? pl[s] : 0.f, w, lsum);
     o = fmaf(use ? po[s] : 0.f, w, o);
   }
-  p.out[head * kHeadDim + tid] = lsum > 0.f ? o / lsum : 0.f;
+  p.out[head * D + tid] = lsum > 0.f ? o / lsum : 0.f;
 }
 
 }  // namespace adamas

@@ -29,8 +29,9 @@ class DeviceCase:
     def __init__(self, case, k, encode=True, variant=0, code_bits=0, thresholds=None):
         self.case, self.k = case, k
         self.thresholds = case.thresholds if thresholds is None else thresholds
+        self.head_dim = int(case.q.shape[-1])
         self.cfg = A.Config.make(case.Hq, case.Hkv, case.pool_tokens, thr_k=self.thresholds,
-                                 variant=variant, code_bits=code_bits)
+                                 variant=variant, code_bits=code_bits, head_dim=self.head_dim)
         self.q = dev_bf16(case.q)
         self.K = dev_bf16(case.K)
         self.V = dev_bf16(case.V)
@@ -45,7 +46,7 @@ class DeviceCase:
         assert nbytes > 0
         # poison the workspace: the library must not rely on its contents
         self.workspace = torch.full((nbytes,), 0xA5, dtype=torch.uint8, device="cuda")
-        self.out = torch.full((case.B, case.Hq, 128), float("nan"), device="cuda")
+        self.out = torch.full((case.B, case.Hq, self.head_dim), float("nan"), device="cuda")
         self.idx = torch.full((case.B, case.Hq, k), -7, dtype=torch.int32, device="cuda")
         if encode:
             A.adamas_encode_keys(self.cfg, self.K, self.codes, 0, case.pool_tokens)
@@ -65,18 +66,21 @@ def oracle_step(case, k, want_dist=True, variant=0):
     hadamard = not (variant & A.VARIANT_NO_HADAMARD)
     squared = bool(variant & A.VARIANT_L2)
     K, V = case.K.copy(), case.V.copy()
-    _, rows = oracle.encode(K, case.thresholds, hadamard=hadamard)
-    out, idx, dist = oracle.decode_step(case.q, K, V, rows, case.seq_start, case.seq_len, k,
-                                        case.thresholds, case.thresholds, SM_SCALE,
-                                        k_new=case.k_new, v_new=case.v_new, want_dist=want_dist,
-                                        hadamard=hadamard, squared=squared)
+    d = int(case.q.shape[-1])
+    with oracle.head_dim(d):
+        _, rows = oracle.encode(K, case.thresholds, hadamard=hadamard)
+        out, idx, dist = oracle.decode_step(case.q, K, V, rows, case.seq_start, case.seq_len, k,
+                                            case.thresholds, case.thresholds, 1.0 / np.sqrt(d),
+                                            k_new=case.k_new, v_new=case.v_new,
+                                            want_dist=want_dist, hadamard=hadamard,
+                                            squared=squared)
     return dict(out=out, idx=idx, dist=dist, K=K, V=V, rows=rows)
 
 
 def attn_rel_err(got: np.ndarray, ref: np.ndarray) -> float:
     """max_i |got_i - ref_i| / max(|ref_i|, 1e-3 * max_j |ref_j|), worst over (b, head)."""
-    got = got.reshape(-1, 128).astype(np.float64)
-    ref = ref.reshape(-1, 128).astype(np.float64)
+    got = got.reshape(-1, got.shape[-1]).astype(np.float64)
+    ref = ref.reshape(-1, ref.shape[-1]).astype(np.float64)
     worst = 0.0
     for g, r in zip(got, ref):
         floor = 1e-3 * np.abs(r).max()

@@ -21,11 +21,11 @@ def H():
     return gpu_harness
 
 
-def small_case(seed, B, Hq, Hkv, lens, append=False, needles=1):
+def small_case(seed, B, Hq, Hkv, lens, append=False, needles=1, head_dim=128):
     G = Hq // Hkv
     return synth.make_case("small", seed, B, Hq, Hkv, lens, [0],
                            lambda b, L, h, rng: rng.choice(L, (G, min(needles, L // G)), replace=False),
-                           append=append)
+                           append=append, head_dim=head_dim)
 
 
 # ----------------------------------------------------------------------------- encode
@@ -269,7 +269,7 @@ def test_decode_step_matches_oracle(H, oracle, B, Hq, Hkv, lens, k, append):
     for b in range(B):
         if case.seq_len[b] == 0:
             assert np.all(out[b] == 0) and np.all(idx[b] == -1)
-    if append:   # Alg. 1 line 4: cache rows and code rows of the new token, bit for bit
+    if append:   # Algorithm 1, cache update: cache rows and code rows of the new token, bit for bit
         assert np.array_equal(H.host_u16(d.K), ref["K"])
         assert np.array_equal(H.host_u16(d.V), ref["V"])
         assert np.array_equal(d.codes.cpu().numpy(), ref["rows"])
@@ -688,3 +688,189 @@ def test_decode_step_random_shapes(H, oracle):
         if append:
             assert np.array_equal(d.codes.cpu().numpy(), rows), tag
             assert np.array_equal(H.host_u16(d.K), K), tag
+
+
+# ------------------------------------------------------------- head dimensions 64 and 256
+
+@pytest.mark.parametrize("hd", [64, 256])
+def test_head_dim_encode_bit_exact(H, oracle, hd):
+    """Bulk key and query encode at d = 64 / 256: rows of d/4 bytes, bit for bit, including a
+    row range that leaves the rest of the plane untouched."""
+    import paper_2510_18413_amd as A
+    case = small_case(900 + hd, 2, 8, 4, [777, 1300], head_dim=hd)
+    d = H.DeviceCase(case, 16)
+    assert d.cfg.code_row_bytes == hd // 4
+    torch.cuda.synchronize()
+    with oracle.head_dim(hd):
+        _, rows = oracle.encode(case.K, case.thresholds)
+        _, qrows = oracle.encode(case.q, case.thresholds)
+    assert rows.shape[-1] == hd // 4
+    assert np.array_equal(d.codes.cpu().numpy(), rows)
+    qcodes = torch.zeros(case.B, case.Hq, hd // 4, dtype=torch.uint8, device="cuda")
+    A.adamas_encode_query(d.cfg, d.q, qcodes)
+    part = torch.full_like(d.codes, 0xEE)
+    A.adamas_encode_keys(d.cfg, d.K, part, 41, 333)
+    torch.cuda.synchronize()
+    assert np.array_equal(qcodes.cpu().numpy(), qrows)
+    got = part.cpu().numpy()
+    assert np.array_equal(got[:, 41:374], rows[:, 41:374])
+    assert np.all(got[:, :41] == 0xEE) and np.all(got[:, 374:] == 0xEE)
+
+
+@pytest.mark.parametrize("hd", [64, 256])
+def test_head_dim_values_on_thresholds(H, oracle, hd):
+    """Vectors whose transform lands exactly on a threshold (strict comparison of Eq. 5) and
+    all-zero vectors, at d = 64 / 256."""
+    import paper_2510_18413_amd as A
+    root = int(np.sqrt(hd))                       # 8 or 16: x = c * e_0 gives y_j = c / sqrt(d)
+    vals = np.array([-1.0, 0.0, 1.0, 2.0, -2.0, 0.5], dtype=np.float32) * root
+    K = np.zeros((1, len(vals) * 2, hd), dtype=np.float32)
+    K[0, :len(vals), 0] = vals                    # every coefficient equals vals / sqrt(d)
+    K[0, len(vals):, 3] = vals                    # signs follow column 3 of the Hadamard matrix
+    Kb = synth.f32_to_bf16_bits(K)
+    cfg = A.Config.make(1, 1, Kb.shape[1], head_dim=hd)
+    codes = torch.zeros(1, Kb.shape[1], hd // 4, dtype=torch.uint8, device="cuda")
+    A.adamas_encode_keys(cfg, H.dev_bf16(Kb), codes, 0, Kb.shape[1])
+    torch.cuda.synchronize()
+    with oracle.head_dim(hd):
+        vals_ref, rows = oracle.encode(Kb, synth.DEFAULT_THRESHOLDS)
+    assert np.array_equal(codes.cpu().numpy(), rows)
+    assert set(np.unique(vals_ref[0, :3])) == {0, 1, 2}     # -1 -> 0, 0 -> 1, 1 -> 2 (strict >)
+
+
+@pytest.mark.parametrize("hd,B,Hq,Hkv,lens,k", [
+    (64, 1, 1, 1, [1024], 64),
+    (64, 2, 8, 2, [4097, 333], 256),       # group 4
+    (64, 1, 8, 1, [9000], 100),            # group 8
+    (64, 3, 6, 2, [1, 64, 65], 8),         # group 3, tiny sequences
+    (256, 1, 1, 1, [1024], 64),
+    (256, 2, 8, 2, [4097, 333], 256),      # group 4 (the largest built at d = 256)
+    (256, 1, 6, 2, [9000], 100),           # group 3
+    (256, 1, 2, 2, [70000], 1024),
+])
+def test_head_dim_distance_and_topk_bit_exact(H, oracle, hd, B, Hq, Hkv, lens, k):
+    import paper_2510_18413_amd as A
+    case = small_case(920 + hd + Hq + B, B, Hq, Hkv, lens, head_dim=hd)
+    d = H.DeviceCase(case, k)
+    qcodes = torch.zeros(B, Hq, hd // 4, dtype=torch.uint8, device="cuda")
+    A.adamas_encode_query(d.cfg, d.q, qcodes)
+    dist = torch.full((B, Hq, d.max_len), 0xFFFF, dtype=torch.uint16, device="cuda")
+    A.adamas_manhattan_distance(d.cfg, qcodes, d.codes, d.seq_start, d.seq_len, dist)
+    dist2 = torch.full((B, Hq, d.max_len), 0xFFFF, dtype=torch.uint16, device="cuda")
+    A.adamas_select_topk(d.cfg, qcodes, d.codes, d.seq_start, d.seq_len, k, d.idx, d.max_len,
+                         d.workspace, dist_out=dist2)
+    torch.cuda.synchronize()
+    ref = H.oracle_step(case, k)
+    got, got2 = H.host_dist(dist), H.host_dist(dist2)
+    for b in range(B):
+        L = int(case.seq_len[b])
+        assert np.array_equal(got[b, :, :L], ref["dist"][b, :, :L])
+        assert np.array_equal(got2[b, :, :L], ref["dist"][b, :, :L])
+        assert np.all(got[b, :, L:] == 0xFFFF)
+    assert np.array_equal(d.idx.cpu().numpy(), ref["idx"])
+
+
+@pytest.mark.parametrize("hd", [64, 256])
+def test_head_dim_extreme_distances(H, oracle, hd):
+    """All codes 3 against all codes 0: the largest distance 3d must survive the 16-bit
+    distance, the histogram bins and the threshold search."""
+    import paper_2510_18413_amd as A
+    case = small_case(940 + hd, 1, 1, 1, [3000], head_dim=hd)
+    big = synth.f32_to_bf16_bits(np.full(hd, 64.0, np.float32))
+    # x = 64 * (1, ..., 1) transforms to (64 sqrt(d), 0, ..., 0): not all codes 3.  Use a vector
+    # whose transform is constant instead: 64 * sqrt(d) * e_0 -> every coefficient 64.
+    e0 = np.zeros(hd, np.float32)
+    e0[0] = 64.0 * np.sqrt(hd)
+    case.q[0, 0] = synth.f32_to_bf16_bits(e0)               # codes all 3
+    case.K[0, 1000:1200] = synth.f32_to_bf16_bits(-e0)      # codes all 0: distance 3d
+    case.K[0, 2000:2100] = synth.f32_to_bf16_bits(e0)       # distance 0
+    del big
+    k = 2950                                                # reaches into the 3d bin
+    d = H.DeviceCase(case, k)
+    qcodes = torch.zeros(1, 1, hd // 4, dtype=torch.uint8, device="cuda")
+    A.adamas_encode_query(d.cfg, d.q, qcodes)
+    dist = torch.zeros((1, 1, d.max_len), dtype=torch.uint16, device="cuda")
+    A.adamas_select_topk(d.cfg, qcodes, d.codes, d.seq_start, d.seq_len, k, d.idx, d.max_len,
+                         d.workspace, dist_out=dist)
+    torch.cuda.synchronize()
+    ref = H.oracle_step(case, k)
+    got = H.host_dist(dist)
+    assert got[0, 0, 1000:1200].min() == 3 * hd and got[0, 0, 2000:2100].max() == 0
+    assert np.array_equal(got[0, :, :3000], ref["dist"][0, :, :3000])
+    assert np.array_equal(d.idx.cpu().numpy(), ref["idx"])
+
+
+@pytest.mark.parametrize("hd,B,Hq,Hkv,lens,k,append", [
+    (64, 1, 1, 1, [1024], 64, False),
+    (64, 2, 8, 2, [4097, 333], 256, True),
+    (64, 4, 8, 1, [0, 1, 4096, 8193], 64, True),      # group 8, an empty sequence
+    (64, 3, 6, 2, [100, 64, 65], 128, False),          # k above every length
+    (64, 1, 2, 2, [70000], 1024, True),
+    (256, 1, 1, 1, [1024], 64, False),
+    (256, 2, 8, 2, [4097, 333], 256, True),
+    (256, 4, 4, 1, [0, 1, 4096, 8193], 64, True),
+    (256, 3, 6, 2, [100, 64, 65], 128, False),
+    (256, 1, 2, 2, [40000], 4096, True),
+])
+def test_head_dim_decode_step_matches_oracle(H, oracle, hd, B, Hq, Hkv, lens, k, append):
+    case = small_case(960 + hd + B + Hq, B, Hq, Hkv, lens, append=append, head_dim=hd)
+    d = H.DeviceCase(case, k)
+    out, idx = d.decode_step()
+    ref = H.oracle_step(case, k, want_dist=False)
+    assert out.shape[-1] == hd
+    assert np.array_equal(idx, ref["idx"])
+    assert H.attn_rel_err(out, ref["out"]) <= H.ATTN_TOL
+    for b in range(B):
+        if case.seq_len[b] == 0:
+            assert np.all(out[b] == 0) and np.all(idx[b] == -1)
+    if append:
+        assert np.array_equal(H.host_u16(d.K), ref["K"])
+        assert np.array_equal(H.host_u16(d.V), ref["V"])
+        assert np.array_equal(d.codes.cpu().numpy(), ref["rows"])
+
+
+@pytest.mark.parametrize("hd", [64, 256])
+def test_head_dim_staged_entry_points_and_full_attention(H, oracle, hd):
+    """select_topk -> sparse_attn (the stand-alone kernels) reproduce the fused step, and the
+    dense comparison kernel matches the oracle's full attention, at d = 64 / 256."""
+    import paper_2510_18413_amd as A
+    B, Hq, Hkv, lens, k = 2, 4, 2, [5000, 700], 96
+    case = small_case(980 + hd, B, Hq, Hkv, lens, head_dim=hd)
+    d = H.DeviceCase(case, k)
+    out, idx = d.decode_step()
+    qcodes = torch.zeros(B, Hq, hd // 4, dtype=torch.uint8, device="cuda")
+    A.adamas_encode_query(d.cfg, d.q, qcodes)
+    idx2 = torch.full_like(d.idx, -9)
+    A.adamas_select_topk(d.cfg, qcodes, d.codes, d.seq_start, d.seq_len, k, idx2, d.max_len,
+                         d.workspace)
+    out2 = torch.full_like(d.out, float("nan"))
+    A.adamas_sparse_attn(d.cfg, d.q, d.K, d.V, d.seq_start, idx2, out2, d.max_len, d.workspace)
+    torch.cuda.synchronize()
+    ref = H.oracle_step(case, k, want_dist=False)
+    assert np.array_equal(idx2.cpu().numpy(), ref["idx"]) and np.array_equal(idx, ref["idx"])
+    assert H.attn_rel_err(out2.cpu().numpy(), ref["out"]) <= H.ATTN_TOL
+    ws = torch.full((A.adamas_full_attn_workspace_bytes(d.cfg, B, d.max_len),), 0xA5,
+                    dtype=torch.uint8, device="cuda")
+    A.adamas_full_attn(d.cfg, d.q, d.K, d.V, d.seq_start, d.seq_len, d.out, d.max_len, ws)
+    torch.cuda.synchronize()
+    got = d.out.cpu().numpy()
+    full = np.zeros_like(got, dtype=np.float64)
+    with oracle.head_dim(hd):
+        for b in range(B):
+            s, L = int(case.seq_start[b]), int(case.seq_len[b])
+            for h in range(Hq):
+                full[b, h] = oracle.full_attention(case.q[b, h], case.K[h // 2, s:s + L],
+                                                   case.V[h // 2, s:s + L], 1.0 / np.sqrt(hd))
+    assert H.attn_rel_err(got, full) <= H.ATTN_TOL
+
+
+def test_head_dim_options_that_are_not_built_are_refused(H, oracle):
+    import paper_2510_18413_amd as A
+    for hd, kw, group in ((64, dict(variant=A.VARIANT_L2), 1), (256, dict(variant=A.VARIANT_L2), 1),
+                          (64, dict(code_bits=3, thr_k=tuple(range(7))), 1),
+                          (256, dict(code_bits=1, thr_k=(0.0,)), 1),
+                          (256, {}, 8), (32, {}, 1), (512, {}, 1)):
+        cfg = A.Config.make(group, 1, 1024, head_dim=hd, **kw)
+        assert A.adamas_workspace_bytes(cfg, 1, 1024, 16) == 0, (hd, kw, group)
+    assert A.adamas_workspace_bytes(A.Config.make(8, 1, 1024, head_dim=64), 1, 1024, 16) > 0
+    assert A.adamas_workspace_bytes(A.Config.make(4, 1, 1024, head_dim=256), 1, 1024, 16) > 0
