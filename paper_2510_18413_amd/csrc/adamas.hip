@@ -693,11 +693,11 @@ int adamas_full_attn(const adamas_config* cfg, const void* q, const void* K, con
   {
     const dim3 mgrid(cfg->num_q_heads, batch);
     if (cfg->head_dim == 64)
-      hipLaunchKernelGGL(merge_parts_kernel<64>, mgrid, dim3(64), 0, st, fp.partial, out, cfg->num_q_heads, pl.n_splits);
+      hipLaunchKernelGGL(merge_parts_kernel<64>, mgrid, dim3(kMergeThreads), 0, st, fp.partial, out, cfg->num_q_heads, pl.n_splits);
     else if (cfg->head_dim == 256)
-      hipLaunchKernelGGL(merge_parts_kernel<256>, mgrid, dim3(256), 0, st, fp.partial, out, cfg->num_q_heads, pl.n_splits);
+      hipLaunchKernelGGL(merge_parts_kernel<256>, mgrid, dim3(kMergeThreads), 0, st, fp.partial, out, cfg->num_q_heads, pl.n_splits);
     else
-      hipLaunchKernelGGL(merge_parts_kernel<128>, mgrid, dim3(128), 0, st, fp.partial, out, cfg->num_q_heads, pl.n_splits);
+      hipLaunchKernelGGL(merge_parts_kernel<128>, mgrid, dim3(kMergeThreads), 0, st, fp.partial, out, cfg->num_q_heads, pl.n_splits);
   }
   return launch_status();
 }

@@ -144,42 +144,67 @@ __global__ __launch_bounds__(kFullThreads) void full_attn_kernel(const FullAttnP
   }
 }
 
-// Merges the n_parts partials of one head, in part order, into out.  Grid (Hq, B).
+// Merges the n_parts partials of one head into out.  Grid (Hq, B), kMergeThreads
+// threads: the parts are cut into kMergeThreads / D contiguous slices, one
+// thread per (slice, output dimension) reduces its slice with eight loads in
+// flight, and the slices are combined through LDS.
+constexpr int kMergeThreads = 512;
+
 template <int D>
-__global__ __launch_bounds__(D) void merge_parts_kernel(const float* __restrict__ partial,
-                                                        float* __restrict__ out, int Hq,
-                                                        int n_parts) {
+__global__ __launch_bounds__(kMergeThreads) void merge_parts_kernel(const float* __restrict__ partial,
+                                                                    float* __restrict__ out, int Hq,
+                                                                    int n_parts) {
   constexpr int kPartial = partial_stride(D);
+  constexpr int S = kMergeThreads / D;  // slices
+  __shared__ float s_m[S], s_l[S], s_o[S][D];
   const int64_t head = (int64_t)blockIdx.y * Hq + blockIdx.x;
-  const int tid = threadIdx.x;
+  const int tid = threadIdx.x % D, slice = threadIdx.x / D;
   const float* ph = partial + head * n_parts * kPartial;
+  const int per = (n_parts + S - 1) / S;
+  const int begin = slice * per, end = min(n_parts, begin + per);  // may be empty
   float M = kNegBig;
-  for (int s0 = 0; s0 < n_parts; s0 += 8) {
+  for (int s0 = begin; s0 < end; s0 += 8) {
     float pm[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) pm[u] = ph[(int64_t)min(s0 + u, n_parts - 1) * kPartial];
+    for (int u = 0; u < 8; ++u) pm[u] = ph[(int64_t)min(s0 + u, end - 1) * kPartial];
 #pragma unroll
     for (int u = 0; u < 8; ++u) M = fmaxf(M, pm[u]);
   }
   float lsum = 0.f, o = 0.f;
-  for (int s0 = 0; s0 < n_parts; s0 += 8) {
+  for (int s0 = begin; s0 < end; s0 += 8) {
     float pm[8], pl[8], po[8];
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
-      const float* ps = ph + (int64_t)min(s0 + u, n_parts - 1) * kPartial;
+      const float* ps = ph + (int64_t)min(s0 + u, end - 1) * kPartial;
       pm[u] = ps[0];
       pl[u] = ps[1];
       po[u] = ps[4 + tid];
     }
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
-      const bool use = s0 + u < n_parts;
+      const bool use = s0 + u < end;
       const float w = use ? exp2f(pm[u] - M) : 0.f;
       lsum = fmaf(use ? pl[u] : 0.f, w, lsum);
       o = fmaf(use ? po[u] : 0.f, w, o);
     }
   }
-  out[head * D + tid] = lsum > 0.f ? o / lsum : 0.f;
+  if (tid == 0) {
+    s_m[slice] = M;
+    s_l[slice] = lsum;
+  }
+  s_o[slice][tid] = o;
+  __syncthreads();
+  if (slice != 0) return;
+  float Mh = kNegBig, lh = 0.f, oh = 0.f;
+#pragma unroll
+  for (int r = 0; r < S; ++r) Mh = fmaxf(Mh, s_m[r]);
+#pragma unroll
+  for (int r = 0; r < S; ++r) {
+    const float w = exp2f(s_m[r] - Mh);  // an empty slice holds l = 0, o = 0
+    lh = fmaf(s_l[r], w, lh);
+    oh = fmaf(s_o[r][tid], w, oh);
+  }
+  out[head * D + tid] = lh > 0.f ? oh / lh : 0.f;
 }
 
 }  // namespace adamas
