@@ -96,18 +96,26 @@ __device__ __forceinline__ void encode_values_wave(const uint32_t (&raw)[D / 64]
 // sums are fp64 and exact under the documented exponent spread, hence identical
 // to the wave-per-vector routine above whatever the order.
 
+// v of lane (l ^ 1) or (l ^ 2).  Every lane of a quad is a valid source, so the
+// move needs no previous value of its destination.
 __device__ __forceinline__ double dpp_quad_xor_f64(double v, bool xor2) {
   const uint64_t bits = __builtin_bit_cast(uint64_t, v);
   const int lo = (int)(uint32_t)bits, hi = (int)(uint32_t)(bits >> 32);
   int plo, phi;
   if (xor2) {
-    plo = __builtin_amdgcn_update_dpp(0, lo, kDppQuadXor2, 0xf, 0xf, false);
-    phi = __builtin_amdgcn_update_dpp(0, hi, kDppQuadXor2, 0xf, 0xf, false);
+    plo = __builtin_amdgcn_mov_dpp(lo, kDppQuadXor2, 0xf, 0xf, true);
+    phi = __builtin_amdgcn_mov_dpp(hi, kDppQuadXor2, 0xf, 0xf, true);
   } else {
-    plo = __builtin_amdgcn_update_dpp(0, lo, kDppQuadXor1, 0xf, 0xf, false);
-    phi = __builtin_amdgcn_update_dpp(0, hi, kDppQuadXor1, 0xf, 0xf, false);
+    plo = __builtin_amdgcn_mov_dpp(lo, kDppQuadXor1, 0xf, 0xf, true);
+    phi = __builtin_amdgcn_mov_dpp(hi, kDppQuadXor1, 0xf, 0xf, true);
   }
   return __builtin_bit_cast(double, ((uint64_t)(uint32_t)phi << 32) | (uint32_t)plo);
+}
+
+// v with its sign bit flipped where sign_flip is 0x80000000 (0: unchanged).
+__device__ __forceinline__ double flip_sign_f64(double v, uint32_t sign_flip) {
+  const uint64_t bits = __builtin_bit_cast(uint64_t, v);
+  return __builtin_bit_cast(double, bits ^ ((uint64_t)sign_flip << 32));
 }
 
 // Appends the sign bit of (tau - y) -- set exactly when y > tau -- to a mask
@@ -164,11 +172,13 @@ __global__ __launch_bounds__(256) void encode_rows_kernel(const uint16_t* __rest
       // index bits 5 and up: across the lanes of the group
 #pragma unroll
       for (int s = 0; (1 << s) < LPV; ++s) {
-        const bool upper = ((j >> s) & 1) != 0;
+        // the upper lane of a pair takes partner - x, the lower one x + partner:
+        // one addition once the upper lane's own value has changed sign
+        const uint32_t sign_flip = ((j >> s) & 1) != 0 ? 0x80000000u : 0u;
 #pragma unroll
         for (int i = 0; i < 32; ++i) {
           const double partner = s < 2 ? dpp_quad_xor_f64(x[i], s == 1) : __shfl_xor(x[i], 4, kWave);
-          x[i] = upper ? partner - x[i] : x[i] + partner;
+          x[i] = flip_sign_f64(x[i], sign_flip) + partner;
         }
       }
     }
