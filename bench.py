@@ -431,9 +431,9 @@ def main():
                 traffic = float(line.split(":")[1])
 
     result = {
-        "metric": "decode-step us/layer at 32K ctx (encode+select+sparse attn); achieved HBM GB/s",
+        "metric": "decode-step \u00b5s/layer at 32K ctx (encode+select+sparse attn); achieved HBM GB/s",
         "value": round(us_step, 3),
-        "unit": "us/layer",
+        "unit": "\u00b5s/layer",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
@@ -547,7 +547,7 @@ def main():
         scale_up = Hkv / n_kv
         result["cpu_baseline"] = {
             "value": round(cpu_s * scale_up * 1e6, 1),
-            "unit": "us/layer",
+            "unit": "\u00b5s/layer",
             "cores": cores,
             "kind": "oracle",
             "single_thread_us_per_layer": None if cpu_1t is None else round(cpu_1t * scale_up * 1e6, 1),
