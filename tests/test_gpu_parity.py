@@ -874,3 +874,38 @@ def test_head_dim_options_that_are_not_built_are_refused(H, oracle):
         assert A.adamas_workspace_bytes(cfg, 1, 1024, 16) == 0, (hd, kw, group)
     assert A.adamas_workspace_bytes(A.Config.make(8, 1, 1024, head_dim=64), 1, 1024, 16) > 0
     assert A.adamas_workspace_bytes(A.Config.make(4, 1, 1024, head_dim=256), 1, 1024, 16) > 0
+
+
+def test_generation_loop_of_appending_steps(H, oracle):
+    """Six consecutive decode steps on a growing cache (one sequence crosses a scan-tile
+    boundary on the way), device lengths bumped in place, one workspace, no host round trip
+    between the library calls of a step: every step's selection and output against the oracle,
+    which keeps its own copy of the cache, and the final caches bit for bit."""
+    B, Hq, Hkv, k, steps = 2, 8, 4, 48, 6
+    start_len = [700, 2046]
+    case = small_case(1200, B, Hq, Hkv, [n + steps for n in start_len])   # pools sized for the end
+    rng = np.random.default_rng(1201)
+    d = H.DeviceCase(case, k)          # encodes the whole pool: rows beyond the lengths are ignored
+    K_ref, V_ref = case.K.copy(), case.V.copy()
+    with oracle.head_dim(128):
+        _, rows_ref = oracle.encode(K_ref, case.thresholds)
+    lens = np.array(start_len, dtype=np.int32)
+    d.seq_len.copy_(torch.from_numpy(lens))
+    import paper_2510_18413_amd as A
+    for step in range(steps):
+        lens = lens + 1
+        d.seq_len.add_(1)
+        q = synth.f32_to_bf16_bits(rng.standard_normal((B, Hq, 128), dtype=np.float32))
+        kn = synth.f32_to_bf16_bits(rng.standard_normal((B, Hkv, 128), dtype=np.float32) * 1.5)
+        vn = synth.f32_to_bf16_bits(rng.standard_normal((B, Hkv, 128), dtype=np.float32))
+        A.adamas_decode_step(d.cfg, H.dev_bf16(q), d.K, d.V, d.codes, d.seq_start, d.seq_len, k,
+                             d.out, d.max_len, d.workspace, k_new=H.dev_bf16(kn),
+                             v_new=H.dev_bf16(vn), idx_out=d.idx)
+        torch.cuda.synchronize()
+        out, idx, _ = oracle.decode_step(q, K_ref, V_ref, rows_ref, case.seq_start, lens, k,
+                                         case.thresholds, case.thresholds, H.SM_SCALE,
+                                         k_new=kn, v_new=vn)
+        assert np.array_equal(d.idx.cpu().numpy(), idx), step
+        assert H.attn_rel_err(d.out.cpu().numpy(), out) <= H.ATTN_TOL, step
+    assert np.array_equal(H.host_u16(d.K), K_ref) and np.array_equal(H.host_u16(d.V), V_ref)
+    assert np.array_equal(d.codes.cpu().numpy(), rows_ref)
