@@ -44,7 +44,10 @@
  * where y = x H / sqrt(128) is the orthonormal transform evaluated EXACTLY:
  * the kernels form the +-1 sums in fp64, which is exact when, within one
  * vector, the binary exponents of the largest and smallest non-zero input
- * differ by at most 38, and compare with (double)thr[i] * sqrt(128.0).
+ * differ by at most 38, and compare with (double)thr[i] * sqrt(128.0).  (The
+ * bulk encode tries fp32 first and keeps a vector's result only where an
+ * error bound proves every comparison equal to the exact one; the other
+ * vectors are redone in fp64.)
  * Inputs outside that range, NaN or Inf give unspecified codes.
  *
  * Selection.  The min(k, seq_len) tokens of smallest distance, equal

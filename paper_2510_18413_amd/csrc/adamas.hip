@@ -155,6 +155,19 @@ Thresholds scaled(const adamas_config* c, const float* thr) {
   const double root = t.transform ? std::sqrt((double)c->head_dim) : 1.0;
   const int n_thr = (1 << code_bits(c)) - 1;
   for (int i = 0; i < n_thr; ++i) t.tau[i] = (double)thr[i] * root;
+  // single-precision copies for the bulk encode's certified attempt
+  t.fast = 1;
+  double worst = 0.0;
+  for (int i = 0; i < n_thr; ++i) {
+    t.tau32[i] = (float)t.tau[i];
+    const double back = (double)t.tau32[i];
+    if (!std::isfinite(t.tau32[i]) || (back > 0.0) != (t.tau[i] > 0.0) || (back < 0.0) != (t.tau[i] < 0.0))
+      t.fast = 0;
+    worst = std::fmax(worst, std::fabs(back - t.tau[i]));
+  }
+  // rounded up: a bound must not shrink when it is stored as a float
+  t.dtau = worst == 0.0 ? 0.f : std::nextafter((float)(worst * 1.000001), INFINITY);
+  if (!std::isfinite(t.dtau)) t.fast = 0;
   return t;
 }
 

@@ -14,6 +14,13 @@ namespace adamas {
 struct Thresholds {
   double tau[7];  // 2^BITS - 1 used
   int transform;
+  // For the bulk encode's single-precision attempt (see encode_rows_kernel):
+  // tau rounded to float, an upper bound of max |tau32[i] - tau[i]|, and
+  // whether that attempt may be made at all (it needs every tau32[i] to keep
+  // the sign of tau[i], zero included).
+  float tau32[7];
+  float dtau;
+  int fast;
 };
 
 // Bit planes of the bucket index c = #{i : y > tau_i} from the nested indicator
@@ -87,43 +94,103 @@ __device__ __forceinline__ void encode_values_wave(const uint32_t (&raw)[D / 64]
 
 // ---- bulk encode: D / 32 lanes per vector ---------------------------------
 //
-// Lane j of a group holds elements 32j .. 32j+31 of one vector as doubles, so
-// five butterfly stages are register-to-register and only the index bits from 5
-// up cross lanes (two stages at D = 128, by DPP quad permutes).  After the
+// Lane j of a group holds elements 32j .. 32j+31 of one vector, so five
+// butterfly stages are register-to-register and only the index bits from 5 up
+// cross lanes (two stages at D = 128, by DPP quad permutes).  After the
 // transform lane j holds coefficients 32j .. 32j+31, which is exactly word j of
 // the packed row: every lane assembles and stores its own word.  At D = 128 a
-// wave encodes 16 vectors and moves 4 KiB in, 512 B out, both contiguous.  All
-// sums are fp64 and exact under the documented exponent spread, hence identical
-// to the wave-per-vector routine above whatever the order.
+// wave encodes 16 vectors and moves 4 KiB in, 512 B out, both contiguous.
+//
+// The codes are defined on the exact sums.  The four-lane routine works in
+// fp32 and certifies its own result (below); the few vectors it cannot certify
+// are redone in fp64 by the whole wave with encode_values_wave, one at a time.
 
-// v of lane (l ^ 1) or (l ^ 2).  Every lane of a quad is a valid source, so the
-// move needs no previous value of its destination.
-__device__ __forceinline__ double dpp_quad_xor_f64(double v, bool xor2) {
-  const uint64_t bits = __builtin_bit_cast(uint64_t, v);
-  const int lo = (int)(uint32_t)bits, hi = (int)(uint32_t)(bits >> 32);
-  int plo, phi;
-  if (xor2) {
-    plo = __builtin_amdgcn_mov_dpp(lo, kDppQuadXor2, 0xf, 0xf, true);
-    phi = __builtin_amdgcn_mov_dpp(hi, kDppQuadXor2, 0xf, 0xf, true);
-  } else {
-    plo = __builtin_amdgcn_mov_dpp(lo, kDppQuadXor1, 0xf, 0xf, true);
-    phi = __builtin_amdgcn_mov_dpp(hi, kDppQuadXor1, 0xf, 0xf, true);
+// ---- bulk encode, single-precision attempt with a certified guard ----------
+//
+// The same butterflies in fp32.  An fp32 sum is rounded, so its comparison with
+// a threshold can come out wrong -- but only when the sum is close to the
+// threshold: every coefficient goes through log2(D) additions, hence
+//   |y_fp32 - y_exact| <= gamma * sum_i |x_i|,  gamma = n u / (1 - n u),
+//   n = log2(D), u = 2^-24
+// (additions in fp32 never lose anything to underflow, and no partial sum
+// exceeds sum |x_i|, which is checked to be far from overflow).  If every
+// coefficient of a vector is further than that bound (plus the rounding of
+// the threshold itself to fp32) from every threshold, all its comparisons are
+// those of the exact sums and the fp32 masks are returned as certified;
+// otherwise the caller has the vector redone exactly.  A vector of zeros has
+// exact sums by itself.  Returns the same verdict in all lanes of the group.
+__device__ __forceinline__ float dpp_quad_xor_f32(float v, bool xor2) {
+  const int b = __float_as_int(v);
+  return __int_as_float(xor2 ? __builtin_amdgcn_mov_dpp(b, kDppQuadXor2, 0xf, 0xf, true)
+                             : __builtin_amdgcn_mov_dpp(b, kDppQuadXor1, 0xf, 0xf, true));
+}
+
+template <int BITS, int D>
+__device__ __forceinline__ bool encode_part_fast(const uint4 (&raw)[4], const Thresholds& thr, int j,
+                                                 uint32_t (&m)[(1 << BITS) - 1]) {
+  constexpr int LPV = D / 32, T = (1 << BITS) - 1;
+  constexpr int kStages = D == 64 ? 6 : D == 128 ? 7 : 8;
+  // gamma with a margin of 1.5 u for the rounding of sum |x_i|, of the guard
+  // itself and of the differences compared with it
+  constexpr float kGuard = (float)((kStages + 1.5) * 5.9604644775390625e-8);
+  float x[32];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const uint32_t w[4] = {raw[i].x, raw[i].y, raw[i].z, raw[i].w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      x[i * 8 + 2 * e] = bf16_lo(w[e]);
+      x[i * 8 + 2 * e + 1] = bf16_hi(w[e]);
+    }
   }
-  return __builtin_bit_cast(double, ((uint64_t)(uint32_t)phi << 32) | (uint32_t)plo);
-}
-
-// v with its sign bit flipped where sign_flip is 0x80000000 (0: unchanged).
-__device__ __forceinline__ double flip_sign_f64(double v, uint32_t sign_flip) {
-  const uint64_t bits = __builtin_bit_cast(uint64_t, v);
-  return __builtin_bit_cast(double, bits ^ ((uint64_t)sign_flip << 32));
-}
-
-// Appends the sign bit of (tau - y) -- set exactly when y > tau -- to a mask
-// that is shifted left once per call: elements must be fed from 31 down to 0.
-__device__ __forceinline__ uint32_t push_greater(uint32_t mask, double y, double tau) {
-  const double d = tau - y;  // +0 when equal: not greater
-  const uint32_t hi = (uint32_t)(__builtin_bit_cast(uint64_t, d) >> 32);
-  return __builtin_amdgcn_alignbit(mask, hi, 31);  // (mask << 1) | (hi >> 31)
+  float sum_abs = 0.f;
+#pragma unroll
+  for (int i = 0; i < 32; ++i) sum_abs += fabsf(x[i]);
+  if (thr.transform) {
+#pragma unroll
+    for (int h = 1; h < 32; h <<= 1) {
+#pragma unroll
+      for (int i = 0; i < 32; ++i) {
+        if ((i & h) == 0) {
+          const float a = x[i], b = x[i + h];
+          x[i] = a + b;
+          x[i + h] = a - b;
+        }
+      }
+    }
+#pragma unroll
+    for (int s = 0; (1 << s) < LPV; ++s) {
+      const uint32_t sign_flip = ((j >> s) & 1) != 0 ? 0x80000000u : 0u;
+#pragma unroll
+      for (int i = 0; i < 32; ++i) {
+        const float partner = s < 2 ? dpp_quad_xor_f32(x[i], s == 1) : __shfl_xor(x[i], 4, kWave);
+        x[i] = __int_as_float(__float_as_int(x[i]) ^ (int)sign_flip) + partner;
+      }
+    }
+  }
+  float nearest = 3.0e38f;  // smallest |coefficient - threshold| of the vector
+#pragma unroll
+  for (int i = 0; i < T; ++i) m[i] = 0;
+#pragma unroll
+  for (int e = 31; e >= 0; --e) {
+#pragma unroll
+    for (int i = 0; i < T; ++i) {
+      const float d = thr.tau32[i] - x[e];  // the sign of a difference is exact; +0 when equal
+      // (m << 1) | sign(d); as an opaque instruction, or the compiler rebuilds the
+      // 32-step chain as a tree over all the differences and runs out of registers
+      asm("v_alignbit_b32 %0, %1, %2, 31" : "=v"(m[i]) : "v"(m[i]), "v"(d));
+      nearest = fminf(nearest, fabsf(d));
+    }
+  }
+  // over the lanes of the group
+#pragma unroll
+  for (int s = 0; (1 << s) < LPV; ++s) {
+    sum_abs += s < 2 ? dpp_quad_xor_f32(sum_abs, s == 1) : __shfl_xor(sum_abs, 4, kWave);
+    nearest = fminf(nearest, s < 2 ? dpp_quad_xor_f32(nearest, s == 1) : __shfl_xor(nearest, 4, kWave));
+  }
+  // Without the transform the "sums" are the elements themselves: exact.
+  const float guard = (thr.transform ? sum_abs * kGuard : 0.f) + thr.dtau;
+  return sum_abs < 1.0e30f && (nearest > guard || guard == 0.f || sum_abs == 0.f);
 }
 
 // Vector v of n_vec = n_heads * n_rows lives at
@@ -136,70 +203,63 @@ __global__ __launch_bounds__(256) void encode_rows_kernel(const uint16_t* __rest
                                                           int64_t row_begin, int64_t n_rows,
                                                           int64_t n_vec, Thresholds thr) {
   constexpr int LPV = D / 32;        // lanes per vector: 2, 4 or 8
+  constexpr int T = (1 << BITS) - 1, W = D / 32, E = D / 64;
+  constexpr int kRowBytes = W * 4 * BITS;
+  const int lane = threadIdx.x & 63;
   const int j = threadIdx.x & (LPV - 1);  // which 32-element part of the vector
   const int64_t quad = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / LPV;
   const int64_t n_quads = ((int64_t)gridDim.x * blockDim.x) / LPV;
-  for (int64_t v = quad; v < n_vec; v += n_quads) {
-    const int64_t head = v / n_rows, r = v - head * n_rows;
-    const int64_t row = head * head_stride_rows + row_begin + r;
-    const uint4* in = reinterpret_cast<const uint4*>(src + row * D + j * 32);
-    uint4 raw[4];
+  // All 64 lanes of a wave stay in the loop as long as its first group has a
+  // vector (the groups of a wave take consecutive vectors), because the exact
+  // redo below needs the whole wave.
+  for (int64_t v = quad; __builtin_amdgcn_readfirstlane((int)(v < n_vec)) != 0; v += n_quads) {
+    const bool valid = v < n_vec;
+    int64_t row = 0;
+    bool certified = true;
+    if (valid) {
+      const int64_t head = v / n_rows, r = v - head * n_rows;
+      row = head * head_stride_rows + row_begin + r;
+      const uint4* in = reinterpret_cast<const uint4*>(src + row * D + j * 32);
+      uint4 raw[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) raw[i] = in[i];
-    double x[32];
+      for (int i = 0; i < 4; ++i) raw[i] = in[i];
+      // Eq. 5 on the lane's 32 coefficients: nested indicator masks, then the
+      // planes of the bucket index; lane j stores word j of the row.
+      uint32_t m[T], plane[BITS];
+      certified = encode_part_fast<BITS, D>(raw, thr, j, m) && thr.fast != 0;
+      if (certified) {
+        planes_from_masks<BITS>(m, plane);
+        uint32_t* out = reinterpret_cast<uint32_t*>(dst + row * kRowBytes + j * (4 * BITS));
+        if constexpr (BITS == 2) {
+          *reinterpret_cast<uint2*>(out) = make_uint2(plane[0], plane[1]);
+        } else {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const uint32_t w[4] = {raw[i].x, raw[i].y, raw[i].z, raw[i].w};
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        x[i * 8 + 2 * e] = (double)bf16_lo(w[e]);
-        x[i * 8 + 2 * e + 1] = (double)bf16_hi(w[e]);
-      }
-    }
-    if (thr.transform) {
-      // index bits 0..4: inside the lane
-#pragma unroll
-      for (int h = 1; h < 32; h <<= 1) {
-#pragma unroll
-        for (int i = 0; i < 32; ++i) {
-          if ((i & h) == 0) {
-            const double a = x[i], b = x[i + h];
-            x[i] = a + b;
-            x[i + h] = a - b;
-          }
-        }
-      }
-      // index bits 5 and up: across the lanes of the group
-#pragma unroll
-      for (int s = 0; (1 << s) < LPV; ++s) {
-        // the upper lane of a pair takes partner - x, the lower one x + partner:
-        // one addition once the upper lane's own value has changed sign
-        const uint32_t sign_flip = ((j >> s) & 1) != 0 ? 0x80000000u : 0u;
-#pragma unroll
-        for (int i = 0; i < 32; ++i) {
-          const double partner = s < 2 ? dpp_quad_xor_f64(x[i], s == 1) : __shfl_xor(x[i], 4, kWave);
-          x[i] = flip_sign_f64(x[i], sign_flip) + partner;
+          for (int p = 0; p < BITS; ++p) out[p] = plane[p];
         }
       }
     }
-    // Eq. 5 on the lane's 32 coefficients: nested indicator masks, then the
-    // planes of the bucket index; lane j stores word j of the row.
-    constexpr int T = (1 << BITS) - 1;
-    uint32_t m[T], plane[BITS];
+    // Vectors without a certificate: the whole wave redoes them exactly, one
+    // after the other (wave-uniform loop over the first lanes of their groups).
+    uint64_t pending = __ballot(valid && !certified && j == 0);
+    while (pending != 0) {
+      const int leader = __builtin_ctzll(pending);
+      pending &= pending - 1;
+      const uint32_t row_lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)row, leader);
+      const uint32_t row_hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)((uint64_t)row >> 32), leader);
+      const int64_t vrow = (int64_t)(((uint64_t)row_hi << 32) | row_lo);
+      uint32_t rawv[E];
 #pragma unroll
-    for (int i = 0; i < T; ++i) m[i] = 0;
+      for (int e = 0; e < E; ++e) rawv[e] = src[vrow * D + lane + 64 * e];
+      uint32_t w[BITS][W];
+      encode_values_wave<BITS, D>(rawv, thr, w);
+      uint32_t* out = reinterpret_cast<uint32_t*>(dst + vrow * kRowBytes);
 #pragma unroll
-    for (int e = 31; e >= 0; --e) {
+      for (int wd = 0; wd < W; ++wd) {
+        if (lane == wd) {  // lane wd stores word wd (every lane holds the whole row)
 #pragma unroll
-      for (int i = 0; i < T; ++i) m[i] = push_greater(m[i], x[e], thr.tau[i]);
-    }
-    planes_from_masks<BITS>(m, plane);
-    uint32_t* out = reinterpret_cast<uint32_t*>(dst + row * (LPV * 4 * BITS) + j * (4 * BITS));
-    if constexpr (BITS == 2) {
-      *reinterpret_cast<uint2*>(out) = make_uint2(plane[0], plane[1]);
-    } else {
-#pragma unroll
-      for (int p = 0; p < BITS; ++p) out[p] = plane[p];
+          for (int p = 0; p < BITS; ++p) out[BITS * wd + p] = w[p][wd];
+        }
+      }
     }
   }
 }

@@ -79,6 +79,50 @@ def test_encode_values_on_thresholds_and_zeros(H, oracle):
         assert np.array_equal(codes.cpu().numpy()[0], oracle.encode(bits, thr)[1])
 
 
+def test_encode_coefficients_within_rounding_of_a_threshold(H, oracle):
+    """The bulk encode first tries single precision and keeps a vector's result only when every
+    coefficient is provably on the right side of every threshold.  near_threshold_cases feeds it
+    vectors for which that cannot be certified and on which plain single precision is wrong (a
+    CPU test shows that).  Bulk and query encode must equal the oracle bit for bit."""
+    import paper_2510_18413_amd as A
+    import near_threshold_cases as ntc
+    n, above = ntc.N_VECTORS, 0
+    for trial, (bits, thr, picks) in enumerate(ntc.trials(oracle)):
+        tau = np.array(thr, dtype=np.float64) * np.sqrt(128.0)
+        above += int(np.sum(np.array(picks) > tau))        # exact sums just above their threshold
+        cfg = A.Config.make(1, 1, n, thr_k=thr)
+        codes = torch.zeros(1, n, 32, dtype=torch.uint8, device="cuda")
+        A.adamas_encode_keys(cfg, H.dev_bf16(bits.reshape(1, n, 128)), codes, 0, n)
+        qcodes = torch.zeros(n, 1, 32, dtype=torch.uint8, device="cuda")
+        A.adamas_encode_query(A.Config.make(1, 1, n, thr_k=thr, thr_q=thr),
+                              H.dev_bf16(bits.reshape(n, 1, 128)), qcodes)
+        torch.cuda.synchronize()
+        ref = oracle.encode(bits, thr)[1]
+        assert np.array_equal(codes.cpu().numpy()[0], ref), trial
+        assert np.array_equal(qcodes.cpu().numpy()[:, 0], ref), trial
+    assert above > 5       # both sides of the thresholds occurred
+
+
+def test_encode_extreme_magnitudes(H, oracle):
+    """Vectors scaled by 2^100 and 2^-100 (thresholds scaled alike): the single-precision
+    attempt must step aside where its sums could overflow, and stay exact where they are tiny."""
+    import paper_2510_18413_amd as A
+    rng = np.random.default_rng(78)
+    x = rng.standard_normal((512, 128), dtype=np.float32)
+    for scale in (2.0 ** 100, 2.0 ** -100):
+        xb = synth.bf16_bits_to_f32(synth.f32_to_bf16_bits(x)) * np.float32(scale)   # exact: a power of two
+        bits = (xb.view(np.uint32) >> np.uint32(16)).astype(np.uint16)
+        assert np.array_equal(synth.bf16_bits_to_f32(bits), xb)
+        thr = tuple(float(np.float32(t * scale)) for t in (-1.0, 0.0, 1.0))
+        cfg = A.Config.make(1, 1, 512, thr_k=thr)
+        codes = torch.zeros(1, 512, 32, dtype=torch.uint8, device="cuda")
+        A.adamas_encode_keys(cfg, H.dev_bf16(bits.reshape(1, 512, 128)), codes, 0, 512)
+        torch.cuda.synchronize()
+        ref_codes, ref = oracle.encode(bits, thr)
+        assert np.array_equal(codes.cpu().numpy()[0], ref), scale
+        assert len(np.unique(ref_codes)) == 4
+
+
 # -------------------------------------------------------------------- distance + top-k
 
 @pytest.mark.parametrize("B,Hq,Hkv,lens,k", [

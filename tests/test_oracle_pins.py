@@ -734,3 +734,21 @@ def test_tiny_config_needle_is_selected(oracle):
     needle = case.needles[0][0][0]
     assert needle in idx[0, 0].tolist()
     assert dist[0, 0, needle] == dist[0, 0, :1024].min()
+
+
+# ------------------------------------------- why the transform sums must be exact (S1)
+
+def test_single_precision_transform_misjudges_near_threshold_inputs(oracle):
+    """Eq. 5 is read on the exact sums.  On the inputs of near_threshold_cases a float32
+    butterfly transform puts coefficients on the wrong side of a threshold in most trials, so
+    an encoder that passes the GPU test on them cannot be a plain float32 one."""
+    import near_threshold_cases as ntc
+    wrong_trials = n_trials = 0
+    for bits, thr, _ in ntc.trials(oracle):
+        tau = np.array(thr, dtype=np.float64) * np.sqrt(128.0)
+        y32 = ntc.fwht_float32(synth.bf16_bits_to_f32(bits)).astype(np.float64)
+        codes32 = (y32[..., None] > tau).sum(-1)
+        exact, _ = oracle.encode(bits, thr)
+        n_trials += 1
+        wrong_trials += int(np.any(codes32 != exact))
+    assert n_trials >= 20 and wrong_trials >= n_trials // 2
