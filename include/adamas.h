@@ -205,8 +205,8 @@ int adamas_select_topk(const adamas_config *cfg, const void *qcodes,
  * Alg. 1, gather and attention steps (Eq. 1): out[b][h] = softmax(q[b][h] . K_s^T * sm_scale) V_s
  * over the rows idx[b][h][0..k) of sequence b (token positions; negative
  * entries are skipped; no valid entry -> zeros).  q bf16 [batch][Hq][128];
- * idx int32 [batch][Hq][k]; out fp32 [batch][Hq][128].  Products and sums are
- * fp32; the caller guarantees 0 <= idx < seq_len[b] for non-negative entries.
+ * idx int32 [batch][Hq][k]; out fp32 [batch][Hq][128].  Scores are formed in
+ * fp64, weights and weighted sums in fp32; the caller guarantees 0 <= idx < seq_len[b] for non-negative entries.
  * max_seq_len is only used to size the workspace (pass the same value as to
  * adamas_workspace_bytes).
  */

@@ -224,9 +224,9 @@ void launch_encode_rows(const adamas_config* c, hipStream_t st, const uint16_t* 
   }
 }
 
-float scale_log2e(const adamas_config* c) {
+double scale_log2e(const adamas_config* c) {
   const double s = c->sm_scale > 0.f ? (double)c->sm_scale : 1.0 / std::sqrt((double)c->head_dim);
-  return (float)(s * kLog2e);
+  return s * kLog2e;
 }
 
 // Drops an error an earlier, unrelated HIP call may have left on this thread,
@@ -691,7 +691,7 @@ int adamas_full_attn(const adamas_config* cfg, const void* q, const void* K, con
   fp.Hkv = cfg->num_kv_heads;
   fp.n_splits = pl.n_splits;
   fp.chunk = pl.chunk;
-  fp.scale_log2e = scale_log2e(cfg);
+  fp.scale_log2e = (float)scale_log2e(cfg);
   const dim3 grid(pl.n_splits, cfg->num_kv_heads, batch);
   switch (cfg->num_q_heads / cfg->num_kv_heads) {
     case 1: launch_full<1>(cfg->head_dim, grid, st, fp); break;

@@ -100,6 +100,25 @@ __device__ __forceinline__ float lanes_sum_f32(float v) {
   return v;
 }
 
+// The same for doubles (two 32-bit moves per step).
+template <int CTRL>
+__device__ __forceinline__ double dpp_f64(double v) {
+  const uint64_t b = __builtin_bit_cast(uint64_t, v);
+  // every lane has a valid source under these patterns: no previous value needed
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_mov_dpp((int)(uint32_t)b, CTRL, 0xf, 0xf, true);
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_mov_dpp((int)(uint32_t)(b >> 32), CTRL, 0xf, 0xf, true);
+  return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
+}
+template <int LANES>
+__device__ __forceinline__ double lanes_sum_f64(double v) {
+  v += dpp_f64<kDppQuadXor1>(v);
+  v += dpp_f64<kDppQuadXor2>(v);
+  v += dpp_f64<kDppRowHalfMirror>(v);
+  if constexpr (LANES >= 16) v += dpp_f64<kDppRowMirror>(v);
+  if constexpr (LANES >= 32) v += __shfl_xor(v, 16, kWave);
+  return v;
+}
+
 // Inclusive prefix sum over the 64 lanes of a wave (Hillis-Steele inside each
 // row, then the row totals are carried across rows with the two broadcasts).
 __device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v) {

@@ -52,7 +52,7 @@ struct SelectParams {
   int64_t pool_tokens, max_seq_len;
   int32_t Hq, Hkv, k;
   int32_t n_tiles, tile_tokens, seg_len;
-  float scale_log2e;          // sm_scale * log2(e)
+  double scale_log2e;         // sm_scale * log2(e)
   // Paged cache (PAGED kernels only), as in ScanParams.
   const int32_t* page_table;
   int32_t max_pages, page_shift;
@@ -99,19 +99,22 @@ template <int THREADS, int D>
 __device__ __forceinline__ void attention_rows(const int32_t* s_sel, int n, int n_tokens,
                                                const uint16_t* __restrict__ q,
                                                const uint16_t* __restrict__ Kp,
-                                               const uint16_t* __restrict__ Vp, float scale_log2e,
+                                               const uint16_t* __restrict__ Vp, double scale_log2e,
                                                AttnShared<THREADS, D>& sh, float& M, float& lsum,
                                                float& o) {
-  // No implicit FMA contraction here: a scaled score must be rounded once, and
-  // that one value must feed both the running maximum and the exponent, or rows
-  // with equal scores would not get equal weights.  The dot products use
-  // explicit fmaf and stay fused.
+  // Scores in fp64: products of bf16 values are exact, and so (for all practical
+  // purposes) is their sum.  An fp32 dot product of 128 terms is off by about
+  // 1e-5 in the exponent of a weight; where the weighted rows nearly cancel that
+  // becomes 1e-3 of the output.  Only the difference between a score and the
+  // running maximum (itself a float, so that every weight of a head refers to
+  // exactly the same number) is rounded to fp32, and rows with equal scores get
+  // equal weights.  No implicit FMA contraction in the fp32 part.
 #pragma clang fp contract(off)
   constexpr int LPR = D / 8;  // lanes per row: 8 dims each
   constexpr int kGroups = THREADS / LPR;
   const int tid = threadIdx.x, grp = tid / LPR, gl = tid % LPR;
 
-  float qf[8];
+  double qf[8];
   {
     const uint4 qv = *reinterpret_cast<const uint4*>(q + gl * 8);
     qf[0] = bf16_lo(qv.x); qf[1] = bf16_hi(qv.x); qf[2] = bf16_lo(qv.y); qf[3] = bf16_hi(qv.y);
@@ -140,22 +143,23 @@ __device__ __forceinline__ void attention_rows(const int32_t* s_sel, int n, int 
         vv[u] = make_uint4(0, 0, 0, 0);
       }
     }
-    float sc[U];
+    double sc[U];
     float mn = m;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      float s = qf[0] * bf16_lo(kv[u].x);
-      s = fmaf(qf[1], bf16_hi(kv[u].x), s);
-      s = fmaf(qf[2], bf16_lo(kv[u].y), s);
-      s = fmaf(qf[3], bf16_hi(kv[u].y), s);
-      s = fmaf(qf[4], bf16_lo(kv[u].z), s);
-      s = fmaf(qf[5], bf16_hi(kv[u].z), s);
-      s = fmaf(qf[6], bf16_lo(kv[u].w), s);
-      s = fmaf(qf[7], bf16_hi(kv[u].w), s);
+      // two chains of four: the additions of a chain wait for each other
+      double s = qf[0] * (double)bf16_lo(kv[u].x), s2 = qf[1] * (double)bf16_hi(kv[u].x);
+      s = fma(qf[2], (double)bf16_lo(kv[u].y), s);
+      s2 = fma(qf[3], (double)bf16_hi(kv[u].y), s2);
+      s = fma(qf[4], (double)bf16_lo(kv[u].z), s);
+      s2 = fma(qf[5], (double)bf16_hi(kv[u].z), s2);
+      s = fma(qf[6], (double)bf16_lo(kv[u].w), s);
+      s2 = fma(qf[7], (double)bf16_hi(kv[u].w), s2);
+      s += s2;
       // the row's D / 8 lanes are an aligned group of 8, 16 or 32 lanes
-      s = lanes_sum_f32<LPR>(s) * scale_log2e;
-      sc[u] = ok[u] ? s : kNegBig;
-      mn = fmaxf(mn, sc[u]);
+      s = lanes_sum_f64<LPR>(s) * scale_log2e;
+      sc[u] = ok[u] ? s : (double)kNegBig;
+      mn = fmaxf(mn, (float)sc[u]);
     }
     // one rescale of the running state for the whole batch of rows
     const float corr = exp2f(m - mn);
@@ -165,7 +169,7 @@ __device__ __forceinline__ void attention_rows(const int32_t* s_sel, int n, int 
     for (int j = 0; j < 8; ++j) acc[j] *= corr;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const float pw = ok[u] ? exp2f(sc[u] - mn) : 0.f;
+      const float pw = ok[u] ? exp2f((float)(sc[u] - (double)mn)) : 0.f;
       l += pw;
       acc[0] = fmaf(pw, bf16_lo(vv[u].x), acc[0]);
       acc[1] = fmaf(pw, bf16_hi(vv[u].x), acc[1]);
@@ -529,7 +533,7 @@ struct AttnParams {
   float* partial;      // [B*Hq][kMaxParts][partial_stride(D)]
   int64_t pool_tokens;
   int32_t Hq, Hkv, k, n_parts, chunk;  // chunk = idx entries per workgroup
-  float scale_log2e;
+  double scale_log2e;
 };
 
 // Grid (n_parts, Hq, B): workgroup `part` attends over idx entries
