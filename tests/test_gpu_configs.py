@@ -36,6 +36,9 @@ def check_case(H, oracle, case, budgets, check_cache=False):
         assert np.array_equal(idx, ref_idx), "indices, k=%d" % k
         err = H.attn_rel_err(out, ref_out)
         assert err <= H.ATTN_TOL, "attention rel err %g, k=%d" % (err, k)
+        # with fp64 scores the step is far inside the bound (measured <= 3.5e-5 on these
+        # configurations); a regression to fp32-score accuracy (1e-4 .. 2e-3) would show here
+        assert err <= H.ATTN_TOL / 10, "attention rel err %g, k=%d" % (err, k)
         for b in range(case.B):
             for h in range(case.Hq):
                 sel = set(idx[b, h].tolist())
