@@ -24,6 +24,9 @@ HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E peak
 
 WORKLOADS = {
     # name: (B, Hq, Hkv, context, default k, append, ragged)
+    "cfg0": dict(B=1, Hq=1, Hkv=1, L=1024, k=64, append=False, ragged=False,
+                 text="config 0: tiny single-head decode, batch 1, 1 query = 1 KV head, "
+                      "head_dim 128, context 1024 (latency only: two launches, no bandwidth figure)"),
     "cfg1": dict(B=1, Hq=32, Hkv=32, L=32768, k=256, append=False, ragged=False,
                  text="config 1: Llama-style MHA layer decode, batch 1, 32 query = 32 KV heads, "
                       "head_dim 128, context 32768, all keys pre-encoded, no append"),
