@@ -103,6 +103,28 @@ def test_encode_coefficients_within_rounding_of_a_threshold(H, oracle):
     assert above > 5       # both sides of the thresholds occurred
 
 
+@pytest.mark.parametrize("hd,bits", [(128, 2), (64, 2), (256, 2), (128, 1), (128, 3)])
+def test_encode_wide_exponent_spread(H, oracle, hd, bits):
+    """60 000 vectors whose elements span about 28 binary orders of magnitude (so that single
+    precision sums round all the time) against odd thresholds: every code byte as the oracle's."""
+    import paper_2510_18413_amd as A
+    rng = np.random.default_rng(900 + hd + bits)
+    n = 60000
+    x = rng.standard_normal((n, hd), dtype=np.float32)
+    x *= np.exp2(rng.integers(-20, 9, size=(n, hd))).astype(np.float32)
+    x[rng.random((n, hd)) < 0.05] = 0.0
+    xb = synth.bf16_bits_to_f32(synth.f32_to_bf16_bits(x))          # synth flushes |x| < 2^-24
+    bf = (xb.view(np.uint32) >> np.uint32(16)).astype(np.uint16)
+    thr = {1: (0.13,), 2: (-0.7, 0.13, 0.9), 3: (-2.1, -0.7, -0.2, 0.13, 0.5, 0.9, 3.3)}[bits]
+    cfg = A.Config.make(1, 1, n, thr_k=thr, head_dim=hd, code_bits=0 if bits == 2 else bits)
+    codes = torch.zeros(1, n, cfg.code_row_bytes, dtype=torch.uint8, device="cuda")
+    A.adamas_encode_keys(cfg, H.dev_bf16(bf.reshape(1, n, hd)), codes, 0, n)
+    torch.cuda.synchronize()
+    with oracle.head_dim(hd):
+        ref = oracle.encode_bits(bf, thr, bits)[1] if bits != 2 else oracle.encode(bf, thr)[1]
+    assert np.array_equal(codes.cpu().numpy()[0], ref)
+
+
 def test_encode_extreme_magnitudes(H, oracle):
     """Vectors scaled by 2^100 and 2^-100 (thresholds scaled alike): the single-precision
     attempt must step aside where its sums could overflow, and stay exact where they are tiny."""
