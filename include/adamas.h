@@ -124,12 +124,12 @@ extern "C" {
 /*
  * Head dimension d.  The text above and below is written for d = 128, the
  * head dimension of the paper's models.  head_dim 64 and 256 run the method
- * itself (Hadamard transform of order d, 2-bit codes, Eq. 6, contiguous
- * cache) through every entry point except adamas_decode_step_paged: read
- * d for 128 and d/4 for the 32-byte code row (d/32 words of 64 bits, same bit
- * placement), distances 0..3d, sm_scale 0 meaning 1/sqrt(d), thresholds
- * compared with x H / sqrt(d).  With them, ADAMAS_VARIANT_L2, code_bits 1
- * or 3, the paged entry point, and at d = 256 a group above 4 return
+ * itself (Hadamard transform of order d, 2-bit codes, Eq. 6, with or without
+ * ADAMAS_VARIANT_NO_HADAMARD, contiguous or paged cache) through every entry
+ * point: read d for 128 and d/4 for the 32-byte code row (d/32 words of 64
+ * bits, same bit placement), distances 0..3d, sm_scale 0 meaning 1/sqrt(d),
+ * thresholds compared with x H / sqrt(d).  With them, ADAMAS_VARIANT_L2,
+ * code_bits 1 or 3, and at d = 256 a group above 4 return
  * ADAMAS_ERR_UNSUPPORTED.
  */
 typedef struct adamas_config {

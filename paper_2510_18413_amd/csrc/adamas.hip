@@ -174,7 +174,7 @@ Thresholds scaled(const adamas_config* c, const float* thr) {
 
 template <bool ATTN, int METRIC, int D>
 void launch_select_m(bool paged, dim3 grid, hipStream_t st, const SelectParams& sl) {
-  if constexpr (ATTN && D == 128) {
+  if constexpr (ATTN) {
     if (paged) {
       hipLaunchKernelGGL((select_kernel<kSelThreads, ATTN, METRIC, true, D>), grid, dim3(kSelThreads), 0, st, sl);
       return;
@@ -184,12 +184,12 @@ void launch_select_m(bool paged, dim3 grid, hipStream_t st, const SelectParams& 
 }
 
 // Head dimensions 64 and 256 are built for the method itself (2-bit codes, Eq. 6,
-// contiguous cache); check_config / the paged entry point reject the rest.
+// contiguous and paged caches); check_config rejects the rest.
 template <bool ATTN>
 void launch_select(int metric, int head_dim, bool paged, dim3 grid, hipStream_t st,
                    const SelectParams& sl) {
-  if (head_dim == 64) return launch_select_m<ATTN, kMetricL1, 64>(false, grid, st, sl);
-  if (head_dim == 256) return launch_select_m<ATTN, kMetricL1, 256>(false, grid, st, sl);
+  if (head_dim == 64) return launch_select_m<ATTN, kMetricL1, 64>(paged, grid, st, sl);
+  if (head_dim == 256) return launch_select_m<ATTN, kMetricL1, 256>(paged, grid, st, sl);
   switch (metric) {
     case kMetricL2: launch_select_m<ATTN, kMetricL2, 128>(paged, grid, st, sl); break;
     case kMetricB1: launch_select_m<ATTN, kMetricB1, 128>(paged, grid, st, sl); break;
@@ -264,6 +264,14 @@ void launch_scan_gm(const Plan& pl, dim3 grid, hipStream_t st, const ScanParams&
 
 template <int G, bool FUSED>
 void launch_scan_g(const Plan& pl, dim3 grid, hipStream_t st, const ScanParams& sp) {
+  if constexpr (FUSED) {  // the paged layout is served by the fused step only
+    if (sp.page_table != nullptr) {
+      if (pl.head_dim == 64) return launch_scan_gmp<G, FUSED, kMetricL1, true, 64>(pl, grid, st, sp);
+      if constexpr (G <= 4) {
+        if (pl.head_dim == 256) return launch_scan_gmp<G, FUSED, kMetricL1, true, 256>(pl, grid, st, sp);
+      }
+    }
+  }
   if (pl.head_dim == 64) return launch_scan_gmp<G, FUSED, kMetricL1, false, 64>(pl, grid, st, sp);
   if constexpr (G <= 4) {  // check_config: groups above four are not built at 256
     if (pl.head_dim == 256) return launch_scan_gmp<G, FUSED, kMetricL1, false, 256>(pl, grid, st, sp);
@@ -546,7 +554,6 @@ int adamas_decode_step_paged(const adamas_config* cfg, const void* q, const void
                              size_t workspace_bytes, void* stream, uint32_t stages) {
   if (int rc = check_config(cfg)) return rc;
   if (page_table == nullptr || max_pages < 1) return ADAMAS_ERR_BAD_ARG;
-  if (cfg->head_dim != 128) return ADAMAS_ERR_UNSUPPORTED;  // paged kernels are built for d = 128
   if (stages != ADAMAS_STAGE_ALL && stages != ADAMAS_STAGE_SCAN) return ADAMAS_ERR_BAD_ARG;
   if (page_tokens < 64 || page_tokens > 4096 || (page_tokens & (page_tokens - 1)) != 0)
     return ADAMAS_ERR_UNSUPPORTED;

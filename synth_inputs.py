@@ -220,8 +220,9 @@ def paginate(case: DecodeCase, page_tokens: int, seed: int, spare_pages: int = 3
     max_pages = max(1, max(need))
     order = rng.permutation(n_pages)
     pool = n_pages * page_tokens
-    K = f32_to_bf16_bits(rng.standard_normal((case.Hkv, pool, D), dtype=np.float32))
-    V = f32_to_bf16_bits(rng.standard_normal((case.Hkv, pool, D), dtype=np.float32))
+    d = case.K.shape[-1]
+    K = f32_to_bf16_bits(rng.standard_normal((case.Hkv, pool, d), dtype=np.float32))
+    V = f32_to_bf16_bits(rng.standard_normal((case.Hkv, pool, d), dtype=np.float32))
     table = np.full((case.B, max_pages), -1, dtype=np.int32)
     at = 0
     for b in range(case.B):

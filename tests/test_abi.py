@@ -128,8 +128,8 @@ def test_null_and_misaligned_pointers_rejected():
     a[8] = 2
     assert lib.adamas_decode_step_paged(*a) == -1                             # table too short for max_seq_len
     a = list(pargs)
-    a[0] = ctypes.byref(cfg(head_dim=64))
-    assert lib.adamas_decode_step_paged(*a) == -2                             # paged: d = 128 only
+    a[0] = ctypes.byref(cfg(head_dim=64, variant=2))
+    assert lib.adamas_decode_step_paged(*a) == -2                             # other head dimensions: the method only
     fargs = [p, FAKE, FAKE, FAKE, FAKE, FAKE, 1, FAKE, 1024, FAKE, 1 << 30, None]
     for pos in (1, 2, 3, 4, 5, 7, 9):
         a = list(fargs)

@@ -930,6 +930,58 @@ def test_head_dim_staged_entry_points_and_full_attention(H, oracle, hd):
     assert H.attn_rel_err(got, full) <= H.ATTN_TOL
 
 
+@pytest.mark.parametrize("hd,B,Hq,Hkv,lens,k,page,append", [
+    (64, 2, 8, 2, [4097, 333], 128, 256, True),        # the new token opens a page
+    (64, 3, 8, 1, [0, 5000, 9000], 256, 64, True),     # group 8, an empty sequence
+    (256, 2, 8, 2, [4097, 333], 128, 256, True),
+    (256, 1, 3, 1, [20000], 1024, 1024, False),        # group 3
+])
+def test_head_dim_paged_decode_step_matches_oracle(H, oracle, hd, B, Hq, Hkv, lens, k, page, append):
+    """The paged step at d = 64 / 256 against the oracle's paged step."""
+    import paper_2510_18413_amd as A
+    case = small_case(990 + hd + Hq, B, Hq, Hkv, lens, append=append, head_dim=hd)
+    pc = synth.paginate(case, page, seed=13)
+    cfg = A.Config.make(Hq, Hkv, pc.pool_tokens, thr_k=case.thresholds, head_dim=hd)
+    Kd, Vd, qd = H.dev_bf16(pc.K), H.dev_bf16(pc.V), H.dev_bf16(case.q)
+    knd = None if case.k_new is None else H.dev_bf16(case.k_new)
+    vnd = None if case.v_new is None else H.dev_bf16(case.v_new)
+    codes = torch.zeros(Hkv, pc.pool_tokens, hd // 4, dtype=torch.uint8, device="cuda")
+    A.adamas_encode_keys(cfg, Kd, codes, 0, pc.pool_tokens)
+    table = torch.from_numpy(pc.page_table).cuda()
+    seq_len = torch.from_numpy(case.seq_len).cuda()
+    max_len = max(case.max_seq_len, 1)
+    ws = torch.full((A.adamas_workspace_bytes(cfg, B, max_len, k),), 0xA5, dtype=torch.uint8,
+                    device="cuda")
+    out = torch.full((B, Hq, hd), float("nan"), device="cuda")
+    idx = torch.full((B, Hq, k), -7, dtype=torch.int32, device="cuda")
+    A.adamas_decode_step_paged(cfg, qd, Kd, Vd, codes, table, page, seq_len, k, out, max_len, ws,
+                               k_new=knd, v_new=vnd, idx_out=idx)
+    torch.cuda.synchronize()
+    Kr, Vr = pc.K.copy(), pc.V.copy()
+    with oracle.head_dim(hd):
+        _, rows = oracle.encode(Kr, case.thresholds)
+        ref_out, ref_idx = oracle.decode_step_paged(
+            case.q, Kr, Vr, rows, pc.page_table, page, case.seq_len, k, case.thresholds,
+            case.thresholds, 1.0 / np.sqrt(hd), k_new=case.k_new, v_new=case.v_new)
+    assert np.array_equal(idx.cpu().numpy(), ref_idx)
+    assert H.attn_rel_err(out.cpu().numpy(), ref_out) <= H.ATTN_TOL
+    assert np.array_equal(H.host_u16(Kd), Kr) and np.array_equal(H.host_u16(Vd), Vr)
+    assert np.array_equal(codes.cpu().numpy(), rows)
+
+
+@pytest.mark.parametrize("hd", [64, 256])
+def test_head_dim_without_hadamard(H, oracle, hd):
+    """The no-transform ablation is a run-time switch of the same kernels: also at d = 64 / 256."""
+    import paper_2510_18413_amd as A
+    case = small_case(995 + hd, 2, 4, 2, [3000, 4100], append=True, head_dim=hd)
+    d = H.DeviceCase(case, 96, variant=A.VARIANT_NO_HADAMARD)
+    out, idx = d.decode_step()
+    ref = H.oracle_step(case, 96, want_dist=False, variant=A.VARIANT_NO_HADAMARD)
+    assert np.array_equal(idx, ref["idx"])
+    assert H.attn_rel_err(out, ref["out"]) <= H.ATTN_TOL
+    assert np.array_equal(d.codes.cpu().numpy(), ref["rows"])
+
+
 def test_head_dim_options_that_are_not_built_are_refused(H, oracle):
     import paper_2510_18413_amd as A
     for hd, kw, group in ((64, dict(variant=A.VARIANT_L2), 1), (256, dict(variant=A.VARIANT_L2), 1),
