@@ -21,6 +21,8 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E peak
+MIN_SWEEPS = 200         # timed graph replays of the fused step (each one sweep over all layers)
+MIN_REPLAYS = 20         # timed graph replays of every secondary leg (scan, stream read, dense, ...)
 
 WORKLOADS = {
     # name: (B, Hq, Hkv, context, default k, append, ragged)
@@ -270,39 +272,49 @@ def main():
                 step(i, stages)
         return g
 
-    def timed(stages, steps, warmup):
-        """Returns (ms per step from HIP events, ms per step wall, per-sweep event ms list)."""
+    def sweep_plan(steps, warmup, min_sweeps):
+        """Whole sweeps only: (timed sweeps, warm-up sweeps) for a request of `steps` / `warmup`
+        single steps; never fewer than `min_sweeps` timed sweeps."""
+        return max(min_sweeps, -(-steps // n_layers)), max(3, -(-warmup // n_layers))
+
+    def replay_timed(g, sweeps, warm_sweeps, per_replay):
+        """Replays graph `g` (per_replay launches of the thing measured) `sweeps` times with a
+        HIP event after every replay, on the stream the graph runs on.  Returns the sorted
+        per-launch times in us, one per replay."""
+        for _ in range(warm_sweeps):
+            g.replay()
+        torch.cuda.synchronize()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(sweeps + 1)]
+        ev[0].record()
+        for s in range(sweeps):
+            g.replay()
+            ev[s + 1].record()
+        torch.cuda.synchronize()
+        return sorted(ev[s].elapsed_time(ev[s + 1]) * 1e3 / per_replay for s in range(sweeps))
+
+    def pct(sorted_us):
+        n = len(sorted_us)
+        return [round(sorted_us[n // 10], 3), round(sorted_us[n // 2], 3),
+                round(sorted_us[(n * 9) // 10], 3)]
+
+    def timed(stages, steps, warmup, min_sweeps=MIN_SWEEPS):
+        """Returns (sorted us per step of every timed sweep, steps timed).  Graph mode times whole
+        sweeps over the rotating layers, whatever `steps` asks for; --eager times `steps` Python
+        launches once."""
         if args.eager:
             for i in range(warmup):
                 step(i, stages)
             torch.cuda.synchronize()
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            t0 = time.perf_counter()
             e0.record()
             for i in range(steps):
                 step(i, stages)
             e1.record()
             torch.cuda.synchronize()
-            wall = (time.perf_counter() - t0) * 1e3
-            return e0.elapsed_time(e1) / steps, wall / steps, []
+            return [e0.elapsed_time(e1) * 1e3 / steps], steps
         g = make_graph(stages)
-        sweeps, rem = divmod(steps, n_layers)
-        for _ in range(max(1, warmup // n_layers)):
-            g.replay()
-        torch.cuda.synchronize()
-        ev = [torch.cuda.Event(enable_timing=True) for _ in range(sweeps + 2)]
-        t0 = time.perf_counter()
-        ev[0].record()
-        for s in range(sweeps):
-            g.replay()
-            ev[s + 1].record()
-        for i in range(rem):
-            step(i, stages)
-        ev[sweeps + 1].record()
-        torch.cuda.synchronize()
-        wall = (time.perf_counter() - t0) * 1e3
-        per_sweep = [ev[s].elapsed_time(ev[s + 1]) for s in range(sweeps)]
-        return ev[0].elapsed_time(ev[sweeps + 1]) / steps, wall / steps, per_sweep
+        sweeps, warm = sweep_plan(steps, warmup, min_sweeps)
+        return replay_timed(g, sweeps, warm, n_layers), sweeps * n_layers
 
     if args.calibrate_copy:
         # bitwise_not: one read and one write of 256 MiB, under a kernel name that is easy to
@@ -316,38 +328,35 @@ def main():
 
     # ------------------------------------------------------------------ the timed region
     if args.scan_only:
-        ms_scan, _, _ = timed(A.STAGE_SCAN, args.steps, args.warmup)
-        print(json.dumps({"scan_us_per_launch": round(ms_scan * 1e3, 3), "config": args.config}))
+        us, n = timed(A.STAGE_SCAN, args.steps, args.warmup)
+        print(json.dumps({"scan_us_per_launch": round(us[len(us) // 2], 3), "timed_launches": n,
+                          "config": args.config}))
         return
-    ms_evt, ms_wall, per_sweep = timed(None, args.steps, args.warmup)
-    us_step = ms_wall * 1e3
+    step_us, timed_steps = timed(None, args.steps, args.warmup)
+    us_step = step_us[len(step_us) // 2]            # median over the timed sweeps
     # dominant kernel alone (distance scan with fused query encode), same rotation
-    ms_scan, _, _ = timed(A.STAGE_SCAN, max(n_layers, args.steps // 4), args.warmup // 4)
+    scan_us, scan_launches = timed(A.STAGE_SCAN, args.steps // 4, args.warmup // 4, MIN_REPLAYS * 2)
+    us_scan = sum(scan_us) / len(scan_us)           # average launch duration (compare rocprofv3)
 
-    # achievable ceiling: a read-only streaming kernel over the same code planes, same rotation
-    sink = torch.zeros(4, dtype=torch.int32, device=dev)
-
-    def stream_graph():
+    def graph_us(fn, reps=MIN_REPLAYS):
+        """Sorted us per call of fn(layer_dict) over the rotating layers: one graph of a sweep,
+        `reps` timed replays with a HIP event after each."""
         for d in layers:
-            A.adamas_stream_read(d["codes"].view(-1), sink)
+            fn(d)
         torch.cuda.synchronize()
         g = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g):
             for d in layers:
-                A.adamas_stream_read(d["codes"].view(-1), sink)
-        return g
-    sg = stream_graph()
-    for _ in range(3):
-        sg.replay()
-    torch.cuda.synchronize()
-    s0, s1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    n_rep = max(1, args.steps // (4 * n_layers))
-    s0.record()
-    for _ in range(n_rep):
-        sg.replay()
-    s1.record()
-    torch.cuda.synchronize()
-    stream_us = s0.elapsed_time(s1) * 1e3 / (n_rep * n_layers)
+                fn(d)
+        return replay_timed(g, reps, 3, len(layers))
+
+    def mean(xs):
+        return sum(xs) / len(xs)
+
+    # achievable ceiling: a read-only streaming kernel over the same code planes, same rotation
+    sink = torch.zeros(4, dtype=torch.int32, device=dev)
+    stream_us = mean(graph_us(lambda d: A.adamas_stream_read(d["codes"].view(-1), sink),
+                              MIN_REPLAYS * 2))
     stream_gbps = Hkv * pool * row_bytes / stream_us / 1e3
 
     # comparison point: dense decode attention (Eq. 1 over every cached row) on the same layers
@@ -357,48 +366,9 @@ def main():
         full_ws = torch.empty(A.adamas_full_attn_workspace_bytes(cfg, B, max_len), dtype=torch.uint8,
                               device=dev)
         full_out = torch.zeros(B, Hq, HD, device=dev)
-
-        def full_graph():
-            for d in layers:
-                A.adamas_full_attn(cfg, d["q"], d["K"], d["V"], seq_start, seq_len, full_out, max_len,
-                                   full_ws)
-            torch.cuda.synchronize()
-            g = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(g):
-                for d in layers:
-                    A.adamas_full_attn(cfg, d["q"], d["K"], d["V"], seq_start, seq_len, full_out,
-                                       max_len, full_ws)
-            return g
-        fg = full_graph()
-        fg.replay()
-        torch.cuda.synchronize()
-        n_rep = max(1, min(20, args.steps // (16 * n_layers)))
-        s0.record()
-        for _ in range(n_rep):
-            fg.replay()
-        s1.record()
-        torch.cuda.synchronize()
-        full_us = s0.elapsed_time(s1) * 1e3 / (n_rep * n_layers)
+        full_us = mean(graph_us(lambda d: A.adamas_full_attn(
+            cfg, d["q"], d["K"], d["V"], seq_start, seq_len, full_out, max_len, full_ws)))
         full_bytes = Hkv * int(lens.sum()) * 4 * HD
-
-    def graph_us(fn, reps=8):
-        """us per call of fn(layer_dict) over the rotating layers, graph replay, HIP events."""
-        for d in layers:
-            fn(d)
-        torch.cuda.synchronize()
-        g = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(g):
-            for d in layers:
-                fn(d)
-        g.replay()
-        torch.cuda.synchronize()
-        a, b_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record()
-        for _ in range(reps):
-            g.replay()
-        b_.record()
-        torch.cuda.synchronize()
-        return a.elapsed_time(b_) * 1e3 / (reps * len(layers))
 
     # the stand-alone entry points, stage by stage (contiguous layout), next to the fused step
     stage_us = None
@@ -407,23 +377,23 @@ def main():
         idx_s = torch.empty(B, Hq, k, dtype=torch.int32, device=dev)
         out_s = torch.empty(B, Hq, HD, device=dev)
         stage_us = {
-            "encode_query": graph_us(lambda d: A.adamas_encode_query(cfg, d["q"], qcodes)),
-            "select_topk": graph_us(lambda d: A.adamas_select_topk(
-                cfg, qcodes, d["codes"], seq_start, seq_len, k, idx_s, max_len, ws)),
-            "sparse_attn": graph_us(lambda d: A.adamas_sparse_attn(
-                cfg, d["q"], d["K"], d["V"], seq_start, idx_s, out_s, max_len, ws)),
+            "encode_query": mean(graph_us(lambda d: A.adamas_encode_query(cfg, d["q"], qcodes))),
+            "select_topk": mean(graph_us(lambda d: A.adamas_select_topk(
+                cfg, qcodes, d["codes"], seq_start, seq_len, k, idx_s, max_len, ws))),
+            "sparse_attn": mean(graph_us(lambda d: A.adamas_sparse_attn(
+                cfg, d["q"], d["K"], d["V"], seq_start, idx_s, out_s, max_len, ws))),
         }
         stage_us = {n: round(v, 2) for n, v in stage_us.items()}
         stage_us["sum"] = round(sum(stage_us.values()), 2)
 
     # one layer over and over: its 32 MiB of codes and the workspace stay in the 256 MB
     # Infinity Cache, so this is NOT the HBM figure
-    resident_us = graph_us(lambda d: step(0))      # n_layers launches per replay, all on layer 0
+    resident_us = mean(graph_us(lambda d: step(0)))   # n_layers launches per replay, all on layer 0
 
     total_bytes, code_bytes = algorithmic_bytes(B, Hq, Hkv, [int(x) for x in lens], k, append,
                                                row_bytes, HD)
     gbps_step = total_bytes / (us_step * 1e-6) / 1e9
-    gbps_scan = code_bytes / (ms_scan * 1e-3) / 1e9
+    gbps_scan = code_bytes / (us_scan * 1e-6) / 1e9
 
     traffic = None
     prof = os.path.join(ROOT, "profiles", "scan_kernel_%s_pmc.md" % args.config)
@@ -440,11 +410,12 @@ def main():
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": round(ms_wall, 6),
+        "timed_steps": timed_steps,
+        "ms_per_step": round(us_step * 1e-3, 6),
         "higher_is_better": False,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "u32 popcount (select) + f32 (attention) on bf16 K/V",
+        "dtype": "f64 transform sums and attention scores, u32 popcount distances, f32 softmax weights and accumulation, on bf16 q/K/V",
         "data": "synthetic",
         "config": {
             "workload": wl["text"].replace("head_dim 128", "head_dim %d" % HD) + ", budget k=%d, %d rotating layer caches" % (k, n_layers),
@@ -452,12 +423,17 @@ def main():
             "sum_context": int(lens.sum()), "k": k, "append": append, "variant": args.variant,
             "code_bits": bits, "head_dim": HD,
             "layout": "paged, %d-token pages, random placement" % page if page else "contiguous",
-            "launch": "eager" if args.eager else "hipGraph of one %d-layer sweep" % n_layers,
+            "launch": ("eager: %d launches from Python between two HIP events" % timed_steps)
+            if args.eager else
+            ("HIP graph of one %d-layer sweep, replayed %d times, a HIP event after every replay; "
+             "value = median sweep / %d" % (n_layers, timed_steps // n_layers, n_layers)),
         },
         "achieved_hbm_GBps": round(gbps_step, 1),
         "hbm_frac_whole_step": round(gbps_step / HBM_PEAK_GBPS, 4),
         "algorithmic_bytes_per_step": total_bytes,
-        "us_per_step_hip_events": round(ms_evt * 1e3, 3),
+        "us_per_layer_p10_p50_p90": pct(step_us) if len(step_us) > 1 else None,
+        "us_per_layer_mean": round(sum(step_us) / len(step_us), 3),
+        "library_build_id": A.build_id(),
         "roofline": {
             "kernel": "scan_kernel (Manhattan-distance scan + fused query encode)",
             "bound": "hbm",
@@ -467,7 +443,9 @@ def main():
             "frac": round(gbps_scan / HBM_PEAK_GBPS, 4),
             "traffic": traffic,
             "algorithmic_bytes_per_launch": code_bytes,
-            "us_per_launch": round(ms_scan * 1e3, 3),
+            "us_per_launch": round(us_scan, 3),
+            "timed_launches": scan_launches,
+            "us_per_launch_p10_p50_p90": pct(scan_us) if len(scan_us) > 1 else None,
             "stream_read_same_planes": {"us_per_launch": round(stream_us, 3),
                                         "GBps": round(stream_gbps, 1),
                                         "bytes_per_launch": Hkv * pool * row_bytes},
@@ -485,11 +463,6 @@ def main():
                                     "GBps": round(full_bytes / full_us / 1e3, 1),
                                     "hbm_frac": round(full_bytes / full_us / 1e3 / HBM_PEAK_GBPS, 4),
                                     "speedup_of_sparse_step": round(full_us / us_step, 2)}
-    if per_sweep:
-        ps = sorted(x / n_layers * 1e3 for x in per_sweep)
-        result["us_per_layer_p10_p50_p90"] = [round(ps[len(ps) // 10], 3), round(ps[len(ps) // 2], 3),
-                                              round(ps[(len(ps) * 9) // 10], 3)]
-
     # ------------------------------------------------------------------ oracle on the host
     if not args.no_cpu_baseline:
         import oracle

@@ -148,6 +148,10 @@ typedef struct adamas_config {
 /* Human-readable name of a status code; never NULL. */
 const char *adamas_status_string(int status);
 
+/* Identifies the build: a hash of the sources and compiler flags the library
+ * was made from ("unknown" when built without one).  Never NULL. */
+const char *adamas_build_id(void);
+
 /* hipError_t (as int) of the launch that made the last call on this thread
  * return ADAMAS_ERR_HIP; 0 if none. */
 int adamas_last_hip_error(void);

@@ -23,6 +23,7 @@ from .binding import (  # noqa: F401
     adamas_status_string,
     adamas_stream_read,
     adamas_workspace_bytes,
+    build_id,
     library,
     library_path,
 )

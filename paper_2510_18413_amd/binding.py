@@ -16,6 +16,7 @@ from . import build as _build
 
 EXPORTED_SYMBOLS = (
     "adamas_status_string",
+    "adamas_build_id",
     "adamas_last_hip_error",
     "adamas_workspace_bytes",
     "adamas_encode_keys",
@@ -87,19 +88,22 @@ def library_path():
 
 
 def library() -> ctypes.CDLL:
-    """Loads libadamas.so (building it first only if it does not exist)."""
+    """Loads libadamas.so, building it first (in a child process, before anything here touches
+    the GPU library) when it is missing or was built from sources other than the tree's."""
     global _lib
     if _lib is None:
         # torch first: the process then has one HIP runtime (the one torch ships), and this
         # library, which only needs the public HIP launch API, binds to it.
         import torch  # noqa: F401
-        if not _build.LIB.exists():
+        if _build.is_stale():
             _build.build()
         lib = ctypes.CDLL(str(_build.LIB))
         vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
         cfgp = ctypes.POINTER(Config)
         lib.adamas_status_string.restype = ctypes.c_char_p
         lib.adamas_status_string.argtypes = [ctypes.c_int]
+        lib.adamas_build_id.restype = ctypes.c_char_p
+        lib.adamas_build_id.argtypes = []
         lib.adamas_last_hip_error.restype = ctypes.c_int
         lib.adamas_last_hip_error.argtypes = []
         lib.adamas_workspace_bytes.restype = sz
@@ -135,6 +139,11 @@ def library() -> ctypes.CDLL:
 
 def adamas_status_string(status: int) -> str:
     return library().adamas_status_string(int(status)).decode()
+
+
+def build_id() -> str:
+    """Hash of the sources the loaded library was built from."""
+    return library().adamas_build_id().decode()
 
 
 def adamas_workspace_bytes(cfg: Config, batch: int, max_seq_len: int, k: int) -> int:

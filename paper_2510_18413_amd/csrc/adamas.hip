@@ -352,6 +352,15 @@ const char* adamas_status_string(int status) {
   }
 }
 
+#ifndef ADAMAS_BUILD_ID
+#define ADAMAS_BUILD_ID "unknown"
+#endif
+const char* adamas_build_id(void) {
+  // the tag lets a build script read the id out of the file without loading it
+  static const char tagged[] = "ADAMAS_BUILD_ID=" ADAMAS_BUILD_ID;
+  return tagged + sizeof("ADAMAS_BUILD_ID=") - 1;
+}
+
 int adamas_last_hip_error(void) { return g_last_hip_error; }
 
 size_t adamas_workspace_bytes(const adamas_config* cfg, int32_t batch, int64_t max_seq_len,
