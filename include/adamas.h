@@ -239,6 +239,31 @@ int adamas_decode_step(const adamas_config *cfg, const void *q,
                        void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * adamas_decode_step for callers that cannot allocate device memory or pass a
+ * workspace along: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  Same arguments, results and errors as
+ * adamas_decode_step, minus `workspace`: the kernels' scratch (distances, tile
+ * histograms, attention partials) lives in a device array of
+ * ADAMAS_STATIC_SCRATCH_BYTES that is part of the library's code object; every
+ * GPU the library runs on holds its own copy until the process ends.  The call
+ * allocates and frees nothing.  Sizes whose scratch would exceed the array
+ * (adamas_workspace_bytes(cfg, batch, max_seq_len, k) >
+ * ADAMAS_STATIC_SCRATCH_BYTES) -> ADAMAS_ERR_WORKSPACE, nothing enqueued.
+ * All calls on one GPU share that GPU's array: two calls whose work may overlap
+ * on one GPU (different streams, different threads) race; calls on one stream
+ * are ordered and safe.  The first call on each device looks the array's
+ * address up (a HIP runtime query, no allocation); make that call outside a
+ * graph capture.
+ */
+#define ADAMAS_STATIC_SCRATCH_BYTES (16u << 20)
+int adamas_decode_step_static(const adamas_config *cfg, const void *q,
+                              const void *k_new, const void *v_new, void *K,
+                              void *V, void *codes, const int64_t *seq_start,
+                              const int32_t *seq_len, int32_t batch, int32_t k,
+                              float *out, int32_t *idx_out, int64_t max_seq_len,
+                              void *stream);
+
+/*
  * Profiling hook: adamas_decode_step cut at its one internal kernel
  * boundary.  `stages` is a bit mask; ADAMAS_STAGE_ALL is exactly
  * adamas_decode_step.  ADAMAS_STAGE_SCAN runs Alg. 1 up to the distance

@@ -26,6 +26,7 @@ EXPORTED_SYMBOLS = (
     "adamas_sparse_attn",
     "adamas_decode_step",
     "adamas_decode_step_stages",
+    "adamas_decode_step_static",
     "adamas_stream_read",
     "adamas_decode_step_paged",
     "adamas_full_attn_workspace_bytes",
@@ -37,6 +38,7 @@ CODE_ROW_BYTES = 32
 VARIANT_NO_HADAMARD = 1
 VARIANT_L2 = 2
 STAGE_SCAN, STAGE_SELECT_ATTN, STAGE_ALL = 1, 2, 3
+STATIC_SCRATCH_BYTES = 16 << 20
 
 
 class AdamasError(RuntimeError):
@@ -121,6 +123,9 @@ def library() -> ctypes.CDLL:
         lib.adamas_decode_step.restype = ctypes.c_int
         lib.adamas_decode_step.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp,
                                            i64, vp, sz, vp]
+        lib.adamas_decode_step_static.restype = ctypes.c_int
+        lib.adamas_decode_step_static.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp,
+                                                  vp, i64, vp]
         lib.adamas_decode_step_paged.restype = ctypes.c_int
         lib.adamas_decode_step_paged.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp,
                                                  i32, i32, vp, vp, i64, vp, sz, vp,
@@ -313,6 +318,28 @@ def adamas_decode_step(cfg: Config, q, K, V, codes, seq_start, seq_len, k: int, 
     adamas_decode_step_stages(cfg, q, K, V, codes, seq_start, seq_len, k, out, max_seq_len,
                               workspace, k_new=k_new, v_new=v_new, idx_out=idx_out, stream=stream,
                               stages=None)
+
+
+def adamas_decode_step_static(cfg: Config, q, K, V, codes, seq_start, seq_len, k: int, out,
+                              max_seq_len: int, k_new=None, v_new=None, idx_out=None,
+                              stream=None) -> None:
+    """adamas_decode_step on the library's own static scratch array: no workspace argument."""
+    import torch
+    batch = q.shape[0]
+    hkv, pool = cfg.num_kv_heads, cfg.pool_tokens
+    rc = library().adamas_decode_step_static(
+        ctypes.byref(cfg), _ptr(q, torch.bfloat16, "q", (batch, cfg.num_q_heads, cfg.head_dim)),
+        _ptr(k_new, torch.bfloat16, "k_new", (batch, hkv, cfg.head_dim), optional=True),
+        _ptr(v_new, torch.bfloat16, "v_new", (batch, hkv, cfg.head_dim), optional=True),
+        _ptr(K, torch.bfloat16, "K", (hkv, pool, cfg.head_dim)),
+        _ptr(V, torch.bfloat16, "V", (hkv, pool, cfg.head_dim)),
+        _ptr(codes, torch.uint8, "codes", (hkv, pool, cfg.code_row_bytes)),
+        _ptr(seq_start, torch.int64, "seq_start", (batch,)),
+        _ptr(seq_len, torch.int32, "seq_len", (batch,)), batch, k,
+        _ptr(out, torch.float32, "out", (batch, cfg.num_q_heads, cfg.head_dim)),
+        _ptr(idx_out, torch.int32, "idx_out", (batch, cfg.num_q_heads, k), optional=True),
+        max_seq_len, _stream(stream))
+    _check(rc, "adamas_decode_step_static")
 
 
 def adamas_decode_step_stages(cfg: Config, q, K, V, codes, seq_start, seq_len, k: int, out,

@@ -4,6 +4,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cmath>
 #include <cstdint>
 
@@ -12,11 +13,40 @@
 #include "select_attn.hpp"
 #include "full_attn.hpp"
 
+// Scratch of adamas_decode_step_static.  In host code this name is only a handle
+// for hipGetSymbolAddress, never a device address: kernels get the looked-up
+// pointer (static_scratch()).
+static __device__ __align__(256) unsigned char scratch[ADAMAS_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 using namespace adamas;
 
 thread_local int g_last_hip_error = 0;
+
+// Device address of `scratch` on the current device (every GPU holds its own
+// copy of the array at its own address), looked up once per device.  Returns
+// nullptr and records the HIP error if the runtime refuses.
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+void* static_scratch() {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    g_last_hip_error = (int)(e != hipSuccess ? e : hipErrorInvalidDevice);
+    return nullptr;
+  }
+  void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (ptr != nullptr) return ptr;
+  e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));  // same answer from every thread
+  if (e != hipSuccess || ptr == nullptr) {
+    g_last_hip_error = (int)(e != hipSuccess ? e : hipErrorInvalidSymbol);
+    return nullptr;
+  }
+  g_scratch_ptr[dev].store(ptr, std::memory_order_release);
+  return ptr;
+}
 
 constexpr int kTargetWorkgroups = 256;  // one per compute unit of an MI355X
 constexpr int kSelThreads = 256;
@@ -541,6 +571,25 @@ int adamas_decode_step(const adamas_config* cfg, const void* q, const void* k_ne
   return adamas_decode_step_stages(cfg, q, k_new, v_new, K, V, codes, seq_start, seq_len, batch, k,
                                    out, idx_out, max_seq_len, workspace, workspace_bytes, stream,
                                    ADAMAS_STAGE_ALL);
+}
+
+int adamas_decode_step_static(const adamas_config* cfg, const void* q, const void* k_new,
+                              const void* v_new, void* K, void* V, void* codes,
+                              const int64_t* seq_start, const int32_t* seq_len, int32_t batch,
+                              int32_t k, float* out, int32_t* idx_out, int64_t max_seq_len,
+                              void* stream) {
+  if (int rc = check_config(cfg)) return rc;
+  if (int rc = check_sizes(batch, max_seq_len, k)) return rc;
+  if (make_plan(cfg, batch, max_seq_len, k).total > (size_t)ADAMAS_STATIC_SCRATCH_BYTES)
+    return ADAMAS_ERR_WORKSPACE;
+  if (!q || !K || !V || !codes || !seq_start || !seq_len || !out) return ADAMAS_ERR_BAD_ARG;
+  void* ws = static_scratch();
+  if (ws == nullptr) return ADAMAS_ERR_HIP;
+  // Nothing in the scratch has to start at zero: the scan kernel clears the
+  // arrival counters it hands to the select kernel, everything else is written
+  // before it is read.
+  return adamas_decode_step(cfg, q, k_new, v_new, K, V, codes, seq_start, seq_len, batch, k, out,
+                            idx_out, max_seq_len, ws, (size_t)ADAMAS_STATIC_SCRATCH_BYTES, stream);
 }
 
 int adamas_decode_step_stages(const adamas_config* cfg, const void* q, const void* k_new,
