@@ -60,8 +60,8 @@
  *     ADAMAS_ERR_BAD_ARG      null pointer, non-positive size, heads not
  *                             divisible, thresholds not strictly increasing,
  *                             non-finite scale, misaligned pool, ...
- *     ADAMAS_ERR_UNSUPPORTED  head_dim not 64 / 128 / 256 (or an option
- *                             not built for it, see below), k > ADAMAS_MAX_K,
+ *     ADAMAS_ERR_UNSUPPORTED  head_dim not one of those listed below,
+ *                             k > ADAMAS_MAX_K,
  *                             group size > ADAMAS_MAX_GROUP,
  *                             max_seq_len > ADAMAS_MAX_SEQ_LEN
  *     ADAMAS_ERR_WORKSPACE    workspace_bytes < adamas_workspace_bytes(...)
@@ -123,14 +123,12 @@ extern "C" {
 
 /*
  * Head dimension d.  The text above and below is written for d = 128, the
- * head dimension of the paper's models.  head_dim 64 and 256 run the method
- * itself (Hadamard transform of order d, 2-bit codes, Eq. 6, with or without
- * ADAMAS_VARIANT_NO_HADAMARD, contiguous or paged cache) through every entry
- * point: read d for 128 and d/4 for the 32-byte code row (d/32 words of 64
- * bits, same bit placement), distances 0..3d, sm_scale 0 meaning 1/sqrt(d),
- * thresholds compared with x H / sqrt(d).  With them, ADAMAS_VARIANT_L2,
- * code_bits 1 or 3, and at d = 256 a group above 4 return
- * ADAMAS_ERR_UNSUPPORTED.
+ * head dimension of the paper's models.  head_dim 64 and 256 run everything
+ * as well (Hadamard transform of order d, every ablation switch, contiguous
+ * or paged cache, every entry point): read d for 128 and d/4 for the 32-byte
+ * code row (d/32 words of 64 bits, same bit placement; 16 * code_bits * d/128
+ * bytes with the code-width switch), distances 0..3d, sm_scale 0 meaning
+ * 1/sqrt(d), thresholds compared with x H / sqrt(d).
  */
 typedef struct adamas_config {
   int32_t head_dim;      /* 128; or 64, 256 (see above) */

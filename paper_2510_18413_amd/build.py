@@ -1,27 +1,45 @@
-"""Builds libadamas.so (HIP kernels + C ABI) in-tree with hipcc for gfx950."""
+"""Builds libadamas.so (HIP kernels + C ABI) in-tree with hipcc for gfx950.
+
+The kernels of every (head dimension, metric) pair are instantiated in an object file of their
+own (csrc/kernels_inst.hip compiled once per pair), so the pairs compile in parallel; adamas.hip
+holds the C ABI and dispatches through the tables those objects export.
+"""
 
 from __future__ import annotations
 
 import hashlib
 import os
+import re
 import subprocess
+from concurrent.futures import ThreadPoolExecutor
 from pathlib import Path
 
 PKG = Path(__file__).resolve().parent
 ROOT = PKG.parent
-SRC = PKG / "csrc" / "adamas.hip"
+CSRC = PKG / "csrc"
+API_SRC = CSRC / "adamas.hip"
+INST_SRC = CSRC / "kernels_inst.hip"
 LIB = PKG / "libadamas.so"
+OBJ_DIR = PKG / "_build"
 
 HIPCC_FLAGS = [
-    "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
+    "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",
     # keep the compiler from forming packed-fp32 instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function",
 ]
+METRICS = 4     # kMetricL1, kMetricL2, kMetricB1, kMetricB3 (csrc/device_utils.hpp)
+
+
+def head_dims():
+    """The head dimensions csrc/kernel_set.hpp lists (ADAMAS_FOR_EACH_HEAD_DIM)."""
+    text = (CSRC / "kernel_set.hpp").read_text()
+    line = re.search(r"#define ADAMAS_FOR_EACH_HEAD_DIM\(X\)(.*)", text).group(1)
+    return [int(d) for d in re.findall(r"X\((\d+)\)", line)]
 
 
 def sources():
-    return [SRC] + sorted((PKG / "csrc").glob("*.hpp")) + [ROOT / "include" / "adamas.h"]
+    return sorted(CSRC.glob("*.hip")) + sorted(CSRC.glob("*.hpp")) + [ROOT / "include" / "adamas.h"]
 
 
 BUILD_ID_TAG = b"ADAMAS_BUILD_ID="
@@ -52,16 +70,49 @@ def is_stale() -> bool:
     return built_id() != source_id()
 
 
-def build(verbose: bool = False, extra_flags=()) -> Path:
-    """Compiles unconditionally; returns the path of the shared library."""
+def build(verbose: bool = False, extra_flags=(), jobs: int = 0) -> Path:
+    """Compiles everything unconditionally; returns the path of the shared library."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    tmp = LIB.with_suffix(".so.tmp%d" % os.getpid())
-    cmd = [hipcc] + HIPCC_FLAGS + list(extra_flags) + ['-DADAMAS_BUILD_ID="%s"' % source_id()] + [
-        "-I", str(ROOT / "include"), "-I", str(PKG / "csrc"), "-o", str(tmp), str(SRC)]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.run(cmd, check=True)
-    os.replace(tmp, LIB)
+    jobs = jobs or min(16, os.cpu_count() or 4)
+    OBJ_DIR.mkdir(exist_ok=True)
+    tag = ".tmp%d" % os.getpid()
+    common = [hipcc] + HIPCC_FLAGS + list(extra_flags) + [
+        "-I", str(ROOT / "include"), "-I", str(CSRC), "-c"]
+    units = [(OBJ_DIR / ("adamas%s.o" % tag),
+              common + ['-DADAMAS_BUILD_ID="%s"' % source_id(), str(API_SRC)])]
+    for d in head_dims():
+        for m in range(METRICS):
+            units.append((OBJ_DIR / ("kernels_d%d_m%d%s.o" % (d, m, tag)),
+                          common + ["-DADAMAS_INST_D=%d" % d, "-DADAMAS_INST_METRIC=%d" % m,
+                                    str(INST_SRC)]))
+
+    def compile_one(unit):
+        obj, cmd = unit
+        cmd = cmd + ["-o", str(obj)]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        # hipcc's host pass does not know the packed-fp32 feature and says so: harmless
+        out = "\n".join(l for l in r.stdout.splitlines() if "packed-fp32-ops" not in l)
+        if r.returncode != 0:
+            raise RuntimeError("hipcc failed (%d): %s\n%s" % (r.returncode, " ".join(cmd), out))
+        if out.strip():
+            print(out, flush=True)
+        return obj
+
+    try:
+        with ThreadPoolExecutor(max_workers=jobs) as pool:
+            objs = list(pool.map(compile_one, units))
+        tmp = LIB.with_suffix(".so" + tag)
+        link = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", str(tmp)] + [str(o) for o in objs]
+        if verbose:
+            print(" ".join(link), flush=True)
+        subprocess.run(link, check=True)
+        os.replace(tmp, LIB)
+    finally:
+        for obj, _ in units:
+            if obj.exists():
+                obj.unlink()
     return LIB
 
 

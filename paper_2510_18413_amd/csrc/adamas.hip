@@ -8,10 +8,7 @@
 #include <cmath>
 #include <cstdint>
 
-#include "encode.hpp"
-#include "scan.hpp"
-#include "select_attn.hpp"
-#include "full_attn.hpp"
+#include "kernel_set.hpp"
 
 // Scratch of adamas_decode_step_static.  In host code this name is only a handle
 // for hipGetSymbolAddress, never a device address: kernels get the looked-up
@@ -49,7 +46,6 @@ void* static_scratch() {
 }
 
 constexpr int kTargetWorkgroups = 256;  // one per compute unit of an MI355X
-constexpr int kSelThreads = 256;
 constexpr int kSegGranule = 4096;
 constexpr double kLog2e = 1.4426950408889634;
 
@@ -77,16 +73,25 @@ int metric_of(const adamas_config* c) {
   return (c->variant & ADAMAS_VARIANT_L2) ? kMetricL2 : kMetricL1;
 }
 
+// uint16 per stored tile histogram (Dist<METRIC, D>::kStride for run-time arguments)
 size_t hist_stride_of(int metric, int head_dim) {
-  if (head_dim == 64) return Dist<kMetricL1, 64>::kStride;
-  if (head_dim == 256) return Dist<kMetricL1, 256>::kStride;
-  switch (metric) {
-    case kMetricL2: return Dist<kMetricL2>::kStride;
-    case kMetricB1: return Dist<kMetricB1>::kStride;
-    case kMetricB3: return Dist<kMetricB3>::kStride;
-    default: return Dist<kMetricL1>::kStride;
-  }
+  const int per_dim = metric == kMetricL1 ? 3 : metric == kMetricL2 ? 9 : metric == kMetricB1 ? 1 : 7;
+  const int bins = per_dim * head_dim + 1;
+  return (size_t)((bins + 7) / 8 * 8);
 }
+
+// The kernels of a (head dimension, metric) pair; nullptr if that pair is not built.
+const KernelSet* find_kernel_set(int head_dim, int metric) {
+#define ADAMAS_SET_CASE(D, M) \
+  if (head_dim == D && metric == M) return &kernel_set<D, M>();
+#define ADAMAS_SET_CASES(D) ADAMAS_FOR_EACH_METRIC(ADAMAS_SET_CASE, D)
+  ADAMAS_FOR_EACH_HEAD_DIM(ADAMAS_SET_CASES)
+#undef ADAMAS_SET_CASES
+#undef ADAMAS_SET_CASE
+  return nullptr;
+}
+
+bool head_dim_built(int head_dim) { return find_kernel_set(head_dim, kMetricL1) != nullptr; }
 
 int check_config(const adamas_config* c) {
   if (c == nullptr) return ADAMAS_ERR_BAD_ARG;
@@ -103,11 +108,7 @@ int check_config(const adamas_config* c) {
     }
   }
   if (!std::isfinite(c->sm_scale) || c->sm_scale < 0.f) return ADAMAS_ERR_BAD_ARG;
-  if (c->head_dim != 64 && c->head_dim != 128 && c->head_dim != 256) return ADAMAS_ERR_UNSUPPORTED;
-  if (c->head_dim != 128) {  // other head dimensions: the method itself only
-    if ((c->variant & ADAMAS_VARIANT_L2) || code_bits(c) != 2) return ADAMAS_ERR_UNSUPPORTED;
-    if (c->head_dim == 256 && c->num_q_heads / c->num_kv_heads > 4) return ADAMAS_ERR_UNSUPPORTED;
-  }
+  if (!head_dim_built(c->head_dim)) return ADAMAS_ERR_UNSUPPORTED;
   if (c->variant & ~(ADAMAS_VARIANT_NO_HADAMARD | ADAMAS_VARIANT_L2)) return ADAMAS_ERR_UNSUPPORTED;
   if ((c->variant & ADAMAS_VARIANT_L2) && code_bits(c) != 2) return ADAMAS_ERR_UNSUPPORTED;
   if (c->num_q_heads / c->num_kv_heads > ADAMAS_MAX_GROUP) return ADAMAS_ERR_UNSUPPORTED;
@@ -202,57 +203,15 @@ Thresholds scaled(const adamas_config* c, const float* thr) {
   return t;
 }
 
-template <bool ATTN, int METRIC, int D>
-void launch_select_m(bool paged, dim3 grid, hipStream_t st, const SelectParams& sl) {
-  if constexpr (ATTN) {
-    if (paged) {
-      hipLaunchKernelGGL((select_kernel<kSelThreads, ATTN, METRIC, true, D>), grid, dim3(kSelThreads), 0, st, sl);
-      return;
-    }
-  }
-  hipLaunchKernelGGL((select_kernel<kSelThreads, ATTN, METRIC, false, D>), grid, dim3(kSelThreads), 0, st, sl);
-}
+const KernelSet& set_of(const adamas_config* c) { return *find_kernel_set(c->head_dim, metric_of(c)); }
 
-// Head dimensions 64 and 256 are built for the method itself (2-bit codes, Eq. 6,
-// contiguous and paged caches); check_config rejects the rest.
-template <bool ATTN>
-void launch_select(int metric, int head_dim, bool paged, dim3 grid, hipStream_t st,
-                   const SelectParams& sl) {
-  if (head_dim == 64) return launch_select_m<ATTN, kMetricL1, 64>(paged, grid, st, sl);
-  if (head_dim == 256) return launch_select_m<ATTN, kMetricL1, 256>(paged, grid, st, sl);
-  switch (metric) {
-    case kMetricL2: launch_select_m<ATTN, kMetricL2, 128>(paged, grid, st, sl); break;
-    case kMetricB1: launch_select_m<ATTN, kMetricB1, 128>(paged, grid, st, sl); break;
-    case kMetricB3: launch_select_m<ATTN, kMetricB3, 128>(paged, grid, st, sl); break;
-    default: launch_select_m<ATTN, kMetricL1, 128>(paged, grid, st, sl); break;
-  }
+// The bulk encode and the kernels that depend on the head dimension only live in
+// the set of the method's own metric (same code rows for the squared distance).
+const KernelSet& encode_set_of(const adamas_config* c) {
+  const int m = metric_of(c);
+  return *find_kernel_set(c->head_dim, m == kMetricL2 ? kMetricL1 : m);
 }
-
-// Bulk encode of n_vec vectors with the config's code width.
-template <int BITS, int D>
-void launch_encode_rows_bd(int64_t n_vec, hipStream_t st, const uint16_t* src, uint8_t* dst,
-                           int64_t head_stride_rows, int64_t row_begin, int64_t n_rows,
-                           const Thresholds& thr) {
-  const int64_t per_wg = 256 / (D / 32);  // vectors per 256-thread workgroup
-  const int64_t want = (n_vec + per_wg - 1) / per_wg;
-  const int grid = (int)(want < 16384 ? want : 16384);
-  hipLaunchKernelGGL((encode_rows_kernel<BITS, D>), dim3(grid), dim3(256), 0, st, src, dst,
-                     head_stride_rows, row_begin, n_rows, n_vec, thr);
-}
-
-void launch_encode_rows(const adamas_config* c, hipStream_t st, const uint16_t* src, uint8_t* dst,
-                        int64_t head_stride_rows, int64_t row_begin, int64_t n_rows, int64_t n_vec,
-                        const Thresholds& thr) {
-  if (c->head_dim == 64)
-    return launch_encode_rows_bd<2, 64>(n_vec, st, src, dst, head_stride_rows, row_begin, n_rows, thr);
-  if (c->head_dim == 256)
-    return launch_encode_rows_bd<2, 256>(n_vec, st, src, dst, head_stride_rows, row_begin, n_rows, thr);
-  switch (code_bits(c)) {
-    case 1: launch_encode_rows_bd<1, 128>(n_vec, st, src, dst, head_stride_rows, row_begin, n_rows, thr); break;
-    case 3: launch_encode_rows_bd<3, 128>(n_vec, st, src, dst, head_stride_rows, row_begin, n_rows, thr); break;
-    default: launch_encode_rows_bd<2, 128>(n_vec, st, src, dst, head_stride_rows, row_begin, n_rows, thr); break;
-  }
-}
+const KernelSet& dim_set_of(const adamas_config* c) { return *find_kernel_set(c->head_dim, kMetricL1); }
 
 double scale_log2e(const adamas_config* c) {
   const double s = c->sm_scale > 0.f ? (double)c->sm_scale : 1.0 / std::sqrt((double)c->head_dim);
@@ -272,64 +231,13 @@ int launch_status() {
   return ADAMAS_OK;
 }
 
-template <int G, bool FUSED, int METRIC, bool PAGED, int D>
-void launch_scan_gmp(const Plan& pl, dim3 grid, hipStream_t st, const ScanParams& sp) {
-  switch (pl.tile_tokens) {
-    case 1024: hipLaunchKernelGGL((scan_kernel<G, FUSED, 4, METRIC, PAGED, D>), grid, dim3(256), 0, st, sp); break;
-    case 2048: hipLaunchKernelGGL((scan_kernel<G, FUSED, 8, METRIC, PAGED, D>), grid, dim3(512), 0, st, sp); break;
-    default: hipLaunchKernelGGL((scan_kernel<G, FUSED, 16, METRIC, PAGED, D>), grid, dim3(1024), 0, st, sp); break;
-  }
-}
-
-template <int G, bool FUSED, int METRIC>
-void launch_scan_gm(const Plan& pl, dim3 grid, hipStream_t st, const ScanParams& sp) {
-  if constexpr (FUSED) {
-    if (sp.page_table != nullptr) {
-      launch_scan_gmp<G, FUSED, METRIC, true, 128>(pl, grid, st, sp);
-      return;
-    }
-  }
-  launch_scan_gmp<G, FUSED, METRIC, false, 128>(pl, grid, st, sp);
-}
-
-template <int G, bool FUSED>
-void launch_scan_g(const Plan& pl, dim3 grid, hipStream_t st, const ScanParams& sp) {
-  if constexpr (FUSED) {  // the paged layout is served by the fused step only
-    if (sp.page_table != nullptr) {
-      if (pl.head_dim == 64) return launch_scan_gmp<G, FUSED, kMetricL1, true, 64>(pl, grid, st, sp);
-      if constexpr (G <= 4) {
-        if (pl.head_dim == 256) return launch_scan_gmp<G, FUSED, kMetricL1, true, 256>(pl, grid, st, sp);
-      }
-    }
-  }
-  if (pl.head_dim == 64) return launch_scan_gmp<G, FUSED, kMetricL1, false, 64>(pl, grid, st, sp);
-  if constexpr (G <= 4) {  // check_config: groups above four are not built at 256
-    if (pl.head_dim == 256) return launch_scan_gmp<G, FUSED, kMetricL1, false, 256>(pl, grid, st, sp);
-  }
-  switch (pl.metric) {
-    case kMetricL2: launch_scan_gm<G, FUSED, kMetricL2>(pl, grid, st, sp); break;
-    case kMetricB1: launch_scan_gm<G, FUSED, kMetricB1>(pl, grid, st, sp); break;
-    case kMetricB3: launch_scan_gm<G, FUSED, kMetricB3>(pl, grid, st, sp); break;
-    default: launch_scan_gm<G, FUSED, kMetricL1>(pl, grid, st, sp); break;
-  }
-}
-
 // pl.tile_tokens is 1024, 2048 or 4096 (make_plan).
-template <bool FUSED>
-void launch_scan(int group, const Plan& pl, int Hkv, int batch, hipStream_t st, ScanParams sp) {
+void launch_scan(const adamas_config* c, bool fused, const Plan& pl, int batch, hipStream_t st,
+                 ScanParams sp) {
+  const int group = c->num_q_heads / c->num_kv_heads;
   sp.g_split = group % pl.g_split == 0 ? pl.g_split : 1;
-  const int G = group / sp.g_split;
-  const dim3 grid(pl.n_tiles, Hkv * sp.g_split, batch);
-  switch (G) {
-    case 1: launch_scan_g<1, FUSED>(pl, grid, st, sp); break;
-    case 2: launch_scan_g<2, FUSED>(pl, grid, st, sp); break;
-    case 3: launch_scan_g<3, FUSED>(pl, grid, st, sp); break;
-    case 4: launch_scan_g<4, FUSED>(pl, grid, st, sp); break;
-    case 5: launch_scan_g<5, FUSED>(pl, grid, st, sp); break;
-    case 6: launch_scan_g<6, FUSED>(pl, grid, st, sp); break;
-    case 7: launch_scan_g<7, FUSED>(pl, grid, st, sp); break;
-    default: launch_scan_g<8, FUSED>(pl, grid, st, sp); break;
-  }
+  const dim3 grid(pl.n_tiles, c->num_kv_heads * sp.g_split, batch);
+  set_of(c).scan(fused, group / sp.g_split, pl.tile_tokens, grid, st, sp);
 }
 
 struct FullPlan {
@@ -351,18 +259,26 @@ FullPlan make_full_plan(const adamas_config* c, int32_t batch, int64_t max_seq_l
   return fp;
 }
 
-template <int G>
-void launch_full(int head_dim, dim3 grid, hipStream_t st, const FullAttnParams& fp) {
-  if (head_dim == 64) hipLaunchKernelGGL((full_attn_kernel<G, 64>), grid, dim3(kFullThreads), 0, st, fp);
-  else if (head_dim == 256) hipLaunchKernelGGL((full_attn_kernel<G, 256>), grid, dim3(kFullThreads), 0, st, fp);
-  else hipLaunchKernelGGL((full_attn_kernel<G, 128>), grid, dim3(kFullThreads), 0, st, fp);
-}
-
-template <typename P>
-void launch_merge(int head_dim, dim3 grid, hipStream_t st, const P& mp) {
-  if (head_dim == 64) hipLaunchKernelGGL(merge_kernel<64>, grid, dim3(64), 0, st, mp);
-  else if (head_dim == 256) hipLaunchKernelGGL(merge_kernel<256>, grid, dim3(256), 0, st, mp);
-  else hipLaunchKernelGGL(merge_kernel<128>, grid, dim3(128), 0, st, mp);
+// Read-only streaming probe in the scan's access pattern (two 32-byte rows per
+// lane, lanes of a wave on consecutive rows): what the memory system delivers
+// when nothing else is done with the rows.
+__global__ __launch_bounds__(256) void stream_read_kernel(const uint4* __restrict__ src,
+                                                          uint32_t* __restrict__ sink,
+                                                          int64_t n_rows) {
+  const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t wave = tid >> 6;
+  const int lane = (int)(tid & 63);
+  uint4 v[4];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int64_t row = min((wave * 2 + i) * kWave + lane, n_rows - 1);
+    v[2 * i] = src[row * 2];
+    v[2 * i + 1] = src[row * 2 + 1];
+  }
+  uint32_t acc = 0;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) acc ^= v[i].x ^ v[i].y ^ v[i].z ^ v[i].w;
+  if (acc == 0x9e3779b9u) sink[0] = acc;  // keeps the loads alive
 }
 
 uint8_t* ws_at(void* ws, size_t off) { return static_cast<uint8_t*>(ws) + off; }
@@ -408,9 +324,9 @@ int adamas_encode_keys(const adamas_config* cfg, const void* K, void* codes, int
   if (n_rows == 0) return ADAMAS_OK;
   clear_stale_error();
   const int64_t n_vec = n_rows * cfg->num_kv_heads;
-  launch_encode_rows(cfg, (hipStream_t)stream, static_cast<const uint16_t*>(K),
-                     static_cast<uint8_t*>(codes), cfg->pool_tokens, row_begin, n_rows, n_vec,
-                     scaled(cfg, cfg->thr_k));
+  encode_set_of(cfg).encode_rows((hipStream_t)stream, static_cast<const uint16_t*>(K),
+                                 static_cast<uint8_t*>(codes), cfg->pool_tokens, row_begin, n_rows,
+                                 n_vec, scaled(cfg, cfg->thr_k));
   return launch_status();
 }
 
@@ -422,8 +338,9 @@ int adamas_encode_query(const adamas_config* cfg, const void* q, void* qcodes, i
   clear_stale_error();
   const int64_t n_vec = (int64_t)batch * cfg->num_q_heads;
   // queries form one "head" of n_vec consecutive rows
-  launch_encode_rows(cfg, (hipStream_t)stream, static_cast<const uint16_t*>(q),
-                     static_cast<uint8_t*>(qcodes), 0, 0, n_vec, n_vec, scaled(cfg, cfg->thr_q));
+  encode_set_of(cfg).encode_rows((hipStream_t)stream, static_cast<const uint16_t*>(q),
+                                 static_cast<uint8_t*>(qcodes), 0, 0, n_vec, n_vec,
+                                 scaled(cfg, cfg->thr_q));
   return launch_status();
 }
 
@@ -448,8 +365,7 @@ int adamas_manhattan_distance(const adamas_config* cfg, const void* qcodes, cons
   sp.Hq = cfg->num_q_heads;
   sp.Hkv = cfg->num_kv_heads;
   sp.n_tiles = pl.n_tiles;
-  launch_scan<false>(cfg->num_q_heads / cfg->num_kv_heads, pl, cfg->num_kv_heads, batch,
-                     (hipStream_t)stream, sp);
+  launch_scan(cfg, false, pl, batch, (hipStream_t)stream, sp);
   return launch_status();
 }
 
@@ -482,7 +398,7 @@ int adamas_select_topk(const adamas_config* cfg, const void* qcodes, const void*
   sp.Hq = cfg->num_q_heads;
   sp.Hkv = cfg->num_kv_heads;
   sp.n_tiles = pl.n_tiles;
-  launch_scan<false>(cfg->num_q_heads / cfg->num_kv_heads, pl, cfg->num_kv_heads, batch, st, sp);
+  launch_scan(cfg, false, pl, batch, st, sp);
   if (int rc = launch_status()) return rc;
 
   SelectParams sl{};
@@ -500,7 +416,7 @@ int adamas_select_topk(const adamas_config* cfg, const void* qcodes, const void*
   sl.n_tiles = pl.n_tiles;
   sl.tile_tokens = pl.tile_tokens;
   sl.seg_len = pl.seg_len;
-  launch_select<false>(pl.metric, cfg->head_dim, false, dim3(pl.n_segs, cfg->num_q_heads, batch), st, sl);
+  set_of(cfg).select(false, false, dim3(pl.n_segs, cfg->num_q_heads, batch), st, sl);
   return launch_status();
 }
 
@@ -535,12 +451,7 @@ int adamas_sparse_attn(const adamas_config* cfg, const void* q, const void* K, c
   ap.chunk = (k + parts - 1) / parts;
   ap.n_parts = (k + ap.chunk - 1) / ap.chunk;
   ap.scale_log2e = scale_log2e(cfg);
-  {
-    const dim3 grid(ap.n_parts, cfg->num_q_heads, batch);
-    if (cfg->head_dim == 64) hipLaunchKernelGGL(sparse_attn_kernel<64>, grid, dim3(kAttnThreads), 0, st, ap);
-    else if (cfg->head_dim == 256) hipLaunchKernelGGL(sparse_attn_kernel<256>, grid, dim3(kAttnThreads), 0, st, ap);
-    else hipLaunchKernelGGL(sparse_attn_kernel<128>, grid, dim3(kAttnThreads), 0, st, ap);
-  }
+  dim_set_of(cfg).sparse_attn(dim3(ap.n_parts, cfg->num_q_heads, batch), st, ap);
   if (int rc = launch_status()) return rc;
   if (ap.n_parts == 1) return ADAMAS_OK;
   MergeParams mp{};
@@ -550,7 +461,7 @@ int adamas_sparse_attn(const adamas_config* cfg, const void* q, const void* K, c
   mp.Hq = cfg->num_q_heads;
   mp.n_parts = ap.n_parts;
   mp.seg_len = 0;
-  launch_merge(cfg->head_dim, dim3(cfg->num_q_heads, batch), st, mp);
+  dim_set_of(cfg).merge(dim3(cfg->num_q_heads, batch), st, mp);
   return launch_status();
 }
 
@@ -674,7 +585,7 @@ int decode_step_impl(const adamas_config* cfg, const void* q, const void* k_new,
   sp.arrivals = reinterpret_cast<uint32_t*>(ws_at(workspace, pl.off_partial)) + 2;
   sp.arrivals_stride = (int64_t)kMaxParts * partial_stride(cfg->head_dim);
   if (stages & ADAMAS_STAGE_SCAN) {
-    launch_scan<true>(cfg->num_q_heads / cfg->num_kv_heads, pl, cfg->num_kv_heads, batch, st, sp);
+    launch_scan(cfg, true, pl, batch, st, sp);
     if (int rc = launch_status()) return rc;
   }
   if (!(stages & ADAMAS_STAGE_SELECT_ATTN)) return ADAMAS_OK;
@@ -705,7 +616,7 @@ int decode_step_impl(const adamas_config* cfg, const void* q, const void* k_new,
   sl.page_table = page_table;
   sl.max_pages = max_pages;
   sl.page_shift = page_shift;
-  launch_select<true>(pl.metric, cfg->head_dim, page_table != nullptr, dim3(pl.n_segs, cfg->num_q_heads, batch), st, sl);
+  set_of(cfg).select(true, page_table != nullptr, dim3(pl.n_segs, cfg->num_q_heads, batch), st, sl);
   if (int rc = launch_status()) return rc;
   if (pl.n_segs == 1 || sl.arrivals != nullptr) return ADAMAS_OK;  // the select kernel wrote `out` itself
   MergeParams mp{};
@@ -718,7 +629,7 @@ int decode_step_impl(const adamas_config* cfg, const void* q, const void* k_new,
   mp.Hq = cfg->num_q_heads;
   mp.n_parts = pl.n_segs;
   mp.seg_len = pl.seg_len;
-  launch_merge(cfg->head_dim, dim3(cfg->num_q_heads, batch), st, mp);
+  dim_set_of(cfg).merge(dim3(cfg->num_q_heads, batch), st, mp);
   return launch_status();
 }
 }  // namespace
@@ -758,26 +669,10 @@ int adamas_full_attn(const adamas_config* cfg, const void* q, const void* K, con
   fp.chunk = pl.chunk;
   fp.scale_log2e = (float)scale_log2e(cfg);
   const dim3 grid(pl.n_splits, cfg->num_kv_heads, batch);
-  switch (cfg->num_q_heads / cfg->num_kv_heads) {
-    case 1: launch_full<1>(cfg->head_dim, grid, st, fp); break;
-    case 2: launch_full<2>(cfg->head_dim, grid, st, fp); break;
-    case 3: launch_full<3>(cfg->head_dim, grid, st, fp); break;
-    case 4: launch_full<4>(cfg->head_dim, grid, st, fp); break;
-    case 5: launch_full<5>(cfg->head_dim, grid, st, fp); break;
-    case 6: launch_full<6>(cfg->head_dim, grid, st, fp); break;
-    case 7: launch_full<7>(cfg->head_dim, grid, st, fp); break;
-    default: launch_full<8>(cfg->head_dim, grid, st, fp); break;
-  }
+  dim_set_of(cfg).full_attn(cfg->num_q_heads / cfg->num_kv_heads, grid, st, fp);
   if (int rc = launch_status()) return rc;
-  {
-    const dim3 mgrid(cfg->num_q_heads, batch);
-    if (cfg->head_dim == 64)
-      hipLaunchKernelGGL(merge_parts_kernel<64>, mgrid, dim3(kMergeThreads), 0, st, fp.partial, out, cfg->num_q_heads, pl.n_splits);
-    else if (cfg->head_dim == 256)
-      hipLaunchKernelGGL(merge_parts_kernel<256>, mgrid, dim3(kMergeThreads), 0, st, fp.partial, out, cfg->num_q_heads, pl.n_splits);
-    else
-      hipLaunchKernelGGL(merge_parts_kernel<128>, mgrid, dim3(kMergeThreads), 0, st, fp.partial, out, cfg->num_q_heads, pl.n_splits);
-  }
+  dim_set_of(cfg).merge_parts(dim3(cfg->num_q_heads, batch), st, fp.partial, out, cfg->num_q_heads,
+                              pl.n_splits);
   return launch_status();
 }
 

@@ -28,8 +28,23 @@ struct Dist {
   static constexpr int kBins = kMaxDist + 1;  // distinct distance values: 385 for the method
   // uint16 per stored tile histogram, a 16-byte multiple (392 for the method)
   static constexpr int kStride = (kBins + 7) / 8 * 8;
-  static_assert(kRowBytes % 16 == 0, "rows are fetched in 16-byte pieces");
+  // a row is fetched in pieces of the largest power of two (up to 16 bytes) that divides it
+  static constexpr int kPiece = kRowBytes % 16 == 0 ? 16 : kRowBytes % 8 == 0 ? 8 : 4;
 };
+
+// One aligned load of BYTES (16, 8 or 4) into consecutive 32-bit words.
+template <int BYTES>
+__device__ __forceinline__ void load_piece(const uint8_t* src, uint32_t* w) {
+  if constexpr (BYTES == 16) {
+    const uint4 v = *reinterpret_cast<const uint4*>(src);
+    w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
+  } else if constexpr (BYTES == 8) {
+    const uint2 v = *reinterpret_cast<const uint2*>(src);
+    w[0] = v.x; w[1] = v.y;
+  } else {
+    w[0] = *reinterpret_cast<const uint32_t*>(src);
+  }
+}
 // floats per attention partial of a head of dimension d: m, l, pad, pad, o[d]
 constexpr int partial_stride(int d) { return d + 4; }
 constexpr int kWave = 64;

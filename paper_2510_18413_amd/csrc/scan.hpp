@@ -27,7 +27,9 @@
 namespace adamas {
 
 constexpr int kScanTokPerThread = 4;
-constexpr int kHistReplicas = 2;  // LDS histogram copies, picked by lane, to thin out same-address atomics
+// LDS histogram copies, picked by lane, to thin out same-address atomics: two
+// unless the histograms of the group would then take more than 48 KiB.
+constexpr int hist_replicas(int group, int bins) { return group * bins * 8 > 48 * 1024 ? 1 : 2; }
 
 struct ScanParams {
   const uint8_t* codes;      // [Hkv][pool][32]
@@ -66,6 +68,7 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
   constexpr int kNumBins = Fmt::kBins, kHistStride = Fmt::kStride;
   constexpr int BITS = Fmt::kBits, kRowBytes = Fmt::kRowBytes, W = Fmt::kWords;
   constexpr int kRowWords = W * BITS;  // 32-bit words per code row
+  constexpr int kHistReplicas = hist_replicas(G, kNumBins);
   constexpr int E = D / 64;            // elements per lane when a wave encodes one vector
   __shared__ uint32_t s_hist[G][kHistReplicas][kNumBins];
   // per query head: plane p of word wd at [W * p + wd]; 2-bit codes also keep lo^hi at [2W + wd]
@@ -152,8 +155,8 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
   }
 
   const uint8_t* plane = p.codes + ((int64_t)kvh * p.pool_tokens + start) * kRowBytes;
-  constexpr int C = kRowBytes / 16;  // 16-byte pieces of a row
-  uint4 rr[kScanTokPerThread][C];
+  constexpr int kPiece = Fmt::kPiece, C = kRowBytes / kPiece;  // a row is fetched in C pieces
+  uint32_t rr[kScanTokPerThread][kRowWords];
 #pragma unroll
   for (int i = 0; i < kScanTokPerThread; ++i) {
     // Unconditional: a lane past the end re-reads the last row (masked at use).
@@ -167,9 +170,9 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
     } else {
       r = min(t0 + (wave * kScanTokPerThread + i) * kWave + lane, L - 1);
     }
-    const uint4* row = reinterpret_cast<const uint4*>(plane + r * kRowBytes);
+    const uint8_t* row = plane + r * kRowBytes;
 #pragma unroll
-    for (int c = 0; c < C; ++c) rr[i][c] = row[c];
+    for (int c = 0; c < C; ++c) load_piece<kPiece>(row + c * kPiece, &rr[i][c * (kPiece / 4)]);
   }
 
   // Nothing above may be consumed before the row loads have been issued.
@@ -234,19 +237,28 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
   // planes cost an extra move per word); large groups keep them scalar to stay
   // within the register budget of a 1024-thread workgroup.
   // qp[g][j][wd]: plane j of word wd; for 2-bit codes j = 2 is lo ^ hi.
+  // Groups whose planes exceed the scalar registers as well (96 words) are read
+  // from LDS where they are used (a broadcast read per word).
   constexpr int QP = BITS == 2 ? 3 : BITS;
-  uint32_t qp[G][QP][W];
+  constexpr bool kQueryInLds = G * QP * W > 96;
+  uint32_t qp[kQueryInLds ? 1 : G][QP][W];
+  if constexpr (!kQueryInLds) {
 #pragma unroll
-  for (int g = 0; g < G; ++g) {
+    for (int g = 0; g < G; ++g) {
 #pragma unroll
-    for (int j = 0; j < QP; ++j) {
+      for (int j = 0; j < QP; ++j) {
 #pragma unroll
-      for (int wd = 0; wd < W; ++wd) {
-        if constexpr (G * QP * W <= 24 || (G * QP * W <= 48 && BITS < 3)) qp[g][j][wd] = s_q[g][W * j + wd];
-        else qp[g][j][wd] = __builtin_amdgcn_readfirstlane(s_q[g][W * j + wd]);
+        for (int wd = 0; wd < W; ++wd) {
+          if constexpr (G * QP * W <= 24 || (G * QP * W <= 48 && BITS < 3)) qp[g][j][wd] = s_q[g][W * j + wd];
+          else qp[g][j][wd] = __builtin_amdgcn_readfirstlane(s_q[g][W * j + wd]);
+        }
       }
     }
   }
+  auto qplane = [&](int g, int j, int wd) -> uint32_t {
+    if constexpr (kQueryInLds) return s_q[g][W * j + wd];
+    else return qp[g][j][wd];
+  };
   uint32_t* hist_lane = &s_hist[0][lane & (kHistReplicas - 1)][0];
 
 #pragma unroll
@@ -257,12 +269,7 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
     // kw[BITS * wd + pl]: plane pl of word wd of the key row
     uint32_t kw[kRowWords];
 #pragma unroll
-    for (int c = 0; c < C; ++c) {
-      kw[4 * c] = rr[i][c].x;
-      kw[4 * c + 1] = rr[i][c].y;
-      kw[4 * c + 2] = rr[i][c].z;
-      kw[4 * c + 3] = rr[i][c].w;
-    }
+    for (int wq = 0; wq < kRowWords; ++wq) kw[wq] = rr[i][wq];
     if (appending && t == L - 1) {
 #pragma unroll
       for (int wq = 0; wq < kRowWords; ++wq) kw[wq] = s_new[wq];
@@ -274,8 +281,8 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
         uint32_t c1 = 0, c2 = 0, c3 = 0;
 #pragma unroll
         for (int wd = 0; wd < W; ++wd) {
-          const uint32_t xl = kw[2 * wd] ^ qp[g][0][wd], xh = kw[2 * wd + 1] ^ qp[g][1][wd];
-          const uint32_t u = xh & ~(xl & qp[g][2][wd]);
+          const uint32_t xl = kw[2 * wd] ^ qplane(g, 0, wd), xh = kw[2 * wd + 1] ^ qplane(g, 1, wd);
+          const uint32_t u = xh & ~(xl & qplane(g, 2, wd));
           c1 += __popc(xl);
           c2 += __popc(u);
           if constexpr (METRIC == kMetricL2) c3 += __popc(u & xl);
@@ -284,14 +291,14 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
       } else if constexpr (BITS == 1) {
         d = 0;
 #pragma unroll
-        for (int wd = 0; wd < W; ++wd) d += __popc(kw[wd] ^ qp[g][0][wd]);
+        for (int wd = 0; wd < W; ++wd) d += __popc(kw[wd] ^ qplane(g, 0, wd));
       } else {
         // |a - b| of 3-bit codes on bit planes (a query, b key): subtract with
         // borrow, then negate where the borrow out (a < b) is set.
         uint32_t c0 = 0, c1 = 0, c2 = 0;
 #pragma unroll
         for (int wd = 0; wd < W; ++wd) {
-          const uint32_t a0 = qp[g][0][wd], a1 = qp[g][1][wd], a2 = qp[g][2][wd];
+          const uint32_t a0 = qplane(g, 0, wd), a1 = qplane(g, 1, wd), a2 = qplane(g, 2, wd);
           const uint32_t b0 = kw[3 * wd], b1 = kw[3 * wd + 1], b2 = kw[3 * wd + 2];
           const uint32_t d0 = a0 ^ b0, br1 = ~a0 & b0;
           const uint32_t x1 = a1 ^ b1, d1 = x1 ^ br1, br2 = (~a1 & b1) | (~x1 & br1);
@@ -371,28 +378,6 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
       reinterpret_cast<uint32_t*>(row)[pr] = lo | (hi << 16);
     }
   }
-}
-
-// Read-only streaming probe in the scan's access pattern (two 32-byte rows per
-// lane, lanes of a wave on consecutive rows): what the memory system delivers
-// when nothing else is done with the rows.
-__global__ __launch_bounds__(256) void stream_read_kernel(const uint4* __restrict__ src,
-                                                          uint32_t* __restrict__ sink,
-                                                          int64_t n_rows) {
-  const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const int64_t wave = tid >> 6;
-  const int lane = (int)(tid & 63);
-  uint4 v[4];
-#pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int64_t row = min((wave * 2 + i) * kWave + lane, n_rows - 1);
-    v[2 * i] = src[row * 2];
-    v[2 * i + 1] = src[row * 2 + 1];
-  }
-  uint32_t acc = 0;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) acc ^= v[i].x ^ v[i].y ^ v[i].z ^ v[i].w;
-  if (acc == 0x9e3779b9u) sink[0] = acc;  // keeps the loads alive
 }
 
 }  // namespace adamas
