@@ -66,6 +66,10 @@ def parse_args():
     ap.add_argument("--eager", action="store_true", help="launch from Python instead of a graph")
     ap.add_argument("--scan-only", action="store_true",
                     help="time only the scan stage (profiling aid; no JSON-contract value)")
+    ap.add_argument("--phase-trace", action="store_true",
+                    help="profiling aid: load the stamping build (python -m "
+                         "paper_2510_18413_amd.build --phase-trace) and print where the time goes "
+                         "inside the two kernels of the step instead of the JSON-contract line")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run 8 plain 256 MiB copy-like kernels (reference for rocprofv3 --pmc "
                          "FETCH_SIZE / WRITE_SIZE readings)")
@@ -93,6 +97,73 @@ def algorithmic_bytes(B, Hq, Hkv, lens, k, append, row_bytes=32, head_dim=128):
     return codes + gather + small + app, codes
 
 
+SCAN_PHASES = ["start", "length known", "query planes ready", "rows consumed",
+               "distances stored", "histogram flushed (end)"]
+SELECT_PHASES = ["start", "distances + histograms + length loaded", "threshold T known",
+                 "compaction done", "first K/V rows arrived", "rows consumed",
+                 "row groups combined", "partial stored + acknowledged", "arrival counted",
+                 "merged (last workgroup only)", "end"]
+
+
+def phase_trace(A, torch, np, make_graph, n_layers, args, sweeps=40):
+    """Replays the graph of one sweep `sweeps` times; after each replay the trace buffers hold
+    the stamps of the sweep's last layer (back-to-back kernels, as in the timed run).  Prints a
+    table per kernel: when, relative to the kernel's first workgroup start, the median / 90th
+    percentile / last workgroup passes each phase boundary (us, 100 MHz clock: 0.01 us steps)."""
+    n_rec = 1 << 16
+    dev = torch.device("cuda:0")
+    tr_scan = torch.zeros(n_rec, A.TRACE_SLOTS, dtype=torch.int64, device=dev)
+    tr_sel = torch.zeros(n_rec, A.TRACE_SLOTS, dtype=torch.int64, device=dev)
+    A.adamas_phase_trace(tr_scan, tr_sel)
+    g = make_graph(None)
+    for _ in range(3):
+        g.replay()
+    torch.cuda.synchronize()
+    rows = {"scan": [], "select": [], "gap": [], "scan_len": [], "select_len": []}
+    for _ in range(sweeps):
+        tr_scan.zero_()
+        tr_sel.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        sc, se = tr_scan.cpu().numpy(), tr_sel.cpu().numpy()
+        sc, se = sc[sc[:, 0] > 0], se[se[:, 0] > 0]
+        s0, e0 = sc[:, 0].min(), se[:, 0].min()
+        rows["scan"].append(np.where(sc > 0, (sc - s0) * 0.01, np.nan))
+        rows["select"].append(np.where(se > 0, (se - e0) * 0.01, np.nan))
+        rows["gap"].append((e0 - sc.max()) * 0.01)
+        rows["scan_len"].append((sc.max() - s0) * 0.01)
+        rows["select_len"].append((se.max() - e0) * 0.01)
+    A.adamas_phase_trace(None, None)
+    out = {"config": args.config, "k": args.k, "sweeps": sweeps, "layers": n_layers,
+           "scan_first_start_to_last_end_us": round(float(np.median(rows["scan_len"])), 2),
+           "select_first_start_to_last_end_us": round(float(np.median(rows["select_len"])), 2),
+           "scan_end_to_select_start_us": round(float(np.median(rows["gap"])), 2)}
+    for name, phases in (("scan", SCAN_PHASES), ("select", SELECT_PHASES)):
+        allr = np.concatenate(rows[name], axis=0)
+        print("\n%s kernel: %d workgroup records per launch, %d launches; us after the kernel's "
+              "first workgroup start" % (name, allr.shape[0] // sweeps, sweeps))
+        print("| phase boundary | workgroups passing | median | p90 | last |")
+        print("|---|---|---|---|---|")
+        tab = []
+        for i, ph in enumerate(phases):
+            col = allr[:, i]
+            col = col[~np.isnan(col)]
+            if col.size == 0:
+                continue
+            # "last": median over launches of the latest workgroup of each launch
+            last = np.median([np.nanmax(r[:, i]) for r in rows[name] if not np.all(np.isnan(r[:, i]))])
+            tab.append((ph, int(col.size // sweeps), float(np.median(col)),
+                        float(np.percentile(col, 90)), float(last)))
+            print("| %s | %d | %.2f | %.2f | %.2f |" % tab[-1])
+        out[name] = [dict(phase=t[0], workgroups=t[1], median_us=round(t[2], 2),
+                          p90_us=round(t[3], 2), last_us=round(t[4], 2)) for t in tab]
+    print("\nscan first start -> last end %.2f us; scan last end -> select first start %.2f us; "
+          "select first start -> last end %.2f us (medians over %d launches)" % (
+              out["scan_first_start_to_last_end_us"], out["scan_end_to_select_start_us"],
+              out["select_first_start_to_last_end_us"], sweeps))
+    print(json.dumps(out), flush=True)
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -104,6 +175,12 @@ def main():
     import numpy as np
     import torch
 
+    if args.phase_trace:
+        trace_lib = os.path.join(ROOT, "paper_2510_18413_amd", "libadamas_trace.so")
+        if not os.path.exists(trace_lib):
+            raise SystemExit("build the stamping library first: python -m paper_2510_18413_amd.build "
+                             "--phase-trace")
+        os.environ["ADAMAS_LIBRARY"] = trace_lib
     import paper_2510_18413_amd as A
     import synth_inputs as synth
 
@@ -325,6 +402,10 @@ def main():
             torch.bitwise_not(src, out=dst)
         torch.cuda.synchronize()
         del src, dst
+
+    if args.phase_trace:
+        phase_trace(A, torch, np, make_graph, n_layers, args)
+        return
 
     # ------------------------------------------------------------------ the timed region
     if args.scan_only:

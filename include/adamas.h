@@ -285,6 +285,22 @@ int adamas_decode_step_stages(const adamas_config *cfg, const void *q,
                               void *stream, uint32_t stages);
 
 /*
+ * Profiling hook, for libraries built with -DADAMAS_PHASE_TRACE only (an
+ * ordinary build returns ADAMAS_ERR_UNSUPPORTED and has no stamping code in
+ * its kernels).  After this call every workgroup of the two kernels of
+ * adamas_decode_step / _stages / _paged leaves a record of ADAMAS_TRACE_SLOTS
+ * uint64 in scan_records / select_records (device memory, n_records records
+ * each, indexed by the workgroup's linear index in its grid; workgroups beyond
+ * n_records leave nothing; either pointer may be NULL): the 100 MHz wall clock
+ * at the kernel's phase boundaries, in the order of enum ScanPhase /
+ * SelectPhase of the kernel sources, 0 where a workgroup did not pass a
+ * boundary.  NULL, NULL, 0 switches the stamps off.  Process-wide state, not
+ * thread-safe; the buffers must stay valid while traced calls run.
+ */
+#define ADAMAS_TRACE_SLOTS 16
+int adamas_phase_trace(void *scan_records, void *select_records, int64_t n_records);
+
+/*
  * adamas_decode_step on a PAGED cache, the layout of the serving engines the
  * paper compares with (Section 4.1): the pools are cut into pages of
  * page_tokens rows (a power of two, 64..4096; pool_tokens a multiple of it)

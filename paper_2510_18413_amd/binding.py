@@ -10,6 +10,7 @@ raises.
 from __future__ import annotations
 
 import ctypes
+import os
 from typing import Optional, Sequence
 
 from . import build as _build
@@ -27,6 +28,7 @@ EXPORTED_SYMBOLS = (
     "adamas_decode_step",
     "adamas_decode_step_stages",
     "adamas_decode_step_static",
+    "adamas_phase_trace",
     "adamas_stream_read",
     "adamas_decode_step_paged",
     "adamas_full_attn_workspace_bytes",
@@ -91,15 +93,19 @@ def library_path():
 
 def library() -> ctypes.CDLL:
     """Loads libadamas.so, building it first (in a child process, before anything here touches
-    the GPU library) when it is missing or was built from sources other than the tree's."""
+    the GPU library) when it is missing or was built from sources other than the tree's.  The
+    environment variable ADAMAS_LIBRARY names another built library to load instead."""
     global _lib
     if _lib is None:
         # torch first: the process then has one HIP runtime (the one torch ships), and this
         # library, which only needs the public HIP launch API, binds to it.
         import torch  # noqa: F401
-        if _build.is_stale():
-            _build.build()
-        lib = ctypes.CDLL(str(_build.LIB))
+        path = os.environ.get("ADAMAS_LIBRARY")     # a library built elsewhere: loaded as it is
+        if not path:
+            if _build.is_stale():
+                _build.build()
+            path = str(_build.LIB)
+        lib = ctypes.CDLL(path)
         vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
         cfgp = ctypes.POINTER(Config)
         lib.adamas_status_string.restype = ctypes.c_char_p
@@ -126,6 +132,8 @@ def library() -> ctypes.CDLL:
         lib.adamas_decode_step_static.restype = ctypes.c_int
         lib.adamas_decode_step_static.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp,
                                                   vp, i64, vp]
+        lib.adamas_phase_trace.restype = ctypes.c_int
+        lib.adamas_phase_trace.argtypes = [vp, vp, i64]
         lib.adamas_decode_step_paged.restype = ctypes.c_int
         lib.adamas_decode_step_paged.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp,
                                                  i32, i32, vp, vp, i64, vp, sz, vp,
@@ -318,6 +326,27 @@ def adamas_decode_step(cfg: Config, q, K, V, codes, seq_start, seq_len, k: int, 
     adamas_decode_step_stages(cfg, q, K, V, codes, seq_start, seq_len, k, out, max_seq_len,
                               workspace, k_new=k_new, v_new=v_new, idx_out=idx_out, stream=stream,
                               stages=None)
+
+
+TRACE_SLOTS = 16
+
+
+def adamas_phase_trace(scan_records, select_records) -> None:
+    """Profiling builds only: int64 tensors [n_records, TRACE_SLOTS] on the GPU that receive the
+    kernels' phase stamps (None, None switches them off)."""
+    import torch
+    n = 0
+    for t in (scan_records, select_records):
+        if t is not None:
+            if t.dim() != 2 or t.shape[1] != TRACE_SLOTS:
+                raise ValueError("trace buffers must have shape (n_records, %d)" % TRACE_SLOTS)
+            n = t.shape[0] if n == 0 else n
+            if t.shape[0] != n:
+                raise ValueError("both trace buffers must hold the same number of records")
+    rc = library().adamas_phase_trace(_ptr(scan_records, torch.int64, "scan_records", optional=True),
+                                      _ptr(select_records, torch.int64, "select_records",
+                                           optional=True), n)
+    _check(rc, "adamas_phase_trace")
 
 
 def adamas_decode_step_static(cfg: Config, q, K, V, codes, seq_start, seq_len, k: int, out,

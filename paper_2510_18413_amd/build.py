@@ -70,21 +70,29 @@ def is_stale() -> bool:
     return built_id() != source_id()
 
 
-def build(verbose: bool = False, extra_flags=(), jobs: int = 0) -> Path:
-    """Compiles everything unconditionally; returns the path of the shared library."""
+def build(verbose: bool = False, extra_flags=(), jobs: int = 0, only=None, out: Path = LIB) -> Path:
+    """Compiles everything unconditionally; returns the path of the shared library.
+
+    only=(head_dim, metric) is a developer option for kernel work: a quick build of that single
+    pair (metric 0 = the method); the resulting library refuses every other configuration.
+    `out` is where the library goes (default: the in-tree libadamas.so that the binding loads).
+    """
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     jobs = jobs or min(16, os.cpu_count() or 4)
     OBJ_DIR.mkdir(exist_ok=True)
     tag = ".tmp%d" % os.getpid()
     common = [hipcc] + HIPCC_FLAGS + list(extra_flags) + [
         "-I", str(ROOT / "include"), "-I", str(CSRC), "-c"]
-    units = [(OBJ_DIR / ("adamas%s.o" % tag),
-              common + ['-DADAMAS_BUILD_ID="%s"' % source_id(), str(API_SRC)])]
-    for d in head_dims():
-        for m in range(METRICS):
-            units.append((OBJ_DIR / ("kernels_d%d_m%d%s.o" % (d, m, tag)),
-                          common + ["-DADAMAS_INST_D=%d" % d, "-DADAMAS_INST_METRIC=%d" % m,
-                                    str(INST_SRC)]))
+    api_flags = ['-DADAMAS_BUILD_ID="%s"' % source_id()]
+    pairs = [(d, m) for d in head_dims() for m in range(METRICS)]
+    if only is not None:
+        pairs = [tuple(only)]
+        api_flags += ["-DADAMAS_ONLY_D=%d" % only[0], "-DADAMAS_ONLY_METRIC=%d" % only[1]]
+    units = [(OBJ_DIR / ("adamas%s.o" % tag), common + api_flags + [str(API_SRC)])]
+    for d, m in pairs:
+        units.append((OBJ_DIR / ("kernels_d%d_m%d%s.o" % (d, m, tag)),
+                      common + ["-DADAMAS_INST_D=%d" % d, "-DADAMAS_INST_METRIC=%d" % m,
+                                str(INST_SRC)]))
 
     def compile_one(unit):
         obj, cmd = unit
@@ -103,18 +111,31 @@ def build(verbose: bool = False, extra_flags=(), jobs: int = 0) -> Path:
     try:
         with ThreadPoolExecutor(max_workers=jobs) as pool:
             objs = list(pool.map(compile_one, units))
-        tmp = LIB.with_suffix(".so" + tag)
+        tmp = Path(str(out) + tag)
         link = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", str(tmp)] + [str(o) for o in objs]
         if verbose:
             print(" ".join(link), flush=True)
         subprocess.run(link, check=True)
-        os.replace(tmp, LIB)
+        os.replace(tmp, out)
     finally:
         for obj, _ in units:
             if obj.exists():
                 obj.unlink()
-    return LIB
+    return out
+
+
+TRACE_LIB = PKG / "libadamas_trace.so"
+
+
+def build_phase_trace(verbose: bool = False) -> Path:
+    """The profiling build `bench.py --phase-trace` loads: the method's own kernels (head
+    dimension 128, Eq. 6) with phase stamps compiled in (-DADAMAS_PHASE_TRACE)."""
+    return build(verbose=verbose, extra_flags=["-DADAMAS_PHASE_TRACE"], only=(128, 0), out=TRACE_LIB)
 
 
 if __name__ == "__main__":
-    print(build(verbose=True))
+    import sys
+    if "--phase-trace" in sys.argv[1:]:
+        print(build_phase_trace(verbose=True))
+    else:
+        print(build(verbose=True))

@@ -21,6 +21,11 @@ using namespace adamas;
 
 thread_local int g_last_hip_error = 0;
 
+// Profiling builds: where the kernels leave their phase stamps (adamas_phase_trace).
+uint64_t* g_trace_scan = nullptr;
+uint64_t* g_trace_select = nullptr;
+int64_t g_trace_records = 0;
+
 // Device address of `scratch` on the current device (every GPU holds its own
 // copy of the array at its own address), looked up once per device.  Returns
 // nullptr and records the HIP error if the runtime refuses.
@@ -82,6 +87,11 @@ size_t hist_stride_of(int metric, int head_dim) {
 
 // The kernels of a (head dimension, metric) pair; nullptr if that pair is not built.
 const KernelSet* find_kernel_set(int head_dim, int metric) {
+#ifdef ADAMAS_ONLY_D  // developer build of a single pair (build.py, only=...)
+  if (head_dim == ADAMAS_ONLY_D && metric == ADAMAS_ONLY_METRIC)
+    return &kernel_set<ADAMAS_ONLY_D, ADAMAS_ONLY_METRIC>();
+  return nullptr;
+#endif
 #define ADAMAS_SET_CASE(D, M) \
   if (head_dim == D && metric == M) return &kernel_set<D, M>();
 #define ADAMAS_SET_CASES(D) ADAMAS_FOR_EACH_METRIC(ADAMAS_SET_CASE, D)
@@ -308,6 +318,19 @@ const char* adamas_build_id(void) {
 }
 
 int adamas_last_hip_error(void) { return g_last_hip_error; }
+
+int adamas_phase_trace(void* scan_records, void* select_records, int64_t n_records) {
+#ifdef ADAMAS_PHASE_TRACE
+  if (n_records < 0 || ((scan_records || select_records) && n_records == 0)) return ADAMAS_ERR_BAD_ARG;
+  g_trace_scan = static_cast<uint64_t*>(scan_records);
+  g_trace_select = static_cast<uint64_t*>(select_records);
+  g_trace_records = n_records;
+  return ADAMAS_OK;
+#else
+  (void)scan_records; (void)select_records; (void)n_records;
+  return ADAMAS_ERR_UNSUPPORTED;
+#endif
+}
 
 size_t adamas_workspace_bytes(const adamas_config* cfg, int32_t batch, int64_t max_seq_len,
                               int32_t k) {
@@ -584,6 +607,8 @@ int decode_step_impl(const adamas_config* cfg, const void* q, const void* k_new,
   // segment counters live in the unused words of each head's first partial slot
   sp.arrivals = reinterpret_cast<uint32_t*>(ws_at(workspace, pl.off_partial)) + 2;
   sp.arrivals_stride = (int64_t)kMaxParts * partial_stride(cfg->head_dim);
+  sp.trace = g_trace_scan;
+  sp.trace_records = g_trace_records;
   if (stages & ADAMAS_STAGE_SCAN) {
     launch_scan(cfg, true, pl, batch, st, sp);
     if (int rc = launch_status()) return rc;
@@ -616,6 +641,8 @@ int decode_step_impl(const adamas_config* cfg, const void* q, const void* k_new,
   sl.page_table = page_table;
   sl.max_pages = max_pages;
   sl.page_shift = page_shift;
+  sl.trace = g_trace_select;
+  sl.trace_records = g_trace_records;
   set_of(cfg).select(true, page_table != nullptr, dim3(pl.n_segs, cfg->num_q_heads, batch), st, sl);
   if (int rc = launch_status()) return rc;
   if (pl.n_segs == 1 || sl.arrivals != nullptr) return ADAMAS_OK;  // the select kernel wrote `out` itself

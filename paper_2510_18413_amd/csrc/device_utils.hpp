@@ -81,6 +81,39 @@ __device__ __forceinline__ uint32_t pk_sub_u16(uint32_t a, uint32_t b) {
   return __builtin_bit_cast(uint32_t, d);
 }
 
+// ---- phase stamps (profiling builds only: -DADAMAS_PHASE_TRACE) -------------
+// Thread 0 of a workgroup notes the 100 MHz wall clock at phase boundaries and
+// writes the notes to record `blockIdx` of a trace buffer when it leaves.  In
+// ordinary builds all of this compiles to nothing.
+constexpr int kTraceSlots = 16;  // 64-bit words per workgroup record
+#ifdef ADAMAS_PHASE_TRACE
+struct PhaseTrace {
+  uint64_t t[kTraceSlots];
+  __device__ __forceinline__ PhaseTrace() {
+#pragma unroll
+    for (int i = 0; i < kTraceSlots; ++i) t[i] = 0;
+  }
+  // waits for this wave's outstanding memory operations first, so that the note
+  // marks the point where the phase's data has arrived
+  __device__ __forceinline__ void stamp(int i) {
+    __builtin_amdgcn_s_waitcnt(0);
+    if (threadIdx.x == 0) t[i] = wall_clock64();
+  }
+  __device__ __forceinline__ void flush(uint64_t* buf, int64_t n_records) const {
+    const int64_t wg = ((int64_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;
+    if (threadIdx.x == 0 && buf != nullptr && wg < n_records) {
+#pragma unroll
+      for (int i = 0; i < kTraceSlots; ++i) buf[wg * kTraceSlots + i] = t[i];
+    }
+  }
+};
+#else
+struct PhaseTrace {
+  __device__ __forceinline__ void stamp(int) {}
+  __device__ __forceinline__ void flush(uint64_t*, int64_t) const {}
+};
+#endif
+
 // ---- data-parallel-primitive (DPP) cross-lane moves: one VALU instruction each,
 // no LDS round trip.  A "row" is 16 consecutive lanes.
 constexpr int kDppQuadXor1 = 0xB1;       // quad_perm [1,0,3,2]

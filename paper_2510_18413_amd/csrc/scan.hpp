@@ -57,6 +57,19 @@ struct ScanParams {
   const int32_t* page_table;
   int32_t max_pages, page_shift;
   Thresholds thr_q, thr_k;
+  // Profiling builds only: one record of phase stamps per workgroup (see PhaseTrace).
+  uint64_t* trace;
+  int64_t trace_records;
+};
+
+// Phase stamps of scan_kernel, in the order they are taken.
+enum ScanPhase {
+  kScanStart = 0,    // first instruction
+  kScanLengthKnown,  // past the early barrier: sequence length and start have arrived
+  kScanQueryReady,   // the query planes are published in LDS
+  kScanRowsDone,     // every row of the tile has arrived and its distances are in LDS
+  kScanDistStored,   // distance stores acknowledged
+  kScanEnd           // histogram flushed and acknowledged
 };
 
 // WAVES = wavefronts per workgroup (4, 8 or 16): the tile is WAVES * 256 tokens.
@@ -80,6 +93,8 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
 
   // blockIdx.y = KV head * g_split + part: the G query heads of this workgroup are
   // part `gsub` of the KV head's group of G * g_split (the parts re-read the rows).
+  PhaseTrace trace;
+  trace.stamp(kScanStart);
   const int tile_id = blockIdx.x, kvh = blockIdx.y / p.g_split, gsub = blockIdx.y % p.g_split;
   const int b = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -136,6 +151,9 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
   __syncthreads();
 
   if (t0 >= L) return;  // whole workgroup
+#ifdef ADAMAS_PHASE_TRACE   // (no wait here: the encode vectors are still on their way)
+  if (threadIdx.x == 0) trace.t[kScanLengthKnown] = wall_clock64();
+#endif
 
   // Order of the memory operations matters: loads return in issue order, so a
   // wave that waits for one load also waits for everything it issued before.
@@ -232,6 +250,7 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
     }
   }
 
+  trace.stamp(kScanQueryReady);
   // The query planes are wave-uniform.  Small groups keep them in vector
   // registers (a VALU instruction takes one scalar operand only, so scalar
   // planes cost an extra move per word); large groups keep them scalar to stay
@@ -321,6 +340,7 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
     }
   }
 
+  trace.stamp(kScanRowsDone);
   // Distances leave through LDS: a lane computed tokens 64 apart, but stores
   // four consecutive tokens (8 bytes), so a wave writes 512 contiguous bytes
   // per query head with one instruction instead of four 2-byte-per-lane ones.
@@ -341,6 +361,7 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
     }
   }
 
+  trace.stamp(kScanDistStored);
   // Algorithm 1, cache update: the new token's K, V and code row enter the cache.  The
   // scan above already used the new code row (from LDS); the stores come last
   // so that no other memory operation sits between the row loads and their use.
@@ -378,6 +399,8 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
       reinterpret_cast<uint32_t*>(row)[pr] = lo | (hi << 16);
     }
   }
+  trace.stamp(kScanEnd);
+  trace.flush(p.trace, p.trace_records);
 }
 
 }  // namespace adamas

@@ -56,6 +56,24 @@ struct SelectParams {
   // Paged cache (PAGED kernels only), as in ScanParams.
   const int32_t* page_table;
   int32_t max_pages, page_shift;
+  // Profiling builds only: one record of phase stamps per workgroup (see PhaseTrace).
+  uint64_t* trace;
+  int64_t trace_records;
+};
+
+// Phase stamps of select_kernel, in the order they are taken.
+enum SelectPhase {
+  kSelStart = 0,      // first instruction
+  kSelLoaded,         // distances, tile histograms and the sequence length have arrived
+  kSelThreshold,      // T and r known to every thread
+  kSelCompacted,      // the segment's selected positions are in LDS / idx_out
+  kSelRowsFirst,      // the first batch of K, V rows has arrived
+  kSelAttended,       // all rows of the segment consumed
+  kSelCombined,       // the row groups' states combined through LDS
+  kSelPartialAcked,   // the partial's stores acknowledged
+  kSelCounted,        // the arrival counter returned
+  kSelMerged,         // (merging workgroup only) partials read back and combined
+  kSelEnd
 };
 
 // Exclusive prefix sum over a workgroup of THREADS threads (a multiple of 64).
@@ -101,7 +119,7 @@ __device__ __forceinline__ void attention_rows(const int32_t* s_sel, int n, int 
                                                const uint16_t* __restrict__ Kp,
                                                const uint16_t* __restrict__ Vp, double scale_log2e,
                                                AttnShared<THREADS, D>& sh, float& M, float& lsum,
-                                               float& o) {
+                                               float& o, PhaseTrace& trace) {
   // Scores in fp64: products of bf16 values are exact, and so (for all practical
   // purposes) is their sum.  An fp32 dot product of 128 terms is off by about
   // 1e-5 in the exponent of a weight; where the weighted rows nearly cancel that
@@ -143,6 +161,7 @@ __device__ __forceinline__ void attention_rows(const int32_t* s_sel, int n, int 
         vv[u] = make_uint4(0, 0, 0, 0);
       }
     }
+    if (i0 == grp) trace.stamp(kSelRowsFirst);
     double sc[U];
     float mn = m;
 #pragma unroll
@@ -182,6 +201,7 @@ __device__ __forceinline__ void attention_rows(const int32_t* s_sel, int n, int 
     }
   }
 
+  trace.stamp(kSelAttended);
   if (gl == 0) {
     sh.m[grp] = m;
     sh.l[grp] = l;
@@ -225,6 +245,8 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
   __shared__ int32_t s_sel[ATTN ? kMaxK : 1];
   __shared__ AttnShared<ATTN ? THREADS : D / 8, D> s_attn;
 
+  PhaseTrace trace;
+  trace.stamp(kSelStart);
   const int seg = blockIdx.x, hq = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63;
   const int64_t head = (int64_t)b * p.Hq + hq;
@@ -283,6 +305,7 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
   const int kk = min(p.k, L);
   const int n_active = max(1, (L + p.seg_len - 1) / p.seg_len);  // segments that hold tokens
   if (seg >= n_active) return;
+  trace.stamp(kSelLoaded);
   const int seg_t1 = min(L, seg_t0 + p.seg_len);
   const int tiles_active = (L + p.tile_tokens - 1) / p.tile_tokens;
 
@@ -357,6 +380,7 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
   __syncthreads();
   const int T = s_T;
   const int r = kk - s_cntlt;  // ties at distance T to take, lowest positions first
+  trace.stamp(kSelThreshold);
 
   if (gridDim.x > 1) {  // tokens of earlier segments: #{D < T} and #{D == T}
     uint32_t ltb = 0, eqb = 0;
@@ -451,13 +475,17 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
   if constexpr (ATTN) {
     const int n_sel = min((int)(run_lt + min(run_eq, (uint32_t)r) - seg_pos0), kk);
     __syncthreads();  // s_sel complete
+    trace.stamp(kSelCompacted);
     const int kvh = hq / (p.Hq / p.Hkv);
     const int64_t row0 = ((int64_t)kvh * p.pool_tokens + (PAGED ? 0 : p.seq_start[b])) * D;
     float M, lsum, o;
     attention_rows<THREADS, D>(s_sel, n_sel, PAGED ? (int)p.pool_tokens : L, p.q + head * D,
-                            p.K + row0, p.V + row0, p.scale_log2e, s_attn, M, lsum, o);
+                            p.K + row0, p.V + row0, p.scale_log2e, s_attn, M, lsum, o, trace);
+    trace.stamp(kSelCombined);
     if (gridDim.x == 1 || (p.arrivals != nullptr && n_active == 1)) {
       if (tid < D) p.out[head * D + tid] = lsum > 0.f ? o / lsum : 0.f;
+      trace.stamp(kSelEnd);
+      trace.flush(p.trace, p.trace_records);
       return;
     }
     float* mine = p.partial + (head * kMaxParts + seg) * kPartial;
@@ -469,6 +497,8 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
         }
         mine[4 + tid] = o;
       }
+      trace.stamp(kSelEnd);
+      trace.flush(p.trace, p.trace_records);
       return;
     }
     // Merge by the last segment to finish.  Everything exchanged between
@@ -487,13 +517,20 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __builtin_amdgcn_s_waitcnt(0);  // this wave's stores are acknowledged
     __syncthreads();
+    trace.stamp(kSelPartialAcked);
     if (tid == 0) {
       const uint32_t before = __hip_atomic_fetch_add(p.arrivals + head * p.arrivals_stride, 1u,
                                                      __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       s_T = before + 1u == (uint32_t)n_active ? 1 : 0;
     }
     __syncthreads();
-    if (s_T == 0 || tid >= D) return;
+    trace.stamp(kSelCounted);
+    if (s_T == 0) {
+      trace.stamp(kSelEnd);
+      trace.flush(p.trace, p.trace_records);
+      return;
+    }
+    if (tid >= D) return;
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
     const float* ph = p.partial + head * kMaxParts * kPartial;
     float pm[kMaxParts], pl[kMaxParts], po[kMaxParts];
@@ -516,6 +553,9 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
       oh = fmaf(use ? po[s] : 0.f, w, oh);
     }
     p.out[head * D + tid] = lh > 0.f ? oh / lh : 0.f;
+    trace.stamp(kSelMerged);
+    trace.stamp(kSelEnd);
+    trace.flush(p.trace, p.trace_records);
   }
 }
 
@@ -566,9 +606,10 @@ __global__ __launch_bounds__(kAttnThreads) void sparse_attn_kernel(const AttnPar
   const int kvh = hq / (p.Hq / p.Hkv);
   const int64_t row0 = ((int64_t)kvh * p.pool_tokens + start) * D;
   float M, lsum, o;
+  PhaseTrace trace;  // not recorded for the stand-alone kernel
   attention_rows<kAttnThreads, D>(s_sel, (int)n, (int)min((int64_t)0x7fffffff, p.pool_tokens - start),
                                p.q + head * D, p.K + row0, p.V + row0,
-                               p.scale_log2e, s_attn, M, lsum, o);
+                               p.scale_log2e, s_attn, M, lsum, o, trace);
   if (tid < D) {
     if (gridDim.x == 1) {
       p.out[head * D + tid] = lsum > 0.f ? o / lsum : 0.f;
