@@ -64,7 +64,7 @@ struct Plan {
   int head_dim;      // 64, 128 or 256
   int g_split;       // scan workgroups per (tile, KV head), each with a share of the query group
   int64_t dist_stride;
-  size_t off_dist, off_hist, off_partial, total;
+  size_t off_dist, off_high, off_hist, off_partial, total;
 };
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -78,11 +78,23 @@ int metric_of(const adamas_config* c) {
   return (c->variant & ADAMAS_VARIANT_L2) ? kMetricL2 : kMetricL1;
 }
 
-// uint16 per stored tile histogram (Dist<METRIC, D>::kStride for run-time arguments)
-size_t hist_stride_of(int metric, int head_dim) {
+// Largest distance of a metric (Dist<METRIC, D>::kMaxDist for run-time arguments).
+int max_dist_of(int metric, int head_dim) {
   const int per_dim = metric == kMetricL1 ? 3 : metric == kMetricL2 ? 9 : metric == kMetricB1 ? 1 : 7;
-  const int bins = per_dim * head_dim + 1;
-  return (size_t)((bins + 7) / 8 * 8);
+  return per_dim * head_dim;
+}
+
+// uint16 per stored tile histogram (Dist<METRIC, D>::kStride)
+size_t hist_stride_of(int metric, int head_dim) {
+  return (size_t)((max_dist_of(metric, head_dim) + 1 + 7) / 8 * 8);
+}
+
+// Bytes per token of the distance plane, and whether a plane of ninth bits goes
+// with it (Dist<METRIC, D>::kDistBytes, kHighPlane).
+int dist_bytes_of(int metric, int head_dim) { return max_dist_of(metric, head_dim) <= 511 ? 1 : 2; }
+bool high_plane_of(int metric, int head_dim) {
+  const int m = max_dist_of(metric, head_dim);
+  return m > 255 && m <= 511;
 }
 
 // The kernels of a (head dimension, metric) pair; nullptr if that pair is not built.
@@ -181,7 +193,9 @@ Plan make_plan(const adamas_config* c, int32_t batch, int64_t max_seq_len, int32
   const size_t heads = (size_t)batch * c->num_q_heads;
   size_t off = 0;
   pl.off_dist = off;
-  off = align256(off + heads * (size_t)pl.dist_stride * sizeof(uint16_t));
+  off = align256(off + heads * (size_t)pl.dist_stride * dist_bytes_of(pl.metric, c->head_dim));
+  pl.off_high = off;
+  if (high_plane_of(pl.metric, c->head_dim)) off = align256(off + heads * (size_t)pl.dist_stride / 8);
   pl.off_hist = off;
   off = align256(off + heads * (size_t)pl.n_tiles * hist_stride_of(pl.metric, c->head_dim) * sizeof(uint16_t));
   pl.off_partial = off;
@@ -411,7 +425,8 @@ int adamas_select_topk(const adamas_config* cfg, const void* qcodes, const void*
   sp.qcodes = static_cast<const uint8_t*>(qcodes);
   sp.seq_start = seq_start;
   sp.seq_len = seq_len;
-  sp.dist = reinterpret_cast<uint16_t*>(ws_at(workspace, pl.off_dist));
+  sp.dist = ws_at(workspace, pl.off_dist);
+  sp.dist_high = reinterpret_cast<uint64_t*>(ws_at(workspace, pl.off_high));
   sp.dist_stride = pl.dist_stride;
   sp.dist_user = dist_out;
   sp.dist_user_stride = max_seq_len;
@@ -426,6 +441,7 @@ int adamas_select_topk(const adamas_config* cfg, const void* qcodes, const void*
 
   SelectParams sl{};
   sl.dist = sp.dist;
+  sl.dist_high = sp.dist_high;
   sl.dist_stride = pl.dist_stride;
   sl.tilehist = sp.tilehist;
   sl.seq_start = seq_start;
@@ -591,7 +607,8 @@ int decode_step_impl(const adamas_config* cfg, const void* q, const void* k_new,
   sp.V = static_cast<uint16_t*>(V);
   sp.seq_start = seq_start;
   sp.seq_len = seq_len;
-  sp.dist = reinterpret_cast<uint16_t*>(ws_at(workspace, pl.off_dist));
+  sp.dist = ws_at(workspace, pl.off_dist);
+  sp.dist_high = reinterpret_cast<uint64_t*>(ws_at(workspace, pl.off_high));
   sp.dist_stride = pl.dist_stride;
   sp.tilehist = reinterpret_cast<uint16_t*>(ws_at(workspace, pl.off_hist));
   sp.pool_tokens = cfg->pool_tokens;
@@ -617,6 +634,7 @@ int decode_step_impl(const adamas_config* cfg, const void* q, const void* k_new,
 
   SelectParams sl{};
   sl.dist = sp.dist;
+  sl.dist_high = sp.dist_high;
   sl.dist_stride = pl.dist_stride;
   sl.tilehist = sp.tilehist;
   sl.seq_start = seq_start;

@@ -30,6 +30,13 @@ struct Dist {
   static constexpr int kStride = (kBins + 7) / 8 * 8;
   // a row is fetched in pieces of the largest power of two (up to 16 bytes) that divides it
   static constexpr int kPiece = kRowBytes % 16 == 0 ? 16 : kRowBytes % 8 == 0 ? 8 : 4;
+  // Distance plane between the scan and the select kernel.  Distances up to 511
+  // travel as one byte (the low eight bits) per token, plus, when they can exceed
+  // 255, a plane of ninth bits (one 64-bit word per 64 consecutive tokens);
+  // larger ranges travel as uint16.
+  static constexpr bool kByteDist = kMaxDist <= 511;
+  static constexpr bool kHighPlane = kByteDist && kMaxDist > 255;
+  static constexpr int kDistBytes = kByteDist ? 1 : 2;
 };
 
 // One aligned load of BYTES (16, 8 or 4) into consecutive 32-bit words.

@@ -5,8 +5,10 @@
 // One workgroup owns one tile of blockDim.x * 4 consecutive tokens of one
 // (sequence, KV head) and evaluates all G query heads of that KV head's
 // group on it, so every code row is fetched once.  It writes
-//   - one uint16 distance per (query head, token) (staged through LDS so that
-//     stores are 8 bytes per lane), and
+//   - one distance per (query head, token), staged through LDS so that a lane
+//     stores four consecutive tokens: a byte each (plus one bit per token in a
+//     plane of ninth bits, written straight from wave ballots) when the metric's
+//     distances stay below 512, as Eq. 6 does (0..384); uint16 otherwise, and
 //   - one histogram of those distances (385 bins for Eq. 6) per (query head, tile),
 // both with plain stores: nothing needs zero-initialised memory and the
 // result does not depend on the order workgroups run in.
@@ -21,6 +23,8 @@
 //   (a - b)^2 = x_lo + 4 * u + 4 * (u & x_lo),  u = x_hi & ~(x_lo & g).
 #pragma once
 
+#include <type_traits>
+
 #include "device_utils.hpp"
 #include "encode.hpp"
 
@@ -28,8 +32,10 @@ namespace adamas {
 
 constexpr int kScanTokPerThread = 4;
 // LDS histogram copies, picked by lane, to thin out same-address atomics: two
-// unless the histograms of the group would then take more than 48 KiB.
-constexpr int hist_replicas(int group, int bins) { return group * bins * 8 > 48 * 1024 ? 1 : 2; }
+// unless the histograms of the group would then take more than 48 KiB.  A copy
+// holds two 16-bit bins per word (a tile has at most 4096 tokens), exactly as
+// the tile histogram is stored.
+constexpr int hist_replicas(int group, int bins) { return group * bins * 4 > 48 * 1024 ? 1 : 2; }
 
 struct ScanParams {
   const uint8_t* codes;      // [Hkv][pool][32]
@@ -42,8 +48,9 @@ struct ScanParams {
   uint16_t* V;
   const int64_t* seq_start;  // [B]
   const int32_t* seq_len;    // [B]
-  uint16_t* dist;            // [B*Hq][dist_stride]; may be null
-  int64_t dist_stride;
+  void* dist;                // [B*Hq][dist_stride] bytes or uint16 (Dist<>::kDistBytes); may be null
+  uint64_t* dist_high;       // ninth bits, [B*Hq][dist_stride / 64] (Dist<>::kHighPlane only)
+  int64_t dist_stride;       // tokens per row, a multiple of 128
   uint16_t* dist_user;       // optional second copy, [B*Hq][dist_user_stride]
   int64_t dist_user_stride;
   uint16_t* tilehist;        // [B*Hq][n_tiles][Dist<METRIC>::kStride]; may be null
@@ -83,13 +90,15 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
   constexpr int kRowWords = W * BITS;  // 32-bit words per code row
   constexpr int kHistReplicas = hist_replicas(G, kNumBins);
   constexpr int E = D / 64;            // elements per lane when a wave encodes one vector
-  __shared__ uint32_t s_hist[G][kHistReplicas][kNumBins];
+  constexpr int kPairs = (kNumBins + 1) / 2;  // 32-bit words of a histogram: two 16-bit bins each
+  __shared__ uint32_t s_hist[G][kHistReplicas][kPairs];
   // per query head: plane p of word wd at [W * p + wd]; 2-bit codes also keep lo^hi at [2W + wd]
   __shared__ uint32_t s_q[G][3 * W];
   __shared__ uint32_t s_new[kRowWords];  // code row of the appended key, as stored
   __shared__ uint32_t s_ready;      // query / new-key code rows published so far
   // per wave: its 256 distances per query head, in token order, for wide stores
-  __shared__ uint16_t s_dt[WAVES][G][kScanTokPerThread * kWave];
+  using DistT = typename std::conditional<Fmt::kByteDist, uint8_t, uint16_t>::type;
+  __shared__ __align__(8) DistT s_dt[WAVES][G][kScanTokPerThread * kWave];
 
   // blockIdx.y = KV head * g_split + part: the G query heads of this workgroup are
   // part `gsub` of the KV head's group of G * g_split (the parts re-read the rows).
@@ -145,7 +154,7 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
   // the waves must not wait for each other: a compute unit serves memory
   // requests in order, so late waves get their rows late, and a barrier after
   // the row loads would hold the early waves back with them.
-  for (int i = tid; i < G * kHistReplicas * kNumBins; i += nthreads)
+  for (int i = tid; i < G * kHistReplicas * kPairs; i += nthreads)
     (&s_hist[0][0][0])[i] = 0u;
   if (tid == 0) s_ready = 0u;
   __syncthreads();
@@ -278,7 +287,7 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
     if constexpr (kQueryInLds) return s_q[g][W * j + wd];
     else return qp[g][j][wd];
   };
-  uint32_t* hist_lane = &s_hist[0][lane & (kHistReplicas - 1)][0];
+  uint32_t* hist_lane = &s_hist[0][lane & (kHistReplicas - 1)][0];  // two 16-bit bins per word
 
 #pragma unroll
   for (int i = 0; i < kScanTokPerThread; ++i) {
@@ -331,11 +340,18 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
         }
         d = c0 + 2u * c1 + 4u * c2;
       }
-      s_dt[wave][g][i * kWave + lane] = (uint16_t)d;
+      s_dt[wave][g][i * kWave + lane] = (DistT)d;
+      if constexpr (Fmt::kHighPlane) {
+        // ninth bits of 64 consecutive tokens = one word of the plane, straight from the ballot
+        const uint64_t high = __ballot(t < L && d > 255u);
+        const int t64 = t0 + (wave * kScanTokPerThread + i) * kWave;
+        if (lane == 0 && p.dist != nullptr && t64 < L)
+          p.dist_high[((int64_t)(head0 + g) * p.dist_stride + t64) >> 6] = high;
+      }
       if (t < L) {
         const int64_t head = head0 + g;
         if (p.dist_user != nullptr) p.dist_user[head * p.dist_user_stride + t] = (uint16_t)d;
-        atomicAdd(hist_lane + g * (kHistReplicas * kNumBins) + d, 1u);
+        atomicAdd(hist_lane + g * (kHistReplicas * kPairs) + (d >> 1), (d & 1u) ? 0x10000u : 1u);
       }
     }
   }
@@ -345,18 +361,21 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
   // four consecutive tokens (8 bytes), so a wave writes 512 contiguous bytes
   // per query head with one instruction instead of four 2-byte-per-lane ones.
   // The region is private to the wave, so no barrier is needed.
+  // A row of the plane holds a multiple of 128 tokens, so a lane whose first
+  // token exists may store all four.
   if (p.dist != nullptr) {
     const int tt = t0 + wave * (kScanTokPerThread * kWave) + kScanTokPerThread * lane;
+    if (tt < L) {
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-      const uint2 v = *reinterpret_cast<const uint2*>(&s_dt[wave][g][kScanTokPerThread * lane]);
-      uint16_t* dst = p.dist + (int64_t)(head0 + g) * p.dist_stride + tt;
-      if (tt + 3 < L) {
-        *reinterpret_cast<uint2*>(dst) = v;
-      } else {
-        if (tt < L) dst[0] = (uint16_t)(v.x & 0xffffu);
-        if (tt + 1 < L) dst[1] = (uint16_t)(v.x >> 16);
-        if (tt + 2 < L) dst[2] = (uint16_t)(v.y & 0xffffu);
+      for (int g = 0; g < G; ++g) {
+        const int64_t at = (int64_t)(head0 + g) * p.dist_stride + tt;
+        if constexpr (Fmt::kByteDist) {
+          *reinterpret_cast<uint32_t*>(static_cast<uint8_t*>(p.dist) + at) =
+              *reinterpret_cast<const uint32_t*>(&s_dt[wave][g][kScanTokPerThread * lane]);
+        } else {
+          *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.dist) + at) =
+              *reinterpret_cast<const uint2*>(&s_dt[wave][g][kScanTokPerThread * lane]);
+        }
       }
     }
   }
@@ -385,18 +404,14 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
     p.arrivals[(int64_t)(head0 + tid) * p.arrivals_stride] = 0u;
   if (p.tilehist != nullptr) {
     __syncthreads();
-    // two 16-bit bins per 32-bit store; bins kNumBins.. of a stored row stay unwritten
-    constexpr int kPairs = (kNumBins + 1) / 2;
+    // bins kNumBins.. of a stored row stay unwritten
     for (int i = tid; i < G * kPairs; i += nthreads) {
       const int g = i / kPairs, pr = i - g * kPairs;
-      uint32_t lo = 0, hi = 0;
+      uint32_t v = 0;
 #pragma unroll
-      for (int r = 0; r < kHistReplicas; ++r) {
-        lo += s_hist[g][r][2 * pr];
-        if (2 * pr + 1 < kNumBins) hi += s_hist[g][r][2 * pr + 1];
-      }
+      for (int r = 0; r < kHistReplicas; ++r) v += s_hist[g][r][pr];
       uint16_t* row = p.tilehist + ((int64_t)(head0 + g) * p.n_tiles + tile_id) * kHistStride;
-      reinterpret_cast<uint32_t*>(row)[pr] = lo | (hi << 16);
+      reinterpret_cast<uint32_t*>(row)[pr] = v;
     }
   }
   trace.stamp(kScanEnd);

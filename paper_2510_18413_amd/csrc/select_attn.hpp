@@ -36,8 +36,9 @@ constexpr int kMaxK = 4096;
 constexpr float kNegBig = -1.0e30f;
 
 struct SelectParams {
-  const uint16_t* dist;       // [B*Hq][dist_stride]
-  int64_t dist_stride;
+  const void* dist;           // [B*Hq][dist_stride] bytes or uint16 (Dist<>::kDistBytes)
+  const uint64_t* dist_high;  // ninth bits, [B*Hq][dist_stride / 64] (Dist<>::kHighPlane only)
+  int64_t dist_stride;        // tokens per row, a multiple of 128
   const uint16_t* tilehist;   // [B*Hq][n_tiles][Dist<METRIC>::kStride]
   const int64_t* seq_start;   // [B]
   const int32_t* seq_len;     // [B]
@@ -223,6 +224,38 @@ __device__ __forceinline__ void attention_rows(const int32_t* s_sel, int n, int 
   }
 }
 
+// Candidate masks of one 32-bit word of the distance plane against the threshold
+// distance T: bit (8 or 16) * j + (7 or 15) of lt / eq is set when token j of the
+// word has distance < T / == T.  Byte planes hold four tokens per word, their
+// ninth bits come separately (high4: bit j = ninth bit of token j).
+template <bool BYTES>
+__device__ __forceinline__ void word_masks(uint32_t w, uint32_t high4, int T, uint32_t& lt, uint32_t& eq) {
+  if constexpr (BYTES) {
+    constexpr uint32_t H = 0x80808080u, L7 = 0x7f7f7f7fu;
+    const uint32_t y = (uint32_t)(T & 255) * 0x01010101u;
+    // per byte, no borrow between bytes: bit 7 of t = (low 7 bits of w >= low 7 bits of y)
+    const uint32_t t = (w | H) - (y & L7);
+    const uint32_t lt8 = ((~w & y) | (~(w ^ y) & ~t)) & H;       // unsigned byte compare
+    const uint32_t z = w ^ y;
+    const uint32_t eq8 = ~(((z & L7) + L7) | z) & H;             // byte of z is zero
+    // ninth bits spread to bit 7 of their bytes
+    const uint32_t e = (high4 * 0x10204080u) & H;
+    if (T < 256) {
+      lt = lt8 & ~e;
+      eq = eq8 & ~e;
+    } else {
+      lt = (~e & H) | lt8;
+      eq = eq8 & e;
+    }
+  } else {
+    // two uint16 per word, both operands below 2^15
+    const uint32_t TT = (uint32_t)T * 0x00010001u;
+    lt = pk_sub_u16(w, TT) & 0x80008000u;
+    const uint32_t z = w ^ TT;
+    eq = pk_sub_u16(z, 0x00010001u) & ~z & 0x80008000u;
+  }
+}
+
 // Grid (n_segs, Hq, B).  With ATTN a head that has a single segment with
 // tokens is finished by that workgroup; otherwise each workgroup leaves an
 // (M, lsum, o[128]) partial, merged by the last one to arrive (p.arrivals set)
@@ -231,15 +264,17 @@ template <int THREADS, bool ATTN, int METRIC, bool PAGED, int D>
 __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
   static_assert(ATTN || !PAGED, "only the gather needs the page table");
   static_assert(THREADS >= D, "one thread per output dimension in the merge");
-  constexpr int kNumBins = Dist<METRIC, D>::kBins, kHistStride = Dist<METRIC, D>::kStride;
+  using Fmt = Dist<METRIC, D>;
+  constexpr int kNumBins = Fmt::kBins, kHistStride = Fmt::kStride;
+  constexpr bool BYTES = Fmt::kByteDist, HIGH = Fmt::kHighPlane;
   constexpr int kPartial = partial_stride(D);
   constexpr int kHistPairs = kHistStride / 2;                      // pairs of uint16 bins per stored row
-  constexpr int PP = (kHistPairs + THREADS - 1) / THREADS;         // pairs owned by one thread
-  constexpr int BPL = (kNumBins + kWave - 1) / kWave;              // bins per lane in the threshold search
-  constexpr int kTot = BPL * kWave;
-  constexpr int PASS = THREADS * kSelTokPerThread;           // tokens per pass
-  __shared__ uint32_t s_tot[kTot];
-  __shared__ uint32_t s_scan[THREADS / kWave];
+  constexpr int PP = (kHistPairs + THREADS - 1) / THREADS;         // consecutive pairs owned by one thread
+  constexpr int NW = THREADS / kWave;
+  constexpr int PASS = THREADS * kSelTokPerThread;                 // tokens per pass
+  constexpr int DW = BYTES ? 4 : 8;                                // 32-bit words of 16 distances
+  constexpr int TPW = 16 / DW;                                     // tokens per word
+  __shared__ uint32_t s_wtot[2][NW], s_wpre[NW];
   __shared__ int32_t s_T, s_cntlt;
   __shared__ uint32_t s_ltb, s_eqb;
   __shared__ int32_t s_sel[ATTN ? kMaxK : 1];
@@ -248,31 +283,30 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
   PhaseTrace trace;
   trace.stamp(kSelStart);
   const int seg = blockIdx.x, hq = blockIdx.y, b = blockIdx.z;
-  const int tid = threadIdx.x, lane = tid & 63;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int64_t head = (int64_t)b * p.Hq + hq;
   const int seg_t0 = seg * p.seg_len;
 
   // Nothing below depends on the sequence length until the loads are issued:
   // the workspace rows exist up to dist_stride / n_tiles whatever L is, and
   // what lies beyond L is masked once L has arrived.
-  const uint16_t* drow = p.dist + head * p.dist_stride;
-  // distances of this thread for the current pass and the next one (rolling prefetch)
-  uint4 cur_a, cur_b, nxt_a, nxt_b;
+  const uint8_t* drow = static_cast<const uint8_t*>(p.dist) + head * p.dist_stride * Fmt::kDistBytes;
+  const uint16_t* hrow_high = reinterpret_cast<const uint16_t*>(p.dist_high) + head * (p.dist_stride >> 4);
+  // distances (and ninth bits) of this thread for the current pass and the next one (rolling prefetch)
+  uint32_t cur[DW], nxt[DW], cur_high = 0, nxt_high = 0;
   {
     const int o0 = tid * kSelTokPerThread, o1 = PASS + tid * kSelTokPerThread;
+#pragma unroll
+    for (int w = 0; w < DW; ++w) cur[w] = nxt[w] = 0;
     if (o0 < p.seg_len && seg_t0 + o0 < p.dist_stride) {
-      const uint4* src = reinterpret_cast<const uint4*>(drow + seg_t0 + o0);
-      cur_a = src[0];
-      cur_b = src[1];
-    } else {
-      cur_a = cur_b = make_uint4(0, 0, 0, 0);
+#pragma unroll
+      for (int c = 0; c < DW / 4; ++c) load_piece<16>(drow + (int64_t)(seg_t0 + o0) * Fmt::kDistBytes + 16 * c, &cur[4 * c]);
+      if constexpr (HIGH) cur_high = hrow_high[(seg_t0 + o0) >> 4];
     }
     if (o1 < p.seg_len && seg_t0 + o1 < p.dist_stride) {
-      const uint4* src = reinterpret_cast<const uint4*>(drow + seg_t0 + o1);
-      nxt_a = src[0];
-      nxt_b = src[1];
-    } else {
-      nxt_a = nxt_b = make_uint4(0, 0, 0, 0);
+#pragma unroll
+      for (int c = 0; c < DW / 4; ++c) load_piece<16>(drow + (int64_t)(seg_t0 + o1) * Fmt::kDistBytes + 16 * c, &nxt[4 * c]);
+      if constexpr (HIGH) nxt_high = hrow_high[(seg_t0 + o1) >> 4];
     }
   }
   // Paged cache: a thread's 16 consecutive tokens share one page; its number is
@@ -284,13 +318,13 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
     cur_pg = prow[min(t_a >> p.page_shift, p.max_pages - 1)];
     nxt_pg = prow[min((t_a + PASS) >> p.page_shift, p.max_pages - 1)];
   }
-  // Tile histograms: a thread owns PP pairs of bins, pair tid + j * THREADS (one
-  // 32-bit load per pair and tile); pairs past the row repeat its last pair.
+  // Tile histograms: a thread owns PP consecutive pairs of bins (one 32-bit load
+  // per pair and tile); pairs past the row repeat its last pair and count as zero.
   const uint16_t* hrow = p.tilehist + head * p.n_tiles * kHistStride;
   const int first_tile = seg_t0 / p.tile_tokens;
   int pair[PP];
 #pragma unroll
-  for (int j = 0; j < PP; ++j) pair[j] = min(tid + j * THREADS, kHistPairs - 1);
+  for (int j = 0; j < PP; ++j) pair[j] = min(tid * PP + j, kHistPairs - 1);
   uint32_t hv[PP][kHistBatch];
 #pragma unroll
   for (int u = 0; u < kHistBatch; ++u) {  // clamped, branch-free: all loads in flight together
@@ -309,10 +343,14 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
   const int seg_t1 = min(L, seg_t0 + p.seg_len);
   const int tiles_active = (L + p.tile_tokens - 1) / p.tile_tokens;
 
-  // Head histogram (all tiles with tokens) and the part of it before this segment.
+  // Head histogram (all tiles with tokens) and the part of it before this
+  // segment, two 16-bit bins per word.  A bin of the head total stays below
+  // 2^16 for sequences of up to 65535 tokens, so that the packed words can be
+  // added as they are; longer sequences add the halves separately.
   uint32_t tot0[PP], tot1[PP], pre0[PP], pre1[PP];
 #pragma unroll
   for (int j = 0; j < PP; ++j) tot0[j] = tot1[j] = pre0[j] = pre1[j] = 0;
+  const bool packed_sums = p.max_seq_len < 65536;
   for (int tb = 0; tb < tiles_active; tb += kHistBatch) {
     if (tb > 0) {
 #pragma unroll
@@ -323,31 +361,56 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
         for (int j = 0; j < PP; ++j) hv[j][u] = trow[pair[j]];
       }
     }
+    if (packed_sums) {
 #pragma unroll
-    for (int u = 0; u < kHistBatch; ++u) {
+      for (int u = 0; u < kHistBatch; ++u) {
 #pragma unroll
-      for (int j = 0; j < PP; ++j) {
-        const uint32_t v = tb + u < tiles_active ? hv[j][u] : 0u;
-        tot0[j] += v & 0xffffu;
-        tot1[j] += v >> 16;
-        if (tb + u < first_tile) {
-          pre0[j] += v & 0xffffu;
-          pre1[j] += v >> 16;
+        for (int j = 0; j < PP; ++j) {
+          tot0[j] += tb + u < tiles_active ? hv[j][u] : 0u;
+          pre0[j] += tb + u < first_tile ? hv[j][u] : 0u;   // first_tile <= tiles_active here
+        }
+      }
+    } else {
+#pragma unroll
+      for (int u = 0; u < kHistBatch; ++u) {
+#pragma unroll
+        for (int j = 0; j < PP; ++j) {
+          const uint32_t v = tb + u < tiles_active ? hv[j][u] : 0u;
+          tot0[j] += v & 0xffffu;
+          tot1[j] += v >> 16;
+          if (tb + u < first_tile) {
+            pre0[j] += v & 0xffffu;
+            pre1[j] += v >> 16;
+          }
         }
       }
     }
   }
-  // Head histogram into LDS: a thread writes the bins of its pairs (bins past
-  // kNumBins hold nothing and count as zero), the tail up to kTot is cleared.
+  uint32_t sum_tot = 0, sum_pre = 0;
 #pragma unroll
   for (int j = 0; j < PP; ++j) {
-    const int pr = tid + j * THREADS;
-    if (pr < kHistPairs) {
-      s_tot[2 * pr] = 2 * pr < kNumBins ? tot0[j] : 0u;
-      s_tot[2 * pr + 1] = 2 * pr + 1 < kNumBins ? tot1[j] : 0u;
+    if (packed_sums) {
+      tot1[j] = tot0[j] >> 16;
+      tot0[j] &= 0xffffu;
+      pre1[j] = pre0[j] >> 16;
+      pre0[j] &= 0xffffu;
     }
+    // bins past the last one were never written (and pairs past the row repeat its last pair)
+    if (2 * (tid * PP + j) >= kNumBins) tot0[j] = pre0[j] = 0u;
+    if (2 * (tid * PP + j) + 1 >= kNumBins) tot1[j] = pre1[j] = 0u;
+    sum_tot += tot0[j] + tot1[j];
+    sum_pre += pre0[j] + pre1[j];
   }
-  for (int i = kHistStride + tid; i < kTot; i += THREADS) s_tot[i] = 0u;
+  // Threshold distance T = the bin in which the cumulative count reaches kk,
+  // #{D < T} over the head, and (for the output offset of this segment) #{D < T}
+  // and #{D == T} over the tokens of earlier segments: two prefix sums over the
+  // bins in thread order, then the one thread whose bins contain the kk-th token
+  // publishes all four.
+  const uint32_t incl_tot = wave_incl_scan_u32(sum_tot), incl_pre = wave_incl_scan_u32(sum_pre);
+  if (lane == 63) {
+    s_wtot[0][wave] = incl_tot;
+    s_wpre[wave] = incl_pre;
+  }
   if (tid == 0) {
     s_ltb = 0u;
     s_eqb = 0u;
@@ -355,64 +418,55 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
     s_cntlt = 0;
   }
   __syncthreads();
-
-  // Threshold distance T and #{D < T}, by one wave: BPL bins per lane.
-  if (tid < kWave) {
-    uint32_t c[BPL], sum = 0;
+  {
+    uint32_t run = incl_tot - sum_tot, run_pre = incl_pre - sum_pre;
 #pragma unroll
-    for (int j = 0; j < BPL; ++j) {
-      c[j] = s_tot[lane * BPL + j];
-      sum += c[j];
+    for (int w = 0; w < NW; ++w) {
+      run += w < wave ? s_wtot[0][w] : 0u;
+      run_pre += w < wave ? s_wpre[w] : 0u;
     }
-    const uint32_t incl = wave_incl_scan_u32(sum);
-    uint32_t run = incl - sum;
-    if (kk > 0 && run < (uint32_t)kk && incl >= (uint32_t)kk) {
+    if (kk > 0 && run < (uint32_t)kk && run + sum_tot >= (uint32_t)kk) {
 #pragma unroll
-      for (int j = 0; j < BPL; ++j) {
-        if (run < (uint32_t)kk && run + c[j] >= (uint32_t)kk) {
-          s_T = lane * BPL + j;
-          s_cntlt = (int32_t)run;
+      for (int j = 0; j < PP; ++j) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          const uint32_t c = h ? tot1[j] : tot0[j], cp = h ? pre1[j] : pre0[j];
+          if (run < (uint32_t)kk && run + c >= (uint32_t)kk) {
+            s_T = 2 * (tid * PP + j) + h;
+            s_cntlt = (int32_t)run;
+            s_ltb = run_pre;
+            s_eqb = cp;
+          }
+          run += c;
+          run_pre += cp;
         }
-        run += c[j];
       }
     }
   }
   __syncthreads();
   const int T = s_T;
   const int r = kk - s_cntlt;  // ties at distance T to take, lowest positions first
-  trace.stamp(kSelThreshold);
-
-  if (gridDim.x > 1) {  // tokens of earlier segments: #{D < T} and #{D == T}
-    uint32_t ltb = 0, eqb = 0;
-#pragma unroll
-    for (int j = 0; j < PP; ++j) {
-      const int pr = tid + j * THREADS, bin0 = 2 * pr, bin1 = 2 * pr + 1;
-      if (pr < kHistPairs) {
-        ltb += (bin0 < T ? pre0[j] : 0u) + (bin1 < T ? pre1[j] : 0u);
-        eqb += (bin0 == T ? pre0[j] : 0u) + (bin1 == T ? pre1[j] : 0u);
-      }
-    }
-    ltb = wave_sum_u32(ltb);
-    eqb = wave_sum_u32(eqb);
-    if (lane == 0) {
-      atomicAdd(&s_ltb, ltb);
-      atomicAdd(&s_eqb, eqb);
-    }
-    __syncthreads();
-  }
   uint32_t run_lt = s_ltb, run_eq = s_eqb;
+  trace.stamp(kSelThreshold);
   const uint32_t seg_pos0 = run_lt + min(run_eq, (uint32_t)r);
   int32_t* idx_row = p.idx_out != nullptr ? p.idx_out + head * p.k : nullptr;
 
-  for (int pass_t0 = seg_t0; pass_t0 < seg_t1; pass_t0 += PASS) {
+  int pass_no = 0;
+  for (int pass_t0 = seg_t0; pass_t0 < seg_t1; pass_t0 += PASS, ++pass_no) {
     const int t = pass_t0 + tid * kSelTokPerThread;
-    const uint4 da = cur_a, db = cur_b;
-    cur_a = nxt_a;
-    cur_b = nxt_b;
+    uint32_t dw[DW];
+#pragma unroll
+    for (int w = 0; w < DW; ++w) {
+      dw[w] = cur[w];
+      cur[w] = nxt[w];
+    }
+    const uint32_t high = cur_high;
+    cur_high = nxt_high;
     if (t + 2 * PASS < seg_t1) {  // fetch the pass after next while this one is processed
-      const uint4* src = reinterpret_cast<const uint4*>(drow + t + 2 * PASS);
-      nxt_a = src[0];
-      nxt_b = src[1];
+#pragma unroll
+      for (int c = 0; c < DW / 4; ++c)
+        load_piece<16>(drow + (int64_t)(t + 2 * PASS) * Fmt::kDistBytes + 16 * c, &nxt[4 * c]);
+      if constexpr (HIGH) nxt_high = hrow_high[(t + 2 * PASS) >> 4];
     }
     int64_t page_row0 = 0;  // pool row of token t's page, minus the page offset of t itself
     if constexpr (PAGED) {
@@ -423,48 +477,59 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
         nxt_pg = p.page_table[(int64_t)b * p.max_pages +
                               min((t + 2 * PASS) >> p.page_shift, p.max_pages - 1)];
     }
-    // Two distances per 32-bit word.  Per half-word, without unpacking:
-    //   d < T  <=> bit 15 of (d - T) mod 2^16   (both below 2^15)
-    //   d == T <=> (z - 1) & ~z has bit 15 set, z = d ^ T
-    // Bit j of m_lt / m_eq stands for token t + j.
-    const uint32_t words[8] = {da.x, da.y, da.z, da.w, db.x, db.y, db.z, db.w};
-    const uint32_t TT = (uint32_t)T * 0x00010001u;
-    uint32_t m_lt = 0, m_eq = 0;
-#pragma unroll
-    for (int w = 0; w < 8; ++w) {
-      const uint32_t y = pk_sub_u16(words[w], TT) & 0x80008000u;
-      const uint32_t z = words[w] ^ TT;
-      const uint32_t e = pk_sub_u16(z, 0x00010001u) & ~z & 0x80008000u;
-      m_lt |= (((y >> 15) & 1u) | (y >> 30)) << (2 * w);
-      m_eq |= (((e >> 15) & 1u) | (e >> 30)) << (2 * w);
-    }
+    // Per word: which of its tokens lie below / at the threshold (word_masks),
+    // restricted to the tokens of this thread that exist.
     const int n_valid = min(max(seg_t1 - t, 0), kSelTokPerThread);
-    const uint32_t vmask = (1u << n_valid) - 1u;
-    m_lt &= vmask;
-    m_eq &= vmask;
-    uint32_t total;
-    const uint32_t ex =
-        block_excl_scan<THREADS>((uint32_t)__popc(m_lt) | ((uint32_t)__popc(m_eq) << 16), s_scan, total);
+    uint32_t m_lt[DW], m_eq[DW], n_lt = 0, n_eq = 0;
+#pragma unroll
+    for (int w = 0; w < DW; ++w) {
+      word_masks<BYTES>(dw[w], HIGH ? (high >> (4 * w)) & 0xfu : 0u, T, m_lt[w], m_eq[w]);
+      // tokens TPW * w .. of the thread: keep the first n_valid - TPW * w of the word
+      const int keep = min(max(n_valid - TPW * w, 0), TPW);
+      const uint32_t vm = keep == TPW ? 0xffffffffu : (1u << ((32 / TPW) * keep)) - 1u;
+      m_lt[w] &= vm;
+      m_eq[w] &= vm;
+      n_lt += (uint32_t)__popc(m_lt[w]);
+      n_eq += (uint32_t)__popc(m_eq[w]);
+    }
+    // exclusive prefix over the workgroup (one barrier per pass: the wave totals alternate buffers)
+    const uint32_t cnt = n_lt | (n_eq << 16);
+    const uint32_t incl = wave_incl_scan_u32(cnt);
+    uint32_t* wt = s_wtot[pass_no & 1];
+    if (lane == 63) wt[wave] = incl;
+    __syncthreads();
+    uint32_t before = 0, total = 0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+      const uint32_t x = wt[w];
+      before += w < wave ? x : 0u;
+      total += x;
+    }
+    const uint32_t ex = before + incl - cnt;
     uint32_t lt = run_lt + (ex & 0xffffu), eq = run_eq + (ex >> 16);
     // Visit only the candidate tokens (set bits), in position order.
-    uint32_t cand = m_lt | m_eq;
-    while (cand != 0u) {
-      const int j = __builtin_ctz(cand);
-      cand &= cand - 1u;
-      const bool is_eq = (m_eq >> j) & 1u;
-      if (!is_eq || eq < (uint32_t)r) {
-        const uint32_t pos = lt + min(eq, (uint32_t)r);
-        // pos < kk always holds for consistent histograms; the checks keep a
-        // corrupted workspace from turning into an out-of-bounds store.
-        if (pos < (uint32_t)kk) {
-          if (idx_row != nullptr) idx_row[pos] = t + j;
-          // the gather list holds token positions, or pool rows for a paged cache
-          if (ATTN && pos - seg_pos0 < (uint32_t)kMaxK)
-            s_sel[pos - seg_pos0] = PAGED ? (int32_t)(page_row0 + j) : t + j;
+#pragma unroll
+    for (int w = 0; w < DW; ++w) {
+      uint32_t cand = m_lt[w] | m_eq[w];
+      while (cand != 0u) {
+        const int bit = __builtin_ctz(cand);
+        cand &= cand - 1u;
+        const bool is_eq = (m_eq[w] >> bit) & 1u;
+        const int j = TPW * w + bit / (32 / TPW);
+        if (!is_eq || eq < (uint32_t)r) {
+          const uint32_t pos = lt + min(eq, (uint32_t)r);
+          // pos < kk always holds for consistent histograms; the checks keep a
+          // corrupted workspace from turning into an out-of-bounds store.
+          if (pos < (uint32_t)kk) {
+            if (idx_row != nullptr) idx_row[pos] = t + j;
+            // the gather list holds token positions, or pool rows for a paged cache
+            if (ATTN && pos - seg_pos0 < (uint32_t)kMaxK)
+              s_sel[pos - seg_pos0] = PAGED ? (int32_t)(page_row0 + j) : t + j;
+          }
         }
+        lt += is_eq ? 0u : 1u;
+        eq += is_eq ? 1u : 0u;
       }
-      lt += is_eq ? 0u : 1u;
-      eq += is_eq ? 1u : 0u;
     }
     run_lt += total & 0xffffu;
     run_eq += total >> 16;
