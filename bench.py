@@ -100,6 +100,7 @@ def algorithmic_bytes(B, Hq, Hkv, lens, k, append, row_bytes=32, head_dim=128):
 SCAN_PHASES = ["start", "length known", "query planes ready", "rows consumed",
                "distances stored", "histogram flushed (end)"]
 SELECT_PHASES = ["start", "distances + histograms + length loaded", "threshold T known",
+                 "first pass: candidate masks and counts", "first pass: prefix over the workgroup",
                  "compaction done", "first K/V rows arrived", "rows consumed",
                  "row groups combined", "partial stored + acknowledged", "arrival counted",
                  "merged (last workgroup only)", "end"]

@@ -58,7 +58,7 @@ constexpr double kLog2e = 1.4426950408889634;
 struct Plan {
   int tile_tokens;   // tokens per scan workgroup (threads = tile_tokens / 4): 1024, 2048 or 4096
   int n_tiles;       // scan tiles per (sequence, KV head)
-  int seg_len;       // tokens per select workgroup, a multiple of kSegGranule (hence of the tile)
+  int seg_len;       // tokens per select workgroup, kSegGranule times a power of two (a multiple of the tile)
   int n_segs;        // select workgroups per (sequence, query head)
   int metric;        // code format + distance estimator (struct Dist)
   int head_dim;      // 64, 128 or 256
@@ -68,6 +68,18 @@ struct Plan {
 };
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// ceil(2^32 / group), 0 for a group of one (kv_head_of in the kernels)
+uint32_t group_magic_of(const adamas_config* c) {
+  const uint64_t g = (uint64_t)(c->num_q_heads / c->num_kv_heads);
+  return g == 1 ? 0u : (uint32_t)((((uint64_t)1 << 32) + g - 1) / g);
+}
+
+int log2_of(int64_t pow2) {
+  int s = 0;
+  while (((int64_t)1 << s) < pow2) ++s;
+  return s;
+}
 
 int code_bits(const adamas_config* c) { return c->code_bits == 0 ? 2 : c->code_bits; }
 
@@ -84,10 +96,8 @@ int max_dist_of(int metric, int head_dim) {
   return per_dim * head_dim;
 }
 
-// uint16 per stored tile histogram (Dist<METRIC, D>::kStride)
-size_t hist_stride_of(int metric, int head_dim) {
-  return (size_t)((max_dist_of(metric, head_dim) + 1 + 7) / 8 * 8);
-}
+// 32-bit words of a tile histogram (Dist<METRIC, D>::kPairs)
+size_t hist_pairs_of(int metric, int head_dim) { return (size_t)(max_dist_of(metric, head_dim) + 2) / 2; }
 
 // Bytes per token of the distance plane, and whether a plane of ninth bits goes
 // with it (Dist<METRIC, D>::kDistBytes, kHighPlane).
@@ -185,8 +195,9 @@ Plan make_plan(const adamas_config* c, int32_t batch, int64_t max_seq_len, int32
   const int64_t n_heads = (int64_t)batch * c->num_q_heads;
   int64_t want = (2 * kTargetWorkgroups + n_heads - 1) / n_heads;
   if (want > kMaxParts) want = kMaxParts;
-  int64_t seg = (max_seq_len + want - 1) / want;
-  seg = (seg + kSegGranule - 1) / kSegGranule * kSegGranule;  // multiple of every tile size
+  // a power of two (the select kernel shifts instead of dividing) and a multiple of every tile size
+  int64_t seg = kSegGranule;
+  while (seg * want < max_seq_len) seg *= 2;
   pl.seg_len = (int)seg;
   pl.n_segs = (int)((max_seq_len + seg - 1) / seg);
   pl.dist_stride = (max_seq_len + 127) & ~(int64_t)127;
@@ -197,7 +208,9 @@ Plan make_plan(const adamas_config* c, int32_t batch, int64_t max_seq_len, int32
   pl.off_high = off;
   if (high_plane_of(pl.metric, c->head_dim)) off = align256(off + heads * (size_t)pl.dist_stride / 8);
   pl.off_hist = off;
-  off = align256(off + heads * (size_t)pl.n_tiles * hist_stride_of(pl.metric, c->head_dim) * sizeof(uint16_t));
+  // + kHistBatch rows: the select kernel reads whole batches of tile rows, also behind the last head's
+  off = align256(off + (heads * (size_t)pl.n_tiles + kHistBatch) * hist_pairs_of(pl.metric, c->head_dim) *
+                           sizeof(uint32_t));
   pl.off_partial = off;
   off = align256(off + heads * (size_t)kMaxParts * partial_stride(c->head_dim) * sizeof(float));
   pl.total = off;
@@ -430,7 +443,7 @@ int adamas_select_topk(const adamas_config* cfg, const void* qcodes, const void*
   sp.dist_stride = pl.dist_stride;
   sp.dist_user = dist_out;
   sp.dist_user_stride = max_seq_len;
-  sp.tilehist = reinterpret_cast<uint16_t*>(ws_at(workspace, pl.off_hist));
+  sp.tilehist = reinterpret_cast<uint32_t*>(ws_at(workspace, pl.off_hist));
   sp.pool_tokens = cfg->pool_tokens;
   sp.max_seq_len = max_seq_len;
   sp.Hq = cfg->num_q_heads;
@@ -452,9 +465,12 @@ int adamas_select_topk(const adamas_config* cfg, const void* qcodes, const void*
   sl.Hq = cfg->num_q_heads;
   sl.Hkv = cfg->num_kv_heads;
   sl.k = k;
+  sl.group_magic = group_magic_of(cfg);
   sl.n_tiles = pl.n_tiles;
   sl.tile_tokens = pl.tile_tokens;
   sl.seg_len = pl.seg_len;
+  sl.tile_shift = log2_of(pl.tile_tokens);
+  sl.seg_shift = log2_of(pl.seg_len);
   set_of(cfg).select(false, false, dim3(pl.n_segs, cfg->num_q_heads, batch), st, sl);
   return launch_status();
 }
@@ -484,6 +500,7 @@ int adamas_sparse_attn(const adamas_config* cfg, const void* q, const void* K, c
   ap.Hq = cfg->num_q_heads;
   ap.Hkv = cfg->num_kv_heads;
   ap.k = k;
+  ap.group_magic = group_magic_of(cfg);
   // about 32 rows per workgroup, at most kAttnPartsMax workgroups per head
   int parts = (k + 31) / 32;
   if (parts > kMaxParts) parts = kMaxParts;
@@ -610,7 +627,7 @@ int decode_step_impl(const adamas_config* cfg, const void* q, const void* k_new,
   sp.dist = ws_at(workspace, pl.off_dist);
   sp.dist_high = reinterpret_cast<uint64_t*>(ws_at(workspace, pl.off_high));
   sp.dist_stride = pl.dist_stride;
-  sp.tilehist = reinterpret_cast<uint16_t*>(ws_at(workspace, pl.off_hist));
+  sp.tilehist = reinterpret_cast<uint32_t*>(ws_at(workspace, pl.off_hist));
   sp.pool_tokens = cfg->pool_tokens;
   sp.max_seq_len = max_seq_len;
   sp.Hq = cfg->num_q_heads;
@@ -652,9 +669,12 @@ int decode_step_impl(const adamas_config* cfg, const void* q, const void* k_new,
   sl.Hq = cfg->num_q_heads;
   sl.Hkv = cfg->num_kv_heads;
   sl.k = k;
+  sl.group_magic = group_magic_of(cfg);
   sl.n_tiles = pl.n_tiles;
   sl.tile_tokens = pl.tile_tokens;
   sl.seg_len = pl.seg_len;
+  sl.tile_shift = log2_of(pl.tile_tokens);
+  sl.seg_shift = log2_of(pl.seg_len);
   sl.scale_log2e = scale_log2e(cfg);
   sl.page_table = page_table;
   sl.max_pages = max_pages;

@@ -26,8 +26,12 @@ struct Dist {
   static constexpr int kMaxDist =  // largest distance between two code vectors
       (METRIC == kMetricL1 ? 3 : METRIC == kMetricL2 ? 9 : METRIC == kMetricB1 ? 1 : 7) * D;
   static constexpr int kBins = kMaxDist + 1;  // distinct distance values: 385 for the method
-  // uint16 per stored tile histogram, a 16-byte multiple (392 for the method)
-  static constexpr int kStride = (kBins + 7) / 8 * 8;
+  // A tile histogram travels as kPairs 32-bit words of two 16-bit bins each (a
+  // tile has at most 4096 tokens): [head][tile][word].  (Word-major rows, which
+  // would let the select kernel fetch 16 tiles of a word with four 16-byte loads,
+  // make every scan workgroup scatter 4-byte stores over lines that workgroups
+  // on other XCDs write too: measured 0.6 us slower for the scan.)
+  static constexpr int kPairs = (kBins + 1) / 2;
   // a row is fetched in pieces of the largest power of two (up to 16 bytes) that divides it
   static constexpr int kPiece = kRowBytes % 16 == 0 ? 16 : kRowBytes % 8 == 0 ? 8 : 4;
   // Distance plane between the scan and the select kernel.  Distances up to 511
@@ -56,21 +60,77 @@ __device__ __forceinline__ void load_piece(const uint8_t* src, uint32_t* w) {
 constexpr int partial_stride(int d) { return d + 4; }
 constexpr int kWave = 64;
 
+// Query head -> KV head without a division: magic = ceil(2^32 / group) from the
+// host (0 for a group of one); exact for every head index below 2^29.
+__device__ __forceinline__ int kv_head_of(int hq, uint32_t group_magic) {
+  return group_magic == 0u ? hq : (int)__umulhi((uint32_t)hq, group_magic);
+}
+
+// Loads of values that every lane of the workgroup reads from one address and
+// that no kernel of the library writes (sequence lengths and starts, page-table
+// entries), in two flavours:
+//  - scalar: through the constant address space, so that the compiler emits
+//    scalar loads.  They have their own counter, so waiting for them does not
+//    wait for vector loads in flight (the scan kernel, which cannot address its
+//    rows without them and has conditional vector loads in front of them);
+//  - vector: plain loads.  Vector loads return in issue order, so a kernel that
+//    requests these first and its speculative data afterwards can wait for
+//    these alone (the select kernel; a scalar load would share its counter with
+//    kernel-argument loads the data loads have to wait for).
+__device__ __forceinline__ int32_t scalar_load(const int32_t* p) {
+  return *(const __attribute__((address_space(4))) int32_t*)(uintptr_t)p;
+}
+__device__ __forceinline__ int64_t scalar_load(const int64_t* p) {
+  return *(const __attribute__((address_space(4))) int64_t*)(uintptr_t)p;
+}
+
 // Length of sequence b as the kernels use it: a sequence whose (device-side,
 // unvalidated) start / length would reach outside the pool or beyond
 // max_seq_len is treated as empty instead of being read out of bounds.
-__device__ __forceinline__ int safe_seq_len(const int32_t* seq_len, const int64_t* seq_start, int b,
-                                            int64_t max_seq_len, int64_t pool_tokens) {
-  const int64_t L = seq_len[b], s = seq_start[b];
-  const bool ok = L >= 0 && L <= max_seq_len && s >= 0 && s + L <= pool_tokens;
-  return ok ? (int)L : 0;
+// The kernels request the raw values first of all (request), issue their
+// speculative loads, and only then look at the values (length).
+struct SeqInfo {
+  int32_t len_raw;
+  int64_t start;  // 0 for a paged cache
+  template <bool PAGED, bool SCALAR>
+  __device__ __forceinline__ static SeqInfo request(const int32_t* seq_len, const int64_t* seq_start, int b) {
+    SeqInfo s;
+    s.len_raw = SCALAR ? scalar_load(seq_len + b) : seq_len[b];
+    s.start = 0;
+    if constexpr (!PAGED) s.start = SCALAR ? scalar_load(seq_start + b) : seq_start[b];
+    return s;
+  }
+  // after vector loads have arrived: tells the compiler that the values are wave-uniform
+  __device__ __forceinline__ void make_uniform() {
+    len_raw = __builtin_amdgcn_readfirstlane(len_raw);
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)start);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)((uint64_t)start >> 32));
+    start = (int64_t)(((uint64_t)hi << 32) | lo);
+  }
+  // contiguous cache: the sequence must lie inside the pool
+  __device__ __forceinline__ int length(int64_t max_seq_len, int64_t pool_tokens) const {
+    const int64_t L = len_raw;
+    const bool ok = (L >= 0) & (L <= max_seq_len) & (start >= 0) & (start + L <= pool_tokens);
+    return ok ? (int)L : 0;
+  }
+  // paged cache: the sequence must fit the pages its table row can name
+  __device__ __forceinline__ int paged_length(int64_t max_seq_len, int64_t table_tokens) const {
+    const int64_t L = len_raw;
+    return ((L >= 0) & (L <= max_seq_len) & (L <= table_tokens)) ? (int)L : 0;
+  }
+};
+
+// Everything requested from memory so far has been issued before anything
+// after this point is looked at: keeps the compiler from sinking speculative
+// loads below the first wait for the sequence length, or hoisting that wait.
+__device__ __forceinline__ void loads_issued_before_here() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_sched_barrier(0);
 }
 
-// The same for a paged cache: the sequence must fit the pages its table row can name.
-__device__ __forceinline__ int safe_paged_len(const int32_t* seq_len, int b, int64_t max_seq_len,
-                                              int64_t table_tokens) {
-  const int64_t L = seq_len[b];
-  return (L >= 0 && L <= max_seq_len && L <= table_tokens) ? (int)L : 0;
+__device__ __forceinline__ int safe_seq_len(const int32_t* seq_len, const int64_t* seq_start, int b,
+                                            int64_t max_seq_len, int64_t pool_tokens) {
+  return SeqInfo::request<false, true>(seq_len, seq_start, b).length(max_seq_len, pool_tokens);
 }
 
 __device__ __forceinline__ float bf16_bits_to_float(uint32_t bits16) {
@@ -80,6 +140,10 @@ __device__ __forceinline__ float bf16_lo(uint32_t packed) { return __uint_as_flo
 __device__ __forceinline__ float bf16_hi(uint32_t packed) {
   return __uint_as_float(packed & 0xffff0000u);
 }
+
+// 2^x for x <= 0 (softmax weights): the hardware instruction as it is.  Results
+// below the normal range come out as 0, which is what a weight of 2^-127 is worth.
+__device__ __forceinline__ float exp2_neg(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // Per-half-word subtraction of two packed uint16 pairs (no borrow across halves).
 typedef unsigned short ushort2_t __attribute__((ext_vector_type(2)));
@@ -100,10 +164,10 @@ struct PhaseTrace {
 #pragma unroll
     for (int i = 0; i < kTraceSlots; ++i) t[i] = 0;
   }
-  // waits for this wave's outstanding memory operations first, so that the note
-  // marks the point where the phase's data has arrived
-  __device__ __forceinline__ void stamp(int i) {
-    __builtin_amdgcn_s_waitcnt(0);
+  // wait: first waits for this wave's outstanding memory operations (stores
+  // included), so that the note marks the point where the phase's data has arrived
+  __device__ __forceinline__ void stamp(int i, bool wait = true) {
+    if (wait) __builtin_amdgcn_s_waitcnt(0);
     if (threadIdx.x == 0) t[i] = wall_clock64();
   }
   __device__ __forceinline__ void flush(uint64_t* buf, int64_t n_records) const {
@@ -116,7 +180,7 @@ struct PhaseTrace {
 };
 #else
 struct PhaseTrace {
-  __device__ __forceinline__ void stamp(int) {}
+  __device__ __forceinline__ void stamp(int, bool = true) {}
   __device__ __forceinline__ void flush(uint64_t*, int64_t) const {}
 };
 #endif

@@ -18,6 +18,15 @@ namespace adamas {
 constexpr int kFullThreads = 256;
 constexpr int kFullMaxSplits = 256;
 
+// One softmax state per row group of a workgroup, for the combine through LDS.
+template <int D>
+struct FullShared {
+  static constexpr int kGroups = kFullThreads / (D / 8);
+  float m[kGroups];
+  float l[kGroups];
+  float acc[kGroups][D];
+};
+
 struct FullAttnParams {
   const uint16_t* q;         // bf16 [B][Hq][128]
   const uint16_t* K;         // pools
@@ -39,7 +48,7 @@ __global__ __launch_bounds__(kFullThreads) void full_attn_kernel(const FullAttnP
   constexpr int LPR = D / 8;  // lanes per row
   constexpr int kGroups = kFullThreads / LPR;
   constexpr int kPartial = partial_stride(D);
-  __shared__ AttnShared<kFullThreads, D> sh;
+  __shared__ FullShared<D> sh;
   const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, grp = tid / LPR, gl = tid % LPR;
   const int head0 = b * p.Hq + kvh * G;

@@ -53,12 +53,12 @@ struct ScanParams {
   int64_t dist_stride;       // tokens per row, a multiple of 128
   uint16_t* dist_user;       // optional second copy, [B*Hq][dist_user_stride]
   int64_t dist_user_stride;
-  uint16_t* tilehist;        // [B*Hq][n_tiles][Dist<METRIC>::kStride]; may be null
+  uint32_t* tilehist;        // [B*Hq][n_tiles][Dist<>::kPairs] words of two 16-bit bins; may be null
   uint32_t* arrivals;        // per-head counter at [head * arrivals_stride], zeroed here; may be null
   int64_t arrivals_stride;
   int64_t pool_tokens, max_seq_len;
   int32_t Hq, Hkv, n_tiles;
-  int32_t g_split;           // workgroups per (tile, KV head): each takes G of the group's G * g_split query heads
+  int32_t g_split;           // workgroups per (tile, KV head), 1 or 2: each takes G of the group's G * g_split query heads
   // Paged cache (PAGED kernels only): token t of sequence b lives in pool row
   // page_table[b * max_pages + (t >> page_shift)] << page_shift | (t & page mask).
   const int32_t* page_table;
@@ -85,12 +85,12 @@ template <int G, bool FUSED, int WAVES, int METRIC, bool PAGED, int D>
 __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p) {
   static_assert(FUSED || !PAGED, "the paged layout is served by the fused step only");
   using Fmt = Dist<METRIC, D>;
-  constexpr int kNumBins = Fmt::kBins, kHistStride = Fmt::kStride;
+  constexpr int kNumBins = Fmt::kBins;
   constexpr int BITS = Fmt::kBits, kRowBytes = Fmt::kRowBytes, W = Fmt::kWords;
   constexpr int kRowWords = W * BITS;  // 32-bit words per code row
   constexpr int kHistReplicas = hist_replicas(G, kNumBins);
   constexpr int E = D / 64;            // elements per lane when a wave encodes one vector
-  constexpr int kPairs = (kNumBins + 1) / 2;  // 32-bit words of a histogram: two 16-bit bins each
+  constexpr int kPairs = Fmt::kPairs;  // 32-bit words of a histogram: two 16-bit bins each
   __shared__ uint32_t s_hist[G][kHistReplicas][kPairs];
   // per query head: plane p of word wd at [W * p + wd]; 2-bit codes also keep lo^hi at [2W + wd]
   __shared__ uint32_t s_q[G][3 * W];
@@ -104,13 +104,16 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
   // part `gsub` of the KV head's group of G * g_split (the parts re-read the rows).
   PhaseTrace trace;
   trace.stamp(kScanStart);
-  const int tile_id = blockIdx.x, kvh = blockIdx.y / p.g_split, gsub = blockIdx.y % p.g_split;
+  // g_split is 1 or 2
+  const int tile_id = blockIdx.x, kvh = blockIdx.y >> (p.g_split - 1), gsub = blockIdx.y & (p.g_split - 1);
   const int b = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   constexpr int nthreads = WAVES * kWave;
   constexpr int tile_tokens = nthreads * kScanTokPerThread;
   const int t0 = tile_id * tile_tokens;
   const int head0 = b * p.Hq + (kvh * p.g_split + gsub) * G;
+  // requested first of all: the row loads cannot be addressed without them
+  SeqInfo seq = SeqInfo::request<PAGED, true>(p.seq_len, p.seq_start, b);
 
   // First of all the encoding waves request their vectors (G queries and, if
   // the call appends, the new key): their addresses need nothing from memory,
@@ -142,12 +145,13 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
 #pragma unroll
     for (int i = 0; i < kScanTokPerThread; ++i) {
       const int pg = min((t0 + (uw * kScanTokPerThread + i) * kWave) >> p.page_shift, p.max_pages - 1);
-      pte[i] = p.page_table[(int64_t)b * p.max_pages + pg];
+      pte[i] = scalar_load(p.page_table + (int64_t)b * p.max_pages + pg);
     }
   }
-  const int L = PAGED ? safe_paged_len(p.seq_len, b, p.max_seq_len, (int64_t)p.max_pages << p.page_shift)
-                      : safe_seq_len(p.seq_len, p.seq_start, b, p.max_seq_len, p.pool_tokens);
-  const int64_t start = PAGED ? 0 : p.seq_start[b];
+  loads_issued_before_here();
+  const int L = PAGED ? seq.paged_length(p.max_seq_len, (int64_t)p.max_pages << p.page_shift)
+                      : seq.length(p.max_seq_len, p.pool_tokens);
+  const int64_t start = seq.start;
 
   // The only workgroup barrier before the scan sits here, where every wave has
   // just started (and while the loads above are still on their way).  Later on
@@ -404,14 +408,12 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
     p.arrivals[(int64_t)(head0 + tid) * p.arrivals_stride] = 0u;
   if (p.tilehist != nullptr) {
     __syncthreads();
-    // bins kNumBins.. of a stored row stay unwritten
     for (int i = tid; i < G * kPairs; i += nthreads) {
       const int g = i / kPairs, pr = i - g * kPairs;
       uint32_t v = 0;
 #pragma unroll
       for (int r = 0; r < kHistReplicas; ++r) v += s_hist[g][r][pr];
-      uint16_t* row = p.tilehist + ((int64_t)(head0 + g) * p.n_tiles + tile_id) * kHistStride;
-      reinterpret_cast<uint32_t*>(row)[pr] = v;
+      p.tilehist[((int64_t)(head0 + g) * p.n_tiles + tile_id) * kPairs + pr] = v;
     }
   }
   trace.stamp(kScanEnd);

@@ -39,7 +39,7 @@ struct SelectParams {
   const void* dist;           // [B*Hq][dist_stride] bytes or uint16 (Dist<>::kDistBytes)
   const uint64_t* dist_high;  // ninth bits, [B*Hq][dist_stride / 64] (Dist<>::kHighPlane only)
   int64_t dist_stride;        // tokens per row, a multiple of 128
-  const uint16_t* tilehist;   // [B*Hq][n_tiles][Dist<METRIC>::kStride]
+  const uint32_t* tilehist;   // [B*Hq][n_tiles][Dist<>::kPairs] words of two 16-bit bins
   const int64_t* seq_start;   // [B]
   const int32_t* seq_len;     // [B]
   int32_t* idx_out;           // [B*Hq][k] or null
@@ -52,7 +52,9 @@ struct SelectParams {
   int64_t arrivals_stride;
   int64_t pool_tokens, max_seq_len;
   int32_t Hq, Hkv, k;
-  int32_t n_tiles, tile_tokens, seg_len;
+  uint32_t group_magic;       // see kv_head_of
+  int32_t n_tiles, tile_tokens, seg_len;  // tile_tokens and seg_len are powers of two
+  int32_t tile_shift, seg_shift;          // their logarithms
   double scale_log2e;         // sm_scale * log2(e)
   // Paged cache (PAGED kernels only), as in ScanParams.
   const int32_t* page_table;
@@ -67,6 +69,8 @@ enum SelectPhase {
   kSelStart = 0,      // first instruction
   kSelLoaded,         // distances, tile histograms and the sequence length have arrived
   kSelThreshold,      // T and r known to every thread
+  kSelMasked,         // (first pass) candidate masks and counts of the thread's 16 tokens
+  kSelPrefix,         // (first pass) candidates before this thread known (past the pass's barrier)
   kSelCompacted,      // the segment's selected positions are in LDS / idx_out
   kSelRowsFirst,      // the first batch of K, V rows has arrived
   kSelAttended,       // all rows of the segment consumed
@@ -100,18 +104,19 @@ __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* s_wave
 
 template <int THREADS, int D = kHeadDim>
 struct AttnShared {
-  static constexpr int kGroups = THREADS / (D / 8);
-  float m[kGroups];
-  float l[kGroups];
-  float acc[kGroups][D];
+  static constexpr int kWaves = THREADS / kWave;  // one combined state per wave
+  float m[kWaves];
+  float l[kWaves];
+  float acc[kWaves][D];
 };
 
 // Softmax attention (Eq. 1) of one query over the n rows listed in s_sel (token
 // positions; Kp, Vp point at the sequence's first row of the right KV head),
-// by the whole workgroup: 16 lanes per row, 8 dims per lane, one-pass online
-// softmax per 16-lane group in fp32 (exp2 domain), groups combined in fixed
-// order through LDS.  Threads 0..127 receive, for output dim tid: M (running
-// maximum), lsum (sum of weights) and o (unnormalised weighted sum of V).
+// by the whole workgroup: D / 8 lanes per row, 8 dims per lane, one-pass online
+// softmax per lane group in fp32 (exp2 domain); the groups of a wave are then
+// combined with cross-lane moves and the waves, in fixed order, through LDS.
+// Threads 0..D-1 receive, for output dim tid: M (running maximum), lsum (sum of
+// weights) and o (unnormalised weighted sum of V).
 // Entries of s_sel are clamped to [0, n_tokens) before use (n_tokens >= 1 when n > 0).
 // All threads must call it.
 template <int THREADS, int D>
@@ -131,7 +136,9 @@ __device__ __forceinline__ void attention_rows(const int32_t* s_sel, int n, int 
 #pragma clang fp contract(off)
   constexpr int LPR = D / 8;  // lanes per row: 8 dims each
   constexpr int kGroups = THREADS / LPR;
+  constexpr int NW = THREADS / kWave;
   const int tid = threadIdx.x, grp = tid / LPR, gl = tid % LPR;
+  const int wave = tid >> 6, lane = tid & 63;
 
   double qf[8];
   {
@@ -143,7 +150,7 @@ __device__ __forceinline__ void attention_rows(const int32_t* s_sel, int n, int 
 #pragma unroll
   for (int j = 0; j < 8; ++j) acc[j] = 0.f;
 
-  constexpr int U = 4;  // rows in flight per 16-lane group
+  constexpr int U = 4;  // rows in flight per lane group
   for (int i0 = grp; i0 < n; i0 += kGroups * U) {
     uint4 kv[U], vv[U];
     bool ok[U];
@@ -151,134 +158,168 @@ __device__ __forceinline__ void attention_rows(const int32_t* s_sel, int n, int 
     for (int u = 0; u < U; ++u) {
       const int i = i0 + u * kGroups;
       ok[u] = i < n;
+      kv[u] = make_uint4(0, 0, 0, 0);
+      vv[u] = make_uint4(0, 0, 0, 0);
       if (ok[u]) {
         // clamped: whatever the list holds, the gather stays inside the sequence
         const int tok = min(max(s_sel[i], 0), n_tokens - 1);
         const int64_t off = (int64_t)tok * D + gl * 8;
         kv[u] = *reinterpret_cast<const uint4*>(Kp + off);
         vv[u] = *reinterpret_cast<const uint4*>(Vp + off);
-      } else {
-        kv[u] = make_uint4(0, 0, 0, 0);
-        vv[u] = make_uint4(0, 0, 0, 0);
       }
     }
-    if (i0 == grp) trace.stamp(kSelRowsFirst);
-    double sc[U];
-    float mn = m;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
+      // Row slots are filled in order, so a slot that no group of this wave uses
+      // ends the batch (a wave-uniform test: the rows of a small selection take
+      // one or two slots, and the unused ones cost nothing).
+      if (__ballot(ok[u]) == 0) break;
+      if (u == 0 && i0 == grp) trace.stamp(kSelRowsFirst);
       // two chains of four: the additions of a chain wait for each other
-      double s = qf[0] * (double)bf16_lo(kv[u].x), s2 = qf[1] * (double)bf16_hi(kv[u].x);
-      s = fma(qf[2], (double)bf16_lo(kv[u].y), s);
+      double s1 = qf[0] * (double)bf16_lo(kv[u].x), s2 = qf[1] * (double)bf16_hi(kv[u].x);
+      s1 = fma(qf[2], (double)bf16_lo(kv[u].y), s1);
       s2 = fma(qf[3], (double)bf16_hi(kv[u].y), s2);
-      s = fma(qf[4], (double)bf16_lo(kv[u].z), s);
+      s1 = fma(qf[4], (double)bf16_lo(kv[u].z), s1);
       s2 = fma(qf[5], (double)bf16_hi(kv[u].z), s2);
-      s = fma(qf[6], (double)bf16_lo(kv[u].w), s);
+      s1 = fma(qf[6], (double)bf16_lo(kv[u].w), s1);
       s2 = fma(qf[7], (double)bf16_hi(kv[u].w), s2);
-      s += s2;
       // the row's D / 8 lanes are an aligned group of 8, 16 or 32 lanes
-      s = lanes_sum_f64<LPR>(s) * scale_log2e;
-      sc[u] = ok[u] ? s : (double)kNegBig;
-      mn = fmaxf(mn, (float)sc[u]);
-    }
-    // one rescale of the running state for the whole batch of rows
-    const float corr = exp2f(m - mn);
-    m = mn;
-    l *= corr;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) acc[j] *= corr;
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const float pw = ok[u] ? exp2f((float)(sc[u] - (double)mn)) : 0.f;
-      l += pw;
-      acc[0] = fmaf(pw, bf16_lo(vv[u].x), acc[0]);
-      acc[1] = fmaf(pw, bf16_hi(vv[u].x), acc[1]);
-      acc[2] = fmaf(pw, bf16_lo(vv[u].y), acc[2]);
-      acc[3] = fmaf(pw, bf16_hi(vv[u].y), acc[3]);
-      acc[4] = fmaf(pw, bf16_lo(vv[u].z), acc[4]);
-      acc[5] = fmaf(pw, bf16_hi(vv[u].z), acc[5]);
-      acc[6] = fmaf(pw, bf16_lo(vv[u].w), acc[6]);
-      acc[7] = fmaf(pw, bf16_hi(vv[u].w), acc[7]);
+      const double sc = ok[u] ? lanes_sum_f64<LPR>(s1 + s2) * scale_log2e : (double)kNegBig;
+      const float mn = fmaxf(m, (float)sc);
+      const float corr = exp2_neg(m - mn);
+      const float pw = ok[u] ? exp2_neg((float)(sc - (double)mn)) : 0.f;
+      m = mn;
+      l = l * corr + pw;
+      acc[0] = fmaf(pw, bf16_lo(vv[u].x), acc[0] * corr);
+      acc[1] = fmaf(pw, bf16_hi(vv[u].x), acc[1] * corr);
+      acc[2] = fmaf(pw, bf16_lo(vv[u].y), acc[2] * corr);
+      acc[3] = fmaf(pw, bf16_hi(vv[u].y), acc[3] * corr);
+      acc[4] = fmaf(pw, bf16_lo(vv[u].z), acc[4] * corr);
+      acc[5] = fmaf(pw, bf16_hi(vv[u].z), acc[5] * corr);
+      acc[6] = fmaf(pw, bf16_lo(vv[u].w), acc[6] * corr);
+      acc[7] = fmaf(pw, bf16_hi(vv[u].w), acc[7] * corr);
     }
   }
-
   trace.stamp(kSelAttended);
-  if (gl == 0) {
-    sh.m[grp] = m;
-    sh.l[grp] = l;
-  }
+
+  // The lane groups of a wave hold the same dims in the same lanes of their
+  // group: combine them pairwise with cross-lane moves (both partners compute
+  // the same values), then the waves through LDS.  A group without rows has
+  // l = 0 and m = kNegBig and drops out with weight exp2(kNegBig - M) = 0.
 #pragma unroll
-  for (int j = 0; j < 8; ++j) sh.acc[grp][gl * 8 + j] = acc[j];
+  for (int step = LPR; step < kWave; step <<= 1) {
+    const float mo = __shfl_xor(m, step, kWave), lo = __shfl_xor(l, step, kWave);
+    const float mn = fmaxf(m, mo);
+    const float wa = exp2_neg(m - mn), wb = exp2_neg(mo - mn);
+    m = mn;
+    l = l * wa + lo * wb;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] = acc[j] * wa + __shfl_xor(acc[j], step, kWave) * wb;
+  }
+  if (lane < LPR) {
+    if (lane == 0) {
+      sh.m[wave] = m;
+      sh.l[wave] = l;
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) sh.acc[wave][lane * 8 + j] = acc[j];
+  }
   __syncthreads();
 
   M = kNegBig;
   lsum = 0.f;
   o = 0.f;
   if (tid < D) {
-    for (int g = 0; g < kGroups; ++g) M = fmaxf(M, sh.m[g]);
-    for (int g = 0; g < kGroups; ++g) {
-      const float w = exp2f(sh.m[g] - M);
-      lsum = fmaf(sh.l[g], w, lsum);
-      o = fmaf(sh.acc[g][tid], w, o);
+#pragma unroll
+    for (int w = 0; w < NW; ++w) M = fmaxf(M, sh.m[w]);
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+      const float wt = exp2_neg(sh.m[w] - M);
+      lsum = fmaf(sh.l[w], wt, lsum);
+      o = fmaf(sh.acc[w][tid], wt, o);
     }
   }
 }
 
 // Candidate masks of one 32-bit word of the distance plane against the threshold
 // distance T: bit (8 or 16) * j + (7 or 15) of lt / eq is set when token j of the
-// word has distance < T / == T.  Byte planes hold four tokens per word, their
-// ninth bits come separately (high4: bit j = ninth bit of token j).
+// word has distance < T / == T.  Byte planes hold four tokens per word and carry
+// the low eight bits of the distance; y = (T & 255) * 0x01010101.
 template <bool BYTES>
-__device__ __forceinline__ void word_masks(uint32_t w, uint32_t high4, int T, uint32_t& lt, uint32_t& eq) {
+__device__ __forceinline__ void word_masks(uint32_t w, uint32_t y, uint32_t& lt, uint32_t& eq) {
   if constexpr (BYTES) {
     constexpr uint32_t H = 0x80808080u, L7 = 0x7f7f7f7fu;
-    const uint32_t y = (uint32_t)(T & 255) * 0x01010101u;
     // per byte, no borrow between bytes: bit 7 of t = (low 7 bits of w >= low 7 bits of y)
     const uint32_t t = (w | H) - (y & L7);
-    const uint32_t lt8 = ((~w & y) | (~(w ^ y) & ~t)) & H;       // unsigned byte compare
+    lt = ((~w & y) | (~(w ^ y) & ~t)) & H;       // unsigned byte compare
     const uint32_t z = w ^ y;
-    const uint32_t eq8 = ~(((z & L7) + L7) | z) & H;             // byte of z is zero
-    // ninth bits spread to bit 7 of their bytes
-    const uint32_t e = (high4 * 0x10204080u) & H;
-    if (T < 256) {
-      lt = lt8 & ~e;
-      eq = eq8 & ~e;
-    } else {
-      lt = (~e & H) | lt8;
-      eq = eq8 & e;
-    }
+    eq = ~(((z & L7) + L7) | z) & H;             // byte of z is zero
   } else {
-    // two uint16 per word, both operands below 2^15
-    const uint32_t TT = (uint32_t)T * 0x00010001u;
-    lt = pk_sub_u16(w, TT) & 0x80008000u;
-    const uint32_t z = w ^ TT;
+    // two uint16 per word, both operands below 2^15; y = T * 0x00010001
+    lt = pk_sub_u16(w, y) & 0x80008000u;
+    const uint32_t z = w ^ y;
     eq = pk_sub_u16(z, 0x00010001u) & ~z & 0x80008000u;
   }
+}
+
+// The last step of the in-kernel merge: slots 0..n_active-1 (n_active <= N) of a
+// head's partials, read with device-scope loads, combined in slot order with
+// merge_kernel's arithmetic.
+template <int N, int D>
+__device__ __forceinline__ float merge_slots(const float* ph, int n_active, int tid) {
+  constexpr int kPartial = partial_stride(D);
+  float pm[N], pl[N], po[N];
+#pragma unroll
+  for (int s = 0; s < N; ++s) {
+    const float* ps = ph + (int64_t)min(s, n_active - 1) * kPartial;
+    pm[s] = __hip_atomic_load(ps + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    pl[s] = __hip_atomic_load(ps + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    po[s] = __hip_atomic_load(ps + 4 + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  float Mh = kNegBig;
+#pragma unroll
+  for (int s = 0; s < N; ++s) Mh = fmaxf(Mh, s < n_active ? pm[s] : kNegBig);
+  float lh = 0.f, oh = 0.f;
+#pragma unroll
+  for (int s = 0; s < N; ++s) {
+    const bool use = s < n_active;
+    const float w = use ? exp2_neg(pm[s] - Mh) : 0.f;
+    lh = fmaf(use ? pl[s] : 0.f, w, lh);
+    oh = fmaf(use ? po[s] : 0.f, w, oh);
+  }
+  return lh > 0.f ? oh / lh : 0.f;
 }
 
 // Grid (n_segs, Hq, B).  With ATTN a head that has a single segment with
 // tokens is finished by that workgroup; otherwise each workgroup leaves an
 // (M, lsum, o[128]) partial, merged by the last one to arrive (p.arrivals set)
 // or by merge_kernel (p.arrivals null).
+//
+// A workgroup is one wave per SIMD and runs alone on its compute unit, so its
+// time is the number of instructions a wave issues (about 2 ns each) plus the
+// memory round trips: the code below is written to issue few.
 template <int THREADS, bool ATTN, int METRIC, bool PAGED, int D>
 __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
   static_assert(ATTN || !PAGED, "only the gather needs the page table");
   static_assert(THREADS >= D, "one thread per output dimension in the merge");
   using Fmt = Dist<METRIC, D>;
-  constexpr int kNumBins = Fmt::kBins, kHistStride = Fmt::kStride;
+  constexpr int kNumBins = Fmt::kBins;
   constexpr bool BYTES = Fmt::kByteDist, HIGH = Fmt::kHighPlane;
+  static_assert(!BYTES || HIGH || Fmt::kMaxDist < 255, "0xff marks a token that does not exist");
+  static_assert(!HIGH || Fmt::kMaxDist < 511, "0x1ff marks a token that does not exist");
   constexpr int kPartial = partial_stride(D);
-  constexpr int kHistPairs = kHistStride / 2;                      // pairs of uint16 bins per stored row
+  constexpr int kHistPairs = Fmt::kPairs;                          // words (pairs of bins) of a histogram
   constexpr int PP = (kHistPairs + THREADS - 1) / THREADS;         // consecutive pairs owned by one thread
   constexpr int NW = THREADS / kWave;
   constexpr int PASS = THREADS * kSelTokPerThread;                 // tokens per pass
   constexpr int DW = BYTES ? 4 : 8;                                // 32-bit words of 16 distances
   constexpr int TPW = 16 / DW;                                     // tokens per word
-  __shared__ uint32_t s_wtot[2][NW], s_wpre[NW];
-  __shared__ int32_t s_T, s_cntlt;
-  __shared__ uint32_t s_ltb, s_eqb;
+  constexpr int TB = 32 / TPW;                                     // bits per token in a word
+  __shared__ __align__(16) uint32_t s_wave[2][NW][2];   // per-wave prefix totals (two buffers)
+  __shared__ __align__(16) int32_t s_found[4];          // T, #{D<T}, and #{D<T}, #{D==T} before the segment
+  __shared__ int32_t s_last;
   __shared__ int32_t s_sel[ATTN ? kMaxK : 1];
-  __shared__ AttnShared<ATTN ? THREADS : D / 8, D> s_attn;
+  __shared__ AttnShared<ATTN ? THREADS : kWave, D> s_attn;
 
   PhaseTrace trace;
   trace.stamp(kSelStart);
@@ -286,28 +327,30 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int64_t head = (int64_t)b * p.Hq + hq;
   const int seg_t0 = seg * p.seg_len;
+  SeqInfo seq = SeqInfo::request<PAGED, false>(p.seq_len, p.seq_start, b);
 
   // Nothing below depends on the sequence length until the loads are issued:
-  // the workspace rows exist up to dist_stride / n_tiles whatever L is, and
-  // what lies beyond L is masked once L has arrived.
-  const uint8_t* drow = static_cast<const uint8_t*>(p.dist) + head * p.dist_stride * Fmt::kDistBytes;
-  const uint16_t* hrow_high = reinterpret_cast<const uint16_t*>(p.dist_high) + head * (p.dist_stride >> 4);
+  // the workspace rows exist up to dist_stride / n_tiles (+ kHistBatch rows of
+  // slack behind the last histogram) whatever L is, and what lies beyond L is
+  // masked once L has arrived.
+  const uint8_t* drow = static_cast<const uint8_t*>(p.dist) +
+                        (head * p.dist_stride + seg_t0 + tid * kSelTokPerThread) * Fmt::kDistBytes;
+  const uint16_t* hrow_high = reinterpret_cast<const uint16_t*>(p.dist_high) +
+                              ((head * p.dist_stride + seg_t0) >> 4) + tid;
   // distances (and ninth bits) of this thread for the current pass and the next one (rolling prefetch)
   uint32_t cur[DW], nxt[DW], cur_high = 0, nxt_high = 0;
-  {
-    const int o0 = tid * kSelTokPerThread, o1 = PASS + tid * kSelTokPerThread;
 #pragma unroll
-    for (int w = 0; w < DW; ++w) cur[w] = nxt[w] = 0;
-    if (o0 < p.seg_len && seg_t0 + o0 < p.dist_stride) {
+  for (int w = 0; w < DW; ++w) cur[w] = nxt[w] = 0;
+  // (the last segment may reach past the row of the plane: nothing is read there)
+  if (tid * kSelTokPerThread < p.seg_len && seg_t0 + tid * kSelTokPerThread < p.dist_stride) {
 #pragma unroll
-      for (int c = 0; c < DW / 4; ++c) load_piece<16>(drow + (int64_t)(seg_t0 + o0) * Fmt::kDistBytes + 16 * c, &cur[4 * c]);
-      if constexpr (HIGH) cur_high = hrow_high[(seg_t0 + o0) >> 4];
-    }
-    if (o1 < p.seg_len && seg_t0 + o1 < p.dist_stride) {
+    for (int c = 0; c < DW / 4; ++c) load_piece<16>(drow + 16 * c, &cur[4 * c]);
+    if constexpr (HIGH) cur_high = hrow_high[0];
+  }
+  if (PASS + tid * kSelTokPerThread < p.seg_len && seg_t0 + PASS + tid * kSelTokPerThread < p.dist_stride) {
 #pragma unroll
-      for (int c = 0; c < DW / 4; ++c) load_piece<16>(drow + (int64_t)(seg_t0 + o1) * Fmt::kDistBytes + 16 * c, &nxt[4 * c]);
-      if constexpr (HIGH) nxt_high = hrow_high[(seg_t0 + o1) >> 4];
-    }
+    for (int c = 0; c < DW / 4; ++c) load_piece<16>(drow + PASS * Fmt::kDistBytes + 16 * c, &nxt[4 * c]);
+    if constexpr (HIGH) nxt_high = hrow_high[PASS >> 4];
   }
   // Paged cache: a thread's 16 consecutive tokens share one page; its number is
   // fetched like the distances, a pass ahead, and used when rows are emitted.
@@ -319,34 +362,38 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
     nxt_pg = prow[min((t_a + PASS) >> p.page_shift, p.max_pages - 1)];
   }
   // Tile histograms: a thread owns PP consecutive pairs of bins (one 32-bit load
-  // per pair and tile); pairs past the row repeat its last pair and count as zero.
-  const uint16_t* hrow = p.tilehist + head * p.n_tiles * kHistStride;
-  const int first_tile = seg_t0 / p.tile_tokens;
-  int pair[PP];
+  // per pair and tile); pairs past the histogram repeat its last pair and count as
+  // zero.  Rows past the head's last tile are read as well (they exist: the next
+  // head's, or the slack behind the last head) and left out of the sums.
+  const uint32_t* hbase = p.tilehist + head * p.n_tiles * kHistPairs;
+  int pair_off[PP];
 #pragma unroll
-  for (int j = 0; j < PP; ++j) pair[j] = min(tid * PP + j, kHistPairs - 1);
+  for (int j = 0; j < PP; ++j) pair_off[j] = min(tid * PP + j, kHistPairs - 1);
   uint32_t hv[PP][kHistBatch];
 #pragma unroll
-  for (int u = 0; u < kHistBatch; ++u) {  // clamped, branch-free: all loads in flight together
-    const uint32_t* trow =
-        reinterpret_cast<const uint32_t*>(hrow + (int64_t)min(u, p.n_tiles - 1) * kHistStride);
+  for (int u = 0; u < kHistBatch; ++u) {
 #pragma unroll
-    for (int j = 0; j < PP; ++j) hv[j][u] = trow[pair[j]];
+    for (int j = 0; j < PP; ++j) hv[j][u] = hbase[u * kHistPairs + pair_off[j]];
   }
 
-  const int L = PAGED ? safe_paged_len(p.seq_len, b, p.max_seq_len, (int64_t)p.max_pages << p.page_shift)
-                      : safe_seq_len(p.seq_len, p.seq_start, b, p.max_seq_len, p.pool_tokens);
+  loads_issued_before_here();
+  seq.make_uniform();
+  const int L = PAGED ? seq.paged_length(p.max_seq_len, (int64_t)p.max_pages << p.page_shift)
+                      : seq.length(p.max_seq_len, p.pool_tokens);
   const int kk = min(p.k, L);
-  const int n_active = max(1, (L + p.seg_len - 1) / p.seg_len);  // segments that hold tokens
+  // segments and tiles are powers of two: no division
+  const int n_active = max(1, (L + p.seg_len - 1) >> p.seg_shift);  // segments that hold tokens
   if (seg >= n_active) return;
   trace.stamp(kSelLoaded);
   const int seg_t1 = min(L, seg_t0 + p.seg_len);
-  const int tiles_active = (L + p.tile_tokens - 1) / p.tile_tokens;
+  const int tiles_active = (L + p.tile_tokens - 1) >> p.tile_shift;
+  const int first_tile = seg_t0 >> p.tile_shift;  // < tiles_active
 
   // Head histogram (all tiles with tokens) and the part of it before this
   // segment, two 16-bit bins per word.  A bin of the head total stays below
   // 2^16 for sequences of up to 65535 tokens, so that the packed words can be
-  // added as they are; longer sequences add the halves separately.
+  // added as they are; longer sequences add the halves separately.  Which tiles
+  // count is wave-uniform; a full batch of tiles needs no masks at all.
   uint32_t tot0[PP], tot1[PP], pre0[PP], pre1[PP];
 #pragma unroll
   for (int j = 0; j < PP; ++j) tot0[j] = tot1[j] = pre0[j] = pre1[j] = 0;
@@ -355,33 +402,51 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
     if (tb > 0) {
 #pragma unroll
       for (int u = 0; u < kHistBatch; ++u) {
-        const uint32_t* trow = reinterpret_cast<const uint32_t*>(
-            hrow + (int64_t)min(tb + u, p.n_tiles - 1) * kHistStride);
 #pragma unroll
-        for (int j = 0; j < PP; ++j) hv[j][u] = trow[pair[j]];
+        for (int j = 0; j < PP; ++j) hv[j][u] = hbase[(tb + u) * kHistPairs + pair_off[j]];
       }
     }
+    const int n_tot = tiles_active - tb, n_pre = first_tile - tb;  // tiles of this batch that count
     if (packed_sums) {
+      if (n_tot >= kHistBatch) {
 #pragma unroll
-      for (int u = 0; u < kHistBatch; ++u) {
+        for (int u = 0; u < kHistBatch; ++u) {
 #pragma unroll
-        for (int j = 0; j < PP; ++j) {
-          tot0[j] += tb + u < tiles_active ? hv[j][u] : 0u;
-          pre0[j] += tb + u < first_tile ? hv[j][u] : 0u;   // first_tile <= tiles_active here
+          for (int j = 0; j < PP; ++j) tot0[j] += hv[j][u];
+        }
+      } else {
+#pragma unroll
+        for (int u = 0; u < kHistBatch; ++u) {
+          const uint32_t on = u < n_tot ? 0xffffffffu : 0u;
+#pragma unroll
+          for (int j = 0; j < PP; ++j) tot0[j] += hv[j][u] & on;
+        }
+      }
+      if (n_pre >= kHistBatch) {
+#pragma unroll
+        for (int u = 0; u < kHistBatch; ++u) {
+#pragma unroll
+          for (int j = 0; j < PP; ++j) pre0[j] += hv[j][u];
+        }
+      } else if (n_pre > 0) {
+#pragma unroll
+        for (int u = 0; u < kHistBatch; ++u) {
+          const uint32_t on = u < n_pre ? 0xffffffffu : 0u;
+#pragma unroll
+          for (int j = 0; j < PP; ++j) pre0[j] += hv[j][u] & on;
         }
       }
     } else {
 #pragma unroll
       for (int u = 0; u < kHistBatch; ++u) {
+        const uint32_t on = u < n_tot ? 0xffffffffu : 0u, before = u < n_pre ? 0xffffffffu : 0u;
 #pragma unroll
         for (int j = 0; j < PP; ++j) {
-          const uint32_t v = tb + u < tiles_active ? hv[j][u] : 0u;
+          const uint32_t v = hv[j][u] & on;
           tot0[j] += v & 0xffffu;
           tot1[j] += v >> 16;
-          if (tb + u < first_tile) {
-            pre0[j] += v & 0xffffu;
-            pre1[j] += v >> 16;
-          }
+          pre0[j] += v & before & 0xffffu;
+          pre1[j] += (v & before) >> 16;
         }
       }
     }
@@ -408,22 +473,22 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
   // publishes all four.
   const uint32_t incl_tot = wave_incl_scan_u32(sum_tot), incl_pre = wave_incl_scan_u32(sum_pre);
   if (lane == 63) {
-    s_wtot[0][wave] = incl_tot;
-    s_wpre[wave] = incl_pre;
+    s_wave[0][wave][0] = incl_tot;
+    s_wave[0][wave][1] = incl_pre;
   }
   if (tid == 0) {
-    s_ltb = 0u;
-    s_eqb = 0u;
-    s_T = 0;
-    s_cntlt = 0;
+    s_found[0] = 0;
+    s_found[1] = 0;
+    s_found[2] = 0;
+    s_found[3] = 0;
   }
   __syncthreads();
   {
     uint32_t run = incl_tot - sum_tot, run_pre = incl_pre - sum_pre;
 #pragma unroll
-    for (int w = 0; w < NW; ++w) {
-      run += w < wave ? s_wtot[0][w] : 0u;
-      run_pre += w < wave ? s_wpre[w] : 0u;
+    for (int w = 0; w < NW - 1; ++w) {  // the last wave's total is nobody's prefix
+      run += w < wave ? s_wave[0][w][0] : 0u;
+      run_pre += w < wave ? s_wave[0][w][1] : 0u;
     }
     if (kk > 0 && run < (uint32_t)kk && run + sum_tot >= (uint32_t)kk) {
 #pragma unroll
@@ -432,10 +497,10 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
         for (int h = 0; h < 2; ++h) {
           const uint32_t c = h ? tot1[j] : tot0[j], cp = h ? pre1[j] : pre0[j];
           if (run < (uint32_t)kk && run + c >= (uint32_t)kk) {
-            s_T = 2 * (tid * PP + j) + h;
-            s_cntlt = (int32_t)run;
-            s_ltb = run_pre;
-            s_eqb = cp;
+            s_found[0] = 2 * (tid * PP + j) + h;
+            s_found[1] = (int32_t)run;
+            s_found[2] = (int32_t)run_pre;
+            s_found[3] = (int32_t)cp;
           }
           run += c;
           run_pre += cp;
@@ -444,14 +509,17 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
     }
   }
   __syncthreads();
-  const int T = s_T;
-  const int r = kk - s_cntlt;  // ties at distance T to take, lowest positions first
-  uint32_t run_lt = s_ltb, run_eq = s_eqb;
-  trace.stamp(kSelThreshold);
+  const int4 found = *reinterpret_cast<const int4*>(s_found);
+  const int T = found.x;
+  const int r = kk - found.y;  // ties at distance T to take, lowest positions first
+  uint32_t run_lt = (uint32_t)found.z, run_eq = (uint32_t)found.w;
+  trace.stamp(kSelThreshold, false);
   const uint32_t seg_pos0 = run_lt + min(run_eq, (uint32_t)r);
   int32_t* idx_row = p.idx_out != nullptr ? p.idx_out + head * p.k : nullptr;
+  // what the low bits of a stored distance are compared with
+  const uint32_t y = BYTES ? (uint32_t)(T & 255) * 0x01010101u : (uint32_t)T * 0x00010001u;
 
-  int pass_no = 0;
+  int pass_no = 1;  // buffer 0 of s_wave was just read
   for (int pass_t0 = seg_t0; pass_t0 < seg_t1; pass_t0 += PASS, ++pass_no) {
     const int t = pass_t0 + tid * kSelTokPerThread;
     uint32_t dw[DW];
@@ -460,13 +528,13 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
       dw[w] = cur[w];
       cur[w] = nxt[w];
     }
-    const uint32_t high = cur_high;
+    uint32_t high = cur_high;
     cur_high = nxt_high;
     if (t + 2 * PASS < seg_t1) {  // fetch the pass after next while this one is processed
+      const uint8_t* src = drow + (int64_t)(pass_t0 - seg_t0 + 2 * PASS) * Fmt::kDistBytes;
 #pragma unroll
-      for (int c = 0; c < DW / 4; ++c)
-        load_piece<16>(drow + (int64_t)(t + 2 * PASS) * Fmt::kDistBytes + 16 * c, &nxt[4 * c]);
-      if constexpr (HIGH) nxt_high = hrow_high[(t + 2 * PASS) >> 4];
+      for (int c = 0; c < DW / 4; ++c) load_piece<16>(src + 16 * c, &nxt[4 * c]);
+      if constexpr (HIGH) nxt_high = hrow_high[(pass_t0 - seg_t0 + 2 * PASS) >> 4];
     }
     int64_t page_row0 = 0;  // pool row of token t's page, minus the page offset of t itself
     if constexpr (PAGED) {
@@ -477,36 +545,62 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
         nxt_pg = p.page_table[(int64_t)b * p.max_pages +
                               min((t + 2 * PASS) >> p.page_shift, p.max_pages - 1)];
     }
-    // Per word: which of its tokens lie below / at the threshold (word_masks),
-    // restricted to the tokens of this thread that exist.
-    const int n_valid = min(max(seg_t1 - t, 0), kSelTokPerThread);
+    // Tokens of this thread past the end of the segment (only in its last
+    // 16-token group) get the largest stored value, which no threshold reaches.
+    if (t + kSelTokPerThread > seg_t1) {
+      const int n_valid = max(seg_t1 - t, 0);
+#pragma unroll
+      for (int w = 0; w < DW; ++w) {
+        const int keep = min(max(n_valid - TPW * w, 0), TPW);
+        const uint32_t gone = keep == TPW ? 0u : ~((1u << (TB * keep)) - 1u);
+        // bytes: 0xff (with the ninth bit below: 0x1ff); uint16: exactly 0x7fff, whatever was loaded
+        dw[w] = BYTES ? (dw[w] | gone) : ((dw[w] & ~gone) | (gone & 0x7fff7fffu));
+      }
+      if (HIGH) high |= ~((1u << n_valid) - 1u);
+    }
+    // Per word: which of its tokens lie below / at the threshold.
     uint32_t m_lt[DW], m_eq[DW], n_lt = 0, n_eq = 0;
 #pragma unroll
+    for (int w = 0; w < DW; ++w) word_masks<BYTES>(dw[w], y, m_lt[w], m_eq[w]);
+    if constexpr (HIGH) {
+      // The bytes were compared on their low eight bits.  Ninth bits are rare,
+      // thresholds of 256 and more too.
+      if ((high & 0xffffu) != 0u || T >= 256) {
+#pragma unroll
+        for (int w = 0; w < DW; ++w) {
+          const uint32_t e = (((high >> (4 * w)) & 0xfu) * 0x10204080u) & 0x80808080u;  // ninth bits at bit 7 of their bytes
+          if (T < 256) {
+            m_lt[w] &= ~e;
+            m_eq[w] &= ~e;
+          } else {
+            m_lt[w] |= ~e & 0x80808080u;
+            m_eq[w] &= e;
+          }
+        }
+      }
+    }
+#pragma unroll
     for (int w = 0; w < DW; ++w) {
-      word_masks<BYTES>(dw[w], HIGH ? (high >> (4 * w)) & 0xfu : 0u, T, m_lt[w], m_eq[w]);
-      // tokens TPW * w .. of the thread: keep the first n_valid - TPW * w of the word
-      const int keep = min(max(n_valid - TPW * w, 0), TPW);
-      const uint32_t vm = keep == TPW ? 0xffffffffu : (1u << ((32 / TPW) * keep)) - 1u;
-      m_lt[w] &= vm;
-      m_eq[w] &= vm;
       n_lt += (uint32_t)__popc(m_lt[w]);
       n_eq += (uint32_t)__popc(m_eq[w]);
     }
+    if (pass_no == 1) trace.stamp(kSelMasked, false);
     // exclusive prefix over the workgroup (one barrier per pass: the wave totals alternate buffers)
     const uint32_t cnt = n_lt | (n_eq << 16);
     const uint32_t incl = wave_incl_scan_u32(cnt);
-    uint32_t* wt = s_wtot[pass_no & 1];
-    if (lane == 63) wt[wave] = incl;
+    uint32_t(*wt)[2] = s_wave[pass_no & 1];
+    if (lane == 63) wt[wave][0] = incl;
     __syncthreads();
     uint32_t before = 0, total = 0;
 #pragma unroll
     for (int w = 0; w < NW; ++w) {
-      const uint32_t x = wt[w];
+      const uint32_t x = wt[w][0];
       before += w < wave ? x : 0u;
       total += x;
     }
     const uint32_t ex = before + incl - cnt;
     uint32_t lt = run_lt + (ex & 0xffffu), eq = run_eq + (ex >> 16);
+    if (pass_no == 1) trace.stamp(kSelPrefix, false);
     // Visit only the candidate tokens (set bits), in position order.
 #pragma unroll
     for (int w = 0; w < DW; ++w) {
@@ -515,7 +609,7 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
         const int bit = __builtin_ctz(cand);
         cand &= cand - 1u;
         const bool is_eq = (m_eq[w] >> bit) & 1u;
-        const int j = TPW * w + bit / (32 / TPW);
+        const int j = TPW * w + bit / TB;
         if (!is_eq || eq < (uint32_t)r) {
           const uint32_t pos = lt + min(eq, (uint32_t)r);
           // pos < kk always holds for consistent histograms; the checks keep a
@@ -540,13 +634,13 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
   if constexpr (ATTN) {
     const int n_sel = min((int)(run_lt + min(run_eq, (uint32_t)r) - seg_pos0), kk);
     __syncthreads();  // s_sel complete
-    trace.stamp(kSelCompacted);
-    const int kvh = hq / (p.Hq / p.Hkv);
-    const int64_t row0 = ((int64_t)kvh * p.pool_tokens + (PAGED ? 0 : p.seq_start[b])) * D;
+    trace.stamp(kSelCompacted, false);  // (not waiting for the index stores)
+    const int kvh = kv_head_of(hq, p.group_magic);
+    const int64_t row0 = ((int64_t)kvh * p.pool_tokens + seq.start) * D;
     float M, lsum, o;
     attention_rows<THREADS, D>(s_sel, n_sel, PAGED ? (int)p.pool_tokens : L, p.q + head * D,
                             p.K + row0, p.V + row0, p.scale_log2e, s_attn, M, lsum, o, trace);
-    trace.stamp(kSelCombined);
+    trace.stamp(kSelCombined, false);
     if (gridDim.x == 1 || (p.arrivals != nullptr && n_active == 1)) {
       if (tid < D) p.out[head * D + tid] = lsum > 0.f ? o / lsum : 0.f;
       trace.stamp(kSelEnd);
@@ -586,11 +680,11 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
     if (tid == 0) {
       const uint32_t before = __hip_atomic_fetch_add(p.arrivals + head * p.arrivals_stride, 1u,
                                                      __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      s_T = before + 1u == (uint32_t)n_active ? 1 : 0;
+      s_last = before + 1u == (uint32_t)n_active ? 1 : 0;
     }
     __syncthreads();
     trace.stamp(kSelCounted);
-    if (s_T == 0) {
+    if (s_last == 0) {
       trace.stamp(kSelEnd);
       trace.flush(p.trace, p.trace_records);
       return;
@@ -598,26 +692,9 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
     if (tid >= D) return;
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
     const float* ph = p.partial + head * kMaxParts * kPartial;
-    float pm[kMaxParts], pl[kMaxParts], po[kMaxParts];
-#pragma unroll
-    for (int s = 0; s < kMaxParts; ++s) {
-      const float* ps = ph + (int64_t)min(s, n_active - 1) * kPartial;
-      pm[s] = __hip_atomic_load(ps + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      pl[s] = __hip_atomic_load(ps + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      po[s] = __hip_atomic_load(ps + 4 + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-    float Mh = kNegBig;
-#pragma unroll
-    for (int s = 0; s < kMaxParts; ++s) Mh = fmaxf(Mh, s < n_active ? pm[s] : kNegBig);
-    float lh = 0.f, oh = 0.f;
-#pragma unroll
-    for (int s = 0; s < kMaxParts; ++s) {
-      const bool use = s < n_active;
-      const float w = use ? exp2f(pm[s] - Mh) : 0.f;
-      lh = fmaf(use ? pl[s] : 0.f, w, lh);
-      oh = fmaf(use ? po[s] : 0.f, w, oh);
-    }
-    p.out[head * D + tid] = lh > 0.f ? oh / lh : 0.f;
+    static_assert(kMaxParts == 16, "two merge widths: up to 8 and up to 16 partials");
+    p.out[head * D + tid] = n_active <= 8 ? merge_slots<8, D>(ph, n_active, tid)
+                                          : merge_slots<16, D>(ph, n_active, tid);
     trace.stamp(kSelMerged);
     trace.stamp(kSelEnd);
     trace.flush(p.trace, p.trace_records);
@@ -638,6 +715,7 @@ struct AttnParams {
   float* partial;      // [B*Hq][kMaxParts][partial_stride(D)]
   int64_t pool_tokens;
   int32_t Hq, Hkv, k, n_parts, chunk;  // chunk = idx entries per workgroup
+  uint32_t group_magic;                // see kv_head_of
   double scale_log2e;
 };
 
@@ -668,7 +746,7 @@ __global__ __launch_bounds__(kAttnThreads) void sparse_attn_kernel(const AttnPar
     n += total;
   }
   __syncthreads();
-  const int kvh = hq / (p.Hq / p.Hkv);
+  const int kvh = kv_head_of(hq, p.group_magic);
   const int64_t row0 = ((int64_t)kvh * p.pool_tokens + start) * D;
   float M, lsum, o;
   PhaseTrace trace;  // not recorded for the stand-alone kernel
@@ -732,7 +810,7 @@ __global__ __launch_bounds__(D) void merge_kernel(const MergeParams p) {
 #pragma unroll
   for (int s = 0; s < kMaxParts; ++s) {
     const bool use = s < n;  // slots past n hold whatever the workspace held
-    const float w = use ? exp2f(pm[s] - M) : 0.f;
+    const float w = use ? exp2_neg(pm[s] - M) : 0.f;
     lsum = fmaf(use ? pl[s] : 0.f, w, lsum);
     o = fmaf(use ? po[s] : 0.f, w, o);
   }
