@@ -105,8 +105,9 @@ def _thr(thr, bits: int = 2) -> np.ndarray:
 
 
 class head_dim:
-    """`with oracle.head_dim(64): ...` runs the calls inside with d = 64 (or 256); 128 is the
-    default and is restored on exit.  Process-wide state of the oracle library."""
+    """`with oracle.head_dim(64): ...` runs the calls inside with d = 64 (or 96, 160, 192, 256:
+    a multiple of 32 of the form 2^n, 2^n * 12 or 2^n * 20); 128 is the default and is restored on
+    exit.  Process-wide state of the oracle library."""
 
     def __init__(self, d: int):
         self.d = int(d)
@@ -115,7 +116,8 @@ class head_dim:
         global D, ROW_BYTES
         self.prev = D
         if lib().oracle_set_head_dim(ctypes.c_int(self.d)) != 0:
-            raise OracleError("head dimension must be 64, 128 or 256")
+            raise OracleError("head dimension must be a multiple of 32 up to 256 of the form "
+                              "2^n, 2^n * 12 or 2^n * 20")
         D, ROW_BYTES = self.d, self.d // 4
         return self
 
@@ -135,7 +137,8 @@ def set_threads(n: int) -> None:
 
 
 def hadamard_matrix(d: int) -> np.ndarray:
-    """+-1 Sylvester-Hadamard matrix of order d by the Kronecker recursion (Eq. 2)."""
+    """+-1 Hadamard matrix of order d = 2^n (Sylvester, Eq. 2), 2^n * 12 or 2^n * 20 (the same
+    Kronecker recursion started from Paley's matrix of order 12 / 20)."""
     H = np.empty((d, d), dtype=np.int8)
     _check(lib().oracle_hadamard_matrix(ctypes.c_int(d), _p(H)), "hadamard_matrix")
     return H

@@ -11,7 +11,10 @@
  * Every stage is the plain definition, not a fast algorithm:
  *   - Hadamard matrix: Kronecker recursion from H_2 (Section 2, Eq. 2),
  *     kept as integer +-1 entries; the 1/sqrt(d) normalisation is applied to
- *     the thresholds instead of to every coefficient.
+ *     the thresholds instead of to every coefficient.  For d = 2^n * m with
+ *     m = 12 or 20 the recursion starts from a Hadamard matrix of order m
+ *     (Section 2, the construction H_d = H_{2^n} (x) H_m under Eq. 2); the paper
+ *     names no H_12 / H_20, this file uses Paley's (see oracle_hadamard_matrix).
  *   - Transform: dense d-term sums y_j = sum_i x_i * H[i][j] in double
  *     (Section 3.2, Eq. 4).
  *   - Bucketize: code = number of thresholds strictly below the value
@@ -46,19 +49,28 @@
 
 /*
  * Head dimension.  The paper's models have d = 128 and that is the default;
- * Section 2 builds the transform for any power of two (H_{2n} from H_n), and
- * oracle_set_head_dim() switches every function below to d = 64 or 256 (test
- * code sets it before a group of calls and restores 128 afterwards; it is
- * process-wide state, only read inside the calls).  A 2-bit code row then has
- * d / 4 bytes: d / 32 words of two 32-bit planes.
+ * Section 2 builds the transform for any power of two (H_{2n} from H_n) and
+ * for d = 2^n * m with m the order of a known Hadamard matrix, and
+ * oracle_set_head_dim() switches every function below to another supported d
+ * (test code sets it before a group of calls and restores 128 afterwards; it
+ * is process-wide state, only read inside the calls).  A 2-bit code row then
+ * has d / 4 bytes: d / 32 words of two 32-bit planes, so d must be a multiple
+ * of 32.
  */
 #define ORACLE_MAX_D 256
 static int oracle_head_dim = 128;
 #define ORACLE_D (oracle_head_dim)
 #define ORACLE_ROW_BYTES (oracle_head_dim / 4)
 
+/* m with d = 2^n * m, m in {1, 12, 20}; 0 if d is not of that form. */
+static int hadamard_base_order(int d) {
+  if (d < 1) return 0;
+  while (d % 2 == 0 && d != 12 && d != 20) d /= 2;
+  return (d == 1 || d == 12 || d == 20) ? d : 0;
+}
+
 int oracle_set_head_dim(int d) {
-  if (d != 64 && d != 128 && d != 256) return -1;
+  if (d < 32 || d > ORACLE_MAX_D || d % 32 != 0 || hadamard_base_order(d) == 0) return -1;
   oracle_head_dim = d;
   return 0;
 }
@@ -85,15 +97,49 @@ static double bf16_to_double(uint16_t b) {
 /* --------------------------------------------------- Hadamard matrix, Eq. 2 */
 
 /*
- * Fills H (d*d, row-major, entries +1/-1) by the Kronecker recursion
- * H_{2n} = H_2 (x) H_n = [[H_n, H_n], [H_n, -H_n]], H_1 = [1].  The factor
- * 1/sqrt(2) per level is left out: the orthonormal matrix is H / sqrt(d).
- * d must be a power of two.
+ * Paley's Hadamard matrix of order m = q + 1 for a prime q = 3 (mod 4) (q = 11
+ * and 19 give the orders 12 and 20 that Section 2's construction needs; the
+ * paper does not say which H_12 / H_20 its authors use, so this choice is this
+ * build's):  with chi the quadratic character mod q (chi(0) = 0, +1 for the
+ * non-zero squares, -1 otherwise),
+ *     P[0][0] = 1,  P[0][j] = 1,  P[i][0] = -1,  P[i][i] = 1,
+ *     P[i][j] = chi(i - j)   for i != j, i, j >= 1.
+ * P P^T = m I because the q x q matrix chi(i - j) is antisymmetric for
+ * q = 3 (mod 4) and has Q Q^T = q I - J, Q J = 0.  P is not symmetric.
+ */
+static void paley_matrix(int q, int8_t *P, int stride) {
+  int m = q + 1;
+  int8_t chi[32];
+  for (int a = 0; a < q; ++a) chi[a] = -1;
+  chi[0] = 0;
+  for (int a = 1; a < q; ++a) chi[(a * a) % q] = 1; /* the non-zero squares */
+  for (int i = 0; i < m; ++i) {
+    for (int j = 0; j < m; ++j) {
+      int8_t v;
+      if (i == 0) v = 1;
+      else if (j == 0) v = -1;
+      else if (i == j) v = 1;
+      else v = chi[(((i - j) % q) + q) % q];
+      P[i * stride + j] = v;
+    }
+  }
+}
+
+/*
+ * Fills H (d*d, row-major, entries +1/-1).  d = 2^n: the Kronecker recursion
+ * H_{2k} = H_2 (x) H_k = [[H_k, H_k], [H_k, -H_k]] from H_1 = [1] (Eq. 2).
+ * d = 2^n * 12 or 2^n * 20: the same recursion started from Paley's matrix of
+ * order 12 / 20, which is H_{2^n} (x) H_m (Section 2, under Eq. 2):
+ *     H[a * m + b][a' * m + b'] = H_{2^n}[a][a'] * H_m[b][b'].
+ * The factor 1/sqrt(2) per level (1/sqrt(d) in all) is left out: the
+ * orthonormal matrix is H / sqrt(d).
  */
 int oracle_hadamard_matrix(int d, int8_t *H) {
-  if (d < 1 || (d & (d - 1)) != 0 || !H) return ORACLE_BAD_ARG;
-  H[0] = 1;
-  for (int n = 1; n < d; n *= 2) {
+  int m = hadamard_base_order(d);
+  if (m == 0 || !H) return ORACLE_BAD_ARG;
+  if (m == 1) H[0] = 1;
+  else paley_matrix(m - 1, H, d);
+  for (int n = m; n < d; n *= 2) {
     /* grow the n x n block in the top-left corner (stride d) to 2n x 2n */
     for (int i = 0; i < n; ++i) {
       for (int j = 0; j < n; ++j) {
@@ -114,7 +160,7 @@ int oracle_hadamard_matrix(int d, int8_t *H) {
  * The orthonormal transform of the paper is y / sqrt(d).
  */
 int oracle_hadamard_transform(int d, const double *x, double *y) {
-  if (d < 1 || (d & (d - 1)) != 0 || !x || !y) return ORACLE_BAD_ARG;
+  if (hadamard_base_order(d) == 0 || !x || !y) return ORACLE_BAD_ARG;
   int8_t *H = (int8_t *)malloc((size_t)d * d);
   if (!H) return ORACLE_NOMEM;
   oracle_hadamard_matrix(d, H);

@@ -264,10 +264,11 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
   }
 
   trace.stamp(kScanQueryReady);
-  // The query planes are wave-uniform.  Small groups keep them in vector
-  // registers (a VALU instruction takes one scalar operand only, so scalar
-  // planes cost an extra move per word); large groups keep them scalar to stay
-  // within the register budget of a 1024-thread workgroup.
+  // The query planes are wave-uniform.  Up to 24 words (the method's group of
+  // one or two) live in vector registers; larger groups keep them in scalar
+  // registers (every instruction of the distance needs only one of them, and the
+  // kernel then fits 64 vector registers: measured faster from a group of four
+  // on, slower for a group of two).
   // qp[g][j][wd]: plane j of word wd; for 2-bit codes j = 2 is lo ^ hi.
   // Groups whose planes exceed the scalar registers as well (96 words) are read
   // from LDS where they are used (a broadcast read per word).
@@ -281,7 +282,7 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
       for (int j = 0; j < QP; ++j) {
 #pragma unroll
         for (int wd = 0; wd < W; ++wd) {
-          if constexpr (G * QP * W <= 24 || (G * QP * W <= 48 && BITS < 3)) qp[g][j][wd] = s_q[g][W * j + wd];
+          if constexpr (G * QP * W <= 24) qp[g][j][wd] = s_q[g][W * j + wd];
           else qp[g][j][wd] = __builtin_amdgcn_readfirstlane(s_q[g][W * j + wd]);
         }
       }

@@ -1023,3 +1023,47 @@ def test_generation_loop_of_appending_steps(H, oracle):
         assert H.attn_rel_err(d.out.cpu().numpy(), out) <= H.ATTN_TOL, step
     assert np.array_equal(H.host_u16(d.K), K_ref) and np.array_equal(H.host_u16(d.V), V_ref)
     assert np.array_equal(d.codes.cpu().numpy(), rows_ref)
+
+
+@pytest.mark.parametrize("hd", [128, 64, 256])
+@pytest.mark.parametrize("far_share,k", [(0.02, 200), (0.5, 64), (0.9, 1500), (0.9, 4000), (1.0, 100)])
+def test_distances_above_255_in_some_tiles(H, oracle, hd, far_share, k):
+    """Byte-sized distances carry a ninth bit only in tiles that need one.  Rows far from the
+    query (every code 3 against every code 0: distance 3 * d) are sprinkled over some tiles or
+    fill most of the cache, so that the threshold distance lies below 256 in one case and above
+    it (with ties broken by position among the far rows) in the others; two sequences, the
+    second without any far row; several scan tiles and select segments."""
+    rng = np.random.default_rng(1234 + hd + k)
+    L0, L1 = 9000, 2500
+    case = synth.make_case("far", 4242 + hd, 2, 4, 2, [L0, L1], [0],
+                           lambda b, L, h, rng: rng.choice(L, (2, 1), replace=False), head_dim=hd)
+    big = int(synth.f32_to_bf16_bits(np.float32([64.0]))[0])
+    neg = int(synth.f32_to_bf16_bits(np.float32([-64.0]))[0])
+    case.q[0] = 0
+    case.q[0, :, 0] = neg                      # sequence 0: every query coefficient -64 -> code 0
+    far = rng.random(L0) < far_share
+    if far_share < 0.1:                        # only in a few tiles
+        far &= (np.arange(L0) // 1024) % 3 == 1
+    rows = np.flatnonzero(far)
+    case.K[:, rows] = 0
+    case.K[:, rows, 0] = big                   # every coefficient +64 -> code 3
+    d = H.DeviceCase(case, k)
+    out, idx = d.decode_step()
+    ref = H.oracle_step(case, k, want_dist=True)
+    if hd >= 128:
+        assert int(ref["dist"][0].max()) == 3 * hd and int(ref["dist"][1].max()) < 3 * hd
+    assert np.array_equal(idx, ref["idx"])
+    assert H.attn_rel_err(out, ref["out"]) <= H.ATTN_TOL
+    # the stand-alone entry point on the same cache, with the user-visible distances
+    import paper_2510_18413_amd as A
+    qcodes = torch.zeros(2, 4, d.cfg.code_row_bytes, dtype=torch.uint8, device="cuda")
+    A.adamas_encode_query(d.cfg, d.q, qcodes)
+    dist = torch.full((2, 4, d.max_len), 0xFFFF, dtype=torch.uint16, device="cuda")
+    idx2 = torch.full((2, 4, k), -7, dtype=torch.int32, device="cuda")
+    A.adamas_select_topk(d.cfg, qcodes, d.codes, d.seq_start, d.seq_len, k, idx2, d.max_len,
+                         d.workspace, dist_out=dist)
+    torch.cuda.synchronize()
+    got = H.host_dist(dist)
+    for b, L in enumerate((L0, L1)):
+        assert np.array_equal(got[b, :, :L], ref["dist"][b, :, :L])
+    assert np.array_equal(idx2.cpu().numpy(), ref["idx"])

@@ -496,7 +496,7 @@ def test_head_dim_encode_rows_and_distance(oracle, d):
     assert oracle.encode(bf16(rng.standard_normal((1, 128))), THR)[1].shape == (1, 32)
 
 
-@pytest.mark.parametrize("d", [64, 256])
+@pytest.mark.parametrize("d", [64, 256, 96, 160, 192])
 def test_head_dim_decode_step_composes_its_stages(oracle, d):
     case = synth.make_case("t", 80 + d, 2, 4, 2, [300, 129], [16],
                            lambda b, L, h, rng: rng.choice(L, (2, 1), replace=False), append=True,
@@ -526,6 +526,110 @@ def test_head_dim_decode_step_composes_its_stages(oracle, d):
                 w = np.exp(sc - sc.max())
                 ref = (w / w.sum()) @ Vf
                 assert np.allclose(out[b, h], ref, rtol=1e-5, atol=1e-6)
+
+
+# ------------------------- head dimensions 2^n * 12 and 2^n * 20 (Section 2, under Eq. 2)
+
+def _residues():
+    out = {}
+    for line in open(os.path.join(GOLDEN, "quadratic_residues.txt")):
+        if line.strip() and not line.startswith("#"):
+            q, vals = line.split(":")
+            out[int(q)] = {int(v) for v in vals.split()}
+    return out
+
+
+@pytest.mark.parametrize("m", [12, 20])
+def test_paley_matrix_of_order_12_and_20(oracle, m):
+    """Entries +-1, rows orthogonal, the stated border and diagonal, and the interior from the
+    hand-typed quadratic residues; a second construction (Euler's criterion) agrees."""
+    P = oracle.hadamard_matrix(m).astype(np.int64)
+    q = m - 1
+    assert set(np.unique(P).tolist()) == {-1, 1}
+    assert np.array_equal(P @ P.T, m * np.eye(m, dtype=np.int64))
+    assert np.array_equal(P.T @ P, m * np.eye(m, dtype=np.int64))
+    assert np.all(P[0] == 1) and np.all(P[1:, 0] == -1) and np.all(np.diag(P) == 1)
+    res = _residues()[q]
+    euler = {a for a in range(1, q) if pow(a, (q - 1) // 2, q) == 1}
+    assert res == euler
+    for i in range(1, m):
+        for j in range(1, m):
+            if i != j:
+                assert P[i, j] == (1 if (i - j) % q in res else -1), (i, j)
+    # antisymmetric off the border and the diagonal: P is not a symmetric matrix
+    core = P[1:, 1:] - np.eye(q, dtype=np.int64)
+    assert np.array_equal(core, -core.T)
+
+
+@pytest.mark.parametrize("d", [24, 40, 96, 160, 192])
+def test_hadamard_of_order_two_to_the_n_times_m(oracle, d):
+    m = 12 if d % 3 == 0 else 20
+    H = oracle.hadamard_matrix(d).astype(np.int64)
+    assert set(np.unique(H).tolist()) == {-1, 1}
+    assert np.array_equal(H @ H.T, d * np.eye(d, dtype=np.int64))
+    want = np.kron(scipy.linalg.hadamard(d // m).astype(np.int64),
+                   oracle.hadamard_matrix(m).astype(np.int64))       # H_{2^n} (x) H_m
+    assert np.array_equal(H, want)
+    # H[a*m + b][a'*m + b'] = (-1)^popcount(a & a') * H_m[b][b'], written out
+    P = oracle.hadamard_matrix(m).astype(np.int64)
+    for (i, j) in [(0, 0), (m, m), (d - 1, d - 1), (m + 3, (2 * m + 5) % d), (d - 2, 7)]:
+        a, b, a2, b2 = i // m, i % m, j // m, j % m
+        assert H[i, j] == (-1) ** bin(a & a2).count("1") * P[b, b2]
+
+
+@pytest.mark.parametrize("d", [96, 160, 192])
+def test_transform_of_order_two_to_the_n_times_m(oracle, d):
+    rng = np.random.default_rng(d)
+    H = oracle.hadamard_matrix(d).astype(np.float64)
+    for i in (0, 1, 11, 12, d - 1):
+        e = np.zeros(d)
+        e[i] = 1.0
+        assert np.array_equal(oracle.hadamard_transform(e), H[i])       # y = x H: row i
+    x = rng.integers(-50, 51, d).astype(np.float64)
+    y = rng.integers(-50, 51, d).astype(np.float64)
+    hx, hy = oracle.hadamard_transform(x), oracle.hadamard_transform(y)
+    assert np.array_equal(hx, x @ H)
+    assert hx @ hy == d * (x @ y)                   # Eq. 3 on the +-1 matrix, exact in integers
+    assert hx @ hx == d * (x @ x)                   # Parseval
+    assert np.array_equal(hx @ H.T, d * x)          # H H^T = d I (H itself is not symmetric)
+    assert not np.array_equal(H, H.T)
+
+
+@pytest.mark.parametrize("d", [96, 160, 192])
+def test_head_dim_two_to_the_n_times_m_encode_rows_and_distance(oracle, d):
+    rng = np.random.default_rng(140 + d)
+    x = bf16(rng.standard_normal((50, d)) * 1.5)
+    with oracle.head_dim(d):
+        codes, rows = oracle.encode(x, THR)
+        assert rows.shape == (50, d // 4)
+        assert np.array_equal(oracle.unpack_rows(rows), codes)
+        Dm = oracle.manhattan(codes[0], codes[1:])
+        full = oracle.manhattan(np.zeros(d, np.uint8), np.full((1, d), 3, np.uint8))[0]
+        one = np.zeros(d, dtype=np.uint8)
+        one[d - 1] = 2
+        words = oracle.pack_row(one).view("<u4").reshape(d // 32, 2)
+        codes3, rows3 = oracle.encode_bits(x, (-1.5, -1.0, -0.5, 0.0, 0.5, 1.0, 1.5), 3)
+        assert rows3.shape == (50, 3 * d // 8) and np.array_equal(oracle.unpack_rows_bits(rows3, 3), codes3)
+    assert full == 3 * d
+    Hm = np.kron(scipy.linalg.hadamard(d // (12 if d % 3 == 0 else 20)),
+                 oracle.hadamard_matrix(12 if d % 3 == 0 else 20)).astype(np.float64)
+    yy = widen(x) @ Hm / np.sqrt(float(d))
+    ref = (yy[..., None] > np.array(THR)).sum(-1)
+    far = np.abs(yy[..., None] - np.array(THR)).min(-1) > 1e-6
+    assert np.array_equal(codes[far], ref[far]) and far.mean() > 0.999
+    assert np.array_equal(Dm, np.abs(codes[0].astype(int)[None] - codes[1:].astype(int)).sum(-1))
+    assert int(words[d // 32 - 1, 1]) == 1 << 31 and int(words.sum()) == 1 << 31
+    assert oracle.encode(bf16(rng.standard_normal((1, 128))), THR)[1].shape == (1, 32)
+
+
+def test_head_dims_the_oracle_refuses(oracle):
+    for d in (0, 16, 80, 100, 224, 288, 512):       # not a multiple of 32, not 2^n * {1, 12, 20}, too large
+        with pytest.raises(oracle.OracleError):
+            with oracle.head_dim(d):
+                pass
+    for d in (36, 56, 100):
+        with pytest.raises(oracle.OracleError):
+            oracle.hadamard_matrix(d)
 
 
 # ------------------------------------------------------------------ paged cache layout
