@@ -123,15 +123,20 @@ extern "C" {
 
 /*
  * Head dimension d.  The text above and below is written for d = 128, the
- * head dimension of the paper's models.  head_dim 64 and 256 run everything
- * as well (Hadamard transform of order d, every ablation switch, contiguous
- * or paged cache, every entry point): read d for 128 and d/4 for the 32-byte
- * code row (d/32 words of 64 bits, same bit placement; 16 * code_bits * d/128
- * bytes with the code-width switch), distances 0..3d, sm_scale 0 meaning
- * 1/sqrt(d), thresholds compared with x H / sqrt(d).
+ * head dimension of the paper's models.  head_dim 64 and 256 (powers of two:
+ * Sylvester's H_d, Eq. 2) and 96, 160, 192 (d = 2^n * m with m = 12 or 20:
+ * H_d = H_{2^n} (x) H_m, Section 2 under Eq. 2, with Paley's Hadamard matrix
+ * of order m built from the quadratic residues mod m - 1; the paper names no
+ * H_12 / H_20, so codes at these dimensions are this library's own) run
+ * everything as well: every ablation switch, contiguous or paged cache, every
+ * entry point.  Read d for 128 and d/4 for the 32-byte code row (d/32 words of
+ * 64 bits, same bit placement; 16 * code_bits * d/128 bytes with the
+ * code-width switch), distances 0..3d, sm_scale 0 meaning 1/sqrt(d),
+ * thresholds compared with x H / sqrt(d).  Other head dimensions ->
+ * ADAMAS_ERR_UNSUPPORTED (a code row needs d to be a multiple of 32).
  */
 typedef struct adamas_config {
-  int32_t head_dim;      /* 128; or 64, 256 (see above) */
+  int32_t head_dim;      /* 128; or 64, 96, 160, 192, 256 (see above) */
   int32_t num_q_heads;   /* Hq */
   int32_t num_kv_heads;  /* Hkv; Hq % Hkv == 0 */
   uint32_t variant;      /* 0 = the method; else ADAMAS_VARIANT_* flags (Sec. 4.4 ablations) */

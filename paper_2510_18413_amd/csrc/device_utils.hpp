@@ -56,6 +56,28 @@ __device__ __forceinline__ void load_piece(const uint8_t* src, uint32_t* w) {
     w[0] = *reinterpret_cast<const uint32_t*>(src);
   }
 }
+// What the kernels derive from the head dimension D = 2^n * m, m = 1, 12 or 20
+// (Section 2: H_D = H_{2^n} (x) H_m), a multiple of 32.
+template <int D>
+struct HeadDim {
+  static_assert(D % 32 == 0, "a code row is D / 32 words");
+  static constexpr bool kPow2 = (D & (D - 1)) == 0;
+  static constexpr int kBase = kPow2 ? 1 : (D % 3 == 0 ? 12 : 20);  // m
+  static_assert(kPow2 || (D % kBase == 0 && ((D / kBase) & (D / kBase - 1)) == 0), "D = 2^n * 12 or 2^n * 20");
+  // One wave encodes one vector.  Powers of two: lane l holds elements l + 64 e,
+  // e < D / 64.  Otherwise lane l < D / (m / 4) holds the m / 4 consecutive
+  // elements from l * m / 4 on, so that a quad of lanes holds one block of m.
+  static constexpr int kEncElems = kPow2 ? D / 64 : kBase / 4;
+  static constexpr int kEncLanes = kPow2 ? 64 : D / kEncElems;
+  __device__ __forceinline__ static int enc_index(int lane, int e) {
+    return kPow2 ? lane + 64 * e : lane * kEncElems + e;
+  }
+  // Attention: a row takes D / 8 lanes of 8 dims inside an aligned group of
+  // 8, 16 or 32 lanes (the next power of two; the other lanes of the group idle).
+  static constexpr int kRowLanes = D / 8;
+  static constexpr int kRowGroup = kRowLanes <= 8 ? 8 : kRowLanes <= 16 ? 16 : 32;
+};
+
 // floats per attention partial of a head of dimension d: m, l, pad, pad, o[d]
 constexpr int partial_stride(int d) { return d + 4; }
 constexpr int kWave = 64;

@@ -47,10 +47,124 @@ __device__ __forceinline__ void planes_from_masks(const M* m, M* plane) {
 // Result: w[p][g], plane p of word g of the packed row, identical in every lane.
 // All 64 lanes must be active.  The elements come already loaded (raw bf16
 // bits), so that a caller can issue that load ahead of other memory traffic.
+// ---- D = 2^n * m, m = 12 or 20 (Section 2: H_D = H_{2^n} (x) H_m) ------------
+//
+// H_m is Paley's matrix for the prime q = m - 1 (the paper names no H_12 / H_20):
+//   P[0][c] = 1,  P[r][0] = -1 (r >= 1),  P[r][r] = 1,
+//   P[r][c] = +1 if r - c is a non-zero square mod q, else -1   (r != c; r, c >= 1).
+// Bit r of paley_neg_column(m, c) is set where P[r][c] = -1: the signs of the
+// inputs in output coefficient c of y = x P.
+constexpr bool paley_is_square(int q, int a) {
+  for (int t = 1; t < q; ++t)
+    if ((t * t) % q == a) return true;
+  return false;
+}
+constexpr uint32_t paley_neg_column(int m, int c) {
+  const int q = m - 1;
+  uint32_t neg = 0;
+  for (int r = 1; r < m; ++r) {
+    bool minus = false;
+    if (c == 0) minus = true;
+    else if (r == c) minus = false;
+    else minus = !paley_is_square(q, (((r - c) % q) + q) % q);
+    if (minus) neg |= 1u << r;
+  }
+  return neg;
+}
+
+template <int CTRL>
+__device__ __forceinline__ double quad_bcast_f64(double v) {
+  const uint64_t b = __builtin_bit_cast(uint64_t, v);
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_mov_dpp((int)(uint32_t)b, CTRL, 0xf, 0xf, true);
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_mov_dpp((int)(uint32_t)(b >> 32), CTRL, 0xf, 0xf, true);
+  return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
+}
+
+// One wave64 encodes one vector of D = 2^n * m elements.  Lane l < 4 * 2^n holds
+// the m / 4 consecutive elements from l * m / 4 on (raw bf16 bits; lanes beyond
+// hold nothing), so that a quad of lanes holds one block of m: the m-point stage
+// gathers the quad's values with DPP broadcasts and forms the lane's own m / 4
+// outputs as signed sums; the 2^n stage is butterflies across lane bits 2 and up.
+// All sums are fp64 and exact for inputs within the documented exponent spread.
+// The bucket indices then move to the lanes that own their bit of the packed
+// row (coefficient 64 k + l to lane l) and wave ballots give the planes.
+// Result: w[p][g], plane p of word g, identical in every lane.  All 64 lanes active.
 template <int BITS, int D>
-__device__ __forceinline__ void encode_values_wave(const uint32_t (&raw)[D / 64],
+__device__ __forceinline__ void encode_values_wave_kron(const uint32_t (&raw)[HeadDim<D>::kEncElems],
+                                                        const Thresholds& thr,
+                                                        uint32_t w[BITS][D / 32]) {
+  constexpr int T = (1 << BITS) - 1, M = HeadDim<D>::kBase, E = M / 4;
+  constexpr int kLanes = HeadDim<D>::kEncLanes;
+  const int lane = threadIdx.x & 63, c4 = lane & 3;
+  double v[E];
+#pragma unroll
+  for (int e = 0; e < E; ++e) v[e] = lane < kLanes ? (double)bf16_bits_to_float(raw[e]) : 0.0;
+  if (thr.transform) {
+    // the quad's block of m inputs, in element order
+    double xs[M];
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+      xs[0 * E + e] = quad_bcast_f64<0x00>(v[e]);
+      xs[1 * E + e] = quad_bcast_f64<0x55>(v[e]);
+      xs[2 * E + e] = quad_bcast_f64<0xAA>(v[e]);
+      xs[3 * E + e] = quad_bcast_f64<0xFF>(v[e]);
+    }
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+      // signs of output coefficient c4 * E + e of the block
+      const uint32_t neg = c4 == 0 ? paley_neg_column(M, 0 * E + e)
+                         : c4 == 1 ? paley_neg_column(M, 1 * E + e)
+                         : c4 == 2 ? paley_neg_column(M, 2 * E + e)
+                                   : paley_neg_column(M, 3 * E + e);
+      double acc = 0.0;
+#pragma unroll
+      for (int r = 0; r < M; ++r) {
+        const uint64_t flip = (uint64_t)((neg >> r) & 1u) << 63;
+        acc += __builtin_bit_cast(double, __builtin_bit_cast(uint64_t, xs[r]) ^ flip);
+      }
+      v[e] = acc;
+    }
+#pragma unroll
+    for (int h = 4; h < kLanes; h <<= 1) {  // index bits of the 2^n factor: across lanes
+      const bool upper = (lane & h) != 0;
+#pragma unroll
+      for (int e = 0; e < E; ++e) {
+        const double partner = __shfl_xor(v[e], h, kWave);
+        v[e] = upper ? partner - v[e] : v[e] + partner;
+      }
+    }
+  }
+  // bucket indices of the lane's coefficients, three bits each
+  uint32_t packed = 0;
+#pragma unroll
+  for (int e = 0; e < E; ++e) {
+    uint32_t c = 0;
+#pragma unroll
+    for (int i = 0; i < T; ++i) c += v[e] > thr.tau[i] ? 1u : 0u;
+    packed |= c << (3 * e);
+  }
+#pragma unroll
+  for (int k = 0; k < (D + 63) / 64; ++k) {
+    const int coef = 64 * k + lane;  // lives in lane coef / E as element coef % E
+    const uint32_t from = (uint32_t)__shfl((int)packed, coef / E, kWave);
+    const uint32_t c = coef < D ? (from >> (3 * (coef % E))) & 7u : 0u;
+#pragma unroll
+    for (int p = 0; p < BITS; ++p) {
+      const uint64_t plane = __ballot((c >> p) & 1u);
+      w[p][2 * k] = (uint32_t)plane;
+      if (2 * k + 1 < D / 32) w[p][2 * k + 1] = (uint32_t)(plane >> 32);
+    }
+  }
+}
+
+template <int BITS, int D>
+__device__ __forceinline__ void encode_values_wave(const uint32_t (&raw)[HeadDim<D>::kEncElems],
                                                    const Thresholds& thr,
                                                    uint32_t w[BITS][D / 32]) {
+  if constexpr (!HeadDim<D>::kPow2) {
+    encode_values_wave_kron<BITS, D>(raw, thr, w);
+    return;
+  } else {
   constexpr int T = (1 << BITS) - 1, E = D / 64;
   const int lane = threadIdx.x & 63;
   double v[E];
@@ -90,6 +204,7 @@ __device__ __forceinline__ void encode_values_wave(const uint32_t (&raw)[D / 64]
       w[p][2 * e + 1] = (uint32_t)(plane[p] >> 32);
     }
   }
+  }  // power of two
 }
 
 // ---- bulk encode: D / 32 lanes per vector ---------------------------------
@@ -202,10 +317,35 @@ __global__ __launch_bounds__(256) void encode_rows_kernel(const uint16_t* __rest
                                                           int64_t head_stride_rows,
                                                           int64_t row_begin, int64_t n_rows,
                                                           int64_t n_vec, Thresholds thr) {
-  constexpr int LPV = D / 32;        // lanes per vector: 2, 4 or 8
-  constexpr int T = (1 << BITS) - 1, W = D / 32, E = D / 64;
+  constexpr int W = D / 32, E = HeadDim<D>::kEncElems;
   constexpr int kRowBytes = W * 4 * BITS;
   const int lane = threadIdx.x & 63;
+  if constexpr (!HeadDim<D>::kPow2) {
+    // D = 2^n * 12 or 2^n * 20: one wave per vector, exact from the start.
+    const int64_t wave0 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int64_t n_waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
+    for (int64_t v = wave0; v < n_vec; v += n_waves) {
+      const int64_t head = v / n_rows, r = v - head * n_rows;
+      const int64_t row = head * head_stride_rows + row_begin + r;
+      uint32_t rawv[E];
+#pragma unroll
+      for (int e = 0; e < E; ++e)
+        rawv[e] = lane < HeadDim<D>::kEncLanes ? src[row * D + HeadDim<D>::enc_index(lane, e)] : 0u;
+      uint32_t w[BITS][W];
+      encode_values_wave<BITS, D>(rawv, thr, w);
+      uint32_t* out = reinterpret_cast<uint32_t*>(dst + row * kRowBytes);
+#pragma unroll
+      for (int wd = 0; wd < W; ++wd) {
+        if (lane == wd) {
+#pragma unroll
+          for (int p = 0; p < BITS; ++p) out[BITS * wd + p] = w[p][wd];
+        }
+      }
+    }
+    return;
+  } else {
+  constexpr int LPV = D / 32;        // lanes per vector: 2, 4 or 8
+  constexpr int T = (1 << BITS) - 1;
   const int j = threadIdx.x & (LPV - 1);  // which 32-element part of the vector
   const int64_t quad = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / LPV;
   const int64_t n_quads = ((int64_t)gridDim.x * blockDim.x) / LPV;
@@ -249,7 +389,7 @@ __global__ __launch_bounds__(256) void encode_rows_kernel(const uint16_t* __rest
       const int64_t vrow = (int64_t)(((uint64_t)row_hi << 32) | row_lo);
       uint32_t rawv[E];
 #pragma unroll
-      for (int e = 0; e < E; ++e) rawv[e] = src[vrow * D + lane + 64 * e];
+      for (int e = 0; e < E; ++e) rawv[e] = src[vrow * D + HeadDim<D>::enc_index(lane, e)];
       uint32_t w[BITS][W];
       encode_values_wave<BITS, D>(rawv, thr, w);
       uint32_t* out = reinterpret_cast<uint32_t*>(dst + vrow * kRowBytes);
@@ -262,6 +402,7 @@ __global__ __launch_bounds__(256) void encode_rows_kernel(const uint16_t* __rest
       }
     }
   }
+  }  // power of two
 }
 
 }  // namespace adamas

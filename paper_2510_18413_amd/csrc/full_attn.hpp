@@ -21,7 +21,7 @@ constexpr int kFullMaxSplits = 256;
 // One softmax state per row group of a workgroup, for the combine through LDS.
 template <int D>
 struct FullShared {
-  static constexpr int kGroups = kFullThreads / (D / 8);
+  static constexpr int kGroups = kFullThreads / HeadDim<D>::kRowGroup;
   float m[kGroups];
   float l[kGroups];
   float acc[kGroups][D];
@@ -45,18 +45,24 @@ struct FullAttnParams {
 template <int G, int D>
 __global__ __launch_bounds__(kFullThreads) void full_attn_kernel(const FullAttnParams p) {
 #pragma clang fp contract(off)  // a scaled score is rounded once and feeds both max and exponent
-  constexpr int LPR = D / 8;  // lanes per row
+  // lanes per row: D / 8 of them hold 8 dims each, inside an aligned group of LPR (a power of two)
+  constexpr int LPR = HeadDim<D>::kRowGroup, kRowLanes = HeadDim<D>::kRowLanes;
   constexpr int kGroups = kFullThreads / LPR;
   constexpr int kPartial = partial_stride(D);
   __shared__ FullShared<D> sh;
   const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
-  const int tid = threadIdx.x, grp = tid / LPR, gl = tid % LPR;
+  const int tid = threadIdx.x, grp = tid / LPR;
+  // lanes of a group beyond the row's D / 8 compute on a zero query: they re-read
+  // the first piece of the row and leave nothing behind
+  const bool lane_on = tid % LPR < kRowLanes;
+  const int gl = lane_on ? tid % LPR : 0;
   const int head0 = b * p.Hq + kvh * G;
 
   float qf[G][8];
 #pragma unroll
   for (int g = 0; g < G; ++g) {
-    const uint4 qv = *reinterpret_cast<const uint4*>(p.q + (int64_t)(head0 + g) * D + gl * 8);
+    uint4 qv = *reinterpret_cast<const uint4*>(p.q + (int64_t)(head0 + g) * D + gl * 8);
+    if (!lane_on) qv = make_uint4(0, 0, 0, 0);
     qf[g][0] = bf16_lo(qv.x); qf[g][1] = bf16_hi(qv.x); qf[g][2] = bf16_lo(qv.y); qf[g][3] = bf16_hi(qv.y);
     qf[g][4] = bf16_lo(qv.z); qf[g][5] = bf16_hi(qv.z); qf[g][6] = bf16_lo(qv.w); qf[g][7] = bf16_hi(qv.w);
   }
@@ -127,12 +133,14 @@ __global__ __launch_bounds__(kFullThreads) void full_attn_kernel(const FullAttnP
   // Combine the 16 row groups, one query head at a time through the same LDS block.
 #pragma unroll
   for (int g = 0; g < G; ++g) {
-    if (gl == 0) {
+    if (tid % LPR == 0) {
       sh.m[grp] = m[g];
       sh.l[grp] = l[g];
     }
+    if (lane_on) {
 #pragma unroll
-    for (int j = 0; j < 8; ++j) sh.acc[grp][gl * 8 + j] = acc[g][j];
+      for (int j = 0; j < 8; ++j) sh.acc[grp][gl * 8 + j] = acc[g][j];
+    }
     __syncthreads();
     if (tid < D) {
       float M = kNegBig, lsum = 0.f, o = 0.f;
@@ -167,7 +175,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_parts_kernel(const float*
   constexpr int S = kMergeThreads / D;  // slices
   __shared__ float s_m[S], s_l[S], s_o[S][D];
   const int64_t head = (int64_t)blockIdx.y * Hq + blockIdx.x;
-  const int tid = threadIdx.x % D, slice = threadIdx.x / D;
+  const int tid = threadIdx.x % D, slice = threadIdx.x / D;  // threads past S * D idle (D = 96, 160, 192)
   const float* ph = partial + head * n_parts * kPartial;
   const int per = (n_parts + S - 1) / S;
   const int begin = slice * per, end = min(n_parts, begin + per);  // may be empty
@@ -197,11 +205,13 @@ __global__ __launch_bounds__(kMergeThreads) void merge_parts_kernel(const float*
       o = fmaf(use ? po[u] : 0.f, w, o);
     }
   }
-  if (tid == 0) {
-    s_m[slice] = M;
-    s_l[slice] = lsum;
+  if (slice < S) {
+    if (tid == 0) {
+      s_m[slice] = M;
+      s_l[slice] = lsum;
+    }
+    s_o[slice][tid] = o;
   }
-  s_o[slice][tid] = o;
   __syncthreads();
   if (slice != 0) return;
   float Mh = kNegBig, lh = 0.f, oh = 0.f;

@@ -41,7 +41,7 @@ template <int D, int METRIC>
 const KernelSet& kernel_set();
 
 // Head dimensions and metrics that are built: one translation unit per pair.
-#define ADAMAS_FOR_EACH_HEAD_DIM(X) X(64) X(128) X(256)
+#define ADAMAS_FOR_EACH_HEAD_DIM(X) X(64) X(96) X(128) X(160) X(192) X(256)
 #define ADAMAS_FOR_EACH_METRIC(X, D) X(D, kMetricL1) X(D, kMetricL2) X(D, kMetricB1) X(D, kMetricB3)
 
 }  // namespace adamas

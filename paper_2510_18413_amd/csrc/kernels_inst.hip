@@ -1,6 +1,6 @@
 // Instantiates every kernel of ONE (head dimension, metric) pair and exports
 // their launchers as a KernelSet.  Compiled once per pair with
-//   -DADAMAS_INST_D=<64|128|256> -DADAMAS_INST_METRIC=<0..3>
+//   -DADAMAS_INST_D=<64|96|128|160|192|256> -DADAMAS_INST_METRIC=<0..3>
 // (see kernel_set.hpp and build.py).
 #include "kernel_set.hpp"
 
@@ -59,7 +59,8 @@ void launch_select(bool attn, bool paged, dim3 grid, hipStream_t st, const Selec
 template <int BITS_>
 void launch_encode_rows(hipStream_t st, const uint16_t* src, uint8_t* dst, int64_t head_stride_rows,
                         int64_t row_begin, int64_t n_rows, int64_t n_vec, const Thresholds& thr) {
-  const int64_t per_wg = 256 / (D / 32);  // vectors per 256-thread workgroup
+  // vectors per 256-thread workgroup and pass: D / 32 lanes per vector, or a whole wave for D = 2^n * 12, 2^n * 20
+  const int64_t per_wg = HeadDim<D>::kPow2 ? 256 / (D / 32) : 4;
   const int64_t want = (n_vec + per_wg - 1) / per_wg;
   const int grid = (int)(want < 16384 ? want : 16384);
   hipLaunchKernelGGL((encode_rows_kernel<BITS_, D>), dim3(grid), dim3(256), 0, st, src, dst,

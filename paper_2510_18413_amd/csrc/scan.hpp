@@ -89,7 +89,7 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
   constexpr int BITS = Fmt::kBits, kRowBytes = Fmt::kRowBytes, W = Fmt::kWords;
   constexpr int kRowWords = W * BITS;  // 32-bit words per code row
   constexpr int kHistReplicas = hist_replicas(G, kNumBins);
-  constexpr int E = D / 64;            // elements per lane when a wave encodes one vector
+  constexpr int E = HeadDim<D>::kEncElems;  // elements per lane when a wave encodes one vector
   constexpr int kPairs = Fmt::kPairs;  // 32-bit words of a histogram: two 16-bit bins each
   __shared__ uint32_t s_hist[G][kHistReplicas][kPairs];
   // per query head: plane p of word wd at [W * p + wd]; 2-bit codes also keep lo^hi at [2W + wd]
@@ -132,7 +132,8 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
       const uint16_t* src = v < G ? p.q + (int64_t)(head0 + v) * D
                                   : p.k_new + ((int64_t)b * p.Hkv + kvh) * D;
 #pragma unroll
-      for (int e = 0; e < E; ++e) enc[r][e] = src[lane + 64 * e];
+      for (int e = 0; e < E; ++e)
+        enc[r][e] = lane < HeadDim<D>::kEncLanes ? src[HeadDim<D>::enc_index(lane, e)] : 0u;
     }
   }
 

@@ -134,15 +134,19 @@ __device__ __forceinline__ void attention_rows(const int32_t* s_sel, int n, int 
   // exactly the same number) is rounded to fp32, and rows with equal scores get
   // equal weights.  No implicit FMA contraction in the fp32 part.
 #pragma clang fp contract(off)
-  constexpr int LPR = D / 8;  // lanes per row: 8 dims each
+  // A row takes D / 8 lanes of 8 dims inside an aligned group of LPR lanes (the
+  // next power of two: the same for the paper's head dimensions; with D = 96,
+  // 160 or 192 the last lanes of a group hold zeros and load nothing).
+  constexpr int LPR = HeadDim<D>::kRowGroup, kRowLanes = HeadDim<D>::kRowLanes;
   constexpr int kGroups = THREADS / LPR;
   constexpr int NW = THREADS / kWave;
   const int tid = threadIdx.x, grp = tid / LPR, gl = tid % LPR;
   const int wave = tid >> 6, lane = tid & 63;
+  const bool lane_on = gl < kRowLanes;
 
   double qf[8];
   {
-    const uint4 qv = *reinterpret_cast<const uint4*>(q + gl * 8);
+    const uint4 qv = lane_on ? *reinterpret_cast<const uint4*>(q + gl * 8) : make_uint4(0, 0, 0, 0);
     qf[0] = bf16_lo(qv.x); qf[1] = bf16_hi(qv.x); qf[2] = bf16_lo(qv.y); qf[3] = bf16_hi(qv.y);
     qf[4] = bf16_lo(qv.z); qf[5] = bf16_hi(qv.z); qf[6] = bf16_lo(qv.w); qf[7] = bf16_hi(qv.w);
   }
@@ -160,7 +164,7 @@ __device__ __forceinline__ void attention_rows(const int32_t* s_sel, int n, int 
       ok[u] = i < n;
       kv[u] = make_uint4(0, 0, 0, 0);
       vv[u] = make_uint4(0, 0, 0, 0);
-      if (ok[u]) {
+      if (ok[u] && lane_on) {
         // clamped: whatever the list holds, the gather stays inside the sequence
         const int tok = min(max(s_sel[i], 0), n_tokens - 1);
         const int64_t off = (int64_t)tok * D + gl * 8;
@@ -183,7 +187,7 @@ __device__ __forceinline__ void attention_rows(const int32_t* s_sel, int n, int 
       s2 = fma(qf[5], (double)bf16_hi(kv[u].z), s2);
       s1 = fma(qf[6], (double)bf16_lo(kv[u].w), s1);
       s2 = fma(qf[7], (double)bf16_hi(kv[u].w), s2);
-      // the row's D / 8 lanes are an aligned group of 8, 16 or 32 lanes
+      // summed over the row's aligned group of 8, 16 or 32 lanes
       const double sc = ok[u] ? lanes_sum_f64<LPR>(s1 + s2) * scale_log2e : (double)kNegBig;
       const float mn = fmaxf(m, (float)sc);
       const float corr = exp2_neg(m - mn);
@@ -216,7 +220,7 @@ __device__ __forceinline__ void attention_rows(const int32_t* s_sel, int n, int 
 #pragma unroll
     for (int j = 0; j < 8; ++j) acc[j] = acc[j] * wa + __shfl_xor(acc[j], step, kWave) * wb;
   }
-  if (lane < LPR) {
+  if (lane < kRowLanes) {
     if (lane == 0) {
       sh.m[wave] = m;
       sh.l[wave] = l;

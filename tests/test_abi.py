@@ -52,7 +52,8 @@ def test_workspace_bytes():
     assert A.adamas_workspace_bytes(c, 1, 32768, 0) == 0
     assert A.adamas_workspace_bytes(c, 1, 32768, 4097) == 0
     assert A.adamas_workspace_bytes(c, 1, (1 << 20) + 1, 128) == 0
-    assert A.adamas_workspace_bytes(cfg(head_dim=96), 1, 32768, 128) == 0
+    assert A.adamas_workspace_bytes(cfg(head_dim=80), 1, 32768, 128) == 0
+    assert A.adamas_workspace_bytes(cfg(head_dim=96), 1, 32768, 128) > 0
     # head dimensions 64 and 256: distances are 2 bytes either way, partials scale with d
     w64 = A.adamas_workspace_bytes(cfg(head_dim=64), 1, 32768, 128)
     w256 = A.adamas_workspace_bytes(cfg(head_dim=256, num_q_heads=32, num_kv_heads=8), 1, 32768, 128)
@@ -60,7 +61,7 @@ def test_workspace_bytes():
 
 
 @pytest.mark.parametrize("bad, status", [
-    (dict(head_dim=96), -2),
+    (dict(head_dim=80), -2),
     (dict(head_dim=512), -2),
     (dict(head_dim=100), -2),
     (dict(num_q_heads=32, num_kv_heads=3), -1),

@@ -83,7 +83,7 @@ SHAPES = [
 ]
 
 
-@pytest.mark.parametrize("hd", [64, 256])
+@pytest.mark.parametrize("hd", [64, 256, 96, 160, 192])
 @pytest.mark.parametrize("bits,variant", [(2, 2), (2, 3), (1, 0), (3, 0), (3, 1)])
 def test_head_dim_with_every_switch(H, oracle, hd, bits, variant):
     for i, (B, Hq, Hkv, lens, k, append) in enumerate(SHAPES):
@@ -91,12 +91,49 @@ def test_head_dim_with_every_switch(H, oracle, hd, bits, variant):
                        B, Hq, Hkv, lens, k, append)
 
 
+@pytest.mark.parametrize("hd", [96, 160, 192])
+def test_head_dims_two_to_the_n_times_12_and_20(H, oracle, hd):
+    """The method itself (Hadamard transform H_{2^n} (x) H_m with Paley's H_12 / H_20, 2-bit
+    codes, Eq. 6) at d = 96, 160, 192: every stage against the oracle, several shapes."""
+    for i, (B, Hq, Hkv, lens, k, append) in enumerate(SHAPES + [(1, 4, 4, [20000], 256, True),
+                                                                 (2, 6, 2, [1, 700], 16, False)]):
+        run_all_stages(H, oracle, hd, 2, 0, 5000 + 10 * hd + i, B, Hq, Hkv, lens, k, append)
+    run_all_stages(H, oracle, hd, 2, 1, 5900 + hd, 2, 4, 2, [3000, 129], 64, True)   # without the transform
+
+
+@pytest.mark.parametrize("hd", [96, 160, 192])
+def test_head_dims_two_to_the_n_times_m_values_on_thresholds(H, oracle, hd):
+    """Coefficients that fall exactly on a threshold (strict comparison, Eq. 5), and zero vectors."""
+    import paper_2510_18413_amd as A
+    rng = np.random.default_rng(hd)
+    n = 512
+    x = np.zeros((1, n, hd), dtype=np.float32)
+    # one element -> every coefficient is +-that element; sqrt(d) scales the thresholds, so choose
+    # thresholds t = v / sqrt(d) with v a bf16 value: coefficients equal to +-v sit on +-t * sqrt(d)
+    vals = rng.choice([0.5, 1.0, 2.0, 3.0], n).astype(np.float32)
+    pos = rng.integers(0, hd, n)
+    x[0, np.arange(n), pos] = vals * rng.choice([-1.0, 1.0], n).astype(np.float32)
+    x[0, :8] = 0.0
+    xb = synth.f32_to_bf16_bits(x)
+    for v in (0.5, 1.0, 2.0):
+        t = float(np.float32(v / np.sqrt(np.float64(hd))))
+        thr = (-t, 0.0, t)
+        cfg = A.Config.make(1, 1, n, thr_k=thr, head_dim=hd)
+        K = H.dev_bf16(xb)
+        codes = torch.zeros(1, n, hd // 4, dtype=torch.uint8, device="cuda")
+        A.adamas_encode_keys(cfg, K, codes, 0, n)
+        torch.cuda.synchronize()
+        with oracle.head_dim(hd):
+            _, rows = oracle.encode(xb, thr)
+        assert np.array_equal(codes.cpu().numpy(), rows), v
+
+
 def test_group_of_eight_at_head_dim_256(H, oracle):
     run_all_stages(H, oracle, 256, 2, 0, 3900, 1, 16, 2, [6000], 200, True)
 
 
-@pytest.mark.parametrize("hd", [64, 256])
-@pytest.mark.parametrize("bits,squared", [(1, False), (3, False), (2, True)])
+@pytest.mark.parametrize("hd", [64, 256, 96, 160, 192])
+@pytest.mark.parametrize("bits,squared", [(1, False), (3, False), (2, True), (2, False)])
 def test_head_dim_largest_distance(H, oracle, hd, bits, squared):
     """Lowest against highest code in every coefficient: the largest distance of the metric."""
     import paper_2510_18413_amd as A
