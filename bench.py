@@ -40,6 +40,13 @@ WORKLOADS = {
     "cfg4": dict(B=16, Hq=32, Hkv=8, L=32768, k=128, append=False, ragged=True,
                  text="config 4: batched decode, 16 sequences with lengths uniform in "
                       "[8192, 32768], 32 query / 8 KV heads, ragged pool"),
+    # two shapes none of the plan's thresholds were fitted on (a check of the launch plan, not a
+    # configuration of the benchmark)
+    "x1": dict(B=4, Hq=32, Hkv=4, L=65536, k=256, append=True, ragged=False,
+               text="off-config check 1: batch 4, 32 query / 4 KV heads (group 8), context 65536, "
+                    "one token appended per step"),
+    "x2": dict(B=64, Hq=32, Hkv=8, L=2048, k=128, append=False, ragged=False,
+               text="off-config check 2: batch 64 short sequences of 2048 tokens, 32 query / 8 KV heads"),
 }
 
 
@@ -193,7 +200,7 @@ def main():
     k = args.k or wl["k"]
     append = wl["append"]
     n_layers = max(1, args.layers)
-    cfg_id = int(args.config[3:])
+    cfg_id = int(args.config[3:]) if args.config.startswith("cfg") else 10 + int(args.config[1:])
 
     # ------------------------------------------------------------------ inputs
     if wl["ragged"]:

@@ -164,6 +164,10 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
   if (tid == 0) s_ready = 0u;
   __syncthreads();
 
+  // The select kernel counts its finished segments per head from zero (tile 0
+  // exists for every sequence, empty ones included).
+  if (p.arrivals != nullptr && tile_id == 0 && tid < G)
+    p.arrivals[(int64_t)(head0 + tid) * p.arrivals_stride] = 0u;
   if (t0 >= L) return;  // whole workgroup
 #ifdef ADAMAS_PHASE_TRACE   // (no wait here: the encode vectors are still on their way)
   if (threadIdx.x == 0) trace.t[kScanLengthKnown] = wall_clock64();
@@ -405,9 +409,6 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
       reinterpret_cast<uint32_t*>(p.V + row * D)[c] = reinterpret_cast<const uint32_t*>(p.v_new + src)[c];
     }
   }
-  // The select kernel counts its finished segments per head from zero.
-  if (p.arrivals != nullptr && tile_id == 0 && tid < G)
-    p.arrivals[(int64_t)(head0 + tid) * p.arrivals_stride] = 0u;
   if (p.tilehist != nullptr) {
     __syncthreads();
     for (int i = tid; i < G * kPairs; i += nthreads) {

@@ -1067,3 +1067,52 @@ def test_distances_above_255_in_some_tiles(H, oracle, hd, far_share, k):
     for b, L in enumerate((L0, L1)):
         assert np.array_equal(got[b, :, :L], ref["dist"][b, :, :L])
     assert np.array_equal(idx2.cpu().numpy(), ref["idx"])
+
+
+@pytest.mark.parametrize("k", [1, 64, 300])
+def test_ragged_batch_of_every_length_up_to_257(H, oracle, k):
+    """257 sequences of lengths 1, 2, ..., 257 in one call (one token of each appended in the
+    same step), a query group of three: indices bit for bit, attention within tolerance, the
+    appended K / V / code rows in place."""
+    lens = list(range(1, 258))
+    case = synth.make_case("ragged257", 7100 + k, 257, 6, 2, lens, [0],
+                           lambda b, L, h, rng: rng.choice(L, (3, min(1, L // 3)), replace=False),
+                           append=True)
+    d = H.DeviceCase(case, k)
+    out, idx = d.decode_step()
+    ref = H.oracle_step(case, k, want_dist=False)
+    assert np.array_equal(idx, ref["idx"])
+    assert H.attn_rel_err(out, ref["out"]) <= H.ATTN_TOL
+    assert np.array_equal(d.codes.cpu().numpy(), ref["rows"])
+    assert np.array_equal(H.host_u16(d.K), ref["K"]) and np.array_equal(H.host_u16(d.V), ref["V"])
+
+
+def test_merge_inside_the_select_kernel_equals_the_merge_kernel_on_a_ragged_batch(H, oracle):
+    """Sixteen segments per head for the longest sequence, fewer for the others (down to one and
+    to an empty sequence), four query heads per sequence: the one-call step (segments merged by the
+    last workgroup to arrive, device-scope atomics) and the staged call (separate merge kernel)
+    must agree bit for bit, call after call on one workspace, and match the oracle."""
+    import paper_2510_18413_amd as A
+    lens = [65536, 40000, 4097, 4096, 300, 0, 20481, 61441]
+    case = synth.make_case("ragged_merge", 7200, len(lens), 4, 2, lens, [0],
+                           lambda b, L, h, rng: rng.choice(L, (2, min(1, L // 2)), replace=False))
+    k = 192
+    d = H.DeviceCase(case, k)
+    for stages in (A.STAGE_SCAN, A.STAGE_SELECT_ATTN):
+        A.adamas_decode_step_stages(d.cfg, d.q, d.K, d.V, d.codes, d.seq_start, d.seq_len, k, d.out,
+                                    d.max_len, d.workspace, idx_out=d.idx, stages=stages)
+    torch.cuda.synchronize()
+    staged_out, staged_idx = d.out.clone(), d.idx.clone()
+    ref = H.oracle_step(case, k, want_dist=False)
+    assert np.array_equal(staged_idx.cpu().numpy(), ref["idx"])
+    assert H.attn_rel_err(staged_out.cpu().numpy(), ref["out"]) <= H.ATTN_TOL
+    outs = []
+    for it in range(12):
+        o = torch.full_like(d.out, float("nan"))
+        A.adamas_decode_step(d.cfg, d.q, d.K, d.V, d.codes, d.seq_start, d.seq_len, k, o, d.max_len,
+                             d.workspace, idx_out=d.idx)
+        outs.append(o)
+    torch.cuda.synchronize()
+    for it, o in enumerate(outs):
+        assert torch.equal(o, staged_out), f"call {it}"
+    assert torch.equal(d.idx, staged_idx)
