@@ -69,6 +69,8 @@ def parse_args():
     ap.add_argument("--paged", type=int, default=0, metavar="PAGE_TOKENS",
                     help="lay the cache out on randomly placed pages of this many tokens and time "
                          "adamas_decode_step_paged (0: contiguous sequences)")
+    ap.add_argument("--min-sweeps", type=int, default=MIN_SWEEPS,
+                    help="fewest timed graph replays of the fused step (a profiler run may want fewer)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--eager", action="store_true", help="launch from Python instead of a graph")
     ap.add_argument("--scan-only", action="store_true",
@@ -379,7 +381,7 @@ def main():
         return [round(sorted_us[n // 10], 3), round(sorted_us[n // 2], 3),
                 round(sorted_us[(n * 9) // 10], 3)]
 
-    def timed(stages, steps, warmup, min_sweeps=MIN_SWEEPS):
+    def timed(stages, steps, warmup, min_sweeps=None):
         """Returns (sorted us per step of every timed sweep, steps timed).  Graph mode times whole
         sweeps over the rotating layers, whatever `steps` asks for; --eager times `steps` Python
         launches once."""
@@ -395,7 +397,7 @@ def main():
             torch.cuda.synchronize()
             return [e0.elapsed_time(e1) * 1e3 / steps], steps
         g = make_graph(stages)
-        sweeps, warm = sweep_plan(steps, warmup, min_sweeps)
+        sweeps, warm = sweep_plan(steps, warmup, args.min_sweeps if min_sweeps is None else min_sweeps)
         return replay_timed(g, sweeps, warm, n_layers), sweeps * n_layers
 
     if args.calibrate_copy:
