@@ -75,6 +75,9 @@ def parse_args():
     ap.add_argument("--eager", action="store_true", help="launch from Python instead of a graph")
     ap.add_argument("--scan-only", action="store_true",
                     help="time only the scan stage (profiling aid; no JSON-contract value)")
+    ap.add_argument("--encode-only", action="store_true",
+                    help="profiling aid: time only the bulk key encode (adamas_encode_keys over the "
+                         "rotating layers) and print its figures instead of the JSON-contract line")
     ap.add_argument("--phase-trace", action="store_true",
                     help="profiling aid: load the stamping build (python -m "
                          "paper_2510_18413_amd.build --phase-trace) and print where the time goes "
@@ -312,19 +315,31 @@ def main():
         data["out"] = torch.zeros(B, Hq, HD, device=dev)
         A.adamas_encode_keys(cfg, data["K"], data["codes"], 0, pool)
         layers.append(data)
-    # bulk key encode (prefill-side, not part of the timed step): average of 20 runs over the
-    # rotating layers, after 5 untimed ones (the clocks have dropped during the set-up above)
-    for i in range(5):
-        A.adamas_encode_keys(cfg, layers[i % n_layers]["K"], layers[i % n_layers]["codes"], 0, pool)
+    # bulk key encode (prefill-side, not part of the timed step): median over 12 timed blocks of
+    # 40 runs each over the rotating layers, after 60 untimed runs (the clocks have dropped during
+    # the set-up above, and a block of a few runs is too short to time)
+    def encode_block(n):
+        for i in range(n):
+            A.adamas_encode_keys(cfg, layers[i % n_layers]["K"], layers[i % n_layers]["codes"], 0, pool)
+    encode_block(60)
     torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for i in range(20):
-        A.adamas_encode_keys(cfg, layers[i % n_layers]["K"], layers[i % n_layers]["codes"], 0, pool)
-    e1.record()
-    torch.cuda.synchronize()
-    encode_us = e0.elapsed_time(e1) * 1e3 / 20
+    encode_blocks = []
+    for _ in range(12):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        encode_block(40)
+        e1.record()
+        torch.cuda.synchronize()
+        encode_blocks.append(e0.elapsed_time(e1) * 1e3 / 40)
+    encode_us = sorted(encode_blocks)[len(encode_blocks) // 2]
     encode_bytes = Hkv * pool * (2 * HD + row_bytes)
+    if args.encode_only:
+        print(json.dumps({"bulk_encode_us": round(encode_us, 2),
+                          "blocks_min_max_us": [round(min(encode_blocks), 2), round(max(encode_blocks), 2)], "rows": Hkv * pool, "bytes": encode_bytes,
+                          "GBps": round(encode_bytes / encode_us / 1e3, 1),
+                          "hbm_frac": round(encode_bytes / encode_us / 1e3 / HBM_PEAK_GBPS, 4),
+                          "config": args.config, "head_dim": HD, "code_bits": bits}))
+        return
     idx0 = torch.empty(B, Hq, k, dtype=torch.int32, device=dev)
     ws = torch.empty(A.adamas_workspace_bytes(cfg, B, max_len, k), dtype=torch.uint8, device=dev)
     torch.cuda.synchronize()

@@ -237,6 +237,7 @@ Thresholds scaled(const adamas_config* c, const float* thr) {
   // rounded up: a bound must not shrink when it is stored as a float
   t.dtau = worst == 0.0 ? 0.f : std::nextafter((float)(worst * 1.000001), INFINITY);
   if (!std::isfinite(t.dtau)) t.fast = 0;
+  t.symmetric = n_thr == 3 && t.tau[1] == 0.0 && t.tau[2] > 0.0 && t.tau[0] == -t.tau[2];
   return t;
 }
 

@@ -21,6 +21,9 @@ struct Thresholds {
   float tau32[7];
   float dtau;
   int fast;
+  // Two-bit codes whose thresholds are (-t, 0, t) with t > 0, exactly: the
+  // attempt then compares |y| with t and reads the sign of y.
+  int symmetric;
 };
 
 // Bit planes of the bucket index c = #{i : y > tau_i} from the nested indicator
@@ -240,9 +243,9 @@ __device__ __forceinline__ float dpp_quad_xor_f32(float v, bool xor2) {
                              : __builtin_amdgcn_mov_dpp(b, kDppQuadXor1, 0xf, 0xf, true));
 }
 
-template <int BITS, int D>
-__device__ __forceinline__ bool encode_part_fast(const uint4 (&raw)[4], const Thresholds& thr, int j,
-                                                 uint32_t (&m)[(1 << BITS) - 1]) {
+template <int BITS, int D, bool TRANSFORM>
+__device__ __forceinline__ bool encode_part_fast_as(const uint4 (&raw)[4], const Thresholds& thr, int j,
+                                                    uint32_t (&m)[(1 << BITS) - 1]) {
   constexpr int LPV = D / 32, T = (1 << BITS) - 1;
   constexpr int kStages = D == 64 ? 6 : D == 128 ? 7 : 8;
   // gamma with a margin of 1.5 u for the rounding of sum |x_i|, of the guard
@@ -261,7 +264,7 @@ __device__ __forceinline__ bool encode_part_fast(const uint4 (&raw)[4], const Th
   float sum_abs = 0.f;
 #pragma unroll
   for (int i = 0; i < 32; ++i) sum_abs += fabsf(x[i]);
-  if (thr.transform) {
+  if constexpr (TRANSFORM) {
 #pragma unroll
     for (int h = 1; h < 32; h <<= 1) {
 #pragma unroll
@@ -284,6 +287,36 @@ __device__ __forceinline__ bool encode_part_fast(const uint4 (&raw)[4], const Th
     }
   }
   float nearest = 3.0e38f;  // smallest |coefficient - threshold| of the vector
+  if constexpr (BITS == 2) {
+    if (thr.symmetric) {
+      // Thresholds (-t, 0, t): with u = |y| - t the distances to the thresholds are
+      // |u| and |y|, and away from the thresholds y > 0 is the cleared sign of y,
+      // y > -t is "y > 0 or u < 0", y > t is "y > 0 and not u < 0".  A coefficient
+      // on a threshold (y = 0 of either sign included) has distance 0 and is never
+      // certified, so the signs of the zeros do not matter; a vector of zeros has
+      // code 1 everywhere.
+      uint32_t neg_y = 0, neg_u = 0;
+#pragma unroll
+      for (int e = 31; e >= 0; --e) {
+        const float u = fabsf(x[e]) - thr.tau32[2];
+        asm("v_alignbit_b32 %0, %1, %2, 31" : "=v"(neg_y) : "v"(neg_y), "v"(x[e]));
+        asm("v_alignbit_b32 %0, %1, %2, 31" : "=v"(neg_u) : "v"(neg_u), "v"(u));
+        // one instruction; a NaN would be skipped here but makes sum_abs fail its test below
+        asm("v_min3_f32 %0, %1, |%2|, |%3|" : "=v"(nearest) : "v"(nearest), "v"(u), "v"(x[e]));
+      }
+#pragma unroll
+      for (int s = 0; (1 << s) < LPV; ++s) {
+        sum_abs += s < 2 ? dpp_quad_xor_f32(sum_abs, s == 1) : __shfl_xor(sum_abs, 4, kWave);
+        nearest = fminf(nearest, s < 2 ? dpp_quad_xor_f32(nearest, s == 1) : __shfl_xor(nearest, 4, kWave));
+      }
+      const bool zeros = sum_abs == 0.f;
+      m[0] = zeros ? 0xffffffffu : (~neg_y | neg_u);
+      m[1] = zeros ? 0u : ~neg_y;
+      m[2] = zeros ? 0u : (~neg_y & ~neg_u);
+      const float guard = (TRANSFORM ? sum_abs * kGuard : 0.f) + thr.dtau;
+      return sum_abs < 1.0e30f && (nearest > guard || zeros);
+    }
+  }
 #pragma unroll
   for (int i = 0; i < T; ++i) m[i] = 0;
 #pragma unroll
@@ -304,8 +337,39 @@ __device__ __forceinline__ bool encode_part_fast(const uint4 (&raw)[4], const Th
     nearest = fminf(nearest, s < 2 ? dpp_quad_xor_f32(nearest, s == 1) : __shfl_xor(nearest, 4, kWave));
   }
   // Without the transform the "sums" are the elements themselves: exact.
-  const float guard = (thr.transform ? sum_abs * kGuard : 0.f) + thr.dtau;
+  const float guard = (TRANSFORM ? sum_abs * kGuard : 0.f) + thr.dtau;
   return sum_abs < 1.0e30f && (nearest > guard || guard == 0.f || sum_abs == 0.f);
+}
+
+// Division of a 32-bit index by a divisor fixed at launch (Granlund and
+// Montgomery's round-up method): with l = ceil(log2 d) and
+// m = floor(2^32 (2^l - d) / d) + 1,  n / d = (t + ((n - t) >> min(l, 1))) >> max(l - 1, 0),
+// t = mulhi(m, n), for every n below 2^32.
+struct Divisor32 {
+  uint32_t mul, sh1, sh2;
+  static Divisor32 of(uint32_t d) {  // host side; d >= 1
+    uint32_t l = 0;
+    while (l < 32 && ((uint64_t)1 << l) < d) ++l;
+    Divisor32 r;
+    r.mul = (uint32_t)(((((uint64_t)1 << l) - d) << 32) / d + 1);
+    r.sh1 = l < 1 ? l : 1;
+    r.sh2 = l < 1 ? 0 : l - 1;
+    return r;
+  }
+  __device__ __forceinline__ uint32_t quotient(uint32_t n) const {
+    const uint32_t t = __umulhi(mul, n);
+    return (t + ((n - t) >> sh1)) >> sh2;
+  }
+};
+
+// With or without the transform (Section 4.4's ablation bucketizes the raw
+// vector): two copies of the routine under one wave-uniform branch, so that
+// neither carries the other's register moves.
+template <int BITS, int D>
+__device__ __forceinline__ bool encode_part_fast(const uint4 (&raw)[4], const Thresholds& thr, int j,
+                                                 uint32_t (&m)[(1 << BITS) - 1]) {
+  if (thr.transform) return encode_part_fast_as<BITS, D, true>(raw, thr, j, m);
+  return encode_part_fast_as<BITS, D, false>(raw, thr, j, m);
 }
 
 // Vector v of n_vec = n_heads * n_rows lives at
@@ -316,7 +380,8 @@ __global__ __launch_bounds__(256) void encode_rows_kernel(const uint16_t* __rest
                                                           uint8_t* __restrict__ dst,
                                                           int64_t head_stride_rows,
                                                           int64_t row_begin, int64_t n_rows,
-                                                          int64_t n_vec, Thresholds thr) {
+                                                          int64_t n_vec, Thresholds thr,
+                                                          Divisor32 by_rows) {
   constexpr int W = D / 32, E = HeadDim<D>::kEncElems;
   constexpr int kRowBytes = W * 4 * BITS;
   const int lane = threadIdx.x & 63;
@@ -357,7 +422,9 @@ __global__ __launch_bounds__(256) void encode_rows_kernel(const uint16_t* __rest
     int64_t row = 0;
     bool certified = true;
     if (valid) {
-      const int64_t head = v / n_rows, r = v - head * n_rows;
+      // by_rows divides by n_rows; built by the launcher when n_vec fits 32 bits (mul = 0 otherwise; a divisor's mul is never 0)
+      const int64_t head = by_rows.mul != 0u ? (int64_t)by_rows.quotient((uint32_t)v) : v / n_rows;
+      const int64_t r = v - head * n_rows;
       row = head * head_stride_rows + row_begin + r;
       const uint4* in = reinterpret_cast<const uint4*>(src + row * D + j * 32);
       uint4 raw[4];

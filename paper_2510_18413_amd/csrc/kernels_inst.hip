@@ -63,8 +63,10 @@ void launch_encode_rows(hipStream_t st, const uint16_t* src, uint8_t* dst, int64
   const int64_t per_wg = HeadDim<D>::kPow2 ? 256 / (D / 32) : 4;
   const int64_t want = (n_vec + per_wg - 1) / per_wg;
   const int grid = (int)(want < 16384 ? want : 16384);
+  Divisor32 by_rows{};  // mul = 0: the kernel divides in 64 bits
+  if (n_vec < ((int64_t)1 << 32) && n_rows >= 1) by_rows = Divisor32::of((uint32_t)n_rows);
   hipLaunchKernelGGL((encode_rows_kernel<BITS_, D>), dim3(grid), dim3(256), 0, st, src, dst,
-                     head_stride_rows, row_begin, n_rows, n_vec, thr);
+                     head_stride_rows, row_begin, n_rows, n_vec, thr, by_rows);
 }
 
 template <int D_>

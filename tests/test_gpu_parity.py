@@ -103,6 +103,45 @@ def test_encode_coefficients_within_rounding_of_a_threshold(H, oracle):
     assert above > 5       # both sides of the thresholds occurred
 
 
+@pytest.mark.parametrize("hd", [64, 128, 256])
+def test_encode_symmetric_thresholds_within_rounding_of_a_coefficient(H, oracle, hd):
+    """Thresholds (-t, 0, t) take a route of their own through the bulk encode (|y| against t and
+    the sign of y).  Here t is the magnitude of one of a vector's exact coefficients rounded to
+    float, the vectors have the wide exponent spread on which single precision rounds, and some
+    have coefficients that are exactly zero (equal elements, zeros of either sign)."""
+    import paper_2510_18413_amd as A
+    rng = np.random.default_rng(4100 + hd)
+    n = 512
+    above = below = 0
+    for trial in range(12):
+        x = rng.standard_normal((n, hd), dtype=np.float32)
+        x[:, 1::2] *= np.float32(2.0 ** -10)
+        x[0::7, :] = x[0::7, :1]                  # constant vectors: every coefficient but one is 0
+        x[1::7, hd // 2:] = x[1::7, :hd // 2]     # repeated halves: half of the coefficients are 0
+        x[2::7, :] = 0.0
+        x[2::7, 3::5] = -0.0
+        bits = synth.f32_to_bf16_bits(x)
+        xs = synth.bf16_bits_to_f32(bits).astype(np.float64)
+        with oracle.head_dim(hd):
+            y = oracle.hadamard_transform(xs[3 + 7 * int(rng.integers(40))])
+        pick = float(np.abs(y[rng.integers(hd)]))
+        t = float(np.float32(pick / np.sqrt(float(hd))))
+        if not t > 0.0:
+            continue
+        tau = t * np.sqrt(float(hd))
+        above += pick > tau
+        below += pick < tau
+        thr = (-t, 0.0, t)
+        cfg = A.Config.make(1, 1, n, thr_k=thr, head_dim=hd)
+        codes = torch.zeros(1, n, hd // 4, dtype=torch.uint8, device="cuda")
+        A.adamas_encode_keys(cfg, H.dev_bf16(bits.reshape(1, n, hd)), codes, 0, n)
+        torch.cuda.synchronize()
+        with oracle.head_dim(hd):
+            ref = oracle.encode(bits, thr)[1]
+        assert np.array_equal(codes.cpu().numpy()[0], ref), trial
+    assert above > 0 and below > 0
+
+
 @pytest.mark.parametrize("hd,bits", [(128, 2), (64, 2), (256, 2), (128, 1), (128, 3)])
 def test_encode_wide_exponent_spread(H, oracle, hd, bits):
     """60 000 vectors whose elements span about 28 binary orders of magnitude (so that single
