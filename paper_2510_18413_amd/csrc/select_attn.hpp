@@ -118,10 +118,18 @@ struct AttnShared {
 // Threads 0..D-1 receive, for output dim tid: M (running maximum), lsum (sum of
 // weights) and o (unnormalised weighted sum of V).
 // Entries of s_sel are clamped to [0, n_tokens) before use (n_tokens >= 1 when n > 0).
+// qv is the lane's piece of the query, from load_query_piece: the caller
+// requests it as early as it can, so that it does not arrive after the rows.
 // All threads must call it.
+template <int D>
+__device__ __forceinline__ uint4 load_query_piece(const uint16_t* __restrict__ q) {
+  constexpr int LPR = HeadDim<D>::kRowGroup;
+  const int gl = threadIdx.x % LPR;
+  return gl < HeadDim<D>::kRowLanes ? *reinterpret_cast<const uint4*>(q + gl * 8) : make_uint4(0, 0, 0, 0);
+}
+
 template <int THREADS, int D>
-__device__ __forceinline__ void attention_rows(const int32_t* s_sel, int n, int n_tokens,
-                                               const uint16_t* __restrict__ q,
+__device__ __forceinline__ void attention_rows(const int32_t* s_sel, int n, int n_tokens, const uint4 qv,
                                                const uint16_t* __restrict__ Kp,
                                                const uint16_t* __restrict__ Vp, double scale_log2e,
                                                AttnShared<THREADS, D>& sh, float& M, float& lsum,
@@ -146,7 +154,6 @@ __device__ __forceinline__ void attention_rows(const int32_t* s_sel, int n, int 
 
   double qf[8];
   {
-    const uint4 qv = lane_on ? *reinterpret_cast<const uint4*>(q + gl * 8) : make_uint4(0, 0, 0, 0);
     qf[0] = bf16_lo(qv.x); qf[1] = bf16_hi(qv.x); qf[2] = bf16_lo(qv.y); qf[3] = bf16_hi(qv.y);
     qf[4] = bf16_lo(qv.z); qf[5] = bf16_hi(qv.z); qf[6] = bf16_lo(qv.w); qf[7] = bf16_hi(qv.w);
   }
@@ -266,6 +273,19 @@ __device__ __forceinline__ void word_masks(uint32_t w, uint32_t y, uint32_t& lt,
   }
 }
 
+// Byte planes: the flags of four words (bit 7 of byte b of word w = token 4 w + b)
+// gathered into 16 bits, bit j = token j.  A dot product of the flag bytes
+// (0x80 or 0) with the weights 1, 2, 4, 8 (and 16 .. 128 for the next word)
+// leaves 128 times the eight flags.
+__device__ __forceinline__ uint32_t flags16(const uint32_t (&m)[4]) {
+  uint32_t lo = __builtin_amdgcn_udot4(m[0], 0x08040201u, 0u, false);
+  lo = __builtin_amdgcn_udot4(m[1], 0x80402010u, lo, false);
+  uint32_t hi = __builtin_amdgcn_udot4(m[2], 0x08040201u, 0u, false);
+  hi = __builtin_amdgcn_udot4(m[3], 0x80402010u, hi, false);
+  return (lo | (hi << 8)) >> 7;
+}
+__device__ __forceinline__ uint32_t flags16(const uint32_t (&)[8]) { return 0u; }  // uint16 planes: not used
+
 // The last step of the in-kernel merge: slots 0..n_active-1 (n_active <= N) of a
 // head's partials, read with device-scope loads, combined in slot order with
 // merge_kernel's arithmetic.
@@ -332,6 +352,8 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
   const int64_t head = (int64_t)b * p.Hq + hq;
   const int seg_t0 = seg * p.seg_len;
   SeqInfo seq = SeqInfo::request<PAGED, false>(p.seq_len, p.seq_start, b);
+  uint4 qv = make_uint4(0, 0, 0, 0);  // this lane's piece of the query, for the attention at the end
+  if constexpr (ATTN) qv = load_query_piece<D>(p.q + head * D);
 
   // Nothing below depends on the sequence length until the loads are issued:
   // the workspace rows exist up to dist_stride / n_tiles (+ kHistBatch rows of
@@ -523,6 +545,14 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
   // what the low bits of a stored distance are compared with
   const uint32_t y = BYTES ? (uint32_t)(T & 255) * 0x01010101u : (uint32_t)T * 0x00010001u;
 
+  // gather: rows of the sequence's KV head (pool rows for a paged cache)
+  constexpr int kRowLines = (D + 63) / 64;  // 128-byte lines that a row of D bf16 values touches
+  const int64_t row0 = ((int64_t)kv_head_of(hq, p.group_magic) * p.pool_tokens + seq.start) * D;
+  const int64_t gather_rows = PAGED ? p.pool_tokens : (int64_t)L;
+  uint32_t early[2 * kRowLines];
+#pragma unroll
+  for (int i = 0; i < 2 * kRowLines; ++i) early[i] = 0u;
+
   int pass_no = 1;  // buffer 0 of s_wave was just read
   for (int pass_t0 = seg_t0; pass_t0 < seg_t1; pass_t0 += PASS, ++pass_no) {
     const int t = pass_t0 + tid * kSelTokPerThread;
@@ -566,27 +596,30 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
     uint32_t m_lt[DW], m_eq[DW], n_lt = 0, n_eq = 0;
 #pragma unroll
     for (int w = 0; w < DW; ++w) word_masks<BYTES>(dw[w], y, m_lt[w], m_eq[w]);
-    if constexpr (HIGH) {
-      // The bytes were compared on their low eight bits.  Ninth bits are rare,
-      // thresholds of 256 and more too.
-      if ((high & 0xffffu) != 0u || T >= 256) {
-#pragma unroll
-        for (int w = 0; w < DW; ++w) {
-          const uint32_t e = (((high >> (4 * w)) & 0xfu) * 0x10204080u) & 0x80808080u;  // ninth bits at bit 7 of their bytes
-          if (T < 256) {
-            m_lt[w] &= ~e;
-            m_eq[w] &= ~e;
-          } else {
-            m_lt[w] |= ~e & 0x80808080u;
-            m_eq[w] &= e;
-          }
+    // Byte planes: the flags of the thread's 16 tokens gathered into 16 bits (bit j = token j).
+    uint32_t lt16 = 0, eq16 = 0;
+    if constexpr (BYTES) {
+      lt16 = flags16(m_lt);
+      eq16 = flags16(m_eq);
+      if constexpr (HIGH) {
+        // The bytes were compared on their low eight bits; `high` holds the ninth bits.
+        const uint32_t h16 = high & 0xffffu;
+        if (T < 256) {
+          lt16 &= ~h16;
+          eq16 &= ~h16;
+        } else {
+          lt16 |= ~h16 & 0xffffu;
+          eq16 &= h16;
         }
       }
-    }
+      n_lt = (uint32_t)__popc(lt16);
+      n_eq = (uint32_t)__popc(eq16);
+    } else {
 #pragma unroll
-    for (int w = 0; w < DW; ++w) {
-      n_lt += (uint32_t)__popc(m_lt[w]);
-      n_eq += (uint32_t)__popc(m_eq[w]);
+      for (int w = 0; w < DW; ++w) {
+        n_lt += (uint32_t)__popc(m_lt[w]);
+        n_eq += (uint32_t)__popc(m_eq[w]);
+      }
     }
     if (pass_no == 1) trace.stamp(kSelMasked, false);
     // exclusive prefix over the workgroup (one barrier per pass: the wave totals alternate buffers)
@@ -605,28 +638,75 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
     const uint32_t ex = before + incl - cnt;
     uint32_t lt = run_lt + (ex & 0xffffu), eq = run_eq + (ex >> 16);
     if (pass_no == 1) trace.stamp(kSelPrefix, false);
-    // Visit only the candidate tokens (set bits), in position order.
+    if constexpr (ATTN) {
+      // The gather below starts only after the compaction; the K and V rows of
+      // this thread's first selected token are requested here already (one word
+      // per 128-byte line, never used), so that the gather finds them in the
+      // cache.  First pass only: the registers are not reused while in flight.
+      if (pass_no == 1) {
+        int j = 0;
+        bool some = false, first_eq = false;
+        if constexpr (BYTES) {
+          const uint32_t c = lt16 | eq16;
+          j = __builtin_ctz(c | 0x10000u);
+          some = c != 0u;
+          first_eq = (eq16 >> j) & 1u;
+        } else {
 #pragma unroll
-    for (int w = 0; w < DW; ++w) {
-      uint32_t cand = m_lt[w] | m_eq[w];
-      while (cand != 0u) {
-        const int bit = __builtin_ctz(cand);
-        cand &= cand - 1u;
-        const bool is_eq = (m_eq[w] >> bit) & 1u;
-        const int j = TPW * w + bit / TB;
-        if (!is_eq || eq < (uint32_t)r) {
-          const uint32_t pos = lt + min(eq, (uint32_t)r);
-          // pos < kk always holds for consistent histograms; the checks keep a
-          // corrupted workspace from turning into an out-of-bounds store.
-          if (pos < (uint32_t)kk) {
-            if (idx_row != nullptr) idx_row[pos] = t + j;
-            // the gather list holds token positions, or pool rows for a paged cache
-            if (ATTN && pos - seg_pos0 < (uint32_t)kMaxK)
-              s_sel[pos - seg_pos0] = PAGED ? (int32_t)(page_row0 + j) : t + j;
+          for (int w = DW - 1; w >= 0; --w) {
+            const uint32_t cw = m_lt[w] | m_eq[w];
+            if (cw != 0u) {
+              const int bit = __builtin_ctz(cw);
+              some = true;
+              first_eq = (m_eq[w] >> bit) & 1u;
+              j = TPW * w + bit / TB;
+            }
           }
         }
-        lt += is_eq ? 0u : 1u;
-        eq += is_eq ? 1u : 0u;
+        if (some && (!first_eq || eq < (uint32_t)r)) {
+          const int64_t row = min(PAGED ? page_row0 + j : (int64_t)(t + j), gather_rows - 1);
+          const uint32_t* kr = reinterpret_cast<const uint32_t*>(p.K + row0 + row * D);
+          const uint32_t* vr = reinterpret_cast<const uint32_t*>(p.V + row0 + row * D);
+#pragma unroll
+          for (int c128 = 0; c128 < kRowLines; ++c128) {
+            early[2 * c128] = kr[32 * c128];
+            early[2 * c128 + 1] = vr[32 * c128];
+          }
+        }
+      }
+    }
+    // Visit only the candidate tokens (set bits), in position order.
+    auto emit = [&](int j, bool is_eq) {
+      if (!is_eq || eq < (uint32_t)r) {
+        const uint32_t pos = lt + min(eq, (uint32_t)r);
+        // pos < kk always holds for consistent histograms; the checks keep a
+        // corrupted workspace from turning into an out-of-bounds store.
+        if (pos < (uint32_t)kk) {
+          if (idx_row != nullptr) idx_row[pos] = t + j;
+          // the gather list holds token positions, or pool rows for a paged cache
+          if (ATTN && pos - seg_pos0 < (uint32_t)kMaxK)
+            s_sel[pos - seg_pos0] = PAGED ? (int32_t)(page_row0 + j) : t + j;
+        }
+      }
+      lt += is_eq ? 0u : 1u;
+      eq += is_eq ? 1u : 0u;
+    };
+    if constexpr (BYTES) {
+      uint32_t cand = lt16 | eq16;
+      while (cand != 0u) {
+        const int j = __builtin_ctz(cand);
+        cand &= cand - 1u;
+        emit(j, (eq16 >> j) & 1u);
+      }
+    } else {
+#pragma unroll
+      for (int w = 0; w < DW; ++w) {
+        uint32_t cand = m_lt[w] | m_eq[w];
+        while (cand != 0u) {
+          const int bit = __builtin_ctz(cand);
+          cand &= cand - 1u;
+          emit(TPW * w + bit / TB, (m_eq[w] >> bit) & 1u);
+        }
       }
     }
     run_lt += total & 0xffffu;
@@ -639,11 +719,12 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
     const int n_sel = min((int)(run_lt + min(run_eq, (uint32_t)r) - seg_pos0), kk);
     __syncthreads();  // s_sel complete
     trace.stamp(kSelCompacted, false);  // (not waiting for the index stores)
-    const int kvh = kv_head_of(hq, p.group_magic);
-    const int64_t row0 = ((int64_t)kvh * p.pool_tokens + seq.start) * D;
     float M, lsum, o;
-    attention_rows<THREADS, D>(s_sel, n_sel, PAGED ? (int)p.pool_tokens : L, p.q + head * D,
+    attention_rows<THREADS, D>(s_sel, n_sel, (int)gather_rows, qv,
                             p.K + row0, p.V + row0, p.scale_log2e, s_attn, M, lsum, o, trace);
+    // the early requests have long returned; this only keeps them alive until here
+#pragma unroll
+    for (int i = 0; i < 2 * kRowLines; ++i) asm volatile("" : : "v"(early[i]));
     trace.stamp(kSelCombined, false);
     if (gridDim.x == 1 || (p.arrivals != nullptr && n_active == 1)) {
       if (tid < D) p.out[head * D + tid] = lsum > 0.f ? o / lsum : 0.f;
@@ -736,6 +817,7 @@ __global__ __launch_bounds__(kAttnThreads) void sparse_attn_kernel(const AttnPar
   const int64_t head = (int64_t)b * p.Hq + hq;
   const int i0 = part * p.chunk, i1 = min(p.k, i0 + p.chunk);
   const int32_t* idx_row = p.idx + head * p.k;
+  const uint4 qv = load_query_piece<D>(p.q + head * D);
   const int64_t start = p.seq_start[b];
   // Order-preserving compaction of the usable entries of this chunk: negative
   // entries are padding; an entry that would leave the pool is dropped too.
@@ -755,8 +837,7 @@ __global__ __launch_bounds__(kAttnThreads) void sparse_attn_kernel(const AttnPar
   float M, lsum, o;
   PhaseTrace trace;  // not recorded for the stand-alone kernel
   attention_rows<kAttnThreads, D>(s_sel, (int)n, (int)min((int64_t)0x7fffffff, p.pool_tokens - start),
-                               p.q + head * D, p.K + row0, p.V + row0,
-                               p.scale_log2e, s_attn, M, lsum, o, trace);
+                               qv, p.K + row0, p.V + row0, p.scale_log2e, s_attn, M, lsum, o, trace);
   if (tid < D) {
     if (gridDim.x == 1) {
       p.out[head * D + tid] = lsum > 0.f ? o / lsum : 0.f;
