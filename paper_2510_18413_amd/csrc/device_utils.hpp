@@ -227,6 +227,16 @@ __device__ __forceinline__ float dpp_f32(float v) {
   return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
 }
 
+// Lane `lane` (0..3) of v receives the wave-uniform value x; the other lanes keep theirs.
+__device__ __forceinline__ void write_lane(uint32_t& v, uint32_t x, int lane) {
+  switch (lane) {
+    case 0: asm("v_writelane_b32 %0, %1, 0" : "+v"(v) : "s"(x)); break;
+    case 1: asm("v_writelane_b32 %0, %1, 1" : "+v"(v) : "s"(x)); break;
+    case 2: asm("v_writelane_b32 %0, %1, 2" : "+v"(v) : "s"(x)); break;
+    default: asm("v_writelane_b32 %0, %1, 3" : "+v"(v) : "s"(x)); break;
+  }
+}
+
 // Sum over each aligned group of LANES lanes (8, 16 or 32); every lane of the
 // group receives the total.  After the two quad steps all lanes of a quad
 // agree, so mirroring inside the half row pairs quad 0 with quad 1, mirroring

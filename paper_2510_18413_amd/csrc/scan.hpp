@@ -299,11 +299,17 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
   };
   uint32_t* hist_lane = &s_hist[0][lane & (kHistReplicas - 1)][0];  // two 16-bit bins per word
 
+  // Ninth bits (byte planes of distances up to 511): the ballot of step i over the
+  // wave's 64 tokens is one word of the plane; lane i keeps the word of step i.
+  uint32_t high_lo[G], high_hi[G];
+#pragma unroll
+  for (int g = 0; g < G; ++g) high_lo[g] = high_hi[g] = 0u;
 #pragma unroll
   for (int i = 0; i < kScanTokPerThread; ++i) {
     // keep the tokens in load order, so that each waits only for its own rows
     __builtin_amdgcn_sched_barrier(0);
     const int t = t0 + (wave * kScanTokPerThread + i) * kWave + lane;
+    const uint64_t in_range = __builtin_amdgcn_ballot_w64(t < L);
     // kw[BITS * wd + pl]: plane pl of word wd of the key row
     uint32_t kw[kRowWords];
 #pragma unroll
@@ -319,8 +325,14 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
         uint32_t c1 = 0, c2 = 0, c3 = 0;
 #pragma unroll
         for (int wd = 0; wd < W; ++wd) {
-          const uint32_t xl = kw[2 * wd] ^ qplane(g, 0, wd), xh = kw[2 * wd + 1] ^ qplane(g, 1, wd);
-          const uint32_t u = xh & ~(xl & qplane(g, 2, wd));
+          // Every instruction below takes one query plane: with two of them in one
+          // instruction (the compiler's choice when it may merge them) a plane held
+          // in a scalar register must first be copied.  Hence the opaque values.
+          uint32_t xl = kw[2 * wd] ^ qplane(g, 0, wd);
+          asm("" : "+v"(xl));
+          uint32_t both = xl & qplane(g, 2, wd);
+          asm("" : "+v"(both));
+          const uint32_t u = (kw[2 * wd + 1] ^ qplane(g, 1, wd)) & ~both;
           c1 += __popc(xl);
           c2 += __popc(u);
           if constexpr (METRIC == kMetricL2) c3 += __popc(u & xl);
@@ -351,18 +363,17 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
         d = c0 + 2u * c1 + 4u * c2;
       }
       s_dt[wave][g][i * kWave + lane] = (DistT)d;
+      // ninth bits of 64 consecutive tokens = one word of the plane, straight from the ballot
       if constexpr (Fmt::kHighPlane) {
-        // ninth bits of 64 consecutive tokens = one word of the plane, straight from the ballot
-        const uint64_t high = __ballot(t < L && d > 255u);
-        const int t64 = t0 + (wave * kScanTokPerThread + i) * kWave;
-        if (lane == 0 && p.dist != nullptr && t64 < L)
-          p.dist_high[((int64_t)(head0 + g) * p.dist_stride + t64) >> 6] = high;
+        const uint64_t word = __builtin_amdgcn_ballot_w64(d > 255u) & in_range;
+        write_lane(high_lo[g], (uint32_t)word, i);
+        write_lane(high_hi[g], (uint32_t)(word >> 32), i);
       }
-      if (t < L) {
-        const int64_t head = head0 + g;
-        if (p.dist_user != nullptr) p.dist_user[head * p.dist_user_stride + t] = (uint16_t)d;
-        atomicAdd(hist_lane + g * (kHistReplicas * kPairs) + (d >> 1), (d & 1u) ? 0x10000u : 1u);
-      }
+      // two 16-bit bins per word: 1 for an even distance, 0x10000 for an odd one
+      // (opaque halves: otherwise the compiler turns them into a compare and a select)
+      uint32_t pair = d >> 1, odd16 = (d & 1u) << 4;
+      asm("" : "+v"(pair), "+v"(odd16));
+      if (t < L) atomicAdd(hist_lane + g * (kHistReplicas * kPairs) + pair, 1u << odd16);
     }
   }
 
@@ -373,6 +384,33 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
   // The region is private to the wave, so no barrier is needed.
   // A row of the plane holds a multiple of 128 tokens, so a lane whose first
   // token exists may store all four.
+  if constexpr (Fmt::kHighPlane) {
+    // The wave's kScanTokPerThread words of the ninth-bit plane are consecutive:
+    // lane i stores word i (64 tokens from t64), if that word holds tokens.
+    const int t64 = t0 + (wave * kScanTokPerThread + lane) * kWave;
+    if (p.dist != nullptr && lane < kScanTokPerThread && t64 < L) {
+#pragma unroll
+      for (int g = 0; g < G; ++g)
+        p.dist_high[((int64_t)(head0 + g) * p.dist_stride + t64) >> 6] =
+            ((uint64_t)high_hi[g] << 32) | high_lo[g];
+    }
+  }
+  if (p.dist_user != nullptr) {  // the caller's own array of distances (adamas_distances)
+#pragma unroll
+    for (int i = 0; i < kScanTokPerThread; ++i) {
+      const int t = t0 + (wave * kScanTokPerThread + i) * kWave + lane;
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        uint32_t d = s_dt[wave][g][i * kWave + lane];
+        if constexpr (Fmt::kHighPlane) {
+          const uint32_t w_lo = (uint32_t)__builtin_amdgcn_readlane((int)high_lo[g], i);
+          const uint32_t w_hi = (uint32_t)__builtin_amdgcn_readlane((int)high_hi[g], i);
+          d |= (((lane < 32 ? w_lo : w_hi) >> (lane & 31)) & 1u) << 8;
+        }
+        if (t < L) p.dist_user[(int64_t)(head0 + g) * p.dist_user_stride + t] = (uint16_t)d;
+      }
+    }
+  }
   if (p.dist != nullptr) {
     const int tt = t0 + wave * (kScanTokPerThread * kWave) + kScanTokPerThread * lane;
     if (tt < L) {
