@@ -280,33 +280,18 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
 
   trace.stamp(kScanQueryReady);
   // The query planes are wave-uniform.  Up to 24 words (the method's group of
-  // one or two) live in vector registers; larger groups keep them in scalar
+  // one or two) live in vector registers.  Larger groups keep them in scalar
   // registers (every instruction of the distance needs only one of them, and the
-  // kernel then fits 64 vector registers: measured faster from a group of four
-  // on, slower for a group of two).
+  // kernel then fits 64 vector registers), at most 24 words at a time: the heads
+  // of the group are served in passes of kPassHeads over the rows, which stay
+  // in registers.  All planes of a group of four at once take about 100 scalar
+  // registers, and it is then the scalar register file that limits how many
+  // waves a compute unit holds (measured: the only resource the dispatcher
+  // reports as full, with about four waves per SIMD resident).
   // qp[g][j][wd]: plane j of word wd; for 2-bit codes j = 2 is lo ^ hi.
-  // Groups whose planes exceed the scalar registers as well (96 words) are read
-  // from LDS where they are used (a broadcast read per word).
   constexpr int QP = BITS == 2 ? 3 : BITS;
-  constexpr bool kQueryInLds = G * QP * W > 96;
-  uint32_t qp[kQueryInLds ? 1 : G][QP][W];
-  if constexpr (!kQueryInLds) {
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-#pragma unroll
-      for (int j = 0; j < QP; ++j) {
-#pragma unroll
-        for (int wd = 0; wd < W; ++wd) {
-          if constexpr (G * QP * W <= 24) qp[g][j][wd] = s_q[g][W * j + wd];
-          else qp[g][j][wd] = __builtin_amdgcn_readfirstlane(s_q[g][W * j + wd]);
-        }
-      }
-    }
-  }
-  auto qplane = [&](int g, int j, int wd) -> uint32_t {
-    if constexpr (kQueryInLds) return s_q[g][W * j + wd];
-    else return qp[g][j][wd];
-  };
+  constexpr bool kPlanesInVgprs = G * QP * W <= 24;
+  constexpr int kPassHeads = kPlanesInVgprs ? G : (24 / (QP * W) > 0 ? 24 / (QP * W) : 1);
   uint32_t* hist_lane = &s_hist[0][lane & (kHistReplicas - 1)][0];
 
   // Ninth bits (byte planes of distances up to 511): the ballot of step i over the
@@ -315,9 +300,24 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
 #pragma unroll
   for (int g = 0; g < G; ++g) high_lo[g] = high_hi[g] = 0u;
 #pragma unroll
+  for (int g0 = 0; g0 < G; g0 += kPassHeads) {
+  uint32_t qp[kPassHeads][QP][W];
+#pragma unroll
+  for (int g = g0; g < g0 + kPassHeads && g < G; ++g) {
+#pragma unroll
+    for (int j = 0; j < QP; ++j) {
+#pragma unroll
+      for (int wd = 0; wd < W; ++wd) {
+        if constexpr (kPlanesInVgprs) qp[g - g0][j][wd] = s_q[g][W * j + wd];
+        else qp[g - g0][j][wd] = __builtin_amdgcn_readfirstlane(s_q[g][W * j + wd]);
+      }
+    }
+  }
+  auto qplane = [&](int g, int j, int wd) -> uint32_t { return qp[g - g0][j][wd]; };
+#pragma unroll
   for (int i = 0; i < kScanTokPerThread; ++i) {
     // keep the tokens in load order, so that each waits only for its own rows
-    __builtin_amdgcn_sched_barrier(0);
+    if (g0 == 0) __builtin_amdgcn_sched_barrier(0);
     const int t = t0 + (wave * kScanTokPerThread + i) * kWave + lane;
     const uint64_t in_range = __builtin_amdgcn_ballot_w64(t < L);
     // kw[BITS * wd + pl]: plane pl of word wd of the key row
@@ -329,7 +329,7 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
       for (int wq = 0; wq < kRowWords; ++wq) kw[wq] = s_new[wq];
     }
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
+    for (int g = g0; g < g0 + kPassHeads && g < G; ++g) {
       uint32_t d;
       if constexpr (BITS == 2) {
         uint32_t c1 = 0, c2 = 0, c3 = 0;
@@ -390,6 +390,7 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
       }
     }
   }
+  }  // passes over the heads of the group
 
   trace.stamp(kScanRowsDone);
   // Distances leave through LDS: a lane computed tokens 64 apart, but stores
