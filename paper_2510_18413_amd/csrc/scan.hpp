@@ -114,6 +114,9 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
   // part `gsub` of the KV head's group of G * g_split (the parts re-read the rows).
   PhaseTrace trace;
   trace.stamp(kScanStart);
+  // requested first of all: the row loads cannot be addressed without them
+  SeqInfo seq = SeqInfo::request<PAGED, true>(p.seq_len, p.seq_start, (int)blockIdx.z);
+  __builtin_amdgcn_sched_barrier(0);
   // g_split is 1 or 2
   const int tile_id = blockIdx.x, kvh = blockIdx.y >> (p.g_split - 1), gsub = blockIdx.y & (p.g_split - 1);
   const int b = blockIdx.z;
@@ -122,8 +125,6 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_kernel(const ScanParams p)
   constexpr int tile_tokens = nthreads * kScanTokPerThread;
   const int t0 = tile_id * tile_tokens;
   const int head0 = b * p.Hq + (kvh * p.g_split + gsub) * G;
-  // requested first of all: the row loads cannot be addressed without them
-  SeqInfo seq = SeqInfo::request<PAGED, true>(p.seq_len, p.seq_start, b);
 
   // First of all the encoding waves request their vectors (G queries and, if
   // the call appends, the new key): their addresses need nothing from memory,

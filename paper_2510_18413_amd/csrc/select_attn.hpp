@@ -347,11 +347,13 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
 
   PhaseTrace trace;
   trace.stamp(kSelStart);
+  // first of all, ahead of everything else the compiler may want to load
+  SeqInfo seq = SeqInfo::request<PAGED, false>(p.seq_len, p.seq_start, (int)blockIdx.z);
+  __builtin_amdgcn_sched_barrier(0);
   const int seg = blockIdx.x, hq = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int64_t head = (int64_t)b * p.Hq + hq;
   const int seg_t0 = seg * p.seg_len;
-  SeqInfo seq = SeqInfo::request<PAGED, false>(p.seq_len, p.seq_start, b);
   uint4 qv = make_uint4(0, 0, 0, 0);  // this lane's piece of the query, for the attention at the end
   if constexpr (ATTN) qv = load_query_piece<D>(p.q + head * D);
 
