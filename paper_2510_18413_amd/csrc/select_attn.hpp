@@ -110,6 +110,50 @@ struct AttnShared {
   float acc[kWaves][D];
 };
 
+// One step of combining the online-softmax states (m, l, acc[8]) of the lane
+// groups of a wave: afterwards lanes i and i ^ STEP hold the combination of
+// their two states (the same bits in both: each side is weighted and the two
+// products are added, which commutes).  STEP 16 and 32 exchange with the
+// swap instructions of the vector ALU (a: the state of the lane whose STEP bit
+// is clear, b: of the lane whose bit is set, both in every lane), STEP 8 with
+// a rotation inside the row of 16 lanes.
+template <int STEP>
+__device__ __forceinline__ void exchange_pair(float v, float& a, float& b) {
+  static_assert(STEP == 8 || STEP == 16 || STEP == 32, "lane groups of 8, 16 or 32");
+  const uint32_t u = __float_as_uint(v);
+  if constexpr (STEP == 32) {
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    a = __uint_as_float(r[0]);
+    b = __uint_as_float(r[1]);
+  } else if constexpr (STEP == 16) {
+    const auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+    a = __uint_as_float(r[0]);
+    b = __uint_as_float(r[1]);
+  } else {
+    const float o = __int_as_float(__builtin_amdgcn_update_dpp(0, (int)u, 0x128 /* row_ror:8 */, 0xf, 0xf, false));
+    const bool upper = (threadIdx.x & 8) != 0;
+    a = upper ? o : v;
+    b = upper ? v : o;
+  }
+}
+template <int STEP>
+__device__ __forceinline__ void combine_lane_groups(float& m, float& l, float (&acc)[8]) {
+#pragma clang fp contract(off)
+  float ma, mb, la, lb;
+  exchange_pair<STEP>(m, ma, mb);
+  exchange_pair<STEP>(l, la, lb);
+  const float mn = fmaxf(ma, mb);
+  const float wa = exp2_neg(ma - mn), wb = exp2_neg(mb - mn);
+  m = mn;
+  l = la * wa + lb * wb;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    float xa, xb;
+    exchange_pair<STEP>(acc[j], xa, xb);
+    acc[j] = xa * wa + xb * wb;
+  }
+}
+
 // Softmax attention (Eq. 1) of one query over the n rows listed in s_sel (token
 // positions; Kp, Vp point at the sequence's first row of the right KV head),
 // by the whole workgroup: D / 8 lanes per row, 8 dims per lane, one-pass online
@@ -217,16 +261,9 @@ __device__ __forceinline__ void attention_rows(const int32_t* s_sel, int n, int 
   // group: combine them pairwise with cross-lane moves (both partners compute
   // the same values), then the waves through LDS.  A group without rows has
   // l = 0 and m = kNegBig and drops out with weight exp2(kNegBig - M) = 0.
-#pragma unroll
-  for (int step = LPR; step < kWave; step <<= 1) {
-    const float mo = __shfl_xor(m, step, kWave), lo = __shfl_xor(l, step, kWave);
-    const float mn = fmaxf(m, mo);
-    const float wa = exp2_neg(m - mn), wb = exp2_neg(mo - mn);
-    m = mn;
-    l = l * wa + lo * wb;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) acc[j] = acc[j] * wa + __shfl_xor(acc[j], step, kWave) * wb;
-  }
+  if constexpr (LPR <= 8) combine_lane_groups<8>(m, l, acc);
+  if constexpr (LPR <= 16) combine_lane_groups<16>(m, l, acc);
+  combine_lane_groups<32>(m, l, acc);
   if (lane < kRowLanes) {
     if (lane == 0) {
       sh.m[wave] = m;
