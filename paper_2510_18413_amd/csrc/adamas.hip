@@ -217,6 +217,16 @@ Plan make_plan(const adamas_config* c, int32_t batch, int64_t max_seq_len, int32
   return pl;
 }
 
+// Whether the select kernel requests its first K / V lines ahead of the gather
+// (SelectParams::early_rows).  Measured on MI355X: it gains 0.25 to 0.6 us
+// where at most two workgroups share a compute unit and a segment takes at most
+// four passes (contexts of 32K to 128K at batch 1 to 4), is neutral to slightly
+// harmful with eight passes per segment (16 ragged sequences, one segment per
+// head), and costs 6 us of 48 with 2048 short heads in flight.
+int early_rows_pay(const Plan& pl, int64_t n_heads) {
+  return n_heads * pl.n_segs <= 2 * kTargetWorkgroups && pl.seg_len <= 4 * kSegGranule ? 1 : 0;
+}
+
 // Thresholds as the kernels compare them (see struct Thresholds).
 Thresholds scaled(const adamas_config* c, const float* thr) {
   Thresholds t{};
@@ -472,6 +482,7 @@ int adamas_select_topk(const adamas_config* cfg, const void* qcodes, const void*
   sl.seg_len = pl.seg_len;
   sl.tile_shift = log2_of(pl.tile_tokens);
   sl.seg_shift = log2_of(pl.seg_len);
+  sl.early_rows = early_rows_pay(pl, (int64_t)batch * cfg->num_q_heads);
   set_of(cfg).select(false, false, dim3(pl.n_segs, cfg->num_q_heads, batch), st, sl);
   return launch_status();
 }
@@ -676,6 +687,7 @@ int decode_step_impl(const adamas_config* cfg, const void* q, const void* k_new,
   sl.seg_len = pl.seg_len;
   sl.tile_shift = log2_of(pl.tile_tokens);
   sl.seg_shift = log2_of(pl.seg_len);
+  sl.early_rows = early_rows_pay(pl, (int64_t)batch * cfg->num_q_heads);
   sl.scale_log2e = scale_log2e(cfg);
   sl.page_table = page_table;
   sl.max_pages = max_pages;

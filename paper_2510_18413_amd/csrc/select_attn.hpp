@@ -55,6 +55,12 @@ struct SelectParams {
   uint32_t group_magic;       // see kv_head_of
   int32_t n_tiles, tile_tokens, seg_len;  // tile_tokens and seg_len are powers of two
   int32_t tile_shift, seg_shift;          // their logarithms
+  // Request the K / V lines of each thread's first selected token ahead of the
+  // gather (see the kernel).  Pays when the kernel is bound by its chain of
+  // memory round trips (few workgroups, few passes each); costs when it is bound
+  // by throughput: the requests are one line per lane and double the gather's
+  // traffic between the caches.
+  int32_t early_rows;
   double scale_log2e;         // sm_scale * log2(e)
   // Paged cache (PAGED kernels only), as in ScanParams.
   const int32_t* page_table;
@@ -682,7 +688,8 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
       // this thread's first selected token are requested here already (one word
       // per 128-byte line, never used), so that the gather finds them in the
       // cache.  First pass only: the registers are not reused while in flight.
-      if (pass_no == 1) {
+      // The host switches this on for launches that are bound by latency.
+      if (pass_no == 1 && p.early_rows != 0) {
         int j = 0;
         bool some = false, first_eq = false;
         if constexpr (BYTES) {
