@@ -404,7 +404,7 @@ int oracle_squared_distance(const uint8_t *qcode, const uint8_t *kcodes, int64_t
   return ORACLE_OK;
 }
 
-/* --------------------------------------------------- top-k, Algorithm 1 l.6 */
+/* --------------------------------------------------- top-k (Algorithm 1, selection step) */
 
 typedef struct {
   int32_t dist;

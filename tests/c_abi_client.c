@@ -2,7 +2,9 @@
  * A plain C program that uses the library the way a serving engine without
  * Python would: hipMalloc'ed buffers, adamas.h, nothing else.  TEST CODE: it
  * checks the fused decode step (with append, ragged batch, GQA) against the CPU
- * oracle, which it links as well.  Exit code 0 = all checks passed.
+ * oracle, which it links as well, then the staged entry points (query codes,
+ * distances, top-k, attention) and the step that allocates nothing against the
+ * same results.  Exit code 0 = all checks passed.
  */
 #include <hip/hip_runtime_api.h>
 #include <math.h>
@@ -126,6 +128,58 @@ int main(void) {
     for (int i = 0; i < K_BUDGET; ++i) found |= idx[(b * Hq) * K_BUDGET + i] == 123;
     if (!found) { fprintf(stderr, "sequence %d: token 123 not selected\n", b); bad = 1; }
   }
-  printf("C ABI client: %s (attention max rel err %.3g)\n", bad ? "FAILED" : "OK", worst);
+  /* The staged entry points on the cache as the step left it (new token appended): query codes,
+   * distances, top-k, attention over the selected rows; then the step again without an append,
+   * through the entry point that allocates nothing.  Indices must equal the fused step's bit for
+   * bit, outputs must meet the same bound against the oracle. */
+  void *dqcodes, *ddist, *didx2, *dout2;
+  HIP_OK(hipMalloc(&dqcodes, B * Hq * 32)); HIP_OK(hipMalloc(&ddist, (size_t)B * Hq * max_len * 2));
+  HIP_OK(hipMalloc(&didx2, sizeof idx)); HIP_OK(hipMalloc(&dout2, sizeof out));
+  HIP_OK(hipMemset(ddist, 0xEE, (size_t)B * Hq * max_len * 2));
+  rc = adamas_encode_query(&cfg, dq, dqcodes, B, NULL);
+  if (!rc) rc = adamas_manhattan_distance(&cfg, dqcodes, dcodes, dstart, dlen, B, ddist, max_len, NULL);
+  if (!rc) rc = adamas_select_topk(&cfg, dqcodes, dcodes, dstart, dlen, B, K_BUDGET, didx2, NULL, max_len,
+                                   dws, ws_bytes, NULL);
+  if (!rc) rc = adamas_sparse_attn(&cfg, dq, dK, dV, dstart, didx2, B, K_BUDGET, dout2, max_len, dws,
+                                   ws_bytes, NULL);
+  if (rc) { fprintf(stderr, "staged calls: %s\n", adamas_status_string(rc)); return 1; }
+  HIP_OK(hipDeviceSynchronize());
+  float out2[B * Hq * D];
+  int32_t idx2[B * Hq * K_BUDGET];
+  uint16_t *dist = malloc((size_t)B * Hq * max_len * 2);
+  if (!dist) return 2;
+  HIP_OK(hipMemcpy(out2, dout2, sizeof out2, hipMemcpyDeviceToHost));
+  HIP_OK(hipMemcpy(idx2, didx2, sizeof idx2, hipMemcpyDeviceToHost));
+  HIP_OK(hipMemcpy(dist, ddist, (size_t)B * Hq * max_len * 2, hipMemcpyDeviceToHost));
+  if (memcmp(idx2, ref_idx, sizeof idx2)) { fprintf(stderr, "staged indices differ\n"); bad = 1; }
+  double worst2 = 0.0;
+  for (int h = 0; h < B * Hq; ++h) {
+    double mx = 0.0;
+    for (int j = 0; j < D; ++j) mx = fmax(mx, fabs(ref_out[h * D + j]));
+    for (int j = 0; j < D; ++j) {
+      double r = ref_out[h * D + j];
+      worst2 = fmax(worst2, fabs(out2[h * D + j] - r) / fmax(fabs(r), 1e-3 * mx));
+    }
+  }
+  if (!(worst2 <= 2e-3)) { fprintf(stderr, "staged attention rel err %g\n", worst2); bad = 1; }
+  for (int b = 0; b < B; ++b) { /* distances: 0..384 inside the sequence, untouched behind it; the copied key is nearest */
+    for (int h = 0; h < Hq; ++h) {
+      const uint16_t *dr = dist + ((size_t)b * Hq + h) * max_len;
+      for (int t = 0; t < max_len; ++t) {
+        if (t < lens[b] ? dr[t] > 384 : dr[t] != 0xEEEE) { fprintf(stderr, "distance [%d][%d][%d] = %u\n", b, h, t, dr[t]); bad = 1; t = max_len; }
+      }
+    }
+    if (dist[(size_t)b * Hq * max_len + 123] != 0) { fprintf(stderr, "sequence %d: distance to its own copy is not 0\n", b); bad = 1; }
+  }
+  HIP_OK(hipMemset(dout2, 0, sizeof out2)); HIP_OK(hipMemset(didx2, 0xFF, sizeof idx2));
+  rc = adamas_decode_step_static(&cfg, dq, NULL, NULL, dK, dV, dcodes, dstart, dlen, B, K_BUDGET, dout2, didx2,
+                                 max_len, NULL);
+  if (rc) { fprintf(stderr, "decode_step_static: %s\n", adamas_status_string(rc)); return 1; }
+  HIP_OK(hipDeviceSynchronize());
+  HIP_OK(hipMemcpy(out2, dout2, sizeof out2, hipMemcpyDeviceToHost));
+  HIP_OK(hipMemcpy(idx2, didx2, sizeof idx2, hipMemcpyDeviceToHost));
+  if (memcmp(idx2, idx, sizeof idx2)) { fprintf(stderr, "static step: indices differ\n"); bad = 1; }
+  if (memcmp(out2, out, sizeof out2)) { fprintf(stderr, "static step: output differs from the step's\n"); bad = 1; }
+  printf("C ABI client: %s (attention max rel err %.3g fused, %.3g staged)\n", bad ? "FAILED" : "OK", worst, worst2);
   return bad;
 }
