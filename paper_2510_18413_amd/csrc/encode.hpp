@@ -3,6 +3,8 @@
 // (Algorithm 1, transform / bucketize / compress steps).
 #pragma once
 
+#include <utility>
+
 #include "device_utils.hpp"
 
 namespace adamas {
@@ -75,6 +77,21 @@ constexpr uint32_t paley_neg_column(int m, int c) {
   return neg;
 }
 
+// The sign masks as compile-time constants (a call of paley_neg_column in device
+// code with a loop variable as argument leaves its loops and remainders to run
+// time when m = 20): kPaleyNeg<M, C>, and a loop whose index is a constant
+// expression to name them with.
+template <int M, int C>
+inline constexpr uint32_t kPaleyNeg = paley_neg_column(M, C);
+template <typename F, int... I>
+__device__ __forceinline__ void static_for_each(F&& f, std::integer_sequence<int, I...>) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  static_for_each(f, std::make_integer_sequence<int, N>{});
+}
+
 template <int CTRL>
 __device__ __forceinline__ double quad_bcast_f64(double v) {
   const uint64_t b = __builtin_bit_cast(uint64_t, v);
@@ -112,21 +129,24 @@ __device__ __forceinline__ void encode_values_wave_kron(const uint32_t (&raw)[He
       xs[2 * E + e] = quad_bcast_f64<0xAA>(v[e]);
       xs[3 * E + e] = quad_bcast_f64<0xFF>(v[e]);
     }
-#pragma unroll
-    for (int e = 0; e < E; ++e) {
+    double out[E];
+    static_for<E>([&](auto e_) {
+      constexpr int e = decltype(e_)::value;
       // signs of output coefficient c4 * E + e of the block
-      const uint32_t neg = c4 == 0 ? paley_neg_column(M, 0 * E + e)
-                         : c4 == 1 ? paley_neg_column(M, 1 * E + e)
-                         : c4 == 2 ? paley_neg_column(M, 2 * E + e)
-                                   : paley_neg_column(M, 3 * E + e);
+      const uint32_t neg = c4 == 0 ? kPaleyNeg<M, 0 * E + e>
+                         : c4 == 1 ? kPaleyNeg<M, 1 * E + e>
+                         : c4 == 2 ? kPaleyNeg<M, 2 * E + e>
+                                   : kPaleyNeg<M, 3 * E + e>;
       double acc = 0.0;
 #pragma unroll
       for (int r = 0; r < M; ++r) {
         const uint64_t flip = (uint64_t)((neg >> r) & 1u) << 63;
         acc += __builtin_bit_cast(double, __builtin_bit_cast(uint64_t, xs[r]) ^ flip);
       }
-      v[e] = acc;
-    }
+      out[e] = acc;
+    });
+#pragma unroll
+    for (int e = 0; e < E; ++e) v[e] = out[e];
 #pragma unroll
     for (int h = 4; h < kLanes; h <<= 1) {  // index bits of the 2^n factor: across lanes
       const bool upper = (lane & h) != 0;
