@@ -192,3 +192,37 @@ def test_product_code_never_touches_the_oracle():
                 text = open(os.path.join(dirpath, f)).read()
                 assert "oracle" not in text.lower(), os.path.join(dirpath, f)
     assert "oracle" not in open(os.path.join(ROOT, "include", "adamas.h")).read().lower()
+
+
+def test_merge_uses_device_scope_accesses(tmp_path):
+    """The attention merge inside the select kernel exchanges partials between workgroups that may
+    run on different XCDs without a cache write-back or invalidate: it relies on every access to
+    a partial being a device-scope access (the `sc1` bit on gfx950), which goes to the memory
+    side instead of the XCD's own L2, and on the arrival counter being a hardware atomic.  A compiler that lowered the
+    relaxed agent-scope atomics of the source differently would break the merge silently, so the
+    kernel's assembly (of our own source, compiled here) must show the three kinds of access."""
+    import subprocess
+    from paper_2510_18413_amd import build as B
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    if not os.path.exists(hipcc):
+        pytest.skip("no hipcc")
+    out = tmp_path / "select.s"
+    flags = [f for f in B.HIPCC_FLAGS if f != "-fPIC"]
+    subprocess.run([hipcc] + flags + ["-w", "-DADAMAS_INST_D=128", "-DADAMAS_INST_METRIC=0",
+                                      "-I", os.path.join(ROOT, "include"), "-I", str(B.CSRC),
+                                      "-S", "--cuda-device-only", "-o", str(out),
+                                      str(B.CSRC / "kernels_inst.hip")], check=True)
+    text = out.read_text()
+    # the decode step's select kernel: 256 threads, with attention, Eq. 6, contiguous cache, d = 128
+    start = re.search(r"^_ZN6adamas13select_kernelILi256ELb1ELi0ELb0ELi128EEE\w*:", text, re.M)
+    assert start, "select kernel not found in the assembly"
+    body = text[start.end():text.index(".Lfunc_end", start.end())]
+    sc1 = [l.split() for l in body.splitlines() if re.search(r"\bsc1\b", l)]
+    kinds = {w[0] for w in sc1}
+    assert any(k.startswith("global_store_dword") for k in kinds), kinds      # partials out
+    assert any(k.startswith("global_load_dword") for k in kinds), kinds       # partials read back
+    # the arrival counter: a returning atomic add (device-wide atomicity is the hardware's; the
+    # compiler marks only system scope with sc1 on read-modify-write instructions)
+    assert re.search(r"^\s*global_atomic_add\w* v\d+, .*\bsc0\b", body, re.M)
+    # and no whole-cache write-back / invalidate crept in (the fence that cost 23 us per step)
+    assert "buffer_wbl2" not in body and "buffer_inv" not in body
