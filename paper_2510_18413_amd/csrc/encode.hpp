@@ -263,10 +263,92 @@ __device__ __forceinline__ float dpp_quad_xor_f32(float v, bool xor2) {
                              : __builtin_amdgcn_mov_dpp(b, kDppQuadXor1, 0xf, 0xf, true));
 }
 
+// Exchange with the lane whose index inside the vector's lane group differs in bit s.
+__device__ __forceinline__ float group_xor_f32(float v, int s) {
+  return s < 2 ? dpp_quad_xor_f32(v, s == 1) : __shfl_xor(v, 1 << s, kWave);
+}
+
+// The comparisons of Eq. 5 on the lane's N single-precision coefficients x, and the
+// certificate: m[i] gets bit e set where x[e] > tau_i; the return value says whether
+// every coefficient of the vector (all LPV lanes of its group) is further from every
+// threshold than guard_per_abs * sum |x_i| (+ the rounding of the thresholds), i.e.
+// whether the masks are those of the exact sums.  sum_abs: this lane's share of sum |x_i|.
+template <int BITS, int N, int LPV, bool TRANSFORM>
+__device__ __forceinline__ bool certified_masks(const float (&x)[N], float sum_abs, const Thresholds& thr,
+                                                float guard_per_abs, uint32_t (&m)[(1 << BITS) - 1]) {
+  constexpr int T = (1 << BITS) - 1;
+  constexpr uint32_t kAll = N == 32 ? 0xffffffffu : (1u << (N & 31)) - 1u;
+  float nearest = 3.0e38f;  // smallest |coefficient - threshold| of the vector
+  if constexpr (BITS == 2) {
+    if (thr.symmetric) {
+      // Thresholds (-t, 0, t): with u = |y| - t the distances to the thresholds are
+      // |u| and |y|, and away from the thresholds y > 0 is the cleared sign of y,
+      // y > -t is "y > 0 or u < 0", y > t is "y > 0 and not u < 0".  A coefficient
+      // on a threshold (y = 0 of either sign included) has distance 0 and is never
+      // certified, so the signs of the zeros do not matter; a vector of zeros has
+      // code 1 everywhere.
+      uint32_t neg_y = 0, neg_u = 0;
+#pragma unroll
+      for (int e = N - 1; e >= 0; --e) {
+        const float u = fabsf(x[e]) - thr.tau32[2];
+        asm("v_alignbit_b32 %0, %1, %2, 31" : "=v"(neg_y) : "v"(neg_y), "v"(x[e]));
+        asm("v_alignbit_b32 %0, %1, %2, 31" : "=v"(neg_u) : "v"(neg_u), "v"(u));
+        // one instruction; a NaN would be skipped here but makes sum_abs fail its test below
+        asm("v_min3_f32 %0, %1, |%2|, |%3|" : "=v"(nearest) : "v"(nearest), "v"(u), "v"(x[e]));
+      }
+#pragma unroll
+      for (int s = 0; (1 << s) < LPV; ++s) {
+        sum_abs += group_xor_f32(sum_abs, s);
+        nearest = fminf(nearest, group_xor_f32(nearest, s));
+      }
+      const bool zeros = sum_abs == 0.f;
+      m[0] = zeros ? kAll : ((~neg_y | neg_u) & kAll);
+      m[1] = zeros ? 0u : (~neg_y & kAll);
+      m[2] = zeros ? 0u : (~neg_y & ~neg_u & kAll);
+      const float guard = (TRANSFORM ? sum_abs * guard_per_abs : 0.f) + thr.dtau;
+      return sum_abs < 1.0e30f && (nearest > guard || zeros);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < T; ++i) m[i] = 0;
+#pragma unroll
+  for (int e = N - 1; e >= 0; --e) {
+#pragma unroll
+    for (int i = 0; i < T; ++i) {
+      const float d = thr.tau32[i] - x[e];  // the sign of a difference is exact; +0 when equal
+      // (m << 1) | sign(d); as an opaque instruction, or the compiler rebuilds the
+      // chain as a tree over all the differences and runs out of registers
+      asm("v_alignbit_b32 %0, %1, %2, 31" : "=v"(m[i]) : "v"(m[i]), "v"(d));
+      nearest = fminf(nearest, fabsf(d));
+    }
+  }
+  // over the lanes of the group
+#pragma unroll
+  for (int s = 0; (1 << s) < LPV; ++s) {
+    sum_abs += group_xor_f32(sum_abs, s);
+    nearest = fminf(nearest, group_xor_f32(nearest, s));
+  }
+  // Without the transform the "sums" are the elements themselves: exact.
+  const float guard = (TRANSFORM ? sum_abs * guard_per_abs : 0.f) + thr.dtau;
+  return sum_abs < 1.0e30f && (nearest > guard || guard == 0.f || sum_abs == 0.f);
+}
+
+// Butterflies across the LPV lanes of a vector's group (index bits above the lane's own elements).
+template <int N, int LPV>
+__device__ __forceinline__ void cross_lane_stages(float (&x)[N], int j) {
+#pragma unroll
+  for (int s = 0; (1 << s) < LPV; ++s) {
+    const uint32_t sign_flip = ((j >> s) & 1) != 0 ? 0x80000000u : 0u;
+#pragma unroll
+    for (int i = 0; i < N; ++i)
+      x[i] = __int_as_float(__float_as_int(x[i]) ^ (int)sign_flip) + group_xor_f32(x[i], s);
+  }
+}
+
 template <int BITS, int D, bool TRANSFORM>
 __device__ __forceinline__ bool encode_part_fast_as(const uint4 (&raw)[4], const Thresholds& thr, int j,
                                                     uint32_t (&m)[(1 << BITS) - 1]) {
-  constexpr int LPV = D / 32, T = (1 << BITS) - 1;
+  constexpr int LPV = D / 32;
   constexpr int kStages = D == 64 ? 6 : D == 128 ? 7 : 8;
   // gamma with a margin of 1.5 u for the rounding of sum |x_i|, of the guard
   // itself and of the differences compared with it
@@ -296,69 +378,55 @@ __device__ __forceinline__ bool encode_part_fast_as(const uint4 (&raw)[4], const
         }
       }
     }
-#pragma unroll
-    for (int s = 0; (1 << s) < LPV; ++s) {
-      const uint32_t sign_flip = ((j >> s) & 1) != 0 ? 0x80000000u : 0u;
-#pragma unroll
-      for (int i = 0; i < 32; ++i) {
-        const float partner = s < 2 ? dpp_quad_xor_f32(x[i], s == 1) : __shfl_xor(x[i], 4, kWave);
-        x[i] = __int_as_float(__float_as_int(x[i]) ^ (int)sign_flip) + partner;
-      }
-    }
+    cross_lane_stages<32, LPV>(x, j);
   }
-  float nearest = 3.0e38f;  // smallest |coefficient - threshold| of the vector
-  if constexpr (BITS == 2) {
-    if (thr.symmetric) {
-      // Thresholds (-t, 0, t): with u = |y| - t the distances to the thresholds are
-      // |u| and |y|, and away from the thresholds y > 0 is the cleared sign of y,
-      // y > -t is "y > 0 or u < 0", y > t is "y > 0 and not u < 0".  A coefficient
-      // on a threshold (y = 0 of either sign included) has distance 0 and is never
-      // certified, so the signs of the zeros do not matter; a vector of zeros has
-      // code 1 everywhere.
-      uint32_t neg_y = 0, neg_u = 0;
+  return certified_masks<BITS, 32, LPV, TRANSFORM>(x, sum_abs, thr, kGuard, m);
+}
+
+// The same attempt for D = 2^n * m (m = 12, 20): lane j of a group of 2^n holds block j of the
+// vector, its m consecutive elements (raw: m / 2 words of two bf16 values).  The m-point stage
+// y_c = sum_r x_r P[r][c] of Paley's matrix runs in the lane:
+//   y_0 = x_0 - S,  y_c = (x_0 - S) + 2 (x_c + A_c),  S = x_1 + ... + x_q,
+//   A_c = sum of the x_r (r >= 1, r != c) with r - c a non-zero square mod q = m - 1,
+// then the butterflies over the 2^n blocks cross the lanes.  A value passes through at most
+// m + n additions (the multiplication by two is exact).
+template <int BITS, int D, bool TRANSFORM>
+__device__ __forceinline__ bool encode_block_fast_as(const uint32_t (&raw)[HeadDim<D>::kBase / 2],
+                                                     const Thresholds& thr, int j,
+                                                     uint32_t (&m)[(1 << BITS) - 1]) {
+  constexpr int M = HeadDim<D>::kBase, Q = M - 1, LPV = D / M;
+  constexpr int kLog = LPV == 4 ? 2 : LPV == 8 ? 3 : 4;
+  constexpr float kGuard = (float)((M + kLog + 1.5) * 5.9604644775390625e-8);
+  float x[M];
 #pragma unroll
-      for (int e = 31; e >= 0; --e) {
-        const float u = fabsf(x[e]) - thr.tau32[2];
-        asm("v_alignbit_b32 %0, %1, %2, 31" : "=v"(neg_y) : "v"(neg_y), "v"(x[e]));
-        asm("v_alignbit_b32 %0, %1, %2, 31" : "=v"(neg_u) : "v"(neg_u), "v"(u));
-        // one instruction; a NaN would be skipped here but makes sum_abs fail its test below
-        asm("v_min3_f32 %0, %1, |%2|, |%3|" : "=v"(nearest) : "v"(nearest), "v"(u), "v"(x[e]));
-      }
-#pragma unroll
-      for (int s = 0; (1 << s) < LPV; ++s) {
-        sum_abs += s < 2 ? dpp_quad_xor_f32(sum_abs, s == 1) : __shfl_xor(sum_abs, 4, kWave);
-        nearest = fminf(nearest, s < 2 ? dpp_quad_xor_f32(nearest, s == 1) : __shfl_xor(nearest, 4, kWave));
-      }
-      const bool zeros = sum_abs == 0.f;
-      m[0] = zeros ? 0xffffffffu : (~neg_y | neg_u);
-      m[1] = zeros ? 0u : ~neg_y;
-      m[2] = zeros ? 0u : (~neg_y & ~neg_u);
-      const float guard = (TRANSFORM ? sum_abs * kGuard : 0.f) + thr.dtau;
-      return sum_abs < 1.0e30f && (nearest > guard || zeros);
-    }
+  for (int i = 0; i < M / 2; ++i) {
+    x[2 * i] = bf16_lo(raw[i]);
+    x[2 * i + 1] = bf16_hi(raw[i]);
   }
+  float sum_abs = 0.f;
 #pragma unroll
-  for (int i = 0; i < T; ++i) m[i] = 0;
+  for (int i = 0; i < M; ++i) sum_abs += fabsf(x[i]);
+  if constexpr (TRANSFORM) {
+    float S = x[1];
 #pragma unroll
-  for (int e = 31; e >= 0; --e) {
+    for (int r = 2; r < M; ++r) S += x[r];
+    const float base = x[0] - S;
+    float y[M];
+    y[0] = base;
+    static_for<Q>([&](auto c_) {
+      constexpr int c = decltype(c_)::value + 1;  // 1 .. q
+      float a = x[c];
+      static_for<Q - 1>([&](auto s_) {
+        constexpr int sq = decltype(s_)::value + 1;  // difference r - c mod q, 1 .. q - 1
+        if constexpr (paley_is_square(Q, sq)) a += x[(c - 1 + sq) % Q + 1];
+      });
+      y[c] = base + 2.0f * a;
+    });
 #pragma unroll
-    for (int i = 0; i < T; ++i) {
-      const float d = thr.tau32[i] - x[e];  // the sign of a difference is exact; +0 when equal
-      // (m << 1) | sign(d); as an opaque instruction, or the compiler rebuilds the
-      // 32-step chain as a tree over all the differences and runs out of registers
-      asm("v_alignbit_b32 %0, %1, %2, 31" : "=v"(m[i]) : "v"(m[i]), "v"(d));
-      nearest = fminf(nearest, fabsf(d));
-    }
+    for (int i = 0; i < M; ++i) x[i] = y[i];
+    cross_lane_stages<M, LPV>(x, j);
   }
-  // over the lanes of the group
-#pragma unroll
-  for (int s = 0; (1 << s) < LPV; ++s) {
-    sum_abs += s < 2 ? dpp_quad_xor_f32(sum_abs, s == 1) : __shfl_xor(sum_abs, 4, kWave);
-    nearest = fminf(nearest, s < 2 ? dpp_quad_xor_f32(nearest, s == 1) : __shfl_xor(nearest, 4, kWave));
-  }
-  // Without the transform the "sums" are the elements themselves: exact.
-  const float guard = (TRANSFORM ? sum_abs * kGuard : 0.f) + thr.dtau;
-  return sum_abs < 1.0e30f && (nearest > guard || guard == 0.f || sum_abs == 0.f);
+  return certified_masks<BITS, M, LPV, TRANSFORM>(x, sum_abs, thr, kGuard, m);
 }
 
 // Division of a 32-bit index by a divisor fixed at launch (Granlund and
@@ -392,9 +460,23 @@ __device__ __forceinline__ bool encode_part_fast(const uint4 (&raw)[4], const Th
   return encode_part_fast_as<BITS, D, false>(raw, thr, j, m);
 }
 
+template <int BITS, int D>
+__device__ __forceinline__ bool encode_block_fast(const uint32_t (&raw)[HeadDim<D>::kBase / 2],
+                                                  const Thresholds& thr, int j,
+                                                  uint32_t (&m)[(1 << BITS) - 1]) {
+  if (thr.transform) return encode_block_fast_as<BITS, D, true>(raw, thr, j, m);
+  return encode_block_fast_as<BITS, D, false>(raw, thr, j, m);
+}
+
+__device__ __forceinline__ uint32_t group_xor_u32(uint32_t v, int s) {
+  return __float_as_uint(group_xor_f32(__uint_as_float(v), s));
+}
+
 // Vector v of n_vec = n_heads * n_rows lives at
 // src + (head * head_stride_rows + row_begin + r) * D, head = v / n_rows,
 // r = v % n_rows; its code row goes to the same row of dst (D / 8 * BITS byte rows).
+// A vector is encoded by a group of LPV lanes: D / 32 lanes with 32 elements each for a power
+// of two, 2^n lanes with one block of m elements each for D = 2^n * m (m = 12, 20).
 template <int BITS, int D>
 __global__ __launch_bounds__(256) void encode_rows_kernel(const uint16_t* __restrict__ src,
                                                           uint8_t* __restrict__ dst,
@@ -404,34 +486,12 @@ __global__ __launch_bounds__(256) void encode_rows_kernel(const uint16_t* __rest
                                                           Divisor32 by_rows) {
   constexpr int W = D / 32, E = HeadDim<D>::kEncElems;
   constexpr int kRowBytes = W * 4 * BITS;
-  const int lane = threadIdx.x & 63;
-  if constexpr (!HeadDim<D>::kPow2) {
-    // D = 2^n * 12 or 2^n * 20: one wave per vector, exact from the start.
-    const int64_t wave0 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
-    const int64_t n_waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
-    for (int64_t v = wave0; v < n_vec; v += n_waves) {
-      const int64_t head = v / n_rows, r = v - head * n_rows;
-      const int64_t row = head * head_stride_rows + row_begin + r;
-      uint32_t rawv[E];
-#pragma unroll
-      for (int e = 0; e < E; ++e)
-        rawv[e] = lane < HeadDim<D>::kEncLanes ? src[row * D + HeadDim<D>::enc_index(lane, e)] : 0u;
-      uint32_t w[BITS][W];
-      encode_values_wave<BITS, D>(rawv, thr, w);
-      uint32_t* out = reinterpret_cast<uint32_t*>(dst + row * kRowBytes);
-#pragma unroll
-      for (int wd = 0; wd < W; ++wd) {
-        if (lane == wd) {
-#pragma unroll
-          for (int p = 0; p < BITS; ++p) out[BITS * wd + p] = w[p][wd];
-        }
-      }
-    }
-    return;
-  } else {
-  constexpr int LPV = D / 32;        // lanes per vector: 2, 4 or 8
+  constexpr bool kPow2 = HeadDim<D>::kPow2;
+  constexpr int M = HeadDim<D>::kBase;          // 12 or 20 (unused for a power of two)
+  constexpr int LPV = kPow2 ? D / 32 : D / M;   // lanes per vector: 2, 4, 8 or 16
   constexpr int T = (1 << BITS) - 1;
-  const int j = threadIdx.x & (LPV - 1);  // which 32-element part of the vector
+  const int lane = threadIdx.x & 63;
+  const int j = threadIdx.x & (LPV - 1);  // which part of the vector
   const int64_t quad = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / LPV;
   const int64_t n_quads = ((int64_t)gridDim.x * blockDim.x) / LPV;
   // All 64 lanes of a wave stay in the loop as long as its first group has a
@@ -441,27 +501,77 @@ __global__ __launch_bounds__(256) void encode_rows_kernel(const uint16_t* __rest
     const bool valid = v < n_vec;
     int64_t row = 0;
     bool certified = true;
+    // Eq. 5 on the lane's coefficients: nested indicator masks (bit e: coefficient e of the lane)
+    uint32_t m[T];
+#pragma unroll
+    for (int i = 0; i < T; ++i) m[i] = 0u;
     if (valid) {
       // by_rows divides by n_rows; built by the launcher when n_vec fits 32 bits (mul = 0 otherwise; a divisor's mul is never 0)
       const int64_t head = by_rows.mul != 0u ? (int64_t)by_rows.quotient((uint32_t)v) : v / n_rows;
       const int64_t r = v - head * n_rows;
       row = head * head_stride_rows + row_begin + r;
-      const uint4* in = reinterpret_cast<const uint4*>(src + row * D + j * 32);
-      uint4 raw[4];
+      if constexpr (kPow2) {
+        const uint4* in = reinterpret_cast<const uint4*>(src + row * D + j * 32);
+        uint4 raw[4];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) raw[i] = in[i];
-      // Eq. 5 on the lane's 32 coefficients: nested indicator masks, then the
-      // planes of the bucket index; lane j stores word j of the row.
-      uint32_t m[T], plane[BITS];
-      certified = encode_part_fast<BITS, D>(raw, thr, j, m) && thr.fast != 0;
-      if (certified) {
-        planes_from_masks<BITS>(m, plane);
+        for (int i = 0; i < 4; ++i) raw[i] = in[i];
+        certified = encode_part_fast<BITS, D>(raw, thr, j, m) && thr.fast != 0;
+      } else {
+        // m bf16 values = m / 4 pieces of 8 bytes (rows and blocks are multiples of 8 bytes)
+        const uint2* in = reinterpret_cast<const uint2*>(src + row * D + j * M);
+        uint32_t raw[M / 2];
+#pragma unroll
+        for (int i = 0; i < M / 4; ++i) {
+          const uint2 piece = in[i];
+          raw[2 * i] = piece.x;
+          raw[2 * i + 1] = piece.y;
+        }
+        certified = encode_block_fast<BITS, D>(raw, thr, j, m) && thr.fast != 0;
+      }
+    }
+    uint32_t plane[BITS];
+    planes_from_masks<BITS>(m, plane);
+    if constexpr (kPow2) {
+      // lane j holds coefficients 32 j .. 32 j + 31 = word j of the row
+      if (valid && certified) {
         uint32_t* out = reinterpret_cast<uint32_t*>(dst + row * kRowBytes + j * (4 * BITS));
         if constexpr (BITS == 2) {
           *reinterpret_cast<uint2*>(out) = make_uint2(plane[0], plane[1]);
         } else {
 #pragma unroll
           for (int p = 0; p < BITS; ++p) out[p] = plane[p];
+        }
+      }
+    } else {
+      // Lane j holds the m bits of coefficients j m .. j m + m - 1 of each plane: they go to bit
+      // (j m) % 32 of word (j m) / 32 and may run over into the next word.  Every lane places
+      // its bits in a row of zeros; an OR across the group's lanes (all lanes of the wave take
+      // part in the exchanges, groups do not mix) leaves the whole row in every lane, and lane
+      // wd < W stores word wd.
+      const int at = j * M, w0 = at >> 5, sh = at & 31;
+      uint32_t words[BITS][W];
+#pragma unroll
+      for (int p = 0; p < BITS; ++p) {
+        const uint32_t lo = plane[p] << sh, hi = sh != 0 ? plane[p] >> (32 - sh) : 0u;
+#pragma unroll
+        for (int wd = 0; wd < W; ++wd) words[p][wd] = (wd == w0 ? lo : 0u) | (wd == w0 + 1 ? hi : 0u);
+      }
+#pragma unroll
+      for (int st = 0; (1 << st) < LPV; ++st) {
+#pragma unroll
+        for (int p = 0; p < BITS; ++p) {
+#pragma unroll
+          for (int wd = 0; wd < W; ++wd) words[p][wd] |= group_xor_u32(words[p][wd], st);
+        }
+      }
+      if (valid && certified) {
+        uint32_t* out = reinterpret_cast<uint32_t*>(dst + row * kRowBytes);
+#pragma unroll
+        for (int wd = 0; wd < W; ++wd) {
+          if (j == wd) {
+#pragma unroll
+            for (int p = 0; p < BITS; ++p) out[BITS * wd + p] = words[p][wd];
+          }
         }
       }
     }
@@ -476,7 +586,8 @@ __global__ __launch_bounds__(256) void encode_rows_kernel(const uint16_t* __rest
       const int64_t vrow = (int64_t)(((uint64_t)row_hi << 32) | row_lo);
       uint32_t rawv[E];
 #pragma unroll
-      for (int e = 0; e < E; ++e) rawv[e] = src[vrow * D + HeadDim<D>::enc_index(lane, e)];
+      for (int e = 0; e < E; ++e)
+        rawv[e] = lane < HeadDim<D>::kEncLanes ? src[vrow * D + HeadDim<D>::enc_index(lane, e)] : 0u;
       uint32_t w[BITS][W];
       encode_values_wave<BITS, D>(rawv, thr, w);
       uint32_t* out = reinterpret_cast<uint32_t*>(dst + vrow * kRowBytes);
@@ -489,7 +600,6 @@ __global__ __launch_bounds__(256) void encode_rows_kernel(const uint16_t* __rest
       }
     }
   }
-  }  // power of two
 }
 
 }  // namespace adamas

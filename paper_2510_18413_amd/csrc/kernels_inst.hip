@@ -59,8 +59,8 @@ void launch_select(bool attn, bool paged, dim3 grid, hipStream_t st, const Selec
 template <int BITS_>
 void launch_encode_rows(hipStream_t st, const uint16_t* src, uint8_t* dst, int64_t head_stride_rows,
                         int64_t row_begin, int64_t n_rows, int64_t n_vec, const Thresholds& thr) {
-  // vectors per 256-thread workgroup and pass: D / 32 lanes per vector, or a whole wave for D = 2^n * 12, 2^n * 20
-  const int64_t per_wg = HeadDim<D>::kPow2 ? 256 / (D / 32) : 4;
+  // vectors per 256-thread workgroup and pass: D / 32 lanes per vector, or D / m lanes for D = 2^n * m (m = 12, 20)
+  const int64_t per_wg = 256 / (HeadDim<D>::kPow2 ? D / 32 : D / HeadDim<D>::kBase);
   const int64_t want = (n_vec + per_wg - 1) / per_wg;
   const int grid = (int)(want < 16384 ? want : 16384);
   Divisor32 by_rows{};  // mul = 0: the kernel divides in 64 bits

@@ -103,7 +103,7 @@ def test_encode_coefficients_within_rounding_of_a_threshold(H, oracle):
     assert above > 5       # both sides of the thresholds occurred
 
 
-@pytest.mark.parametrize("hd", [64, 128, 256])
+@pytest.mark.parametrize("hd", [64, 128, 256, 96, 160, 192])
 def test_encode_symmetric_thresholds_within_rounding_of_a_coefficient(H, oracle, hd):
     """Thresholds (-t, 0, t) take a route of their own through the bulk encode (|y| against t and
     the sign of y).  Here t is the magnitude of one of a vector's exact coefficients rounded to
@@ -142,7 +142,8 @@ def test_encode_symmetric_thresholds_within_rounding_of_a_coefficient(H, oracle,
     assert above > 0 and below > 0
 
 
-@pytest.mark.parametrize("hd,bits", [(128, 2), (64, 2), (256, 2), (128, 1), (128, 3)])
+@pytest.mark.parametrize("hd,bits", [(128, 2), (64, 2), (256, 2), (128, 1), (128, 3),
+                                     (96, 2), (160, 2), (192, 2), (96, 3), (160, 1), (192, 3)])
 def test_encode_wide_exponent_spread(H, oracle, hd, bits):
     """60 000 vectors whose elements span about 28 binary orders of magnitude (so that single
     precision sums round all the time) against odd thresholds: every code byte as the oracle's."""
