@@ -7,7 +7,9 @@ append, Manhattan-distance scan over the whole code plane, top-k, gather and spa
 256 MB last-level cache cannot stand in for HBM, and are replayed from a HIP graph that holds
 one sweep over all layers (launch latency of the Python caller is not what is measured).
 
-Prints ONE JSON line ("Measurement").
+Whole sweeps are timed, at least 200 of them whatever --steps asks for, with an event after
+every replay; `value` is the median microseconds per layer.  Prints ONE JSON line with the
+step's figures, the scan kernel's roofline and the CPU oracle's time on the same workload.
 """
 
 import argparse
