@@ -385,6 +385,31 @@ def test_decode_step_matches_oracle(H, oracle, B, Hq, Hkv, lens, k, append):
     assert np.array_equal(out, out2)
 
 
+def test_decode_step_prologue_on_vectors_within_rounding_of_a_threshold(H, oracle):
+    """The decode step encodes its queries and the appended keys in its own prologue, one vector
+    per wave (exact sums in double precision).  Queries and new keys here are the vectors of near_threshold_cases, some of whose coefficients lie within a
+    rounding of a threshold (plain single precision misjudges them).  The appended code rows must
+    equal the oracle's bit for bit, and so must the selection: a query code off by one moves every
+    distance and with it the ties."""
+    import near_threshold_cases as ntc
+    B, Hq, Hkv = 8, 4, 2
+    for trial, (bits, thr, picks) in enumerate(ntc.trials(oracle, n_trials=8)):
+        case = small_case(1300 + trial, B, Hq, Hkv, [300 + 170 * b for b in range(B)], append=True)
+        special = [17, 117, 217]                    # the vectors the thresholds were taken from
+        others = [i for i in range(ntc.N_VECTORS) if i not in special]
+        kn = (special + others[:B * Hkv - 3])
+        qs = (others[40:40 + B * Hq - 3] + special)
+        case.k_new = np.ascontiguousarray(bits[kn].reshape(B, Hkv, 128))
+        case.q = np.ascontiguousarray(bits[qs].reshape(B, Hq, 128))
+        case.thresholds = thr
+        d = H.DeviceCase(case, 48)
+        out, idx = d.decode_step()
+        ref = H.oracle_step(case, 48, want_dist=False)
+        assert np.array_equal(d.codes.cpu().numpy(), ref["rows"]), trial
+        assert np.array_equal(idx, ref["idx"]), trial
+        assert H.attn_rel_err(out, ref["out"]) <= H.ATTN_TOL
+
+
 def test_decode_step_repeatable_and_workspace_reusable(H, oracle):
     case = small_case(601, 2, 8, 2, [3000, 9000])
     d = H.DeviceCase(case, 128)
