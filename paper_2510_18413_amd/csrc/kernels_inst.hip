@@ -45,13 +45,21 @@ void launch_scan(bool fused, int G, int tile_tokens, dim3 grid, hipStream_t st, 
   }
 }
 
-void launch_select(bool attn, bool paged, dim3 grid, hipStream_t st, const SelectParams& sl) {
+template <int CHUNK>
+void launch_select_chunk(bool attn, bool paged, dim3 grid, hipStream_t st, const SelectParams& sl) {
   if (!attn)
-    hipLaunchKernelGGL((select_kernel<kSelThreads, false, METRIC, false, D>), grid, dim3(kSelThreads), 0, st, sl);
+    hipLaunchKernelGGL((select_kernel<kSelThreads, false, METRIC, false, D, CHUNK>), grid, dim3(kSelThreads), 0, st, sl);
   else if (paged)
-    hipLaunchKernelGGL((select_kernel<kSelThreads, true, METRIC, true, D>), grid, dim3(kSelThreads), 0, st, sl);
+    hipLaunchKernelGGL((select_kernel<kSelThreads, true, METRIC, true, D, CHUNK>), grid, dim3(kSelThreads), 0, st, sl);
   else
-    hipLaunchKernelGGL((select_kernel<kSelThreads, true, METRIC, false, D>), grid, dim3(kSelThreads), 0, st, sl);
+    hipLaunchKernelGGL((select_kernel<kSelThreads, true, METRIC, false, D, CHUNK>), grid, dim3(kSelThreads), 0, st, sl);
+}
+
+void launch_select(bool attn, bool paged, dim3 grid, hipStream_t st, const SelectParams& sl) {
+  // segments of more than two passes (4096 tokens each) share one barrier among up to eight passes;
+  // only planes of byte distances have that form
+  if (Dist<METRIC, D>::kByteDist && sl.seg_len > 2 * 4096) launch_select_chunk<8>(attn, paged, grid, st, sl);
+  else launch_select_chunk<1>(attn, paged, grid, st, sl);
 }
 
 // The launchers below are templates so that a set that does not export them

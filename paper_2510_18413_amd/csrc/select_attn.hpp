@@ -25,6 +25,8 @@
 // calls, stand-alone attention) a small follow-up kernel does the same merge.
 #pragma once
 
+#include <type_traits>
+
 #include "device_utils.hpp"
 
 namespace adamas {
@@ -365,8 +367,9 @@ __device__ __forceinline__ float merge_slots(const float* ph, int n_active, int 
 // A workgroup is one wave per SIMD and runs alone on its compute unit, so its
 // time is the number of instructions a wave issues (about 2 ns each) plus the
 // memory round trips: the code below is written to issue few.
-template <int THREADS, bool ATTN, int METRIC, bool PAGED, int D>
+template <int THREADS, bool ATTN, int METRIC, bool PAGED, int D, int CHUNK>
 __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
+  static_assert(CHUNK == 1 || CHUNK == 8, "passes per workgroup barrier");
   static_assert(ATTN || !PAGED, "only the gather needs the page table");
   static_assert(THREADS >= D, "one thread per output dimension in the merge");
   using Fmt = Dist<METRIC, D>;
@@ -382,7 +385,8 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
   constexpr int DW = BYTES ? 4 : 8;                                // 32-bit words of 16 distances
   constexpr int TPW = 16 / DW;                                     // tokens per word
   constexpr int TB = 32 / TPW;                                     // bits per token in a word
-  __shared__ __align__(16) uint32_t s_wave[2][NW][2];   // per-wave prefix totals (two buffers)
+  __shared__ __align__(16) uint32_t s_wave[1][NW][2];   // per-wave prefix totals of the threshold search
+  __shared__ uint32_t s_pass[BYTES ? CHUNK : 1][NW];    // per-wave totals of the passes of a chunk
   __shared__ __align__(16) int32_t s_found[4];          // T, #{D<T}, and #{D<T}, #{D==T} before the segment
   __shared__ int32_t s_last;
   __shared__ int32_t s_sel[ATTN ? kMaxK : 1];
@@ -598,104 +602,144 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
 #pragma unroll
   for (int i = 0; i < 2 * kRowLines; ++i) early[i] = 0u;
 
-  int pass_no = 1;  // buffer 0 of s_wave was just read
-  for (int pass_t0 = seg_t0; pass_t0 < seg_t1; pass_t0 += PASS, ++pass_no) {
-    const int t = pass_t0 + tid * kSelTokPerThread;
-    uint32_t dw[DW];
+  // The passes of a segment (4096 tokens each, 16 per thread) are taken in chunks of up to kChunk:
+  // first the candidate flags and counts of every pass of the chunk (the distances are needed
+  // for nothing else), then ONE workgroup barrier for the prefix sums of all of them, then the
+  // emission from the stored flags.  (A barrier per pass cost a segment of eight passes about
+  // 0.15 us each.)  uint16 planes keep their flags in eight words per pass and take a pass at a time.
+  // CHUNK = 1 (a pass at a time) is its own instantiation of the kernel, launched for segments of
+  // one or two passes: with both forms in one kernel those lose 0.3-0.8 us.
+  auto run_passes = [&](auto chunk_) {
+  constexpr int kChunk = decltype(chunk_)::value;
+  bool first_chunk = true;
+  for (int chunk_t0 = seg_t0; chunk_t0 < seg_t1; chunk_t0 += kChunk * PASS) {
+    const int n_pass = min(kChunk, (seg_t1 - chunk_t0 + PASS - 1) / PASS);  // wave-uniform, >= 1
+    uint32_t flags[kChunk], cnt[kChunk];   // byte planes: lt flags | eq flags << 16; counts packed alike
+    int64_t prow[kChunk];                  // paged cache: pool row of the thread's first token of the pass
+    uint32_t m_lt[DW], m_eq[DW];           // uint16 planes (one pass per chunk)
 #pragma unroll
-    for (int w = 0; w < DW; ++w) {
-      dw[w] = cur[w];
-      cur[w] = nxt[w];
-    }
-    uint32_t high = cur_high;
-    cur_high = nxt_high;
-    if (t + 2 * PASS < seg_t1) {  // fetch the pass after next while this one is processed
-      const uint8_t* src = drow + (int64_t)(pass_t0 - seg_t0 + 2 * PASS) * Fmt::kDistBytes;
+    for (int w = 0; w < DW; ++w) m_lt[w] = m_eq[w] = 0u;
 #pragma unroll
-      for (int c = 0; c < DW / 4; ++c) load_piece<16>(src + 16 * c, &nxt[4 * c]);
-      if constexpr (HIGH) nxt_high = hrow_high[(pass_t0 - seg_t0 + 2 * PASS) >> 4];
-    }
-    int64_t page_row0 = 0;  // pool row of token t's page, minus the page offset of t itself
-    if constexpr (PAGED) {
-      const int64_t pg = min(max((int64_t)cur_pg, (int64_t)0), (p.pool_tokens >> p.page_shift) - 1);
-      page_row0 = (pg << p.page_shift) + (t & ((1 << p.page_shift) - 1));
-      cur_pg = nxt_pg;
-      if (t + 2 * PASS < seg_t1)
-        nxt_pg = p.page_table[(int64_t)b * p.max_pages +
-                              min((t + 2 * PASS) >> p.page_shift, p.max_pages - 1)];
-    }
-    // Tokens of this thread past the end of the segment (only in its last
-    // 16-token group) get the largest stored value, which no threshold reaches.
-    if (t + kSelTokPerThread > seg_t1) {
-      const int n_valid = max(seg_t1 - t, 0);
+    for (int c = 0; c < kChunk; ++c) {
+      flags[c] = cnt[c] = 0u;
+      prow[c] = 0;
+      if (c < n_pass) {
+        const int pass_t0 = chunk_t0 + c * PASS;
+        const int t = pass_t0 + tid * kSelTokPerThread;
+        uint32_t dw[DW];
 #pragma unroll
-      for (int w = 0; w < DW; ++w) {
-        const int keep = min(max(n_valid - TPW * w, 0), TPW);
-        const uint32_t gone = keep == TPW ? 0u : ~((1u << (TB * keep)) - 1u);
-        // bytes: 0xff (with the ninth bit below: 0x1ff); uint16: exactly 0x7fff, whatever was loaded
-        dw[w] = BYTES ? (dw[w] | gone) : ((dw[w] & ~gone) | (gone & 0x7fff7fffu));
-      }
-      if (HIGH) high |= ~((1u << n_valid) - 1u);
-    }
-    // Per word: which of its tokens lie below / at the threshold.
-    uint32_t m_lt[DW], m_eq[DW], n_lt = 0, n_eq = 0;
-#pragma unroll
-    for (int w = 0; w < DW; ++w) word_masks<BYTES>(dw[w], y, m_lt[w], m_eq[w]);
-    // Byte planes: the flags of the thread's 16 tokens gathered into 16 bits (bit j = token j).
-    uint32_t lt16 = 0, eq16 = 0;
-    if constexpr (BYTES) {
-      lt16 = flags16(m_lt);
-      eq16 = flags16(m_eq);
-      if constexpr (HIGH) {
-        // The bytes were compared on their low eight bits; `high` holds the ninth bits.
-        const uint32_t h16 = high & 0xffffu;
-        if (T < 256) {
-          lt16 &= ~h16;
-          eq16 &= ~h16;
-        } else {
-          lt16 |= ~h16 & 0xffffu;
-          eq16 &= h16;
+        for (int w = 0; w < DW; ++w) {
+          dw[w] = cur[w];
+          cur[w] = nxt[w];
         }
-      }
-      n_lt = (uint32_t)__popc(lt16);
-      n_eq = (uint32_t)__popc(eq16);
-    } else {
+        uint32_t high = cur_high;
+        cur_high = nxt_high;
+        if (t + 2 * PASS < seg_t1) {  // fetch the pass after next while this one is processed
+          const uint8_t* src = drow + (int64_t)(pass_t0 - seg_t0 + 2 * PASS) * Fmt::kDistBytes;
 #pragma unroll
-      for (int w = 0; w < DW; ++w) {
-        n_lt += (uint32_t)__popc(m_lt[w]);
-        n_eq += (uint32_t)__popc(m_eq[w]);
+          for (int q4 = 0; q4 < DW / 4; ++q4) load_piece<16>(src + 16 * q4, &nxt[4 * q4]);
+          if constexpr (HIGH) nxt_high = hrow_high[(pass_t0 - seg_t0 + 2 * PASS) >> 4];
+        }
+        if constexpr (PAGED) {
+          // pool row of token t's page, minus the page offset of t itself
+          const int64_t pg = min(max((int64_t)cur_pg, (int64_t)0), (p.pool_tokens >> p.page_shift) - 1);
+          prow[c] = (pg << p.page_shift) + (t & ((1 << p.page_shift) - 1));
+          cur_pg = nxt_pg;
+          if (t + 2 * PASS < seg_t1)
+            nxt_pg = p.page_table[(int64_t)b * p.max_pages +
+                                  min((t + 2 * PASS) >> p.page_shift, p.max_pages - 1)];
+        }
+        // Tokens of this thread past the end of the segment (only in its last
+        // 16-token group) get the largest stored value, which no threshold reaches.
+        if (t + kSelTokPerThread > seg_t1) {
+          const int n_valid = max(seg_t1 - t, 0);
+#pragma unroll
+          for (int w = 0; w < DW; ++w) {
+            const int keep = min(max(n_valid - TPW * w, 0), TPW);
+            const uint32_t gone = keep == TPW ? 0u : ~((1u << (TB * keep)) - 1u);
+            // bytes: 0xff (with the ninth bit below: 0x1ff); uint16: exactly 0x7fff, whatever was loaded
+            dw[w] = BYTES ? (dw[w] | gone) : ((dw[w] & ~gone) | (gone & 0x7fff7fffu));
+          }
+          if (HIGH) high |= ~((1u << n_valid) - 1u);
+        }
+        // Per word: which of its tokens lie below / at the threshold.
+        uint32_t n_lt = 0, n_eq = 0;
+#pragma unroll
+        for (int w = 0; w < DW; ++w) word_masks<BYTES>(dw[w], y, m_lt[w], m_eq[w]);
+        if constexpr (BYTES) {
+          // the flags of the thread's 16 tokens gathered into 16 bits (bit j = token j)
+          uint32_t lt16 = flags16(m_lt), eq16 = flags16(m_eq);
+          if constexpr (HIGH) {
+            // The bytes were compared on their low eight bits; `high` holds the ninth bits.
+            const uint32_t h16 = high & 0xffffu;
+            if (T < 256) {
+              lt16 &= ~h16;
+              eq16 &= ~h16;
+            } else {
+              lt16 |= ~h16 & 0xffffu;
+              eq16 &= h16;
+            }
+          }
+          n_lt = (uint32_t)__popc(lt16);
+          n_eq = (uint32_t)__popc(eq16);
+          flags[c] = lt16 | (eq16 << 16);
+        } else {
+#pragma unroll
+          for (int w = 0; w < DW; ++w) {
+            n_lt += (uint32_t)__popc(m_lt[w]);
+            n_eq += (uint32_t)__popc(m_eq[w]);
+          }
+        }
+        cnt[c] = n_lt | (n_eq << 16);
       }
     }
-    if (pass_no == 1) trace.stamp(kSelMasked, false);
-    // exclusive prefix over the workgroup (one barrier per pass: the wave totals alternate buffers)
-    const uint32_t cnt = n_lt | (n_eq << 16);
-    const uint32_t incl = wave_incl_scan_u32(cnt);
-    uint32_t(*wt)[2] = s_wave[pass_no & 1];
-    if (lane == 63) wt[wave][0] = incl;
+    if (first_chunk) trace.stamp(kSelMasked, false);
+    // exclusive prefixes over the workgroup, all passes of the chunk behind one barrier
+    uint32_t incl[kChunk];
+#pragma unroll
+    for (int c = 0; c < kChunk; ++c) {
+      incl[c] = 0u;
+      if (c < n_pass) {
+        incl[c] = wave_incl_scan_u32(cnt[c]);
+        if (lane == 63) s_pass[c][wave] = incl[c];
+      }
+    }
     __syncthreads();
-    uint32_t before = 0, total = 0;
+    uint32_t lt0[kChunk], eq0[kChunk];
 #pragma unroll
-    for (int w = 0; w < NW; ++w) {
-      const uint32_t x = wt[w][0];
-      before += w < wave ? x : 0u;
-      total += x;
+    for (int c = 0; c < kChunk; ++c) {
+      lt0[c] = eq0[c] = 0u;
+      if (c < n_pass) {
+        uint32_t before = 0, total = 0;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+          const uint32_t x = s_pass[c][w];
+          before += w < wave ? x : 0u;
+          total += x;
+        }
+        const uint32_t ex = before + incl[c] - cnt[c];
+        lt0[c] = run_lt + (ex & 0xffffu);
+        eq0[c] = run_eq + (ex >> 16);
+        run_lt += total & 0xffffu;
+        run_eq += total >> 16;
+      }
     }
-    const uint32_t ex = before + incl - cnt;
-    uint32_t lt = run_lt + (ex & 0xffffu), eq = run_eq + (ex >> 16);
-    if (pass_no == 1) trace.stamp(kSelPrefix, false);
+    if (first_chunk) trace.stamp(kSelPrefix, false);
     if constexpr (ATTN) {
       // The gather below starts only after the compaction; the K and V rows of
       // this thread's first selected token are requested here already (one word
       // per 128-byte line, never used), so that the gather finds them in the
       // cache.  First pass only: the registers are not reused while in flight.
       // The host switches this on for launches that are bound by latency.
-      if (pass_no == 1 && p.early_rows != 0) {
+      if (first_chunk && p.early_rows != 0) {
+        const int t = chunk_t0 + tid * kSelTokPerThread;
         int j = 0;
         bool some = false, first_eq = false;
         if constexpr (BYTES) {
-          const uint32_t c = lt16 | eq16;
-          j = __builtin_ctz(c | 0x10000u);
-          some = c != 0u;
+          const uint32_t lt16 = flags[0] & 0xffffu, eq16 = flags[0] >> 16;
+          const uint32_t c16 = lt16 | eq16;
+          j = __builtin_ctz(c16 | 0x10000u);
+          some = c16 != 0u;
           first_eq = (eq16 >> j) & 1u;
         } else {
 #pragma unroll
@@ -709,8 +753,8 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
             }
           }
         }
-        if (some && (!first_eq || eq < (uint32_t)r)) {
-          const int64_t row = min(PAGED ? page_row0 + j : (int64_t)(t + j), gather_rows - 1);
+        if (some && (!first_eq || eq0[0] < (uint32_t)r)) {
+          const int64_t row = min(PAGED ? prow[0] + j : (int64_t)(t + j), gather_rows - 1);
           const uint32_t* kr = reinterpret_cast<const uint32_t*>(p.K + row0 + row * D);
           const uint32_t* vr = reinterpret_cast<const uint32_t*>(p.V + row0 + row * D);
 #pragma unroll
@@ -722,42 +766,54 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const SelectParams p) {
       }
     }
     // Visit only the candidate tokens (set bits), in position order.
-    auto emit = [&](int j, bool is_eq) {
-      if (!is_eq || eq < (uint32_t)r) {
-        const uint32_t pos = lt + min(eq, (uint32_t)r);
-        // pos < kk always holds for consistent histograms; the checks keep a
-        // corrupted workspace from turning into an out-of-bounds store.
-        if (pos < (uint32_t)kk) {
-          if (idx_row != nullptr) idx_row[pos] = t + j;
-          // the gather list holds token positions, or pool rows for a paged cache
-          if (ATTN && pos - seg_pos0 < (uint32_t)kMaxK)
-            s_sel[pos - seg_pos0] = PAGED ? (int32_t)(page_row0 + j) : t + j;
-        }
-      }
-      lt += is_eq ? 0u : 1u;
-      eq += is_eq ? 1u : 0u;
-    };
-    if constexpr (BYTES) {
-      uint32_t cand = lt16 | eq16;
-      while (cand != 0u) {
-        const int j = __builtin_ctz(cand);
-        cand &= cand - 1u;
-        emit(j, (eq16 >> j) & 1u);
-      }
-    } else {
 #pragma unroll
-      for (int w = 0; w < DW; ++w) {
-        uint32_t cand = m_lt[w] | m_eq[w];
-        while (cand != 0u) {
-          const int bit = __builtin_ctz(cand);
-          cand &= cand - 1u;
-          emit(TPW * w + bit / TB, (m_eq[w] >> bit) & 1u);
+    for (int c = 0; c < kChunk; ++c) {
+      if (c < n_pass) {
+        const int t = chunk_t0 + c * PASS + tid * kSelTokPerThread;
+        const int64_t page_row0 = prow[c];
+        uint32_t lt = lt0[c], eq = eq0[c];
+        auto emit = [&](int j, bool is_eq) {
+          if (!is_eq || eq < (uint32_t)r) {
+            const uint32_t pos = lt + min(eq, (uint32_t)r);
+            // pos < kk always holds for consistent histograms; the checks keep a
+            // corrupted workspace from turning into an out-of-bounds store.
+            if (pos < (uint32_t)kk) {
+              if (idx_row != nullptr) idx_row[pos] = t + j;
+              // the gather list holds token positions, or pool rows for a paged cache
+              if (ATTN && pos - seg_pos0 < (uint32_t)kMaxK)
+                s_sel[pos - seg_pos0] = PAGED ? (int32_t)(page_row0 + j) : t + j;
+            }
+          }
+          lt += is_eq ? 0u : 1u;
+          eq += is_eq ? 1u : 0u;
+        };
+        if constexpr (BYTES) {
+          const uint32_t eq16 = flags[c] >> 16;
+          uint32_t cand = (flags[c] & 0xffffu) | eq16;
+          while (cand != 0u) {
+            const int j = __builtin_ctz(cand);
+            cand &= cand - 1u;
+            emit(j, (eq16 >> j) & 1u);
+          }
+        } else {
+#pragma unroll
+          for (int w = 0; w < DW; ++w) {
+            uint32_t cand = m_lt[w] | m_eq[w];
+            while (cand != 0u) {
+              const int bit = __builtin_ctz(cand);
+              cand &= cand - 1u;
+              emit(TPW * w + bit / TB, (m_eq[w] >> bit) & 1u);
+            }
+          }
         }
       }
     }
-    run_lt += total & 0xffffu;
-    run_eq += total >> 16;
+    first_chunk = false;
+    // the next chunk rewrites the wave totals that slower waves may still be reading
+    if (chunk_t0 + kChunk * PASS < seg_t1) __syncthreads();
   }
+  };
+  run_passes(std::integral_constant<int, BYTES ? CHUNK : 1>{});
   if (seg == 0 && idx_row != nullptr)
     for (int i = kk + tid; i < p.k; i += THREADS) idx_row[i] = -1;
 

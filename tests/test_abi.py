@@ -213,16 +213,20 @@ def test_merge_uses_device_scope_accesses(tmp_path):
                                       "-S", "--cuda-device-only", "-o", str(out),
                                       str(B.CSRC / "kernels_inst.hip")], check=True)
     text = out.read_text()
-    # the decode step's select kernel: 256 threads, with attention, Eq. 6, contiguous cache, d = 128
-    start = re.search(r"^_ZN6adamas13select_kernelILi256ELb1ELi0ELb0ELi128EEE\w*:", text, re.M)
-    assert start, "select kernel not found in the assembly"
-    body = text[start.end():text.index(".Lfunc_end", start.end())]
-    sc1 = [l.split() for l in body.splitlines() if re.search(r"\bsc1\b", l)]
-    kinds = {w[0] for w in sc1}
-    assert any(k.startswith("global_store_dword") for k in kinds), kinds      # partials out
-    assert any(k.startswith("global_load_dword") for k in kinds), kinds       # partials read back
-    # the arrival counter: a returning atomic add (device-wide atomicity is the hardware's; the
-    # compiler marks only system scope with sc1 on read-modify-write instructions)
-    assert re.search(r"^\s*global_atomic_add\w* v\d+, .*\bsc0\b", body, re.M)
+    # the decode step's select kernels (a pass at a time / eight passes per barrier): 256 threads,
+    # with attention, Eq. 6, contiguous cache, d = 128
+    starts = list(re.finditer(r"^_ZN6adamas13select_kernelILi256ELb1ELi0ELb0ELi128ELi\d+EEE\w*:", text, re.M))
+    assert len(starts) == 2, "select kernels not found in the assembly"
+    body = ""
+    for start in starts:
+        one = text[start.end():text.index(".Lfunc_end", start.end())]
+        sc1 = [l.split() for l in one.splitlines() if re.search(r"\bsc1\b", l)]
+        kinds = {w[0] for w in sc1}
+        assert any(k.startswith("global_store_dword") for k in kinds), kinds      # partials out
+        assert any(k.startswith("global_load_dword") for k in kinds), kinds       # partials read back
+        # the arrival counter: a returning atomic add (device-wide atomicity is the hardware's; the
+        # compiler marks only system scope with sc1 on read-modify-write instructions)
+        assert re.search(r"^\s*global_atomic_add\w* v\d+, .*\bsc0\b", one, re.M)
+        body += one
     # and no whole-cache write-back / invalidate crept in (the fence that cost 23 us per step)
     assert "buffer_wbl2" not in body and "buffer_inv" not in body
